@@ -1,0 +1,117 @@
+"""Seeded synthetic inputs for the parallel draft step.
+
+This module only draws numbers and lays them out; it holds none of the
+method's arithmetic, so both the CPU oracle's tests and the HIP path's callers
+may use it.  Every tensor has its own Philox stream keyed by (seed, tensor id),
+so any subset can be regenerated on its own.
+
+Value recipe (benchmark definition): matrices, mask-independent weights and the
+cached K/V ~ N(0, 0.02); norm gains 1 + N(0, 0.02); input hidden states and the
+[MASK] embeddings ~ N(0, 1).  For bf16 workloads every tensor is rounded to
+bf16 (round to nearest even) here and handed out as uint16 bit patterns, so the
+oracle and the device read exactly the same stored values.
+"""
+import numpy as np
+
+_TENSOR_IDS = {
+    "g_in": 1, "wq": 2, "wk": 3, "wv": 4, "wo": 5, "g_post": 6, "w_gate": 7, "w_up": 8,
+    "w_down": 9, "g_final": 10, "w_lm": 11, "mask_emb": 12, "x": 13, "k_cache": 14,
+    "v_cache": 15, "kv_len": 16, "n_new_mix": 17,
+}
+
+
+def _rng(seed, name, sub=0):
+    return np.random.Generator(np.random.Philox(key=[int(seed), _TENSOR_IDS[name] + 1000 * int(sub)]))
+
+
+def f32_to_bf16_bits(a):
+    """Round float32 to bfloat16 (nearest even); returns uint16 bit patterns."""
+    u = np.ascontiguousarray(a, dtype=np.float32).view(np.uint32)
+    r = (u + np.uint32(0x7FFF) + ((u >> np.uint32(16)) & np.uint32(1))) >> np.uint32(16)
+    return r.astype(np.uint16)
+
+
+def bf16_bits_to_f32(b):
+    return (np.ascontiguousarray(b, dtype=np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32)
+
+
+def _store(a, dtype):
+    if dtype == "bf16":
+        return f32_to_bf16_bits(a)
+    return np.ascontiguousarray(a, dtype=np.float32)
+
+
+def _normal(seed, name, shape, std, mean, dtype, sub=0):
+    g = _rng(seed, name, sub)
+    a = g.standard_normal(shape, dtype=np.float32)
+    if std != 1.0:
+        a *= np.float32(std)
+    if mean != 0.0:
+        a += np.float32(mean)
+    return _store(a, dtype)
+
+
+def make_weights(shape, seed):
+    """All drafter weights, row-major [out, in]; bf16 tensors as uint16 bits."""
+    s, dt = shape, shape.dtype
+    w = {
+        "g_in": _normal(seed, "g_in", (s.hidden,), 0.02, 1.0, dt),
+        "wq": _normal(seed, "wq", (s.q_dim, s.hidden), 0.02, 0.0, dt),
+        "wk": _normal(seed, "wk", (s.kv_dim, s.hidden), 0.02, 0.0, dt),
+        "wv": _normal(seed, "wv", (s.kv_dim, s.hidden), 0.02, 0.0, dt),
+        "wo": _normal(seed, "wo", (s.hidden, s.q_dim), 0.02, 0.0, dt),
+        "g_post": _normal(seed, "g_post", (s.hidden,), 0.02, 1.0, dt),
+        "w_gate": _normal(seed, "w_gate", (s.ffn, s.hidden), 0.02, 0.0, dt),
+        "w_up": _normal(seed, "w_up", (s.ffn, s.hidden), 0.02, 0.0, dt),
+        "w_down": _normal(seed, "w_down", (s.hidden, s.ffn), 0.02, 0.0, dt),
+        "g_final": _normal(seed, "g_final", (s.hidden,), 0.02, 1.0, dt),
+        "w_lm": _normal(seed, "w_lm", (s.vocab, s.hidden), 0.02, 0.0, dt),
+        "mask_emb": _normal(seed, "mask_emb", (s.k_max, s.hidden), 1.0, 0.0, dt),
+    }
+    return w
+
+
+def draw_kv_len(workload):
+    """Per-sequence valid cache lengths: fixed, or uniform in the stated range."""
+    if workload.kv_len:
+        return tuple(int(v) for v in workload.kv_len)
+    lo, hi = workload.kv_len_range
+    g = _rng(workload.seed, "kv_len")
+    return tuple(int(v) for v in g.integers(lo, hi + 1, size=workload.batch))
+
+
+def draw_n_new_mix(workload, steps):
+    """Accepted-length mix: n_new per step, uniform over workload.n_new_mix."""
+    g = _rng(workload.seed, "n_new_mix")
+    mix = np.asarray(workload.n_new_mix if workload.n_new_mix else (workload.n_new,))
+    return [int(v) for v in mix[g.integers(0, len(mix), size=steps)]]
+
+
+def make_step_inputs(workload, kv_len=None, n_new=None, k=None, slack=0, sub=0):
+    """Input hidden states and a ragged KV cache with an offsets array.
+
+    Sequence b owns cache rows [kv_offsets[b], kv_offsets[b+1]); its first
+    kv_len[b] rows hold N(0, 0.02) values, the remaining n_new + k (+ slack)
+    rows are zero and receive this step's new K/V rows.
+    """
+    s = workload.shape
+    kv_len = tuple(draw_kv_len(workload) if kv_len is None else kv_len)
+    n_new = workload.n_new if n_new is None else n_new
+    k = workload.k if k is None else k
+    m = n_new + k
+    cap = [l + m + slack for l in kv_len]
+    off = np.zeros(len(kv_len) + 1, dtype=np.int64)
+    off[1:] = np.cumsum(cap)
+    total = int(off[-1])
+    kc = np.zeros((total, s.n_kv_heads, s.head_dim), dtype=np.uint16 if s.dtype == "bf16" else np.float32)
+    vc = np.zeros_like(kc)
+    for b, l in enumerate(kv_len):
+        if l == 0:
+            continue
+        kc[off[b]:off[b] + l] = _normal(workload.seed, "k_cache", (l, s.n_kv_heads, s.head_dim), 0.02, 0.0,
+                                        s.dtype, sub=sub * 64 + b)
+        vc[off[b]:off[b] + l] = _normal(workload.seed, "v_cache", (l, s.n_kv_heads, s.head_dim), 0.02, 0.0,
+                                        s.dtype, sub=sub * 64 + b)
+    x = _normal(workload.seed, "x", (len(kv_len), n_new, s.hidden), 1.0, 0.0, s.dtype, sub=sub)
+    return {"x": x, "k_cache": kc, "v_cache": vc, "kv_offsets": off,
+            "kv_len": np.asarray(kv_len, dtype=np.int32), "n_new": n_new, "k": k}
