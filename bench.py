@@ -1,0 +1,192 @@
+#!/usr/bin/env python3
+"""Benchmark of the parallel draft step on one MI355X.
+
+    python bench.py --gpus 1 --steps K --warmup W [--workload c1]
+
+A "step" is one ps_draft_step: one forward of the one-layer drafter over n_new real rows
+plus k [MASK] rows against the KV cache, LM head with fused softmax/top-k included.  All
+inputs are seeded, synthetic and resident in HBM before the timed region.  Prints ONE JSON
+line: draft tokens/s (k+1 tokens per sequence per step), step latency, the HBM roofline of
+the dominant kernel (the LM-head GEMM, timed live with HIP events on the launch stream) and
+of the whole step, and the CPU oracle timed on this machine's host cores as a baseline.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_HBM_GBS = 8000.0   # MI355X HBM3E, published peak
+
+
+def algorithmic_bytes(wl, kv_len, n_new, k):
+    """Weights once + valid KV once + new KV rows written once (per step), in bytes."""
+    s = wl.shape
+    esz = 2 if s.dtype == "bf16" else 4
+    m = n_new + k
+    weights = {
+        "qkv": (s.q_dim + 2 * s.kv_dim) * s.hidden + s.hidden,
+        "oproj": s.hidden * s.q_dim,
+        "gateup": 2 * s.ffn * s.hidden + s.hidden,
+        "down": s.hidden * s.ffn,
+        "lmhead": s.vocab * s.hidden + s.hidden,
+    }
+    per = {n: v * esz for n, v in weights.items()}
+    per["mask_emb"] = k * s.hidden * esz
+    per["kv_read"] = sum(2 * l * s.kv_dim * esz for l in kv_len)
+    per["kv_write"] = len(kv_len) * 2 * m * s.kv_dim * esz
+    per["total"] = sum(per.values())
+    return per
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=300)
+    ap.add_argument("--warmup", type=int, default=30)
+    ap.add_argument("--workload", default="c1")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--oracle-steps", type=int, default=2)
+    ap.add_argument("--no-kernel-timing", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus %d is not supported"
+              % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2410_05589_amd import binding as B
+    from paper_2410_05589_amd import inputs
+    from paper_2410_05589_amd.configs import WORKLOADS
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    wl = WORKLOADS[args.workload]
+    shape = wl.shape
+    kv_len = inputs.draw_kv_len(wl)
+    mix = inputs.draw_n_new_mix(wl, args.steps + args.warmup) if wl.n_new_mix else None
+    max_new = max(wl.n_new_mix) if wl.n_new_mix else wl.n_new
+
+    w = inputs.make_weights(shape, wl.seed)
+    drafter = B.Drafter(shape, w, max_batch=wl.batch, max_new=max_new,
+                        max_positions=max(kv_len) + max_new + wl.k, max_topk=wl.topk, k_max=wl.k)
+    # one input set per distinct n_new (the accepted-length mix of c2); the cache is reset by
+    # keeping kv_len fixed, so every step rewrites the same n_new + k rows
+    variants = {}
+    for n_new in sorted(set(mix)) if mix else [wl.n_new]:
+        inp = inputs.make_step_inputs(wl, kv_len=kv_len, n_new=n_new, k=wl.k)
+        dev = {n: B.to_device(inp[n], shape.dtype) for n in ("x", "k_cache", "v_cache")}
+        outs = drafter.alloc_outputs(wl.batch, n_new, wl.k, wl.topk)
+        a = drafter.make_args(dev["x"], dev["k_cache"], dev["v_cache"], inp["kv_offsets"], inp["kv_len"],
+                              n_new, wl.k, wl.topk, outs)
+        variants[n_new] = (a, inp, outs)
+    seq = mix if mix else [wl.n_new] * (args.steps + args.warmup)
+
+    stream = torch.cuda.current_stream()
+    for i in range(args.warmup):
+        drafter.step(variants[seq[i]][0])
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    ev0.record(stream)
+    for i in range(args.steps):
+        drafter.step(variants[seq[args.warmup + i]][0])
+    ev1.record(stream)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    wall_ms = (t1 - t0) * 1e3 / args.steps
+    ev_ms = ev0.elapsed_time(ev1) / args.steps
+    ms_per_step = wall_ms
+    tokens_per_step = wl.batch * (wl.k + 1)
+    value = tokens_per_step / (ms_per_step * 1e-3)
+
+    n_new_mean = float(np.mean(seq[args.warmup:]))
+    bytes_mean = float(np.mean([algorithmic_bytes(wl, kv_len, n, wl.k)["total"] for n in seq[args.warmup:]]))
+    per = algorithmic_bytes(wl, kv_len, seq[-1], wl.k)
+
+    # ---- per-kernel durations, live, with HIP events on the launch stream (second region of K steps)
+    kernel_us = None
+    roofline = None
+    if not args.no_kernel_timing:
+        ksteps = min(args.steps, 200)
+        evs = [[torch.cuda.Event(enable_timing=True) for _ in range(B.PS_PROFILE_EVENTS)] for _ in range(ksteps)]
+        for row in evs:
+            for e in row:
+                e.record(stream)          # creates the underlying hipEvent_t
+        torch.cuda.synchronize()
+        for i in range(ksteps):
+            st = B.ps_draft_set_profile_events(drafter.ctx, [e.cuda_event for e in evs[i]])
+            assert st == B.PS_OK
+            drafter.step(variants[seq[args.warmup + i]][0])
+        B.ps_draft_set_profile_events(drafter.ctx, None)
+        torch.cuda.synchronize()
+        acc = np.zeros(B.PS_PROFILE_EVENTS - 1)
+        for row in evs:
+            for j in range(B.PS_PROFILE_EVENTS - 1):
+                acc[j] += row[j].elapsed_time(row[j + 1])
+        kernel_us = {n: float(acc[j] / ksteps * 1e3) for j, n in enumerate(B.PROFILE_KERNELS)}
+        dom = "lmhead"
+        dom_bytes = per["lmhead"]
+        achieved = dom_bytes / (kernel_us[dom] * 1e-6) / 1e9
+        roofline = {"bound": "hbm", "kernel": "gemm_kernel<bf16,1,LMHEAD>" if shape.dtype == "bf16" else
+                    "gemm_kernel<f32,1,LMHEAD>", "achieved": round(achieved, 1), "peak": PEAK_HBM_GBS,
+                    "unit": "GB/s", "frac": round(achieved / PEAK_HBM_GBS, 4), "traffic": None,
+                    "algorithmic_bytes_per_launch": dom_bytes, "avg_launch_us": round(kernel_us[dom], 2)}
+
+    step_gbs = bytes_mean / (ms_per_step * 1e-3) / 1e9
+    result = {
+        "metric": "draft tokens/sec (parallel draft step, k+1 tokens per sequence per step)",
+        "value": round(value, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": shape.dtype, "data": "synthetic",
+        "config": {"workload": "%s: 1 decoder layer H%d %dq/%dkv x%d F%d V%d, batch %d, KV %s, n_new %s, k %d, topk %d"
+                   % (wl.name, shape.hidden, shape.n_heads, shape.n_kv_heads, shape.head_dim, shape.ffn, shape.vocab,
+                      wl.batch, list(kv_len) if wl.batch > 1 else kv_len[0],
+                      "mix %s (mean %.2f)" % (list(wl.n_new_mix), n_new_mean) if mix else wl.n_new, wl.k, wl.topk),
+                   "tokens_per_step": tokens_per_step},
+        "latency_us": round(ms_per_step * 1e3, 2),
+        "latency_us_hip_events": round(ev_ms * 1e3, 2),
+        "step_roofline": {"algorithmic_bytes": int(bytes_mean), "achieved_GBps": round(step_gbs, 1),
+                          "peak_GBps": PEAK_HBM_GBS, "frac": round(step_gbs / PEAK_HBM_GBS, 4),
+                          "roofline_latency_us": round(bytes_mean / PEAK_HBM_GBS / 1e3, 2)},
+        "kernel_us": {n: round(v, 2) for n, v in kernel_us.items()} if kernel_us else None,
+        "roofline": roofline,
+    }
+
+    if not args.no_cpu_baseline:
+        from oracle import ps_oracle
+        try:
+            from threadpoolctl import threadpool_info
+            threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+        except Exception:
+            threads = 1
+        a, inp, outs = variants[seq[-1]]
+        n_new = seq[-1]
+        times = []
+        for _ in range(args.oracle_steps):
+            c0 = time.perf_counter()
+            ref = ps_oracle.draft_step(shape, w, inp["x"], inp["k_cache"], inp["v_cache"], inp["kv_offsets"], inp["kv_len"],
+                                       n_new, wl.k, wl.topk)
+            times.append(time.perf_counter() - c0)
+        best = float(np.mean(times))
+        # sanity: the timed GPU step agrees with the oracle on the top-1 tokens
+        torch.cuda.synchronize()
+        gpu_top1 = outs["top_ids"].cpu().numpy()[..., 0]
+        agree = float((gpu_top1 == ref["top_ids"][..., 0]).mean())
+        result["cpu_baseline"] = {"value": round(tokens_per_step / best, 2), "unit": "tokens/s", "cores": int(threads),
+                                  "kind": "oracle", "sample": "%d full steps of the same workload (numpy float64, "
+                                  "mean %.2f s per step, host cores available %d)" % (args.oracle_steps, best,
+                                                                                       len(os.sched_getaffinity(0))),
+                                  "top1_agreement_with_gpu": agree}
+    drafter.close()
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,176 @@
+/*
+ * ps_draft.h - C ABI of the ParallelSpec parallel draft step on AMD MI355X (gfx950).
+ *
+ * One call of ps_draft_step runs the drafter of Section 4.1 ("Parallel Drafting",
+ * paragraph "Inference") once: the k special tokens [MASK]_1..[MASK]_k are appended after
+ * the sequence, ONE forward pass of the drafter produces the representation of the last
+ * real token (which decodes x_t) and of the k mask tokens (which decode x_{t+1..t+k}), and
+ * the LM head turns those k+1 representations into k+1 token distributions
+ * q(x | x_<n), q(x | x_<n, [MASK]_1), ..., q(x | x_<n, [MASK]_1..k)  (Algorithm 1, draft line).
+ * The drafter is a single Llama-style Transformer layer shaped like a layer of the target
+ * model (Section 5.1 "Models"); its LM head is the target's, shared and frozen
+ * (Section 4.3, Medusa integration).  The prefix x_<n is represented by the drafter's KV
+ * cache plus the hidden states of the n_new positions accepted since the previous step.
+ * [MASK] rows of earlier steps are never visible (Section 4.1, "Group-wise Parallel
+ * Training": the model must behave the same in training and evaluation): a step writes
+ * n_new + k new K/V rows after the valid cache rows, and the caller commits only the
+ * first n_new of them by advancing kv_len by n_new, so the next step overwrites the rest.
+ *
+ * All pointers named "device" are HIP device pointers of the current device, owned by
+ * the caller; nothing is copied or retained beyond what is stated.  No function throws
+ * or aborts; every function returns a ps_status (0 = success, negative = error).  On any
+ * error nothing has been enqueued on the stream.
+ */
+#ifndef PS_DRAFT_H
+#define PS_DRAFT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct ps_draft_ctx ps_draft_ctx;
+
+enum ps_dtype { PS_F32 = 0, PS_BF16 = 1 };
+
+enum ps_status {
+    PS_OK = 0,
+    PS_ERR_NULL = -1,        /* a required pointer is NULL */
+    PS_ERR_CONFIG = -2,      /* a configuration field is out of range or inconsistent */
+    PS_ERR_SHAPE = -3,       /* a step argument (batch, n_new, k, topk) is outside the configured bounds */
+    PS_ERR_KV_CAPACITY = -4, /* kv_len + n_new + k exceeds the sequence's cache rows or max_positions */
+    PS_ERR_OFFSETS = -5,     /* kv_offsets is negative or not non-decreasing */
+    PS_ERR_WORKSPACE = -6,   /* workspace too small or misaligned (256 bytes) */
+    PS_ERR_UNSUPPORTED = -7, /* a legal shape this build has no kernel for (see ps_draft_config) */
+    PS_ERR_DEVICE = -8       /* a HIP call failed (no device, launch failure) */
+};
+
+#define PS_FLAG_FINAL_NORM 1u /* apply the RMSNorm with gain g_final before the LM head */
+
+/*
+ * Shape of the drafter layer and bounds of the step.  Supported by this build:
+ *   head_dim 64 or 128; n_heads a multiple of n_kv_heads;
+ *   hidden, n_heads*head_dim and ffn multiples of 32 (PS_BF16) or 16 (PS_F32); ffn a multiple of 8;
+ *   hidden a multiple of 16; vocab >= 1 (any value);
+ *   max_batch * (max_new + k_max) <= 64 rows per step;
+ *   (n_heads / n_kv_heads) * (max_new + k_max) <= 64; 1 <= max_topk <= 32.
+ * Anything else legal returns PS_ERR_UNSUPPORTED, anything illegal PS_ERR_CONFIG.
+ */
+typedef struct ps_draft_config {
+    int32_t hidden;        /* H: model width */
+    int32_t n_heads;       /* query heads */
+    int32_t n_kv_heads;    /* key/value heads (grouped-query attention when < n_heads) */
+    int32_t head_dim;      /* d */
+    int32_t ffn;           /* F: SwiGLU inner width */
+    int32_t vocab;         /* V: rows of the LM head */
+    int32_t k_max;         /* rows of mask_emb = largest k a step may use (>= 0) */
+    int32_t max_batch;     /* largest batch a step may use (>= 1) */
+    int32_t max_new;       /* largest n_new a step may use (>= 1) */
+    int32_t max_positions; /* largest kv_len + n_new + k of any sequence (rotary table rows) */
+    int32_t max_topk;      /* largest topk a step may use */
+    int32_t dtype;         /* ps_dtype of weights, mask_emb, x and the KV cache */
+    float rms_eps;         /* epsilon inside every RMSNorm */
+    float rope_base;       /* rotary base; pair (j, j + d/2) turns by position * base^(-2j/d) */
+    uint32_t flags;        /* PS_FLAG_* */
+} ps_draft_config;
+
+/*
+ * Drafter weights: device pointers, row-major [out_features, in_features], element type
+ * config.dtype, no biases (Section 5.1: 4H^2 + 3HF parameters give the printed 202M / 317M).
+ * Borrowed for the lifetime of the context; never written.
+ */
+typedef struct ps_draft_weights {
+    const void* g_in;     /* [H]                 gain of the RMSNorm before attention */
+    const void* wq;       /* [n_heads*d, H] */
+    const void* wk;       /* [n_kv_heads*d, H] */
+    const void* wv;       /* [n_kv_heads*d, H] */
+    const void* wo;       /* [H, n_heads*d] */
+    const void* g_post;   /* [H]                 gain of the RMSNorm before the MLP */
+    const void* w_gate;   /* [F, H] */
+    const void* w_up;     /* [F, H] */
+    const void* w_down;   /* [H, F] */
+    const void* g_final;  /* [H]                 gain of the final RMSNorm (may be NULL without PS_FLAG_FINAL_NORM) */
+    const void* w_lm;     /* [V, H]              LM head shared with the target model */
+    const void* mask_emb; /* [k_max, H]          embeddings of [MASK]_1..[MASK]_k_max (may be NULL if k_max == 0) */
+} ps_draft_weights;
+
+/*
+ * Bytes of device scratch ps_draft_init needs for this configuration (activations,
+ * split-K partial sums, attention partials, completion counters, rotary table).
+ * Returns 0 if the configuration is invalid or unsupported.  Host-only; touches no device.
+ */
+size_t ps_draft_workspace_bytes(const ps_draft_config* config);
+
+/*
+ * Creates a context.  config and weights are copied (the structs, not the tensors).
+ * workspace: device memory of at least ps_draft_workspace_bytes(config) bytes, 256-byte
+ * aligned, owned by the caller, used exclusively by this context until ps_draft_free.
+ * stream: hipStream_t (may be NULL = default stream); the rotary table upload and the
+ * clearing of the counters are enqueued on it and the call waits for them.
+ * Validation happens before any HIP call, so configuration errors are reported on a
+ * machine without a GPU as well.  *out is set only on success.
+ */
+int ps_draft_init(ps_draft_ctx** out, const ps_draft_config* config, const ps_draft_weights* weights,
+                  void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Arguments of one draft step.  Sequences are independent; all use the same n_new and k.
+ * Per sequence the step processes M = n_new + k rows: the n_new real rows x[b, 0..n_new-1]
+ * followed by mask_emb[0..k-1], at positions kv_len[b] .. kv_len[b] + M - 1.
+ * Output rows per sequence ("rows" below): out_rows == 0 -> the k+1 decoding rows
+ * (last real row, then the k mask rows); out_rows == 1 -> all M rows (testing).
+ */
+typedef struct ps_draft_step_args {
+    int32_t batch;  /* 1..max_batch */
+    int32_t n_new;  /* 1..max_new: real positions accepted since the previous step (Section 3: 1..gamma+1) */
+    int32_t k;      /* 0..k_max: [MASK] slots appended (k = 0 is an ordinary decode step) */
+    int32_t topk;   /* 1..min(max_topk, vocab): candidates per output row (token tree fan-out, Appendix A.3) */
+    int32_t out_rows;
+    const void* x;  /* device [batch, n_new, H], config.dtype: hidden states of the new real positions */
+    void* k_cache;  /* device [total_positions, n_kv_heads, d], config.dtype; keys stored after rotary embedding */
+    void* v_cache;  /* device, same layout.  Rows off[b]+kv_len[b] .. +M-1 of both are overwritten. */
+    const int64_t* kv_offsets; /* HOST [batch+1], in positions: sequence b owns cache rows [off[b], off[b+1]) */
+    const int32_t* kv_len;     /* HOST [batch]: valid positions of sequence b before this step (>= 0) */
+    int32_t* top_ids;  /* device [batch, rows, topk]: token ids by descending logit, equal logits by ascending id */
+    float* top_p;      /* device [batch, rows, topk]: softmax probability of each top id */
+    float* lse;        /* device [batch, rows]: log-sum-exp of the row's logits */
+    float* logits;     /* device [batch, rows, V] or NULL */
+    float* probs;      /* device [batch, rows, V] or NULL: softmax(logits) */
+    float* hidden_out; /* device [batch, M, H] or NULL: layer output before the final norm */
+} ps_draft_step_args;
+
+/*
+ * Enqueues one draft step on stream (hipStream_t, NULL = default stream) and returns
+ * without waiting.  Performs no allocation, no host synchronisation and reads no device
+ * memory from the host; kv_offsets and kv_len are read before the call returns.
+ * top_ids, top_p and lse are required; logits, probs and hidden_out are optional.
+ * Steps of one context must not overlap in time (they share the workspace).
+ * Errors: PS_ERR_NULL, PS_ERR_SHAPE, PS_ERR_OFFSETS, PS_ERR_KV_CAPACITY (kv_len[b] + M
+ * exceeds off[b+1] - off[b] or max_positions), PS_ERR_DEVICE.
+ */
+int ps_draft_step(ps_draft_ctx* ctx, const ps_draft_step_args* args, void* stream);
+
+/*
+ * Measurement aid (no part of the method): when events is non-NULL, every following
+ * ps_draft_step records events[0] before its first kernel and events[i] after kernel i
+ * (i = 1..7: QKV projection, attention, output projection, gate/up projection, down
+ * projection, LM head, LM-head merge incl. optional probabilities) on the step's stream, so
+ * the caller can time each kernel with hipEventElapsedTime.  events: HOST array of
+ * PS_PROFILE_EVENTS hipEvent_t handles created by the caller with timing enabled; the
+ * array is copied.  NULL switches recording off again.  Returns PS_ERR_NULL for a NULL ctx.
+ */
+#define PS_PROFILE_EVENTS 8
+int ps_draft_set_profile_events(ps_draft_ctx* ctx, void* const* events);
+
+/* Releases the host-side context; ps_draft_free(NULL) is a no-op.  The workspace stays the caller's. */
+void ps_draft_free(ps_draft_ctx* ctx);
+
+/* Static, NUL-terminated description of a ps_status value. */
+const char* ps_draft_strerror(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PS_DRAFT_H */

@@ -1,0 +1,63 @@
+// Internal declarations shared by the host dispatcher and the HIP kernels of the
+// parallel draft step (not part of the public C ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+#include "ps_draft.h"
+
+#define PS_MAX_ROWS 64     // activation rows per step (MFMA column tiles: up to 4 x 16)
+#define PS_WG_THREADS 1024 // one workgroup per compute unit, 16 wavefronts of 64 lanes
+#define PS_WAVES 16
+#define PS_LDS_BYTES (160 * 1024)
+
+enum { PH_QKV = 0, PH_OPROJ = 1, PH_GATEUP = 2, PH_DOWN = 3, PH_LMHEAD = 4, PH_COUNT = 5 };
+
+// How one weight-streaming GEMM phase is cut up.  A "tile" is 16 weight rows; a "step" is
+// the 64-byte piece of a weight row one MFMA group consumes (32 bf16 or 16 f32 elements).
+struct PhasePlan {
+    int T;           // tiles
+    int Kt;          // steps along the contraction dimension
+    int S;           // K-slices across workgroups (partials meet in global memory)
+    int KW;          // K-split across the wavefronts of one workgroup (partials meet in LDS)
+    int panel_steps; // steps of the activation panel held in LDS at a time
+    int nwg;         // workgroups launched for the phase
+    int cnt_base;    // first completion counter of the phase
+    int lds_bytes;   // dynamic LDS the phase needs
+};
+
+struct StepParams {
+    // shape
+    int H, nq, nkv, d, F, V, QD, KVD;
+    int B, n_new, k, M, Mtot, R, Rtot, all_rows, topk;
+    int final_norm, max_positions;
+    float eps, inv_sqrt_d;
+    // weights and step inputs (config dtype)
+    const void *g_in, *wq, *wk, *wv, *wo, *g_post, *w_gate, *w_up, *w_down, *g_final, *w_lm, *mask_emb;
+    const void* x;
+    void *kc, *vc;
+    // workspace
+    const float2* rope; // [max_positions][d/2] (cos, sin)
+    float *q_buf, *o_buf, *y_buf, *u_buf, *y2_buf;
+    float* part;       // split-K partial fragments
+    float* attn_acc;   // [items][g*M][d] unnormalised partial outputs
+    float2* attn_ml;   // [items][g*M] (running max, sum of exponentials)
+    int* counters;     // completion counters, all zero between steps
+    float* lm_part;    // [workgroups][Rtot][2 + 2*topk]
+    float* logits_store; // where logits go (caller's buffer, internal scratch, or NULL)
+    // outputs
+    int32_t* top_ids;
+    float *top_p, *lse, *probs, *hidden_out;
+    // attention work list
+    int attn_items, attn_chunk, attn_cnt_base, attn_nwg;
+    long long kv_off[PS_MAX_ROWS];
+    int kv_len[PS_MAX_ROWS];
+    PhasePlan plan[PH_COUNT];
+};
+
+// Launches all kernels of one step on the stream.  Returns hipSuccess or the launch error.
+// events: NULL or PS_PROFILE_EVENTS events recorded around the kernels.
+hipError_t ps_launch_step(const StepParams& P, int dtype, hipStream_t stream, hipEvent_t* events);
+// Raises the dynamic-LDS limit of every kernel instantiation once per process.
+hipError_t ps_kernels_prepare(int lds_limit);

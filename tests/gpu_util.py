@@ -1,0 +1,112 @@
+"""Helpers of the GPU parity tests: run one step through the C ABI, compare with the oracle."""
+import numpy as np
+
+from oracle import ps_oracle as orc
+from paper_2410_05589_amd import binding as B
+from paper_2410_05589_amd import inputs
+
+ID_GAP = 1e-3   # token ids must match wherever the oracle's logit gaps exceed this
+
+
+def run_gpu_step(drafter, inp, n_new, k, topk, all_rows=False, want=("logits", "probs", "hidden")):
+    """One ps_draft_step on copies of the caches; returns numpy outputs and the updated caches."""
+    import torch
+    dt = drafter.shape.dtype
+    x = B.to_device(inp["x"], dt)
+    kc = B.to_device(inp["k_cache"], dt)
+    vc = B.to_device(inp["v_cache"], dt)
+    outs = drafter.alloc_outputs(len(inp["kv_len"]), n_new, k, topk, all_rows=all_rows,
+                                 logits="logits" in want, probs="probs" in want, hidden="hidden" in want)
+    for t in outs.values():
+        t.fill_(-12345) if t.dtype != torch.int32 else t.fill_(-7)
+    args = drafter.make_args(x, kc, vc, inp["kv_offsets"], inp["kv_len"], n_new, k, topk, outs, all_rows=all_rows)
+    drafter.step(args)
+    torch.cuda.synchronize()
+    res = {n: t.cpu().numpy() for n, t in outs.items()}
+    res["k_cache"] = B.from_device(kc)
+    res["v_cache"] = B.from_device(vc)
+    return res
+
+
+def check_topk(gpu_ids, gpu_p, ref, b, r, topk, p_rtol):
+    """Ids bit-exact where unique (oracle gaps > ID_GAP on both sides); otherwise a valid choice."""
+    logits = ref["logits"][b, r]
+    order = np.lexsort((np.arange(logits.shape[0]), -logits))[:topk + 1]
+    ol = logits[order]
+    ids = gpu_ids[b, r]
+    assert len(set(ids.tolist())) == topk, "duplicate ids"
+    assert ids.min() >= 0 and ids.max() < logits.shape[0]
+    n_exact = 0
+    for t in range(topk):
+        gap_up = ol[t - 1] - ol[t] if t > 0 else np.inf
+        gap_dn = ol[t] - ol[t + 1] if t + 1 < len(ol) else np.inf
+        if gap_up > ID_GAP and gap_dn > ID_GAP:
+            assert ids[t] == order[t], (b, r, t, ids, order)
+            n_exact += 1
+        else:
+            assert abs(logits[ids[t]] - ol[t]) <= ID_GAP, (b, r, t)
+        np.testing.assert_allclose(gpu_p[b, r, t], ref["probs"][b, r, ids[t]], rtol=p_rtol, atol=1e-9)
+    return n_exact
+
+
+def compare_with_oracle(shape, res, ref, inp, n_new, k, topk, check_cache=True):
+    """Element-by-element comparison at the stated tolerances; returns a dict of max errors."""
+    f32 = shape.dtype == "f32"
+    B_, R = ref["logits"].shape[:2]
+    maxlog = np.abs(ref["logits"]).max()
+    stats = {}
+    # logits: max-abs 1e-4 (f32) or 2e-2 relative to max |logit| (bf16); the id guarantee needs < ID_GAP / 2
+    if "logits" in res:
+        err = np.abs(res["logits"].astype(np.float64) - ref["logits"]).max()
+        stats["logits_max_abs_err"] = float(err)
+        tol = 1e-4 if f32 else 2e-2 * maxlog
+        assert err <= tol, (err, tol)
+        assert err < ID_GAP / 2, err
+    if "probs" in res:
+        perr = np.abs(res["probs"].astype(np.float64) - ref["probs"]).max()
+        stats["probs_max_abs_err"] = float(perr)
+        np.testing.assert_allclose(res["probs"].astype(np.float64), ref["probs"],
+                                   rtol=2e-4 if f32 else 2e-3, atol=1e-9)
+        np.testing.assert_allclose(res["probs"].astype(np.float64).sum(-1), 1.0, atol=2e-4)
+    lerr = np.abs(res["lse"].astype(np.float64) - ref["lse"]).max()
+    stats["lse_max_abs_err"] = float(lerr)
+    assert lerr <= (1e-4 if f32 else 5e-4)
+    exact = 0
+    for b in range(B_):
+        for r in range(R):
+            exact += check_topk(res["top_ids"], res["top_p"], ref, b, r, topk, p_rtol=1e-3 if f32 else 3e-3)
+    stats["ids_checked_exact"] = exact
+    if "hidden_out" in res:
+        herr = np.abs(res["hidden_out"].astype(np.float64) - ref["hidden_out"]).max()
+        stats["hidden_max_abs_err"] = float(herr)
+        assert herr <= (1e-4 if f32 else 5e-4 * max(1.0, np.abs(ref["hidden_out"]).max())), herr
+    if check_cache:
+        for name in ("k_cache", "v_cache"):
+            g = orc.widen(res[name], shape.dtype)
+            o = orc.widen(ref[name], shape.dtype)
+            if f32:
+                np.testing.assert_allclose(g, o, rtol=2e-5, atol=2e-6)
+            else:
+                # the fp32 value before rounding carries ~1e-6 of the operands' magnitude, so a stored
+                # element may land on the neighbouring bf16 value: one unit in the last place (2^-7
+                # relative) plus that absolute slack where rotary terms cancel
+                d = np.abs(g - o)
+                bound = 2.0 ** -7 * np.abs(o) + 1e-5 * np.abs(o).max()
+                assert np.all(d <= bound), (name, float((d - bound).max()))
+                # (the bf16 high/low split of the activations leaves ~1e-5 relative error, so about
+                # 0.3% of the new elements sit close enough to a rounding boundary to flip)
+                n_mis = int((res[name] != ref[name]).sum())
+                stats[name + "_mismatches"] = n_mis
+                assert n_mis <= 1e-2 * len(inp["kv_len"]) * (n_new + k) * res[name].shape[1] * res[name].shape[2]
+            M = n_new + k
+            off, ln = inp["kv_offsets"], inp["kv_len"]
+            untouched = np.ones(res[name].shape[0], dtype=bool)
+            for b in range(len(ln)):
+                untouched[off[b] + ln[b]: off[b] + ln[b] + M] = False
+            assert np.array_equal(res[name][untouched], inp[name][untouched])
+    return stats
+
+
+def oracle_step(shape, w, inp, n_new, k, topk, all_rows=False):
+    return orc.draft_step(shape, w, inp["x"], inp["k_cache"], inp["v_cache"], inp["kv_offsets"], inp["kv_len"],
+                          n_new, k, topk, all_rows=all_rows)
