@@ -97,8 +97,9 @@ typedef struct ps_draft_weights {
 } ps_draft_weights;
 
 /*
- * Bytes of device scratch ps_draft_init needs for this configuration (activations,
- * split-K partial sums, attention partials, completion counters, rotary table).
+ * Bytes of device scratch ps_draft_init needs for this configuration: a copy of the five
+ * weight matrices in the kernels' streaming order (as large as the matrices themselves),
+ * activations, split-K partial sums, attention partials, completion counters, rotary table.
  * Returns 0 if the configuration is invalid or unsupported.  Host-only; touches no device.
  */
 size_t ps_draft_workspace_bytes(const ps_draft_config* config);
@@ -107,8 +108,10 @@ size_t ps_draft_workspace_bytes(const ps_draft_config* config);
  * Creates a context.  config and weights are copied (the structs, not the tensors).
  * workspace: device memory of at least ps_draft_workspace_bytes(config) bytes, 256-byte
  * aligned, owned by the caller, used exclusively by this context until ps_draft_free.
- * stream: hipStream_t (may be NULL = default stream); the rotary table upload and the
- * clearing of the counters are enqueued on it and the call waits for them.
+ * stream: hipStream_t (may be NULL = default stream); the repacking of the weight matrices,
+ * the rotary table upload and the clearing of the counters are enqueued on it and the call
+ * waits for them.  The matrices are read only during this call; the gain vectors and
+ * mask_emb are read by every step.
  * Validation happens before any HIP call, so configuration errors are reported on a
  * machine without a GPU as well.  *out is set only on success.
  */

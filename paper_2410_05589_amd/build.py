@@ -2,12 +2,18 @@
 import os
 import subprocess
 import sys
+from concurrent.futures import ThreadPoolExecutor
 
 PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG_DIR)
 LIB_PATH = os.path.join(PKG_DIR, "libps_draft.so")
-SOURCES = [os.path.join(PKG_DIR, "csrc", n) for n in ("ps_host.hip", "ps_kernels.hip")]
-HEADERS = [os.path.join(PKG_DIR, "csrc", "ps_internal.h"), os.path.join(ROOT, "include", "ps_draft.h")]
+CSRC = os.path.join(PKG_DIR, "csrc")
+BUILD_DIR = os.path.join(PKG_DIR, "_build")
+HEADERS = [os.path.join(CSRC, "ps_internal.h"), os.path.join(CSRC, "ps_device.h"),
+           os.path.join(ROOT, "include", "ps_draft.h")]
+SOURCES = [os.path.join(CSRC, "ps_host.hip"), os.path.join(CSRC, "ps_inst.hip")]
+# the device code is instantiated once per (storage type, head_dim)
+INSTANCES = [("f32_d64", 0, 64), ("f32_d128", 0, 128), ("bf16_d64", 1, 64), ("bf16_d128", 1, 128)]
 
 
 def hipcc_path():
@@ -17,14 +23,7 @@ def hipcc_path():
     return "hipcc"
 
 
-def build_library(verbose=True):
-    """Compiles every HIP source for gfx950; always rebuilds."""
-    cmd = [hipcc_path(), "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
-           "-fno-gpu-rdc",
-           # packed-FP32 instruction selection is switched off for device code
-           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-           "-I", os.path.join(ROOT, "include"), "-I", os.path.join(PKG_DIR, "csrc"),
-           "-o", LIB_PATH] + SOURCES
+def _run(cmd, verbose):
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
@@ -33,6 +32,24 @@ def build_library(verbose=True):
         raise RuntimeError("hipcc failed:\n" + out)
     if verbose and out.strip():
         print(out)
+
+
+def build_library(verbose=True, jobs=4):
+    """Compiles every HIP source for gfx950 and links the shared library; always rebuilds."""
+    os.makedirs(BUILD_DIR, exist_ok=True)
+    common = [hipcc_path(), "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
+              # packed-FP32 instruction selection is switched off for device code
+              "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+              "-I", os.path.join(ROOT, "include"), "-I", CSRC]
+    units = [(os.path.join(BUILD_DIR, "ps_host.o"), [os.path.join(CSRC, "ps_host.hip")])]
+    for name, bf, d in INSTANCES:
+        units.append((os.path.join(BUILD_DIR, "ps_inst_%s.o" % name),
+                      ["-DPS_INST_NAME=%s" % name, "-DPS_INST_BF16=%d" % bf, "-DPS_INST_D=%d" % d,
+                       os.path.join(CSRC, "ps_inst.hip")]))
+    with ThreadPoolExecutor(max_workers=jobs) as pool:
+        list(pool.map(lambda u: _run(common + ["-c", "-o", u[0]] + u[1], verbose), units))
+    _run([hipcc_path(), "--offload-arch=gfx950", "-shared", "-fPIC", "-fno-gpu-rdc", "-o", LIB_PATH]
+         + [u[0] for u in units], verbose)
     return LIB_PATH
 
 

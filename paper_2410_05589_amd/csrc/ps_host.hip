@@ -11,7 +11,13 @@
 
 #include "ps_internal.h"
 
-int ps_attn_chunk(int dtype, int d);
+static const PsInstance* find_instance(int dtype, int d) {
+    const PsInstance* all[4] = {ps_instance_f32_d64(), ps_instance_f32_d128(), ps_instance_bf16_d64(),
+                                ps_instance_bf16_d128()};
+    for (int i = 0; i < 4; ++i)
+        if (all[i]->dtype == dtype && all[i]->head_dim == d) return all[i];
+    return nullptr;
+}
 
 #define PS_MAX_WG 512   // upper bound on workgroups per phase used to size the workspace
 
@@ -25,18 +31,22 @@ static bool hip_ok(hipError_t e, const char* what) {
 struct ps_draft_ctx {
     ps_draft_config cfg;
     ps_draft_weights w;
+    const PsInstance* inst;
+    int fused;                        // 1: whole step as one persistent kernel, 0: one kernel per phase
     int device;
     int n_cu;
     int lds_limit;                    // dynamic LDS a workgroup may use on this device
     // workspace carve-up (device pointers)
     float2* rope;
-    float *q_buf, *o_buf, *y_buf, *u_buf, *y2_buf, *part, *attn_acc, *lm_part, *logits_ws;
+    float *q_buf, *o_buf, *y_buf, *u_buf, *y2_buf, *part, *ssq_part, *attn_acc, *lm_part, *logits_ws;
     float2* attn_ml;
+    char* wpack[PH_COUNT];
     int* counters;
     int n_counters;
     size_t frag_cap;                  // 1 KiB split-K fragments the workspace holds
     int plan_override[PH_COUNT][2];   // S, KW from PS_DRAFT_PLAN (0 = automatic)
     bool profile;
+    unsigned long long* timeline;
     hipEvent_t events[PS_PROFILE_EVENTS];
 };
 
@@ -71,7 +81,8 @@ static int validate_config(const ps_draft_config* c) {
 static size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
 struct WsLayout {
-    size_t rope, q_buf, o_buf, y_buf, u_buf, y2_buf, part, attn_acc, attn_ml, counters, lm_part, logits_ws, total;
+    size_t wpack[PH_COUNT];
+    size_t rope, q_buf, o_buf, y_buf, u_buf, y2_buf, part, ssq_part, attn_acc, attn_ml, counters, lm_part, logits_ws, total;
     size_t frag_cap;
     int n_counters;
 };
@@ -84,16 +95,31 @@ static int max_tiles(const ps_draft_config* c) {
     return t;
 }
 
+// tiles (16 weight rows) and steps (64-byte pieces of a row) of the five GEMM phases
+static void phase_dims(const ps_draft_config* c, int* T, int* Kt) {
+    const int kstep = c->dtype == PS_BF16 ? 32 : 16;
+    const int qd = c->n_heads * c->head_dim;
+    T[PH_QKV] = (c->n_heads + 2 * c->n_kv_heads) * (c->head_dim / 16); Kt[PH_QKV] = c->hidden / kstep;
+    T[PH_OPROJ] = c->hidden / 16; Kt[PH_OPROJ] = qd / kstep;
+    T[PH_GATEUP] = c->ffn / 8; Kt[PH_GATEUP] = c->hidden / kstep;
+    T[PH_DOWN] = c->hidden / 16; Kt[PH_DOWN] = c->ffn / kstep;
+    T[PH_LMHEAD] = (c->vocab + 15) / 16; Kt[PH_LMHEAD] = c->hidden / kstep;
+}
+
 static WsLayout ws_layout(const ps_draft_config* c) {
     WsLayout L;
     const size_t rows = (size_t)c->max_batch * (c->max_new + c->k_max);
     const size_t qd = (size_t)c->n_heads * c->head_dim;
     const int grp = c->n_heads / c->n_kv_heads;
-    const int ch = ps_attn_chunk(c->dtype, c->head_dim);
+    const int ch = find_instance(c->dtype, c->head_dim)->attn_chunk;
     const size_t max_items = (size_t)c->max_batch * c->n_kv_heads * ((c->max_positions + ch - 1) / ch);
     const size_t ra = (size_t)grp * (c->max_new + c->k_max);
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off = align256(off + bytes); return o; };
+    int T[PH_COUNT], Kt[PH_COUNT];
+    phase_dims(c, T, Kt);
+    // + 8 KiB: the streaming loop always loads 8 steps ahead, also at the end of the last tile
+    for (int ph = 0; ph < PH_COUNT; ++ph) L.wpack[ph] = take((size_t)T[ph] * Kt[ph] * 1024 + 8192);
     L.rope = take((size_t)c->max_positions * (c->head_dim / 2) * sizeof(float2));
     L.q_buf = take(rows * qd * 4);
     L.o_buf = take(rows * qd * 4);
@@ -105,11 +131,12 @@ static WsLayout ws_layout(const ps_draft_config* c) {
     if ((size_t)max_tiles(c) * 2 > frag) frag = (size_t)max_tiles(c) * 2;
     L.frag_cap = frag * 4;
     L.part = take(L.frag_cap * 1024);
+    L.ssq_part = take(L.frag_cap * PS_MAX_ROWS * 4);
     L.attn_acc = take(max_items * ra * c->head_dim * 4);
     L.attn_ml = take(max_items * ra * sizeof(float2));
     L.n_counters = max_tiles(c) * 4 + c->max_batch * c->n_kv_heads;
-    L.counters = take((size_t)L.n_counters * 4);
-    L.lm_part = take((size_t)PS_MAX_WG * rows * (2 + 2 * c->max_topk) * 4);
+    L.counters = take((size_t)(L.n_counters + 4) * 4);   // + grid barrier, end-of-step counter, error flag
+    L.lm_part = take((size_t)PS_MAX_WG * rows * (8 + 8 * c->max_topk) + 64);
     L.logits_ws = take(rows * c->vocab * 4);
     L.total = off;
     return L;
@@ -176,18 +203,28 @@ extern "C" int ps_draft_init(ps_draft_ctx** out, const ps_draft_config* config, 
     if (getenv("PS_DRAFT_DEBUG")) fprintf(stderr, "ps_draft: %s, %d CUs, LDS per workgroup %d\n", prop.name, prop.multiProcessorCount, lds_limit);
     if (lds_limit > PS_LDS_BYTES) lds_limit = PS_LDS_BYTES;
     if (lds_limit < 64 * 1024) return PS_ERR_DEVICE;
-    if (!hip_ok(ps_kernels_prepare(lds_limit), "hipFuncSetAttribute")) return PS_ERR_DEVICE;
+    const PsInstance* inst = find_instance(config->dtype, config->head_dim);
+    if (!inst) return PS_ERR_UNSUPPORTED;
+    if (!hip_ok(inst->prepare(lds_limit), "hipFuncSetAttribute")) return PS_ERR_DEVICE;
+    int coop = 0;
+    if (!hip_ok(hipDeviceGetAttribute(&coop, hipDeviceAttributeCooperativeLaunch, dev), "hipDeviceGetAttribute")) return PS_ERR_DEVICE;
 
     ps_draft_ctx* ctx = new (std::nothrow) ps_draft_ctx;
     if (!ctx) return PS_ERR_DEVICE;
     ctx->cfg = *config;
     ctx->w = *weights;
     ctx->device = dev;
+    ctx->inst = inst;
+    {
+        const char* mode = getenv("PS_DRAFT_MODE");   // "multi": one kernel per phase (profiling, fallback)
+        ctx->fused = coop && !(mode && strcmp(mode, "multi") == 0);
+    }
     ctx->lds_limit = lds_limit;
     ctx->n_cu = prop.multiProcessorCount;
     if (ctx->n_cu < 1) ctx->n_cu = 1;
     if (ctx->n_cu > PS_MAX_WG) ctx->n_cu = PS_MAX_WG;
     char* base = (char*)workspace;
+    for (int ph = 0; ph < PH_COUNT; ++ph) ctx->wpack[ph] = base + L.wpack[ph];
     ctx->rope = (float2*)(base + L.rope);
     ctx->q_buf = (float*)(base + L.q_buf);
     ctx->o_buf = (float*)(base + L.o_buf);
@@ -195,6 +232,7 @@ extern "C" int ps_draft_init(ps_draft_ctx** out, const ps_draft_config* config, 
     ctx->u_buf = (float*)(base + L.u_buf);
     ctx->y2_buf = (float*)(base + L.y2_buf);
     ctx->part = (float*)(base + L.part);
+    ctx->ssq_part = (float*)(base + L.ssq_part);
     ctx->attn_acc = (float*)(base + L.attn_acc);
     ctx->attn_ml = (float2*)(base + L.attn_ml);
     ctx->counters = (int*)(base + L.counters);
@@ -204,6 +242,7 @@ extern "C" int ps_draft_init(ps_draft_ctx** out, const ps_draft_config* config, 
     ctx->logits_ws = (float*)(base + L.logits_ws);
     parse_plan_override(ctx);
     ctx->profile = false;
+    ctx->timeline = nullptr;
 
     // rotary table: (cos, sin) of pos * base^(-2j/d), rotate-half pairing (j, j + d/2)
     const int half = config->head_dim / 2;
@@ -217,7 +256,19 @@ extern "C" int ps_draft_init(ps_draft_ctx** out, const ps_draft_config* config, 
     }
     hipStream_t s = (hipStream_t)stream;
     hipError_t e = hipMemcpyAsync(ctx->rope, tab.data(), tab.size() * sizeof(float2), hipMemcpyHostToDevice, s);
-    if (e == hipSuccess) e = hipMemsetAsync(ctx->counters, 0, (size_t)L.n_counters * 4, s);
+    if (e == hipSuccess) e = hipMemsetAsync(ctx->counters, 0, (size_t)(L.n_counters + 4) * 4, s);
+    {   // copy the five weight matrices into streaming order
+        StepParams P;
+        memset(&P, 0, sizeof(P));
+        P.H = config->hidden; P.nq = config->n_heads; P.nkv = config->n_kv_heads; P.d = config->head_dim;
+        P.F = config->ffn; P.V = config->vocab; P.QD = config->n_heads * config->head_dim;
+        P.wq = w->wq; P.wk = w->wk; P.wv = w->wv; P.wo = w->wo; P.w_gate = w->w_gate; P.w_up = w->w_up;
+        P.w_down = w->w_down; P.w_lm = w->w_lm;
+        int T[PH_COUNT], Kt[PH_COUNT];
+        phase_dims(config, T, Kt);
+        for (int ph = 0; ph < PH_COUNT && e == hipSuccess; ++ph)
+            e = inst->pack(P, ph, T[ph], Kt[ph], ctx->wpack[ph], s);
+    }
     if (e == hipSuccess) e = hipStreamSynchronize(s);
     if (!hip_ok(e, "rotary table upload")) { delete ctx; return PS_ERR_DEVICE; }
     *out = ctx;
@@ -225,6 +276,14 @@ extern "C" int ps_draft_init(ps_draft_ctx** out, const ps_draft_config* config, 
 }
 
 extern "C" void ps_draft_free(ps_draft_ctx* ctx) { delete ctx; }
+
+// Debugging aid, not declared in the public header: device buffer of 32 x 1024 uint64 receiving
+// per-workgroup wall-clock stamps of the following steps (NULL = off).
+extern "C" __attribute__((visibility("default"))) int ps_draft_debug_timeline(ps_draft_ctx* ctx, void* buf) {
+    if (!ctx) return PS_ERR_NULL;
+    ctx->timeline = (unsigned long long*)buf;
+    return PS_OK;
+}
 
 extern "C" int ps_draft_set_profile_events(ps_draft_ctx* ctx, void* const* events) {
     if (!ctx) return PS_ERR_NULL;
@@ -248,9 +307,8 @@ int panel_row_stride_host(int panel_steps) {
 }
 
 // Cuts one GEMM phase: T tiles x Kt steps over nwg workgroups of 16 wavefronts.
-static bool make_plan(PhasePlan* pl, int ph, int T, int Kt, int rows, bool bf, int nwg, int cnt_base,
+static bool make_plan(PhasePlan* pl, int ph, int T, int Kt, int rows, int mt, bool bf, int nwg, int cnt_base,
                       const int* override_, int lds_limit) {
-    const int mt = (rows + 15) / 16;
     const int waves = nwg * PS_WAVES;
     int split = floor_pow2(waves / T > 0 ? waves / T : 1);
     while (split > 1 && Kt / split < 4) split /= 2;   // keep at least 4 steps per piece
@@ -309,12 +367,14 @@ extern "C" int ps_draft_step(ps_draft_ctx* ctx, const ps_draft_step_args* a, voi
     P.g_post = ctx->w.g_post; P.w_gate = ctx->w.w_gate; P.w_up = ctx->w.w_up; P.w_down = ctx->w.w_down;
     P.g_final = ctx->w.g_final; P.w_lm = ctx->w.w_lm; P.mask_emb = ctx->w.mask_emb;
     P.x = a->x; P.kc = a->k_cache; P.vc = a->v_cache;
+    for (int ph = 0; ph < PH_COUNT; ++ph) P.wpack[ph] = ctx->wpack[ph];
     P.rope = ctx->rope; P.q_buf = ctx->q_buf; P.o_buf = ctx->o_buf; P.y_buf = ctx->y_buf; P.u_buf = ctx->u_buf;
     P.y2_buf = ctx->y2_buf; P.part = ctx->part; P.attn_acc = ctx->attn_acc; P.attn_ml = ctx->attn_ml;
-    P.counters = ctx->counters; P.lm_part = ctx->lm_part;
+    P.counters = ctx->counters; P.lm_part = ctx->lm_part; P.ssq_part = ctx->ssq_part;
+    P.barrier = ctx->counters + ctx->n_counters; P.error_flag = ctx->counters + ctx->n_counters + 2;
     P.logits_store = a->logits ? a->logits : (a->probs ? ctx->logits_ws : nullptr);
     P.top_ids = a->top_ids; P.top_p = a->top_p; P.lse = a->lse; P.probs = a->probs; P.hidden_out = a->hidden_out;
-    const int ch = ps_attn_chunk(c.dtype, c.head_dim);
+    const int ch = ctx->inst->attn_chunk;
     int items = 0;
     for (int b = 0; b < a->batch; ++b) {
         P.kv_off[b] = a->kv_offsets[b];
@@ -325,20 +385,39 @@ extern "C" int ps_draft_step(ps_draft_ctx* ctx, const ps_draft_step_args* a, voi
     P.attn_nwg = items < ctx->n_cu ? items : ctx->n_cu;
 
     const bool bf = c.dtype == PS_BF16;
-    const int kstep = bf ? 32 : 16;
     const int nwg = ctx->n_cu;
     const int mtiles = max_tiles(&c);
-    const int T[PH_COUNT] = {(c.n_heads + 2 * c.n_kv_heads) * (c.head_dim / 16), c.hidden / 16, c.ffn / 8,
-                             c.hidden / 16, (c.vocab + 15) / 16};
-    const int Kt[PH_COUNT] = {c.hidden / kstep, P.QD / kstep, c.hidden / kstep, c.ffn / kstep, c.hidden / kstep};
+    int T[PH_COUNT], Kt[PH_COUNT];
+    phase_dims(&c, T, Kt);
     for (int ph = 0; ph < PH_COUNT; ++ph) {
         const int rows = ph == PH_LMHEAD ? P.Rtot : P.Mtot;
-        if (!make_plan(&P.plan[ph], ph, T[ph], Kt[ph], rows, bf, nwg, ph * mtiles, ctx->plan_override[ph], ctx->lds_limit))
+        // the persistent kernel runs every phase with the column tiles of the widest one
+        const int mt = (ctx->fused ? P.Mtot + 15 : rows + 15) / 16;
+        if (!make_plan(&P.plan[ph], ph, T[ph], Kt[ph], rows, mt, bf, nwg, ph * mtiles, ctx->plan_override[ph], ctx->lds_limit))
             return PS_ERR_UNSUPPORTED;
         if (P.plan[ph].S > 1 && (size_t)P.plan[ph].S * T[ph] * ((rows + 15) / 16) > ctx->frag_cap) return PS_ERR_UNSUPPORTED;
     }
     P.attn_cnt_base = 4 * mtiles;
+    P.timeline = ctx->timeline;
 
-    if (!hip_ok(ps_launch_step(P, c.dtype, (hipStream_t)stream, ctx->profile ? ctx->events : nullptr), "kernel launch")) return PS_ERR_DEVICE;
+    // the persistent kernel needs the largest LDS footprint of its phases and one workgroup per CU
+    int lds = ctx->inst->attn_lds;
+    for (int ph = 0; ph < PH_COUNT; ++ph) {
+        if (P.plan[ph].lds_bytes > lds) lds = P.plan[ph].lds_bytes;
+    }
+    if (lds < 256 + PS_WAVES * (8192 + 128)) lds = 256 + PS_WAVES * (8192 + 128);   // end-of-step merge scratch
+    P.fused_nwg = nwg; P.fused_lds = lds;
+    hipStream_t st = (hipStream_t)stream;
+    hipEvent_t* ev = ctx->profile ? ctx->events : nullptr;
+    if (ctx->fused && lds <= ctx->lds_limit) {
+        if (ev && !hip_ok(hipEventRecord(ev[0], st), "hipEventRecord")) return PS_ERR_DEVICE;
+        if (!hip_ok(ctx->inst->launch_fused(P, st), "cooperative kernel launch")) return PS_ERR_DEVICE;
+        if (ev)
+            for (int i = 1; i < PS_PROFILE_EVENTS; ++i)
+                if (!hip_ok(hipEventRecord(ev[i], st), "hipEventRecord")) return PS_ERR_DEVICE;
+    } else {
+        if (!hip_ok(ctx->inst->launch_multi(P, st, ev), "kernel launch")) return PS_ERR_DEVICE;
+    }
+    if (P.probs && !hip_ok(ctx->inst->launch_probs(P, st), "kernel launch")) return PS_ERR_DEVICE;
     return PS_OK;
 }

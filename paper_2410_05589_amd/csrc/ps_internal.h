@@ -37,13 +37,17 @@ struct StepParams {
     const void *g_in, *wq, *wk, *wv, *wo, *g_post, *w_gate, *w_up, *w_down, *g_final, *w_lm, *mask_emb;
     const void* x;
     void *kc, *vc;
+    const char* wpack[PH_COUNT]; // matrices of each phase, prepacked at init in streaming order
     // workspace
     const float2* rope; // [max_positions][d/2] (cos, sin)
     float *q_buf, *o_buf, *y_buf, *u_buf, *y2_buf;
     float* part;       // split-K partial fragments
+    float* ssq_part;   // per fragment: the K-slice's sums of squares of the activation rows (RMSNorm)
     float* attn_acc;   // [items][g*M][d] unnormalised partial outputs
     float2* attn_ml;   // [items][g*M] (running max, sum of exponentials)
     int* counters;     // completion counters, all zero between steps
+    int* barrier;      // [2] grid barrier and end-of-step counters of the persistent kernel
+    int* error_flag;   // set if a grid barrier timed out
     float* lm_part;    // [workgroups][Rtot][2 + 2*topk]
     float* logits_store; // where logits go (caller's buffer, internal scratch, or NULL)
     // outputs
@@ -51,13 +55,24 @@ struct StepParams {
     float *top_p, *lse, *probs, *hidden_out;
     // attention work list
     int attn_items, attn_chunk, attn_cnt_base, attn_nwg;
+    int fused_nwg, fused_lds;
     long long kv_off[PS_MAX_ROWS];
     int kv_len[PS_MAX_ROWS];
     PhasePlan plan[PH_COUNT];
+    unsigned long long* timeline; // debugging aid: per-workgroup time stamps, or NULL
 };
 
-// Launches all kernels of one step on the stream.  Returns hipSuccess or the launch error.
-// events: NULL or PS_PROFILE_EVENTS events recorded around the kernels.
-hipError_t ps_launch_step(const StepParams& P, int dtype, hipStream_t stream, hipEvent_t* events);
-// Raises the dynamic-LDS limit of every kernel instantiation once per process.
-hipError_t ps_kernels_prepare(int lds_limit);
+// One compiled instantiation of the device code (storage type x head_dim) and its launchers.
+struct PsInstance {
+    int dtype, head_dim, attn_chunk, attn_lds;
+    hipError_t (*prepare)(int lds_limit);   // raises the dynamic-LDS limit of every kernel
+    hipError_t (*launch_multi)(const StepParams& P, hipStream_t stream, hipEvent_t* events);
+    hipError_t (*launch_fused)(const StepParams& P, hipStream_t stream);
+    hipError_t (*launch_probs)(const StepParams& P, hipStream_t stream);
+    // copies one phase's weight matrix (T tiles x Kt steps) into streaming order at dst (T*Kt KiB)
+    hipError_t (*pack)(const StepParams& P, int ph, int T, int Kt, char* dst, hipStream_t stream);
+};
+const PsInstance* ps_instance_f32_d64();
+const PsInstance* ps_instance_f32_d128();
+const PsInstance* ps_instance_bf16_d64();
+const PsInstance* ps_instance_bf16_d128();

@@ -61,7 +61,12 @@ def compare_with_oracle(shape, res, ref, inp, n_new, k, topk, check_cache=True):
         stats["logits_max_abs_err"] = float(err)
         tol = 1e-4 if f32 else 2e-2 * maxlog
         assert err <= tol, (err, tol)
-        assert err < ID_GAP / 2, err
+        # engineering bound, tighter than the stated one.  f32: arithmetic error only.  bf16: the new
+        # K/V rows are rounded to bf16 before attention reads them, so wherever the fp32 value and the
+        # oracle's float64 value fall on different sides of a rounding boundary one cache element moves
+        # by one unit in the last place; a few such flips move logits by ~1e-3 (measured by flipping
+        # elements in the oracle), far below the stated tolerance but above the arithmetic error
+        assert err < (ID_GAP / 2 if f32 else 5e-3), err
     if "probs" in res:
         perr = np.abs(res["probs"].astype(np.float64) - ref["probs"]).max()
         stats["probs_max_abs_err"] = float(perr)
