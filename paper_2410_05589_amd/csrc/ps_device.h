@@ -31,9 +31,13 @@
 // tile's counter adds the S fragments in slice order (results do not depend on arrival order)
 // and runs the phase epilogue.
 //
-// Data that one workgroup writes and another reads inside the same kernel goes through
-// agent-scope accesses (sc1 buffer loads/stores, relaxed agent-scope atomics): they write
-// through / bypass the per-XCD L2, so no cache-wide write-back or invalidate is ever needed.
+// Data that one workgroup writes and another reads inside the same step (activations between
+// phases, split-K fragments, attention partials, LM-head statistics) is exchanged WITHOUT
+// barriers, counters or fences: every 4-byte value travels with a 4-byte sequence number of the
+// step in one 8-byte unit, written and read with agent-scope (sc1) buffer accesses that write
+// through / bypass the per-XCD L2.  A consumer simply re-reads a unit until its sequence number
+// is the current step's.  The persistent kernel therefore has no grid-wide synchronisation:
+// each workgroup walks through the phases at its own pace and waits only for the data it needs.
 #pragma once
 #include "ps_internal.h"
 
@@ -117,6 +121,59 @@ __device__ __forceinline__ void coh_st_f4(rsrc_t r, unsigned off, f32x4 v) { coh
 __device__ __forceinline__ float coh_ld_f(rsrc_t r, unsigned off) { return __uint_as_float(coh_ld4(r, off)); }
 __device__ __forceinline__ void coh_st_f(rsrc_t r, unsigned off, float v) { coh_st4(r, off, __float_as_uint(v)); }
 
+// ---- sequence-tagged exchange: element i of such a buffer is the 8-byte unit {value, seq} at
+// byte offset 8 i.  Four consecutive elements are moved as two 16-byte accesses.
+struct LL4 { u32x4 a, b; };
+__device__ __forceinline__ void ll_st4(rsrc_t r, unsigned i, f32x4 v, unsigned seq) {
+    const u32x4 a = {__float_as_uint(v[0]), seq, __float_as_uint(v[1]), seq};
+    const u32x4 b = {__float_as_uint(v[2]), seq, __float_as_uint(v[3]), seq};
+    coh_st16(r, i * 8, a);
+    coh_st16(r, i * 8 + 16, b);
+}
+__device__ __forceinline__ void ll_st1(rsrc_t r, unsigned i, float v, unsigned seq) {
+    const u32x2 a = {__float_as_uint(v), seq};
+    coh_st8(r, i * 8, a);
+}
+__device__ __forceinline__ LL4 ll_ld4(rsrc_t r, unsigned i) {
+    LL4 x;
+    x.a = coh_ld16(r, i * 8);
+    x.b = coh_ld16(r, i * 8 + 16);
+    return x;
+}
+__device__ __forceinline__ bool ll_ok(const LL4& x, unsigned seq) {
+    return x.a[1] == seq && x.a[3] == seq && x.b[1] == seq && x.b[3] == seq;
+}
+__device__ __forceinline__ f32x4 ll_val(const LL4& x) {
+    const f32x4 v = {__uint_as_float(x.a[0]), __uint_as_float(x.a[2]), __uint_as_float(x.b[0]), __uint_as_float(x.b[2])};
+    return v;
+}
+// Bounded wait: a consumer that never sees its data (possible only after a fault elsewhere)
+// raises the error flag and goes on, so the kernel always terminates.
+#define PS_SPIN_LIMIT (1 << 20)
+__device__ __forceinline__ bool spin_again(const StepParams& P, int& spins) {
+    __builtin_amdgcn_s_sleep(2);
+    if (++spins > PS_SPIN_LIMIT) {
+        __hip_atomic_store(P.error_flag, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        return false;
+    }
+    return true;
+}
+// one element / four elements, waiting until they carry this step's sequence number
+__device__ __forceinline__ float ll_wait1(const StepParams& P, rsrc_t r, unsigned i) {
+    int spins = 0;
+    for (;;) {
+        const u32x2 x = coh_ld8(r, i * 8);
+        if (__all(x[1] == P.seq) || !spin_again(P, spins)) return __uint_as_float(x[0]);
+    }
+}
+__device__ __forceinline__ f32x4 ll_wait4(const StepParams& P, rsrc_t r, unsigned i) {
+    int spins = 0;
+    for (;;) {
+        const LL4 x = ll_ld4(r, i);
+        if (__all(ll_ok(x, P.seq)) || !spin_again(P, spins)) return ll_val(x);
+    }
+}
+
 // per-lane 64-bit addresses (KV-cache rows): relaxed agent-scope atomics, dword granularity
 __device__ __forceinline__ void st_agent_u32(void* p, unsigned v) {
     __hip_atomic_store((unsigned*)p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -124,25 +181,20 @@ __device__ __forceinline__ void st_agent_u32(void* p, unsigned v) {
 __device__ __forceinline__ unsigned ld_agent_u32(const void* p) {
     return __hip_atomic_load((const unsigned*)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
-template <typename WT> __device__ __forceinline__ void store4_agent(void* p, f32x4 v);
-template <> __device__ __forceinline__ void store4_agent<float>(void* p, f32x4 v) {
-#pragma unroll
-    for (int e = 0; e < 4; ++e) st_agent_u32((unsigned*)p + e, __float_as_uint(v[e]));
-}
-template <> __device__ __forceinline__ void store4_agent<bf16_t>(void* p, f32x4 v) {
-    st_agent_u32(p, f32_to_bf16(v[0]) | (f32_to_bf16(v[1]) << 16));
-    st_agent_u32((unsigned*)p + 1, f32_to_bf16(v[2]) | (f32_to_bf16(v[3]) << 16));
-}
-__device__ __forceinline__ uint4 ld16_agent(const void* p) {
-    uint4 v;
-    v.x = ld_agent_u32((const unsigned*)p); v.y = ld_agent_u32((const unsigned*)p + 1);
-    v.z = ld_agent_u32((const unsigned*)p + 2); v.w = ld_agent_u32((const unsigned*)p + 3);
+// 4 values -> the cache's storage type: stores them, returns them as stored (widened again)
+template <typename WT> __device__ __forceinline__ f32x4 store4(void* p, f32x4 v);
+template <> __device__ __forceinline__ f32x4 store4<float>(void* p, f32x4 v) {
+    *reinterpret_cast<f32x4*>(p) = v;
     return v;
 }
-// the writer waits for its stores before it bumps a completion counter
-__device__ __forceinline__ void wait_stores_done() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
-__device__ __forceinline__ int arrive_agent(int* counter) {
-    return __hip_atomic_fetch_add(counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+template <> __device__ __forceinline__ f32x4 store4<bf16_t>(void* p, f32x4 v) {
+    const unsigned b0 = f32_to_bf16(v[0]), b1 = f32_to_bf16(v[1]), b2 = f32_to_bf16(v[2]), b3 = f32_to_bf16(v[3]);
+    uint2 o;
+    o.x = b0 | (b1 << 16);
+    o.y = b2 | (b3 << 16);
+    *reinterpret_cast<uint2*>(p) = o;
+    const f32x4 r = {bf16_to_f32(b0), bf16_to_f32(b1), bf16_to_f32(b2), bf16_to_f32(b3)};
+    return r;
 }
 
 // ---- wavefront reductions with DPP (row = 16 lanes); the result is returned to every lane.
@@ -417,7 +469,7 @@ __device__ __forceinline__ void epilogue_qkv(const StepParams& P, int tau, int l
     const int hh = tau / tph, sub = tau - hh * tph;
     const int jb = 8 * sub + 4 * (q & 1);            // rotary frequency index of this lane's 4 values
     const int f = jb + ((q >= 2) ? half : 0);        // feature inside the head
-    const rsrc_t rq = make_rsrc(P.q_buf);
+    const rsrc_t rq = make_rsrc(P.q_buf), rn = make_rsrc(P.kvnew);
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
         f32x4 v = acc[mt], pv;
@@ -437,13 +489,16 @@ __device__ __forceinline__ void epilogue_qkv(const StepParams& P, int tau, int l
             }
         }
         if (hh < P.nq) {
-            coh_st_f4(rq, (unsigned)(((size_t)m * P.QD + hh * P.d + f) * 4), o);
+            ll_st4(rq, (unsigned)((size_t)m * P.QD + hh * P.d + f), o, P.seq);
         } else {
+            // new K/V rows: into the cache in its storage type (for later steps), and - exactly as
+            // stored - into the tagged side buffer this step's attention reads
             const bool isk = hh < P.nq + P.nkv;
             const int hk = isk ? hh - P.nq : hh - P.nq - P.nkv;
             char* cache = (char*)(isk ? P.kc : P.vc);
             const size_t e = ((size_t)(P.kv_off[b] + pos) * P.nkv + hk) * P.d + f;
-            store4_agent<WT>(cache + e * Traits<WT>::ESZ, o);
+            const f32x4 stored = store4<WT>(cache + e * Traits<WT>::ESZ, o);
+            ll_st4(rn, (unsigned)(((size_t)m * 2 + (isk ? 0 : 1)) * P.KVD + hk * P.d + f), stored, P.seq);
         }
     }
 }
@@ -458,7 +513,7 @@ __device__ __forceinline__ void epilogue_oproj(const StepParams& P, int tau, int
         const int m = 16 * mt + c;
         if (m >= P.Mtot) continue;
         const f32x4 z = load4<WT>(z_ptr<WT>(P, m, n));
-        coh_st_f4(ry, (unsigned)(((size_t)m * P.H + n) * 4), z + acc[mt]);
+        ll_st4(ry, (unsigned)((size_t)m * P.H + n), z + acc[mt], P.seq);
     }
 }
 
@@ -479,7 +534,7 @@ __device__ __forceinline__ void epilogue_gateup(const StepParams& P, int tau, in
             const float g = acc[mt][r];
             u[r] = g / (1.0f + expf(-g)) * up[r];
         }
-        coh_st_f4(ru, (unsigned)(((size_t)m * P.F + 8 * tau + 4 * q) * 4), u);
+        ll_st4(ru, (unsigned)((size_t)m * P.F + 8 * tau + 4 * q), u, P.seq);
     }
 }
 
@@ -492,9 +547,9 @@ __device__ __forceinline__ void epilogue_down(const StepParams& P, int tau, int 
     for (int mt = 0; mt < MT; ++mt) {
         const int m = 16 * mt + c;
         if (m >= P.Mtot) continue;
-        const unsigned off = (unsigned)(((size_t)m * P.H + n) * 4);
-        const f32x4 o = coh_ld_f4(ry, off) + acc[mt];
-        coh_st_f4(ry2, off, o);
+        const unsigned idx = (unsigned)((size_t)m * P.H + n);
+        const f32x4 o = ll_wait4(P, ry, idx) + acc[mt];
+        ll_st4(ry2, idx, o, P.seq);
         if (P.hidden_out) *reinterpret_cast<f32x4*>(P.hidden_out + (size_t)m * P.H + n) = o;
     }
 }
@@ -546,7 +601,8 @@ __device__ __forceinline__ void stage_panel(const StepParams& P, char* smem, int
                                             int rows, int a, int b, bool norm, bool first_piece, bool want_ssq) {
     constexpr bool BF = Traits<WT>::BF;
     constexpr int KSTEP = Traits<WT>::KSTEP, GE = Traits<WT>::GE, ESZ = Traits<WT>::ESZ;
-    constexpr int BATCH = 4;
+    constexpr int BATCH = (PH == PH_QKV) ? 4 : 2;   // groups per lane requested before any is used
+    constexpr int NL = GE / 4;                       // tagged 4-element loads per group
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     float* s_ssq = reinterpret_cast<float*>(smem + PS_LDS_SSQ);
     const int groups = (b - a) * 4;
@@ -561,20 +617,30 @@ __device__ __forceinline__ void stage_panel(const StepParams& P, char* smem, int
         const int srow = phase_src_row<PH>(P, r);
         float ss = 0.f;
         for (int gb = g0 + lane; gb - lane < g1; gb += 64 * BATCH) {
-            uint4 araw[BATCH][2], graw[BATCH];
+            uint4 zraw[BATCH], graw[BATCH];
+            LL4 araw[BATCH][NL];
+            int spins = 0;
+            for (;;) {
+                bool ok = true;
 #pragma unroll
-            for (int i = 0; i < BATCH; ++i) {
-                int gi = gb + 64 * i;
-                if (gi >= g1) gi = g1 - 1;                       // clamped: loads stay unconditional
-                const int kk = a * KSTEP + gi * GE;
-                if (PH == PH_QKV) {
-                    araw[i][0] = ld16(z_ptr<WT>(P, r, kk));
-                } else {
-                    const unsigned off = (unsigned)(((size_t)srow * ld + kk) * 4);
-                    araw[i][0] = __builtin_bit_cast(uint4, coh_ld16(rs, off));
-                    if (BF) araw[i][1] = __builtin_bit_cast(uint4, coh_ld16(rs, off + 16));
+                for (int i = 0; i < BATCH; ++i) {
+                    int gi = gb + 64 * i;
+                    if (gi >= g1) gi = g1 - 1;                   // clamped: loads stay unconditional
+                    const int kk = a * KSTEP + gi * GE;
+                    if (PH == PH_QKV) {
+                        zraw[i] = ld16(z_ptr<WT>(P, r, kk));
+                    } else {
+#pragma unroll
+                        for (int h = 0; h < NL; ++h) araw[i][h] = ll_ld4(rs, (unsigned)((size_t)srow * ld + kk + 4 * h));
+                    }
+                    if (norm) graw[i] = ld16((const char*)gain + (size_t)kk * ESZ);
                 }
-                if (norm) graw[i] = ld16((const char*)gain + (size_t)kk * ESZ);
+                if (PH == PH_QKV) break;                         // the step's inputs were complete at launch
+#pragma unroll
+                for (int i = 0; i < BATCH; ++i)
+#pragma unroll
+                    for (int h = 0; h < NL; ++h) ok = ok && ll_ok(araw[i][h], P.seq);
+                if (__all(ok) || !spin_again(P, spins)) break;   // produced earlier in this step: wait for it
             }
 #pragma unroll
             for (int i = 0; i < BATCH; ++i) {
@@ -582,10 +648,13 @@ __device__ __forceinline__ void stage_panel(const StepParams& P, char* smem, int
                 if (gi >= g1) continue;
                 float v[GE];
                 if (PH == PH_QKV) {
-                    unpack_group<WT>(araw[i][0], v);
+                    unpack_group<WT>(zraw[i], v);
                 } else {
-                    unpack_group<float>(araw[i][0], v);
-                    if constexpr (BF) unpack_group<float>(araw[i][1], v + 4);
+#pragma unroll
+                    for (int h = 0; h < NL; ++h) {
+                        const f32x4 t = ll_val(araw[i][h]);
+                        v[4 * h] = t[0]; v[4 * h + 1] = t[1]; v[4 * h + 2] = t[2]; v[4 * h + 3] = t[3];
+                    }
                 }
                 if (norm) {
                     float gn[GE];
@@ -730,44 +799,61 @@ __device__ void gemm_phase(const StepParams& P, int wg, char* smem, uint4 (&wb)[
             }
             bool run_epilogue = true;
             if (S > 1) {
-                // K-slices of other workgroups: publish this fragment (and the slice's sums of
-                // squares); the last arrival adds all S in slice order
+                // K-slices of other workgroups meet here.  Every slice publishes its fragment (and its
+                // sums of squares) as tagged data; the wavefront of slice tau % S waits for the other
+                // S - 1 fragments and adds all S in slice order, so the result does not depend on timing.
                 const rsrc_t rp = make_rsrc(P.part), rq = make_rsrc(P.ssq_part);
-                const unsigned fbase = (unsigned)((size_t)s * pl.T + tau);
+                // all phases share the fragment buffer: the tag names the phase as well as the step
+                const unsigned ftag = P.seq * 8u + PH + 1u;
+                const int s_red = tau % S;
+                run_epilogue = (s == s_red);
+                if (!run_epilogue) {
+                    const unsigned fb = (unsigned)((size_t)s * pl.T + tau);
 #pragma unroll
-                for (int mt = 0; mt < MT; ++mt) {
-                    coh_st_f4(rp, ((fbase * MT + mt) * 64 + lane) * 16, acc[mt]);
-                    if (norm && lane < 16) coh_st_f(rq, (fbase * PS_MAX_ROWS + 16 * mt + lane) * 4, ssq[mt]);
-                }
-                wait_stores_done();   // fragment is in memory before the count says so
-                int old = 0;
-                if (lane == 0) old = arrive_agent(P.counters + pl.cnt_base + tau);
-                old = __builtin_amdgcn_readfirstlane(old);
-                run_epilogue = (old == S - 1);
-                if (run_epilogue) {
-                    if (lane == 0) P.counters[pl.cnt_base + tau] = 0;   // ready for the next step
+                    for (int mt = 0; mt < MT; ++mt) {
+                        ll_st4(rp, ((fb * MT + mt) * 64 + lane) * 4, acc[mt], ftag);
+                        if (norm && lane < 16) ll_st1(rq, fb * PS_MAX_ROWS + 16 * mt + lane, ssq[mt], ftag);
+                    }
+                } else {
+                    f32x4 own[MT];
+                    float own_q[MT];
 #pragma unroll
-                    for (int mt = 0; mt < MT; ++mt) { acc[mt] = f32x4{0.f, 0.f, 0.f, 0.f}; ssq[mt] = 0.f; }
-                    // four slices' fragments are requested before any is added (one memory round
-                    // trip per four slices); the additions stay in slice order
-                    for (int s0 = 0; s0 < S; s0 += 4) {
-                        f32x4 fr[4][MT];
-                        float fq[4][MT];
+                    for (int mt = 0; mt < MT; ++mt) {
+                        own[mt] = acc[mt]; own_q[mt] = ssq[mt];
+                        acc[mt] = f32x4{0.f, 0.f, 0.f, 0.f}; ssq[mt] = 0.f;
+                    }
+                    for (int s0 = 0; s0 < S; s0 += 4) {   // four slices are requested per round trip
+                        LL4 fr[4][MT];
+                        u32x2 fq[4][MT];
+                        int spins = 0;
+                        for (;;) {
+                            bool ok = true;
 #pragma unroll
-                        for (int i = 0; i < 4; ++i) {
-                            const int ss = s0 + i < S ? s0 + i : S - 1;
-                            const unsigned fb = (unsigned)((size_t)ss * pl.T + tau);
+                            for (int i = 0; i < 4; ++i) {
+                                int ss = s0 + i < S ? s0 + i : S - 1;
+                                const bool mine = ss == s;
+                                if (mine) ss = (s + 1) % S;   // placeholder load, never used
+                                const unsigned fb = (unsigned)((size_t)ss * pl.T + tau);
 #pragma unroll
-                            for (int mt = 0; mt < MT; ++mt) {
-                                fr[i][mt] = coh_ld_f4(rp, ((fb * MT + mt) * 64 + lane) * 16);
-                                fq[i][mt] = norm ? coh_ld_f(rq, (fb * PS_MAX_ROWS + 16 * mt + c) * 4) : 0.f;
+                                for (int mt = 0; mt < MT; ++mt) {
+                                    fr[i][mt] = ll_ld4(rp, ((fb * MT + mt) * 64 + lane) * 4);
+                                    fq[i][mt] = coh_ld8(rq, (fb * PS_MAX_ROWS + 16 * mt + c) * 8);
+                                    if (!mine) {
+                                        ok = ok && ll_ok(fr[i][mt], ftag);
+                                        if (norm && 16 * mt + c < rows) ok = ok && fq[i][mt][1] == ftag;
+                                    }
+                                }
                             }
+                            if (__all(ok) || !spin_again(P, spins)) break;
                         }
 #pragma unroll
                         for (int i = 0; i < 4; ++i) {
-                            if (s0 + i < S) {
+                            const int ss = s0 + i;
+                            if (ss >= S) continue;
 #pragma unroll
-                                for (int mt = 0; mt < MT; ++mt) { acc[mt] += fr[i][mt]; ssq[mt] += fq[i][mt]; }
+                            for (int mt = 0; mt < MT; ++mt) {
+                                if (ss == s) { acc[mt] += own[mt]; ssq[mt] += own_q[mt]; }
+                                else { acc[mt] += ll_val(fr[i][mt]); ssq[mt] += __uint_as_float(fq[i][mt][0]); }
                             }
                         }
                     }
@@ -797,7 +883,7 @@ __device__ void gemm_phase(const StepParams& P, int wg, char* smem, uint4 (&wb)[
         const int n_el = g.rounds * SL * 16;
         const int topk = P.topk;
         const rsrc_t rl = make_rsrc(P.lm_part);
-        const unsigned stride = 8 + 8 * topk;   // bytes: max, sum exp, topk keys
+        const unsigned stride = 2 + 2 * topk;   // tagged elements: max, sum exp, topk keys (low, high word)
         for (int m = wave; m < rows; m += PS_WAVES) {
             constexpr int EPL = 8;   // elements per lane kept in registers (more: re-read from LDS)
             u64 keys[EPL];
@@ -821,7 +907,7 @@ __device__ void gemm_phase(const StepParams& P, int wg, char* smem, uint4 (&wb)[
                 for (int x = lane; x < n_el; x += 64) se += expf(s_lm[((size_t)(x >> 4) * rows + m) * 16 + (x & 15)] - mx);
             se = wave_sum(se);
             const unsigned obase = (unsigned)(((size_t)wg * rows + m) * stride);
-            if (lane == 0) { coh_st_f(rl, obase, mx); coh_st_f(rl, obase + 4, se); }
+            if (lane < 2) ll_st1(rl, obase + lane, lane ? se : mx, P.seq);
             u64 prev = ~0ull;   // keys are unique: the next winner is the largest key below the previous one
             for (int t = 0; t < topk; ++t) {
                 u64 best = 0;
@@ -837,10 +923,8 @@ __device__ void gemm_phase(const StepParams& P, int wg, char* smem, uint4 (&wb)[
                     if (kx < prev && kx > best) best = kx;
                 }
                 best = wave_max_u64(best);
-                if (lane == 0) {
-                    u32x2 kv = {(unsigned)best, (unsigned)(best >> 32)};
-                    coh_st8(rl, obase + 8 + 8 * t, kv);
-                }
+                if (lane < 2)
+                    ll_st1(rl, obase + 2 + 2 * t + lane, __uint_as_float(lane ? (unsigned)(best >> 32) : (unsigned)best), P.seq);
                 prev = best ? best : 0;   // 0: list exhausted, every later entry is "none"
             }
         }
@@ -887,13 +971,12 @@ __device__ void attn_phase(const StepParams& P, int wg, int nwg, char* smem) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int grp = P.nq / P.nkv;
     const int Ra = grp * P.M;
-    int& s_last = *reinterpret_cast<int*>(smem);                // completion flag of the current item
     float* sQ = reinterpret_cast<float*>(smem + 256);           // [Ra][D]
     float* sP = sQ + PS_MAX_ROWS * D;                           // [Ra][CH]
     char* sK = reinterpret_cast<char*>(sP + PS_MAX_ROWS * CH);  // [CH][KSTR]
     char* sV = sK + CH * KSTR;
-    const rsrc_t rq = make_rsrc(P.q_buf), racc = make_rsrc(P.attn_acc), rml = make_rsrc(P.attn_ml),
-                 ro = make_rsrc(P.o_buf);
+    const rsrc_t rq = make_rsrc(P.q_buf), rn = make_rsrc(P.kvnew), racc = make_rsrc(P.attn_acc),
+                 rml = make_rsrc(P.attn_ml), ro = make_rsrc(P.o_buf);
 
     for (int item = wg; item < P.attn_items; item += nwg) {
         // decode item -> (b, hk, chunk)
@@ -908,24 +991,40 @@ __device__ void attn_phase(const StepParams& P, int wg, int nwg, char* smem) {
         const int c0 = ch * CH, c1 = min(c0 + CH, L + P.M);
         const int nk = c1 - c0;
         __syncthreads();   // previous item's LDS use is over
-        // stage Q rows of the head group, and the K/V chunk
-        for (int x = tid; x < Ra * (D / 4); x += PS_WG_THREADS) {
-            const int rho = x / (D / 4), dd = (x - rho * (D / 4)) * 4;
-            const int gi = rho / P.M, i = rho - gi * P.M;
-            const f32x4 v = coh_ld_f4(rq, (unsigned)(((size_t)(b * P.M + i) * P.QD + (hk * grp + gi) * D + dd) * 4));
-            *reinterpret_cast<f32x4*>(sQ + rho * D + dd) = v;
-        }
+        // stage the K/V chunk: rows already in the cache come from there; rows of this step come,
+        // exactly as stored, from the tagged side buffer the QKV epilogue fills
         constexpr int GPR = D / GE;   // 16-byte groups per key row
         for (int x = tid; x < nk * GPR; x += PS_WG_THREADS) {
             const int key = x / GPR, gg = x - key * GPR;
-            const size_t e = ((size_t)(P.kv_off[b] + c0 + key) * P.nkv + hk) * D + gg * GE;
-            if (c0 + key >= L) {   // rows written by this step's QKV phase
-                *reinterpret_cast<uint4*>(sK + key * KSTR + gg * 16) = ld16_agent((const char*)P.kc + e * ESZ);
-                *reinterpret_cast<uint4*>(sV + key * KSTR + gg * 16) = ld16_agent((const char*)P.vc + e * ESZ);
-            } else {
+            if (c0 + key < L) {
+                const size_t e = ((size_t)(P.kv_off[b] + c0 + key) * P.nkv + hk) * D + gg * GE;
                 *reinterpret_cast<uint4*>(sK + key * KSTR + gg * 16) = ld16((const char*)P.kc + e * ESZ);
                 *reinterpret_cast<uint4*>(sV + key * KSTR + gg * 16) = ld16((const char*)P.vc + e * ESZ);
             }
+        }
+        const int n_old = L > c0 ? min(L - c0, nk) : 0;          // keys of this chunk that were cached
+        for (int x = tid; x < (nk - n_old) * 2 * (D / 4); x += PS_WG_THREADS) {
+            const int kn = x / (2 * (D / 4)), rest = x - kn * (2 * (D / 4));
+            const int isv = rest / (D / 4), dd = (rest - isv * (D / 4)) * 4;
+            const int key = n_old + kn;
+            const int m = b * P.M + (c0 + key - L);
+            const f32x4 v = ll_wait4(P, rn, (unsigned)(((size_t)m * 2 + isv) * P.KVD + hk * D + dd));
+            char* dst = (isv ? sV : sK) + key * KSTR + dd * ESZ;
+            if constexpr (Traits<WT>::BF) {
+                uint2 o;
+                o.x = f32_to_bf16(v[0]) | (f32_to_bf16(v[1]) << 16);
+                o.y = f32_to_bf16(v[2]) | (f32_to_bf16(v[3]) << 16);
+                *reinterpret_cast<uint2*>(dst) = o;
+            } else {
+                *reinterpret_cast<f32x4*>(dst) = v;
+            }
+        }
+        // Q rows of the head group
+        for (int x = tid; x < Ra * (D / 4); x += PS_WG_THREADS) {
+            const int rho = x / (D / 4), dd = (x - rho * (D / 4)) * 4;
+            const int gi = rho / P.M, i = rho - gi * P.M;
+            const f32x4 v = ll_wait4(P, rq, (unsigned)((size_t)(b * P.M + i) * P.QD + (hk * grp + gi) * D + dd));
+            *reinterpret_cast<f32x4*>(sQ + rho * D + dd) = v;
         }
         __syncthreads();
         for (int rho = wave; rho < Ra; rho += PS_WAVES) {
@@ -982,43 +1081,57 @@ __device__ void attn_phase(const StepParams& P, int wg, int nwg, char* smem) {
                     o[e] += p * vv;
                 }
             }
-            const unsigned abase = (unsigned)((((size_t)item * Ra + rho) * D + lane * DPL) * 4);
+            const unsigned orow = (unsigned)((size_t)(b * P.M + i) * P.QD + (hk * grp + gi) * D + lane * DPL);
+            if (nch == 1) {
+                // the only chunk: normalise and hand the row to the output projection
 #pragma unroll
-            for (int e = 0; e < DPL; ++e) coh_st_f(racc, abase + 4 * e, o[e]);
-            if (lane == 0) {
-                const unsigned mb = (unsigned)(((size_t)item * Ra + rho) * 8);
-                coh_st_f(rml, mb, mx); coh_st_f(rml, mb + 4, l);
+                for (int e = 0; e < DPL; ++e) ll_st1(ro, orow + e, o[e] / l, P.seq);
+            } else {
+                // partial (max, sum, unnormalised output) of this chunk, as tagged data
+                const unsigned abase = (unsigned)(((size_t)item * Ra + rho) * D + lane * DPL);
+#pragma unroll
+                for (int e = 0; e < DPL; ++e) ll_st1(racc, abase + e, o[e], P.seq);
+                if (lane < 2) ll_st1(rml, (unsigned)(((size_t)item * Ra + rho) * 2 + lane), lane ? l : mx, P.seq);
             }
         }
-        // completion of (b, hk): the workgroup that finishes the last chunk merges all chunks
-        wait_stores_done();
-        __syncthreads();
-        if (tid == 0) {
-            int* cnt = P.counters + P.attn_cnt_base + b * P.nkv + hk;
-            const int old = arrive_agent(cnt);
-            s_last = (old == nch - 1);
-            if (s_last) *cnt = 0;
-        }
-        __syncthreads();
-        if (s_last) {
+        // several chunks: the workgroup of the last chunk waits for the others' partials and merges
+        if (nch > 1 && ch == nch - 1) {
             const int item0 = item - ch;   // chunk 0 of this (b, hk)
             for (int x = tid; x < Ra * D; x += PS_WG_THREADS) {
                 const int rho = x / D, dd = x - rho * D;
-                float mstar = -INFINITY;
-                for (int cc = 0; cc < nch; ++cc)
-                    mstar = fmaxf(mstar, coh_ld_f(rml, (unsigned)(((size_t)(item0 + cc) * Ra + rho) * 8)));
-                float num = 0.f, den = 0.f;
-                for (int cc = 0; cc < nch; ++cc) {
-                    const unsigned mb = (unsigned)(((size_t)(item0 + cc) * Ra + rho) * 8);
-                    const float m_c = coh_ld_f(rml, mb), l_c = coh_ld_f(rml, mb + 4);
-                    if (l_c > 0.f) {
-                        const float w = expf(m_c - mstar);
-                        den += l_c * w;
-                        num += coh_ld_f(racc, (unsigned)((((size_t)(item0 + cc) * Ra + rho) * D + dd) * 4)) * w;
+                // chunks are folded in order with a running maximum; four chunks per round trip
+                float mrun = -INFINITY, num = 0.f, den = 0.f;
+                for (int cb = 0; cb < nch; cb += 4) {
+                    u32x2 ml0[4], ml1[4], av[4];
+                    int spins = 0;
+                    for (;;) {
+                        bool ok = true;
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            const int cc = cb + i < nch ? cb + i : nch - 1;
+                            const unsigned mb = (unsigned)(((size_t)(item0 + cc) * Ra + rho) * 2);
+                            ml0[i] = coh_ld8(rml, mb * 8);
+                            ml1[i] = coh_ld8(rml, (mb + 1) * 8);
+                            av[i] = coh_ld8(racc, (unsigned)(((size_t)(item0 + cc) * Ra + rho) * D + dd) * 8);
+                            ok = ok && ml0[i][1] == P.seq && ml1[i][1] == P.seq && av[i][1] == P.seq;
+                        }
+                        if (__all(ok) || !spin_again(P, spins)) break;
+                    }
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        if (cb + i >= nch) continue;
+                        const float m_c = __uint_as_float(ml0[i][0]), l_c = __uint_as_float(ml1[i][0]);
+                        if (l_c > 0.f) {
+                            const float mnew = fmaxf(mrun, m_c);
+                            const float so = expf(mrun - mnew), sn = expf(m_c - mnew);   // exp(-inf) = 0 at the start
+                            num = num * so + __uint_as_float(av[i][0]) * sn;
+                            den = den * so + l_c * sn;
+                            mrun = mnew;
+                        }
                     }
                 }
                 const int gi = rho / P.M, i = rho - gi * P.M;
-                coh_st_f(ro, (unsigned)(((size_t)(b * P.M + i) * P.QD + (hk * grp + gi) * D + dd) * 4), num / den);
+                ll_st1(ro, (unsigned)((size_t)(b * P.M + i) * P.QD + (hk * grp + gi) * D + dd), num / den, P.seq);
             }
         }
     }
@@ -1036,22 +1149,34 @@ __device__ void attn_phase(const StepParams& P, int wg, int nwg, char* smem) {
 __device__ void lm_merge_row(const StepParams& P, int m, int lane, u64* sk) {
     const int nparts = P.plan[PH_LMHEAD].nwg;
     const int topk = P.topk;
-    const unsigned stride = 8 + 8 * topk;
+    const unsigned stride = 2 + 2 * topk;                  // tagged elements per (workgroup, row)
     const unsigned pstride = (unsigned)P.Rtot * stride;
     const rsrc_t rl = make_rsrc(P.lm_part);
     const unsigned base = (unsigned)m * stride;
     constexpr int HPL = PS_MAX_PARTS / 64;   // lists per lane
     float hmax[HPL], hsum[HPL];
     u64 hk[HPL];
+    {
+        LL4 hd[HPL];
+        int spins = 0;
+        for (;;) {   // every workgroup's statistics of this row, once they have arrived
+            bool ok = true;
 #pragma unroll
-    for (int u = 0; u < HPL; ++u) {
-        const int gp = lane + 64 * u;
-        const bool ok = gp < nparts;
-        const unsigned off = base + (ok ? gp : 0) * pstride;
-        const u32x4 v = coh_ld16(rl, off);   // max, sum exp, first key
-        hmax[u] = ok ? __uint_as_float(v[0]) : -INFINITY;
-        hsum[u] = ok ? __uint_as_float(v[1]) : 0.f;
-        hk[u] = ok ? (((u64)v[3] << 32) | v[2]) : 0;
+            for (int u = 0; u < HPL; ++u) {
+                const int gp = lane + 64 * u;
+                hd[u] = ll_ld4(rl, base + (gp < nparts ? gp : 0) * pstride);   // max, sum exp, first key
+                ok = ok && ll_ok(hd[u], P.seq);
+            }
+            if (__all(ok) || !spin_again(P, spins)) break;
+        }
+#pragma unroll
+        for (int u = 0; u < HPL; ++u) {
+            const bool ok = lane + 64 * u < nparts;
+            const f32x4 v = ll_val(hd[u]);
+            hmax[u] = ok ? v[0] : -INFINITY;
+            hsum[u] = ok ? v[1] : 0.f;
+            hk[u] = ok ? (((u64)__float_as_uint(v[3]) << 32) | __float_as_uint(v[2])) : 0;
+        }
     }
     float mx = -INFINITY;
 #pragma unroll
@@ -1076,7 +1201,7 @@ __device__ void lm_merge_row(const StepParams& P, int m, int lane, u64* sk) {
     }
     // only lists whose head reaches the threshold can contribute: at most topk of them.  Their
     // indices are compacted into LDS, then every (list, entry) pair is fetched in one round.
-    int* sl = reinterpret_cast<int*>(sk + PS_MERGE_CAP) ;   // [topk] qualifying list indices (behind the keys)
+    int* sl = reinterpret_cast<int*>(sk + PS_MERGE_CAP);   // [32] qualifying list indices (behind the keys)
     int nl = 0;
 #pragma unroll
     for (int u = 0; u < HPL; ++u) {
@@ -1091,18 +1216,24 @@ __device__ void lm_merge_row(const StepParams& P, int m, int lane, u64* sk) {
     int ns = 0;
     const int npair = nl * topk;
     for (int x0 = 0; x0 < npair; x0 += 64 * 4) {
-        u32x2 raw[4];
+        u32x4 raw[4];
+        int spins = 0;
+        for (;;) {
+            bool ok = true;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            int x = x0 + 64 * i + lane;
-            if (x >= npair) x = npair - 1;
-            const int li = x / topk, tt = x - li * topk;
-            raw[i] = coh_ld8(rl, base + sl[li] * pstride + 8 + 8 * tt);
+            for (int i = 0; i < 4; ++i) {
+                int x = x0 + 64 * i + lane;
+                if (x >= npair) x = npair - 1;
+                const int li = x / topk, tt = x - li * topk;
+                raw[i] = coh_ld16(rl, (base + sl[li] * pstride + 2 + 2 * tt) * 8);   // {low, seq, high, seq}
+                ok = ok && raw[i][1] == P.seq && raw[i][3] == P.seq;
+            }
+            if (__all(ok) || !spin_again(P, spins)) break;
         }
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int x = x0 + 64 * i + lane;
-            const u64 kx = ((u64)raw[i][1] << 32) | raw[i][0];
+            const u64 kx = ((u64)raw[i][2] << 32) | raw[i][0];
             const bool keep = x < npair && kx != 0 && kx >= thr;
             const u64 mask = __ballot(keep);
             const int pos = ns + __popcll(mask & ((1ull << lane) - 1ull));
@@ -1158,31 +1289,10 @@ static __global__ void __launch_bounds__(256) probs_kernel(const StepParams P) {
         P.probs[(size_t)m * P.V + n] = expf(P.logits_store[(size_t)m * P.V + n] - lse);
 }
 
-// Grid barrier of the persistent kernel: every workgroup arrives once per barrier; the counter
-// grows monotonically within a step and is cleared by the step's last workgroup.  The wait is
-// bounded: if the other workgroups never arrive (they are all resident by construction of the
-// cooperative launch, so this means a fault elsewhere) the error flag is raised and the kernel
-// runs on to its end instead of hanging the device.
-#define PS_SPIN_LIMIT (1 << 20)
-__device__ __forceinline__ void grid_barrier(const StepParams& P, int ordinal) {
-    wait_stores_done();
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        arrive_agent(P.barrier);
-        const int target = ordinal * (int)gridDim.x;
-        int spins = 0;
-        while (__hip_atomic_load(P.barrier, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
-            __builtin_amdgcn_s_sleep(1);
-            if (++spins > PS_SPIN_LIMIT) {
-                __hip_atomic_store(P.error_flag, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                break;
-            }
-        }
-    }
-    __syncthreads();
-}
-
-// The whole step in one persistent kernel: gridDim.x = workgroups that are all resident.
+// The whole step in one persistent kernel: gridDim.x workgroups, all resident (cooperative
+// launch).  No grid-wide synchronisation: the phases are chained by the tagged data itself.
+// While a workgroup waits for the activations of its next phase, the first weight loads of that
+// phase are already in flight.
 template <typename WT, int D, int MT>
 __global__ void __launch_bounds__(PS_WG_THREADS) fused_kernel(const StepParams P) {
     extern __shared__ __attribute__((aligned(256))) char smem[];
@@ -1191,35 +1301,24 @@ __global__ void __launch_bounds__(PS_WG_THREADS) fused_kernel(const StepParams P
     stamp(P, wg, 30);
     preload_weights(wb, first_stream<PH_QKV>(P, wg, wave, lane));
     gemm_phase<WT, MT, PH_QKV>(P, wg, smem, wb, P.wpack[PH_QKV] + lane * 16);
-    grid_barrier(P, 1);
+    __syncthreads();
     stamp(P, wg, 25);
     attn_phase<WT, D>(P, wg, gridDim.x, smem);
-    wait_stores_done();
-    preload_weights(wb, first_stream<PH_OPROJ>(P, wg, wave, lane));   // in flight across the barrier
-    grid_barrier(P, 2);
+    __syncthreads();
+    stamp(P, wg, 26);
+    preload_weights(wb, first_stream<PH_OPROJ>(P, wg, wave, lane));
     gemm_phase<WT, MT, PH_OPROJ>(P, wg, smem, wb, first_stream<PH_GATEUP>(P, wg, wave, lane));
-    grid_barrier(P, 3);
+    __syncthreads();
     gemm_phase<WT, MT, PH_GATEUP>(P, wg, smem, wb, first_stream<PH_DOWN>(P, wg, wave, lane));
-    grid_barrier(P, 4);
+    __syncthreads();
     gemm_phase<WT, MT, PH_DOWN>(P, wg, smem, wb, first_stream<PH_LMHEAD>(P, wg, wave, lane));
-    grid_barrier(P, 5);
+    __syncthreads();
     gemm_phase<WT, MT, PH_LMHEAD>(P, wg, smem, wb, P.wpack[PH_LMHEAD] + lane * 16);
-    // the workgroup that finishes last merges the per-workgroup LM-head statistics of every row
-    wait_stores_done();
     __syncthreads();
-    int& s_last = *reinterpret_cast<int*>(smem);
-    if (threadIdx.x == 0) {
-        const int old = arrive_agent(P.barrier + 1);
-        s_last = (old == (int)gridDim.x - 1);
-        if (s_last) {   // nobody waits on either counter any more: clear them for the next step
-            __hip_atomic_store(P.barrier, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            __hip_atomic_store(P.barrier + 1, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
-    }
-    __syncthreads();
-    if (s_last) {
-        u64* sk = reinterpret_cast<u64*>(smem + 256 + (size_t)wave * PS_MERGE_BYTES);
-        for (int m = wave; m < P.Rtot; m += PS_WAVES) lm_merge_row(P, m, lane, sk);
+    // output row m is merged by wavefront 0 of workgroup m mod gridDim.x
+    if (wave == 0) {
+        u64* sk = reinterpret_cast<u64*>(smem + 256);
+        for (int m = wg; m < P.Rtot; m += gridDim.x) lm_merge_row(P, m, lane, sk);
     }
     stamp(P, wg, 31);
 }

@@ -38,8 +38,9 @@ struct ps_draft_ctx {
     int lds_limit;                    // dynamic LDS a workgroup may use on this device
     // workspace carve-up (device pointers)
     float2* rope;
-    float *q_buf, *o_buf, *y_buf, *u_buf, *y2_buf, *part, *ssq_part, *attn_acc, *lm_part, *logits_ws;
-    float2* attn_ml;
+    float *q_buf, *o_buf, *y_buf, *u_buf, *y2_buf, *kvnew, *part, *ssq_part, *attn_acc, *attn_ml, *lm_part, *logits_ws;
+    unsigned seq;                     // sequence number of the last enqueued step
+    size_t exch_begin, exch_end;      // workspace range of the tagged exchange buffers (cleared at init)
     char* wpack[PH_COUNT];
     int* counters;
     int n_counters;
@@ -82,7 +83,8 @@ static size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
 struct WsLayout {
     size_t wpack[PH_COUNT];
-    size_t rope, q_buf, o_buf, y_buf, u_buf, y2_buf, part, ssq_part, attn_acc, attn_ml, counters, lm_part, logits_ws, total;
+    size_t rope, q_buf, o_buf, y_buf, u_buf, y2_buf, kvnew, part, ssq_part, attn_acc, attn_ml, counters, lm_part, logits_ws, total;
+    size_t exch_begin, exch_end;
     size_t frag_cap;
     int n_counters;
 };
@@ -121,22 +123,27 @@ static WsLayout ws_layout(const ps_draft_config* c) {
     // + 8 KiB: the streaming loop always loads 8 steps ahead, also at the end of the last tile
     for (int ph = 0; ph < PH_COUNT; ++ph) L.wpack[ph] = take((size_t)T[ph] * Kt[ph] * 1024 + 8192);
     L.rope = take((size_t)c->max_positions * (c->head_dim / 2) * sizeof(float2));
-    L.q_buf = take(rows * qd * 4);
-    L.o_buf = take(rows * qd * 4);
-    L.y_buf = take(rows * c->hidden * 4);
-    L.u_buf = take(rows * c->ffn * 4);
-    L.y2_buf = take(rows * c->hidden * 4);
-    // split-K fragments: S * T never exceeds the wavefronts of a phase (see make_plan), 1 KiB per column tile
+    // tagged exchange buffers: 8 bytes per element (value + sequence number)
+    L.exch_begin = off;
+    L.q_buf = take(rows * qd * 8);
+    L.o_buf = take(rows * qd * 8);
+    L.y_buf = take(rows * c->hidden * 8);
+    L.u_buf = take(rows * c->ffn * 8);
+    L.y2_buf = take(rows * c->hidden * 8);
+    L.kvnew = take(rows * 2 * (size_t)c->n_kv_heads * c->head_dim * 8);
+    // split-K fragments: S * T never exceeds the wavefronts of a phase (see make_plan); one fragment
+    // is 64 lanes x 4 values per column tile
     size_t frag = (size_t)PS_MAX_WG * PS_WAVES;
     if ((size_t)max_tiles(c) * 2 > frag) frag = (size_t)max_tiles(c) * 2;
     L.frag_cap = frag * 4;
-    L.part = take(L.frag_cap * 1024);
-    L.ssq_part = take(L.frag_cap * PS_MAX_ROWS * 4);
-    L.attn_acc = take(max_items * ra * c->head_dim * 4);
-    L.attn_ml = take(max_items * ra * sizeof(float2));
-    L.n_counters = max_tiles(c) * 4 + c->max_batch * c->n_kv_heads;
-    L.counters = take((size_t)(L.n_counters + 4) * 4);   // + grid barrier, end-of-step counter, error flag
-    L.lm_part = take((size_t)PS_MAX_WG * rows * (8 + 8 * c->max_topk) + 64);
+    L.part = take(L.frag_cap * 2048);
+    L.ssq_part = take(L.frag_cap * PS_MAX_ROWS * 8);
+    L.attn_acc = take(max_items * ra * c->head_dim * 8);
+    L.attn_ml = take(max_items * ra * 2 * 8);
+    L.lm_part = take((size_t)PS_MAX_WG * rows * (2 + 2 * c->max_topk) * 8 + 64);
+    L.exch_end = off;
+    L.n_counters = 0;
+    L.counters = take(64);   // error flag
     L.logits_ws = take(rows * c->vocab * 4);
     L.total = off;
     return L;
@@ -231,10 +238,13 @@ extern "C" int ps_draft_init(ps_draft_ctx** out, const ps_draft_config* config, 
     ctx->y_buf = (float*)(base + L.y_buf);
     ctx->u_buf = (float*)(base + L.u_buf);
     ctx->y2_buf = (float*)(base + L.y2_buf);
+    ctx->kvnew = (float*)(base + L.kvnew);
     ctx->part = (float*)(base + L.part);
     ctx->ssq_part = (float*)(base + L.ssq_part);
     ctx->attn_acc = (float*)(base + L.attn_acc);
-    ctx->attn_ml = (float2*)(base + L.attn_ml);
+    ctx->attn_ml = (float*)(base + L.attn_ml);
+    ctx->seq = 0;
+    ctx->exch_begin = L.exch_begin; ctx->exch_end = L.exch_end;
     ctx->counters = (int*)(base + L.counters);
     ctx->n_counters = L.n_counters;
     ctx->frag_cap = L.frag_cap;
@@ -256,7 +266,9 @@ extern "C" int ps_draft_init(ps_draft_ctx** out, const ps_draft_config* config, 
     }
     hipStream_t s = (hipStream_t)stream;
     hipError_t e = hipMemcpyAsync(ctx->rope, tab.data(), tab.size() * sizeof(float2), hipMemcpyHostToDevice, s);
-    if (e == hipSuccess) e = hipMemsetAsync(ctx->counters, 0, (size_t)(L.n_counters + 4) * 4, s);
+    // sequence numbers start at 1: cleared exchange buffers never look valid
+    if (e == hipSuccess) e = hipMemsetAsync(base + L.exch_begin, 0, L.exch_end - L.exch_begin, s);
+    if (e == hipSuccess) e = hipMemsetAsync(ctx->counters, 0, 64, s);
     {   // copy the five weight matrices into streaming order
         StepParams P;
         memset(&P, 0, sizeof(P));
@@ -312,9 +324,13 @@ static bool make_plan(PhasePlan* pl, int ph, int T, int Kt, int rows, int mt, bo
     const int waves = nwg * PS_WAVES;
     int split = floor_pow2(waves / T > 0 ? waves / T : 1);
     while (split > 1 && Kt / split < 4) split /= 2;   // keep at least 4 steps per piece
+    // S (K-slices across workgroups) costs a fragment exchange with one memory round trip per four
+    // slices, but divides the activation panel every workgroup has to fetch; KW (K-split across the
+    // wavefronts of a workgroup) is free.  The LM head keeps whole logits in the workgroup (S = 1);
+    // the QKV phase reads caller data that is cached, so its panel is cheap (S = 1).
     int S, KW;
-    if (ph == PH_LMHEAD) { S = 1; KW = split > PS_WAVES ? PS_WAVES : split; }   // logits must be complete in the workgroup
-    else { S = split > 16 ? 16 : split; KW = split / S; if (KW > PS_WAVES) KW = PS_WAVES; }
+    if (ph == PH_LMHEAD || ph == PH_QKV) { S = 1; KW = split > PS_WAVES ? PS_WAVES : split; }
+    else { S = split > 4 ? 4 : split; KW = split / S; if (KW > PS_WAVES) KW = PS_WAVES; }
     if (override_ && override_[0] > 0 && override_[1] > 0) { S = override_[0]; KW = override_[1]; }
     if (ph == PH_LMHEAD) S = 1;
     if (S > nwg) S = floor_pow2(nwg);
@@ -370,8 +386,10 @@ extern "C" int ps_draft_step(ps_draft_ctx* ctx, const ps_draft_step_args* a, voi
     for (int ph = 0; ph < PH_COUNT; ++ph) P.wpack[ph] = ctx->wpack[ph];
     P.rope = ctx->rope; P.q_buf = ctx->q_buf; P.o_buf = ctx->o_buf; P.y_buf = ctx->y_buf; P.u_buf = ctx->u_buf;
     P.y2_buf = ctx->y2_buf; P.part = ctx->part; P.attn_acc = ctx->attn_acc; P.attn_ml = ctx->attn_ml;
-    P.counters = ctx->counters; P.lm_part = ctx->lm_part; P.ssq_part = ctx->ssq_part;
-    P.barrier = ctx->counters + ctx->n_counters; P.error_flag = ctx->counters + ctx->n_counters + 2;
+    P.lm_part = ctx->lm_part; P.ssq_part = ctx->ssq_part; P.kvnew = ctx->kvnew;
+    P.error_flag = ctx->counters;
+    ctx->seq = ctx->seq >= 0x1FFFFFF0u ? 1u : ctx->seq + 1u;   // seq * 8 + phase must fit in 32 bits; 0 = cleared
+    P.seq = ctx->seq;
     P.logits_store = a->logits ? a->logits : (a->probs ? ctx->logits_ws : nullptr);
     P.top_ids = a->top_ids; P.top_p = a->top_p; P.lse = a->lse; P.probs = a->probs; P.hidden_out = a->hidden_out;
     const int ch = ctx->inst->attn_chunk;
@@ -393,11 +411,10 @@ extern "C" int ps_draft_step(ps_draft_ctx* ctx, const ps_draft_step_args* a, voi
         const int rows = ph == PH_LMHEAD ? P.Rtot : P.Mtot;
         // the persistent kernel runs every phase with the column tiles of the widest one
         const int mt = (ctx->fused ? P.Mtot + 15 : rows + 15) / 16;
-        if (!make_plan(&P.plan[ph], ph, T[ph], Kt[ph], rows, mt, bf, nwg, ph * mtiles, ctx->plan_override[ph], ctx->lds_limit))
+        if (!make_plan(&P.plan[ph], ph, T[ph], Kt[ph], rows, mt, bf, nwg, 0, ctx->plan_override[ph], ctx->lds_limit))
             return PS_ERR_UNSUPPORTED;
         if (P.plan[ph].S > 1 && (size_t)P.plan[ph].S * T[ph] * ((rows + 15) / 16) > ctx->frag_cap) return PS_ERR_UNSUPPORTED;
     }
-    P.attn_cnt_base = 4 * mtiles;
     P.timeline = ctx->timeline;
 
     // the persistent kernel needs the largest LDS footprint of its phases and one workgroup per CU
@@ -405,7 +422,7 @@ extern "C" int ps_draft_step(ps_draft_ctx* ctx, const ps_draft_step_args* a, voi
     for (int ph = 0; ph < PH_COUNT; ++ph) {
         if (P.plan[ph].lds_bytes > lds) lds = P.plan[ph].lds_bytes;
     }
-    if (lds < 256 + PS_WAVES * (8192 + 128)) lds = 256 + PS_WAVES * (8192 + 128);   // end-of-step merge scratch
+    if (lds < 256 + 8192 + 128) lds = 256 + 8192 + 128;   // end-of-step merge scratch
     P.fused_nwg = nwg; P.fused_lds = lds;
     hipStream_t st = (hipStream_t)stream;
     hipEvent_t* ev = ctx->profile ? ctx->events : nullptr;

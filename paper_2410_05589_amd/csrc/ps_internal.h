@@ -32,6 +32,7 @@ struct StepParams {
     int H, nq, nkv, d, F, V, QD, KVD;
     int B, n_new, k, M, Mtot, R, Rtot, all_rows, topk;
     int final_norm, max_positions;
+    unsigned seq;      // sequence number of this step, tags every value exchanged between workgroups
     float eps, inv_sqrt_d;
     // weights and step inputs (config dtype)
     const void *g_in, *wq, *wk, *wv, *wo, *g_post, *w_gate, *w_up, *w_down, *g_final, *w_lm, *mask_emb;
@@ -40,21 +41,21 @@ struct StepParams {
     const char* wpack[PH_COUNT]; // matrices of each phase, prepacked at init in streaming order
     // workspace
     const float2* rope; // [max_positions][d/2] (cos, sin)
-    float *q_buf, *o_buf, *y_buf, *u_buf, *y2_buf;
-    float* part;       // split-K partial fragments
+    // Buffers exchanged between workgroups hold 8-byte units {value, seq}: element counts below.
+    float *q_buf, *o_buf, *y_buf, *u_buf, *y2_buf;   // [Mtot][QD], [Mtot][QD], [Mtot][H], [Mtot][F], [Mtot][H]
+    float* kvnew;      // [Mtot][2][KVD] this step's K and V rows as stored in the cache
+    float* part;       // split-K fragments: [S][T][MT][64 lanes][4]
     float* ssq_part;   // per fragment: the K-slice's sums of squares of the activation rows (RMSNorm)
     float* attn_acc;   // [items][g*M][d] unnormalised partial outputs
-    float2* attn_ml;   // [items][g*M] (running max, sum of exponentials)
-    int* counters;     // completion counters, all zero between steps
-    int* barrier;      // [2] grid barrier and end-of-step counters of the persistent kernel
-    int* error_flag;   // set if a grid barrier timed out
-    float* lm_part;    // [workgroups][Rtot][2 + 2*topk]
+    float* attn_ml;    // [items][g*M][2] (running max, sum of exponentials)
+    int* error_flag;   // set if a wait for exchanged data timed out
+    float* lm_part;    // [workgroups][Rtot][2 + 2*topk]: max, sum exp, top-k keys (low, high word)
     float* logits_store; // where logits go (caller's buffer, internal scratch, or NULL)
     // outputs
     int32_t* top_ids;
     float *top_p, *lse, *probs, *hidden_out;
     // attention work list
-    int attn_items, attn_chunk, attn_cnt_base, attn_nwg;
+    int attn_items, attn_chunk, attn_nwg;
     int fused_nwg, fused_lds;
     long long kv_off[PS_MAX_ROWS];
     int kv_len[PS_MAX_ROWS];
