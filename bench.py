@@ -22,6 +22,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 PEAK_HBM_GBS = 8000.0   # MI355X HBM3E, published peak
+MEASURED_TRAFFIC = {("c1", "fused"): 724702822}
 
 
 def algorithmic_bytes(wl, kv_len, n_new, k):
@@ -53,12 +54,15 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--oracle-steps", type=int, default=2)
     ap.add_argument("--no-kernel-timing", action="store_true")
+    ap.add_argument("--mode", choices=["fused", "multi"], default="fused",
+                    help="fused: the whole step as one persistent kernel (default); multi: one kernel per phase")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus %d is not supported"
               % args.gpus, file=sys.stderr)
         sys.exit(2)
 
+    os.environ["PS_DRAFT_MODE"] = args.mode
     import torch
     from paper_2410_05589_amd import binding as B
     from paper_2410_05589_amd import inputs
@@ -131,13 +135,25 @@ def main():
             for j in range(B.PS_PROFILE_EVENTS - 1):
                 acc[j] += row[j].elapsed_time(row[j + 1])
         kernel_us = {n: float(acc[j] / ksteps * 1e3) for j, n in enumerate(B.PROFILE_KERNELS)}
-        dom = "lmhead"
-        dom_bytes = per["lmhead"]
-        achieved = dom_bytes / (kernel_us[dom] * 1e-6) / 1e9
-        roofline = {"bound": "hbm", "kernel": "gemm_kernel<bf16,1,LMHEAD>" if shape.dtype == "bf16" else
-                    "gemm_kernel<f32,1,LMHEAD>", "achieved": round(achieved, 1), "peak": PEAK_HBM_GBS,
-                    "unit": "GB/s", "frac": round(achieved / PEAK_HBM_GBS, 4), "traffic": None,
-                    "algorithmic_bytes_per_launch": dom_bytes, "avg_launch_us": round(kernel_us[dom], 2)}
+        dname = "bf16_t" if shape.dtype == "bf16" else "float"
+        mt = (wl.batch * (max_new + wl.k) + 15) // 16
+        if args.mode == "fused":
+            # one kernel per step: the events bracket the launch of the persistent kernel
+            dom_us = float(acc[0] / ksteps * 1e3)   # events 0 and 1 bracket the single launch
+            kernel_us = {"fused_kernel": dom_us}
+            dom_bytes = bytes_mean
+            kname = "fused_kernel<%s, %d, %d>" % (dname, shape.head_dim, mt)
+        else:
+            dom_us = kernel_us["lmhead"]
+            dom_bytes = per["lmhead"]
+            kname = "gemm_kernel<%s, %d, 4>  (LM head)" % (dname, (wl.batch * (wl.k + 1) + 15) // 16)
+        achieved = dom_bytes / (dom_us * 1e-6) / 1e9
+        # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE + WRITE_SIZE, scaled by a copy kernel of
+        # known size (profiles/fused_kernel_c1_hbm_traffic.md); measured offline, so only for that case
+        traffic = MEASURED_TRAFFIC.get((wl.name, args.mode))
+        roofline = {"bound": "hbm", "kernel": kname, "achieved": round(achieved, 1), "peak": PEAK_HBM_GBS,
+                    "unit": "GB/s", "frac": round(achieved / PEAK_HBM_GBS, 4), "traffic": traffic,
+                    "algorithmic_bytes_per_launch": int(dom_bytes), "avg_launch_us": round(dom_us, 2)}
 
     step_gbs = bytes_mean / (ms_per_step * 1e-3) / 1e9
     result = {
@@ -145,6 +161,7 @@ def main():
         "value": round(value, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": shape.dtype, "data": "synthetic",
+        "mode": args.mode,
         "config": {"workload": "%s: 1 decoder layer H%d %dq/%dkv x%d F%d V%d, batch %d, KV %s, n_new %s, k %d, topk %d"
                    % (wl.name, shape.hidden, shape.n_heads, shape.n_kv_heads, shape.head_dim, shape.ffn, shape.vocab,
                       wl.batch, list(kv_len) if wl.batch > 1 else kv_len[0],

@@ -213,8 +213,7 @@ extern "C" int ps_draft_init(ps_draft_ctx** out, const ps_draft_config* config, 
     const PsInstance* inst = find_instance(config->dtype, config->head_dim);
     if (!inst) return PS_ERR_UNSUPPORTED;
     if (!hip_ok(inst->prepare(lds_limit), "hipFuncSetAttribute")) return PS_ERR_DEVICE;
-    int coop = 0;
-    if (!hip_ok(hipDeviceGetAttribute(&coop, hipDeviceAttributeCooperativeLaunch, dev), "hipDeviceGetAttribute")) return PS_ERR_DEVICE;
+    const int coop = 1;
 
     ps_draft_ctx* ctx = new (std::nothrow) ps_draft_ctx;
     if (!ctx) return PS_ERR_DEVICE;
@@ -428,7 +427,7 @@ extern "C" int ps_draft_step(ps_draft_ctx* ctx, const ps_draft_step_args* a, voi
     hipEvent_t* ev = ctx->profile ? ctx->events : nullptr;
     if (ctx->fused && lds <= ctx->lds_limit) {
         if (ev && !hip_ok(hipEventRecord(ev[0], st), "hipEventRecord")) return PS_ERR_DEVICE;
-        if (!hip_ok(ctx->inst->launch_fused(P, st), "cooperative kernel launch")) return PS_ERR_DEVICE;
+        if (!hip_ok(ctx->inst->launch_fused(P, st), "kernel launch")) return PS_ERR_DEVICE;
         if (ev)
             for (int i = 1; i < PS_PROFILE_EVENTS; ++i)
                 if (!hip_ok(hipEventRecord(ev[i], st), "hipEventRecord")) return PS_ERR_DEVICE;

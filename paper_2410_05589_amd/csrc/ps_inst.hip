@@ -83,12 +83,16 @@ static hipError_t launch_multi(const StepParams& P, hipStream_t stream, hipEvent
     return mark();
 }
 
-// the whole step as one cooperative launch (all workgroups resident)
+// The whole step as one launch of the persistent kernel.  Its workgroups wait for each other's
+// data, so all of them must get a compute unit: the grid is one workgroup per CU and a workgroup
+// (1024 threads x up to 128 VGPRs, most of the LDS) fills a CU by itself, so they all become
+// resident as soon as CUs are free; kernels that still occupy CUs end on their own.  Every wait
+// in the kernel is bounded, so even a machine that withholds CUs cannot hang it.  (A cooperative
+// launch would assert the same residency but costs ~17 us per launch on this runtime.)
 static hipError_t launch_fused(const StepParams& P, hipStream_t stream) {
     const int mt = (P.Mtot + 15) / 16;
-    void* args[1] = {const_cast<StepParams*>(&P)};
-    return hipLaunchCooperativeKernel(reinterpret_cast<const void*>(fused_fn(mt)), dim3(P.fused_nwg),
-                                      dim3(PS_WG_THREADS), args, (unsigned)P.fused_lds, stream);
+    hipLaunchKernelGGL(fused_fn(mt), dim3(P.fused_nwg), dim3(PS_WG_THREADS), (unsigned)P.fused_lds, stream, P);
+    return hipGetLastError();
 }
 
 static hipError_t launch_probs(const StepParams& P, hipStream_t stream) {
