@@ -9,7 +9,7 @@ import os
 import numpy as np
 
 _PKG_DIR = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_PKG_DIR, "libps_draft.so")
+LIB_PATH = os.environ.get("PS_DRAFT_LIB") or os.path.join(_PKG_DIR, "libps_draft.so")
 
 PS_F32, PS_BF16 = 0, 1
 PS_OK = 0

@@ -40,7 +40,7 @@ def build_library(verbose=True, jobs=4):
     common = [hipcc_path(), "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
               # packed-FP32 instruction selection is switched off for device code
               "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-              "-I", os.path.join(ROOT, "include"), "-I", CSRC]
+              "-I", os.path.join(ROOT, "include"), "-I", CSRC] + os.environ.get("PS_BUILD_DEFS", "").split()
     units = [(os.path.join(BUILD_DIR, "ps_host.o"), [os.path.join(CSRC, "ps_host.hip")])]
     for name, bf, d in INSTANCES:
         units.append((os.path.join(BUILD_DIR, "ps_inst_%s.o" % name),
@@ -48,9 +48,10 @@ def build_library(verbose=True, jobs=4):
                        os.path.join(CSRC, "ps_inst.hip")]))
     with ThreadPoolExecutor(max_workers=jobs) as pool:
         list(pool.map(lambda u: _run(common + ["-c", "-o", u[0]] + u[1], verbose), units))
-    _run([hipcc_path(), "--offload-arch=gfx950", "-shared", "-fPIC", "-fno-gpu-rdc", "-o", LIB_PATH]
+    out = os.environ.get("PS_BUILD_OUT") or LIB_PATH   # tuning aid: build a variant beside the library
+    _run([hipcc_path(), "--offload-arch=gfx950", "-shared", "-fPIC", "-fno-gpu-rdc", "-o", out]
          + [u[0] for u in units], verbose)
-    return LIB_PATH
+    return out
 
 
 def library_is_current():

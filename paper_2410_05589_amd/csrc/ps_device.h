@@ -174,6 +174,39 @@ __device__ __forceinline__ f32x4 ll_wait4(const StepParams& P, rsrc_t r, unsigne
     }
 }
 
+// ---- sentinel-coded exchange for the activation buffers (the bulk of the exchanged bytes, read
+// by every workgroup): plain fp32 values, "not written yet" is the bit pattern 0xFFFFFFFF (a NaN no
+// computation on finite inputs produces).  Each buffer exists twice; step n uses copy n & 1, and
+// whoever writes element i of the current copy also resets element i of the other copy, so the
+// copy the next step uses is clean again without a separate clearing pass.
+#define PS_SENT 0xFFFFFFFFu
+struct SxBuf { rsrc_t cur, alt; };
+__device__ __forceinline__ SxBuf sx_buf(const StepParams& P, const float* cur) {
+    SxBuf b;
+    b.cur = make_rsrc(cur);
+    b.alt = make_rsrc(reinterpret_cast<const char*>(cur) + P.alt_delta);
+    return b;
+}
+__device__ __forceinline__ void sx_st4(const SxBuf& b, unsigned i, f32x4 v) {
+    coh_st16(b.cur, i * 4, __builtin_bit_cast(u32x4, v));
+    const u32x4 sent = {PS_SENT, PS_SENT, PS_SENT, PS_SENT};
+    coh_st16(b.alt, i * 4, sent);
+}
+__device__ __forceinline__ void sx_st1(const SxBuf& b, unsigned i, float v) {
+    coh_st4(b.cur, i * 4, __float_as_uint(v));
+    coh_st4(b.alt, i * 4, PS_SENT);
+}
+__device__ __forceinline__ bool sx_ok(u32x4 x) {
+    return x[0] != PS_SENT && x[1] != PS_SENT && x[2] != PS_SENT && x[3] != PS_SENT;
+}
+__device__ __forceinline__ f32x4 sx_wait4(const StepParams& P, rsrc_t r, unsigned i) {
+    int spins = 0;
+    for (;;) {
+        const u32x4 x = coh_ld16(r, i * 4);
+        if (__all(sx_ok(x)) || !spin_again(P, spins)) return __builtin_bit_cast(f32x4, x);
+    }
+}
+
 // per-lane 64-bit addresses (KV-cache rows): relaxed agent-scope atomics, dword granularity
 __device__ __forceinline__ void st_agent_u32(void* p, unsigned v) {
     __hip_atomic_store((unsigned*)p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -261,7 +294,9 @@ __device__ __forceinline__ const char* z_ptr(const StepParams& P, int m, int e) 
 
 // Debugging aid: thread 0 of every workgroup stamps the 100 MHz wall clock at point `ev`.
 __device__ __forceinline__ void stamp(const StepParams& P, int wg, int ev) {
+#ifdef PS_TIMELINE
     if (P.timeline && threadIdx.x == 0) P.timeline[(size_t)ev * 1024 + wg] = wall_clock64();
+#endif
 }
 
 // ------------------------------------------------------------------------------------------
@@ -356,7 +391,6 @@ __device__ __forceinline__ void mma_step(uint4 w, const BRegs<WT, MT>& b, f32x4 
     }
 }
 
-constexpr int PS_U = 8;       // weight loads in flight per lane (8 x 16 B = 8 KiB per wavefront)
 constexpr int PS_WS = 1024;   // prepacked weights: one step of a tile = 64 lanes x 16 B, contiguous
 
 // Issues the first PS_U loads of a weight stream.  Weights do not depend on the activations, so
@@ -375,23 +409,34 @@ __device__ __forceinline__ void preload_weights(uint4 (&wb)[PS_U], const char* w
 // continue at next_wp (the wavefront's next stream), so when this returns wb holds the
 // preloaded head of that stream.  Only the oldest load is waited for at each step.
 template <typename WT, int MT>
-__device__ __forceinline__ void consume_weights(uint4 (&wb)[PS_U], const char* wp, int n, const char* next_wp,
+__device__ __forceinline__ void consume_weights(uint4 (&wb)[PS_U], const char* wp, int n_, const char* next_wp,
                                                 const char* const (&pa)[MT], const int (&pinc)[MT],
                                                 const int (&plo)[MT], f32x4 (&acc)[MT]) {
     constexpr int U = PS_U;
+    const int n = __builtin_amdgcn_readfirstlane(n_);   // wavefront-uniform: keep the loop control scalar
     const int n_main = n & ~(U - 1), r = n - n_main;
     BRegs<WT, MT> bc, bn;
     load_b<WT, MT>(bc, pa, pinc, plo, 0);
     const int last = n > 0 ? n - 1 : 0;
-    for (int t0 = 0; t0 < n_main; t0 += U) {
+    int t0 = 0;
+    for (; t0 + 2 * U <= n_main; t0 += U) {   // steady state: every load is inside this stream
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            mma_step<WT, MT>(wb[u], bc, acc);
+            wb[u] = ldg_stream16(wp + (size_t)(t0 + u + U) * PS_WS);   // reuses the register just consumed
+            load_b<WT, MT>(bn, pa, pinc, plo, t0 + u + 1);
+            bc = bn;
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+    if (t0 < n_main) {   // last full group: its loads start the next stream (or fetch the tail steps)
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             mma_step<WT, MT>(wb[u], bc, acc);
             const int idx = t0 + u + U;
-            const char* src;
-            if (r == 0) src = idx < n ? wp + (size_t)idx * PS_WS : next_wp + (size_t)(idx - n) * PS_WS;
-            else src = wp + (size_t)(idx < n ? idx : last) * PS_WS;   // tail steps, then harmless re-reads
-            wb[u] = ldg_stream16(src);                                  // reuses the register just consumed
+            const char* src = r == 0 ? next_wp + (size_t)u * PS_WS
+                                     : wp + (size_t)(idx < n ? idx : last) * PS_WS;   // tail, then harmless re-reads
+            wb[u] = ldg_stream16(src);
             const int tb = t0 + u + 1;
             load_b<WT, MT>(bn, pa, pinc, plo, tb < n ? tb : last);
             bc = bn;
@@ -469,7 +514,7 @@ __device__ __forceinline__ void epilogue_qkv(const StepParams& P, int tau, int l
     const int hh = tau / tph, sub = tau - hh * tph;
     const int jb = 8 * sub + 4 * (q & 1);            // rotary frequency index of this lane's 4 values
     const int f = jb + ((q >= 2) ? half : 0);        // feature inside the head
-    const rsrc_t rq = make_rsrc(P.q_buf), rn = make_rsrc(P.kvnew);
+    const SxBuf rq = sx_buf(P, P.q_buf), rn = sx_buf(P, P.kvnew);
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
         f32x4 v = acc[mt], pv;
@@ -489,7 +534,7 @@ __device__ __forceinline__ void epilogue_qkv(const StepParams& P, int tau, int l
             }
         }
         if (hh < P.nq) {
-            ll_st4(rq, (unsigned)((size_t)m * P.QD + hh * P.d + f), o, P.seq);
+            sx_st4(rq, (unsigned)((size_t)m * P.QD + hh * P.d + f), o);
         } else {
             // new K/V rows: into the cache in its storage type (for later steps), and - exactly as
             // stored - into the tagged side buffer this step's attention reads
@@ -498,7 +543,7 @@ __device__ __forceinline__ void epilogue_qkv(const StepParams& P, int tau, int l
             char* cache = (char*)(isk ? P.kc : P.vc);
             const size_t e = ((size_t)(P.kv_off[b] + pos) * P.nkv + hk) * P.d + f;
             const f32x4 stored = store4<WT>(cache + e * Traits<WT>::ESZ, o);
-            ll_st4(rn, (unsigned)(((size_t)m * 2 + (isk ? 0 : 1)) * P.KVD + hk * P.d + f), stored, P.seq);
+            sx_st4(rn, (unsigned)(((size_t)m * 2 + (isk ? 0 : 1)) * P.KVD + hk * P.d + f), stored);
         }
     }
 }
@@ -507,20 +552,20 @@ template <typename WT, int MT>
 __device__ __forceinline__ void epilogue_oproj(const StepParams& P, int tau, int lane, f32x4 (&acc)[MT]) {
     const int c = lane & 15, q = lane >> 4;
     const int n = 16 * tau + 4 * q;
-    const rsrc_t ry = make_rsrc(P.y_buf);
+    const SxBuf ry = sx_buf(P, P.y_buf);
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
         const int m = 16 * mt + c;
         if (m >= P.Mtot) continue;
         const f32x4 z = load4<WT>(z_ptr<WT>(P, m, n));
-        ll_st4(ry, (unsigned)((size_t)m * P.H + n), z + acc[mt], P.seq);
+        sx_st4(ry, (unsigned)((size_t)m * P.H + n), z + acc[mt]);
     }
 }
 
 template <typename WT, int MT>
 __device__ __forceinline__ void epilogue_gateup(const StepParams& P, int tau, int lane, f32x4 (&acc)[MT]) {
     const int c = lane & 15, q = lane >> 4;
-    const rsrc_t ru = make_rsrc(P.u_buf);
+    const SxBuf ru = sx_buf(P, P.u_buf);
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
         f32x4 up;
@@ -534,7 +579,7 @@ __device__ __forceinline__ void epilogue_gateup(const StepParams& P, int tau, in
             const float g = acc[mt][r];
             u[r] = g / (1.0f + expf(-g)) * up[r];
         }
-        ll_st4(ru, (unsigned)((size_t)m * P.F + 8 * tau + 4 * q), u, P.seq);
+        sx_st4(ru, (unsigned)((size_t)m * P.F + 8 * tau + 4 * q), u);
     }
 }
 
@@ -542,14 +587,15 @@ template <typename WT, int MT>
 __device__ __forceinline__ void epilogue_down(const StepParams& P, int tau, int lane, f32x4 (&acc)[MT]) {
     const int c = lane & 15, q = lane >> 4;
     const int n = 16 * tau + 4 * q;
-    const rsrc_t ry = make_rsrc(P.y_buf), ry2 = make_rsrc(P.y2_buf);
+    const rsrc_t ry = make_rsrc(P.y_buf);
+    const SxBuf ry2 = sx_buf(P, P.y2_buf);
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
         const int m = 16 * mt + c;
         if (m >= P.Mtot) continue;
         const unsigned idx = (unsigned)((size_t)m * P.H + n);
-        const f32x4 o = ll_wait4(P, ry, idx) + acc[mt];
-        ll_st4(ry2, idx, o, P.seq);
+        const f32x4 o = sx_wait4(P, ry, idx) + acc[mt];
+        sx_st4(ry2, idx, o);
         if (P.hidden_out) *reinterpret_cast<f32x4*>(P.hidden_out + (size_t)m * P.H + n) = o;
     }
 }
@@ -601,8 +647,8 @@ __device__ __forceinline__ void stage_panel(const StepParams& P, char* smem, int
                                             int rows, int a, int b, bool norm, bool first_piece, bool want_ssq) {
     constexpr bool BF = Traits<WT>::BF;
     constexpr int KSTEP = Traits<WT>::KSTEP, GE = Traits<WT>::GE, ESZ = Traits<WT>::ESZ;
-    constexpr int BATCH = (PH == PH_QKV) ? 4 : 2;   // groups per lane requested before any is used
-    constexpr int NL = GE / 4;                       // tagged 4-element loads per group
+    constexpr int BATCH = 4;                         // groups per lane requested before any is used
+    constexpr int NL = GE / 4;                       // 4-element loads per group
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     float* s_ssq = reinterpret_cast<float*>(smem + PS_LDS_SSQ);
     const int groups = (b - a) * 4;
@@ -618,7 +664,7 @@ __device__ __forceinline__ void stage_panel(const StepParams& P, char* smem, int
         float ss = 0.f;
         for (int gb = g0 + lane; gb - lane < g1; gb += 64 * BATCH) {
             uint4 zraw[BATCH], graw[BATCH];
-            LL4 araw[BATCH][NL];
+            u32x4 araw[BATCH][NL];
             int spins = 0;
             for (;;) {
                 bool ok = true;
@@ -631,7 +677,7 @@ __device__ __forceinline__ void stage_panel(const StepParams& P, char* smem, int
                         zraw[i] = ld16(z_ptr<WT>(P, r, kk));
                     } else {
 #pragma unroll
-                        for (int h = 0; h < NL; ++h) araw[i][h] = ll_ld4(rs, (unsigned)((size_t)srow * ld + kk + 4 * h));
+                        for (int h = 0; h < NL; ++h) araw[i][h] = coh_ld16(rs, (unsigned)((size_t)srow * ld + kk + 4 * h) * 4);
                     }
                     if (norm) graw[i] = ld16((const char*)gain + (size_t)kk * ESZ);
                 }
@@ -639,7 +685,7 @@ __device__ __forceinline__ void stage_panel(const StepParams& P, char* smem, int
 #pragma unroll
                 for (int i = 0; i < BATCH; ++i)
 #pragma unroll
-                    for (int h = 0; h < NL; ++h) ok = ok && ll_ok(araw[i][h], P.seq);
+                    for (int h = 0; h < NL; ++h) ok = ok && sx_ok(araw[i][h]);
                 if (__all(ok) || !spin_again(P, spins)) break;   // produced earlier in this step: wait for it
             }
 #pragma unroll
@@ -652,7 +698,7 @@ __device__ __forceinline__ void stage_panel(const StepParams& P, char* smem, int
                 } else {
 #pragma unroll
                     for (int h = 0; h < NL; ++h) {
-                        const f32x4 t = ll_val(araw[i][h]);
+                        const f32x4 t = __builtin_bit_cast(f32x4, araw[i][h]);
                         v[4 * h] = t[0]; v[4 * h + 1] = t[1]; v[4 * h + 2] = t[2]; v[4 * h + 3] = t[3];
                     }
                 }
@@ -976,7 +1022,8 @@ __device__ void attn_phase(const StepParams& P, int wg, int nwg, char* smem) {
     char* sK = reinterpret_cast<char*>(sP + PS_MAX_ROWS * CH);  // [CH][KSTR]
     char* sV = sK + CH * KSTR;
     const rsrc_t rq = make_rsrc(P.q_buf), rn = make_rsrc(P.kvnew), racc = make_rsrc(P.attn_acc),
-                 rml = make_rsrc(P.attn_ml), ro = make_rsrc(P.o_buf);
+                 rml = make_rsrc(P.attn_ml);
+    const SxBuf ro = sx_buf(P, P.o_buf);
 
     for (int item = wg; item < P.attn_items; item += nwg) {
         // decode item -> (b, hk, chunk)
@@ -1008,7 +1055,7 @@ __device__ void attn_phase(const StepParams& P, int wg, int nwg, char* smem) {
             const int isv = rest / (D / 4), dd = (rest - isv * (D / 4)) * 4;
             const int key = n_old + kn;
             const int m = b * P.M + (c0 + key - L);
-            const f32x4 v = ll_wait4(P, rn, (unsigned)(((size_t)m * 2 + isv) * P.KVD + hk * D + dd));
+            const f32x4 v = sx_wait4(P, rn, (unsigned)(((size_t)m * 2 + isv) * P.KVD + hk * D + dd));
             char* dst = (isv ? sV : sK) + key * KSTR + dd * ESZ;
             if constexpr (Traits<WT>::BF) {
                 uint2 o;
@@ -1023,7 +1070,7 @@ __device__ void attn_phase(const StepParams& P, int wg, int nwg, char* smem) {
         for (int x = tid; x < Ra * (D / 4); x += PS_WG_THREADS) {
             const int rho = x / (D / 4), dd = (x - rho * (D / 4)) * 4;
             const int gi = rho / P.M, i = rho - gi * P.M;
-            const f32x4 v = ll_wait4(P, rq, (unsigned)((size_t)(b * P.M + i) * P.QD + (hk * grp + gi) * D + dd));
+            const f32x4 v = sx_wait4(P, rq, (unsigned)((size_t)(b * P.M + i) * P.QD + (hk * grp + gi) * D + dd));
             *reinterpret_cast<f32x4*>(sQ + rho * D + dd) = v;
         }
         __syncthreads();
@@ -1085,7 +1132,7 @@ __device__ void attn_phase(const StepParams& P, int wg, int nwg, char* smem) {
             if (nch == 1) {
                 // the only chunk: normalise and hand the row to the output projection
 #pragma unroll
-                for (int e = 0; e < DPL; ++e) ll_st1(ro, orow + e, o[e] / l, P.seq);
+                for (int e = 0; e < DPL; ++e) sx_st1(ro, orow + e, o[e] / l);
             } else {
                 // partial (max, sum, unnormalised output) of this chunk, as tagged data
                 const unsigned abase = (unsigned)(((size_t)item * Ra + rho) * D + lane * DPL);
@@ -1131,7 +1178,7 @@ __device__ void attn_phase(const StepParams& P, int wg, int nwg, char* smem) {
                     }
                 }
                 const int gi = rho / P.M, i = rho - gi * P.M;
-                ll_st1(ro, (unsigned)((size_t)(b * P.M + i) * P.QD + (hk * grp + gi) * D + dd), num / den, P.seq);
+                sx_st1(ro, (unsigned)((size_t)(b * P.M + i) * P.QD + (hk * grp + gi) * D + dd), num / den);
             }
         }
     }
@@ -1263,7 +1310,7 @@ __device__ void lm_merge_row(const StepParams& P, int m, int lane, u64* sk) {
 // kernels
 // ------------------------------------------------------------------------------------------
 template <typename WT, int MT, int PH>
-__global__ void __launch_bounds__(PS_WG_THREADS) gemm_kernel(const StepParams P) {
+__global__ void __launch_bounds__(PS_WG_THREADS, 1) gemm_kernel(const StepParams P) {
     extern __shared__ __attribute__((aligned(256))) char smem[];
     uint4 wb[PS_U];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -1294,7 +1341,7 @@ static __global__ void __launch_bounds__(256) probs_kernel(const StepParams P) {
 // While a workgroup waits for the activations of its next phase, the first weight loads of that
 // phase are already in flight.
 template <typename WT, int D, int MT>
-__global__ void __launch_bounds__(PS_WG_THREADS) fused_kernel(const StepParams P) {
+__global__ void __launch_bounds__(PS_WG_THREADS, 1) fused_kernel(const StepParams P) {
     extern __shared__ __attribute__((aligned(256))) char smem[];
     const int wg = blockIdx.x, wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     uint4 wb[PS_U];

@@ -41,6 +41,10 @@ struct ps_draft_ctx {
     float *q_buf, *o_buf, *y_buf, *u_buf, *y2_buf, *kvnew, *part, *ssq_part, *attn_acc, *attn_ml, *lm_part, *logits_ws;
     unsigned seq;                     // sequence number of the last enqueued step
     size_t exch_begin, exch_end;      // workspace range of the tagged exchange buffers (cleared at init)
+    char* act_base;                   // two copies of the activation buffers, act_bytes each
+    size_t act_bytes;
+    size_t off_q, off_o, off_y, off_u, off_y2, off_kvnew;   // offsets inside one copy
+    int last_shape[3];                // batch, n_new, k of the previous step
     char* wpack[PH_COUNT];
     int* counters;
     int n_counters;
@@ -85,6 +89,7 @@ struct WsLayout {
     size_t wpack[PH_COUNT];
     size_t rope, q_buf, o_buf, y_buf, u_buf, y2_buf, kvnew, part, ssq_part, attn_acc, attn_ml, counters, lm_part, logits_ws, total;
     size_t exch_begin, exch_end;
+    size_t act_base, act_bytes, off_q, off_o, off_y, off_u, off_y2, off_kvnew;
     size_t frag_cap;
     int n_counters;
 };
@@ -120,17 +125,25 @@ static WsLayout ws_layout(const ps_draft_config* c) {
     auto take = [&](size_t bytes) { size_t o = off; off = align256(off + bytes); return o; };
     int T[PH_COUNT], Kt[PH_COUNT];
     phase_dims(c, T, Kt);
-    // + 8 KiB: the streaming loop always loads 8 steps ahead, also at the end of the last tile
-    for (int ph = 0; ph < PH_COUNT; ++ph) L.wpack[ph] = take((size_t)T[ph] * Kt[ph] * 1024 + 8192);
+    // padding: the streaming loop always loads PS_U steps ahead, also at the end of the last tile
+    for (int ph = 0; ph < PH_COUNT; ++ph) L.wpack[ph] = take((size_t)T[ph] * Kt[ph] * 1024 + PS_U_MAX * 1024);
     L.rope = take((size_t)c->max_positions * (c->head_dim / 2) * sizeof(float2));
-    // tagged exchange buffers: 8 bytes per element (value + sequence number)
+    // activations between phases: fp32, two alternating copies (see PS_SENT in ps_device.h)
+    {
+        size_t a = 0;
+        auto sub = [&](size_t bytes) { size_t o = a; a = align256(a + bytes); return o; };
+        L.off_q = sub(rows * qd * 4);
+        L.off_o = sub(rows * qd * 4);
+        L.off_y = sub(rows * c->hidden * 4);
+        L.off_u = sub(rows * c->ffn * 4);
+        L.off_y2 = sub(rows * c->hidden * 4);
+        L.off_kvnew = sub(rows * 2 * (size_t)c->n_kv_heads * c->head_dim * 4);
+        L.act_bytes = a;
+        L.act_base = take(2 * a);
+    }
+    L.q_buf = L.o_buf = L.y_buf = L.u_buf = L.y2_buf = L.kvnew = 0;   // set per step from the copy in use
+    // tagged exchange buffers: 8 bytes per element (value + tag)
     L.exch_begin = off;
-    L.q_buf = take(rows * qd * 8);
-    L.o_buf = take(rows * qd * 8);
-    L.y_buf = take(rows * c->hidden * 8);
-    L.u_buf = take(rows * c->ffn * 8);
-    L.y2_buf = take(rows * c->hidden * 8);
-    L.kvnew = take(rows * 2 * (size_t)c->n_kv_heads * c->head_dim * 8);
     // split-K fragments: S * T never exceeds the wavefronts of a phase (see make_plan); one fragment
     // is 64 lanes x 4 values per column tile
     size_t frag = (size_t)PS_MAX_WG * PS_WAVES;
@@ -232,12 +245,10 @@ extern "C" int ps_draft_init(ps_draft_ctx** out, const ps_draft_config* config, 
     char* base = (char*)workspace;
     for (int ph = 0; ph < PH_COUNT; ++ph) ctx->wpack[ph] = base + L.wpack[ph];
     ctx->rope = (float2*)(base + L.rope);
-    ctx->q_buf = (float*)(base + L.q_buf);
-    ctx->o_buf = (float*)(base + L.o_buf);
-    ctx->y_buf = (float*)(base + L.y_buf);
-    ctx->u_buf = (float*)(base + L.u_buf);
-    ctx->y2_buf = (float*)(base + L.y2_buf);
-    ctx->kvnew = (float*)(base + L.kvnew);
+    ctx->act_base = base + L.act_base; ctx->act_bytes = L.act_bytes;
+    ctx->off_q = L.off_q; ctx->off_o = L.off_o; ctx->off_y = L.off_y; ctx->off_u = L.off_u;
+    ctx->off_y2 = L.off_y2; ctx->off_kvnew = L.off_kvnew;
+    ctx->last_shape[0] = ctx->last_shape[1] = ctx->last_shape[2] = -1;
     ctx->part = (float*)(base + L.part);
     ctx->ssq_part = (float*)(base + L.ssq_part);
     ctx->attn_acc = (float*)(base + L.attn_acc);
@@ -267,6 +278,7 @@ extern "C" int ps_draft_init(ps_draft_ctx** out, const ps_draft_config* config, 
     hipError_t e = hipMemcpyAsync(ctx->rope, tab.data(), tab.size() * sizeof(float2), hipMemcpyHostToDevice, s);
     // sequence numbers start at 1: cleared exchange buffers never look valid
     if (e == hipSuccess) e = hipMemsetAsync(base + L.exch_begin, 0, L.exch_end - L.exch_begin, s);
+    if (e == hipSuccess) e = hipMemsetAsync(ctx->act_base, 0xFF, 2 * L.act_bytes, s);   // both copies: nothing written yet
     if (e == hipSuccess) e = hipMemsetAsync(ctx->counters, 0, 64, s);
     {   // copy the five weight matrices into streaming order
         StepParams P;
@@ -383,12 +395,25 @@ extern "C" int ps_draft_step(ps_draft_ctx* ctx, const ps_draft_step_args* a, voi
     P.g_final = ctx->w.g_final; P.w_lm = ctx->w.w_lm; P.mask_emb = ctx->w.mask_emb;
     P.x = a->x; P.kc = a->k_cache; P.vc = a->v_cache;
     for (int ph = 0; ph < PH_COUNT; ++ph) P.wpack[ph] = ctx->wpack[ph];
-    P.rope = ctx->rope; P.q_buf = ctx->q_buf; P.o_buf = ctx->o_buf; P.y_buf = ctx->y_buf; P.u_buf = ctx->u_buf;
-    P.y2_buf = ctx->y2_buf; P.part = ctx->part; P.attn_acc = ctx->attn_acc; P.attn_ml = ctx->attn_ml;
-    P.lm_part = ctx->lm_part; P.ssq_part = ctx->ssq_part; P.kvnew = ctx->kvnew;
+    P.rope = ctx->rope; P.part = ctx->part; P.attn_acc = ctx->attn_acc; P.attn_ml = ctx->attn_ml;
+    P.lm_part = ctx->lm_part; P.ssq_part = ctx->ssq_part;
     P.error_flag = ctx->counters;
     ctx->seq = ctx->seq >= 0x1FFFFFF0u ? 1u : ctx->seq + 1u;   // seq * 8 + phase must fit in 32 bits; 0 = cleared
     P.seq = ctx->seq;
+    {   // the activation copy of this step; the other one is reset while this one is written
+        const int par = (int)(P.seq & 1u);
+        char* cur = ctx->act_base + (size_t)par * ctx->act_bytes;
+        P.q_buf = (float*)(cur + ctx->off_q); P.o_buf = (float*)(cur + ctx->off_o); P.y_buf = (float*)(cur + ctx->off_y);
+        P.u_buf = (float*)(cur + ctx->off_u); P.y2_buf = (float*)(cur + ctx->off_y2); P.kvnew = (float*)(cur + ctx->off_kvnew);
+        P.alt_delta = par ? -(long long)ctx->act_bytes : (long long)ctx->act_bytes;
+        // a step only resets the elements it writes: when the row layout changes, elements the previous
+        // step did not touch could still look written, so this step's copy is cleared first
+        if (ctx->last_shape[0] != a->batch || ctx->last_shape[1] != a->n_new || ctx->last_shape[2] != a->k) {
+            if (ctx->last_shape[0] >= 0 &&
+                !hip_ok(hipMemsetAsync(cur, 0xFF, ctx->act_bytes, (hipStream_t)stream), "hipMemsetAsync")) return PS_ERR_DEVICE;
+            ctx->last_shape[0] = a->batch; ctx->last_shape[1] = a->n_new; ctx->last_shape[2] = a->k;
+        }
+    }
     P.logits_store = a->logits ? a->logits : (a->probs ? ctx->logits_ws : nullptr);
     P.top_ids = a->top_ids; P.top_p = a->top_p; P.lse = a->lse; P.probs = a->probs; P.hidden_out = a->hidden_out;
     const int ch = ctx->inst->attn_chunk;
@@ -422,6 +447,7 @@ extern "C" int ps_draft_step(ps_draft_ctx* ctx, const ps_draft_step_args* a, voi
         if (P.plan[ph].lds_bytes > lds) lds = P.plan[ph].lds_bytes;
     }
     if (lds < 256 + 8192 + 128) lds = 256 + 8192 + 128;   // end-of-step merge scratch
+    if (lds < 84 * 1024 && ctx->lds_limit >= 84 * 1024) lds = 84 * 1024;   // more than half a CU's LDS: one workgroup per CU
     P.fused_nwg = nwg; P.fused_lds = lds;
     hipStream_t st = (hipStream_t)stream;
     hipEvent_t* ev = ctx->profile ? ctx->events : nullptr;

@@ -8,8 +8,17 @@
 #include "ps_draft.h"
 
 #define PS_MAX_ROWS 64     // activation rows per step (MFMA column tiles: up to 4 x 16)
-#define PS_WG_THREADS 1024 // one workgroup per compute unit, 16 wavefronts of 64 lanes
-#define PS_WAVES 16
+// One workgroup per compute unit.  512 threads = 8 wavefronts of 64 lanes, two per SIMD: each lane
+// may use 256 VGPRs, which pays for 16 weight loads in flight per lane and large staging batches
+// without spills (1024 threads would cap lanes at 128 VGPRs).
+#ifndef PS_WG_THREADS
+#define PS_WG_THREADS 512
+#endif
+#define PS_WAVES (PS_WG_THREADS / 64)
+#ifndef PS_U
+#define PS_U 16            // 16-byte weight loads in flight per lane (PS_U KiB per wavefront)
+#endif
+#define PS_U_MAX 32        // packed weight buffers are padded by this many KiB (streaming reads ahead)
 #define PS_LDS_BYTES (160 * 1024)
 
 enum { PH_QKV = 0, PH_OPROJ = 1, PH_GATEUP = 2, PH_DOWN = 3, PH_LMHEAD = 4, PH_COUNT = 5 };
@@ -41,9 +50,12 @@ struct StepParams {
     const char* wpack[PH_COUNT]; // matrices of each phase, prepacked at init in streaming order
     // workspace
     const float2* rope; // [max_positions][d/2] (cos, sin)
-    // Buffers exchanged between workgroups hold 8-byte units {value, seq}: element counts below.
+    // Activations between phases: plain fp32, 0xFFFFFFFF = not written yet; the copy for this step
+    // (two copies alternate), the other copy is alt_delta bytes away.
     float *q_buf, *o_buf, *y_buf, *u_buf, *y2_buf;   // [Mtot][QD], [Mtot][QD], [Mtot][H], [Mtot][F], [Mtot][H]
     float* kvnew;      // [Mtot][2][KVD] this step's K and V rows as stored in the cache
+    long long alt_delta;
+    // Buffers below hold 8-byte units {value, tag}: element counts.
     float* part;       // split-K fragments: [S][T][MT][64 lanes][4]
     float* ssq_part;   // per fragment: the K-slice's sums of squares of the activation rows (RMSNorm)
     float* attn_acc;   // [items][g*M][d] unnormalised partial outputs
