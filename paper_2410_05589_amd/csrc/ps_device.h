@@ -13,30 +13,28 @@
 //   LMHEAD  logits = RMSNorm(Y2[rows]; g_final) . Wlm^T -> per-workgroup (max, sum exp, top-k)
 //   MERGE   per row: log-sum-exp, top-k ids and probabilities
 //
-// They run either as one persistent kernel (one 1024-thread workgroup per compute unit, grid
-// barriers between phases, the next phase's first weight loads already in flight across each
-// barrier) or as one kernel per phase (profiling and fallback).
+// They run either as one persistent kernel (one 512-thread workgroup per compute unit, no grid
+// barriers, the next phase's first weight loads already in flight while a workgroup waits for its
+// activations) or as one kernel per phase (profiling).
 //
 // GEMM engine.  Weights are the 16-row MFMA operand.  At init they are repacked so that one
 // step (64 bytes of each of a tile's 16 rows) is one contiguous KiB in lane order; a wavefront
-// streams its tiles with 16-byte non-temporal loads, 8 in flight per lane, waiting only for the
-// oldest.  The few activation rows are the 16-column operand, staged once per workgroup in LDS.
+// streams its tiles with 16-byte non-temporal loads, PS_U in flight per lane, waiting only for
+// the oldest.  The few activation rows are the 16-column operand, staged once per workgroup in LDS.
 // bf16 weights use v_mfma_f32_16x16x32_bf16 twice per step: the fp32 activations are split into
 // a bf16 high and a bf16 low part (x = hi + lo to ~2^-17), so products with the exactly-bf16
 // weights keep fp32-class accuracy at no extra weight traffic.  f32 weights use
 // v_mfma_f32_16x16x4_f32.  Accumulation is fp32.  RMSNorm is folded in: the panel holds
 // x (.) gain, the per-row factor 1/rms multiplies the accumulator in the epilogue.
-// The contraction dimension is cut across workgroups (S slices) and/or across the wavefronts of
-// a workgroup (KW).  Slices meet through global fragments; the wavefront that arrives last at a
-// tile's counter adds the S fragments in slice order (results do not depend on arrival order)
-// and runs the phase epilogue.
+// The contraction dimension of a tile is shared by 1, 2, 4 or 8 wavefronts of one workgroup;
+// their partial sums meet in LDS and are added in a fixed order.
 //
 // Data that one workgroup writes and another reads inside the same step (activations between
-// phases, split-K fragments, attention partials, LM-head statistics) is exchanged WITHOUT
-// barriers, counters or fences: every 4-byte value travels with a 4-byte sequence number of the
-// step in one 8-byte unit, written and read with agent-scope (sc1) buffer accesses that write
-// through / bypass the per-XCD L2.  A consumer simply re-reads a unit until its sequence number
-// is the current step's.  The persistent kernel therefore has no grid-wide synchronisation:
+// phases, attention partials, LM-head statistics) is exchanged WITHOUT barriers, counters or
+// fences, with agent-scope (sc1) buffer accesses that write through / bypass the per-XCD L2:
+// activations are plain fp32 where the bit pattern 0xFFFFFFFF means "not written yet"; the other
+// buffers hold 8-byte units {value, sequence number of the step}.  A consumer simply re-reads
+// until the data is there.  The persistent kernel therefore has no grid-wide synchronisation:
 // each workgroup walks through the phases at its own pace and waits only for the data it needs.
 #pragma once
 #include "ps_internal.h"
@@ -282,9 +280,13 @@ __device__ __forceinline__ int key_id(u64 k) { return 0x7FFFFFFF - (int)(unsigne
 
 // Row m of the step's activation matrix Z = [x rows ; mask embeddings] (Section 4.1: the k
 // [MASK] tokens are appended after the sequence), element offset e.
+// m / M for the small row counts of a step, with the reciprocal the host prepared
+__device__ __forceinline__ int row_seq(const StepParams& P, int m) {
+    return P.M == 1 ? m : (int)__umulhi((unsigned)m, P.m_magic);
+}
 template <typename WT>
 __device__ __forceinline__ const char* z_ptr(const StepParams& P, int m, int e) {
-    const int b = m / P.M, i = m - b * P.M;
+    const int b = row_seq(P, m), i = m - b * P.M;
     const char* base;
     long long off;
     if (i < P.n_new) { base = (const char*)P.x; off = ((long long)(b * P.n_new + i)) * P.H + e; }
@@ -292,15 +294,35 @@ __device__ __forceinline__ const char* z_ptr(const StepParams& P, int m, int e) 
     return base + off * Traits<WT>::ESZ;
 }
 
-// Debugging aid: thread 0 of every workgroup stamps the 100 MHz wall clock at point `ev`.
+// Debugging aid (builds with -DPS_TIMELINE only): thread 0 of every workgroup notes the shader
+// clock at point `ev` in the top 512 bytes of LDS; flush_stamps copies them out at the end
+// together with the 100 MHz wall clock of the kernel's start and end.
+#define PS_TL_OFF (PS_LDS_BYTES - 512)
 __device__ __forceinline__ void stamp(const StepParams& P, int wg, int ev) {
 #ifdef PS_TIMELINE
-    if (P.timeline && threadIdx.x == 0) P.timeline[(size_t)ev * 1024 + wg] = wall_clock64();
+    extern __shared__ __attribute__((aligned(256))) char tl_smem[];
+    if (P.timeline && threadIdx.x == 0)
+        reinterpret_cast<volatile unsigned long long*>(tl_smem + PS_TL_OFF)[ev] = __builtin_amdgcn_s_memtime();
+#endif
+}
+__device__ __forceinline__ void stamp_wall(const StepParams& P, int wg, int ev) {
+#ifdef PS_TIMELINE
+    extern __shared__ __attribute__((aligned(256))) char tl_smem[];
+    if (P.timeline && threadIdx.x == 0)
+        reinterpret_cast<volatile unsigned long long*>(tl_smem + PS_TL_OFF)[ev] = wall_clock64();
+#endif
+}
+__device__ __forceinline__ void flush_stamps(const StepParams& P, int wg) {
+#ifdef PS_TIMELINE
+    extern __shared__ __attribute__((aligned(256))) char tl_smem[];
+    __syncthreads();
+    if (P.timeline && threadIdx.x < 64)
+        P.timeline[(size_t)threadIdx.x * 1024 + wg] = reinterpret_cast<unsigned long long*>(tl_smem + PS_TL_OFF)[threadIdx.x];
 #endif
 }
 
 // ------------------------------------------------------------------------------------------
-// GEMM phase descriptors: which weight row a lane streams, where activations come from
+// which weight row a lane of the init-time packing kernel copies
 // ------------------------------------------------------------------------------------------
 template <typename WT, int PH>
 __device__ __forceinline__ const char* weight_row_ptr(const StepParams& P, int tau, int i) {
@@ -330,26 +352,10 @@ __device__ __forceinline__ const char* weight_row_ptr(const StepParams& P, int t
     }
 }
 
-template <int PH> __device__ __forceinline__ int phase_K(const StepParams& P) {
-    return PH == PH_OPROJ ? P.QD : (PH == PH_DOWN ? P.F : P.H);
-}
-template <int PH> __device__ __forceinline__ int phase_rows(const StepParams& P) {
-    return PH == PH_LMHEAD ? P.Rtot : P.Mtot;
-}
-template <int PH> __device__ __forceinline__ bool phase_norm(const StepParams& P) {
-    return PH == PH_QKV || PH == PH_GATEUP || (PH == PH_LMHEAD && P.final_norm);
-}
-template <int PH> __device__ __forceinline__ const void* phase_gain(const StepParams& P) {
-    return PH == PH_QKV ? P.g_in : (PH == PH_GATEUP ? P.g_post : P.g_final);
-}
-// fp32 source buffer of the phase's activations (phases other than QKV) and its row stride
-template <int PH> __device__ __forceinline__ const float* phase_src(const StepParams& P) {
-    return PH == PH_OPROJ ? P.o_buf : (PH == PH_GATEUP ? P.y_buf : (PH == PH_DOWN ? P.u_buf : P.y2_buf));
-}
-template <int PH> __device__ __forceinline__ int phase_src_row(const StepParams& P, int r) {
-    if (PH != PH_LMHEAD) return r;
-    // decoding rows: last real row and the k mask rows of each sequence (or all rows)
-    const int b = r / P.R, jj = r - b * P.R;
+// Panel row r of the LM head is a decoding row: the last real row and the k mask rows of each
+// sequence (or all rows).
+__device__ __forceinline__ int lm_src_row(const StepParams& P, int r) {
+    const int b = P.R == 1 ? r : (int)__umulhi((unsigned)r, P.r_magic), jj = r - b * P.R;
     return b * P.M + (P.all_rows ? jj : (P.n_new - 1 + jj));
 }
 
@@ -393,114 +399,66 @@ __device__ __forceinline__ void mma_step(uint4 w, const BRegs<WT, MT>& b, f32x4 
 
 constexpr int PS_WS = 1024;   // prepacked weights: one step of a tile = 64 lanes x 16 B, contiguous
 
-// Issues the first PS_U loads of a weight stream.  Weights do not depend on the activations, so
-// this can run before the panel is staged (and before the grid barrier that ends the previous
-// phase): the HBM pipe stays busy while the activations arrive.  Every load is unconditional
-// (streams shorter than PS_U steps read on into the following KiBs, which always exist: the
-// packed buffers are padded), so the compiler can count outstanding loads exactly.
-__device__ __forceinline__ void preload_weights(uint4 (&wb)[PS_U], const char* wp) {
+// Issues the first PS_U loads of a weight stream (base is wavefront-uniform, lane16 = 16 * lane).
+// Weights do not depend on the activations, so this runs before the panel is staged: the HBM
+// pipe stays busy while the activations arrive.
+__device__ __forceinline__ void preload_weights(uint4 (&wb)[PS_U], const char* base, int lane16) {
 #pragma unroll
-    for (int u = 0; u < PS_U; ++u) wb[u] = ldg_stream16(wp + u * PS_WS);
+    for (int u = 0; u < PS_U; ++u) wb[u] = ldg_stream16(base + u * PS_WS + lane16);
 }
 
-// Software pipeline over the n steps of one weight stream: step t multiplies the weights loaded
-// PS_U steps earlier with the B operands read one step earlier, then refills its register with
-// step t + PS_U and reads the B operands of step t + 1.  Loads past the end of the stream
-// continue at next_wp (the wavefront's next stream), so when this returns wb holds the
-// preloaded head of that stream.  Only the oldest load is waited for at each step.
+// Software pipeline over the n steps (a positive multiple of PS_U) of one weight stream: step t
+// multiplies the weights loaded PS_U steps earlier with the B operands read one step earlier,
+// then refills its register with step t + PS_U and reads the B operands of step t + 1.  The
+// loads of the last group start the wavefront's next stream, so when this returns wb holds the
+// head of that stream.  Every load is unconditional and only the oldest is waited for.
 template <typename WT, int MT>
-__device__ __forceinline__ void consume_weights(uint4 (&wb)[PS_U], const char* wp, int n_, const char* next_wp,
+__device__ __forceinline__ void consume_weights(uint4 (&wb)[PS_U], const char* wp, int n, const char* next_wp, int lane16,
                                                 const char* const (&pa)[MT], const int (&pinc)[MT],
                                                 const int (&plo)[MT], f32x4 (&acc)[MT]) {
     constexpr int U = PS_U;
-    const int n = __builtin_amdgcn_readfirstlane(n_);   // wavefront-uniform: keep the loop control scalar
-    const int n_main = n & ~(U - 1), r = n - n_main;
     BRegs<WT, MT> bc, bn;
     load_b<WT, MT>(bc, pa, pinc, plo, 0);
-    const int last = n > 0 ? n - 1 : 0;
-    int t0 = 0;
-    for (; t0 + 2 * U <= n_main; t0 += U) {   // steady state: every load is inside this stream
+    for (int t0 = 0; t0 < n; t0 += U) {
+        const char* src = (t0 + U < n) ? wp + (size_t)(t0 + U) * PS_WS : next_wp;
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             mma_step<WT, MT>(wb[u], bc, acc);
-            wb[u] = ldg_stream16(wp + (size_t)(t0 + u + U) * PS_WS);   // reuses the register just consumed
-            load_b<WT, MT>(bn, pa, pinc, plo, t0 + u + 1);
+            wb[u] = ldg_stream16(src + u * PS_WS + lane16);   // reuses the register just consumed
+            int tb = t0 + u + 1;
+            if (u == U - 1 && tb >= n) tb = n - 1;            // nothing follows the last step
+            load_b<WT, MT>(bn, pa, pinc, plo, tb);
             bc = bn;
             __builtin_amdgcn_sched_barrier(0);
         }
-    }
-    if (t0 < n_main) {   // last full group: its loads start the next stream (or fetch the tail steps)
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            mma_step<WT, MT>(wb[u], bc, acc);
-            const int idx = t0 + u + U;
-            const char* src = r == 0 ? next_wp + (size_t)u * PS_WS
-                                     : wp + (size_t)(idx < n ? idx : last) * PS_WS;   // tail, then harmless re-reads
-            wb[u] = ldg_stream16(src);
-            const int tb = t0 + u + 1;
-            load_b<WT, MT>(bn, pa, pinc, plo, tb < n ? tb : last);
-            bc = bn;
-            __builtin_amdgcn_sched_barrier(0);
-        }
-    }
-    if (r != 0 || n == 0) {   // K not a multiple of PS_U steps: finish the tail, then start the next stream afresh
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            if (u < r) {
-                mma_step<WT, MT>(wb[u], bc, acc);
-                const int tb = n_main + u + 1;
-                load_b<WT, MT>(bn, pa, pinc, plo, tb < n ? tb : last);
-                bc = bn;
-            }
-        }
-        preload_weights(wb, next_wp);
     }
 }
 
-// Where the weight stream of segment q of this wavefront starts, and its length in steps.
-// A phase is cut into rounds (one tile per wavefront slot per round) and, inside a round, into
-// the K-pieces whose activation panel fits in LDS; segment q = round * pieces + piece.
-struct PhaseGeom {
-    int S, KW, s, j, Gs, k_lo, k_hi, SL, slot, kw, per_round, rounds, nsub, nseg;
-    bool active;
-};
-template <int PH>
-__device__ __forceinline__ PhaseGeom phase_geom(const StepParams& P, int wg, int wave) {
-    const PhasePlan& pl = P.plan[PH];
-    PhaseGeom g;
-    g.S = pl.S; g.KW = pl.KW;
-    g.s = wg % g.S; g.j = wg / g.S; g.Gs = pl.nwg / g.S;
-    g.active = g.j < g.Gs;
-    g.k_lo = (int)((long long)g.s * pl.Kt / g.S); g.k_hi = (int)((long long)(g.s + 1) * pl.Kt / g.S);
-    g.SL = PS_WAVES / g.KW; g.slot = wave / g.KW; g.kw = wave - g.slot * g.KW;
-    g.per_round = g.Gs * g.SL;
-    g.rounds = g.active ? (pl.T + g.per_round - 1) / g.per_round : 0;
-    g.nsub = (g.k_hi - g.k_lo + pl.panel_steps - 1) / pl.panel_steps;
-    g.nseg = g.rounds * g.nsub;
-    return g;
+// Head of the stream of wavefront kw (of the 2^kw_log that share tile tau) inside the panel piece
+// that covers groups [g_lo, g_lo + ng); a0 = the stream's first step relative to the piece,
+// n = its length in steps.  The host makes sure every piece has at least 2^kw_log groups.
+__device__ __forceinline__ const char* stream_ptr(const PhaseDesc& D, int tau, int g_lo, int ng, int kw, int& a0, int& n) {
+    const int w0 = (kw * ng) >> D.kw_log, w1 = ((kw + 1) * ng) >> D.kw_log;
+    a0 = w0 * PS_U;
+    n = (w1 - w0) * PS_U;
+    return D.wpack + ((size_t)tau * D.Kt + (size_t)(g_lo + w0) * PS_U) * PS_WS;
 }
-struct WeightSeg { const char* wp; int n; int tau; int a; int b; bool valid; };
-template <int PH>
-__device__ __forceinline__ WeightSeg segment(const StepParams& P, const PhaseGeom& g, int q, int lane) {
-    const PhasePlan& pl = P.plan[PH];
-    WeightSeg sg;
-    const int rd = q / g.nsub, si = q - rd * g.nsub;
-    sg.tau = rd * g.per_round + g.slot * g.Gs + g.j;
-    sg.valid = q < g.nseg && sg.tau < pl.T;
-    sg.a = g.k_lo + si * pl.panel_steps;
-    sg.b = min(sg.a + pl.panel_steps, g.k_hi);
-    const int n = sg.b - sg.a;
-    const int t0 = (int)((long long)g.kw * n / g.KW), t1 = (int)((long long)(g.kw + 1) * n / g.KW);
-    sg.n = sg.valid ? t1 - t0 : 0;
-    // invalid segments point at the start of the packed matrix: always readable, always cached
-    sg.wp = P.wpack[PH] + (sg.valid ? ((size_t)sg.tau * pl.Kt + sg.a + t0) * PS_WS : (size_t)0) + lane * 16;
-    return sg;
+// The groups [lo, hi) of the contraction dimension that K-slice s of a phase covers, and the
+// piece pc of it that is staged at a time.
+__device__ __forceinline__ void slice_groups(const PhaseDesc& D, int s, int& lo, int& hi) {
+    const int NG = D.Kt / PS_U;
+    lo = (s * NG) >> D.s_log;
+    hi = ((s + 1) * NG) >> D.s_log;
 }
-// head of the stream a wavefront reads first in phase PH
-template <int PH>
-__device__ __forceinline__ const char* first_stream(const StepParams& P, int wg, int wave, int lane) {
-    const PhaseGeom g = phase_geom<PH>(P, wg, wave);
-    return segment<PH>(P, g, 0, lane).wp;
+// Head of the stream a wavefront reads first in phase ph (any readable address if it has none)
+__device__ __forceinline__ const char* first_stream(const StepParams& P, int ph, int wg, int wave) {
+    const PhaseDesc& D = P.ph[ph];
+    const int s = wg & ((1 << D.s_log) - 1), j = wg >> D.s_log;
+    const int tau = (wave >> D.kw_log) * D.Gs + j;
+    if (tau >= D.T) return D.wpack;
+    int lo, hi, a0, n;
+    slice_groups(D, s, lo, hi);
+    return stream_ptr(D, tau, lo, min(D.piece_groups, hi - lo), wave & ((1 << D.kw_log) - 1), a0, n);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -510,8 +468,8 @@ __device__ __forceinline__ const char* first_stream(const StepParams& P, int wg,
 template <typename WT, int MT>
 __device__ __forceinline__ void epilogue_qkv(const StepParams& P, int tau, int lane, f32x4 (&acc)[MT]) {
     const int c = lane & 15, q = lane >> 4;
-    const int tph = P.d >> 4, half = P.d >> 1;
-    const int hh = tau / tph, sub = tau - hh * tph;
+    const int half = P.d >> 1;
+    const int hh = tau >> P.tph_log, sub = tau - (hh << P.tph_log);   // head_dim / 16 tiles per head
     const int jb = 8 * sub + 4 * (q & 1);            // rotary frequency index of this lane's 4 values
     const int f = jb + ((q >= 2) ? half : 0);        // feature inside the head
     const SxBuf rq = sx_buf(P, P.q_buf), rn = sx_buf(P, P.kvnew);
@@ -522,7 +480,7 @@ __device__ __forceinline__ void epilogue_qkv(const StepParams& P, int tau, int l
         for (int r = 0; r < 4; ++r) pv[r] = __shfl_xor(v[r], 32, 64);   // rotary partner (j <-> j + d/2)
         const int m = 16 * mt + c;
         if (m >= P.Mtot) continue;
-        const int b = m / P.M, i = m - b * P.M;
+        const int b = row_seq(P, m), i = m - b * P.M;
         const int pos = P.kv_len[b] + i;             // positions continue after the valid cache rows
         f32x4 o = v;
         if (hh < P.nq + P.nkv) {
@@ -633,146 +591,173 @@ __host__ __device__ inline int panel_row_stride(int panel_steps) {
     return len + ((64 - (len & 255)) + 256) % 256;
 }
 // LDS layout of a GEMM phase (bytes from the start of dynamic LDS)
-#define PS_LDS_SSQ 0        // [64 units] partial sums of squares (RMSNorm)
-#define PS_LDS_ZERO 256     // 64 zero bytes: B operand of unused MFMA columns
-#define PS_LDS_RED 512      // [16 wavefronts][MT][64 lanes] f32x4: K-split inside the workgroup
+#define PS_LDS_SSQ 0        // [64 rows][8] partial sums of squares (RMSNorm)
+#define PS_LDS_ZERO 2048    // 64 zero bytes: B operand of unused MFMA columns
+#define PS_LDS_RED 2304     // [wavefronts][MT][64 lanes] f32x4: partial sums of wavefronts sharing a tile
 __host__ __device__ inline int panel_offset(int mt) { return PS_LDS_RED + PS_WAVES * mt * 1024; }
 
-// Stages steps [a, b) of the activation panel: rows x (b-a) x 4 groups of 16 bytes.  A unit is
-// (row, part of the row's groups); wavefronts take units round-robin, lanes stride over the
-// groups, four groups per lane are loaded before any is processed.  The panel holds x (.) gain
-// (RMSNorm's 1/rms is applied in the epilogue); the unit's sum of x^2 goes to s_ssq[unit].
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+// two floats -> two bf16 (round to nearest even) in one dword, first value in the low half
+__device__ __forceinline__ unsigned pack_bf16x2(float a, float b) {
+    const f32x2_t v = {a, b};
+    return __builtin_bit_cast(unsigned, __builtin_convertvector(v, bf16x2_t));
+}
+
+// Stages steps [a_step, a_step + nsteps) of the activation panel.  The 16-byte groups of a row
+// lie along 2^g2_log threads, the remaining threads take different rows; every thread requests
+// its group of RB rows before it uses any of them (one memory round trip per RB rows), and
+// re-requests them until none holds the "not written" pattern.  The panel holds x (.) gain
+// (RMSNorm's 1/rms is applied in the epilogue); the sum of x^2 of row r over the groups a
+// wavefront saw goes to s_ssq[8 r + w] (w = the wavefront's index along the row).
 template <typename WT, int PH>
-__device__ __forceinline__ void stage_panel(const StepParams& P, char* smem, int RS, char* s_pa, char* s_pb,
-                                            int rows, int a, int b, bool norm, bool first_piece, bool want_ssq) {
+__device__ __forceinline__ void stage_piece(const StepParams& P, const PhaseDesc& D, int wave, char* smem,
+                                            char* s_pa, char* s_pb, int a_step, int nsteps, bool first_piece,
+                                            bool want_ssq, uint4 (&wb)[PS_U], const char* late_wp) {
     constexpr bool BF = Traits<WT>::BF;
     constexpr int KSTEP = Traits<WT>::KSTEP, GE = Traits<WT>::GE, ESZ = Traits<WT>::ESZ;
-    constexpr int BATCH = 4;                         // groups per lane requested before any is used
-    constexpr int NL = GE / 4;                       // 4-element loads per group
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    constexpr int NL = GE / 4;                       // 16-byte loads per group of exchanged fp32
+    constexpr int RB = 8;                            // rows per thread requested before any is used
+    constexpr bool from_x = PH == PH_QKV;            // the step's input rows, complete at launch
+    const int tid = threadIdx.x, lane = tid & 63;
     float* s_ssq = reinterpret_cast<float*>(smem + PS_LDS_SSQ);
-    const int groups = (b - a) * 4;
-    const int wpr = rows >= PS_WAVES ? 1 : PS_WAVES / rows;      // units per row
-    const int units = rows * wpr;
-    const void* gain = phase_gain<PH>(P);
-    const rsrc_t rs = make_rsrc(PH == PH_QKV ? (const void*)P.x : (const void*)phase_src<PH>(P));
-    const int ld = phase_K<PH>(P);
-    for (int u = wave; u < units; u += PS_WAVES) {
-        const int r = u / wpr, sub = u - r * wpr;
-        const int g0 = (int)((long long)sub * groups / wpr), g1 = (int)((long long)(sub + 1) * groups / wpr);
-        const int srow = phase_src_row<PH>(P, r);
-        float ss = 0.f;
-        for (int gb = g0 + lane; gb - lane < g1; gb += 64 * BATCH) {
-            uint4 zraw[BATCH], graw[BATCH];
-            u32x4 araw[BATCH][NL];
+    const int G = nsteps * 4;
+    const int g2_log = D.g2_log, G2 = 1 << g2_log;
+    // rows are wavefront-uniform (2^g2_log >= 64 threads lie along a row): everything that
+    // depends only on the row is scalar arithmetic
+    const int gi0 = tid & (G2 - 1), rsub = (wave << 6) >> g2_log, nrt = PS_WG_THREADS >> g2_log;
+    const int wsub = wave & ((G2 >> 6) - 1);
+    const int rows = D.rows, K = D.K, RS = D.rs, ld = D.src_ld;
+    const bool norm = PH == PH_QKV || PH == PH_GATEUP || (PH == PH_LMHEAD && D.norm != 0);
+    const rsrc_t rs = make_rsrc(from_x ? P.x : (const void*)D.src), rmask = make_rsrc(from_x ? P.mask_emb : (const void*)D.src);
+    if (late_wp && rsub >= rows) {   // wavefronts without a row to stage
+        preload_weights(wb, late_wp, lane * 16);
+        late_wp = nullptr;
+    }
+    for (int gc = 0; gc < G; gc += G2) {
+        const int gi = gc + gi0;
+        const bool gvalid = gi < G;
+        const int gic = gvalid ? gi : G - 1;         // clamped: loads stay unconditional
+        const int kk = a_step * KSTEP + gic * GE;
+        const bool live = gvalid && kk < K;          // beyond K the packed weights are zero: so is the panel
+        const int kkc = kk < K ? kk : 0;
+        float gn[GE];
+        if (norm) unpack_group<WT>(ld16((const char*)D.gain + (size_t)kkc * ESZ), gn);
+        for (int rb = rsub; rb < rows; rb += nrt * RB) {
+            u32x4 raw[RB][NL];
             int spins = 0;
             for (;;) {
+#pragma unroll
+                for (int i = 0; i < RB; ++i) {
+                    const int r = min(rb + nrt * i, rows - 1);   // clamped: every load is unconditional
+                    if (from_x) {
+                        // row r of Z = [x rows ; mask embeddings] of its sequence
+                        const int b = row_seq(P, r), ii = r - b * P.M;
+                        raw[i][0] = ii < P.n_new
+                            ? __builtin_amdgcn_raw_buffer_load_b128(rs, kkc * ESZ, (b * P.n_new + ii) * P.H * ESZ, 0)
+                            : __builtin_amdgcn_raw_buffer_load_b128(rmask, kkc * ESZ, (ii - P.n_new) * P.H * ESZ, 0);
+                    } else {
+                        const int srow = PH == PH_LMHEAD ? lm_src_row(P, r) : r;
+#pragma unroll
+                        for (int h = 0; h < NL; ++h)
+                            raw[i][h] = __builtin_amdgcn_raw_buffer_load_b128(rs, (kkc + 4 * h) * 4, srow * ld * 4, PS_SC1);
+                    }
+                }
+                if (late_wp) {   // the step's first weight loads queue up behind the first activation loads
+                    preload_weights(wb, late_wp, lane * 16);
+                    late_wp = nullptr;
+                }
+                if (from_x) break;
                 bool ok = true;
 #pragma unroll
-                for (int i = 0; i < BATCH; ++i) {
-                    int gi = gb + 64 * i;
-                    if (gi >= g1) gi = g1 - 1;                   // clamped: loads stay unconditional
-                    const int kk = a * KSTEP + gi * GE;
-                    if (PH == PH_QKV) {
-                        zraw[i] = ld16(z_ptr<WT>(P, r, kk));
-                    } else {
+                for (int i = 0; i < RB; ++i)
 #pragma unroll
-                        for (int h = 0; h < NL; ++h) araw[i][h] = coh_ld16(rs, (unsigned)((size_t)srow * ld + kk + 4 * h) * 4);
-                    }
-                    if (norm) graw[i] = ld16((const char*)gain + (size_t)kk * ESZ);
-                }
-                if (PH == PH_QKV) break;                         // the step's inputs were complete at launch
-#pragma unroll
-                for (int i = 0; i < BATCH; ++i)
-#pragma unroll
-                    for (int h = 0; h < NL; ++h) ok = ok && sx_ok(araw[i][h]);
+                    for (int h = 0; h < NL; ++h) ok = ok && sx_ok(raw[i][h]);
                 if (__all(ok) || !spin_again(P, spins)) break;   // produced earlier in this step: wait for it
             }
 #pragma unroll
-            for (int i = 0; i < BATCH; ++i) {
-                const int gi = gb + 64 * i;
-                if (gi >= g1) continue;
+            for (int i = 0; i < RB; ++i) {
+                const int r = rb + nrt * i;
+                if (r >= rows) continue;
                 float v[GE];
-                if (PH == PH_QKV) {
-                    unpack_group<WT>(zraw[i], v);
+                if (from_x) {
+                    unpack_group<WT>(make_uint4(raw[i][0][0], raw[i][0][1], raw[i][0][2], raw[i][0][3]), v);
                 } else {
 #pragma unroll
-                    for (int h = 0; h < NL; ++h) {
-                        const f32x4 t = __builtin_bit_cast(f32x4, araw[i][h]);
-                        v[4 * h] = t[0]; v[4 * h + 1] = t[1]; v[4 * h + 2] = t[2]; v[4 * h + 3] = t[3];
+                    for (int h = 0; h < NL; ++h)
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) v[4 * h + j] = __uint_as_float(raw[i][h][j]);
+                }
+                float ss = 0.f;
+#pragma unroll
+                for (int e = 0; e < GE; ++e) {
+                    if (!live) v[e] = 0.f;
+                    if (norm) { ss += v[e] * v[e]; v[e] *= gn[e]; }
+                }
+                if (gvalid) {
+                    if constexpr (BF) {
+                        uint4 ph4, pl4;
+                        unsigned* hp = &ph4.x;
+                        unsigned* lp = &pl4.x;
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+                            const unsigned hi = pack_bf16x2(v[2 * j], v[2 * j + 1]);
+                            hp[j] = hi;
+                            lp[j] = pack_bf16x2(v[2 * j] - __uint_as_float(hi << 16), v[2 * j + 1] - __uint_as_float(hi & 0xFFFF0000u));
+                        }
+                        *reinterpret_cast<uint4*>(s_pa + r * RS + gi * 16) = ph4;
+                        *reinterpret_cast<uint4*>(s_pb + r * RS + gi * 16) = pl4;
+                    } else {
+                        *reinterpret_cast<uint4*>(s_pa + r * RS + gi * 16) =
+                            make_uint4(__float_as_uint(v[0]), __float_as_uint(v[1]), __float_as_uint(v[2]), __float_as_uint(v[3]));
                     }
                 }
-                if (norm) {
-                    float gn[GE];
-                    unpack_group<WT>(graw[i], gn);
-#pragma unroll
-                    for (int e = 0; e < GE; ++e) { ss += v[e] * v[e]; v[e] *= gn[e]; }
-                }
-                if constexpr (BF) {
-                    uint32_t hi[GE], lo[GE];
-#pragma unroll
-                    for (int e = 0; e < GE; ++e) {
-                        hi[e] = f32_to_bf16(v[e]);
-                        lo[e] = f32_to_bf16(v[e] - bf16_to_f32(hi[e]));
-                    }
-                    uint4 ph, plw;
-                    ph.x = hi[0] | (hi[1] << 16); ph.y = hi[2] | (hi[3] << 16);
-                    ph.z = hi[4] | (hi[5] << 16); ph.w = hi[6] | (hi[7] << 16);
-                    plw.x = lo[0] | (lo[1] << 16); plw.y = lo[2] | (lo[3] << 16);
-                    plw.z = lo[4] | (lo[5] << 16); plw.w = lo[6] | (lo[7] << 16);
-                    *reinterpret_cast<uint4*>(s_pa + (size_t)r * RS + gi * 16) = ph;
-                    *reinterpret_cast<uint4*>(s_pb + (size_t)r * RS + gi * 16) = plw;
-                } else {
-                    uint4 pv;
-                    pv.x = __float_as_uint(v[0]); pv.y = __float_as_uint(v[1]);
-                    pv.z = __float_as_uint(v[2]); pv.w = __float_as_uint(v[3]);
-                    *reinterpret_cast<uint4*>(s_pa + (size_t)r * RS + gi * 16) = pv;
+                if (norm && want_ssq) {
+                    ss = wave_sum(ss);
+                    if (lane == 0) s_ssq[r * 8 + wsub] = (first_piece && gc == 0) ? ss : s_ssq[r * 8 + wsub] + ss;
                 }
             }
-        }
-        if (norm && want_ssq) {
-            ss = wave_sum(ss);
-            if (lane == 0) s_ssq[u] = first_piece ? ss : s_ssq[u] + ss;
         }
     }
 }
 
-// 1/rms of panel row m from the per-unit sums in LDS (this workgroup's K-slice)
-__device__ __forceinline__ float slice_ssq(const char* smem, int rows, int m) {
-    const float* s_ssq = reinterpret_cast<const float*>(smem + PS_LDS_SSQ);
-    const int wpr = rows >= PS_WAVES ? 1 : PS_WAVES / rows;
-    float t = 0.f;
-    for (int sub = 0; sub < wpr; ++sub) t += s_ssq[m * wpr + sub];
-    return t;
-}
-
-// wb: the wavefront's weight-load registers.  On entry they hold the preloaded head of segment 0
-// (preload_weights(first_stream<PH>(..))); on exit they hold PS_U loads from after_wp (the head of
-// whatever this wavefront streams next, or any readable address).
+// One phase for one workgroup.  wb: the wavefront's weight-load registers.  On entry they hold
+// the preloaded head of first_stream(ph) - or nothing yet if late_wp is that head: then the loads
+// are issued right after the first activation loads (loads return in order, so at the start of
+// the step the activations should not wait behind the weights).  On exit they hold PS_U loads
+// from after_wp (the head of whatever this wavefront streams next, or any readable address).
 template <typename WT, int MT, int PH>
-__device__ void gemm_phase(const StepParams& P, int wg, char* smem, uint4 (&wb)[PS_U], const char* after_wp) {
+__device__ __forceinline__ void gemm_phase(const StepParams& P, int wg, int wave, char* smem, uint4 (&wb)[PS_U],
+                                           const char* after_wp, const char* late_wp) {
     constexpr bool BF = Traits<WT>::BF;
-    const PhasePlan pl = P.plan[PH];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    constexpr int ph = PH;
+    constexpr bool sliceable = PH == PH_OPROJ || PH == PH_GATEUP || PH == PH_DOWN;   // see make_desc on the host
+    const PhaseDesc& D = P.ph[ph];
+    const int tid = threadIdx.x, lane = tid & 63, lane16 = lane * 16;
     const int c = lane & 15, kb = lane >> 4;
-    const int rows = phase_rows<PH>(P);
-    const int K = phase_K<PH>(P);
-    const PhaseGeom g = phase_geom<PH>(P, wg, wave);
-    const int S = g.S, KW = g.KW, s = g.s, SL = g.SL, slot = g.slot, kw = g.kw;
-    const bool norm = phase_norm<PH>(P);
+    const int rows = D.rows;
+    const int kw_log = D.kw_log, KW = 1 << kw_log, SL = PS_WAVES >> kw_log, sl_log = PS_WAVES_LOG - kw_log;
+    const int slot = wave >> kw_log, kw = wave & (KW - 1);
+    const int S = sliceable ? 1 << D.s_log : 1, s = wg & (S - 1), j = sliceable ? wg >> D.s_log : wg;   // K-slice and column of this workgroup
+    const int RS = D.rs;
 
     char* s_zero = smem + PS_LDS_ZERO;
     char* s_red = smem + PS_LDS_RED;
-    const int RS = panel_row_stride(pl.panel_steps);
     char* s_pa = smem + panel_offset(MT);                        // high parts (or f32 values)
-    char* s_pb = s_pa + (size_t)rows * RS;                       // low parts (bf16 only)
-    float* s_lm = reinterpret_cast<float*>(s_pb + (BF ? (size_t)rows * RS : 0));
+    char* s_pb = s_pa + rows * RS;                               // low parts (bf16 only)
+    float* s_lm = reinterpret_cast<float*>(s_pb + (BF ? rows * RS : 0));
+    const float* s_ssq = reinterpret_cast<const float*>(smem + PS_LDS_SSQ);
+    const int nsub = (1 << D.g2_log) >> 6;                       // entries of s_ssq per row
+    const bool norm = PH == PH_QKV || PH == PH_GATEUP || (PH == PH_LMHEAD && D.norm != 0);
 
-    stamp(P, wg, PH * 4 + 0);
-    if (g.active) {
+    stamp(P, wg, 2 + ph * 6 + 0);
+    if (j >= D.T) {                   // more workgroup columns than tiles: nothing to do in this phase
+        preload_weights(wb, after_wp, lane16);
+        return;
+    }
     if (tid < 16) reinterpret_cast<uint32_t*>(s_zero)[tid] = 0u;
-    if (PH == PH_LMHEAD) {
-        const int n_lm = g.rounds * SL * rows * 16;
+    if (ph == PH_LMHEAD) {
+        const int n_lm = D.rounds * SL * rows * 16;
         for (int x = tid; x < n_lm; x += PS_WG_THREADS) s_lm[x] = -INFINITY;
     }
 
@@ -782,43 +767,49 @@ __device__ void gemm_phase(const StepParams& P, int wg, char* smem, uint4 (&wb)[
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
         const int m = 16 * mt + c;
-        if (m < rows) { pa[mt] = s_pa + (size_t)m * RS + kb * 16; pinc[mt] = 64; plo[mt] = (int)(s_pb - s_pa); }
+        if (m < rows) { pa[mt] = s_pa + m * RS + kb * 16; pinc[mt] = 64; plo[mt] = (int)(s_pb - s_pa); }
         else { pa[mt] = s_zero + kb * 16; pinc[mt] = 0; plo[mt] = 0; }
     }
+    int sg_lo, sg_hi;
+    slice_groups(D, s, sg_lo, sg_hi);
 
-    int staged_a = -1, staged_b = -1;
-    f32x4 acc[MT];
-    for (int q = 0; q < g.nseg; ++q) {
-        const WeightSeg sg = segment<PH>(P, g, q, lane);
-        const int rd = q / g.nsub, si = q - rd * g.nsub;
-        const int tau = sg.tau;
-        const bool valid = sg.valid;
-        if (si == 0) {
+    bool streamed = false;
+    for (int rd = 0; rd < D.rounds; ++rd) {
+        const int tau = rd * D.per_round + slot * D.Gs + j;
+        const bool valid = tau < D.T;
+        f32x4 acc[MT];
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt) acc[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
-        }
-        const int a = sg.a, b = sg.b;
-        if (a != staged_a || b != staged_b) {
-            if (q > 0) __syncthreads();   // everyone is done with the previous panel
-            stage_panel<WT, PH>(P, smem, RS, s_pa, s_pb, rows, a, b, norm, si == 0, rd == 0);
-            __syncthreads();
-            staged_a = a; staged_b = b;
-        }
-        if (q == 0) stamp(P, wg, PH * 4 + 1);
-        {
-            // this wavefront's share [t0, t1) of the staged piece; the stream continues in segment q + 1
-            const int n = b - a;
-            const int t0 = (int)((long long)kw * n / KW);
-            const char* next_wp = (q + 1 < g.nseg) ? segment<PH>(P, g, q + 1, lane).wp : after_wp;
-            const char* pa_t[MT];
+        for (int mt = 0; mt < MT; ++mt) acc[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int pc = 0; pc < D.npieces; ++pc) {
+            const int g_lo = sg_lo + pc * D.piece_groups;
+            const int ng = min(D.piece_groups, sg_hi - g_lo);
+            if (rd == 0 || D.npieces > 1) {   // a panel that fits as a whole is staged once
+                if (rd > 0 || pc > 0) __syncthreads();   // everyone is done with the previous piece
+                stage_piece<WT, PH>(P, D, wave, smem, s_pa, s_pb, g_lo * PS_U, ng * PS_U, pc == 0, rd == 0, wb,
+                                rd == 0 && pc == 0 ? late_wp : nullptr);
+                __syncthreads();
+                if (rd == 0 && pc == 0) stamp(P, wg, 2 + ph * 6 + 1);
+            }
+            if (valid) {
+                int a0, n, na, nn;
+                const char* wp = stream_ptr(D, tau, g_lo, ng, kw, a0, n);
+                const char* next_wp = after_wp;
+                if (pc + 1 < D.npieces) {
+                    const int g2 = g_lo + D.piece_groups;
+                    next_wp = stream_ptr(D, tau, g2, min(D.piece_groups, sg_hi - g2), kw, na, nn);
+                } else if (rd + 1 < D.rounds && tau + D.per_round < D.T) {
+                    next_wp = stream_ptr(D, tau + D.per_round, sg_lo, min(D.piece_groups, sg_hi - sg_lo), kw, na, nn);
+                }
+                const char* pa_t[MT];
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt) pa_t[mt] = pa[mt] + t0 * pinc[mt];
-            consume_weights<WT, MT>(wb, sg.wp, sg.n, next_wp, pa_t, pinc, plo, acc);
+                for (int mt = 0; mt < MT; ++mt) pa_t[mt] = pa[mt] + a0 * pinc[mt];
+                consume_weights<WT, MT>(wb, wp, n, next_wp, lane16, pa_t, pinc, plo, acc);
+                streamed = true;
+            }
         }
-        if (si != g.nsub - 1) continue;
-        if (q == g.nseg - 1) stamp(P, wg, PH * 4 + 2);
+        if (rd == D.rounds - 1) stamp(P, wg, 2 + ph * 6 + 2);
 
-        // K-split inside the workgroup: wavefront kw = 0 of each slot adds the others in order
+        // wavefronts sharing the tile: wavefront kw = 0 adds the others' partial sums in order
         if (KW > 1) {
             f32x4* red = reinterpret_cast<f32x4*>(s_red);
             if (valid && kw > 0) {
@@ -832,101 +823,96 @@ __device__ void gemm_phase(const StepParams& P, int wg, char* smem, uint4 (&wb)[
                     for (int mt = 0; mt < MT; ++mt) acc[mt] += red[((wave + o) * MT + mt) * 64 + lane];
                 }
             }
-            __syncthreads();
+            if (rd + 1 < D.rounds) __syncthreads();
         }
+        if (rd == D.rounds - 1) stamp(P, wg, 2 + ph * 6 + 3);
 
         if (valid && kw == 0) {
-            // sum of squares of this lane's activation rows over the workgroup's K-slice
-            float ssq[MT];
+            if (sliceable && S > 1) {
+                // K-slices of other workgroups: publish this slice's part of the tile (and, once per
+                // slice, its sums of squares); the sums are formed after the last round
+                const SxBuf rfrag = sx_buf(P, D.frag), rssq = sx_buf(P, D.ssq_frag);
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt) {
-                const int m = 16 * mt + c;
-                ssq[mt] = (norm && m < rows) ? slice_ssq(smem, rows, m) : 0.f;
-            }
-            bool run_epilogue = true;
-            if (S > 1) {
-                // K-slices of other workgroups meet here.  Every slice publishes its fragment (and its
-                // sums of squares) as tagged data; the wavefront of slice tau % S waits for the other
-                // S - 1 fragments and adds all S in slice order, so the result does not depend on timing.
-                const rsrc_t rp = make_rsrc(P.part), rq = make_rsrc(P.ssq_part);
-                // all phases share the fragment buffer: the tag names the phase as well as the step
-                const unsigned ftag = P.seq * 8u + PH + 1u;
-                const int s_red = tau % S;
-                run_epilogue = (s == s_red);
-                if (!run_epilogue) {
-                    const unsigned fb = (unsigned)((size_t)s * pl.T + tau);
-#pragma unroll
-                    for (int mt = 0; mt < MT; ++mt) {
-                        ll_st4(rp, ((fb * MT + mt) * 64 + lane) * 4, acc[mt], ftag);
-                        if (norm && lane < 16) ll_st1(rq, fb * PS_MAX_ROWS + 16 * mt + lane, ssq[mt], ftag);
-                    }
-                } else {
-                    f32x4 own[MT];
-                    float own_q[MT];
-#pragma unroll
-                    for (int mt = 0; mt < MT; ++mt) {
-                        own[mt] = acc[mt]; own_q[mt] = ssq[mt];
-                        acc[mt] = f32x4{0.f, 0.f, 0.f, 0.f}; ssq[mt] = 0.f;
-                    }
-                    for (int s0 = 0; s0 < S; s0 += 4) {   // four slices are requested per round trip
-                        LL4 fr[4][MT];
-                        u32x2 fq[4][MT];
-                        int spins = 0;
-                        for (;;) {
-                            bool ok = true;
-#pragma unroll
-                            for (int i = 0; i < 4; ++i) {
-                                int ss = s0 + i < S ? s0 + i : S - 1;
-                                const bool mine = ss == s;
-                                if (mine) ss = (s + 1) % S;   // placeholder load, never used
-                                const unsigned fb = (unsigned)((size_t)ss * pl.T + tau);
-#pragma unroll
-                                for (int mt = 0; mt < MT; ++mt) {
-                                    fr[i][mt] = ll_ld4(rp, ((fb * MT + mt) * 64 + lane) * 4);
-                                    fq[i][mt] = coh_ld8(rq, (fb * PS_MAX_ROWS + 16 * mt + c) * 8);
-                                    if (!mine) {
-                                        ok = ok && ll_ok(fr[i][mt], ftag);
-                                        if (norm && 16 * mt + c < rows) ok = ok && fq[i][mt][1] == ftag;
-                                    }
-                                }
-                            }
-                            if (__all(ok) || !spin_again(P, spins)) break;
-                        }
-#pragma unroll
-                        for (int i = 0; i < 4; ++i) {
-                            const int ss = s0 + i;
-                            if (ss >= S) continue;
-#pragma unroll
-                            for (int mt = 0; mt < MT; ++mt) {
-                                if (ss == s) { acc[mt] += own[mt]; ssq[mt] += own_q[mt]; }
-                                else { acc[mt] += ll_val(fr[i][mt]); ssq[mt] += __uint_as_float(fq[i][mt][0]); }
-                            }
-                        }
-                    }
+                for (int mt = 0; mt < MT; ++mt)
+                    sx_st4(rfrag, (unsigned)((((s * D.T + tau) * MT + mt) * 64 + lane) * 4), acc[mt]);
+                if (norm && rd == 0 && j == 0 && slot == 0 && lane < rows) {
+                    float t = 0.f;
+                    for (int w = 0; w < nsub; ++w) t += s_ssq[lane * 8 + w];
+                    sx_st1(rssq, (unsigned)(s * PS_MAX_ROWS + lane), t);
                 }
-            }
-            if (run_epilogue) {
+            } else {
                 if (norm) {   // RMSNorm: the panel held x (.) gain, 1/rms multiplies the result
 #pragma unroll
                     for (int mt = 0; mt < MT; ++mt) {
-                        const float rinv = 1.0f / sqrtf(ssq[mt] / (float)K + P.eps);
-                        acc[mt] *= rinv;
+                        const int m = 16 * mt + c;
+                        float t = 0.f;
+                        if (m < rows)
+                            for (int w = 0; w < nsub; ++w) t += s_ssq[m * 8 + w];
+                        acc[mt] *= 1.0f / sqrtf(t / (float)D.K + P.eps);
                     }
                 }
-                if (PH == PH_QKV) epilogue_qkv<WT, MT>(P, tau, lane, acc);
-                else if (PH == PH_OPROJ) epilogue_oproj<WT, MT>(P, tau, lane, acc);
-                else if (PH == PH_GATEUP) epilogue_gateup<WT, MT>(P, tau, lane, acc);
-                else if (PH == PH_DOWN) epilogue_down<WT, MT>(P, tau, lane, acc);
-                else epilogue_lm<WT, MT>(P, tau, lane, acc, s_lm, rd * SL + slot);
+                switch (ph) {
+                    case PH_QKV: epilogue_qkv<WT, MT>(P, tau, lane, acc); break;
+                    case PH_OPROJ: epilogue_oproj<WT, MT>(P, tau, lane, acc); break;
+                    case PH_GATEUP: epilogue_gateup<WT, MT>(P, tau, lane, acc); break;
+                    case PH_DOWN: epilogue_down<WT, MT>(P, tau, lane, acc); break;
+                    default: epilogue_lm<WT, MT>(P, tau, lane, acc, s_lm, rd * SL + slot); break;
+                }
             }
         }
     }
-    stamp(P, wg, PH * 4 + 3);
+    if (sliceable && S > 1) {
+        // Sum over the K-slices.  Of the tiles of this workgroup column, slice s completes every S-th;
+        // its wavefronts take one each, wait for all S parts (its own included) and add them in slice
+        // order, so the result does not depend on timing.  Then the phase's epilogue.
+        const rsrc_t rf = make_rsrc(D.frag), rq = make_rsrc(D.ssq_frag);
+        const int ntl = D.rounds * SL;
+        for (int lt = s + S * wave; lt < ntl; lt += S * PS_WAVES) {
+            const int tau = (lt >> sl_log) * D.per_round + (lt & (SL - 1)) * D.Gs + j;
+            if (tau >= D.T) continue;
+            f32x4 acc[MT];
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) {
+                constexpr int SB = 8;                // slices requested per round trip (S <= 8)
+                const int m = 16 * mt + c;
+                u32x4 fr[SB];
+                unsigned fq[SB];
+                int spins = 0;
+                for (;;) {
+                    bool ok = true;
+#pragma unroll
+                    for (int i = 0; i < SB; ++i) {
+                        const int ss = i < S ? i : S - 1;
+                        fr[i] = coh_ld16(rf, (unsigned)((((ss * D.T + tau) * MT + mt) * 64 + lane) * 16));
+                        fq[i] = norm ? coh_ld4(rq, (unsigned)((ss * PS_MAX_ROWS + (m < rows ? m : 0)) * 4)) : 0u;
+                        ok = ok && sx_ok(fr[i]) && fq[i] != PS_SENT;
+                    }
+                    if (__all(ok) || !spin_again(P, spins)) break;
+                }
+                f32x4 sum = f32x4{0.f, 0.f, 0.f, 0.f};
+                float t = 0.f;
+#pragma unroll
+                for (int i = 0; i < SB; ++i) {
+                    if (i < S) { sum += __builtin_bit_cast(f32x4, fr[i]); t += __uint_as_float(fq[i]); }
+                }
+                if (norm) sum *= 1.0f / sqrtf(t / (float)D.K + P.eps);
+                acc[mt] = sum;
+            }
+            switch (ph) {
+                case PH_QKV: epilogue_qkv<WT, MT>(P, tau, lane, acc); break;
+                case PH_OPROJ: epilogue_oproj<WT, MT>(P, tau, lane, acc); break;
+                case PH_GATEUP: epilogue_gateup<WT, MT>(P, tau, lane, acc); break;
+                default: epilogue_down<WT, MT>(P, tau, lane, acc); break;
+            }
+        }
+    }
+    stamp(P, wg, 2 + ph * 6 + 4);
+    if (!streamed) preload_weights(wb, after_wp, lane16);   // keep the contract on wb
 
-    if (PH == PH_LMHEAD) {
+    if (ph == PH_LMHEAD) {
         // per-workgroup softmax statistics and top-k over the logits held in LDS: one wavefront per row
         __syncthreads();
-        const int n_el = g.rounds * SL * 16;
+        const int n_el = D.rounds * SL * 16;
         const int topk = P.topk;
         const rsrc_t rl = make_rsrc(P.lm_part);
         const unsigned stride = 2 + 2 * topk;   // tagged elements: max, sum exp, topk keys (low, high word)
@@ -940,19 +926,18 @@ __device__ void gemm_phase(const StepParams& P, int wg, char* smem, uint4 (&wb)[
                 keys[i] = 0;
                 if (x < n_el) {
                     const int lt = x >> 4;
-                    const float v = s_lm[((size_t)lt * rows + m) * 16 + (x & 15)];
-                    const int rd2 = lt / SL, sl2 = lt - rd2 * SL;
-                    const int id = 16 * (rd2 * g.per_round + sl2 * g.Gs + g.j) + (x & 15);
+                    const float v = s_lm[(lt * rows + m) * 16 + (x & 15)];
+                    const int id = 16 * ((lt >> sl_log) * D.per_round + (lt & (SL - 1)) * D.Gs + j) + (x & 15);
                     if (v > -INFINITY) { keys[i] = make_key(v, id); mx = fmaxf(mx, v); }
                 }
             }
-            for (int x = lane + 64 * EPL; x < n_el; x += 64) mx = fmaxf(mx, s_lm[((size_t)(x >> 4) * rows + m) * 16 + (x & 15)]);
+            for (int x = lane + 64 * EPL; x < n_el; x += 64) mx = fmaxf(mx, s_lm[((x >> 4) * rows + m) * 16 + (x & 15)]);
             mx = wave_max(mx);
             float se = 0.f;
             if (mx > -INFINITY)
-                for (int x = lane; x < n_el; x += 64) se += expf(s_lm[((size_t)(x >> 4) * rows + m) * 16 + (x & 15)] - mx);
+                for (int x = lane; x < n_el; x += 64) se += expf(s_lm[((x >> 4) * rows + m) * 16 + (x & 15)] - mx);
             se = wave_sum(se);
-            const unsigned obase = (unsigned)(((size_t)wg * rows + m) * stride);
+            const unsigned obase = (unsigned)((wg * rows + m) * stride);
             if (lane < 2) ll_st1(rl, obase + lane, lane ? se : mx, P.seq);
             u64 prev = ~0ull;   // keys are unique: the next winner is the largest key below the previous one
             for (int t = 0; t < topk; ++t) {
@@ -962,9 +947,8 @@ __device__ void gemm_phase(const StepParams& P, int wg, char* smem, uint4 (&wb)[
                     if (keys[i] < prev && keys[i] > best) best = keys[i];
                 for (int x = lane + 64 * EPL; x < n_el; x += 64) {
                     const int lt = x >> 4;
-                    const float v = s_lm[((size_t)lt * rows + m) * 16 + (x & 15)];
-                    const int rd2 = lt / SL, sl2 = lt - rd2 * SL;
-                    const int id = 16 * (rd2 * g.per_round + sl2 * g.Gs + g.j) + (x & 15);
+                    const float v = s_lm[(lt * rows + m) * 16 + (x & 15)];
+                    const int id = 16 * ((lt >> sl_log) * D.per_round + (lt & (SL - 1)) * D.Gs + j) + (x & 15);
                     const u64 kx = v > -INFINITY ? make_key(v, id) : 0;
                     if (kx < prev && kx > best) best = kx;
                 }
@@ -975,10 +959,7 @@ __device__ void gemm_phase(const StepParams& P, int wg, char* smem, uint4 (&wb)[
             }
         }
     }
-    } else {
-        preload_weights(wb, after_wp);   // keep the contract on wb for workgroups without work here
-    }
-    stamp(P, wg, 20 + PH);
+    stamp(P, wg, 2 + ph * 6 + 5);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -986,41 +967,79 @@ __device__ void gemm_phase(const StepParams& P, int wg, char* smem, uint4 (&wb)[
 // the exact order the streaming loop reads it: lane (i = lane % 16, kb = lane / 16) gets bytes
 // [64 t + 16 kb, +16) of tile row i, so a wavefront load is one contiguous 1 KiB burst.
 // ------------------------------------------------------------------------------------------
+// Steps Kreal .. Kt-1 (the padding of the contraction dimension to whole groups) hold zeros.
 template <typename WT, int PH>
-__global__ void __launch_bounds__(256) pack_kernel(const StepParams P, int T, int Kt, char* dst) {
+__global__ void __launch_bounds__(256) pack_kernel(const StepParams P, int T, int Kt, int Kreal, char* dst) {
     const size_t units = (size_t)T * Kt;
     const int lane = threadIdx.x & 63;
     for (size_t u = (size_t)blockIdx.x * 4 + (threadIdx.x >> 6); u < units; u += (size_t)gridDim.x * 4) {
         const int tau = (int)(u / Kt), t = (int)(u - (size_t)tau * Kt);
-        const char* src = weight_row_ptr<WT, PH>(P, tau, lane & 15) + (size_t)t * 64 + (lane >> 4) * 16;
-        *reinterpret_cast<uint4*>(dst + u * 1024 + lane * 16) = ld16(src);
+        uint4 v = make_uint4(0u, 0u, 0u, 0u);
+        if (t < Kreal) v = ld16(weight_row_ptr<WT, PH>(P, tau, lane & 15) + (size_t)t * 64 + (lane >> 4) * 16);
+        *reinterpret_cast<uint4*>(dst + u * 1024 + lane * 16) = v;
     }
 }
 
 // ------------------------------------------------------------------------------------------
-// attention: one work item = (sequence b, kv head hk, chunk of CH keys); all g*M query rows
-// of the kv head are processed against the chunk; K/V tiles are staged in LDS; row i of the
-// step sees cache positions 0 .. kv_len[b] + i (its own and earlier rows of this step
-// included; Algorithm 1: distribution j is conditioned on [MASK]_1..j only).
+// attention: one work item = (sequence b, kv head hk, chunk of CH keys); all g*M query rows of
+// the kv head are processed against the chunk.  Row i of the step sees cache positions
+// 0 .. kv_len[b] + i (its own and earlier rows of this step included; Algorithm 1: distribution
+// j is conditioned on [MASK]_1..j only).
+//
+// Each wavefront takes 16 keys of the chunk.  Scores are one MFMA tile per 16 query rows: the
+// keys' K rows are the 16-row operand, loaded straight from the cache in its storage type; the
+// query rows (fp32, split into bf16 high + low parts like every activation) are the 16-column
+// operand.  The row maxima of the eight wavefronts meet in LDS, so all of them exponentiate
+// against the same maximum and their partial sums and partial P.V products simply add up, in
+// wavefront order.  P.V is plain FMA work: a lane owns D/64 adjacent output columns, reads the
+// V rows of its wavefront's keys with coalesced loads and the probabilities as LDS broadcasts.
+// Keys written in this very step come, exactly as stored in the cache, from the exchange buffer
+// the QKV epilogue fills.
 // ------------------------------------------------------------------------------------------
 template <typename WT, int D> struct AttnCfg {
-    static constexpr int CH = Traits<WT>::BF ? 128 : (D == 64 ? 128 : 64);
-    static constexpr int LDS = 256 + PS_MAX_ROWS * D * 4 + PS_MAX_ROWS * CH * 4 + 2 * CH * (D * Traits<WT>::ESZ + 16);
+    static constexpr int CH = 16 * PS_WAVES;
+    static constexpr int OFF_M = 256;                                // [waves][16] row maxima
+    static constexpr int OFF_L = OFF_M + PS_WAVES * 16 * 4;          // [waves][16] row sums
+    static constexpr int OFF_P = OFF_L + PS_WAVES * 16 * 4;          // [waves][16 rows][16 keys]
+    static constexpr int OFF_O = OFF_P + PS_WAVES * 16 * 16 * 4;     // [waves][16 rows][D]
+    static constexpr int LDS = OFF_O + PS_WAVES * 16 * D * 4;
 };
 
+// DPL adjacent elements of a V row in the cache's storage type -> floats
+template <typename WT, int DPL> __device__ __forceinline__ void load_v(const char* p, float* out) {
+    if constexpr (Traits<WT>::BF) {
+        if constexpr (DPL == 2) {
+            const uint32_t u = *reinterpret_cast<const uint32_t*>(p);
+            out[0] = bf16_to_f32(u & 0xFFFFu); out[1] = bf16_to_f32(u >> 16);
+        } else {
+            out[0] = bf16_to_f32(*reinterpret_cast<const uint16_t*>(p));
+        }
+    } else {
+        if constexpr (DPL == 2) {
+            const float2 u = *reinterpret_cast<const float2*>(p);
+            out[0] = u.x; out[1] = u.y;
+        } else {
+            out[0] = *reinterpret_cast<const float*>(p);
+        }
+    }
+}
+
 template <typename WT, int D>
-__device__ void attn_phase(const StepParams& P, int wg, int nwg, char* smem) {
-    constexpr int CH = AttnCfg<WT, D>::CH;
-    constexpr int ESZ = Traits<WT>::ESZ, GE = Traits<WT>::GE;
-    constexpr int KSTR = D * ESZ + 16;              // padded K/V row stride in LDS (bytes)
+__device__ __forceinline__ void attn_phase(const StepParams& P, int wg, int nwg, int wave, char* smem) {
+    typedef AttnCfg<WT, D> C;
+    constexpr bool BF = Traits<WT>::BF;
+    constexpr int CH = C::CH, ESZ = Traits<WT>::ESZ, GE = Traits<WT>::GE, KSTEP = Traits<WT>::KSTEP;
+    constexpr int NL = GE / 4;                      // 16-byte loads per group of exchanged fp32
+    constexpr int STEPS = D / KSTEP;                // MFMA steps along the head dimension
     constexpr int DPL = D / 64;                     // output columns per lane
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int c = lane & 15, kb = lane >> 4;
     const int grp = P.nq / P.nkv;
     const int Ra = grp * P.M;
-    float* sQ = reinterpret_cast<float*>(smem + 256);           // [Ra][D]
-    float* sP = sQ + PS_MAX_ROWS * D;                           // [Ra][CH]
-    char* sK = reinterpret_cast<char*>(sP + PS_MAX_ROWS * CH);  // [CH][KSTR]
-    char* sV = sK + CH * KSTR;
+    float* sM = reinterpret_cast<float*>(smem + C::OFF_M);
+    float* sL = reinterpret_cast<float*>(smem + C::OFF_L);
+    float* sP = reinterpret_cast<float*>(smem + C::OFF_P);
+    float* sO = reinterpret_cast<float*>(smem + C::OFF_O);
     const rsrc_t rq = make_rsrc(P.q_buf), rn = make_rsrc(P.kvnew), racc = make_rsrc(P.attn_acc),
                  rml = make_rsrc(P.attn_ml);
     const SxBuf ro = sx_buf(P, P.o_buf);
@@ -1035,112 +1054,199 @@ __device__ void attn_phase(const StepParams& P, int wg, int nwg, char* smem) {
         }
         const int hk = rem / nch, ch = rem - hk * nch;
         const int L = P.kv_len[b];
-        const int c0 = ch * CH, c1 = min(c0 + CH, L + P.M);
-        const int nk = c1 - c0;
-        __syncthreads();   // previous item's LDS use is over
-        // stage the K/V chunk: rows already in the cache come from there; rows of this step come,
-        // exactly as stored, from the tagged side buffer the QKV epilogue fills
-        constexpr int GPR = D / GE;   // 16-byte groups per key row
-        for (int x = tid; x < nk * GPR; x += PS_WG_THREADS) {
-            const int key = x / GPR, gg = x - key * GPR;
-            if (c0 + key < L) {
-                const size_t e = ((size_t)(P.kv_off[b] + c0 + key) * P.nkv + hk) * D + gg * GE;
-                *reinterpret_cast<uint4*>(sK + key * KSTR + gg * 16) = ld16((const char*)P.kc + e * ESZ);
-                *reinterpret_cast<uint4*>(sV + key * KSTR + gg * 16) = ld16((const char*)P.vc + e * ESZ);
-            }
-        }
-        const int n_old = L > c0 ? min(L - c0, nk) : 0;          // keys of this chunk that were cached
-        for (int x = tid; x < (nk - n_old) * 2 * (D / 4); x += PS_WG_THREADS) {
-            const int kn = x / (2 * (D / 4)), rest = x - kn * (2 * (D / 4));
-            const int isv = rest / (D / 4), dd = (rest - isv * (D / 4)) * 4;
-            const int key = n_old + kn;
-            const int m = b * P.M + (c0 + key - L);
-            const f32x4 v = sx_wait4(P, rn, (unsigned)(((size_t)m * 2 + isv) * P.KVD + hk * D + dd));
-            char* dst = (isv ? sV : sK) + key * KSTR + dd * ESZ;
-            if constexpr (Traits<WT>::BF) {
-                uint2 o;
-                o.x = f32_to_bf16(v[0]) | (f32_to_bf16(v[1]) << 16);
-                o.y = f32_to_bf16(v[2]) | (f32_to_bf16(v[3]) << 16);
-                *reinterpret_cast<uint2*>(dst) = o;
-            } else {
-                *reinterpret_cast<f32x4*>(dst) = v;
-            }
-        }
-        // Q rows of the head group
-        for (int x = tid; x < Ra * (D / 4); x += PS_WG_THREADS) {
-            const int rho = x / (D / 4), dd = (x - rho * (D / 4)) * 4;
-            const int gi = rho / P.M, i = rho - gi * P.M;
-            const f32x4 v = sx_wait4(P, rq, (unsigned)((size_t)(b * P.M + i) * P.QD + (hk * grp + gi) * D + dd));
-            *reinterpret_cast<f32x4*>(sQ + rho * D + dd) = v;
-        }
-        __syncthreads();
-        for (int rho = wave; rho < Ra; rho += PS_WAVES) {
-            const int gi = rho / P.M, i = rho - gi * P.M;
-            const int last_visible = L + i;            // absolute position
-            // scores: lane handles keys lane, lane + 64, ...
-            constexpr int KPL = CH / 64;
-            float sc[KPL];
-            float mx = -INFINITY;
+        const int c0 = ch * CH;
+        const int key0 = c0 + 16 * wave;            // this wavefront's keys: positions key0 .. key0 + 15
+        const int end = L + P.M;                    // positions that exist
+        const bool has_new = key0 + 15 >= L && key0 < end;
+        const size_t cache_row0 = (size_t)P.kv_off[b] * P.nkv + hk;   // in units of D elements
+
+        // ---- this wavefront's K rows (MFMA operand: lane (c, kb) holds 16 bytes of key c) and V rows
+        const int kpos = key0 + c;
+        const bool k_new = kpos >= L;
+        uint4 kreg[STEPS];
+        {
+            const int pc = kpos < L ? kpos : (L > 0 ? L - 1 : 0);     // clamped: the load stays unconditional
+            const char* krow = (const char*)P.kc + (cache_row0 + (size_t)pc * P.nkv) * D * ESZ + kb * 16;
 #pragma unroll
-            for (int kk = 0; kk < KPL; ++kk) {
-                const int key = lane + 64 * kk;
-                float dot = 0.f;
-                if (key < nk && c0 + key <= last_visible) {
-                    const char* krow = sK + key * KSTR;
-#pragma unroll 4
-                    for (int gg = 0; gg < GPR; ++gg) {
-                        float kv[GE];
-                        load_group<WT>(krow + gg * 16, kv);
+            for (int t = 0; t < STEPS; ++t) kreg[t] = ld16(krow + t * 64);
+        }
+        float v[16][DPL];
 #pragma unroll
-                        for (int e = 0; e < GE; e += 4) {
-                            const f32x4 qv = *reinterpret_cast<const f32x4*>(sQ + rho * D + gg * GE + e);
-                            dot += qv[0] * kv[e] + qv[1] * kv[e + 1] + qv[2] * kv[e + 2] + qv[3] * kv[e + 3];
+        for (int kk = 0; kk < 16; ++kk) {
+            const int pos = key0 + kk;                               // wavefront-uniform
+#pragma unroll
+            for (int e = 0; e < DPL; ++e) v[kk][e] = 0.f;
+            if (pos < L)
+                load_v<WT, DPL>((const char*)P.vc + ((cache_row0 + (size_t)pos * P.nkv) * D + DPL * lane) * ESZ, v[kk]);
+        }
+        if (has_new) {   // rows of this step: wait until the QKV phase has published them
+            const int pn = kpos < L ? L : (kpos < end ? kpos : end - 1);
+            const unsigned kbase = (unsigned)(((size_t)(b * P.M + (pn - L)) * 2) * P.KVD + hk * D + kb * GE);
+            u32x4 kx[STEPS][NL];
+            float vx[16][DPL];
+            int spins = 0;
+            for (;;) {
+                bool ok = true;
+#pragma unroll
+                for (int t = 0; t < STEPS; ++t)
+#pragma unroll
+                    for (int h = 0; h < NL; ++h) {
+                        kx[t][h] = coh_ld16(rn, (kbase + t * KSTEP + 4 * h) * 4);
+                        ok = ok && (!k_new || kpos >= end || sx_ok(kx[t][h]));
+                    }
+#pragma unroll
+                for (int kk = 0; kk < 16; ++kk) {
+                    const int pos = key0 + kk;
+                    if (pos >= L && pos < end) {
+                        const unsigned vb = (unsigned)(((size_t)(b * P.M + (pos - L)) * 2 + 1) * P.KVD + hk * D + DPL * lane);
+#pragma unroll
+                        for (int e = 0; e < DPL; ++e) {
+                            const unsigned u = coh_ld4(rn, (vb + e) * 4);
+                            ok = ok && u != PS_SENT;
+                            vx[kk][e] = __uint_as_float(u);
                         }
                     }
-                    sc[kk] = dot * P.inv_sqrt_d;
-                } else {
-                    sc[kk] = -INFINITY;                // masked in-register
                 }
-                mx = fmaxf(mx, sc[kk]);
+                if (__all(ok) || !spin_again(P, spins)) break;
             }
-            mx = wave_max(mx);
-            float l = 0.f;
+            if (k_new) {
 #pragma unroll
-            for (int kk = 0; kk < KPL; ++kk) {
-                const float p = (sc[kk] > -INFINITY) ? expf(sc[kk] - mx) : 0.f;
-                l += p;
-                sP[rho * CH + lane + 64 * kk] = p;
-            }
-            l = wave_sum(l);
-            // P.V: lane owns DPL adjacent output columns
-            float o[DPL];
-#pragma unroll
-            for (int e = 0; e < DPL; ++e) o[e] = 0.f;
-#pragma unroll 4
-            for (int key = 0; key < nk; ++key) {
-                const float p = sP[rho * CH + key];
-                const char* vrow = sV + key * KSTR + lane * DPL * ESZ;
-#pragma unroll
-                for (int e = 0; e < DPL; ++e) {
-                    float vv;
-                    if constexpr (Traits<WT>::BF) vv = bf16_to_f32(*reinterpret_cast<const uint16_t*>(vrow + e * 2));
-                    else vv = *reinterpret_cast<const float*>(vrow + e * 4);
-                    o[e] += p * vv;
+                for (int t = 0; t < STEPS; ++t) {
+                    if constexpr (BF) {
+                        kreg[t].x = pack_bf16x2(__uint_as_float(kx[t][0][0]), __uint_as_float(kx[t][0][1]));
+                        kreg[t].y = pack_bf16x2(__uint_as_float(kx[t][0][2]), __uint_as_float(kx[t][0][3]));
+                        kreg[t].z = pack_bf16x2(__uint_as_float(kx[t][1][0]), __uint_as_float(kx[t][1][1]));
+                        kreg[t].w = pack_bf16x2(__uint_as_float(kx[t][1][2]), __uint_as_float(kx[t][1][3]));
+                    } else {
+                        kreg[t] = make_uint4(kx[t][0][0], kx[t][0][1], kx[t][0][2], kx[t][0][3]);
+                    }
                 }
             }
-            const unsigned orow = (unsigned)((size_t)(b * P.M + i) * P.QD + (hk * grp + gi) * D + lane * DPL);
-            if (nch == 1) {
-                // the only chunk: normalise and hand the row to the output projection
 #pragma unroll
-                for (int e = 0; e < DPL; ++e) sx_st1(ro, orow + e, o[e] / l);
-            } else {
-                // partial (max, sum, unnormalised output) of this chunk, as tagged data
-                const unsigned abase = (unsigned)(((size_t)item * Ra + rho) * D + lane * DPL);
+            for (int kk = 0; kk < 16; ++kk) {
+                const int pos = key0 + kk;
+                if (pos >= L && pos < end) {
 #pragma unroll
-                for (int e = 0; e < DPL; ++e) ll_st1(racc, abase + e, o[e], P.seq);
-                if (lane < 2) ll_st1(rml, (unsigned)(((size_t)item * Ra + rho) * 2 + lane), lane ? l : mx, P.seq);
+                    for (int e = 0; e < DPL; ++e) v[kk][e] = vx[kk][e];
+                }
             }
         }
+
+        for (int r0 = 0; r0 < Ra; r0 += 16) {       // 16 query rows per pass
+            const int nr = min(16, Ra - r0);
+            // ---- query rows as the 16-column operand: lane (c, kb) holds row r0 + c
+            const int rho = r0 + c < Ra ? r0 + c : Ra - 1;
+            const int gi = row_seq(P, rho), i = rho - gi * P.M;
+            const unsigned qbase = (unsigned)((size_t)(b * P.M + i) * P.QD + (hk * grp + gi) * D + kb * GE);
+            BRegs<WT, 1> bq[STEPS];
+            {
+                u32x4 qx[STEPS][NL];
+                int spins = 0;
+                for (;;) {
+                    bool ok = true;
+#pragma unroll
+                    for (int t = 0; t < STEPS; ++t)
+#pragma unroll
+                        for (int h = 0; h < NL; ++h) {
+                            qx[t][h] = coh_ld16(rq, (qbase + t * KSTEP + 4 * h) * 4);
+                            ok = ok && sx_ok(qx[t][h]);
+                        }
+                    if (__all(ok) || !spin_again(P, spins)) break;
+                }
+#pragma unroll
+                for (int t = 0; t < STEPS; ++t) {
+                    if constexpr (BF) {
+                        unsigned* hp = &bq[t].h[0].x;
+                        unsigned* lp = &bq[t].l[0].x;
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+                            const float f0 = __uint_as_float(qx[t][j >> 1][2 * (j & 1)]);
+                            const float f1 = __uint_as_float(qx[t][j >> 1][2 * (j & 1) + 1]);
+                            const unsigned hi = pack_bf16x2(f0, f1);
+                            hp[j] = hi;
+                            lp[j] = pack_bf16x2(f0 - __uint_as_float(hi << 16), f1 - __uint_as_float(hi & 0xFFFF0000u));
+                        }
+                    } else {
+                        bq[t].h[0] = make_uint4(qx[t][0][0], qx[t][0][1], qx[t][0][2], qx[t][0][3]);
+                    }
+                }
+            }
+            if (item == wg && r0 == 0) stamp(P, wg, 33);
+            // ---- scores of keys 4 kb .. 4 kb + 3 (of this wavefront's 16) for query row c
+            f32x4 acc[1] = {f32x4{0.f, 0.f, 0.f, 0.f}};
+#pragma unroll
+            for (int t = 0; t < STEPS; ++t) mma_step<WT, 1>(kreg[t], bq[t], acc);
+            float sc[4], mloc = -INFINITY;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int pos = key0 + 4 * kb + r;
+                const bool vis = r0 + c < Ra && pos < end && pos <= L + i;
+                sc[r] = vis ? acc[0][r] * P.inv_sqrt_d : -INFINITY;
+                mloc = fmaxf(mloc, sc[r]);
+            }
+            mloc = fmaxf(mloc, __shfl_xor(mloc, 16, 64));
+            mloc = fmaxf(mloc, __shfl_xor(mloc, 32, 64));
+            __syncthreads();                        // the previous pass is done with the LDS areas
+            if (kb == 0) sM[wave * 16 + c] = mloc;
+            __syncthreads();
+            float mrow = -INFINITY;
+#pragma unroll
+            for (int w = 0; w < PS_WAVES; ++w) mrow = fmaxf(mrow, sM[w * 16 + c]);
+            f32x4 pr;
+            float lloc = 0.f;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                pr[r] = sc[r] > -INFINITY ? expf(sc[r] - mrow) : 0.f;
+                lloc += pr[r];
+            }
+            lloc += __shfl_xor(lloc, 16, 64);
+            lloc += __shfl_xor(lloc, 32, 64);
+            if (kb == 0) sL[wave * 16 + c] = lloc;
+            *reinterpret_cast<f32x4*>(sP + (wave * 16 + c) * 16 + 4 * kb) = pr;
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");   // written and read by this wavefront only
+            __builtin_amdgcn_wave_barrier();
+            // ---- this wavefront's part of P.V for every row of the pass
+            for (int rr = 0; rr < nr; ++rr) {
+                const f32x4* prow = reinterpret_cast<const f32x4*>(sP + (wave * 16 + rr) * 16);
+                float o[DPL];
+#pragma unroll
+                for (int e = 0; e < DPL; ++e) o[e] = 0.f;
+#pragma unroll
+                for (int k4 = 0; k4 < 4; ++k4) {
+                    const f32x4 p4 = prow[k4];
+#pragma unroll
+                    for (int r = 0; r < 4; ++r)
+#pragma unroll
+                        for (int e = 0; e < DPL; ++e) o[e] += p4[r] * v[4 * k4 + r][e];
+                }
+#pragma unroll
+                for (int e = 0; e < DPL; ++e) sO[(wave * 16 + rr) * D + DPL * lane + e] = o[e];
+            }
+            __syncthreads();
+            // ---- add the wavefronts' parts in order
+            for (int x = tid; x < nr * D; x += PS_WG_THREADS) {
+                const int rr = x / D, dd = x - rr * D;
+                float o = 0.f, l = 0.f;
+#pragma unroll
+                for (int w = 0; w < PS_WAVES; ++w) { o += sO[(w * 16 + rr) * D + dd]; l += sL[w * 16 + rr]; }
+                const int rho2 = r0 + rr;
+                const int gi2 = row_seq(P, rho2), i2 = rho2 - gi2 * P.M;
+                if (nch == 1) {
+                    // the only chunk: normalise and hand the row to the output projection
+                    sx_st1(ro, (unsigned)((size_t)(b * P.M + i2) * P.QD + (hk * grp + gi2) * D + dd), o / l);
+                } else {
+                    // partial (max, sum, unnormalised output) of this chunk, as tagged data
+                    ll_st1(racc, (unsigned)(((size_t)item * Ra + rho2) * D + dd), o, P.seq);
+                    if (dd < 2) {
+                        float mr = -INFINITY;
+#pragma unroll
+                        for (int w = 0; w < PS_WAVES; ++w) mr = fmaxf(mr, sM[w * 16 + rr]);
+                        ll_st1(rml, (unsigned)(((size_t)item * Ra + rho2) * 2 + dd), dd ? l : mr, P.seq);
+                    }
+                }
+            }
+        }
+        stamp(P, wg, 34);
         // several chunks: the workgroup of the last chunk waits for the others' partials and merges
         if (nch > 1 && ch == nch - 1) {
             const int item0 = item - ch;   // chunk 0 of this (b, hk)
@@ -1177,7 +1283,7 @@ __device__ void attn_phase(const StepParams& P, int wg, int nwg, char* smem) {
                         }
                     }
                 }
-                const int gi = rho / P.M, i = rho - gi * P.M;
+                const int gi = row_seq(P, rho), i = rho - gi * P.M;
                 sx_st1(ro, (unsigned)((size_t)(b * P.M + i) * P.QD + (hk * grp + gi) * D + dd), num / den);
             }
         }
@@ -1193,8 +1299,8 @@ __device__ void attn_phase(const StepParams& P, int wg, int nwg, char* smem) {
 #define PS_MAX_PARTS 512
 #define PS_MERGE_CAP 1024
 #define PS_MERGE_BYTES (PS_MERGE_CAP * 8 + 128)
-__device__ void lm_merge_row(const StepParams& P, int m, int lane, u64* sk) {
-    const int nparts = P.plan[PH_LMHEAD].nwg;
+__device__ __forceinline__ void lm_merge_row(const StepParams& P, int m, int lane, u64* sk) {
+    const int nparts = min(P.ph[PH_LMHEAD].nwg, P.ph[PH_LMHEAD].T);   // workgroups that had vocabulary tiles
     const int topk = P.topk;
     const unsigned stride = 2 + 2 * topk;                  // tagged elements per (workgroup, row)
     const unsigned pstride = (unsigned)P.Rtot * stride;
@@ -1225,6 +1331,7 @@ __device__ void lm_merge_row(const StepParams& P, int m, int lane, u64* sk) {
             hk[u] = ok ? (((u64)__float_as_uint(v[3]) << 32) | __float_as_uint(v[2])) : 0;
         }
     }
+    stamp(P, blockIdx.x, 41);
     float mx = -INFINITY;
 #pragma unroll
     for (int u = 0; u < HPL; ++u) mx = fmaxf(mx, hmax[u]);
@@ -1288,6 +1395,7 @@ __device__ void lm_merge_row(const StepParams& P, int m, int lane, u64* sk) {
             ns += __popcll(mask);
         }
     }
+    stamp(P, blockIdx.x, 42);
     if (ns > PS_MERGE_CAP) ns = PS_MERGE_CAP;
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");   // survivors written by this wavefront, read by it below
     u64 prev = ~0ull;
@@ -1313,15 +1421,14 @@ template <typename WT, int MT, int PH>
 __global__ void __launch_bounds__(PS_WG_THREADS, 1) gemm_kernel(const StepParams P) {
     extern __shared__ __attribute__((aligned(256))) char smem[];
     uint4 wb[PS_U];
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    preload_weights(wb, first_stream<PH>(P, blockIdx.x, wave, lane));
-    gemm_phase<WT, MT, PH>(P, blockIdx.x, smem, wb, P.wpack[PH] + lane * 16);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    gemm_phase<WT, MT, PH>(P, blockIdx.x, wave, smem, wb, P.ph[PH].wpack, first_stream(P, PH, blockIdx.x, wave));
 }
 
 template <typename WT, int D>
 __global__ void __launch_bounds__(PS_WG_THREADS) attn_kernel(const StepParams P) {
     extern __shared__ __attribute__((aligned(256))) char smem[];
-    attn_phase<WT, D>(P, blockIdx.x, gridDim.x, smem);
+    attn_phase<WT, D>(P, blockIdx.x, gridDim.x, __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), smem);
 }
 
 static __global__ void __launch_bounds__(64) lm_merge_kernel(const StepParams P) {
@@ -1336,36 +1443,39 @@ static __global__ void __launch_bounds__(256) probs_kernel(const StepParams P) {
         P.probs[(size_t)m * P.V + n] = expf(P.logits_store[(size_t)m * P.V + n] - lse);
 }
 
-// The whole step in one persistent kernel: gridDim.x workgroups, all resident (cooperative
-// launch).  No grid-wide synchronisation: the phases are chained by the tagged data itself.
-// While a workgroup waits for the activations of its next phase, the first weight loads of that
-// phase are already in flight.
+// The whole step in one persistent kernel: gridDim.x workgroups, all resident.  No grid-wide
+// synchronisation: the phases are chained by the exchanged data itself.  While a workgroup waits
+// for the activations of its next phase, the first weight loads of that phase are already in
+// flight.
 template <typename WT, int D, int MT>
 __global__ void __launch_bounds__(PS_WG_THREADS, 1) fused_kernel(const StepParams P) {
     extern __shared__ __attribute__((aligned(256))) char smem[];
-    const int wg = blockIdx.x, wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int wg = blockIdx.x, lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     uint4 wb[PS_U];
-    stamp(P, wg, 30);
-    preload_weights(wb, first_stream<PH_QKV>(P, wg, wave, lane));
-    gemm_phase<WT, MT, PH_QKV>(P, wg, smem, wb, P.wpack[PH_QKV] + lane * 16);
+    stamp_wall(P, wg, 0);
+    stamp(P, wg, 1);
+    gemm_phase<WT, MT, PH_QKV>(P, wg, wave, smem, wb, first_stream(P, PH_OPROJ, wg, wave), first_stream(P, PH_QKV, wg, wave));
     __syncthreads();
-    stamp(P, wg, 25);
-    attn_phase<WT, D>(P, wg, gridDim.x, smem);
+    stamp(P, wg, 32);
+    attn_phase<WT, D>(P, wg, gridDim.x, wave, smem);
     __syncthreads();
-    stamp(P, wg, 26);
-    preload_weights(wb, first_stream<PH_OPROJ>(P, wg, wave, lane));
-    gemm_phase<WT, MT, PH_OPROJ>(P, wg, smem, wb, first_stream<PH_GATEUP>(P, wg, wave, lane));
+    stamp(P, wg, 36);
+    gemm_phase<WT, MT, PH_OPROJ>(P, wg, wave, smem, wb, first_stream(P, PH_GATEUP, wg, wave), nullptr);
     __syncthreads();
-    gemm_phase<WT, MT, PH_GATEUP>(P, wg, smem, wb, first_stream<PH_DOWN>(P, wg, wave, lane));
+    gemm_phase<WT, MT, PH_GATEUP>(P, wg, wave, smem, wb, first_stream(P, PH_DOWN, wg, wave), nullptr);
     __syncthreads();
-    gemm_phase<WT, MT, PH_DOWN>(P, wg, smem, wb, first_stream<PH_LMHEAD>(P, wg, wave, lane));
+    gemm_phase<WT, MT, PH_DOWN>(P, wg, wave, smem, wb, first_stream(P, PH_LMHEAD, wg, wave), nullptr);
     __syncthreads();
-    gemm_phase<WT, MT, PH_LMHEAD>(P, wg, smem, wb, P.wpack[PH_LMHEAD] + lane * 16);
+    gemm_phase<WT, MT, PH_LMHEAD>(P, wg, wave, smem, wb, P.ph[PH_QKV].wpack, nullptr);
     __syncthreads();
     // output row m is merged by wavefront 0 of workgroup m mod gridDim.x
     if (wave == 0) {
         u64* sk = reinterpret_cast<u64*>(smem + 256);
+        stamp(P, wg, 40);
         for (int m = wg; m < P.Rtot; m += gridDim.x) lm_merge_row(P, m, lane, sk);
     }
-    stamp(P, wg, 31);
+    stamp(P, wg, 62);
+    stamp_wall(P, wg, 63);
+    flush_stamps(P, wg);
 }

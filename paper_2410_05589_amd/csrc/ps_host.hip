@@ -20,6 +20,7 @@ static const PsInstance* find_instance(int dtype, int d) {
 }
 
 #define PS_MAX_WG 512   // upper bound on workgroups per phase used to size the workspace
+#define PS_S_MAX 8      // most K-slices across workgroups
 
 // With PS_DRAFT_DEBUG set, a failing HIP call is named on stderr before PS_ERR_DEVICE is returned.
 static bool hip_ok(hipError_t e, const char* what) {
@@ -38,7 +39,7 @@ struct ps_draft_ctx {
     int lds_limit;                    // dynamic LDS a workgroup may use on this device
     // workspace carve-up (device pointers)
     float2* rope;
-    float *q_buf, *o_buf, *y_buf, *u_buf, *y2_buf, *kvnew, *part, *ssq_part, *attn_acc, *attn_ml, *lm_part, *logits_ws;
+    float *q_buf, *o_buf, *y_buf, *u_buf, *y2_buf, *kvnew, *attn_acc, *attn_ml, *lm_part, *logits_ws;
     unsigned seq;                     // sequence number of the last enqueued step
     size_t exch_begin, exch_end;      // workspace range of the tagged exchange buffers (cleared at init)
     char* act_base;                   // two copies of the activation buffers, act_bytes each
@@ -48,8 +49,8 @@ struct ps_draft_ctx {
     char* wpack[PH_COUNT];
     int* counters;
     int n_counters;
-    size_t frag_cap;                  // 1 KiB split-K fragments the workspace holds
-    int plan_override[PH_COUNT][2];   // S, KW from PS_DRAFT_PLAN (0 = automatic)
+    int plan_override[PH_COUNT][2];   // K-slices, wavefronts per tile from PS_DRAFT_PLAN (0 = automatic)
+    size_t off_frag[PH_COUNT], off_ssqf[PH_COUNT];
     bool profile;
     unsigned long long* timeline;
     hipEvent_t events[PS_PROFILE_EVENTS];
@@ -87,23 +88,14 @@ static size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
 struct WsLayout {
     size_t wpack[PH_COUNT];
-    size_t rope, q_buf, o_buf, y_buf, u_buf, y2_buf, kvnew, part, ssq_part, attn_acc, attn_ml, counters, lm_part, logits_ws, total;
+    size_t rope, q_buf, o_buf, y_buf, u_buf, y2_buf, kvnew, attn_acc, attn_ml, counters, lm_part, logits_ws, total;
     size_t exch_begin, exch_end;
-    size_t act_base, act_bytes, off_q, off_o, off_y, off_u, off_y2, off_kvnew;
-    size_t frag_cap;
+    size_t act_base, act_bytes, off_q, off_o, off_y, off_u, off_y2, off_kvnew, off_frag[PH_COUNT], off_ssqf[PH_COUNT];
     int n_counters;
 };
 
-static int max_tiles(const ps_draft_config* c) {
-    const int qkv = (c->n_heads + 2 * c->n_kv_heads) * (c->head_dim / 16);
-    int t = qkv;
-    if (c->hidden / 16 > t) t = c->hidden / 16;
-    if (c->ffn / 8 > t) t = c->ffn / 8;
-    return t;
-}
-
-// tiles (16 weight rows) and steps (64-byte pieces of a row) of the five GEMM phases
-static void phase_dims(const ps_draft_config* c, int* T, int* Kt) {
+// tiles (16 weight rows), contraction lengths and steps (64-byte pieces of a row) of the five GEMM phases
+static void phase_dims(const ps_draft_config* c, int* T, int* Kt, int* K = nullptr) {
     const int kstep = c->dtype == PS_BF16 ? 32 : 16;
     const int qd = c->n_heads * c->head_dim;
     T[PH_QKV] = (c->n_heads + 2 * c->n_kv_heads) * (c->head_dim / 16); Kt[PH_QKV] = c->hidden / kstep;
@@ -111,7 +103,10 @@ static void phase_dims(const ps_draft_config* c, int* T, int* Kt) {
     T[PH_GATEUP] = c->ffn / 8; Kt[PH_GATEUP] = c->hidden / kstep;
     T[PH_DOWN] = c->hidden / 16; Kt[PH_DOWN] = c->ffn / kstep;
     T[PH_LMHEAD] = (c->vocab + 15) / 16; Kt[PH_LMHEAD] = c->hidden / kstep;
+    if (K) { K[PH_QKV] = K[PH_GATEUP] = K[PH_LMHEAD] = c->hidden; K[PH_OPROJ] = qd; K[PH_DOWN] = c->ffn; }
 }
+// steps per tile in the packed matrices: whole groups of PS_U steps
+static int padded_steps(int kt) { return (kt + PS_U - 1) / PS_U * PS_U; }
 
 static WsLayout ws_layout(const ps_draft_config* c) {
     WsLayout L;
@@ -126,7 +121,7 @@ static WsLayout ws_layout(const ps_draft_config* c) {
     int T[PH_COUNT], Kt[PH_COUNT];
     phase_dims(c, T, Kt);
     // padding: the streaming loop always loads PS_U steps ahead, also at the end of the last tile
-    for (int ph = 0; ph < PH_COUNT; ++ph) L.wpack[ph] = take((size_t)T[ph] * Kt[ph] * 1024 + PS_U_MAX * 1024);
+    for (int ph = 0; ph < PH_COUNT; ++ph) L.wpack[ph] = take((size_t)T[ph] * padded_steps(Kt[ph]) * 1024 + PS_U_MAX * 1024);
     L.rope = take((size_t)c->max_positions * (c->head_dim / 2) * sizeof(float2));
     // activations between phases: fp32, two alternating copies (see PS_SENT in ps_device.h)
     {
@@ -138,19 +133,19 @@ static WsLayout ws_layout(const ps_draft_config* c) {
         L.off_u = sub(rows * c->ffn * 4);
         L.off_y2 = sub(rows * c->hidden * 4);
         L.off_kvnew = sub(rows * 2 * (size_t)c->n_kv_heads * c->head_dim * 4);
+        // parts of the tiles from up to PS_S_MAX K-slices (1 KiB per slice, tile and 16 rows)
+        const size_t mt_max = (rows + 15) / 16;
+        for (int ph = 0; ph < PH_COUNT; ++ph) {
+            const bool sliced = ph == PH_OPROJ || ph == PH_GATEUP || ph == PH_DOWN;
+            L.off_frag[ph] = sub(sliced ? (size_t)PS_S_MAX * T[ph] * mt_max * 1024 : 256);
+            L.off_ssqf[ph] = sub((size_t)PS_S_MAX * PS_MAX_ROWS * 4);
+        }
         L.act_bytes = a;
         L.act_base = take(2 * a);
     }
     L.q_buf = L.o_buf = L.y_buf = L.u_buf = L.y2_buf = L.kvnew = 0;   // set per step from the copy in use
     // tagged exchange buffers: 8 bytes per element (value + tag)
     L.exch_begin = off;
-    // split-K fragments: S * T never exceeds the wavefronts of a phase (see make_plan); one fragment
-    // is 64 lanes x 4 values per column tile
-    size_t frag = (size_t)PS_MAX_WG * PS_WAVES;
-    if ((size_t)max_tiles(c) * 2 > frag) frag = (size_t)max_tiles(c) * 2;
-    L.frag_cap = frag * 4;
-    L.part = take(L.frag_cap * 2048);
-    L.ssq_part = take(L.frag_cap * PS_MAX_ROWS * 8);
     L.attn_acc = take(max_items * ra * c->head_dim * 8);
     L.attn_ml = take(max_items * ra * 2 * 8);
     L.lm_part = take((size_t)PS_MAX_WG * rows * (2 + 2 * c->max_topk) * 8 + 64);
@@ -182,7 +177,8 @@ extern "C" const char* ps_draft_strerror(int status) {
     }
 }
 
-// PS_DRAFT_PLAN="qkv:4:1,oproj:16:1,gateup:2:1,down:16:1,lm:1:2" overrides (S, KW) per phase (tuning aid)
+// PS_DRAFT_PLAN="qkv:1:8,oproj:8:1,gateup:8:1,down:8:1,lm:1:1" overrides, per phase, the K-slices across
+// workgroups and the wavefronts that share a tile (tuning aid)
 static void parse_plan_override(ps_draft_ctx* ctx) {
     memset(ctx->plan_override, 0, sizeof(ctx->plan_override));
     const char* e = getenv("PS_DRAFT_PLAN");
@@ -191,9 +187,9 @@ static void parse_plan_override(ps_draft_ctx* ctx) {
     for (int ph = 0; ph < PH_COUNT; ++ph) {
         const char* p = strstr(e, names[ph]);
         if (!p) continue;
-        int s = 0, kw = 0;
-        if (sscanf(p + strlen(names[ph]), ":%d:%d", &s, &kw) == 2) {
-            ctx->plan_override[ph][0] = s;
+        int sl = 0, kw = 0;
+        if (sscanf(p + strlen(names[ph]), ":%d:%d", &sl, &kw) == 2) {
+            ctx->plan_override[ph][0] = sl;
             ctx->plan_override[ph][1] = kw;
         }
     }
@@ -248,16 +244,14 @@ extern "C" int ps_draft_init(ps_draft_ctx** out, const ps_draft_config* config, 
     ctx->act_base = base + L.act_base; ctx->act_bytes = L.act_bytes;
     ctx->off_q = L.off_q; ctx->off_o = L.off_o; ctx->off_y = L.off_y; ctx->off_u = L.off_u;
     ctx->off_y2 = L.off_y2; ctx->off_kvnew = L.off_kvnew;
+    for (int ph = 0; ph < PH_COUNT; ++ph) { ctx->off_frag[ph] = L.off_frag[ph]; ctx->off_ssqf[ph] = L.off_ssqf[ph]; }
     ctx->last_shape[0] = ctx->last_shape[1] = ctx->last_shape[2] = -1;
-    ctx->part = (float*)(base + L.part);
-    ctx->ssq_part = (float*)(base + L.ssq_part);
     ctx->attn_acc = (float*)(base + L.attn_acc);
     ctx->attn_ml = (float*)(base + L.attn_ml);
     ctx->seq = 0;
     ctx->exch_begin = L.exch_begin; ctx->exch_end = L.exch_end;
     ctx->counters = (int*)(base + L.counters);
     ctx->n_counters = L.n_counters;
-    ctx->frag_cap = L.frag_cap;
     ctx->lm_part = (float*)(base + L.lm_part);
     ctx->logits_ws = (float*)(base + L.logits_ws);
     parse_plan_override(ctx);
@@ -289,8 +283,12 @@ extern "C" int ps_draft_init(ps_draft_ctx** out, const ps_draft_config* config, 
         P.w_down = w->w_down; P.w_lm = w->w_lm;
         int T[PH_COUNT], Kt[PH_COUNT];
         phase_dims(config, T, Kt);
-        for (int ph = 0; ph < PH_COUNT && e == hipSuccess; ++ph)
-            e = inst->pack(P, ph, T[ph], Kt[ph], ctx->wpack[ph], s);
+        for (int ph = 0; ph < PH_COUNT && e == hipSuccess; ++ph) {
+            const int ktp = padded_steps(Kt[ph]);
+            e = inst->pack(P, ph, T[ph], ktp, Kt[ph], ctx->wpack[ph], s);
+            // the streaming loop reads up to PS_U KiB past the last tile: make that zeros, not stale memory
+            if (e == hipSuccess) e = hipMemsetAsync(ctx->wpack[ph] + (size_t)T[ph] * ktp * 1024, 0, PS_U_MAX * 1024, s);
+        }
     }
     if (e == hipSuccess) e = hipStreamSynchronize(s);
     if (!hip_ok(e, "rotary table upload")) { delete ctx; return PS_ERR_DEVICE; }
@@ -300,8 +298,8 @@ extern "C" int ps_draft_init(ps_draft_ctx** out, const ps_draft_config* config, 
 
 extern "C" void ps_draft_free(ps_draft_ctx* ctx) { delete ctx; }
 
-// Debugging aid, not declared in the public header: device buffer of 32 x 1024 uint64 receiving
-// per-workgroup wall-clock stamps of the following steps (NULL = off).
+// Debugging aid, not declared in the public header: device buffer of 64 x 1024 uint64 receiving
+// per-workgroup clock stamps of the following steps (NULL = off; builds with -DPS_TIMELINE only).
 extern "C" __attribute__((visibility("default"))) int ps_draft_debug_timeline(ps_draft_ctx* ctx, void* buf) {
     if (!ctx) return PS_ERR_NULL;
     ctx->timeline = (unsigned long long*)buf;
@@ -322,45 +320,84 @@ extern "C" int ps_draft_set_profile_events(ps_draft_ctx* ctx, void* const* event
 // ------------------------------------------------------------------------------------------
 // launch plan
 // ------------------------------------------------------------------------------------------
-static int floor_pow2(int v) { int p = 1; while (p * 2 <= v) p *= 2; return p; }
-
 int panel_row_stride_host(int panel_steps) {
     const int len = panel_steps * 64;
     return len + ((64 - (len & 255)) + 256) % 256;
 }
+static int panel_offset_host(int mt) { return 2304 + PS_WAVES * mt * 1024; }   // see PS_LDS_RED in ps_device.h
 
-// Cuts one GEMM phase: T tiles x Kt steps over nwg workgroups of 16 wavefronts.
-static bool make_plan(PhasePlan* pl, int ph, int T, int Kt, int rows, int mt, bool bf, int nwg, int cnt_base,
+// Cuts one GEMM phase: T tiles x Kt steps (K elements) over nwg workgroups of PS_WAVES wavefronts.
+//
+// S K-slices across workgroups (oproj, gateup, down only).  Every workgroup has to fetch the
+// activations of its K range from memory (exchanged data bypasses the L2), so without slices the
+// whole grid pulls nwg copies of the full activation matrix, tens of MB per phase, through the
+// fabric.  With S slices a workgroup fetches 1/S of it; workgroup wg is slice wg % S, and since
+// workgroups are dealt round-robin to the 8 XCDs, S = 8 makes all workgroups of an XCD read the
+// same eighth.  The price is one more exchange: the slices' parts of a tile meet in global memory.
+//
+// kw wavefronts of a workgroup share a tile (kw = 1, 2, 4 or 8; partial sums meet in LDS).  More
+// sharing keeps more wavefronts streaming when tiles are few, but a workgroup then takes fewer
+// tiles per round and every extra round costs a synchronisation and a reduction: the score is the
+// fraction of wavefront slots at work minus a small charge per extra round.
+static bool make_desc(PhaseDesc* d, int ph, int T, int Kt, int K, int rows, int mt, bool bf, int nwg,
                       const int* override_, int lds_limit) {
-    const int waves = nwg * PS_WAVES;
-    int split = floor_pow2(waves / T > 0 ? waves / T : 1);
-    while (split > 1 && Kt / split < 4) split /= 2;   // keep at least 4 steps per piece
-    // S (K-slices across workgroups) costs a fragment exchange with one memory round trip per four
-    // slices, but divides the activation panel every workgroup has to fetch; KW (K-split across the
-    // wavefronts of a workgroup) is free.  The LM head keeps whole logits in the workgroup (S = 1);
-    // the QKV phase reads caller data that is cached, so its panel is cheap (S = 1).
-    int S, KW;
-    if (ph == PH_LMHEAD || ph == PH_QKV) { S = 1; KW = split > PS_WAVES ? PS_WAVES : split; }
-    else { S = split > 4 ? 4 : split; KW = split / S; if (KW > PS_WAVES) KW = PS_WAVES; }
-    if (override_ && override_[0] > 0 && override_[1] > 0) { S = override_[0]; KW = override_[1]; }
-    if (ph == PH_LMHEAD) S = 1;
-    if (S > nwg) S = floor_pow2(nwg);
-    if (KW > PS_WAVES) KW = PS_WAVES;
-    if (PS_WAVES % KW) KW = floor_pow2(KW);
-    pl->T = T; pl->Kt = Kt; pl->S = S; pl->KW = KW; pl->nwg = nwg; pl->cnt_base = cnt_base;
-    const int Gs = nwg / S, SL = PS_WAVES / KW;
-    const int rounds = (T + Gs * SL - 1) / (Gs * SL);
-    const int fixed = 512 + PS_WAVES * mt * 1024 + (ph == PH_LMHEAD ? rounds * SL * rows * 64 : 0);
-    const int budget = lds_limit - fixed - 1024;
-    if (budget <= 0) return false;
-    const int slice_steps = (Kt + S - 1) / S;
-    int steps = slice_steps;
-    const int per_row_arrays = bf ? 2 : 1;
-    while (steps > 1 && (long long)rows * per_row_arrays * panel_row_stride_host(steps) > budget) steps = (steps + 1) / 2;
-    if ((long long)rows * per_row_arrays * panel_row_stride_host(steps) > budget) return false;
-    pl->panel_steps = steps;
-    pl->lds_bytes = fixed + rows * per_row_arrays * panel_row_stride_host(steps);
-    return true;
+    const int ktp = padded_steps(Kt), NG = ktp / PS_U;
+    const int arrays = bf ? 2 : 1;
+    memset(d, 0, sizeof(*d));
+    int s_log = 0;
+    // measured: slices pay for the two narrow projections (few tiles, long K); gate/up has tiles enough
+    if (ph == PH_OPROJ || ph == PH_DOWN)
+        while (s_log < 3 && (2 << s_log) <= NG && (2 << s_log) <= nwg) ++s_log;
+    if (override_[0] > 0) {
+        int want = 0;
+        while ((2 << want) <= override_[0]) ++want;
+        if (want < s_log || (ph != PH_LMHEAD && ph != PH_QKV && (1 << want) <= NG && (1 << want) <= nwg && want <= 3)) s_log = want;
+    }
+    for (; s_log >= 0; --s_log) {
+        const int S = 1 << s_log, Gs = nwg >> s_log;
+        const int min_slice = NG / S, max_slice = (NG + S - 1) / S;   // groups per slice
+        int best_log = 0;
+        double best = -1e9;
+        for (int lg = 0; lg <= PS_WAVES_LOG; ++lg) {
+            const int kw = 1 << lg;
+            if (kw > min_slice) break;
+            const int per_round = Gs * (PS_WAVES >> lg);
+            const int rounds = (T + per_round - 1) / per_round;
+            const double util = (double)T * kw * S / ((double)rounds * nwg * PS_WAVES);
+            const double score = util - 0.04 * (rounds - 1);
+            if (score > best + 1e-9) { best = score; best_log = lg; }
+        }
+        if (override_[1] > 0) {
+            best_log = 0;
+            while ((2 << best_log) <= override_[1] && best_log < PS_WAVES_LOG && (2 << best_log) <= min_slice) ++best_log;
+        }
+        for (; best_log >= 0; --best_log) {
+            const int kw = 1 << best_log, SL = PS_WAVES >> best_log;
+            const int per_round = Gs * SL;
+            const int rounds = (T + per_round - 1) / per_round;
+            const int fixed = panel_offset_host(mt) + (ph == PH_LMHEAD ? rounds * SL * rows * 64 : 0);
+            const int budget = lds_limit - fixed - 256;
+            if (budget <= 0) continue;
+            // fewest pieces whose panel fits; every piece needs at least kw groups
+            int np = 1;
+            while (np <= max_slice && (long long)rows * arrays * panel_row_stride_host((max_slice + np - 1) / np * PS_U) > budget) ++np;
+            if (np > max_slice) continue;
+            if (S > 1 && np > 1) break;   // sliced phases keep their whole slice in LDS: try fewer slices
+            const int pg = (max_slice + np - 1) / np;
+            const int npieces = (max_slice + pg - 1) / pg;
+            const int last = min_slice - (npieces - 1) * pg;   // smallest last piece over the slices
+            if (pg < kw || last < kw) continue;
+            d->T = T; d->Kt = ktp; d->K = K; d->rows = rows; d->kw_log = best_log; d->s_log = s_log; d->Gs = Gs;
+            d->nwg = nwg; d->per_round = per_round; d->rounds = rounds; d->piece_groups = pg; d->npieces = npieces;
+            d->rs = panel_row_stride_host(pg * PS_U);
+            int g2 = 6;
+            while ((1 << g2) < pg * PS_U * 4 && (1 << g2) < PS_WG_THREADS) ++g2;
+            d->g2_log = g2;
+            d->lds_bytes = fixed + rows * arrays * d->rs + 256;
+            return true;
+        }
+    }
+    return false;
 }
 
 extern "C" int ps_draft_step(ps_draft_ctx* ctx, const ps_draft_step_args* a, void* stream) {
@@ -394,15 +431,17 @@ extern "C" int ps_draft_step(ps_draft_ctx* ctx, const ps_draft_step_args* a, voi
     P.g_post = ctx->w.g_post; P.w_gate = ctx->w.w_gate; P.w_up = ctx->w.w_up; P.w_down = ctx->w.w_down;
     P.g_final = ctx->w.g_final; P.w_lm = ctx->w.w_lm; P.mask_emb = ctx->w.mask_emb;
     P.x = a->x; P.kc = a->k_cache; P.vc = a->v_cache;
-    for (int ph = 0; ph < PH_COUNT; ++ph) P.wpack[ph] = ctx->wpack[ph];
-    P.rope = ctx->rope; P.part = ctx->part; P.attn_acc = ctx->attn_acc; P.attn_ml = ctx->attn_ml;
-    P.lm_part = ctx->lm_part; P.ssq_part = ctx->ssq_part;
+    P.rope = ctx->rope; P.attn_acc = ctx->attn_acc; P.attn_ml = ctx->attn_ml;
+    P.lm_part = ctx->lm_part;
+    P.m_magic = 0xFFFFFFFFu / (unsigned)M + 1u;   // ceil(2^32 / M); M = 1 is handled on the device
+    P.tph_log = c.head_dim == 128 ? 3 : 2;
     P.error_flag = ctx->counters;
-    ctx->seq = ctx->seq >= 0x1FFFFFF0u ? 1u : ctx->seq + 1u;   // seq * 8 + phase must fit in 32 bits; 0 = cleared
+    ctx->seq = ctx->seq >= 0xFFFFFFF0u ? 1u : ctx->seq + 1u;   // 0 = cleared buffers
     P.seq = ctx->seq;
+    char* act_cur;
     {   // the activation copy of this step; the other one is reset while this one is written
         const int par = (int)(P.seq & 1u);
-        char* cur = ctx->act_base + (size_t)par * ctx->act_bytes;
+        char* cur = act_cur = ctx->act_base + (size_t)par * ctx->act_bytes;
         P.q_buf = (float*)(cur + ctx->off_q); P.o_buf = (float*)(cur + ctx->off_o); P.y_buf = (float*)(cur + ctx->off_y);
         P.u_buf = (float*)(cur + ctx->off_u); P.y2_buf = (float*)(cur + ctx->off_y2); P.kvnew = (float*)(cur + ctx->off_kvnew);
         P.alt_delta = par ? -(long long)ctx->act_bytes : (long long)ctx->act_bytes;
@@ -428,26 +467,36 @@ extern "C" int ps_draft_step(ps_draft_ctx* ctx, const ps_draft_step_args* a, voi
 
     const bool bf = c.dtype == PS_BF16;
     const int nwg = ctx->n_cu;
-    const int mtiles = max_tiles(&c);
-    int T[PH_COUNT], Kt[PH_COUNT];
-    phase_dims(&c, T, Kt);
+    P.r_magic = 0xFFFFFFFFu / (unsigned)P.R + 1u;
+    int T[PH_COUNT], Kt[PH_COUNT], K[PH_COUNT];
+    phase_dims(&c, T, Kt, K);
     for (int ph = 0; ph < PH_COUNT; ++ph) {
         const int rows = ph == PH_LMHEAD ? P.Rtot : P.Mtot;
         // the persistent kernel runs every phase with the column tiles of the widest one
         const int mt = (ctx->fused ? P.Mtot + 15 : rows + 15) / 16;
-        if (!make_plan(&P.plan[ph], ph, T[ph], Kt[ph], rows, mt, bf, nwg, 0, ctx->plan_override[ph], ctx->lds_limit))
+        if (!make_desc(&P.ph[ph], ph, T[ph], Kt[ph], K[ph], rows, mt, bf, nwg, ctx->plan_override[ph], ctx->lds_limit))
             return PS_ERR_UNSUPPORTED;
-        if (P.plan[ph].S > 1 && (size_t)P.plan[ph].S * T[ph] * ((rows + 15) / 16) > ctx->frag_cap) return PS_ERR_UNSUPPORTED;
+        P.ph[ph].wpack = ctx->wpack[ph];
+        P.ph[ph].frag = (float*)(act_cur + ctx->off_frag[ph]);
+        P.ph[ph].ssq_frag = (float*)(act_cur + ctx->off_ssqf[ph]);
     }
+    P.ph[PH_QKV].norm = 1; P.ph[PH_QKV].gain = P.g_in; P.ph[PH_QKV].src = nullptr; P.ph[PH_QKV].src_ld = P.H;
+    P.ph[PH_OPROJ].src = P.o_buf; P.ph[PH_OPROJ].src_ld = P.QD;
+    P.ph[PH_GATEUP].norm = 1; P.ph[PH_GATEUP].gain = P.g_post; P.ph[PH_GATEUP].src = P.y_buf; P.ph[PH_GATEUP].src_ld = P.H;
+    P.ph[PH_DOWN].src = P.u_buf; P.ph[PH_DOWN].src_ld = P.F;
+    P.ph[PH_LMHEAD].norm = P.final_norm; P.ph[PH_LMHEAD].gain = P.g_final; P.ph[PH_LMHEAD].src = P.y2_buf; P.ph[PH_LMHEAD].src_ld = P.H;
     P.timeline = ctx->timeline;
 
     // the persistent kernel needs the largest LDS footprint of its phases and one workgroup per CU
     int lds = ctx->inst->attn_lds;
     for (int ph = 0; ph < PH_COUNT; ++ph) {
-        if (P.plan[ph].lds_bytes > lds) lds = P.plan[ph].lds_bytes;
+        if (P.ph[ph].lds_bytes > lds) lds = P.ph[ph].lds_bytes;
     }
     if (lds < 256 + 8192 + 128) lds = 256 + 8192 + 128;   // end-of-step merge scratch
     if (lds < 84 * 1024 && ctx->lds_limit >= 84 * 1024) lds = 84 * 1024;   // more than half a CU's LDS: one workgroup per CU
+#ifdef PS_TIMELINE
+    lds = ctx->lds_limit;   // the stamps live in the top 512 bytes of LDS
+#endif
     P.fused_nwg = nwg; P.fused_lds = lds;
     hipStream_t st = (hipStream_t)stream;
     hipEvent_t* ev = ctx->profile ? ctx->events : nullptr;

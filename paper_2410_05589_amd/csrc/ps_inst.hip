@@ -39,13 +39,12 @@ static kernel_fn fused_fn(int mt) {
 
 static hipError_t prepare(int lds_limit) {
     hipError_t e;
-    for (int ph = 0; ph < PH_COUNT; ++ph)
-        for (int mt = 1; mt <= 4; ++mt) {
+    for (int mt = 1; mt <= 4; ++mt) {
+        for (int ph = 0; ph < PH_COUNT; ++ph) {
             e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_fn_ph(ph, mt)),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, lds_limit);
             if (e != hipSuccess) return e;
         }
-    for (int mt = 1; mt <= 4; ++mt) {
         e = hipFuncSetAttribute(reinterpret_cast<const void*>(fused_fn(mt)),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, lds_limit);
         if (e != hipSuccess) return e;
@@ -62,7 +61,7 @@ static hipError_t launch_multi(const StepParams& P, hipStream_t stream, hipEvent
     int n_ev = 0;
     auto mark = [&]() -> hipError_t { return events ? hipEventRecord(events[n_ev++], stream) : hipSuccess; };
     auto gemm = [&](int ph, int mt) -> hipError_t {
-        const PhasePlan& pl = P.plan[ph];
+        const PhaseDesc& pl = P.ph[ph];
         hipLaunchKernelGGL(gemm_fn_ph(ph, mt), dim3(pl.nwg), dim3(PS_WG_THREADS), pl.lds_bytes, stream, P);
         hipError_t le = hipGetLastError();
         return le != hipSuccess ? le : mark();
@@ -85,7 +84,7 @@ static hipError_t launch_multi(const StepParams& P, hipStream_t stream, hipEvent
 
 // The whole step as one launch of the persistent kernel.  Its workgroups wait for each other's
 // data, so all of them must get a compute unit: the grid is one workgroup per CU and a workgroup
-// (1024 threads x up to 128 VGPRs, most of the LDS) fills a CU by itself, so they all become
+// (512 threads x up to 256 VGPRs, more than half of the LDS) fills a CU by itself, so they all become
 // resident as soon as CUs are free; kernels that still occupy CUs end on their own.  Every wait
 // in the kernel is bounded, so even a machine that withholds CUs cannot hang it.  (A cooperative
 // launch would assert the same residency but costs ~17 us per launch on this runtime.)
@@ -101,8 +100,8 @@ static hipError_t launch_probs(const StepParams& P, hipStream_t stream) {
     return hipGetLastError();
 }
 
-typedef void (*pack_fn)(const StepParams, int, int, char*);
-static hipError_t pack(const StepParams& P, int ph, int T, int Kt, char* dst, hipStream_t stream) {
+typedef void (*pack_fn)(const StepParams, int, int, int, char*);
+static hipError_t pack(const StepParams& P, int ph, int T, int Kt, int Kreal, char* dst, hipStream_t stream) {
     pack_fn f;
     switch (ph) {
         case PH_QKV: f = pack_kernel<WT_, PH_QKV>; break;
@@ -113,7 +112,7 @@ static hipError_t pack(const StepParams& P, int ph, int T, int Kt, char* dst, hi
     }
     const size_t units = (size_t)T * Kt;
     const int grid = (int)((units + 3) / 4 < 65536 ? (units + 3) / 4 : 65536);
-    hipLaunchKernelGGL(f, dim3(grid), dim3(256), 0, stream, P, T, Kt, dst);
+    hipLaunchKernelGGL(f, dim3(grid), dim3(256), 0, stream, P, T, Kt, Kreal, dst);
     return hipGetLastError();
 }
 

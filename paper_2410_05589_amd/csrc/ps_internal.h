@@ -9,31 +9,51 @@
 
 #define PS_MAX_ROWS 64     // activation rows per step (MFMA column tiles: up to 4 x 16)
 // One workgroup per compute unit.  512 threads = 8 wavefronts of 64 lanes, two per SIMD: each lane
-// may use 256 VGPRs, which pays for 16 weight loads in flight per lane and large staging batches
+// may use 256 VGPRs, which pays for the weight loads in flight per lane and large staging batches
 // without spills (1024 threads would cap lanes at 128 VGPRs).
 #ifndef PS_WG_THREADS
 #define PS_WG_THREADS 512
 #endif
 #define PS_WAVES (PS_WG_THREADS / 64)
+#define PS_WAVES_LOG 3
 #ifndef PS_U
-#define PS_U 16            // 16-byte weight loads in flight per lane (PS_U KiB per wavefront)
+#define PS_U 8             // 16-byte weight loads in flight per lane (PS_U KiB per wavefront)
 #endif
 #define PS_U_MAX 32        // packed weight buffers are padded by this many KiB (streaming reads ahead)
 #define PS_LDS_BYTES (160 * 1024)
+static_assert((1 << PS_WAVES_LOG) == PS_WAVES, "PS_WAVES_LOG");
+static_assert((PS_U & (PS_U - 1)) == 0 && PS_U <= PS_U_MAX, "PS_U");
 
 enum { PH_QKV = 0, PH_OPROJ = 1, PH_GATEUP = 2, PH_DOWN = 3, PH_LMHEAD = 4, PH_COUNT = 5 };
 
-// How one weight-streaming GEMM phase is cut up.  A "tile" is 16 weight rows; a "step" is
-// the 64-byte piece of a weight row one MFMA group consumes (32 bf16 or 16 f32 elements).
-struct PhasePlan {
-    int T;           // tiles
-    int Kt;          // steps along the contraction dimension
-    int S;           // K-slices across workgroups (partials meet in global memory)
-    int KW;          // K-split across the wavefronts of one workgroup (partials meet in LDS)
-    int panel_steps; // steps of the activation panel held in LDS at a time
-    int nwg;         // workgroups launched for the phase
-    int cnt_base;    // first completion counter of the phase
-    int lds_bytes;   // dynamic LDS the phase needs
+// How one weight-streaming GEMM phase is cut up.  A "tile" is 16 weight rows; a "step" is the
+// 64-byte piece of a weight row one MFMA group consumes (32 bf16 or 16 f32 elements); a "group"
+// is PS_U consecutive steps, the unit in which wavefronts share the contraction dimension.
+// Everything a workgroup needs to find its work is precomputed here on the host, so the device
+// code walks through a phase with a few scalar multiplications and no division.
+struct PhaseDesc {
+    int T;             // tiles
+    int Kt;            // steps per tile in the packed matrix: a multiple of PS_U (zero weights beyond K)
+    int K;             // contraction length in elements
+    int rows;          // activation rows
+    int norm;          // RMSNorm folded into the phase
+    int kw_log;        // log2 of the wavefronts that share one tile (their partial sums meet in LDS)
+    int s_log;         // log2 of the K-slices across workgroups (their partial sums meet in global memory)
+    int Gs;            // workgroup columns: nwg >> s_log; workgroup wg is slice wg % S of column wg / S
+    int nwg;           // workgroups of the grid
+    int per_round;     // tiles the grid takes per round: Gs * (PS_WAVES >> kw_log)
+    int rounds;
+    int piece_groups;  // groups of the activation panel held in LDS at a time
+    int npieces;
+    int rs;            // bytes between panel rows in LDS
+    int g2_log;        // staging: log2 of the threads laid along the contraction dimension
+    int src_ld;        // elements between rows of src
+    int lds_bytes;     // dynamic LDS the phase needs
+    const void* gain;  // RMSNorm gain (config dtype)
+    const float* src;  // exchanged fp32 activations the phase reads (QKV reads x / mask_emb instead)
+    const char* wpack; // the phase's matrices, prepacked at init in streaming order
+    float* frag;       // [S][T][MT][64 lanes][4]: the K-slices' parts of every tile (coded like the activations)
+    float* ssq_frag;   // [S][PS_MAX_ROWS]: the K-slices' sums of squares of the activation rows
 };
 
 struct StepParams {
@@ -47,7 +67,6 @@ struct StepParams {
     const void *g_in, *wq, *wk, *wv, *wo, *g_post, *w_gate, *w_up, *w_down, *g_final, *w_lm, *mask_emb;
     const void* x;
     void *kc, *vc;
-    const char* wpack[PH_COUNT]; // matrices of each phase, prepacked at init in streaming order
     // workspace
     const float2* rope; // [max_positions][d/2] (cos, sin)
     // Activations between phases: plain fp32, 0xFFFFFFFF = not written yet; the copy for this step
@@ -56,8 +75,6 @@ struct StepParams {
     float* kvnew;      // [Mtot][2][KVD] this step's K and V rows as stored in the cache
     long long alt_delta;
     // Buffers below hold 8-byte units {value, tag}: element counts.
-    float* part;       // split-K fragments: [S][T][MT][64 lanes][4]
-    float* ssq_part;   // per fragment: the K-slice's sums of squares of the activation rows (RMSNorm)
     float* attn_acc;   // [items][g*M][d] unnormalised partial outputs
     float* attn_ml;    // [items][g*M][2] (running max, sum of exponentials)
     int* error_flag;   // set if a wait for exchanged data timed out
@@ -71,7 +88,9 @@ struct StepParams {
     int fused_nwg, fused_lds;
     long long kv_off[PS_MAX_ROWS];
     int kv_len[PS_MAX_ROWS];
-    PhasePlan plan[PH_COUNT];
+    unsigned m_magic, r_magic;   // ceil(2^32 / M), ceil(2^32 / R): row -> sequence without a division
+    int tph_log;                 // log2(head_dim / 16): QKV tile -> head
+    PhaseDesc ph[PH_COUNT];
     unsigned long long* timeline; // debugging aid: per-workgroup time stamps, or NULL
 };
 
@@ -82,8 +101,9 @@ struct PsInstance {
     hipError_t (*launch_multi)(const StepParams& P, hipStream_t stream, hipEvent_t* events);
     hipError_t (*launch_fused)(const StepParams& P, hipStream_t stream);
     hipError_t (*launch_probs)(const StepParams& P, hipStream_t stream);
-    // copies one phase's weight matrix (T tiles x Kt steps) into streaming order at dst (T*Kt KiB)
-    hipError_t (*pack)(const StepParams& P, int ph, int T, int Kt, char* dst, hipStream_t stream);
+    // copies one phase's weight matrix (T tiles x Kt steps, of which the first Kreal hold weights
+    // and the rest zeros) into streaming order at dst (T*Kt KiB)
+    hipError_t (*pack)(const StepParams& P, int ph, int T, int Kt, int Kreal, char* dst, hipStream_t stream);
 };
 const PsInstance* ps_instance_f32_d64();
 const PsInstance* ps_instance_f32_d128();
