@@ -254,14 +254,17 @@ __device__ __forceinline__ float wave_max(float v) {
 #undef PS_C
     return __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(v), 63));
 }
-__device__ __forceinline__ u64 wave_max_u64(u64 v) {
-#define PS_C(CTRL, RM) { const unsigned lo = dpp_u32<CTRL, RM>((unsigned)v, (unsigned)v);                 \
-                         const unsigned hi = dpp_u32<CTRL, RM>((unsigned)(v >> 32), (unsigned)(v >> 32)); \
-                         const u64 o = ((u64)hi << 32) | lo; v = o > v ? o : v; }
+__device__ __forceinline__ unsigned wave_max_u32(unsigned v) {
+#define PS_C(CTRL, RM) { const unsigned o = dpp_u32<CTRL, RM>(v, v); v = o > v ? o : v; }
     PS_DPP_STEPS(PS_C)
 #undef PS_C
-    const unsigned lo = __builtin_amdgcn_readlane((unsigned)v, 63);
-    const unsigned hi = __builtin_amdgcn_readlane((unsigned)(v >> 32), 63);
+    return __builtin_amdgcn_readlane(v, 63);
+}
+// maximum of 64-bit keys as two 32-bit reductions: the high words first, then the low words of
+// the lanes that hold the winning high word
+__device__ __forceinline__ u64 wave_max_u64(u64 v) {
+    const unsigned hi = wave_max_u32((unsigned)(v >> 32));
+    const unsigned lo = wave_max_u32((unsigned)(v >> 32) == hi ? (unsigned)v : 0u);
     return ((u64)hi << 32) | lo;
 }
 
@@ -450,11 +453,15 @@ __device__ __forceinline__ void slice_groups(const PhaseDesc& D, int s, int& lo,
     lo = (s * NG) >> D.s_log;
     hi = ((s + 1) * NG) >> D.s_log;
 }
+// The tile that slot `slot` of workgroup column j takes in round rd
+__device__ __forceinline__ int tile_index(const PhaseDesc& D, int rd, int slot, int j) {
+    return rd * D.per_round + slot * D.Gs + j;
+}
 // Head of the stream a wavefront reads first in phase ph (any readable address if it has none)
 __device__ __forceinline__ const char* first_stream(const StepParams& P, int ph, int wg, int wave) {
     const PhaseDesc& D = P.ph[ph];
     const int s = wg & ((1 << D.s_log) - 1), j = wg >> D.s_log;
-    const int tau = (wave >> D.kw_log) * D.Gs + j;
+    const int tau = tile_index(D, 0, wave >> D.kw_log, j);
     if (tau >= D.T) return D.wpack;
     int lo, hi, a0, n;
     slice_groups(D, s, lo, hi);
@@ -738,7 +745,8 @@ __device__ __forceinline__ void gemm_phase(const StepParams& P, int wg, int wave
     const int rows = D.rows;
     const int kw_log = D.kw_log, KW = 1 << kw_log, SL = PS_WAVES >> kw_log, sl_log = PS_WAVES_LOG - kw_log;
     const int slot = wave >> kw_log, kw = wave & (KW - 1);
-    const int S = sliceable ? 1 << D.s_log : 1, s = wg & (S - 1), j = sliceable ? wg >> D.s_log : wg;   // K-slice and column of this workgroup
+    const int S = sliceable ? 1 << D.s_log : 1, s = wg & (S - 1);   // K-slice and column of this workgroup
+    const int j = S > 1 ? wg >> D.s_log : wg;
     const int RS = D.rs;
 
     char* s_zero = smem + PS_LDS_ZERO;
@@ -775,7 +783,7 @@ __device__ __forceinline__ void gemm_phase(const StepParams& P, int wg, int wave
 
     bool streamed = false;
     for (int rd = 0; rd < D.rounds; ++rd) {
-        const int tau = rd * D.per_round + slot * D.Gs + j;
+        const int tau = tile_index(D, rd, slot, j);
         const bool valid = tau < D.T;
         f32x4 acc[MT];
 #pragma unroll
@@ -797,8 +805,8 @@ __device__ __forceinline__ void gemm_phase(const StepParams& P, int wg, int wave
                 if (pc + 1 < D.npieces) {
                     const int g2 = g_lo + D.piece_groups;
                     next_wp = stream_ptr(D, tau, g2, min(D.piece_groups, sg_hi - g2), kw, na, nn);
-                } else if (rd + 1 < D.rounds && tau + D.per_round < D.T) {
-                    next_wp = stream_ptr(D, tau + D.per_round, sg_lo, min(D.piece_groups, sg_hi - sg_lo), kw, na, nn);
+                } else if (rd + 1 < D.rounds && tile_index(D, rd + 1, slot, j) < D.T) {
+                    next_wp = stream_ptr(D, tile_index(D, rd + 1, slot, j), sg_lo, min(D.piece_groups, sg_hi - sg_lo), kw, na, nn);
                 }
                 const char* pa_t[MT];
 #pragma unroll
@@ -868,7 +876,7 @@ __device__ __forceinline__ void gemm_phase(const StepParams& P, int wg, int wave
         const rsrc_t rf = make_rsrc(D.frag), rq = make_rsrc(D.ssq_frag);
         const int ntl = D.rounds * SL;
         for (int lt = s + S * wave; lt < ntl; lt += S * PS_WAVES) {
-            const int tau = (lt >> sl_log) * D.per_round + (lt & (SL - 1)) * D.Gs + j;
+            const int tau = tile_index(D, lt >> sl_log, lt & (SL - 1), j);
             if (tau >= D.T) continue;
             f32x4 acc[MT];
 #pragma unroll
@@ -927,7 +935,7 @@ __device__ __forceinline__ void gemm_phase(const StepParams& P, int wg, int wave
                 if (x < n_el) {
                     const int lt = x >> 4;
                     const float v = s_lm[(lt * rows + m) * 16 + (x & 15)];
-                    const int id = 16 * ((lt >> sl_log) * D.per_round + (lt & (SL - 1)) * D.Gs + j) + (x & 15);
+                    const int id = 16 * tile_index(D, lt >> sl_log, lt & (SL - 1), j) + (x & 15);
                     if (v > -INFINITY) { keys[i] = make_key(v, id); mx = fmaxf(mx, v); }
                 }
             }
@@ -937,7 +945,7 @@ __device__ __forceinline__ void gemm_phase(const StepParams& P, int wg, int wave
             if (mx > -INFINITY)
                 for (int x = lane; x < n_el; x += 64) se += expf(s_lm[((x >> 4) * rows + m) * 16 + (x & 15)] - mx);
             se = wave_sum(se);
-            const unsigned obase = (unsigned)((wg * rows + m) * stride);
+            const unsigned obase = (unsigned)((j * rows + m) * stride);
             if (lane < 2) ll_st1(rl, obase + lane, lane ? se : mx, P.seq);
             u64 prev = ~0ull;   // keys are unique: the next winner is the largest key below the previous one
             for (int t = 0; t < topk; ++t) {
@@ -948,7 +956,7 @@ __device__ __forceinline__ void gemm_phase(const StepParams& P, int wg, int wave
                 for (int x = lane + 64 * EPL; x < n_el; x += 64) {
                     const int lt = x >> 4;
                     const float v = s_lm[(lt * rows + m) * 16 + (x & 15)];
-                    const int id = 16 * ((lt >> sl_log) * D.per_round + (lt & (SL - 1)) * D.Gs + j) + (x & 15);
+                    const int id = 16 * tile_index(D, lt >> sl_log, lt & (SL - 1), j) + (x & 15);
                     const u64 kx = v > -INFINITY ? make_key(v, id) : 0;
                     if (kx < prev && kx > best) best = kx;
                 }
@@ -1291,127 +1299,112 @@ __device__ __forceinline__ void attn_phase(const StepParams& P, int wg, int nwg,
 }
 
 // ------------------------------------------------------------------------------------------
-// LM-head merge of one output row by one wavefront.  Every workgroup's list is sorted, so the
-// topk-th largest of the list HEADS is a lower bound of the global topk-th key: candidates below
-// it are dropped in one pass (at most topk^2 survive) and only those go through the selection.
-// sk: LDS scratch of PS_MERGE_BYTES, private to the calling wavefront.
+// LM-head merge of one output row by one workgroup.  Thread p fetches workgroup p's statistics
+// of the row (max, sum of exponentials, its sorted top-k keys) in one round of loads; every
+// wavefront merges the lists of its 64 threads into a sorted top-k, wavefront 0 merges those.
+// Keys are unique, so "the largest key below the previous winner" enumerates them in order.
+// sk: LDS scratch of PS_MERGE_BYTES.
 // ------------------------------------------------------------------------------------------
-#define PS_MAX_PARTS 512
-#define PS_MERGE_CAP 1024
-#define PS_MERGE_BYTES (PS_MERGE_CAP * 8 + 128)
-__device__ __forceinline__ void lm_merge_row(const StepParams& P, int m, int lane, u64* sk) {
+#define PS_MAX_TOPK 32
+#define PS_MERGE_BYTES (PS_WAVES * PS_MAX_TOPK * 8 + PS_WAVES * 8)
+__device__ __forceinline__ void lm_merge_row(const StepParams& P, int m, int wave, char* scratch) {
+    const int tid = threadIdx.x, lane = tid & 63;
     const int nparts = min(P.ph[PH_LMHEAD].nwg, P.ph[PH_LMHEAD].T);   // workgroups that had vocabulary tiles
     const int topk = P.topk;
     const unsigned stride = 2 + 2 * topk;                  // tagged elements per (workgroup, row)
     const unsigned pstride = (unsigned)P.Rtot * stride;
     const rsrc_t rl = make_rsrc(P.lm_part);
-    const unsigned base = (unsigned)m * stride;
-    constexpr int HPL = PS_MAX_PARTS / 64;   // lists per lane
-    float hmax[HPL], hsum[HPL];
-    u64 hk[HPL];
-    {
-        LL4 hd[HPL];
-        int spins = 0;
-        for (;;) {   // every workgroup's statistics of this row, once they have arrived
-            bool ok = true;
+    u64* sk = reinterpret_cast<u64*>(scratch);                              // [waves][PS_MAX_TOPK] keys
+    float* sf = reinterpret_cast<float*>(scratch + PS_WAVES * PS_MAX_TOPK * 8);   // [waves] max, [waves] sum
+    const bool mine = tid < nparts;                        // host: nparts <= PS_WG_THREADS
+    const unsigned base = ((unsigned)m * stride + (mine ? tid : 0) * pstride) * 8;   // bytes
+    constexpr int KB = 8;                                  // keys requested per round trip
+    u64 keys[PS_MAX_TOPK];
+    float pmax = -INFINITY, psum = 0.f;
 #pragma unroll
-            for (int u = 0; u < HPL; ++u) {
-                const int gp = lane + 64 * u;
-                hd[u] = ll_ld4(rl, base + (gp < nparts ? gp : 0) * pstride);   // max, sum exp, first key
-                ok = ok && ll_ok(hd[u], P.seq);
-            }
-            if (__all(ok) || !spin_again(P, spins)) break;
+    for (int t0 = 0; t0 < PS_MAX_TOPK; t0 += KB) {
+        if (t0 >= topk) {
+#pragma unroll
+            for (int i = 0; i < KB; ++i) keys[t0 + i] = 0;
+            continue;
         }
-#pragma unroll
-        for (int u = 0; u < HPL; ++u) {
-            const bool ok = lane + 64 * u < nparts;
-            const f32x4 v = ll_val(hd[u]);
-            hmax[u] = ok ? v[0] : -INFINITY;
-            hsum[u] = ok ? v[1] : 0.f;
-            hk[u] = ok ? (((u64)__float_as_uint(v[3]) << 32) | __float_as_uint(v[2])) : 0;
-        }
-    }
-    stamp(P, blockIdx.x, 41);
-    float mx = -INFINITY;
-#pragma unroll
-    for (int u = 0; u < HPL; ++u) mx = fmaxf(mx, hmax[u]);
-    mx = wave_max(mx);
-    float se = 0.f;
-#pragma unroll
-    for (int u = 0; u < HPL; ++u)
-        if (hmax[u] > -INFINITY) se += hsum[u] * expf(hmax[u] - mx);
-    se = wave_sum(se);
-    const float lse = mx + logf(se);
-    if (lane == 0) P.lse[m] = lse;
-    // threshold: the topk-th largest head
-    u64 thr = ~0ull;
-    for (int t = 0; t < topk; ++t) {
-        u64 best = 0;
-#pragma unroll
-        for (int u = 0; u < HPL; ++u)
-            if (hk[u] < thr && hk[u] > best) best = hk[u];
-        thr = wave_max_u64(best);
-        if (thr == 0) break;   // fewer than topk non-empty lists: keep everything
-    }
-    // only lists whose head reaches the threshold can contribute: at most topk of them.  Their
-    // indices are compacted into LDS, then every (list, entry) pair is fetched in one round.
-    int* sl = reinterpret_cast<int*>(sk + PS_MERGE_CAP);   // [32] qualifying list indices (behind the keys)
-    int nl = 0;
-#pragma unroll
-    for (int u = 0; u < HPL; ++u) {
-        const bool q = hk[u] != 0 && hk[u] >= thr;
-        const u64 mask = __ballot(q);
-        const int pos = nl + __popcll(mask & ((1ull << lane) - 1ull));
-        if (q && pos < 32) sl[pos] = lane + 64 * u;
-        nl += __popcll(mask);
-    }
-    if (nl > 32) nl = 32;
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-    int ns = 0;
-    const int npair = nl * topk;
-    for (int x0 = 0; x0 < npair; x0 += 64 * 4) {
-        u32x4 raw[4];
+        u32x4 hd, kr[KB];
         int spins = 0;
         for (;;) {
             bool ok = true;
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                int x = x0 + 64 * i + lane;
-                if (x >= npair) x = npair - 1;
-                const int li = x / topk, tt = x - li * topk;
-                raw[i] = coh_ld16(rl, (base + sl[li] * pstride + 2 + 2 * tt) * 8);   // {low, seq, high, seq}
-                ok = ok && raw[i][1] == P.seq && raw[i][3] == P.seq;
+            if (t0 == 0) {
+                hd = coh_ld16(rl, base);                   // {max, tag, sum, tag}
+                ok = hd[1] == P.seq && hd[3] == P.seq;
             }
-            if (__all(ok) || !spin_again(P, spins)) break;
-        }
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int x = x0 + 64 * i + lane;
-            const u64 kx = ((u64)raw[i][2] << 32) | raw[i][0];
-            const bool keep = x < npair && kx != 0 && kx >= thr;
-            const u64 mask = __ballot(keep);
-            const int pos = ns + __popcll(mask & ((1ull << lane) - 1ull));
-            if (keep && pos < PS_MERGE_CAP) sk[pos] = kx;
-            ns += __popcll(mask);
+            for (int i = 0; i < KB; ++i) {
+                const int t = t0 + i < topk ? t0 + i : topk - 1;
+                kr[i] = coh_ld16(rl, base + (2 + 2 * t) * 8);   // {low, tag, high, tag}
+                ok = ok && kr[i][1] == P.seq && kr[i][3] == P.seq;
+            }
+            if (__all(ok || !mine) || !spin_again(P, spins)) break;
         }
+        if (t0 == 0 && mine) { pmax = __uint_as_float(hd[0]); psum = __uint_as_float(hd[2]); }
+#pragma unroll
+        for (int i = 0; i < KB; ++i)
+            keys[t0 + i] = (mine && t0 + i < topk) ? (((u64)kr[i][2] << 32) | kr[i][0]) : 0;
     }
-    stamp(P, blockIdx.x, 42);
-    if (ns > PS_MERGE_CAP) ns = PS_MERGE_CAP;
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");   // survivors written by this wavefront, read by it below
+    if (m == (int)blockIdx.x) stamp(P, blockIdx.x, 41);
+    // this wavefront's share of the log-sum-exp and its sorted top-k
+    const float wmax = wave_max(pmax);
+    if (lane == 0) sf[wave] = wmax;
     u64 prev = ~0ull;
     for (int t = 0; t < topk; ++t) {
         u64 best = 0;
-        for (int x = lane; x < ns; x += 64) {
-            const u64 kx = sk[x];
-            if (kx < prev && kx > best) best = kx;
+#pragma unroll
+        for (int i0 = 0; i0 < PS_MAX_TOPK; i0 += KB) {
+            if (i0 < topk) {   // entries beyond topk are "none"
+#pragma unroll
+                for (int i = i0; i < i0 + KB; ++i)
+                    if (keys[i] < prev && keys[i] > best) best = keys[i];
+            }
         }
         best = wave_max_u64(best);
-        if (lane == 0) {
-            P.top_ids[(size_t)m * topk + t] = best ? key_id(best) : 0x7FFFFFFF;
-            P.top_p[(size_t)m * topk + t] = best ? expf(key_value(best) - lse) : 0.f;
-        }
-        prev = best;
+        if (lane == 0) sk[wave * PS_MAX_TOPK + t] = best;
+        prev = best;                                       // 0: exhausted, every later entry is "none"
     }
+    __syncthreads();
+    float mx = -INFINITY;
+#pragma unroll
+    for (int w = 0; w < PS_WAVES; ++w) mx = fmaxf(mx, sf[w]);
+    const float wsum = wave_sum(pmax > -INFINITY ? psum * expf(pmax - mx) : 0.f);
+    if (lane == 0) sf[PS_WAVES + wave] = wsum;
+    __syncthreads();
+    if (m == (int)blockIdx.x) stamp(P, blockIdx.x, 42);
+    if (wave == 0) {
+        float se = 0.f;
+#pragma unroll
+        for (int w = 0; w < PS_WAVES; ++w) se += sf[PS_WAVES + w];
+        const float lse = mx + logf(se);
+        if (lane == 0) P.lse[m] = lse;
+        // PS_WAVES sorted lists of topk keys: 4 candidates per lane
+        constexpr int CPL = PS_WAVES * PS_MAX_TOPK / 64;
+        u64 cand[CPL];
+#pragma unroll
+        for (int i = 0; i < CPL; ++i) {
+            const int x = lane + 64 * i, w = x / PS_MAX_TOPK, t = x - w * PS_MAX_TOPK;
+            cand[i] = t < topk ? sk[x] : 0;
+        }
+        u64 prev2 = ~0ull;
+        for (int t = 0; t < topk; ++t) {
+            u64 best = 0;
+#pragma unroll
+            for (int i = 0; i < CPL; ++i)
+                if (cand[i] < prev2 && cand[i] > best) best = cand[i];
+            best = wave_max_u64(best);
+            if (lane == 0) {
+                P.top_ids[(size_t)m * topk + t] = best ? key_id(best) : 0x7FFFFFFF;
+                P.top_p[(size_t)m * topk + t] = best ? expf(key_value(best) - lse) : 0.f;
+            }
+            prev2 = best;
+        }
+    }
+    __syncthreads();   // the scratch is reused by the next row
 }
 
 // ------------------------------------------------------------------------------------------
@@ -1431,9 +1424,9 @@ __global__ void __launch_bounds__(PS_WG_THREADS) attn_kernel(const StepParams P)
     attn_phase<WT, D>(P, blockIdx.x, gridDim.x, __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), smem);
 }
 
-static __global__ void __launch_bounds__(64) lm_merge_kernel(const StepParams P) {
+static __global__ void __launch_bounds__(PS_WG_THREADS) lm_merge_kernel(const StepParams P) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
-    lm_merge_row(P, blockIdx.x, threadIdx.x, reinterpret_cast<u64*>(smem));
+    lm_merge_row(P, blockIdx.x, __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), smem);
 }
 
 static __global__ void __launch_bounds__(256) probs_kernel(const StepParams P) {
@@ -1469,12 +1462,9 @@ __global__ void __launch_bounds__(PS_WG_THREADS, 1) fused_kernel(const StepParam
     __syncthreads();
     gemm_phase<WT, MT, PH_LMHEAD>(P, wg, wave, smem, wb, P.ph[PH_QKV].wpack, nullptr);
     __syncthreads();
-    // output row m is merged by wavefront 0 of workgroup m mod gridDim.x
-    if (wave == 0) {
-        u64* sk = reinterpret_cast<u64*>(smem + 256);
-        stamp(P, wg, 40);
-        for (int m = wg; m < P.Rtot; m += gridDim.x) lm_merge_row(P, m, lane, sk);
-    }
+    // output row m is merged by workgroup m mod gridDim.x
+    stamp(P, wg, 40);
+    for (int m = wg; m < P.Rtot; m += gridDim.x) lm_merge_row(P, m, wave, smem + 256);
     stamp(P, wg, 62);
     stamp_wall(P, wg, 63);
     flush_stamps(P, wg);

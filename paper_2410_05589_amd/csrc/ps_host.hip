@@ -338,7 +338,7 @@ static int panel_offset_host(int mt) { return 2304 + PS_WAVES * mt * 1024; }   /
 // kw wavefronts of a workgroup share a tile (kw = 1, 2, 4 or 8; partial sums meet in LDS).  More
 // sharing keeps more wavefronts streaming when tiles are few, but a workgroup then takes fewer
 // tiles per round and every extra round costs a synchronisation and a reduction: the score is the
-// fraction of wavefront slots at work minus a small charge per extra round.
+// fraction of wavefront slots at work minus a charge per extra round.
 static bool make_desc(PhaseDesc* d, int ph, int T, int Kt, int K, int rows, int mt, bool bf, int nwg,
                       const int* override_, int lds_limit) {
     const int ktp = padded_steps(Kt), NG = ktp / PS_U;
@@ -364,7 +364,7 @@ static bool make_desc(PhaseDesc* d, int ph, int T, int Kt, int K, int rows, int 
             const int per_round = Gs * (PS_WAVES >> lg);
             const int rounds = (T + per_round - 1) / per_round;
             const double util = (double)T * kw * S / ((double)rounds * nwg * PS_WAVES);
-            const double score = util - 0.04 * (rounds - 1);
+            const double score = util - 0.15 * (rounds - 1);
             if (score > best + 1e-9) { best = score; best_log = lg; }
         }
         if (override_[1] > 0) {
