@@ -1255,45 +1255,110 @@ __device__ __forceinline__ void attn_phase(const StepParams& P, int wg, int nwg,
             }
         }
         stamp(P, wg, 34);
-        // several chunks: the workgroup of the last chunk waits for the others' partials and merges
-        if (nch > 1 && ch == nch - 1) {
-            const int item0 = item - ch;   // chunk 0 of this (b, hk)
-            for (int x = tid; x < Ra * D; x += PS_WG_THREADS) {
-                const int rho = x / D, dd = x - rho * D;
-                // chunks are folded in order with a running maximum; four chunks per round trip
-                float mrun = -INFINITY, num = 0.f, den = 0.f;
-                for (int cb = 0; cb < nch; cb += 4) {
-                    u32x2 ml0[4], ml1[4], av[4];
-                    int spins = 0;
-                    for (;;) {
-                        bool ok = true;
+    }
+
+    // ---- sequences cut into several blocks: put the blocks' partial results together.  One work
+    // item = (sequence, kv head, 8 query rows).  Wavefront w turns the (max, sum) pairs of row w
+    // into one weight per block (in LDS); then thread (row, column pair) adds up the blocks'
+    // outputs with these weights, 16 blocks per round of loads.  Blocks are taken in groups of
+    // 256; groups are folded with a running maximum, so any number of blocks works.
+    constexpr int MR = PS_WAVES;                     // rows per work item: one wavefront per row
+    constexpr int GRP = 256, CB = 16;
+    constexpr int PP = D / 2;                        // column pairs per row
+    const int RT = (Ra + MR - 1) / MR;
+    float* sW = sP;                                  // [MR][GRP] weights (the probabilities' area: same size)
+    for (int mi = wg; mi < P.attn_merge_items; mi += nwg) {
+        int b = 0, rem = mi, nch = 0, item_base = 0;
+        for (;; ++b) {
+            nch = (P.kv_len[b] + P.M + CH - 1) / CH;
+            const int n = nch > 1 ? P.nkv * RT : 0;
+            if (rem < n) break;
+            rem -= n;
+            item_base += nch * P.nkv;
+        }
+        const int hk = rem / RT, rt = rem - hk * RT;
+        const int item0 = item_base + hk * nch;      // block 0 of this (b, hk)
+        const int r0 = rt * MR, nr = min(MR, Ra - r0);
+        const int myrow = tid / PP, dp = tid - myrow * PP;
+        const bool active = myrow < nr;
+        float num0 = 0.f, num1 = 0.f, den = 0.f, mrun = -INFINITY;
+        for (int g0 = 0; g0 < nch; g0 += GRP) {
+            const int gn = min(GRP, nch - g0);
+            __syncthreads();                         // the weights of the previous group (or item) are no longer read
+            if (wave < nr) {
+                const int rho = r0 + wave;
+                u32x4 ml[GRP / 64];
+                int spins = 0;
+                for (;;) {
+                    bool ok = true;
 #pragma unroll
-                        for (int i = 0; i < 4; ++i) {
-                            const int cc = cb + i < nch ? cb + i : nch - 1;
-                            const unsigned mb = (unsigned)(((size_t)(item0 + cc) * Ra + rho) * 2);
-                            ml0[i] = coh_ld8(rml, mb * 8);
-                            ml1[i] = coh_ld8(rml, (mb + 1) * 8);
-                            av[i] = coh_ld8(racc, (unsigned)(((size_t)(item0 + cc) * Ra + rho) * D + dd) * 8);
-                            ok = ok && ml0[i][1] == P.seq && ml1[i][1] == P.seq && av[i][1] == P.seq;
-                        }
-                        if (__all(ok) || !spin_again(P, spins)) break;
+                    for (int q = 0; q < GRP / 64; ++q) {
+                        const int cx = lane + 64 * q;
+                        const int cc = g0 + (cx < gn ? cx : gn - 1);
+                        ml[q] = coh_ld16(rml, (unsigned)(((size_t)(item0 + cc) * Ra + rho) * 2) * 8);   // {max, tag, sum, tag}
+                        ok = ok && ml[q][1] == P.seq && ml[q][3] == P.seq;
                     }
+                    if (__all(ok) || !spin_again(P, spins)) break;
+                }
+                float mloc = -INFINITY;
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        if (cb + i >= nch) continue;
-                        const float m_c = __uint_as_float(ml0[i][0]), l_c = __uint_as_float(ml1[i][0]);
-                        if (l_c > 0.f) {
-                            const float mnew = fmaxf(mrun, m_c);
-                            const float so = expf(mrun - mnew), sn = expf(m_c - mnew);   // exp(-inf) = 0 at the start
-                            num = num * so + __uint_as_float(av[i][0]) * sn;
-                            den = den * so + l_c * sn;
-                            mrun = mnew;
-                        }
+                for (int q = 0; q < GRP / 64; ++q)
+                    if (lane + 64 * q < gn && __uint_as_float(ml[q][2]) > 0.f) mloc = fmaxf(mloc, __uint_as_float(ml[q][0]));
+                const float mg = wave_max(mloc);
+                float lsum = 0.f;
+#pragma unroll
+                for (int q = 0; q < GRP / 64; ++q) {
+                    const float l_c = __uint_as_float(ml[q][2]);
+                    const float w = (lane + 64 * q < gn && l_c > 0.f) ? expf(__uint_as_float(ml[q][0]) - mg) : 0.f;
+                    sW[wave * GRP + lane + 64 * q] = w;
+                    lsum += l_c * w;
+                }
+                lsum = wave_sum(lsum);
+                if (lane == 0) { sM[wave] = mg; sL[wave] = lsum; }
+            }
+            __syncthreads();
+            float o0 = 0.f, o1 = 0.f;
+            for (int cb = 0; cb < gn; cb += CB) {
+                u32x4 av[CB];
+                int spins = 0;
+                for (;;) {
+                    bool ok = true;
+#pragma unroll
+                    for (int i = 0; i < CB; ++i) {
+                        const int cc = g0 + (cb + i < gn ? cb + i : gn - 1);
+                        const int rho = r0 + (active ? myrow : 0);
+                        av[i] = coh_ld16(racc, (unsigned)(((size_t)(item0 + cc) * Ra + rho) * D + 2 * dp) * 8);   // {o, tag, o', tag}
+                        ok = ok && av[i][1] == P.seq && av[i][3] == P.seq;
+                    }
+                    if (__all(ok || !active) || !spin_again(P, spins)) break;
+                }
+#pragma unroll
+                for (int i = 0; i < CB; ++i) {
+                    if (cb + i < gn && active) {
+                        const float w = sW[myrow * GRP + cb + i];
+                        o0 += __uint_as_float(av[i][0]) * w;
+                        o1 += __uint_as_float(av[i][2]) * w;
                     }
                 }
-                const int gi = row_seq(P, rho), i = rho - gi * P.M;
-                sx_st1(ro, (unsigned)((size_t)(b * P.M + i) * P.QD + (hk * grp + gi) * D + dd), num / den);
             }
+            if (active) {
+                const float mg = sM[myrow], lg = sL[myrow];
+                if (lg > 0.f) {
+                    const float mnew = fmaxf(mrun, mg);
+                    const float so = expf(mrun - mnew), sn = expf(mg - mnew);   // exp(-inf) = 0 at the start
+                    num0 = num0 * so + o0 * sn;
+                    num1 = num1 * so + o1 * sn;
+                    den = den * so + lg * sn;
+                    mrun = mnew;
+                }
+            }
+        }
+        if (active) {
+            const int rho = r0 + myrow;
+            const int gi = row_seq(P, rho), i = rho - gi * P.M;
+            const unsigned oi = (unsigned)((size_t)(b * P.M + i) * P.QD + (hk * grp + gi) * D + 2 * dp);
+            sx_st1(ro, oi, num0 / den);
+            sx_st1(ro, oi + 1, num1 / den);
         }
     }
 }

@@ -463,7 +463,15 @@ extern "C" int ps_draft_step(ps_draft_ctx* ctx, const ps_draft_step_args* a, voi
         items += c.n_kv_heads * ((a->kv_len[b] + M + ch - 1) / ch);
     }
     P.attn_items = items; P.attn_chunk = ch;
-    P.attn_nwg = items < ctx->n_cu ? items : ctx->n_cu;
+    {   // sequences that span several key blocks are put together by (sequence, kv head, 8 rows) work items
+        const int ra = (c.n_heads / c.n_kv_heads) * M, rt = (ra + PS_WAVES - 1) / PS_WAVES;
+        int mi = 0;
+        for (int b = 0; b < a->batch; ++b)
+            if ((a->kv_len[b] + M + ch - 1) / ch > 1) mi += c.n_kv_heads * rt;
+        P.attn_merge_items = mi;
+        const int want = items > mi ? items : mi;
+        P.attn_nwg = want < ctx->n_cu ? want : ctx->n_cu;
+    }
 
     const bool bf = c.dtype == PS_BF16;
     const int nwg = ctx->n_cu;

@@ -85,6 +85,7 @@ struct StepParams {
     float *top_p, *lse, *probs, *hidden_out;
     // attention work list
     int attn_items, attn_chunk, attn_nwg;
+    int attn_merge_items;   // (sequence, kv head, 8 query rows) of the sequences that span several key blocks
     int fused_nwg, fused_lds;
     long long kv_off[PS_MAX_ROWS];
     int kv_len[PS_MAX_ROWS];
