@@ -738,7 +738,7 @@ __device__ __forceinline__ void gemm_phase(const StepParams& P, int wg, int wave
                                            const char* after_wp, const char* late_wp) {
     constexpr bool BF = Traits<WT>::BF;
     constexpr int ph = PH;
-    constexpr bool sliceable = PH == PH_OPROJ || PH == PH_GATEUP || PH == PH_DOWN;   // see make_desc on the host
+    constexpr bool sliceable = PH != PH_LMHEAD;   // see make_desc on the host
     const PhaseDesc& D = P.ph[ph];
     const int tid = threadIdx.x, lane = tid & 63, lane16 = lane * 16;
     const int c = lane & 15, kb = lane >> 4;

@@ -136,7 +136,7 @@ static WsLayout ws_layout(const ps_draft_config* c) {
         // parts of the tiles from up to PS_S_MAX K-slices (1 KiB per slice, tile and 16 rows)
         const size_t mt_max = (rows + 15) / 16;
         for (int ph = 0; ph < PH_COUNT; ++ph) {
-            const bool sliced = ph == PH_OPROJ || ph == PH_GATEUP || ph == PH_DOWN;
+            const bool sliced = ph != PH_LMHEAD;
             L.off_frag[ph] = sub(sliced ? (size_t)PS_S_MAX * T[ph] * mt_max * 1024 : 256);
             L.off_ssqf[ph] = sub((size_t)PS_S_MAX * PS_MAX_ROWS * 4);
         }
@@ -328,7 +328,7 @@ static int panel_offset_host(int mt) { return 2304 + PS_WAVES * mt * 1024; }   /
 
 // Cuts one GEMM phase: T tiles x Kt steps (K elements) over nwg workgroups of PS_WAVES wavefronts.
 //
-// S K-slices across workgroups (oproj, gateup, down only).  Every workgroup has to fetch the
+// S K-slices across workgroups (every phase but the LM head).  Every workgroup has to fetch the
 // activations of its K range from memory (exchanged data bypasses the L2), so without slices the
 // whole grid pulls nwg copies of the full activation matrix, tens of MB per phase, through the
 // fabric.  With S slices a workgroup fetches 1/S of it; workgroup wg is slice wg % S, and since
@@ -344,14 +344,16 @@ static bool make_desc(PhaseDesc* d, int ph, int T, int Kt, int K, int rows, int 
     const int ktp = padded_steps(Kt), NG = ktp / PS_U;
     const int arrays = bf ? 2 : 1;
     memset(d, 0, sizeof(*d));
+    // Slices pay for the two narrow projections (few tiles, long K: measured), and for any phase but
+    // the LM head whose activation panel does not fit in LDS as a whole (many rows): a workgroup
+    // that needs only 1/S of the panel stages it in far fewer pieces.
     int s_log = 0;
-    // measured: slices pay for the two narrow projections (few tiles, long K); gate/up has tiles enough
-    if (ph == PH_OPROJ || ph == PH_DOWN)
+    const bool whole_fits = (long long)rows * arrays * panel_row_stride_host(ktp) <= lds_limit - panel_offset_host(mt) - 256;
+    if (ph == PH_OPROJ || ph == PH_DOWN || (ph != PH_LMHEAD && !whole_fits))
         while (s_log < 3 && (2 << s_log) <= NG && (2 << s_log) <= nwg) ++s_log;
-    if (override_[0] > 0) {
-        int want = 0;
-        while ((2 << want) <= override_[0]) ++want;
-        if (want < s_log || (ph != PH_LMHEAD && ph != PH_QKV && (1 << want) <= NG && (1 << want) <= nwg && want <= 3)) s_log = want;
+    if (override_[0] > 0 && ph != PH_LMHEAD) {
+        s_log = 0;
+        while (s_log < 3 && (2 << s_log) <= override_[0] && (2 << s_log) <= NG && (2 << s_log) <= nwg) ++s_log;
     }
     for (; s_log >= 0; --s_log) {
         const int S = 1 << s_log, Gs = nwg >> s_log;
@@ -378,13 +380,14 @@ static bool make_desc(PhaseDesc* d, int ph, int T, int Kt, int K, int rows, int 
             const int fixed = panel_offset_host(mt) + (ph == PH_LMHEAD ? rounds * SL * rows * 64 : 0);
             const int budget = lds_limit - fixed - 256;
             if (budget <= 0) continue;
-            // fewest pieces whose panel fits; every piece needs at least kw groups
+            // fewest pieces whose panel fits; every slice must have the same number of pieces, each of
+            // at least kw groups (the streaming loop relies on it)
             int np = 1;
             while (np <= max_slice && (long long)rows * arrays * panel_row_stride_host((max_slice + np - 1) / np * PS_U) > budget) ++np;
             if (np > max_slice) continue;
-            if (S > 1 && np > 1) break;   // sliced phases keep their whole slice in LDS: try fewer slices
             const int pg = (max_slice + np - 1) / np;
             const int npieces = (max_slice + pg - 1) / pg;
+            if ((min_slice + pg - 1) / pg != npieces) continue;
             const int last = min_slice - (npieces - 1) * pg;   // smallest last piece over the slices
             if (pg < kw || last < kw) continue;
             d->T = T; d->Kt = ktp; d->K = K; d->rows = rows; d->kw_log = best_log; d->s_log = s_log; d->Gs = Gs;
