@@ -179,7 +179,7 @@ __device__ __forceinline__ f32x4 ll_wait4(const StepParams& P, rsrc_t r, unsigne
 // copy the next step uses is clean again without a separate clearing pass.
 #define PS_SENT 0xFFFFFFFFu
 struct SxBuf { rsrc_t cur, alt; };
-__device__ __forceinline__ SxBuf sx_buf(const StepParams& P, const float* cur) {
+__device__ __forceinline__ SxBuf sx_buf(const StepParams& P, const void* cur) {
     SxBuf b;
     b.cur = make_rsrc(cur);
     b.alt = make_rsrc(reinterpret_cast<const char*>(cur) + P.alt_delta);
@@ -301,26 +301,25 @@ __device__ __forceinline__ const char* z_ptr(const StepParams& P, int m, int e) 
 // clock at point `ev` in the top 512 bytes of LDS; flush_stamps copies them out at the end
 // together with the 100 MHz wall clock of the kernel's start and end.
 #define PS_TL_OFF (PS_LDS_BYTES - 512)
+#ifdef PS_TIMELINE
+typedef __attribute__((address_space(3))) unsigned long long lds_u64;
+// the kernels have no static LDS: dynamic LDS starts at LDS address 0
+__device__ __forceinline__ volatile lds_u64* tl_slot(int ev) { return (volatile lds_u64*)(unsigned)(PS_TL_OFF + 8 * ev); }
+#endif
 __device__ __forceinline__ void stamp(const StepParams& P, int wg, int ev) {
 #ifdef PS_TIMELINE
-    extern __shared__ __attribute__((aligned(256))) char tl_smem[];
-    if (P.timeline && threadIdx.x == 0)
-        reinterpret_cast<volatile unsigned long long*>(tl_smem + PS_TL_OFF)[ev] = __builtin_amdgcn_s_memtime();
+    if (P.timeline && threadIdx.x == 0) *tl_slot(ev) = __builtin_amdgcn_s_memtime();
 #endif
 }
 __device__ __forceinline__ void stamp_wall(const StepParams& P, int wg, int ev) {
 #ifdef PS_TIMELINE
-    extern __shared__ __attribute__((aligned(256))) char tl_smem[];
-    if (P.timeline && threadIdx.x == 0)
-        reinterpret_cast<volatile unsigned long long*>(tl_smem + PS_TL_OFF)[ev] = wall_clock64();
+    if (P.timeline && threadIdx.x == 0) *tl_slot(ev) = wall_clock64();
 #endif
 }
 __device__ __forceinline__ void flush_stamps(const StepParams& P, int wg) {
 #ifdef PS_TIMELINE
-    extern __shared__ __attribute__((aligned(256))) char tl_smem[];
     __syncthreads();
-    if (P.timeline && threadIdx.x < 64)
-        P.timeline[(size_t)threadIdx.x * 1024 + wg] = reinterpret_cast<unsigned long long*>(tl_smem + PS_TL_OFF)[threadIdx.x];
+    if (P.timeline && threadIdx.x < 64) P.timeline[(size_t)threadIdx.x * 1024 + wg] = *tl_slot(threadIdx.x);
 #endif
 }
 
@@ -502,7 +501,7 @@ __device__ __forceinline__ void epilogue_qkv(const StepParams& P, int tau, int l
             sx_st4(rq, (unsigned)((size_t)m * P.QD + hh * P.d + f), o);
         } else {
             // new K/V rows: into the cache in its storage type (for later steps), and - exactly as
-            // stored - into the tagged side buffer this step's attention reads
+            // stored - into the exchange buffer this step's attention reads
             const bool isk = hh < P.nq + P.nkv;
             const int hk = isk ? hh - P.nq : hh - P.nq - P.nkv;
             char* cache = (char*)(isk ? P.kc : P.vc);
@@ -887,15 +886,16 @@ __device__ __forceinline__ void gemm_phase(const StepParams& P, int wg, int wave
                 unsigned fq[SB];
                 int spins = 0;
                 for (;;) {
-                    bool ok = true;
 #pragma unroll
                     for (int i = 0; i < SB; ++i) {
                         const int ss = i < S ? i : S - 1;
                         fr[i] = coh_ld16(rf, (unsigned)((((ss * D.T + tau) * MT + mt) * 64 + lane) * 16));
                         fq[i] = norm ? coh_ld4(rq, (unsigned)((ss * PS_MAX_ROWS + (m < rows ? m : 0)) * 4)) : 0u;
-                        ok = ok && sx_ok(fr[i]) && fq[i] != PS_SENT;
                     }
-                    if (__all(ok) || !spin_again(P, spins)) break;
+                    unsigned bad = 0;   // all loads first, then all checks: no wait between the loads
+#pragma unroll
+                    for (int i = 0; i < SB; ++i) bad |= (unsigned)!sx_ok(fr[i]) | (unsigned)(fq[i] == PS_SENT);
+                    if (__all(!bad) || !spin_again(P, spins)) break;
                 }
                 f32x4 sum = f32x4{0.f, 0.f, 0.f, 0.f};
                 float t = 0.f;
@@ -1013,30 +1013,166 @@ template <typename WT, int D> struct AttnCfg {
     static constexpr int LDS = OFF_O + PS_WAVES * 16 * D * 4;
 };
 
-// DPL adjacent elements of a V row in the cache's storage type -> floats
-template <typename WT, int DPL> __device__ __forceinline__ void load_v(const char* p, float* out) {
-    if constexpr (Traits<WT>::BF) {
-        if constexpr (DPL == 2) {
-            const uint32_t u = *reinterpret_cast<const uint32_t*>(p);
-            out[0] = bf16_to_f32(u & 0xFFFFu); out[1] = bf16_to_f32(u >> 16);
-        } else {
-            out[0] = bf16_to_f32(*reinterpret_cast<const uint16_t*>(p));
+// One attention work item: sequence b, kv head hk, key block ch of nch; L = valid cache rows
+struct AttnItem { int b, hk, ch, nch, L; };
+__device__ __forceinline__ AttnItem attn_decode(const StepParams& P, int item, int CH) {
+    AttnItem it;
+    int b = 0, rem = item, nch = 0;
+    for (;; ++b) {
+        nch = (P.kv_len[b] + P.M + CH - 1) / CH;
+        if (rem < nch * P.nkv) break;
+        rem -= nch * P.nkv;
+    }
+    it.b = b; it.nch = nch; it.hk = rem / nch; it.ch = rem - it.hk * nch; it.L = P.kv_len[b];
+    return it;
+}
+
+// K rows of the wavefront's 16 keys key0 .. key0 + 15 as the MFMA operand: lane (c, kb) gets
+// bytes [64 t + 16 kb, +16) of key c.  Keys beyond the sequence are clamped (masked later); keys
+// written in this step are taken from the exchange buffer once the QKV phase has published them.
+template <typename WT, int D>
+__device__ __forceinline__ void attn_load_k(const StepParams& P, const AttnItem& it, int key0, int lane,
+                                            uint4 (&kreg)[D / Traits<WT>::KSTEP]) {
+    constexpr bool BF = Traits<WT>::BF;
+    constexpr int ESZ = Traits<WT>::ESZ, GE = Traits<WT>::GE, KSTEP = Traits<WT>::KSTEP, NL = GE / 4, STEPS = D / KSTEP;
+    const int c = lane & 15, kb = lane >> 4;
+    const int L = it.L, end = L + P.M;
+    const int kpos = key0 + c;
+    const int pc = kpos < L ? kpos : (L > 0 ? L - 1 : 0);
+    const char* krow = (const char*)P.kc + (((size_t)P.kv_off[it.b] + pc) * P.nkv + it.hk) * D * ESZ + kb * 16;
+#pragma unroll
+    for (int t = 0; t < STEPS; ++t) kreg[t] = ld16(krow + t * 64);
+    if (key0 + 15 >= L && key0 < end) {
+        const rsrc_t rn = make_rsrc(P.kvnew);
+        const bool k_new = kpos >= L;
+        const int pn = kpos < L ? L : (kpos < end ? kpos : end - 1);
+        const unsigned kbase = (unsigned)(((size_t)(it.b * P.M + (pn - L)) * 2) * P.KVD + it.hk * D + kb * GE);
+        u32x4 kx[STEPS][NL];
+        int spins = 0;
+        const bool wanted = k_new && kpos < end;
+        for (;;) {
+#pragma unroll
+            for (int t = 0; t < STEPS; ++t)
+#pragma unroll
+                for (int h = 0; h < NL; ++h) kx[t][h] = coh_ld16(rn, (kbase + t * KSTEP + 4 * h) * 4);
+            unsigned bad = 0;   // all loads first, then all checks: no wait between the loads
+#pragma unroll
+            for (int t = 0; t < STEPS; ++t)
+#pragma unroll
+                for (int h = 0; h < NL; ++h) bad |= (unsigned)!sx_ok(kx[t][h]);
+            if (__all(!wanted || !bad) || !spin_again(P, spins)) break;
         }
-    } else {
-        if constexpr (DPL == 2) {
-            const float2 u = *reinterpret_cast<const float2*>(p);
-            out[0] = u.x; out[1] = u.y;
-        } else {
-            out[0] = *reinterpret_cast<const float*>(p);
+        if (k_new) {
+#pragma unroll
+            for (int t = 0; t < STEPS; ++t) {
+                if constexpr (BF) {
+                    kreg[t].x = pack_bf16x2(__uint_as_float(kx[t][0][0]), __uint_as_float(kx[t][0][1]));
+                    kreg[t].y = pack_bf16x2(__uint_as_float(kx[t][0][2]), __uint_as_float(kx[t][0][3]));
+                    kreg[t].z = pack_bf16x2(__uint_as_float(kx[t][1][0]), __uint_as_float(kx[t][1][1]));
+                    kreg[t].w = pack_bf16x2(__uint_as_float(kx[t][1][2]), __uint_as_float(kx[t][1][3]));
+                } else {
+                    kreg[t] = make_uint4(kx[t][0][0], kx[t][0][1], kx[t][0][2], kx[t][0][3]);
+                }
+            }
         }
     }
+}
+// V rows of the same keys: a lane owns columns [DPL lane, DPL lane + DPL).  attn_issue_v requests
+// them (unconditionally, positions clamped, so all 16 loads are in flight together) as raw bits and
+// fetches the rows written in this step from the exchange buffer; attn_finish_v widens them and
+// zeroes the keys beyond the sequence.
+template <typename WT, int DPL> struct VRaw;
+template <> struct VRaw<bf16_t, 2> { typedef uint32_t type; };
+template <> struct VRaw<bf16_t, 1> { typedef uint16_t type; };
+template <> struct VRaw<float, 2> { typedef float2 type; };
+template <> struct VRaw<float, 1> { typedef float type; };
+__device__ __forceinline__ void widen_v(uint32_t u, float* out) { out[0] = bf16_to_f32(u & 0xFFFFu); out[1] = bf16_to_f32(u >> 16); }
+__device__ __forceinline__ void widen_v(uint16_t u, float* out) { out[0] = bf16_to_f32(u); }
+__device__ __forceinline__ void widen_v(float2 u, float* out) { out[0] = u.x; out[1] = u.y; }
+__device__ __forceinline__ void widen_v(float u, float* out) { out[0] = u; }
+__device__ __forceinline__ void narrow_v(const float* in, uint32_t& u) { u = pack_bf16x2(in[0], in[1]); }
+__device__ __forceinline__ void narrow_v(const float* in, uint16_t& u) { u = (uint16_t)f32_to_bf16(in[0]); }
+__device__ __forceinline__ void narrow_v(const float* in, float2& u) { u = make_float2(in[0], in[1]); }
+__device__ __forceinline__ void narrow_v(const float* in, float& u) { u = in[0]; }
+
+template <typename WT, int D>
+__device__ __forceinline__ void attn_issue_v(const StepParams& P, const AttnItem& it, int key0, int lane,
+                                             typename VRaw<WT, D / 64>::type (&vraw)[16]) {
+    constexpr int ESZ = Traits<WT>::ESZ, DPL = D / 64;
+    typedef typename VRaw<WT, DPL>::type raw_t;
+    const int L = it.L, end = L + P.M;
+    const size_t cache_row0 = (size_t)P.kv_off[it.b] * P.nkv + it.hk;   // in units of D elements
+#pragma unroll
+    for (int kk = 0; kk < 16; ++kk) {
+        const int pos = key0 + kk;                                // wavefront-uniform
+        const int pc = pos < L ? pos : (L > 0 ? L - 1 : 0);
+        vraw[kk] = *reinterpret_cast<const raw_t*>((const char*)P.vc + ((cache_row0 + (size_t)pc * P.nkv) * D + DPL * lane) * ESZ);
+    }
+    if (key0 + 15 >= L && key0 < end) {
+        // rows written in this step: from the exchange buffer, as soon as the QKV phase has published
+        // them; they are exactly representable in the storage type (they were rounded to it)
+        const rsrc_t rn = make_rsrc(P.kvnew);
+        float vx[16][DPL];
+        int spins = 0;
+        for (;;) {
+#pragma unroll
+            for (int kk = 0; kk < 16; ++kk) {
+                const int pos = key0 + kk;
+                const int pn = pos < L ? L : (pos < end ? pos : end - 1);   // clamped: every load is unconditional
+                const unsigned vb = (unsigned)(((size_t)(it.b * P.M + (pn - L)) * 2 + 1) * P.KVD + it.hk * D + DPL * lane);
+#pragma unroll
+                for (int e = 0; e < DPL; ++e) vx[kk][e] = __uint_as_float(coh_ld4(rn, (vb + e) * 4));
+            }
+            unsigned bad = 0;   // clamped positions repeat a wanted row: checking them all is right
+#pragma unroll
+            for (int kk = 0; kk < 16; ++kk)
+#pragma unroll
+                for (int e = 0; e < DPL; ++e) bad |= (unsigned)(__float_as_uint(vx[kk][e]) == PS_SENT);
+            if (__all(!bad) || !spin_again(P, spins)) break;
+        }
+#pragma unroll
+        for (int kk = 0; kk < 16; ++kk) {
+            const int pos = key0 + kk;
+            if (pos >= L && pos < end) narrow_v(vx[kk], vraw[kk]);
+        }
+    }
+}
+template <typename WT, int D>
+__device__ __forceinline__ void attn_finish_v(const StepParams& P, const AttnItem& it, int key0, int lane,
+                                              const typename VRaw<WT, D / 64>::type (&vraw)[16], float (&v)[16][D / 64]) {
+    constexpr int DPL = D / 64;
+    const int end = it.L + P.M;
+#pragma unroll
+    for (int kk = 0; kk < 16; ++kk) {
+        widen_v(vraw[kk], v[kk]);
+        if (key0 + kk >= end) {                                   // beyond the sequence
+#pragma unroll
+            for (int e = 0; e < DPL; ++e) v[kk][e] = 0.f;
+        }
+    }
+}
+// Requests the query rows r0 .. r0 + 15 of the item as the 16-column operand (lane (c, kb) holds
+// row r0 + c) without waiting for them
+template <typename WT, int D>
+__device__ __forceinline__ void attn_issue_q(const StepParams& P, const AttnItem& it, int r0, int Ra, int grp, int lane,
+                                             u32x4 (&qx)[D / Traits<WT>::KSTEP][Traits<WT>::GE / 4]) {
+    constexpr int GE = Traits<WT>::GE, KSTEP = Traits<WT>::KSTEP, NL = GE / 4, STEPS = D / KSTEP;
+    const int c = lane & 15, kb = lane >> 4;
+    const rsrc_t rq = make_rsrc(P.q_buf);
+    const int rho = r0 + c < Ra ? r0 + c : Ra - 1;
+    const int gi = row_seq(P, rho), i = rho - gi * P.M;
+    const unsigned qbase = (unsigned)((size_t)(it.b * P.M + i) * P.QD + (it.hk * grp + gi) * D + kb * GE);
+#pragma unroll
+    for (int t = 0; t < STEPS; ++t)
+#pragma unroll
+        for (int h = 0; h < NL; ++h) qx[t][h] = coh_ld16(rq, (qbase + t * KSTEP + 4 * h) * 4);
 }
 
 template <typename WT, int D>
 __device__ __forceinline__ void attn_phase(const StepParams& P, int wg, int nwg, int wave, char* smem) {
     typedef AttnCfg<WT, D> C;
     constexpr bool BF = Traits<WT>::BF;
-    constexpr int CH = C::CH, ESZ = Traits<WT>::ESZ, GE = Traits<WT>::GE, KSTEP = Traits<WT>::KSTEP;
+    constexpr int CH = C::CH, GE = Traits<WT>::GE, KSTEP = Traits<WT>::KSTEP;
     constexpr int NL = GE / 4;                      // 16-byte loads per group of exchanged fp32
     constexpr int STEPS = D / KSTEP;                // MFMA steps along the head dimension
     constexpr int DPL = D / 64;                     // output columns per lane
@@ -1048,118 +1184,46 @@ __device__ __forceinline__ void attn_phase(const StepParams& P, int wg, int nwg,
     float* sL = reinterpret_cast<float*>(smem + C::OFF_L);
     float* sP = reinterpret_cast<float*>(smem + C::OFF_P);
     float* sO = reinterpret_cast<float*>(smem + C::OFF_O);
-    const rsrc_t rq = make_rsrc(P.q_buf), rn = make_rsrc(P.kvnew), racc = make_rsrc(P.attn_acc),
-                 rml = make_rsrc(P.attn_ml);
+    const rsrc_t racc = make_rsrc(P.attn_acc), rml = make_rsrc(P.attn_ml);
     const SxBuf ro = sx_buf(P, P.o_buf);
 
+    // The loads of a work item are requested while the previous item is still being computed: the
+    // K rows and the first query rows right after the score MFMAs, the V rows right after P.V.
+    uint4 kreg[STEPS];
+    typename VRaw<WT, DPL>::type vraw[16];
+    u32x4 qx[STEPS][NL];
+    AttnItem cur = {0, 0, 0, 1, 0};
+    if (wg < P.attn_items) {
+        cur = attn_decode(P, wg, CH);
+        attn_load_k<WT, D>(P, cur, cur.ch * CH + 16 * wave, lane, kreg);
+        attn_issue_v<WT, D>(P, cur, cur.ch * CH + 16 * wave, lane, vraw);
+        attn_issue_q<WT, D>(P, cur, 0, Ra, grp, lane, qx);
+    }
     for (int item = wg; item < P.attn_items; item += nwg) {
-        // decode item -> (b, hk, chunk)
-        int b = 0, rem = item, nch = 0;
-        for (;; ++b) {
-            nch = (P.kv_len[b] + P.M + CH - 1) / CH;
-            if (rem < nch * P.nkv) break;
-            rem -= nch * P.nkv;
-        }
-        const int hk = rem / nch, ch = rem - hk * nch;
-        const int L = P.kv_len[b];
+        const bool has_next = item + nwg < P.attn_items;
+        const AttnItem nx = has_next ? attn_decode(P, item + nwg, CH) : cur;
+        const int b = cur.b, hk = cur.hk, ch = cur.ch, nch = cur.nch, L = cur.L;
         const int c0 = ch * CH;
         const int key0 = c0 + 16 * wave;            // this wavefront's keys: positions key0 .. key0 + 15
         const int end = L + P.M;                    // positions that exist
-        const bool has_new = key0 + 15 >= L && key0 < end;
-        const size_t cache_row0 = (size_t)P.kv_off[b] * P.nkv + hk;   // in units of D elements
-
-        // ---- this wavefront's K rows (MFMA operand: lane (c, kb) holds 16 bytes of key c) and V rows
-        const int kpos = key0 + c;
-        const bool k_new = kpos >= L;
-        uint4 kreg[STEPS];
-        {
-            const int pc = kpos < L ? kpos : (L > 0 ? L - 1 : 0);     // clamped: the load stays unconditional
-            const char* krow = (const char*)P.kc + (cache_row0 + (size_t)pc * P.nkv) * D * ESZ + kb * 16;
-#pragma unroll
-            for (int t = 0; t < STEPS; ++t) kreg[t] = ld16(krow + t * 64);
-        }
-        float v[16][DPL];
-#pragma unroll
-        for (int kk = 0; kk < 16; ++kk) {
-            const int pos = key0 + kk;                               // wavefront-uniform
-#pragma unroll
-            for (int e = 0; e < DPL; ++e) v[kk][e] = 0.f;
-            if (pos < L)
-                load_v<WT, DPL>((const char*)P.vc + ((cache_row0 + (size_t)pos * P.nkv) * D + DPL * lane) * ESZ, v[kk]);
-        }
-        if (has_new) {   // rows of this step: wait until the QKV phase has published them
-            const int pn = kpos < L ? L : (kpos < end ? kpos : end - 1);
-            const unsigned kbase = (unsigned)(((size_t)(b * P.M + (pn - L)) * 2) * P.KVD + hk * D + kb * GE);
-            u32x4 kx[STEPS][NL];
-            float vx[16][DPL];
-            int spins = 0;
-            for (;;) {
-                bool ok = true;
-#pragma unroll
-                for (int t = 0; t < STEPS; ++t)
-#pragma unroll
-                    for (int h = 0; h < NL; ++h) {
-                        kx[t][h] = coh_ld16(rn, (kbase + t * KSTEP + 4 * h) * 4);
-                        ok = ok && (!k_new || kpos >= end || sx_ok(kx[t][h]));
-                    }
-#pragma unroll
-                for (int kk = 0; kk < 16; ++kk) {
-                    const int pos = key0 + kk;
-                    if (pos >= L && pos < end) {
-                        const unsigned vb = (unsigned)(((size_t)(b * P.M + (pos - L)) * 2 + 1) * P.KVD + hk * D + DPL * lane);
-#pragma unroll
-                        for (int e = 0; e < DPL; ++e) {
-                            const unsigned u = coh_ld4(rn, (vb + e) * 4);
-                            ok = ok && u != PS_SENT;
-                            vx[kk][e] = __uint_as_float(u);
-                        }
-                    }
-                }
-                if (__all(ok) || !spin_again(P, spins)) break;
-            }
-            if (k_new) {
-#pragma unroll
-                for (int t = 0; t < STEPS; ++t) {
-                    if constexpr (BF) {
-                        kreg[t].x = pack_bf16x2(__uint_as_float(kx[t][0][0]), __uint_as_float(kx[t][0][1]));
-                        kreg[t].y = pack_bf16x2(__uint_as_float(kx[t][0][2]), __uint_as_float(kx[t][0][3]));
-                        kreg[t].z = pack_bf16x2(__uint_as_float(kx[t][1][0]), __uint_as_float(kx[t][1][1]));
-                        kreg[t].w = pack_bf16x2(__uint_as_float(kx[t][1][2]), __uint_as_float(kx[t][1][3]));
-                    } else {
-                        kreg[t] = make_uint4(kx[t][0][0], kx[t][0][1], kx[t][0][2], kx[t][0][3]);
-                    }
-                }
-            }
-#pragma unroll
-            for (int kk = 0; kk < 16; ++kk) {
-                const int pos = key0 + kk;
-                if (pos >= L && pos < end) {
-#pragma unroll
-                    for (int e = 0; e < DPL; ++e) v[kk][e] = vx[kk][e];
-                }
-            }
-        }
 
         for (int r0 = 0; r0 < Ra; r0 += 16) {       // 16 query rows per pass
             const int nr = min(16, Ra - r0);
-            // ---- query rows as the 16-column operand: lane (c, kb) holds row r0 + c
+            const bool last_pass = r0 + 16 >= Ra;
             const int rho = r0 + c < Ra ? r0 + c : Ra - 1;
-            const int gi = row_seq(P, rho), i = rho - gi * P.M;
-            const unsigned qbase = (unsigned)((size_t)(b * P.M + i) * P.QD + (hk * grp + gi) * D + kb * GE);
+            const int i = rho - row_seq(P, rho) * P.M;
+            if (r0 > 0) attn_issue_q<WT, D>(P, cur, r0, Ra, grp, lane, qx);
             BRegs<WT, 1> bq[STEPS];
             {
-                u32x4 qx[STEPS][NL];
                 int spins = 0;
-                for (;;) {
-                    bool ok = true;
+                for (;;) {   // requested earlier; asked for again until the QKV phase has published the rows
+                    unsigned bad = 0;
 #pragma unroll
                     for (int t = 0; t < STEPS; ++t)
 #pragma unroll
-                        for (int h = 0; h < NL; ++h) {
-                            qx[t][h] = coh_ld16(rq, (qbase + t * KSTEP + 4 * h) * 4);
-                            ok = ok && sx_ok(qx[t][h]);
-                        }
-                    if (__all(ok) || !spin_again(P, spins)) break;
+                        for (int h = 0; h < NL; ++h) bad |= (unsigned)!sx_ok(qx[t][h]);
+                    if (__all(!bad) || !spin_again(P, spins)) break;
+                    attn_issue_q<WT, D>(P, cur, r0, Ra, grp, lane, qx);
                 }
 #pragma unroll
                 for (int t = 0; t < STEPS; ++t) {
@@ -1179,11 +1243,14 @@ __device__ __forceinline__ void attn_phase(const StepParams& P, int wg, int nwg,
                     }
                 }
             }
-            if (item == wg && r0 == 0) stamp(P, wg, 33);
             // ---- scores of keys 4 kb .. 4 kb + 3 (of this wavefront's 16) for query row c
             f32x4 acc[1] = {f32x4{0.f, 0.f, 0.f, 0.f}};
 #pragma unroll
             for (int t = 0; t < STEPS; ++t) mma_step<WT, 1>(kreg[t], bq[t], acc);
+            if (last_pass && has_next) {   // the K rows and query rows are consumed: request the next item's
+                attn_load_k<WT, D>(P, nx, nx.ch * CH + 16 * wave, lane, kreg);
+                attn_issue_q<WT, D>(P, nx, 0, Ra, grp, lane, qx);
+            }
             float sc[4], mloc = -INFINITY;
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
@@ -1214,6 +1281,8 @@ __device__ __forceinline__ void attn_phase(const StepParams& P, int wg, int nwg,
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");   // written and read by this wavefront only
             __builtin_amdgcn_wave_barrier();
             // ---- this wavefront's part of P.V for every row of the pass
+            float v[16][DPL];
+            attn_finish_v<WT, D>(P, cur, key0, lane, vraw, v);
             for (int rr = 0; rr < nr; ++rr) {
                 const f32x4* prow = reinterpret_cast<const f32x4*>(sP + (wave * 16 + rr) * 16);
                 float o[DPL];
@@ -1230,6 +1299,7 @@ __device__ __forceinline__ void attn_phase(const StepParams& P, int wg, int nwg,
 #pragma unroll
                 for (int e = 0; e < DPL; ++e) sO[(wave * 16 + rr) * D + DPL * lane + e] = o[e];
             }
+            if (last_pass && has_next) attn_issue_v<WT, D>(P, nx, nx.ch * CH + 16 * wave, lane, vraw);
             __syncthreads();
             // ---- add the wavefronts' parts in order
             for (int x = tid; x < nr * D; x += PS_WG_THREADS) {
@@ -1254,6 +1324,7 @@ __device__ __forceinline__ void attn_phase(const StepParams& P, int wg, int nwg,
                 }
             }
         }
+        cur = nx;
         stamp(P, wg, 34);
     }
 
@@ -1290,15 +1361,16 @@ __device__ __forceinline__ void attn_phase(const StepParams& P, int wg, int nwg,
                 u32x4 ml[GRP / 64];
                 int spins = 0;
                 for (;;) {
-                    bool ok = true;
 #pragma unroll
                     for (int q = 0; q < GRP / 64; ++q) {
                         const int cx = lane + 64 * q;
                         const int cc = g0 + (cx < gn ? cx : gn - 1);
                         ml[q] = coh_ld16(rml, (unsigned)(((size_t)(item0 + cc) * Ra + rho) * 2) * 8);   // {max, tag, sum, tag}
-                        ok = ok && ml[q][1] == P.seq && ml[q][3] == P.seq;
                     }
-                    if (__all(ok) || !spin_again(P, spins)) break;
+                    unsigned bad = 0;
+#pragma unroll
+                    for (int q = 0; q < GRP / 64; ++q) bad |= (unsigned)(ml[q][1] != P.seq) | (unsigned)(ml[q][3] != P.seq);
+                    if (__all(!bad) || !spin_again(P, spins)) break;
                 }
                 float mloc = -INFINITY;
 #pragma unroll
@@ -1322,15 +1394,16 @@ __device__ __forceinline__ void attn_phase(const StepParams& P, int wg, int nwg,
                 u32x4 av[CB];
                 int spins = 0;
                 for (;;) {
-                    bool ok = true;
 #pragma unroll
                     for (int i = 0; i < CB; ++i) {
                         const int cc = g0 + (cb + i < gn ? cb + i : gn - 1);
                         const int rho = r0 + (active ? myrow : 0);
                         av[i] = coh_ld16(racc, (unsigned)(((size_t)(item0 + cc) * Ra + rho) * D + 2 * dp) * 8);   // {o, tag, o', tag}
-                        ok = ok && av[i][1] == P.seq && av[i][3] == P.seq;
                     }
-                    if (__all(ok || !active) || !spin_again(P, spins)) break;
+                    unsigned bad = 0;
+#pragma unroll
+                    for (int i = 0; i < CB; ++i) bad |= (unsigned)(av[i][1] != P.seq) | (unsigned)(av[i][3] != P.seq);
+                    if (__all(!bad || !active) || !spin_again(P, spins)) break;
                 }
 #pragma unroll
                 for (int i = 0; i < CB; ++i) {
@@ -1396,18 +1469,16 @@ __device__ __forceinline__ void lm_merge_row(const StepParams& P, int m, int wav
         u32x4 hd, kr[KB];
         int spins = 0;
         for (;;) {
-            bool ok = true;
-            if (t0 == 0) {
-                hd = coh_ld16(rl, base);                   // {max, tag, sum, tag}
-                ok = hd[1] == P.seq && hd[3] == P.seq;
-            }
+            hd = coh_ld16(rl, base);                       // {max, tag, sum, tag}
 #pragma unroll
             for (int i = 0; i < KB; ++i) {
                 const int t = t0 + i < topk ? t0 + i : topk - 1;
                 kr[i] = coh_ld16(rl, base + (2 + 2 * t) * 8);   // {low, tag, high, tag}
-                ok = ok && kr[i][1] == P.seq && kr[i][3] == P.seq;
             }
-            if (__all(ok || !mine) || !spin_again(P, spins)) break;
+            unsigned bad = (unsigned)(hd[1] != P.seq) | (unsigned)(hd[3] != P.seq);   // all loads first, then all checks
+#pragma unroll
+            for (int i = 0; i < KB; ++i) bad |= (unsigned)(kr[i][1] != P.seq) | (unsigned)(kr[i][3] != P.seq);
+            if (__all(!bad || !mine) || !spin_again(P, spins)) break;
         }
         if (t0 == 0 && mine) { pmax = __uint_as_float(hd[0]); psum = __uint_as_float(hd[2]); }
 #pragma unroll
