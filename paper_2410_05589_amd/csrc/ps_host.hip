@@ -46,6 +46,8 @@ struct ps_draft_ctx {
     size_t act_bytes;
     size_t off_q, off_o, off_y, off_u, off_y2, off_kvnew;   // offsets inside one copy
     int last_shape[3];                // batch, n_new, k of the previous step
+    unsigned last_frag_sig;           // column tiles and K-slices per phase of the previous step
+    size_t act_small;                 // bytes of a copy whose slots in use depend on the shape only
     char* wpack[PH_COUNT];
     int* counters;
     int n_counters;
@@ -90,7 +92,7 @@ struct WsLayout {
     size_t wpack[PH_COUNT];
     size_t rope, q_buf, o_buf, y_buf, u_buf, y2_buf, kvnew, attn_acc, attn_ml, counters, lm_part, logits_ws, total;
     size_t exch_begin, exch_end;
-    size_t act_base, act_bytes, off_q, off_o, off_y, off_u, off_y2, off_kvnew, off_frag[PH_COUNT], off_ssqf[PH_COUNT];
+    size_t act_base, act_bytes, act_small, off_q, off_o, off_y, off_u, off_y2, off_kvnew, off_frag[PH_COUNT], off_ssqf[PH_COUNT];
     int n_counters;
 };
 
@@ -135,10 +137,11 @@ static WsLayout ws_layout(const ps_draft_config* c) {
         L.off_kvnew = sub(rows * 2 * (size_t)c->n_kv_heads * c->head_dim * 4);
         // parts of the tiles from up to PS_S_MAX K-slices (1 KiB per slice, tile and 16 rows)
         const size_t mt_max = (rows + 15) / 16;
+        for (int ph = 0; ph < PH_COUNT; ++ph) L.off_ssqf[ph] = sub((size_t)PS_S_MAX * PS_MAX_ROWS * 4);
+        L.act_small = a;   // up to here the slots in use depend on (batch, n_new, k); behind it on the K-slice plan
         for (int ph = 0; ph < PH_COUNT; ++ph) {
             const bool sliced = ph != PH_LMHEAD;
             L.off_frag[ph] = sub(sliced ? (size_t)PS_S_MAX * T[ph] * mt_max * 1024 : 256);
-            L.off_ssqf[ph] = sub((size_t)PS_S_MAX * PS_MAX_ROWS * 4);
         }
         L.act_bytes = a;
         L.act_base = take(2 * a);
@@ -246,6 +249,7 @@ extern "C" int ps_draft_init(ps_draft_ctx** out, const ps_draft_config* config, 
     ctx->off_y2 = L.off_y2; ctx->off_kvnew = L.off_kvnew;
     for (int ph = 0; ph < PH_COUNT; ++ph) { ctx->off_frag[ph] = L.off_frag[ph]; ctx->off_ssqf[ph] = L.off_ssqf[ph]; }
     ctx->last_shape[0] = ctx->last_shape[1] = ctx->last_shape[2] = -1;
+    ctx->last_frag_sig = 0; ctx->act_small = L.act_small;
     ctx->attn_acc = (float*)(base + L.attn_acc);
     ctx->attn_ml = (float*)(base + L.attn_ml);
     ctx->seq = 0;
@@ -449,10 +453,11 @@ extern "C" int ps_draft_step(ps_draft_ctx* ctx, const ps_draft_step_args* a, voi
         P.u_buf = (float*)(cur + ctx->off_u); P.y2_buf = (float*)(cur + ctx->off_y2); P.kvnew = (float*)(cur + ctx->off_kvnew);
         P.alt_delta = par ? -(long long)ctx->act_bytes : (long long)ctx->act_bytes;
         // a step only resets the elements it writes: when the row layout changes, elements the previous
-        // step did not touch could still look written, so this step's copy is cleared first
+        // step did not touch could still look written, so this step's copy is cleared first (the part
+        // whose slots depend on the rows here; the K-slice fragments further down, once the plan is known)
         if (ctx->last_shape[0] != a->batch || ctx->last_shape[1] != a->n_new || ctx->last_shape[2] != a->k) {
             if (ctx->last_shape[0] >= 0 &&
-                !hip_ok(hipMemsetAsync(cur, 0xFF, ctx->act_bytes, (hipStream_t)stream), "hipMemsetAsync")) return PS_ERR_DEVICE;
+                !hip_ok(hipMemsetAsync(cur, 0xFF, ctx->act_small, (hipStream_t)stream), "hipMemsetAsync")) return PS_ERR_DEVICE;
             ctx->last_shape[0] = a->batch; ctx->last_shape[1] = a->n_new; ctx->last_shape[2] = a->k;
         }
     }
@@ -490,6 +495,16 @@ extern "C" int ps_draft_step(ps_draft_ctx* ctx, const ps_draft_step_args* a, voi
         P.ph[ph].wpack = ctx->wpack[ph];
         P.ph[ph].frag = (float*)(act_cur + ctx->off_frag[ph]);
         P.ph[ph].ssq_frag = (float*)(act_cur + ctx->off_ssqf[ph]);
+    }
+    {   // which fragment slots a step uses depends on the column tiles and the K-slices of each phase
+        unsigned sig = (unsigned)((P.Mtot + 15) / 16);
+        for (int ph = 0; ph < PH_COUNT; ++ph) sig = sig * 8u + (unsigned)P.ph[ph].s_log + 1u;
+        if (sig != ctx->last_frag_sig) {
+            if (ctx->last_frag_sig != 0 &&
+                !hip_ok(hipMemsetAsync(act_cur + ctx->act_small, 0xFF, ctx->act_bytes - ctx->act_small, (hipStream_t)stream), "hipMemsetAsync"))
+                return PS_ERR_DEVICE;
+            ctx->last_frag_sig = sig;
+        }
     }
     P.ph[PH_QKV].norm = 1; P.ph[PH_QKV].gain = P.g_in; P.ph[PH_QKV].src = nullptr; P.ph[PH_QKV].src_ld = P.H;
     P.ph[PH_OPROJ].src = P.o_buf; P.ph[PH_OPROJ].src_ld = P.QD;
