@@ -619,7 +619,7 @@ __device__ __forceinline__ unsigned pack_bf16x2(float a, float b) {
 template <typename WT, int PH>
 __device__ __forceinline__ void stage_piece(const StepParams& P, const PhaseDesc& D, int wave, char* smem,
                                             char* s_pa, char* s_pb, int a_step, int nsteps, bool first_piece,
-                                            bool want_ssq, uint4 (&wb)[PS_U], const char* late_wp) {
+                                            bool want_ssq) {
     constexpr bool BF = Traits<WT>::BF;
     constexpr int KSTEP = Traits<WT>::KSTEP, GE = Traits<WT>::GE, ESZ = Traits<WT>::ESZ;
     constexpr int NL = GE / 4;                       // 16-byte loads per group of exchanged fp32
@@ -636,10 +636,6 @@ __device__ __forceinline__ void stage_piece(const StepParams& P, const PhaseDesc
     const int rows = D.rows, K = D.K, RS = D.rs, ld = D.src_ld;
     const bool norm = PH == PH_QKV || PH == PH_GATEUP || (PH == PH_LMHEAD && D.norm != 0);
     const rsrc_t rs = make_rsrc(from_x ? P.x : (const void*)D.src), rmask = make_rsrc(from_x ? P.mask_emb : (const void*)D.src);
-    if (late_wp && rsub >= rows) {   // wavefronts without a row to stage
-        preload_weights(wb, late_wp, lane * 16);
-        late_wp = nullptr;
-    }
     for (int gc = 0; gc < G; gc += G2) {
         const int gi = gc + gi0;
         const bool gvalid = gi < G;
@@ -668,10 +664,6 @@ __device__ __forceinline__ void stage_piece(const StepParams& P, const PhaseDesc
                         for (int h = 0; h < NL; ++h)
                             raw[i][h] = __builtin_amdgcn_raw_buffer_load_b128(rs, (kkc + 4 * h) * 4, srow * ld * 4, PS_SC1);
                     }
-                }
-                if (late_wp) {   // the step's first weight loads queue up behind the first activation loads
-                    preload_weights(wb, late_wp, lane * 16);
-                    late_wp = nullptr;
                 }
                 if (from_x) break;
                 bool ok = true;
@@ -728,13 +720,11 @@ __device__ __forceinline__ void stage_piece(const StepParams& P, const PhaseDesc
 }
 
 // One phase for one workgroup.  wb: the wavefront's weight-load registers.  On entry they hold
-// the preloaded head of first_stream(ph) - or nothing yet if late_wp is that head: then the loads
-// are issued right after the first activation loads (loads return in order, so at the start of
-// the step the activations should not wait behind the weights).  On exit they hold PS_U loads
-// from after_wp (the head of whatever this wavefront streams next, or any readable address).
+// the preloaded head of first_stream(ph); on exit they hold PS_U loads from after_wp (the head of
+// whatever this wavefront streams next, or any readable address).
 template <typename WT, int MT, int PH>
 __device__ __forceinline__ void gemm_phase(const StepParams& P, int wg, int wave, char* smem, uint4 (&wb)[PS_U],
-                                           const char* after_wp, const char* late_wp) {
+                                           const char* after_wp) {
     constexpr bool BF = Traits<WT>::BF;
     constexpr int ph = PH;
     constexpr bool sliceable = PH != PH_LMHEAD;   // see make_desc on the host
@@ -792,8 +782,7 @@ __device__ __forceinline__ void gemm_phase(const StepParams& P, int wg, int wave
             const int ng = min(D.piece_groups, sg_hi - g_lo);
             if (rd == 0 || D.npieces > 1) {   // a panel that fits as a whole is staged once
                 if (rd > 0 || pc > 0) __syncthreads();   // everyone is done with the previous piece
-                stage_piece<WT, PH>(P, D, wave, smem, s_pa, s_pb, g_lo * PS_U, ng * PS_U, pc == 0, rd == 0, wb,
-                                rd == 0 && pc == 0 ? late_wp : nullptr);
+                stage_piece<WT, PH>(P, D, wave, smem, s_pa, s_pb, g_lo * PS_U, ng * PS_U, pc == 0, rd == 0);
                 __syncthreads();
                 if (rd == 0 && pc == 0) stamp(P, wg, 2 + ph * 6 + 1);
             }
@@ -947,12 +936,13 @@ __device__ __forceinline__ void gemm_phase(const StepParams& P, int wg, int wave
             se = wave_sum(se);
             const unsigned obase = (unsigned)((j * rows + m) * stride);
             if (lane < 2) ll_st1(rl, obase + lane, lane ? se : mx, P.seq);
+            const int nepl = min(EPL, (n_el + 63) >> 6);   // registers per lane that hold elements
             u64 prev = ~0ull;   // keys are unique: the next winner is the largest key below the previous one
             for (int t = 0; t < topk; ++t) {
                 u64 best = 0;
 #pragma unroll
                 for (int i = 0; i < EPL; ++i)
-                    if (keys[i] < prev && keys[i] > best) best = keys[i];
+                    if (i < nepl && keys[i] < prev && keys[i] > best) best = keys[i];
                 for (int x = lane + 64 * EPL; x < n_el; x += 64) {
                     const int lt = x >> 4;
                     const float v = s_lm[(lt * rows + m) * 16 + (x & 15)];
@@ -1551,7 +1541,8 @@ __global__ void __launch_bounds__(PS_WG_THREADS, 1) gemm_kernel(const StepParams
     extern __shared__ __attribute__((aligned(256))) char smem[];
     uint4 wb[PS_U];
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    gemm_phase<WT, MT, PH>(P, blockIdx.x, wave, smem, wb, P.ph[PH].wpack, first_stream(P, PH, blockIdx.x, wave));
+    preload_weights(wb, first_stream(P, PH, blockIdx.x, wave), (threadIdx.x & 63) * 16);
+    gemm_phase<WT, MT, PH>(P, blockIdx.x, wave, smem, wb, P.ph[PH].wpack);
 }
 
 template <typename WT, int D>
@@ -1584,19 +1575,20 @@ __global__ void __launch_bounds__(PS_WG_THREADS, 1) fused_kernel(const StepParam
     uint4 wb[PS_U];
     stamp_wall(P, wg, 0);
     stamp(P, wg, 1);
-    gemm_phase<WT, MT, PH_QKV>(P, wg, wave, smem, wb, first_stream(P, PH_OPROJ, wg, wave), first_stream(P, PH_QKV, wg, wave));
+    preload_weights(wb, first_stream(P, PH_QKV, wg, wave), lane * 16);
+    gemm_phase<WT, MT, PH_QKV>(P, wg, wave, smem, wb, first_stream(P, PH_OPROJ, wg, wave));
     __syncthreads();
     stamp(P, wg, 32);
     attn_phase<WT, D>(P, wg, gridDim.x, wave, smem);
     __syncthreads();
     stamp(P, wg, 36);
-    gemm_phase<WT, MT, PH_OPROJ>(P, wg, wave, smem, wb, first_stream(P, PH_GATEUP, wg, wave), nullptr);
+    gemm_phase<WT, MT, PH_OPROJ>(P, wg, wave, smem, wb, first_stream(P, PH_GATEUP, wg, wave));
     __syncthreads();
-    gemm_phase<WT, MT, PH_GATEUP>(P, wg, wave, smem, wb, first_stream(P, PH_DOWN, wg, wave), nullptr);
+    gemm_phase<WT, MT, PH_GATEUP>(P, wg, wave, smem, wb, first_stream(P, PH_DOWN, wg, wave));
     __syncthreads();
-    gemm_phase<WT, MT, PH_DOWN>(P, wg, wave, smem, wb, first_stream(P, PH_LMHEAD, wg, wave), nullptr);
+    gemm_phase<WT, MT, PH_DOWN>(P, wg, wave, smem, wb, first_stream(P, PH_LMHEAD, wg, wave));
     __syncthreads();
-    gemm_phase<WT, MT, PH_LMHEAD>(P, wg, wave, smem, wb, P.ph[PH_QKV].wpack, nullptr);
+    gemm_phase<WT, MT, PH_LMHEAD>(P, wg, wave, smem, wb, P.ph[PH_QKV].wpack);
     __syncthreads();
     // output row m is merged by workgroup m mod gridDim.x
     stamp(P, wg, 40);
