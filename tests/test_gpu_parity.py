@@ -31,7 +31,7 @@ def _run_case(wl, kv_len=None, n_new=None, k=None, topk=None, all_rows=False, la
     w = inputs.make_weights(shape, wl.seed)
     inp = inputs.make_step_inputs(wl, kv_len=kv_len, n_new=n_new, k=k)
     d = _drafter(shape, w, max_batch=len(inp["kv_len"]), max_new=n_new,
-                 max_positions=int(max(inp["kv_len"])) + n_new + k, k_max=k)
+                 max_positions=int(max(inp["kv_len"])) + n_new + k, max_topk=max(8, topk), k_max=k)
     res = run_gpu_step(d, inp, n_new, k, topk, all_rows=all_rows)
     ref = oracle_step(shape, w, inp, n_new, k, topk, all_rows=all_rows)
     stats = compare_with_oracle(shape, res, ref, inp, n_new, k, topk)
@@ -70,6 +70,39 @@ def test_ragged_batch_many_rows_bf16():
     shape = small_shape("bf16", hidden=1024, n_heads=8, n_kv_heads=8, head_dim=128, ffn=2752, vocab=4000)
     wl = Workload("ragged", shape, batch=8, kv_len=(128, 2048, 777, 130, 1, 1500, 300, 64), n_new=1, k=5,
                   topk=8, seed=23)
+    _run_case(wl)
+
+
+def test_changing_shapes_on_one_context():
+    """Row layout, column tiles and K-slice plan change from step to step on ONE context: exchange-buffer
+    slots a step does not write must never look written to a later step (two alternating copies)."""
+    shape = small_shape("bf16", hidden=1024, n_heads=8, n_kv_heads=8, head_dim=128, ffn=2752, vocab=2069)
+    w = inputs.make_weights(shape, 31)
+    d = _drafter(shape, w, max_batch=8, max_new=3, max_positions=700, k_max=5)
+    seq = [(1, 1, 5, (100,)), (8, 1, 5, (128, 600, 77, 130, 1, 500, 300, 64)), (1, 1, 5, (100,)), (3, 2, 5, (5, 300, 129)),
+           (3, 2, 5, (5, 300, 129)), (8, 3, 5, (30, 31, 32, 33, 34, 35, 36, 37)), (2, 1, 0, (64, 65)), (1, 1, 5, (100,)),
+           (1, 3, 2, (257,)), (1, 1, 5, (100,))]
+    for step, (batch, n_new, k, kv) in enumerate(seq):
+        wl = Workload("shapes", shape, batch=batch, kv_len=kv, n_new=n_new, k=k, topk=4, seed=100 + step)
+        inp = inputs.make_step_inputs(wl, kv_len=kv, n_new=n_new, k=k)
+        res = run_gpu_step(d, inp, n_new, k, 4)
+        ref = oracle_step(shape, w, inp, n_new, k, 4)
+        print("step", step, (batch, n_new, k), compare_with_oracle(shape, res, ref, inp, n_new, k, 4), flush=True)
+    d.close()
+
+
+def test_maximum_rows_and_topk():
+    # 8 sequences x 8 rows = 64 activation rows (the most the library takes), top-32, all rows decoded
+    shape = small_shape("bf16", hidden=512, n_heads=8, n_kv_heads=4, head_dim=64, ffn=1376, vocab=3000)
+    wl = Workload("maxrows", shape, batch=8, kv_len=(9, 200, 63, 64, 65, 0, 127, 129), n_new=3, k=5, topk=32, seed=32)
+    _run_case(wl)
+    _run_case(wl, all_rows=True, topk=1, label="64 rows, all decoded, top-1")
+
+
+def test_very_long_sequence_many_key_blocks():
+    # 33000 keys = 258 attention blocks: more than one group of 256 blocks in the combination pass
+    shape = small_shape("bf16", hidden=256, n_heads=4, n_kv_heads=2, head_dim=64, ffn=704, vocab=1024)
+    wl = Workload("long", shape, batch=2, kv_len=(33000, 2100), n_new=1, k=4, topk=4, seed=33)
     _run_case(wl)
 
 
