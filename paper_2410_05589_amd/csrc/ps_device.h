@@ -156,22 +156,6 @@ __device__ __forceinline__ bool spin_again(const StepParams& P, int& spins) {
     }
     return true;
 }
-// one element / four elements, waiting until they carry this step's sequence number
-__device__ __forceinline__ float ll_wait1(const StepParams& P, rsrc_t r, unsigned i) {
-    int spins = 0;
-    for (;;) {
-        const u32x2 x = coh_ld8(r, i * 8);
-        if (__all(x[1] == P.seq) || !spin_again(P, spins)) return __uint_as_float(x[0]);
-    }
-}
-__device__ __forceinline__ f32x4 ll_wait4(const StepParams& P, rsrc_t r, unsigned i) {
-    int spins = 0;
-    for (;;) {
-        const LL4 x = ll_ld4(r, i);
-        if (__all(ll_ok(x, P.seq)) || !spin_again(P, spins)) return ll_val(x);
-    }
-}
-
 // ---- sentinel-coded exchange for the activation buffers (the bulk of the exchanged bytes, read
 // by every workgroup): plain fp32 values, "not written yet" is the bit pattern 0xFFFFFFFF (a NaN no
 // computation on finite inputs produces).  Each buffer exists twice; step n uses copy n & 1, and
@@ -179,10 +163,25 @@ __device__ __forceinline__ f32x4 ll_wait4(const StepParams& P, rsrc_t r, unsigne
 // copy the next step uses is clean again without a separate clearing pass.
 #define PS_SENT 0xFFFFFFFFu
 struct SxBuf { rsrc_t cur, alt; };
-__device__ __forceinline__ SxBuf sx_buf(const StepParams& P, const void* cur) {
+// The step's sequence number.  It lives in device memory (the kernel arguments of a replayed
+// graph launch never change): thread 0 of every workgroup reads the counter when the kernel
+// starts and leaves number = counter + 1 in LDS (step_begin); the last workgroup to do so
+// advances the counter for the next launch (step_end).
+#define PS_LDS_SEQ 16       // LDS bytes [0, 256) are reserved for this in every phase's layout
+typedef __attribute__((address_space(3))) unsigned lds_u32;
+__device__ __forceinline__ unsigned ps_seq() {
+    return __builtin_amdgcn_readfirstlane(*(const lds_u32*)(unsigned)PS_LDS_SEQ);
+}
+// Exchange buffers exist twice; P holds the addresses in copy 0, step n uses copy n & 1
+__device__ __forceinline__ const char* act_ptr(const StepParams& P, const void* copy0) {
+    return reinterpret_cast<const char*>(copy0) + (ps_seq() & 1u) * P.act_bytes;
+}
+__device__ __forceinline__ SxBuf sx_buf(const StepParams& P, const void* copy0) {
+    const unsigned par = ps_seq() & 1u;
+    const char* base = reinterpret_cast<const char*>(copy0);
     SxBuf b;
-    b.cur = make_rsrc(cur);
-    b.alt = make_rsrc(reinterpret_cast<const char*>(cur) + P.alt_delta);
+    b.cur = make_rsrc(base + par * P.act_bytes);
+    b.alt = make_rsrc(base + (1u - par) * P.act_bytes);
     return b;
 }
 __device__ __forceinline__ void sx_st4(const SxBuf& b, unsigned i, f32x4 v) {
@@ -551,7 +550,7 @@ template <typename WT, int MT>
 __device__ __forceinline__ void epilogue_down(const StepParams& P, int tau, int lane, f32x4 (&acc)[MT]) {
     const int c = lane & 15, q = lane >> 4;
     const int n = 16 * tau + 4 * q;
-    const rsrc_t ry = make_rsrc(P.y_buf);
+    const rsrc_t ry = make_rsrc(act_ptr(P, P.y_buf));
     const SxBuf ry2 = sx_buf(P, P.y2_buf);
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
@@ -597,9 +596,9 @@ __host__ __device__ inline int panel_row_stride(int panel_steps) {
     return len + ((64 - (len & 255)) + 256) % 256;
 }
 // LDS layout of a GEMM phase (bytes from the start of dynamic LDS)
-#define PS_LDS_SSQ 0        // [64 rows][8] partial sums of squares (RMSNorm)
-#define PS_LDS_ZERO 2048    // 64 zero bytes: B operand of unused MFMA columns
-#define PS_LDS_RED 2304     // [wavefronts][MT][64 lanes] f32x4: partial sums of wavefronts sharing a tile
+#define PS_LDS_SSQ 256      // [64 rows][8] partial sums of squares (RMSNorm); bytes [0, 256): see PS_LDS_SEQ
+#define PS_LDS_ZERO 2304    // 64 zero bytes: B operand of unused MFMA columns
+#define PS_LDS_RED 2560     // [wavefronts][MT][64 lanes] f32x4: partial sums of wavefronts sharing a tile
 __host__ __device__ inline int panel_offset(int mt) { return PS_LDS_RED + PS_WAVES * mt * 1024; }
 
 typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
@@ -635,7 +634,7 @@ __device__ __forceinline__ void stage_piece(const StepParams& P, const PhaseDesc
     const int wsub = wave & ((G2 >> 6) - 1);
     const int rows = D.rows, K = D.K, RS = D.rs, ld = D.src_ld;
     const bool norm = PH == PH_QKV || PH == PH_GATEUP || (PH == PH_LMHEAD && D.norm != 0);
-    const rsrc_t rs = make_rsrc(from_x ? P.x : (const void*)D.src), rmask = make_rsrc(from_x ? P.mask_emb : (const void*)D.src);
+    const rsrc_t rs = make_rsrc(from_x ? P.x : (const void*)act_ptr(P, D.src)), rmask = make_rsrc(P.mask_emb);
     for (int gc = 0; gc < G; gc += G2) {
         const int gi = gc + gi0;
         const bool gvalid = gi < G;
@@ -724,7 +723,7 @@ __device__ __forceinline__ void stage_piece(const StepParams& P, const PhaseDesc
 // whatever this wavefront streams next, or any readable address).
 template <typename WT, int MT, int PH>
 __device__ __forceinline__ void gemm_phase(const StepParams& P, int wg, int wave, char* smem, uint4 (&wb)[PS_U],
-                                           const char* after_wp) {
+                                           const char* after_wp, unsigned publish_seq = 0) {
     constexpr bool BF = Traits<WT>::BF;
     constexpr int ph = PH;
     constexpr bool sliceable = PH != PH_LMHEAD;   // see make_desc on the host
@@ -750,6 +749,7 @@ __device__ __forceinline__ void gemm_phase(const StepParams& P, int wg, int wave
     stamp(P, wg, 2 + ph * 6 + 0);
     if (j >= D.T) {                   // more workgroup columns than tiles: nothing to do in this phase
         preload_weights(wb, after_wp, lane16);
+        if (publish_seq) *(lds_u32*)(unsigned)PS_LDS_SEQ = publish_seq;
         return;
     }
     if (tid < 16) reinterpret_cast<uint32_t*>(s_zero)[tid] = 0u;
@@ -783,6 +783,7 @@ __device__ __forceinline__ void gemm_phase(const StepParams& P, int wg, int wave
             if (rd == 0 || D.npieces > 1) {   // a panel that fits as a whole is staged once
                 if (rd > 0 || pc > 0) __syncthreads();   // everyone is done with the previous piece
                 stage_piece<WT, PH>(P, D, wave, smem, s_pa, s_pb, g_lo * PS_U, ng * PS_U, pc == 0, rd == 0);
+                if (publish_seq && rd == 0 && pc == 0) *(lds_u32*)(unsigned)PS_LDS_SEQ = publish_seq;   // see step_read
                 __syncthreads();
                 if (rd == 0 && pc == 0) stamp(P, wg, 2 + ph * 6 + 1);
             }
@@ -861,7 +862,7 @@ __device__ __forceinline__ void gemm_phase(const StepParams& P, int wg, int wave
         // Sum over the K-slices.  Of the tiles of this workgroup column, slice s completes every S-th;
         // its wavefronts take one each, wait for all S parts (its own included) and add them in slice
         // order, so the result does not depend on timing.  Then the phase's epilogue.
-        const rsrc_t rf = make_rsrc(D.frag), rq = make_rsrc(D.ssq_frag);
+        const rsrc_t rf = make_rsrc(act_ptr(P, D.frag)), rq = make_rsrc(act_ptr(P, D.ssq_frag));
         const int ntl = D.rounds * SL;
         for (int lt = s + S * wave; lt < ntl; lt += S * PS_WAVES) {
             const int tau = tile_index(D, lt >> sl_log, lt & (SL - 1), j);
@@ -913,6 +914,7 @@ __device__ __forceinline__ void gemm_phase(const StepParams& P, int wg, int wave
         const int topk = P.topk;
         const rsrc_t rl = make_rsrc(P.lm_part);
         const unsigned stride = 2 + 2 * topk;   // tagged elements: max, sum exp, topk keys (low, high word)
+        const unsigned seq = ps_seq();
         for (int m = wave; m < rows; m += PS_WAVES) {
             constexpr int EPL = 8;   // elements per lane kept in registers (more: re-read from LDS)
             u64 keys[EPL];
@@ -935,7 +937,7 @@ __device__ __forceinline__ void gemm_phase(const StepParams& P, int wg, int wave
                 for (int x = lane; x < n_el; x += 64) se += expf(s_lm[((x >> 4) * rows + m) * 16 + (x & 15)] - mx);
             se = wave_sum(se);
             const unsigned obase = (unsigned)((j * rows + m) * stride);
-            if (lane < 2) ll_st1(rl, obase + lane, lane ? se : mx, P.seq);
+            if (lane < 2) ll_st1(rl, obase + lane, lane ? se : mx, seq);
             const int nepl = min(EPL, (n_el + 63) >> 6);   // registers per lane that hold elements
             u64 prev = ~0ull;   // keys are unique: the next winner is the largest key below the previous one
             for (int t = 0; t < topk; ++t) {
@@ -952,7 +954,7 @@ __device__ __forceinline__ void gemm_phase(const StepParams& P, int wg, int wave
                 }
                 best = wave_max_u64(best);
                 if (lane < 2)
-                    ll_st1(rl, obase + 2 + 2 * t + lane, __uint_as_float(lane ? (unsigned)(best >> 32) : (unsigned)best), P.seq);
+                    ll_st1(rl, obase + 2 + 2 * t + lane, __uint_as_float(lane ? (unsigned)(best >> 32) : (unsigned)best), seq);
                 prev = best ? best : 0;   // 0: list exhausted, every later entry is "none"
             }
         }
@@ -1033,7 +1035,7 @@ __device__ __forceinline__ void attn_load_k(const StepParams& P, const AttnItem&
 #pragma unroll
     for (int t = 0; t < STEPS; ++t) kreg[t] = ld16(krow + t * 64);
     if (key0 + 15 >= L && key0 < end) {
-        const rsrc_t rn = make_rsrc(P.kvnew);
+        const rsrc_t rn = make_rsrc(act_ptr(P, P.kvnew));
         const bool k_new = kpos >= L;
         const int pn = kpos < L ? L : (kpos < end ? kpos : end - 1);
         const unsigned kbase = (unsigned)(((size_t)(it.b * P.M + (pn - L)) * 2) * P.KVD + it.hk * D + kb * GE);
@@ -1101,7 +1103,7 @@ __device__ __forceinline__ void attn_issue_v(const StepParams& P, const AttnItem
     if (key0 + 15 >= L && key0 < end) {
         // rows written in this step: from the exchange buffer, as soon as the QKV phase has published
         // them; they are exactly representable in the storage type (they were rounded to it)
-        const rsrc_t rn = make_rsrc(P.kvnew);
+        const rsrc_t rn = make_rsrc(act_ptr(P, P.kvnew));
         float vx[16][DPL];
         int spins = 0;
         for (;;) {
@@ -1148,7 +1150,7 @@ __device__ __forceinline__ void attn_issue_q(const StepParams& P, const AttnItem
                                              u32x4 (&qx)[D / Traits<WT>::KSTEP][Traits<WT>::GE / 4]) {
     constexpr int GE = Traits<WT>::GE, KSTEP = Traits<WT>::KSTEP, NL = GE / 4, STEPS = D / KSTEP;
     const int c = lane & 15, kb = lane >> 4;
-    const rsrc_t rq = make_rsrc(P.q_buf);
+    const rsrc_t rq = make_rsrc(act_ptr(P, P.q_buf));
     const int rho = r0 + c < Ra ? r0 + c : Ra - 1;
     const int gi = row_seq(P, rho), i = rho - gi * P.M;
     const unsigned qbase = (unsigned)((size_t)(it.b * P.M + i) * P.QD + (it.hk * grp + gi) * D + kb * GE);
@@ -1176,6 +1178,7 @@ __device__ __forceinline__ void attn_phase(const StepParams& P, int wg, int nwg,
     float* sO = reinterpret_cast<float*>(smem + C::OFF_O);
     const rsrc_t racc = make_rsrc(P.attn_acc), rml = make_rsrc(P.attn_ml);
     const SxBuf ro = sx_buf(P, P.o_buf);
+    const unsigned seq = ps_seq();
 
     // The loads of a work item are requested while the previous item is still being computed: the
     // K rows and the first query rows right after the score MFMAs, the V rows right after P.V.
@@ -1304,12 +1307,12 @@ __device__ __forceinline__ void attn_phase(const StepParams& P, int wg, int nwg,
                     sx_st1(ro, (unsigned)((size_t)(b * P.M + i2) * P.QD + (hk * grp + gi2) * D + dd), o / l);
                 } else {
                     // partial (max, sum, unnormalised output) of this chunk, as tagged data
-                    ll_st1(racc, (unsigned)(((size_t)item * Ra + rho2) * D + dd), o, P.seq);
+                    ll_st1(racc, (unsigned)(((size_t)item * Ra + rho2) * D + dd), o, seq);
                     if (dd < 2) {
                         float mr = -INFINITY;
 #pragma unroll
                         for (int w = 0; w < PS_WAVES; ++w) mr = fmaxf(mr, sM[w * 16 + rr]);
-                        ll_st1(rml, (unsigned)(((size_t)item * Ra + rho2) * 2 + dd), dd ? l : mr, P.seq);
+                        ll_st1(rml, (unsigned)(((size_t)item * Ra + rho2) * 2 + dd), dd ? l : mr, seq);
                     }
                 }
             }
@@ -1359,7 +1362,7 @@ __device__ __forceinline__ void attn_phase(const StepParams& P, int wg, int nwg,
                     }
                     unsigned bad = 0;
 #pragma unroll
-                    for (int q = 0; q < GRP / 64; ++q) bad |= (unsigned)(ml[q][1] != P.seq) | (unsigned)(ml[q][3] != P.seq);
+                    for (int q = 0; q < GRP / 64; ++q) bad |= (unsigned)(ml[q][1] != seq) | (unsigned)(ml[q][3] != seq);
                     if (__all(!bad) || !spin_again(P, spins)) break;
                 }
                 float mloc = -INFINITY;
@@ -1392,7 +1395,7 @@ __device__ __forceinline__ void attn_phase(const StepParams& P, int wg, int nwg,
                     }
                     unsigned bad = 0;
 #pragma unroll
-                    for (int i = 0; i < CB; ++i) bad |= (unsigned)(av[i][1] != P.seq) | (unsigned)(av[i][3] != P.seq);
+                    for (int i = 0; i < CB; ++i) bad |= (unsigned)(av[i][1] != seq) | (unsigned)(av[i][3] != seq);
                     if (__all(!bad || !active) || !spin_again(P, spins)) break;
                 }
 #pragma unroll
@@ -1442,6 +1445,7 @@ __device__ __forceinline__ void lm_merge_row(const StepParams& P, int m, int wav
     const unsigned stride = 2 + 2 * topk;                  // tagged elements per (workgroup, row)
     const unsigned pstride = (unsigned)P.Rtot * stride;
     const rsrc_t rl = make_rsrc(P.lm_part);
+    const unsigned seq = ps_seq();
     u64* sk = reinterpret_cast<u64*>(scratch);                              // [waves][PS_MAX_TOPK] keys
     float* sf = reinterpret_cast<float*>(scratch + PS_WAVES * PS_MAX_TOPK * 8);   // [waves] max, [waves] sum
     const bool mine = tid < nparts;                        // host: nparts <= PS_WG_THREADS
@@ -1465,9 +1469,9 @@ __device__ __forceinline__ void lm_merge_row(const StepParams& P, int m, int wav
                 const int t = t0 + i < topk ? t0 + i : topk - 1;
                 kr[i] = coh_ld16(rl, base + (2 + 2 * t) * 8);   // {low, tag, high, tag}
             }
-            unsigned bad = (unsigned)(hd[1] != P.seq) | (unsigned)(hd[3] != P.seq);   // all loads first, then all checks
+            unsigned bad = (unsigned)(hd[1] != seq) | (unsigned)(hd[3] != seq);   // all loads first, then all checks
 #pragma unroll
-            for (int i = 0; i < KB; ++i) bad |= (unsigned)(kr[i][1] != P.seq) | (unsigned)(kr[i][3] != P.seq);
+            for (int i = 0; i < KB; ++i) bad |= (unsigned)(kr[i][1] != seq) | (unsigned)(kr[i][3] != seq);
             if (__all(!bad || !mine) || !spin_again(P, spins)) break;
         }
         if (t0 == 0 && mine) { pmax = __uint_as_float(hd[0]); psum = __uint_as_float(hd[2]); }
@@ -1536,11 +1540,43 @@ __device__ __forceinline__ void lm_merge_row(const StepParams& P, int m, int wav
 // ------------------------------------------------------------------------------------------
 // kernels
 // ------------------------------------------------------------------------------------------
+// Every kernel starts by reading the step counter: the step's number goes to LDS.  In the kernel
+// that ends a step (count = true) every workgroup also takes a ticket; the workgroup with the
+// last ticket - by then all of them have read the counter - advances it in step_end.  The ticket
+// is only looked at when the kernel ends, so its round trip costs nothing.  step_read only
+// requests (thread 0 returns the number, the others 0); the persistent kernel hands the number to
+// its first phase, which stores it to LDS just before its first barrier: the first phase reads
+// only the step's inputs, so the counter's round trip hides behind the first activation loads.
+__device__ __forceinline__ unsigned step_read(const StepParams& P, bool count, unsigned& ticket) {
+    unsigned seq = 0;
+    ticket = 0xFFFFFFFFu;
+    if (threadIdx.x == 0) {
+        seq = ld_agent_u32(P.step_ctr) + 1u;
+        if (seq == 0u) seq = 1u;   // 0 is what cleared exchange buffers hold
+        if (count) ticket = __hip_atomic_fetch_add(P.done_ctr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    return seq;
+}
+__device__ __forceinline__ unsigned step_begin(const StepParams& P, bool count) {
+    unsigned ticket;
+    const unsigned seq = step_read(P, count, ticket);
+    if (threadIdx.x == 0) *(lds_u32*)(unsigned)PS_LDS_SEQ = seq;
+    __syncthreads();
+    return ticket;
+}
+__device__ __forceinline__ void step_end(const StepParams& P, unsigned ticket, unsigned nwg) {
+    if (threadIdx.x == 0 && ticket == nwg - 1u) {
+        st_agent_u32(P.done_ctr, 0u);
+        st_agent_u32(P.step_ctr, ps_seq());
+    }
+}
+
 template <typename WT, int MT, int PH>
 __global__ void __launch_bounds__(PS_WG_THREADS, 1) gemm_kernel(const StepParams P) {
     extern __shared__ __attribute__((aligned(256))) char smem[];
     uint4 wb[PS_U];
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    step_begin(P, false);
     preload_weights(wb, first_stream(P, PH, blockIdx.x, wave), (threadIdx.x & 63) * 16);
     gemm_phase<WT, MT, PH>(P, blockIdx.x, wave, smem, wb, P.ph[PH].wpack);
 }
@@ -1548,12 +1584,15 @@ __global__ void __launch_bounds__(PS_WG_THREADS, 1) gemm_kernel(const StepParams
 template <typename WT, int D>
 __global__ void __launch_bounds__(PS_WG_THREADS) attn_kernel(const StepParams P) {
     extern __shared__ __attribute__((aligned(256))) char smem[];
+    step_begin(P, false);
     attn_phase<WT, D>(P, blockIdx.x, gridDim.x, __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), smem);
 }
 
 static __global__ void __launch_bounds__(PS_WG_THREADS) lm_merge_kernel(const StepParams P) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
-    lm_merge_row(P, blockIdx.x, __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), smem);
+    const unsigned ticket = step_begin(P, true);   // the last kernel of a step in this mode
+    lm_merge_row(P, blockIdx.x, __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), smem + 256);
+    step_end(P, ticket, gridDim.x);
 }
 
 static __global__ void __launch_bounds__(256) probs_kernel(const StepParams P) {
@@ -1575,13 +1614,18 @@ __global__ void __launch_bounds__(PS_WG_THREADS, 1) fused_kernel(const StepParam
     uint4 wb[PS_U];
     stamp_wall(P, wg, 0);
     stamp(P, wg, 1);
+    unsigned ticket;
+    const unsigned my_seq = step_read(P, false, ticket);
     preload_weights(wb, first_stream(P, PH_QKV, wg, wave), lane * 16);
-    gemm_phase<WT, MT, PH_QKV>(P, wg, wave, smem, wb, first_stream(P, PH_OPROJ, wg, wave));
+    gemm_phase<WT, MT, PH_QKV>(P, wg, wave, smem, wb, first_stream(P, PH_OPROJ, wg, wave), my_seq);
     __syncthreads();
     stamp(P, wg, 32);
     attn_phase<WT, D>(P, wg, gridDim.x, wave, smem);
     __syncthreads();
     stamp(P, wg, 36);
+    // the ticket (see step_read) is taken here: the next thing this workgroup does is wait for the
+    // attention outputs of all the others, so the atomic's round trip delays nothing
+    if (threadIdx.x == 0) ticket = __hip_atomic_fetch_add(P.done_ctr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     gemm_phase<WT, MT, PH_OPROJ>(P, wg, wave, smem, wb, first_stream(P, PH_GATEUP, wg, wave));
     __syncthreads();
     gemm_phase<WT, MT, PH_GATEUP>(P, wg, wave, smem, wb, first_stream(P, PH_DOWN, wg, wave));
@@ -1593,6 +1637,7 @@ __global__ void __launch_bounds__(PS_WG_THREADS, 1) fused_kernel(const StepParam
     // output row m is merged by workgroup m mod gridDim.x
     stamp(P, wg, 40);
     for (int m = wg; m < P.Rtot; m += gridDim.x) lm_merge_row(P, m, wave, smem + 256);
+    step_end(P, ticket, gridDim.x);
     stamp(P, wg, 62);
     stamp_wall(P, wg, 63);
     flush_stamps(P, wg);

@@ -40,7 +40,6 @@ struct ps_draft_ctx {
     // workspace carve-up (device pointers)
     float2* rope;
     float *q_buf, *o_buf, *y_buf, *u_buf, *y2_buf, *kvnew, *attn_acc, *attn_ml, *lm_part, *logits_ws;
-    unsigned seq;                     // sequence number of the last enqueued step
     size_t exch_begin, exch_end;      // workspace range of the tagged exchange buffers (cleared at init)
     char* act_base;                   // two copies of the activation buffers, act_bytes each
     size_t act_bytes;
@@ -154,7 +153,7 @@ static WsLayout ws_layout(const ps_draft_config* c) {
     L.lm_part = take((size_t)PS_MAX_WG * rows * (2 + 2 * c->max_topk) * 8 + 64);
     L.exch_end = off;
     L.n_counters = 0;
-    L.counters = take(64);   // error flag
+    L.counters = take(64);   // [0] error flag, [1] steps completed, [2] tickets of the running kernel
     L.logits_ws = take(rows * c->vocab * 4);
     L.total = off;
     return L;
@@ -252,7 +251,6 @@ extern "C" int ps_draft_init(ps_draft_ctx** out, const ps_draft_config* config, 
     ctx->last_frag_sig = 0; ctx->act_small = L.act_small;
     ctx->attn_acc = (float*)(base + L.attn_acc);
     ctx->attn_ml = (float*)(base + L.attn_ml);
-    ctx->seq = 0;
     ctx->exch_begin = L.exch_begin; ctx->exch_end = L.exch_end;
     ctx->counters = (int*)(base + L.counters);
     ctx->n_counters = L.n_counters;
@@ -328,7 +326,7 @@ int panel_row_stride_host(int panel_steps) {
     const int len = panel_steps * 64;
     return len + ((64 - (len & 255)) + 256) % 256;
 }
-static int panel_offset_host(int mt) { return 2304 + PS_WAVES * mt * 1024; }   // see PS_LDS_RED in ps_device.h
+static int panel_offset_host(int mt) { return 2560 + PS_WAVES * mt * 1024; }   // see PS_LDS_RED in ps_device.h
 
 // Cuts one GEMM phase: T tiles x Kt steps (K elements) over nwg workgroups of PS_WAVES wavefronts.
 //
@@ -443,23 +441,24 @@ extern "C" int ps_draft_step(ps_draft_ctx* ctx, const ps_draft_step_args* a, voi
     P.m_magic = 0xFFFFFFFFu / (unsigned)M + 1u;   // ceil(2^32 / M); M = 1 is handled on the device
     P.tph_log = c.head_dim == 128 ? 3 : 2;
     P.error_flag = ctx->counters;
-    ctx->seq = ctx->seq >= 0xFFFFFFF0u ? 1u : ctx->seq + 1u;   // 0 = cleared buffers
-    P.seq = ctx->seq;
-    char* act_cur;
-    {   // the activation copy of this step; the other one is reset while this one is written
-        const int par = (int)(P.seq & 1u);
-        char* cur = act_cur = ctx->act_base + (size_t)par * ctx->act_bytes;
-        P.q_buf = (float*)(cur + ctx->off_q); P.o_buf = (float*)(cur + ctx->off_o); P.y_buf = (float*)(cur + ctx->off_y);
-        P.u_buf = (float*)(cur + ctx->off_u); P.y2_buf = (float*)(cur + ctx->off_y2); P.kvnew = (float*)(cur + ctx->off_kvnew);
-        P.alt_delta = par ? -(long long)ctx->act_bytes : (long long)ctx->act_bytes;
-        // a step only resets the elements it writes: when the row layout changes, elements the previous
-        // step did not touch could still look written, so this step's copy is cleared first (the part
-        // whose slots depend on the rows here; the K-slice fragments further down, once the plan is known)
-        if (ctx->last_shape[0] != a->batch || ctx->last_shape[1] != a->n_new || ctx->last_shape[2] != a->k) {
-            if (ctx->last_shape[0] >= 0 &&
-                !hip_ok(hipMemsetAsync(cur, 0xFF, ctx->act_small, (hipStream_t)stream), "hipMemsetAsync")) return PS_ERR_DEVICE;
-            ctx->last_shape[0] = a->batch; ctx->last_shape[1] = a->n_new; ctx->last_shape[2] = a->k;
-        }
+    // The step's sequence number is kept on the device (ctx->counters[1], advanced by the kernels), so a
+    // captured launch can be replayed.  The exchange buffers exist twice, step n uses copy n & 1; the
+    // pointers here are those of copy 0.
+    P.step_ctr = (unsigned*)ctx->counters + 1;
+    P.done_ctr = (unsigned*)ctx->counters + 2;
+    char* const act0 = ctx->act_base;
+    P.act_bytes = (long long)ctx->act_bytes;
+    P.q_buf = (float*)(act0 + ctx->off_q); P.o_buf = (float*)(act0 + ctx->off_o); P.y_buf = (float*)(act0 + ctx->off_y);
+    P.u_buf = (float*)(act0 + ctx->off_u); P.y2_buf = (float*)(act0 + ctx->off_y2); P.kvnew = (float*)(act0 + ctx->off_kvnew);
+    // A step only resets the elements it writes: when the row layout changes, elements the previous
+    // step did not touch could still look written, so the part of both copies whose slots depend on the
+    // rows is cleared first (the K-slice fragments further down, once the plan is known).
+    if (ctx->last_shape[0] != a->batch || ctx->last_shape[1] != a->n_new || ctx->last_shape[2] != a->k) {
+        if (ctx->last_shape[0] >= 0)
+            for (int cp = 0; cp < 2; ++cp)
+                if (!hip_ok(hipMemsetAsync(act0 + (size_t)cp * ctx->act_bytes, 0xFF, ctx->act_small, (hipStream_t)stream), "hipMemsetAsync"))
+                    return PS_ERR_DEVICE;
+        ctx->last_shape[0] = a->batch; ctx->last_shape[1] = a->n_new; ctx->last_shape[2] = a->k;
     }
     P.logits_store = a->logits ? a->logits : (a->probs ? ctx->logits_ws : nullptr);
     P.top_ids = a->top_ids; P.top_p = a->top_p; P.lse = a->lse; P.probs = a->probs; P.hidden_out = a->hidden_out;
@@ -493,16 +492,18 @@ extern "C" int ps_draft_step(ps_draft_ctx* ctx, const ps_draft_step_args* a, voi
         if (!make_desc(&P.ph[ph], ph, T[ph], Kt[ph], K[ph], rows, mt, bf, nwg, ctx->plan_override[ph], ctx->lds_limit))
             return PS_ERR_UNSUPPORTED;
         P.ph[ph].wpack = ctx->wpack[ph];
-        P.ph[ph].frag = (float*)(act_cur + ctx->off_frag[ph]);
-        P.ph[ph].ssq_frag = (float*)(act_cur + ctx->off_ssqf[ph]);
+        P.ph[ph].frag = (float*)(ctx->act_base + ctx->off_frag[ph]);
+        P.ph[ph].ssq_frag = (float*)(ctx->act_base + ctx->off_ssqf[ph]);
     }
     {   // which fragment slots a step uses depends on the column tiles and the K-slices of each phase
         unsigned sig = (unsigned)((P.Mtot + 15) / 16);
         for (int ph = 0; ph < PH_COUNT; ++ph) sig = sig * 8u + (unsigned)P.ph[ph].s_log + 1u;
         if (sig != ctx->last_frag_sig) {
-            if (ctx->last_frag_sig != 0 &&
-                !hip_ok(hipMemsetAsync(act_cur + ctx->act_small, 0xFF, ctx->act_bytes - ctx->act_small, (hipStream_t)stream), "hipMemsetAsync"))
-                return PS_ERR_DEVICE;
+            if (ctx->last_frag_sig != 0)
+                for (int cp = 0; cp < 2; ++cp)
+                    if (!hip_ok(hipMemsetAsync(ctx->act_base + (size_t)cp * ctx->act_bytes + ctx->act_small, 0xFF,
+                                               ctx->act_bytes - ctx->act_small, (hipStream_t)stream), "hipMemsetAsync"))
+                        return PS_ERR_DEVICE;
             ctx->last_frag_sig = sig;
         }
     }

@@ -77,7 +77,7 @@ static hipError_t launch_multi(const StepParams& P, hipStream_t stream, hipEvent
     if ((e = gemm(PH_GATEUP, mt_all)) != hipSuccess) return e;
     if ((e = gemm(PH_DOWN, mt_all)) != hipSuccess) return e;
     if ((e = gemm(PH_LMHEAD, mt_lm)) != hipSuccess) return e;
-    hipLaunchKernelGGL(lm_merge_kernel, dim3(P.Rtot), dim3(PS_WG_THREADS), PS_MERGE_BYTES, stream, P);
+    hipLaunchKernelGGL(lm_merge_kernel, dim3(P.Rtot), dim3(PS_WG_THREADS), PS_MERGE_BYTES + 256, stream, P);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     return mark();
 }

@@ -61,7 +61,6 @@ struct StepParams {
     int H, nq, nkv, d, F, V, QD, KVD;
     int B, n_new, k, M, Mtot, R, Rtot, all_rows, topk;
     int final_norm, max_positions;
-    unsigned seq;      // sequence number of this step, tags every value exchanged between workgroups
     float eps, inv_sqrt_d;
     // weights and step inputs (config dtype)
     const void *g_in, *wq, *wk, *wv, *wo, *g_post, *w_gate, *w_up, *w_down, *g_final, *w_lm, *mask_emb;
@@ -69,11 +68,12 @@ struct StepParams {
     void *kc, *vc;
     // workspace
     const float2* rope; // [max_positions][d/2] (cos, sin)
-    // Activations between phases: plain fp32, 0xFFFFFFFF = not written yet; the copy for this step
-    // (two copies alternate), the other copy is alt_delta bytes away.
+    // Activations between phases: plain fp32, 0xFFFFFFFF = not written yet.  Two copies alternate; the
+    // pointers are those of copy 0, step n uses copy n & 1.
     float *q_buf, *o_buf, *y_buf, *u_buf, *y2_buf;   // [Mtot][QD], [Mtot][QD], [Mtot][H], [Mtot][F], [Mtot][H]
     float* kvnew;      // [Mtot][2][KVD] this step's K and V rows as stored in the cache
-    long long alt_delta;
+    long long act_bytes;   // distance between the two copies
+    unsigned *step_ctr, *done_ctr;   // steps completed so far; tickets of the running kernel (see step_begin)
     // Buffers below hold 8-byte units {value, tag}: element counts.
     float* attn_acc;   // [items][g*M][d] unnormalised partial outputs
     float* attn_ml;    // [items][g*M][2] (running max, sum of exponentials)

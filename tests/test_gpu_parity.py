@@ -151,6 +151,50 @@ def test_repeated_steps_are_bitwise_identical():
     d.close()
 
 
+def test_step_replayed_from_a_graph():
+    """A captured ps_draft_step can be replayed: the step's sequence number lives on the device.  Replays
+    alternate with eager steps of the same context and with new inputs written into the captured buffers;
+    every replay is compared with the oracle."""
+    import torch
+    shape = small_shape("bf16", vocab=2069)
+    wl = Workload("graph", shape, batch=2, kv_len=(200, 70), n_new=1, k=5, topk=8, seed=41)
+    w = inputs.make_weights(shape, wl.seed)
+    d = _drafter(shape, w, max_batch=2, max_new=1, max_positions=300, k_max=5)
+    inp0 = inputs.make_step_inputs(wl)
+    dt = shape.dtype
+    x = B.to_device(inp0["x"], dt)
+    kc = B.to_device(inp0["k_cache"], dt)
+    vc = B.to_device(inp0["v_cache"], dt)
+    outs = d.alloc_outputs(2, 1, 5, 8, logits=True, probs=True, hidden=True)
+    args = d.make_args(x, kc, vc, inp0["kv_offsets"], inp0["kv_len"], 1, 5, 8, outs)
+    d.step(args)                               # eager warm-up (first use of the context)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            d.step(args, stream=side)
+    torch.cuda.synchronize()
+    for rep in range(5):
+        wl_r = Workload("graph", shape, batch=2, kv_len=(200, 70), n_new=1, k=5, topk=8, seed=50 + rep)
+        inp = inputs.make_step_inputs(wl_r)
+        x.copy_(B.to_device(inp["x"], dt)); kc.copy_(B.to_device(inp["k_cache"], dt)); vc.copy_(B.to_device(inp["v_cache"], dt))
+        for t in outs.values():
+            t.fill_(-12345) if t.dtype != torch.int32 else t.fill_(-7)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        res = {n: t.cpu().numpy() for n, t in outs.items()}
+        res["k_cache"] = B.from_device(kc); res["v_cache"] = B.from_device(vc)
+        ref = oracle_step(shape, w, inp, 1, 5, 8)
+        print("replay", rep, compare_with_oracle(shape, res, ref, inp, 1, 5, 8), flush=True)
+        if rep % 2 == 0:                       # an eager step of the same context in between
+            other = run_gpu_step(d, inp0, 1, 5, 8)
+            ref0 = oracle_step(shape, w, inp0, 1, 5, 8)
+            compare_with_oracle(shape, other, ref0, inp0, 1, 5, 8)
+    d.close()
+
+
 def test_optional_outputs_may_be_null():
     shape = small_shape("bf16")
     wl = Workload("opt", shape, batch=1, kv_len=(50,), n_new=1, k=3, topk=4, seed=27)
