@@ -247,17 +247,18 @@ __device__ __forceinline__ float wave_sum(float v) {
 #undef PS_C
     return __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(v), 63));
 }
-__device__ __forceinline__ float wave_max(float v) {
-#define PS_C(CTRL, RM) { const float o = __uint_as_float(dpp_u32<CTRL, RM>(__float_as_uint(v), __float_as_uint(v))); v = fmaxf(v, o); }
-    PS_DPP_STEPS(PS_C)
-#undef PS_C
-    return __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(v), 63));
-}
 __device__ __forceinline__ unsigned wave_max_u32(unsigned v) {
-#define PS_C(CTRL, RM) { const unsigned o = dpp_u32<CTRL, RM>(v, v); v = o > v ? o : v; }
+#define PS_C(CTRL, RM) { const unsigned o = dpp_u32<CTRL, RM>(0u, v); v = o > v ? o : v; }
     PS_DPP_STEPS(PS_C)
 #undef PS_C
     return __builtin_amdgcn_readlane(v, 63);
+}
+// float maximum through the order-preserving map to unsigned (finite values and infinities): the
+// unsigned reduction folds each lane exchange into its max instruction, the float one does not
+__device__ __forceinline__ float wave_max(float v) {
+    const unsigned u = __float_as_uint(v);
+    const unsigned m = wave_max_u32(u ^ ((u >> 31) ? 0xFFFFFFFFu : 0x80000000u));
+    return __uint_as_float(m ^ ((m >> 31) ? 0x80000000u : 0xFFFFFFFFu));
 }
 // maximum of 64-bit keys as two 32-bit reductions: the high words first, then the low words of
 // the lanes that hold the winning high word
@@ -986,7 +987,9 @@ __global__ void __launch_bounds__(256) pack_kernel(const StepParams P, int T, in
 // 0 .. kv_len[b] + i (its own and earlier rows of this step included; Algorithm 1: distribution
 // j is conditioned on [MASK]_1..j only).
 //
-// Each wavefront takes 16 keys of the chunk.  Scores are one MFMA tile per 16 query rows: the
+// Each wavefront takes NK groups of 16 keys of the chunk (CH = 128 NK keys; NK = PS_ATTN_NK = 1:
+// two groups per wavefront were measured to be no faster, and their registers do not fit beside the
+// weight loads the persistent kernel keeps in flight).  Scores are one MFMA tile per 16 keys and 16 query rows: the
 // keys' K rows are the 16-row operand, loaded straight from the cache in its storage type; the
 // query rows (fp32, split into bf16 high + low parts like every activation) are the 16-column
 // operand.  The row maxima of the eight wavefronts meet in LDS, so all of them exponentiate
@@ -996,22 +999,26 @@ __global__ void __launch_bounds__(256) pack_kernel(const StepParams P, int T, in
 // Keys written in this very step come, exactly as stored in the cache, from the exchange buffer
 // the QKV epilogue fills.
 // ------------------------------------------------------------------------------------------
-template <typename WT, int D> struct AttnCfg {
-    static constexpr int CH = 16 * PS_WAVES;
+template <typename WT, int D, int NK> struct AttnCfg {
+    static constexpr int CH = PS_ATTN_KEYS * NK;
+    static constexpr int CH_LOG = PS_ATTN_KEYS_LOG + (NK == 2 ? 1 : 0);
     static constexpr int OFF_M = 256;                                // [waves][16] row maxima
     static constexpr int OFF_L = OFF_M + PS_WAVES * 16 * 4;          // [waves][16] row sums
-    static constexpr int OFF_P = OFF_L + PS_WAVES * 16 * 4;          // [waves][16 rows][16 keys]
-    static constexpr int OFF_O = OFF_P + PS_WAVES * 16 * 16 * 4;     // [waves][16 rows][D]
-    static constexpr int LDS = OFF_O + PS_WAVES * 16 * D * 4;
+    static constexpr int OFF_P = OFF_L + PS_WAVES * 16 * 4;          // [waves][NK][16 rows][16 keys]
+    static constexpr int OFF_O = OFF_P + PS_WAVES * NK * 16 * 16 * 4;   // [waves][16 rows][D]
+    static constexpr int OFF_Q = OFF_O + PS_WAVES * 16 * D * 4;      // 16 query rows as MFMA operands: [step][hi, lo][64 lanes] x 16 B
+    static constexpr int LDS = OFF_Q + 16 * D * 4;
+    static_assert(NK == 1 || NK == 2, "NK");
+    static_assert(PS_ATTN_KEYS == 16 * PS_WAVES && LDS == ps_attn_lds_bytes(D, NK), "host and device agree on the layout");
 };
 
 // One attention work item: sequence b, kv head hk, key block ch of nch; L = valid cache rows
 struct AttnItem { int b, hk, ch, nch, L; };
-__device__ __forceinline__ AttnItem attn_decode(const StepParams& P, int item, int CH) {
+__device__ __forceinline__ AttnItem attn_decode(const StepParams& P, int item, int ch_log) {
     AttnItem it;
     int b = 0, rem = item, nch = 0;
     for (;; ++b) {
-        nch = (P.kv_len[b] + P.M + CH - 1) / CH;
+        nch = (P.kv_len[b] + P.M + (1 << ch_log) - 1) >> ch_log;
         if (rem < nch * P.nkv) break;
         rem -= nch * P.nkv;
     }
@@ -1024,7 +1031,7 @@ __device__ __forceinline__ AttnItem attn_decode(const StepParams& P, int item, i
 // written in this step are taken from the exchange buffer once the QKV phase has published them.
 template <typename WT, int D>
 __device__ __forceinline__ void attn_load_k(const StepParams& P, const AttnItem& it, int key0, int lane,
-                                            uint4 (&kreg)[D / Traits<WT>::KSTEP]) {
+                                            uint4 (&kreg)[D / Traits<WT>::KSTEP], bool with_new = true) {
     constexpr bool BF = Traits<WT>::BF;
     constexpr int ESZ = Traits<WT>::ESZ, GE = Traits<WT>::GE, KSTEP = Traits<WT>::KSTEP, NL = GE / 4, STEPS = D / KSTEP;
     const int c = lane & 15, kb = lane >> 4;
@@ -1034,7 +1041,7 @@ __device__ __forceinline__ void attn_load_k(const StepParams& P, const AttnItem&
     const char* krow = (const char*)P.kc + (((size_t)P.kv_off[it.b] + pc) * P.nkv + it.hk) * D * ESZ + kb * 16;
 #pragma unroll
     for (int t = 0; t < STEPS; ++t) kreg[t] = ld16(krow + t * 64);
-    if (key0 + 15 >= L && key0 < end) {
+    if (with_new && key0 + 15 >= L && key0 < end) {
         const rsrc_t rn = make_rsrc(act_ptr(P, P.kvnew));
         const bool k_new = kpos >= L;
         const int pn = kpos < L ? L : (kpos < end ? kpos : end - 1);
@@ -1089,7 +1096,7 @@ __device__ __forceinline__ void narrow_v(const float* in, float& u) { u = in[0];
 
 template <typename WT, int D>
 __device__ __forceinline__ void attn_issue_v(const StepParams& P, const AttnItem& it, int key0, int lane,
-                                             typename VRaw<WT, D / 64>::type (&vraw)[16]) {
+                                             typename VRaw<WT, D / 64>::type (&vraw)[16], bool with_new = true) {
     constexpr int ESZ = Traits<WT>::ESZ, DPL = D / 64;
     typedef typename VRaw<WT, DPL>::type raw_t;
     const int L = it.L, end = L + P.M;
@@ -1100,7 +1107,7 @@ __device__ __forceinline__ void attn_issue_v(const StepParams& P, const AttnItem
         const int pc = pos < L ? pos : (L > 0 ? L - 1 : 0);
         vraw[kk] = *reinterpret_cast<const raw_t*>((const char*)P.vc + ((cache_row0 + (size_t)pc * P.nkv) * D + DPL * lane) * ESZ);
     }
-    if (key0 + 15 >= L && key0 < end) {
+    if (with_new && key0 + 15 >= L && key0 < end) {
         // rows written in this step: from the exchange buffer, as soon as the QKV phase has published
         // them; they are exactly representable in the storage type (they were rounded to it)
         const rsrc_t rn = make_rsrc(act_ptr(P, P.kvnew));
@@ -1143,28 +1150,55 @@ __device__ __forceinline__ void attn_finish_v(const StepParams& P, const AttnIte
         }
     }
 }
-// Requests the query rows r0 .. r0 + 15 of the item as the 16-column operand (lane (c, kb) holds
-// row r0 + c) without waiting for them
+// The 16 query rows r0 .. r0 + 15 of an item are the same for all wavefronts: thread (row, group of
+// 4 columns) requests its 16 bytes (attn_issue_q, no wait), and once they have arrived puts them
+// into LDS as the 16-column MFMA operand (attn_store_q; bf16: split into high and low parts): lane
+// (c, kb) of step t finds row r0 + c, elements [t KSTEP + kb GE, + GE) at ((t [* 2 + lo]) * 64 + lane) * 16.
 template <typename WT, int D>
-__device__ __forceinline__ void attn_issue_q(const StepParams& P, const AttnItem& it, int r0, int Ra, int grp, int lane,
-                                             u32x4 (&qx)[D / Traits<WT>::KSTEP][Traits<WT>::GE / 4]) {
-    constexpr int GE = Traits<WT>::GE, KSTEP = Traits<WT>::KSTEP, NL = GE / 4, STEPS = D / KSTEP;
-    const int c = lane & 15, kb = lane >> 4;
+__device__ __forceinline__ u32x4 attn_issue_q(const StepParams& P, const AttnItem& it, int r0, int Ra, int grp, int tid) {
+    constexpr int GPR = D / 4;                       // 16-byte groups per row
+    const int r = tid / GPR < 16 ? tid / GPR : 15, g = tid % GPR;
     const rsrc_t rq = make_rsrc(act_ptr(P, P.q_buf));
-    const int rho = r0 + c < Ra ? r0 + c : Ra - 1;
+    const int rho = r0 + r < Ra ? r0 + r : Ra - 1;
     const int gi = row_seq(P, rho), i = rho - gi * P.M;
-    const unsigned qbase = (unsigned)((size_t)(it.b * P.M + i) * P.QD + (it.hk * grp + gi) * D + kb * GE);
-#pragma unroll
-    for (int t = 0; t < STEPS; ++t)
-#pragma unroll
-        for (int h = 0; h < NL; ++h) qx[t][h] = coh_ld16(rq, (qbase + t * KSTEP + 4 * h) * 4);
+    return coh_ld16(rq, (unsigned)((size_t)(it.b * P.M + i) * P.QD + (it.hk * grp + gi) * D + 4 * g) * 4);
+}
+template <typename WT, int D>
+__device__ __forceinline__ void attn_store_q(char* sq, int tid, u32x4 x) {
+    constexpr int GPR = D / 4;
+    if (tid >= 16 * GPR) return;
+    const int r = tid / GPR, e0 = 4 * (tid % GPR);
+    if constexpr (Traits<WT>::BF) {
+        const int t = e0 >> 5, kb = (e0 & 31) >> 3, half = (e0 & 7) >> 2;
+        const float f0 = __uint_as_float(x[0]), f1 = __uint_as_float(x[1]), f2 = __uint_as_float(x[2]), f3 = __uint_as_float(x[3]);
+        const unsigned h01 = pack_bf16x2(f0, f1), h23 = pack_bf16x2(f2, f3);
+        const unsigned l01 = pack_bf16x2(f0 - __uint_as_float(h01 << 16), f1 - __uint_as_float(h01 & 0xFFFF0000u));
+        const unsigned l23 = pack_bf16x2(f2 - __uint_as_float(h23 << 16), f3 - __uint_as_float(h23 & 0xFFFF0000u));
+        char* p = sq + ((2 * t * 64) + kb * 16 + r) * 16 + half * 8;
+        *reinterpret_cast<uint2*>(p) = make_uint2(h01, h23);
+        *reinterpret_cast<uint2*>(p + 64 * 16) = make_uint2(l01, l23);
+    } else {
+        const int t = e0 >> 4, kb = (e0 & 15) >> 2;
+        *reinterpret_cast<uint4*>(sq + (t * 64 + kb * 16 + r) * 16) = make_uint4(x[0], x[1], x[2], x[3]);
+    }
 }
 
+// qx: the rows requested earlier with attn_issue_q(it, r0)
 template <typename WT, int D>
+__device__ __forceinline__ void attn_place_q(const StepParams& P, const AttnItem it, int r0, int Ra, int grp, int tid,
+                                             u32x4& qx, char* sq) {
+    if (!__all(sx_ok(qx))) {
+        int spins = 0;
+        do qx = attn_issue_q<WT, D>(P, it, r0, Ra, grp, tid); while (!__all(sx_ok(qx)) && spin_again(P, spins));
+    }
+    attn_store_q<WT, D>(sq, tid, qx);
+}
+
+template <typename WT, int D, int NK, bool SINGLE>
 __device__ __forceinline__ void attn_phase(const StepParams& P, int wg, int nwg, int wave, char* smem) {
-    typedef AttnCfg<WT, D> C;
+    typedef AttnCfg<WT, D, NK> C;
     constexpr bool BF = Traits<WT>::BF;
-    constexpr int CH = C::CH, GE = Traits<WT>::GE, KSTEP = Traits<WT>::KSTEP;
+    constexpr int CH = C::CH, CH_LOG = C::CH_LOG, GE = Traits<WT>::GE, KSTEP = Traits<WT>::KSTEP;
     constexpr int NL = GE / 4;                      // 16-byte loads per group of exchanged fp32
     constexpr int STEPS = D / KSTEP;                // MFMA steps along the head dimension
     constexpr int DPL = D / 64;                     // output columns per lane
@@ -1176,126 +1210,186 @@ __device__ __forceinline__ void attn_phase(const StepParams& P, int wg, int nwg,
     float* sL = reinterpret_cast<float*>(smem + C::OFF_L);
     float* sP = reinterpret_cast<float*>(smem + C::OFF_P);
     float* sO = reinterpret_cast<float*>(smem + C::OFF_O);
+    char* sQ = smem + C::OFF_Q;
     const rsrc_t racc = make_rsrc(P.attn_acc), rml = make_rsrc(P.attn_ml);
     const SxBuf ro = sx_buf(P, P.o_buf);
     const unsigned seq = ps_seq();
 
     // The loads of a work item are requested while the previous item is still being computed: the
     // K rows and the first query rows right after the score MFMAs, the V rows right after P.V.
-    uint4 kreg[STEPS];
-    typename VRaw<WT, DPL>::type vraw[16];
-    u32x4 qx[STEPS][NL];
+    // For these loads to stay in flight the waits in front of their uses must count exactly the
+    // younger memory operations, and the compiler can only do that along straight-line code: so a
+    // workgroup's last item requests (harmless, clamped) loads as if another one followed; the
+    // stores of an item's results are a fixed number per thread; and SINGLE (all g*M query rows
+    // fit in one pass of 16: the host knows) removes the loop over the passes.
+    uint4 kreg[NK][STEPS];
+    typename VRaw<WT, DPL>::type vraw[NK][16];
+    u32x4 qx;
+    // The query rows of a pass are requested during the previous pass (or item) and put into LDS at
+    // its end.  The first look at them is straight-line code, not behind a loop's back edge, so
+    // that the wait in front of it counts exactly the younger operations (the V rows) and leaves
+    // them in flight.  Only a failed look (the QKV phase has not published the rows yet) asks
+    // again, in a loop.
     AttnItem cur = {0, 0, 0, 1, 0};
+    const int wkey = 16 * NK * wave;                // this wavefront's keys within a chunk: wkey .. wkey + 16 NK - 1
     if (wg < P.attn_items) {
-        cur = attn_decode(P, wg, CH);
-        attn_load_k<WT, D>(P, cur, cur.ch * CH + 16 * wave, lane, kreg);
-        attn_issue_v<WT, D>(P, cur, cur.ch * CH + 16 * wave, lane, vraw);
-        attn_issue_q<WT, D>(P, cur, 0, Ra, grp, lane, qx);
+        cur = attn_decode(P, wg, CH_LOG);
+#pragma unroll
+        for (int j = 0; j < NK; ++j) attn_load_k<WT, D>(P, cur, cur.ch * CH + wkey + 16 * j, lane, kreg[j]);
+        qx = attn_issue_q<WT, D>(P, cur, 0, Ra, grp, tid);   // same order as in the loop: K, Q, then V
+#pragma unroll
+        for (int j = 0; j < NK; ++j) attn_issue_v<WT, D>(P, cur, cur.ch * CH + wkey + 16 * j, lane, vraw[j]);
+        attn_place_q<WT, D>(P, cur, 0, Ra, grp, tid, qx, sQ);
     }
+    __syncthreads();
     for (int item = wg; item < P.attn_items; item += nwg) {
         const bool has_next = item + nwg < P.attn_items;
-        const AttnItem nx = has_next ? attn_decode(P, item + nwg, CH) : cur;
+        const AttnItem nx = has_next ? attn_decode(P, item + nwg, CH_LOG) : cur;
         const int b = cur.b, hk = cur.hk, ch = cur.ch, nch = cur.nch, L = cur.L;
-        const int c0 = ch * CH;
-        const int key0 = c0 + 16 * wave;            // this wavefront's keys: positions key0 .. key0 + 15
+        const int key0 = ch * CH + wkey;            // this wavefront's keys: positions key0 .. key0 + 16 NK - 1
         const int end = L + P.M;                    // positions that exist
+        stamp(P, wg, 44);
 
-        for (int r0 = 0; r0 < Ra; r0 += 16) {       // 16 query rows per pass
+        for (int r0 = 0; r0 < (SINGLE ? 16 : Ra); r0 += 16) {       // 16 query rows per pass
             const int nr = min(16, Ra - r0);
-            const bool last_pass = r0 + 16 >= Ra;
+            const bool last_pass = SINGLE || r0 + 16 >= Ra;
             const int rho = r0 + c < Ra ? r0 + c : Ra - 1;
             const int i = rho - row_seq(P, rho) * P.M;
-            if (r0 > 0) attn_issue_q<WT, D>(P, cur, r0, Ra, grp, lane, qx);
             BRegs<WT, 1> bq[STEPS];
-            {
-                int spins = 0;
-                for (;;) {   // requested earlier; asked for again until the QKV phase has published the rows
-                    unsigned bad = 0;
 #pragma unroll
-                    for (int t = 0; t < STEPS; ++t)
-#pragma unroll
-                        for (int h = 0; h < NL; ++h) bad |= (unsigned)!sx_ok(qx[t][h]);
-                    if (__all(!bad) || !spin_again(P, spins)) break;
-                    attn_issue_q<WT, D>(P, cur, r0, Ra, grp, lane, qx);
-                }
-#pragma unroll
-                for (int t = 0; t < STEPS; ++t) {
-                    if constexpr (BF) {
-                        unsigned* hp = &bq[t].h[0].x;
-                        unsigned* lp = &bq[t].l[0].x;
-#pragma unroll
-                        for (int j = 0; j < 4; ++j) {
-                            const float f0 = __uint_as_float(qx[t][j >> 1][2 * (j & 1)]);
-                            const float f1 = __uint_as_float(qx[t][j >> 1][2 * (j & 1) + 1]);
-                            const unsigned hi = pack_bf16x2(f0, f1);
-                            hp[j] = hi;
-                            lp[j] = pack_bf16x2(f0 - __uint_as_float(hi << 16), f1 - __uint_as_float(hi & 0xFFFF0000u));
-                        }
-                    } else {
-                        bq[t].h[0] = make_uint4(qx[t][0][0], qx[t][0][1], qx[t][0][2], qx[t][0][3]);
-                    }
+            for (int t = 0; t < STEPS; ++t) {
+                if constexpr (BF) {
+                    bq[t].h[0] = ld16(sQ + (2 * t * 64 + lane) * 16);
+                    bq[t].l[0] = ld16(sQ + ((2 * t + 1) * 64 + lane) * 16);
+                } else {
+                    bq[t].h[0] = ld16(sQ + (t * 64 + lane) * 16);
                 }
             }
-            // ---- scores of keys 4 kb .. 4 kb + 3 (of this wavefront's 16) for query row c
-            f32x4 acc[1] = {f32x4{0.f, 0.f, 0.f, 0.f}};
+            // ---- scores of keys 4 kb .. 4 kb + 3 (of each of this wavefront's groups of 16) for query row c
+            f32x4 acc[NK][1];
 #pragma unroll
-            for (int t = 0; t < STEPS; ++t) mma_step<WT, 1>(kreg[t], bq[t], acc);
-            if (last_pass && has_next) {   // the K rows and query rows are consumed: request the next item's
-                attn_load_k<WT, D>(P, nx, nx.ch * CH + 16 * wave, lane, kreg);
-                attn_issue_q<WT, D>(P, nx, 0, Ra, grp, lane, qx);
-            }
-            float sc[4], mloc = -INFINITY;
+            for (int j = 0; j < NK; ++j) {
+                acc[j][0] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const int pos = key0 + 4 * kb + r;
-                const bool vis = r0 + c < Ra && pos < end && pos <= L + i;
-                sc[r] = vis ? acc[0][r] * P.inv_sqrt_d : -INFINITY;
-                mloc = fmaxf(mloc, sc[r]);
+                for (int t = 0; t < STEPS; ++t) mma_step<WT, 1>(kreg[j][t], bq[t], acc[j]);
             }
+            if (!last_pass) {              // request the query rows of the next pass,
+                qx = attn_issue_q<WT, D>(P, cur, r0 + 16, Ra, grp, tid);
+            } else {                       // or, the K rows being consumed, the next item's K and query rows
+#pragma unroll
+                for (int j = 0; j < NK; ++j) attn_load_k<WT, D>(P, nx, nx.ch * CH + wkey + 16 * j, lane, kreg[j], has_next);
+                qx = attn_issue_q<WT, D>(P, nx, 0, Ra, grp, tid);
+            }
+            stamp(P, wg, 45);
+            float sc[NK][4], mloc = -INFINITY;
+#pragma unroll
+            for (int j = 0; j < NK; ++j)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int pos = key0 + 16 * j + 4 * kb + r;
+                    const bool vis = r0 + c < Ra && pos < end && pos <= L + i;
+                    sc[j][r] = vis ? acc[j][0][r] * P.inv_sqrt_d : -INFINITY;
+                    mloc = fmaxf(mloc, sc[j][r]);
+                }
             mloc = fmaxf(mloc, __shfl_xor(mloc, 16, 64));
             mloc = fmaxf(mloc, __shfl_xor(mloc, 32, 64));
             __syncthreads();                        // the previous pass is done with the LDS areas
             if (kb == 0) sM[wave * 16 + c] = mloc;
             __syncthreads();
+            stamp(P, wg, 46);
             float mrow = -INFINITY;
 #pragma unroll
             for (int w = 0; w < PS_WAVES; ++w) mrow = fmaxf(mrow, sM[w * 16 + c]);
-            f32x4 pr;
             float lloc = 0.f;
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                pr[r] = sc[r] > -INFINITY ? expf(sc[r] - mrow) : 0.f;
-                lloc += pr[r];
+            for (int j = 0; j < NK; ++j) {
+                f32x4 pr;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    pr[r] = sc[j][r] > -INFINITY ? expf(sc[j][r] - mrow) : 0.f;
+                    lloc += pr[r];
+                }
+                *reinterpret_cast<f32x4*>(sP + ((wave * NK + j) * 16 + c) * 16 + 4 * kb) = pr;
             }
             lloc += __shfl_xor(lloc, 16, 64);
             lloc += __shfl_xor(lloc, 32, 64);
             if (kb == 0) sL[wave * 16 + c] = lloc;
-            *reinterpret_cast<f32x4*>(sP + (wave * 16 + c) * 16 + 4 * kb) = pr;
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");   // written and read by this wavefront only
             __builtin_amdgcn_wave_barrier();
             // ---- this wavefront's part of P.V for every row of the pass
-            float v[16][DPL];
-            attn_finish_v<WT, D>(P, cur, key0, lane, vraw, v);
-            for (int rr = 0; rr < nr; ++rr) {
-                const f32x4* prow = reinterpret_cast<const f32x4*>(sP + (wave * 16 + rr) * 16);
-                float o[DPL];
+            if constexpr (NK == 1) {
+                float v[16][DPL];
+                attn_finish_v<WT, D>(P, cur, key0, lane, vraw[0], v);
+                // the raw V rows are consumed: request the next item's, ahead of the arithmetic
+                if (last_pass) attn_issue_v<WT, D>(P, nx, nx.ch * CH + wkey, lane, vraw[0], has_next);
+                for (int rr = 0; rr < nr; ++rr) {
+                    const f32x4* prow = reinterpret_cast<const f32x4*>(sP + (wave * 16 + rr) * 16);
+                    float o[DPL];
 #pragma unroll
-                for (int e = 0; e < DPL; ++e) o[e] = 0.f;
+                    for (int e = 0; e < DPL; ++e) o[e] = 0.f;
 #pragma unroll
-                for (int k4 = 0; k4 < 4; ++k4) {
-                    const f32x4 p4 = prow[k4];
+                    for (int k4 = 0; k4 < 4; ++k4) {
+                        const f32x4 p4 = prow[k4];
 #pragma unroll
-                    for (int r = 0; r < 4; ++r)
+                        for (int r = 0; r < 4; ++r)
 #pragma unroll
-                        for (int e = 0; e < DPL; ++e) o[e] += p4[r] * v[4 * k4 + r][e];
+                            for (int e = 0; e < DPL; ++e) o[e] += p4[r] * v[4 * k4 + r][e];
+                    }
+#pragma unroll
+                    for (int e = 0; e < DPL; ++e) sO[(wave * 16 + rr) * D + DPL * lane + e] = o[e];
+                }
+            } else {
+                // the rows' sums stay in registers while the groups of 16 keys are widened one at a time
+                float o[16][DPL];
+#pragma unroll
+                for (int rr = 0; rr < 16; ++rr)
+#pragma unroll
+                    for (int e = 0; e < DPL; ++e) o[rr][e] = 0.f;
+#pragma unroll
+                for (int j = 0; j < NK; ++j) {
+                    float v[16][DPL];
+                    attn_finish_v<WT, D>(P, cur, key0 + 16 * j, lane, vraw[j], v);
+                    if (last_pass) attn_issue_v<WT, D>(P, nx, nx.ch * CH + wkey + 16 * j, lane, vraw[j], has_next);
+#pragma unroll
+                    for (int rr = 0; rr < 16; ++rr) {
+                        if (rr < nr) {   // wavefront-uniform
+                            const f32x4* prow = reinterpret_cast<const f32x4*>(sP + ((wave * NK + j) * 16 + rr) * 16);
+#pragma unroll
+                            for (int k4 = 0; k4 < 4; ++k4) {
+                                const f32x4 p4 = prow[k4];
+#pragma unroll
+                                for (int r = 0; r < 4; ++r)
+#pragma unroll
+                                    for (int e = 0; e < DPL; ++e) o[rr][e] += p4[r] * v[4 * k4 + r][e];
+                            }
+                        }
+                    }
                 }
 #pragma unroll
-                for (int e = 0; e < DPL; ++e) sO[(wave * 16 + rr) * D + DPL * lane + e] = o[e];
+                for (int rr = 0; rr < 16; ++rr)
+                    if (rr < nr) {
+#pragma unroll
+                        for (int e = 0; e < DPL; ++e) sO[(wave * 16 + rr) * D + DPL * lane + e] = o[rr][e];
+                    }
             }
-            if (last_pass && has_next) attn_issue_v<WT, D>(P, nx, nx.ch * CH + 16 * wave, lane, vraw);
+            stamp(P, wg, 47);
+            // every wavefront has read this pass's query rows (before the pass's first barrier):
+            // the next ones take their place; they are read after the barrier below
+            if (!last_pass) attn_place_q<WT, D>(P, cur, r0 + 16, Ra, grp, tid, qx, sQ);
+            else if (has_next) attn_place_q<WT, D>(P, nx, 0, Ra, grp, tid, qx, sQ);
             __syncthreads();
-            // ---- add the wavefronts' parts in order
-            for (int x = tid; x < nr * D; x += PS_WG_THREADS) {
+            stamp(P, wg, 48);
+            // ---- add the wavefronts' parts in order.  SINGLE: a fixed number of rounds; threads beyond
+            // the last element repeat it (same value to the same place)
+            constexpr int XR = (16 * D + PS_WG_THREADS - 1) / PS_WG_THREADS;
+#pragma unroll
+            for (int xi = 0; xi < XR; ++xi) {
+                int x = tid + xi * PS_WG_THREADS;
+                if constexpr (SINGLE) {
+                    x = min(x, nr * D - 1);
+                } else {
+                    if (x >= nr * D) break;
+                }
                 const int rr = x / D, dd = x - rr * D;
                 float o = 0.f, l = 0.f;
 #pragma unroll
@@ -1308,12 +1402,23 @@ __device__ __forceinline__ void attn_phase(const StepParams& P, int wg, int nwg,
                 } else {
                     // partial (max, sum, unnormalised output) of this chunk, as tagged data
                     ll_st1(racc, (unsigned)(((size_t)item * Ra + rho2) * D + dd), o, seq);
-                    if (dd < 2) {
-                        float mr = -INFINITY;
+                    if constexpr (!SINGLE) {
+                        if (dd < 2) {
+                            float mr = -INFINITY;
 #pragma unroll
-                        for (int w = 0; w < PS_WAVES; ++w) mr = fmaxf(mr, sM[w * 16 + rr]);
-                        ll_st1(rml, (unsigned)(((size_t)item * Ra + rho2) * 2 + dd), dd ? l : mr, seq);
+                            for (int w = 0; w < PS_WAVES; ++w) mr = fmaxf(mr, sM[w * 16 + rr]);
+                            ll_st1(rml, (unsigned)(((size_t)item * Ra + rho2) * 2 + dd), dd ? l : mr, seq);
+                        }
                     }
+                }
+            }
+            if constexpr (SINGLE) {
+                if (nch > 1) {   // (max, sum) of row tid / 2: one store per thread, the surplus threads repeat the last
+                    const int e = min(tid, 2 * nr - 1), rr = e >> 1;
+                    float mr = -INFINITY, l = 0.f;
+#pragma unroll
+                    for (int w = 0; w < PS_WAVES; ++w) { mr = fmaxf(mr, sM[w * 16 + rr]); l += sL[w * 16 + rr]; }
+                    ll_st1(rml, (unsigned)(((size_t)item * Ra + r0 + rr) * 2 + (e & 1)), (e & 1) ? l : mr, seq);
                 }
             }
         }
@@ -1334,7 +1439,7 @@ __device__ __forceinline__ void attn_phase(const StepParams& P, int wg, int nwg,
     for (int mi = wg; mi < P.attn_merge_items; mi += nwg) {
         int b = 0, rem = mi, nch = 0, item_base = 0;
         for (;; ++b) {
-            nch = (P.kv_len[b] + P.M + CH - 1) / CH;
+            nch = (P.kv_len[b] + P.M + CH - 1) >> CH_LOG;
             const int n = nch > 1 ? P.nkv * RT : 0;
             if (rem < n) break;
             rem -= n;
@@ -1349,21 +1454,46 @@ __device__ __forceinline__ void attn_phase(const StepParams& P, int wg, int nwg,
         for (int g0 = 0; g0 < nch; g0 += GRP) {
             const int gn = min(GRP, nch - g0);
             __syncthreads();                         // the weights of the previous group (or item) are no longer read
+            // Both kinds of loads are requested at once, the (max, sum) pairs first: the outputs of the
+            // first 16 blocks are on their way while the weights are worked out.  The first look at
+            // either is straight-line code (see the query rows above); only a failed look loops.
+            u32x4 ml[GRP / 64];
+            u32x4 av[CB];
+            const int rho_w = r0 + (wave < nr ? wave : 0);
+            auto issue_ml = [&]() __attribute__((always_inline)) {
+#pragma unroll
+                for (int q = 0; q < GRP / 64; ++q) {
+                    const int cx = lane + 64 * q;
+                    const int cc = g0 + (cx < gn ? cx : gn - 1);
+                    ml[q] = coh_ld16(rml, (unsigned)(((size_t)(item0 + cc) * Ra + rho_w) * 2) * 8);   // {max, tag, sum, tag}
+                }
+            };
+            auto bad_ml = [&]() __attribute__((always_inline)) {
+                unsigned bad = 0;
+#pragma unroll
+                for (int q = 0; q < GRP / 64; ++q) bad |= (unsigned)(ml[q][1] != seq) | (unsigned)(ml[q][3] != seq);
+                return bad;
+            };
+            auto issue_av = [&](int cb) __attribute__((always_inline)) {
+#pragma unroll
+                for (int i = 0; i < CB; ++i) {
+                    const int cc = g0 + (cb + i < gn ? cb + i : gn - 1);
+                    const int rho = r0 + (active ? myrow : 0);
+                    av[i] = coh_ld16(racc, (unsigned)(((size_t)(item0 + cc) * Ra + rho) * D + 2 * dp) * 8);   // {o, tag, o', tag}
+                }
+            };
+            auto bad_av = [&]() __attribute__((always_inline)) {
+                unsigned bad = 0;
+#pragma unroll
+                for (int i = 0; i < CB; ++i) bad |= (unsigned)(av[i][1] != seq) | (unsigned)(av[i][3] != seq);
+                return bad;
+            };
+            if (wave < nr) issue_ml();
+            issue_av(0);
             if (wave < nr) {
-                const int rho = r0 + wave;
-                u32x4 ml[GRP / 64];
-                int spins = 0;
-                for (;;) {
-#pragma unroll
-                    for (int q = 0; q < GRP / 64; ++q) {
-                        const int cx = lane + 64 * q;
-                        const int cc = g0 + (cx < gn ? cx : gn - 1);
-                        ml[q] = coh_ld16(rml, (unsigned)(((size_t)(item0 + cc) * Ra + rho) * 2) * 8);   // {max, tag, sum, tag}
-                    }
-                    unsigned bad = 0;
-#pragma unroll
-                    for (int q = 0; q < GRP / 64; ++q) bad |= (unsigned)(ml[q][1] != seq) | (unsigned)(ml[q][3] != seq);
-                    if (__all(!bad) || !spin_again(P, spins)) break;
+                if (!__all(!bad_ml())) {
+                    int spins = 0;
+                    do issue_ml(); while (!__all(!bad_ml()) && spin_again(P, spins));
                 }
                 float mloc = -INFINITY;
 #pragma unroll
@@ -1384,19 +1514,10 @@ __device__ __forceinline__ void attn_phase(const StepParams& P, int wg, int nwg,
             __syncthreads();
             float o0 = 0.f, o1 = 0.f;
             for (int cb = 0; cb < gn; cb += CB) {
-                u32x4 av[CB];
-                int spins = 0;
-                for (;;) {
-#pragma unroll
-                    for (int i = 0; i < CB; ++i) {
-                        const int cc = g0 + (cb + i < gn ? cb + i : gn - 1);
-                        const int rho = r0 + (active ? myrow : 0);
-                        av[i] = coh_ld16(racc, (unsigned)(((size_t)(item0 + cc) * Ra + rho) * D + 2 * dp) * 8);   // {o, tag, o', tag}
-                    }
-                    unsigned bad = 0;
-#pragma unroll
-                    for (int i = 0; i < CB; ++i) bad |= (unsigned)(av[i][1] != seq) | (unsigned)(av[i][3] != seq);
-                    if (__all(!bad || !active) || !spin_again(P, spins)) break;
+                if (cb > 0) issue_av(cb);
+                if (!__all(!bad_av() || !active)) {
+                    int spins = 0;
+                    do issue_av(cb); while (!__all(!bad_av() || !active) && spin_again(P, spins));
                 }
 #pragma unroll
                 for (int i = 0; i < CB; ++i) {
@@ -1581,11 +1702,11 @@ __global__ void __launch_bounds__(PS_WG_THREADS, 1) gemm_kernel(const StepParams
     gemm_phase<WT, MT, PH>(P, blockIdx.x, wave, smem, wb, P.ph[PH].wpack);
 }
 
-template <typename WT, int D>
+template <typename WT, int D, int NK, bool SINGLE>
 __global__ void __launch_bounds__(PS_WG_THREADS) attn_kernel(const StepParams P) {
     extern __shared__ __attribute__((aligned(256))) char smem[];
     step_begin(P, false);
-    attn_phase<WT, D>(P, blockIdx.x, gridDim.x, __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), smem);
+    attn_phase<WT, D, NK, SINGLE>(P, blockIdx.x, gridDim.x, __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), smem);
 }
 
 static __global__ void __launch_bounds__(PS_WG_THREADS) lm_merge_kernel(const StepParams P) {
@@ -1620,7 +1741,8 @@ __global__ void __launch_bounds__(PS_WG_THREADS, 1) fused_kernel(const StepParam
     gemm_phase<WT, MT, PH_QKV>(P, wg, wave, smem, wb, first_stream(P, PH_OPROJ, wg, wave), my_seq);
     __syncthreads();
     stamp(P, wg, 32);
-    attn_phase<WT, D>(P, wg, gridDim.x, wave, smem);
+    if (P.attn_single) attn_phase<WT, D, PS_ATTN_NK, true>(P, wg, gridDim.x, wave, smem);
+    else attn_phase<WT, D, PS_ATTN_NK, false>(P, wg, gridDim.x, wave, smem);
     __syncthreads();
     stamp(P, wg, 36);
     // the ticket (see step_read) is taken here: the next thing this workgroup does is wait for the

@@ -114,7 +114,7 @@ static WsLayout ws_layout(const ps_draft_config* c) {
     const size_t rows = (size_t)c->max_batch * (c->max_new + c->k_max);
     const size_t qd = (size_t)c->n_heads * c->head_dim;
     const int grp = c->n_heads / c->n_kv_heads;
-    const int ch = find_instance(c->dtype, c->head_dim)->attn_chunk;
+    const int ch = PS_ATTN_KEYS * PS_ATTN_NK;
     const size_t max_items = (size_t)c->max_batch * c->n_kv_heads * ((c->max_positions + ch - 1) / ch);
     const size_t ra = (size_t)grp * (c->max_new + c->k_max);
     size_t off = 0;
@@ -462,16 +462,18 @@ extern "C" int ps_draft_step(ps_draft_ctx* ctx, const ps_draft_step_args* a, voi
     }
     P.logits_store = a->logits ? a->logits : (a->probs ? ctx->logits_ws : nullptr);
     P.top_ids = a->top_ids; P.top_p = a->top_p; P.lse = a->lse; P.probs = a->probs; P.hidden_out = a->hidden_out;
-    const int ch = ctx->inst->attn_chunk;
-    int items = 0;
     for (int b = 0; b < a->batch; ++b) {
         P.kv_off[b] = a->kv_offsets[b];
         P.kv_len[b] = a->kv_len[b];
-        items += c.n_kv_heads * ((a->kv_len[b] + M + ch - 1) / ch);
     }
-    P.attn_items = items; P.attn_chunk = ch;
+    // attention work items: (sequence, kv head, block of ch keys)
+    const int ra = (c.n_heads / c.n_kv_heads) * M;
+    const int ch = PS_ATTN_KEYS * PS_ATTN_NK;
+    int items = 0;
+    for (int b = 0; b < a->batch; ++b) items += c.n_kv_heads * ((a->kv_len[b] + M + ch - 1) / ch);
+    P.attn_items = items; P.attn_single = ra <= 16;
     {   // sequences that span several key blocks are put together by (sequence, kv head, 8 rows) work items
-        const int ra = (c.n_heads / c.n_kv_heads) * M, rt = (ra + PS_WAVES - 1) / PS_WAVES;
+        const int rt = (ra + PS_WAVES - 1) / PS_WAVES;
         int mi = 0;
         for (int b = 0; b < a->batch; ++b)
             if ((a->kv_len[b] + M + ch - 1) / ch > 1) mi += c.n_kv_heads * rt;
@@ -515,7 +517,7 @@ extern "C" int ps_draft_step(ps_draft_ctx* ctx, const ps_draft_step_args* a, voi
     P.timeline = ctx->timeline;
 
     // the persistent kernel needs the largest LDS footprint of its phases and one workgroup per CU
-    int lds = ctx->inst->attn_lds;
+    int lds = ps_attn_lds_bytes(c.head_dim, PS_ATTN_NK);
     for (int ph = 0; ph < PH_COUNT; ++ph) {
         if (P.ph[ph].lds_bytes > lds) lds = P.ph[ph].lds_bytes;
     }

@@ -37,6 +37,10 @@ static kernel_fn fused_fn(int mt) {
     }
 }
 
+static kernel_fn attn_fn(int single) {
+    return single ? attn_kernel<WT_, D_, PS_ATTN_NK, true> : attn_kernel<WT_, D_, PS_ATTN_NK, false>;
+}
+
 static hipError_t prepare(int lds_limit) {
     hipError_t e;
     for (int mt = 1; mt <= 4; ++mt) {
@@ -49,10 +53,13 @@ static hipError_t prepare(int lds_limit) {
                                 hipFuncAttributeMaxDynamicSharedMemorySize, lds_limit);
         if (e != hipSuccess) return e;
     }
-    if (AttnCfg<WT_, D_>::LDS > lds_limit) return hipErrorInvalidValue;
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_kernel<WT_, D_>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, AttnCfg<WT_, D_>::LDS);
-    return e;
+    if (ps_attn_lds_bytes(D_, PS_ATTN_NK) > lds_limit) return hipErrorInvalidValue;
+    for (int single = 0; single < 2; ++single) {
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_fn(single)), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                ps_attn_lds_bytes(D_, PS_ATTN_NK));
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
 }
 
 // one kernel per phase; events: NULL or PS_PROFILE_EVENTS events recorded around the kernels
@@ -69,8 +76,7 @@ static hipError_t launch_multi(const StepParams& P, hipStream_t stream, hipEvent
     hipError_t e;
     if ((e = mark()) != hipSuccess) return e;
     if ((e = gemm(PH_QKV, mt_all)) != hipSuccess) return e;
-    constexpr int attn_lds = AttnCfg<WT_, D_>::LDS;
-    hipLaunchKernelGGL((attn_kernel<WT_, D_>), dim3(P.attn_nwg), dim3(PS_WG_THREADS), attn_lds, stream, P);
+    hipLaunchKernelGGL(attn_fn(P.attn_single), dim3(P.attn_nwg), dim3(PS_WG_THREADS), ps_attn_lds_bytes(D_, PS_ATTN_NK), stream, P);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     if ((e = mark()) != hipSuccess) return e;
     if ((e = gemm(PH_OPROJ, mt_all)) != hipSuccess) return e;
@@ -120,7 +126,7 @@ static hipError_t pack(const StepParams& P, int ph, int T, int Kt, int Kreal, ch
 #define PS_CAT(a, b) PS_CAT2(a, b)
 const PsInstance* PS_CAT(ps_instance_, PS_INST_NAME)() {
     static const PsInstance inst = {
-        PS_INST_BF16 ? PS_BF16 : PS_F32, PS_INST_D, AttnCfg<WT_, D_>::CH, AttnCfg<WT_, D_>::LDS,
+        PS_INST_BF16 ? PS_BF16 : PS_F32, PS_INST_D,
         prepare, launch_multi, launch_fused, launch_probs, pack,
     };
     return &inst;

@@ -24,6 +24,15 @@
 static_assert((1 << PS_WAVES_LOG) == PS_WAVES, "PS_WAVES_LOG");
 static_assert((PS_U & (PS_U - 1)) == 0 && PS_U <= PS_U_MAX, "PS_U");
 
+// Attention work items cover PS_ATTN_KEYS * PS_ATTN_NK keys of one (sequence, kv head): every wavefront
+// takes PS_ATTN_NK groups of 16 keys.  LDS an item needs (see AttnCfg in ps_device.h):
+#define PS_ATTN_NK 1
+#define PS_ATTN_KEYS (16 * PS_WAVES)
+#define PS_ATTN_KEYS_LOG (4 + PS_WAVES_LOG)
+constexpr int ps_attn_lds_bytes(int d, int nk) {
+    return 256 + 2 * PS_WAVES * 16 * 4 + PS_WAVES * nk * 16 * 16 * 4 + PS_WAVES * 16 * d * 4 + 16 * d * 4;
+}
+
 enum { PH_QKV = 0, PH_OPROJ = 1, PH_GATEUP = 2, PH_DOWN = 3, PH_LMHEAD = 4, PH_COUNT = 5 };
 
 // How one weight-streaming GEMM phase is cut up.  A "tile" is 16 weight rows; a "step" is the
@@ -84,7 +93,8 @@ struct StepParams {
     int32_t* top_ids;
     float *top_p, *lse, *probs, *hidden_out;
     // attention work list
-    int attn_items, attn_chunk, attn_nwg;
+    int attn_items, attn_nwg;   // work items; workgroups of the attention kernel (multi mode)
+    int attn_single;        // the g*M query rows of a kv head fit in one pass of 16
     int attn_merge_items;   // (sequence, kv head, 8 query rows) of the sequences that span several key blocks
     int fused_nwg, fused_lds;
     long long kv_off[PS_MAX_ROWS];
@@ -97,7 +107,7 @@ struct StepParams {
 
 // One compiled instantiation of the device code (storage type x head_dim) and its launchers.
 struct PsInstance {
-    int dtype, head_dim, attn_chunk, attn_lds;
+    int dtype, head_dim;
     hipError_t (*prepare)(int lds_limit);   // raises the dynamic-LDS limit of every kernel
     hipError_t (*launch_multi)(const StepParams& P, hipStream_t stream, hipEvent_t* events);
     hipError_t (*launch_fused)(const StepParams& P, hipStream_t stream);
