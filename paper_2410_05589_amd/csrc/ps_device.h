@@ -771,6 +771,22 @@ __device__ __forceinline__ void gemm_phase(const StepParams& P, int wg, int wave
     int sg_lo, sg_hi;
     slice_groups(D, s, sg_lo, sg_hi);
 
+    // While the workgroup waits for its activations the memory is idle: besides the PS_U KiB per
+    // wavefront that are already on their way into registers (wb), the next PS_PF * 8 KiB of the
+    // wavefront's first weight stream are pulled into the L2 of this XCD, one 4-byte load per
+    // 128-byte line.  The values are not used; they stay registers until the panel is staged.
+    unsigned pf[PS_PF > 0 ? PS_PF : 1];
+    if (PS_PF > 0 && tile_index(D, 0, slot, j) < D.T) {
+        int a0, n;
+        const char* wp0 = stream_ptr(D, tile_index(D, 0, slot, j), sg_lo, min(D.piece_groups, sg_hi - sg_lo), kw, a0, n);
+        const int lines = (n - PS_U) * (PS_WS / 128);            // 128-byte lines that follow the preloaded steps
+#pragma unroll
+        for (int i = 0; i < PS_PF; ++i) {
+            const int ln = min(64 * i + (lane16 >> 4), lines - 1);
+            pf[i] = lines > 0 ? *reinterpret_cast<const unsigned*>(wp0 + PS_U * PS_WS + (size_t)ln * 128) : 0u;
+        }
+    }
+
     bool streamed = false;
     for (int rd = 0; rd < D.rounds; ++rd) {
         const int tau = tile_index(D, rd, slot, j);
@@ -786,7 +802,11 @@ __device__ __forceinline__ void gemm_phase(const StepParams& P, int wg, int wave
                 stage_piece<WT, PH>(P, D, wave, smem, s_pa, s_pb, g_lo * PS_U, ng * PS_U, pc == 0, rd == 0);
                 if (publish_seq && rd == 0 && pc == 0) *(lds_u32*)(unsigned)PS_LDS_SEQ = publish_seq;   // see step_read
                 __syncthreads();
-                if (rd == 0 && pc == 0) stamp(P, wg, 2 + ph * 6 + 1);
+                if (rd == 0 && pc == 0) {
+#pragma unroll
+                    for (int i = 0; i < (PS_PF > 0 ? PS_PF : 0); ++i) asm volatile("" ::"v"(pf[i]));
+                    stamp(P, wg, 2 + ph * 6 + 1);
+                }
             }
             if (valid) {
                 int a0, n, na, nn;

@@ -19,6 +19,9 @@
 #ifndef PS_U
 #define PS_U 8             // 16-byte weight loads in flight per lane (PS_U KiB per wavefront)
 #endif
+#ifndef PS_PF
+#define PS_PF 1            // 8-KiB pieces of its first weight stream a wavefront pulls into the L2 while it waits
+#endif
 #define PS_U_MAX 32        // packed weight buffers are padded by this many KiB (streaming reads ahead)
 #define PS_LDS_BYTES (160 * 1024)
 static_assert((1 << PS_WAVES_LOG) == PS_WAVES, "PS_WAVES_LOG");
