@@ -117,6 +117,7 @@ def main():
     # ---- per-kernel durations, live, with HIP events on the launch stream (second region of K steps)
     kernel_us = None
     roofline = None
+    per_step_us = None
     if not args.no_kernel_timing:
         ksteps = min(args.steps, 200)
         evs = [[torch.cuda.Event(enable_timing=True) for _ in range(B.PS_PROFILE_EVENTS)] for _ in range(ksteps)]
@@ -131,9 +132,13 @@ def main():
         B.ps_draft_set_profile_events(drafter.ctx, None)
         torch.cuda.synchronize()
         acc = np.zeros(B.PS_PROFILE_EVENTS - 1)
+        per_step = []
         for row in evs:
             for j in range(B.PS_PROFILE_EVENTS - 1):
                 acc[j] += row[j].elapsed_time(row[j + 1])
+            # fused: events 0 and 1 bracket the one kernel of the step; multi: first to last event = all its kernels
+            per_step.append(row[0].elapsed_time(row[1 if args.mode == "fused" else -1]) * 1e3)
+        per_step_us = {q: round(float(np.percentile(per_step, p)), 2) for q, p in (("p10", 10), ("median", 50), ("p90", 90))}
         kernel_us = {n: float(acc[j] / ksteps * 1e3) for j, n in enumerate(B.PROFILE_KERNELS)}
         dname = "bf16_t" if shape.dtype == "bf16" else "float"
         mt = (wl.batch * (max_new + wl.k) + 15) // 16
@@ -155,6 +160,26 @@ def main():
                     "unit": "GB/s", "frac": round(achieved / PEAK_HBM_GBS, 4), "traffic": traffic,
                     "algorithmic_bytes_per_launch": int(dom_bytes), "avg_launch_us": round(dom_us, 2)}
 
+    # ---- the same step captured once in a HIP graph and replayed (only when every step has the same n_new)
+    graph_us = None
+    if not args.no_kernel_timing and not mix:
+        a0 = variants[wl.n_new][0]
+        side = torch.cuda.Stream()
+        graph = torch.cuda.CUDAGraph()
+        torch.cuda.synchronize()
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(graph, stream=side):
+                drafter.step(a0, stream=side)
+        torch.cuda.synchronize()
+        for _ in range(min(args.warmup, 20)):
+            graph.replay()
+        torch.cuda.synchronize()
+        g0 = time.perf_counter()
+        for _ in range(args.steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        graph_us = (time.perf_counter() - g0) * 1e6 / args.steps
+
     step_gbs = bytes_mean / (ms_per_step * 1e-3) / 1e9
     result = {
         "metric": "draft tokens/sec (parallel draft step, k+1 tokens per sequence per step)",
@@ -169,6 +194,8 @@ def main():
                    "tokens_per_step": tokens_per_step},
         "latency_us": round(ms_per_step * 1e3, 2),
         "latency_us_hip_events": round(ev_ms * 1e3, 2),
+        "latency_us_per_step_events": per_step_us,
+        "latency_us_graph_replay": round(graph_us, 2) if graph_us else None,
         "step_roofline": {"algorithmic_bytes": int(bytes_mean), "achieved_GBps": round(step_gbs, 1),
                           "peak_GBps": PEAK_HBM_GBS, "frac": round(step_gbs / PEAK_HBM_GBS, 4),
                           "roofline_latency_us": round(bytes_mean / PEAK_HBM_GBS / 1e3, 2)},
