@@ -38,6 +38,7 @@
 // each workgroup walks through the phases at its own pace and waits only for the data it needs.
 #pragma once
 #include "ps_internal.h"
+#include <type_traits>
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
@@ -1262,9 +1263,11 @@ __device__ __forceinline__ void attn_phase(const StepParams& P, int wg, int nwg,
         attn_place_q<WT, D>(P, cur, 0, Ra, grp, tid, qx, sQ);
     }
     __syncthreads();
-    for (int item = wg; item < P.attn_items; item += nwg) {
-        const bool has_next = item + nwg < P.attn_items;
-        const AttnItem nx = has_next ? attn_decode(P, item + nwg, CH_LOG) : cur;
+    // One work item.  RQ: the loads of a following item nx are requested here: if there is none
+    // (has_next false) they are harmless, clamped loads of the same item, so that the body stays
+    // straight-line code.  A workgroup with a single item uses the variant without requests.
+    auto do_item = [&](int item, const AttnItem nx, bool has_next, auto RQ) __attribute__((always_inline)) {
+        constexpr bool requests = decltype(RQ)::value;
         const int b = cur.b, hk = cur.hk, ch = cur.ch, nch = cur.nch, L = cur.L;
         const int key0 = ch * CH + wkey;            // this wavefront's keys: positions key0 .. key0 + 16 NK - 1
         const int end = L + P.M;                    // positions that exist
@@ -1295,7 +1298,7 @@ __device__ __forceinline__ void attn_phase(const StepParams& P, int wg, int nwg,
             }
             if (!last_pass) {              // request the query rows of the next pass,
                 qx = attn_issue_q<WT, D>(P, cur, r0 + 16, Ra, grp, tid);
-            } else {                       // or, the K rows being consumed, the next item's K and query rows
+            } else if constexpr (requests) {   // or, the K rows being consumed, the next item's K and query rows
 #pragma unroll
                 for (int j = 0; j < NK; ++j) attn_load_k<WT, D>(P, nx, nx.ch * CH + wkey + 16 * j, lane, kreg[j], has_next);
                 qx = attn_issue_q<WT, D>(P, nx, 0, Ra, grp, tid);
@@ -1341,7 +1344,8 @@ __device__ __forceinline__ void attn_phase(const StepParams& P, int wg, int nwg,
                 float v[16][DPL];
                 attn_finish_v<WT, D>(P, cur, key0, lane, vraw[0], v);
                 // the raw V rows are consumed: request the next item's, ahead of the arithmetic
-                if (last_pass) attn_issue_v<WT, D>(P, nx, nx.ch * CH + wkey, lane, vraw[0], has_next);
+                if constexpr (requests)
+                    if (last_pass) attn_issue_v<WT, D>(P, nx, nx.ch * CH + wkey, lane, vraw[0], has_next);
                 for (int rr = 0; rr < nr; ++rr) {
                     const f32x4* prow = reinterpret_cast<const f32x4*>(sP + (wave * 16 + rr) * 16);
                     float o[DPL];
@@ -1369,7 +1373,8 @@ __device__ __forceinline__ void attn_phase(const StepParams& P, int wg, int nwg,
                 for (int j = 0; j < NK; ++j) {
                     float v[16][DPL];
                     attn_finish_v<WT, D>(P, cur, key0 + 16 * j, lane, vraw[j], v);
-                    if (last_pass) attn_issue_v<WT, D>(P, nx, nx.ch * CH + wkey + 16 * j, lane, vraw[j], has_next);
+                    if constexpr (requests)
+                        if (last_pass) attn_issue_v<WT, D>(P, nx, nx.ch * CH + wkey + 16 * j, lane, vraw[j], has_next);
 #pragma unroll
                     for (int rr = 0; rr < 16; ++rr) {
                         if (rr < nr) {   // wavefront-uniform
@@ -1396,7 +1401,7 @@ __device__ __forceinline__ void attn_phase(const StepParams& P, int wg, int nwg,
             // every wavefront has read this pass's query rows (before the pass's first barrier):
             // the next ones take their place; they are read after the barrier below
             if (!last_pass) attn_place_q<WT, D>(P, cur, r0 + 16, Ra, grp, tid, qx, sQ);
-            else if (has_next) attn_place_q<WT, D>(P, nx, 0, Ra, grp, tid, qx, sQ);
+            else if (requests && has_next) attn_place_q<WT, D>(P, nx, 0, Ra, grp, tid, qx, sQ);
             __syncthreads();
             stamp(P, wg, 48);
             // ---- add the wavefronts' parts in order.  SINGLE: a fixed number of rounds; threads beyond
@@ -1444,6 +1449,14 @@ __device__ __forceinline__ void attn_phase(const StepParams& P, int wg, int nwg,
         }
         cur = nx;
         stamp(P, wg, 34);
+    };
+    if (wg + nwg >= P.attn_items) {
+        if (wg < P.attn_items) do_item(wg, cur, false, std::false_type());
+    } else {
+        for (int item = wg; item < P.attn_items; item += nwg) {
+            const bool has_next = item + nwg < P.attn_items;
+            do_item(item, has_next ? attn_decode(P, item + nwg, CH_LOG) : cur, has_next, std::true_type());
+        }
     }
 
     // ---- sequences cut into several blocks: put the blocks' partial results together.  One work
