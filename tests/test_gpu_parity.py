@@ -73,6 +73,24 @@ def test_ragged_batch_many_rows_bf16():
     _run_case(wl)
 
 
+@pytest.mark.parametrize("plan", [
+    "qkv:1:1,oproj:1:1,gateup:1:1,down:1:1,lm:1:1",
+    "qkv:1:8,oproj:2:4,gateup:4:2,down:8:1,lm:1:8",
+    "qkv:1:4,oproj:4:2,gateup:2:4,down:2:2,lm:1:2",
+    "qkv:1:2,oproj:8:1,gateup:8:1,down:4:2,lm:1:4",
+])
+def test_every_k_split_of_the_gemm_engine(plan, monkeypatch):
+    """The way a phase's contraction dimension is shared (K-slices across workgroups x wavefronts per
+    tile) is normally chosen by the library; PS_DRAFT_PLAN forces other splits, all of which must
+    give the same results.  One and three MFMA column tiles."""
+    monkeypatch.setenv("PS_DRAFT_PLAN", plan)
+    shape = small_shape("bf16", hidden=1024, n_heads=8, n_kv_heads=4, head_dim=128, ffn=2752, vocab=4000)
+    wl = Workload("plans", shape, batch=1, kv_len=(300,), n_new=1, k=5, topk=8, seed=31)
+    _run_case(wl, label="plan " + plan)
+    wl3 = Workload("plans3", shape, batch=7, kv_len=(5, 130, 64, 700, 0, 256, 33), n_new=2, k=4, topk=8, seed=32)
+    _run_case(wl3, label="plan " + plan + " (42 rows)")
+
+
 def test_changing_shapes_on_one_context():
     """Row layout, column tiles and K-slice plan change from step to step on ONE context: exchange-buffer
     slots a step does not write must never look written to a later step (two alternating copies)."""
