@@ -1039,7 +1039,7 @@ __device__ __forceinline__ AttnItem attn_decode(const StepParams& P, int item, i
     AttnItem it;
     int b = 0, rem = item, nch = 0;
     for (;; ++b) {
-        nch = (P.kv_len[b] + P.M + (1 << ch_log) - 1) >> ch_log;
+        nch = (P.kv_len[b] + P.attn_tail + (1 << ch_log) - 1) >> ch_log;
         if (rem < nch * P.nkv) break;
         rem -= nch * P.nkv;
     }
@@ -1056,13 +1056,13 @@ __device__ __forceinline__ void attn_load_k(const StepParams& P, const AttnItem&
     constexpr bool BF = Traits<WT>::BF;
     constexpr int ESZ = Traits<WT>::ESZ, GE = Traits<WT>::GE, KSTEP = Traits<WT>::KSTEP, NL = GE / 4, STEPS = D / KSTEP;
     const int c = lane & 15, kb = lane >> 4;
-    const int L = it.L, end = L + P.M;
+    const int L = it.L, end = L + P.attn_tail;
     const int kpos = key0 + c;
     const int pc = kpos < L ? kpos : (L > 0 ? L - 1 : 0);
     const char* krow = (const char*)P.kc + (((size_t)P.kv_off[it.b] + pc) * P.nkv + it.hk) * D * ESZ + kb * 16;
 #pragma unroll
     for (int t = 0; t < STEPS; ++t) kreg[t] = ld16(krow + t * 64);
-    if (with_new && key0 + 15 >= L && key0 < end) {
+    if (with_new && end > L && key0 + 15 >= L && key0 < end) {
         const rsrc_t rn = make_rsrc(act_ptr(P, P.kvnew));
         const bool k_new = kpos >= L;
         const int pn = kpos < L ? L : (kpos < end ? kpos : end - 1);
@@ -1120,7 +1120,7 @@ __device__ __forceinline__ void attn_issue_v(const StepParams& P, const AttnItem
                                              typename VRaw<WT, D / 64>::type (&vraw)[16], bool with_new = true) {
     constexpr int ESZ = Traits<WT>::ESZ, DPL = D / 64;
     typedef typename VRaw<WT, DPL>::type raw_t;
-    const int L = it.L, end = L + P.M;
+    const int L = it.L, end = L + P.attn_tail;
     const size_t cache_row0 = (size_t)P.kv_off[it.b] * P.nkv + it.hk;   // in units of D elements
 #pragma unroll
     for (int kk = 0; kk < 16; ++kk) {
@@ -1128,7 +1128,7 @@ __device__ __forceinline__ void attn_issue_v(const StepParams& P, const AttnItem
         const int pc = pos < L ? pos : (L > 0 ? L - 1 : 0);
         vraw[kk] = *reinterpret_cast<const raw_t*>((const char*)P.vc + ((cache_row0 + (size_t)pc * P.nkv) * D + DPL * lane) * ESZ);
     }
-    if (with_new && key0 + 15 >= L && key0 < end) {
+    if (with_new && end > L && key0 + 15 >= L && key0 < end) {
         // rows written in this step: from the exchange buffer, as soon as the QKV phase has published
         // them; they are exactly representable in the storage type (they were rounded to it)
         const rsrc_t rn = make_rsrc(act_ptr(P, P.kvnew));
@@ -1161,7 +1161,7 @@ template <typename WT, int D>
 __device__ __forceinline__ void attn_finish_v(const StepParams& P, const AttnItem& it, int key0, int lane,
                                               const typename VRaw<WT, D / 64>::type (&vraw)[16], float (&v)[16][D / 64]) {
     constexpr int DPL = D / 64;
-    const int end = it.L + P.M;
+    const int end = it.L + P.attn_tail;
 #pragma unroll
     for (int kk = 0; kk < 16; ++kk) {
         widen_v(vraw[kk], v[kk]);
@@ -1270,7 +1270,7 @@ __device__ __forceinline__ void attn_phase(const StepParams& P, int wg, int nwg,
         constexpr bool requests = decltype(RQ)::value;
         const int b = cur.b, hk = cur.hk, ch = cur.ch, nch = cur.nch, L = cur.L;
         const int key0 = ch * CH + wkey;            // this wavefront's keys: positions key0 .. key0 + 16 NK - 1
-        const int end = L + P.M;                    // positions that exist
+        const int end = L + P.attn_tail;            // positions the blocks cover (see attn_sep)
         stamp(P, wg, 44);
 
         for (int r0 = 0; r0 < (SINGLE ? 16 : Ra); r0 += 16) {       // 16 query rows per pass
@@ -1421,7 +1421,7 @@ __device__ __forceinline__ void attn_phase(const StepParams& P, int wg, int nwg,
                 for (int w = 0; w < PS_WAVES; ++w) { o += sO[(w * 16 + rr) * D + dd]; l += sL[w * 16 + rr]; }
                 const int rho2 = r0 + rr;
                 const int gi2 = row_seq(P, rho2), i2 = rho2 - gi2 * P.M;
-                if (nch == 1) {
+                if (nch == 1 && !P.attn_sep) {
                     // the only chunk: normalise and hand the row to the output projection
                     sx_st1(ro, (unsigned)((size_t)(b * P.M + i2) * P.QD + (hk * grp + gi2) * D + dd), o / l);
                 } else {
@@ -1438,7 +1438,7 @@ __device__ __forceinline__ void attn_phase(const StepParams& P, int wg, int nwg,
                 }
             }
             if constexpr (SINGLE) {
-                if (nch > 1) {   // (max, sum) of row tid / 2: one store per thread, the surplus threads repeat the last
+                if (nch > 1 || P.attn_sep) {   // (max, sum) of row tid / 2: one store per thread, the surplus threads repeat the last
                     const int e = min(tid, 2 * nr - 1), rr = e >> 1;
                     float mr = -INFINITY, l = 0.f;
 #pragma unroll
@@ -1472,8 +1472,8 @@ __device__ __forceinline__ void attn_phase(const StepParams& P, int wg, int nwg,
     for (int mi = wg; mi < P.attn_merge_items; mi += nwg) {
         int b = 0, rem = mi, nch = 0, item_base = 0;
         for (;; ++b) {
-            nch = (P.kv_len[b] + P.M + CH - 1) >> CH_LOG;
-            const int n = nch > 1 ? P.nkv * RT : 0;
+            nch = (P.kv_len[b] + P.attn_tail + CH - 1) >> CH_LOG;
+            const int n = (nch > 1 || P.attn_sep) ? P.nkv * RT : 0;
             if (rem < n) break;
             rem -= n;
             item_base += nch * P.nkv;
@@ -1571,6 +1571,86 @@ __device__ __forceinline__ void attn_phase(const StepParams& P, int wg, int nwg,
                     den = den * so + lg * sn;
                     mrun = mnew;
                 }
+            }
+        }
+        if (P.attn_sep) {
+            // The rows written in this step are not part of any block: wavefront w works out row w's
+            // attention over them (at most 16 keys, a lane owns DPL columns of q, K and V, the dot
+            // products are wavefront sums) and the result is folded in like one more group of blocks.
+            __syncthreads();                         // sM, sL and the output area are free
+            if (wave < nr) {
+                const int rho = r0 + wave;
+                const int gi = row_seq(P, rho), i = rho - gi * P.M;
+                const rsrc_t rq = make_rsrc(act_ptr(P, P.q_buf)), rn = make_rsrc(act_ptr(P, P.kvnew));
+                const unsigned qo = (unsigned)((size_t)(b * P.M + i) * P.QD + (hk * grp + gi) * D + DPL * lane);
+                float q[DPL], kx[16][DPL], vx[16][DPL];
+                auto issue_new = [&]() __attribute__((always_inline)) {
+#pragma unroll
+                    for (int e = 0; e < DPL; ++e) q[e] = coh_ld_f(rq, (qo + e) * 4);
+#pragma unroll
+                    for (int jj = 0; jj < 16; ++jj) {
+                        const int jc = jj < P.M ? jj : P.M - 1;     // clamped: every load is unconditional
+                        const unsigned ko = (unsigned)(((size_t)(b * P.M + jc) * 2) * P.KVD + hk * D + DPL * lane);
+#pragma unroll
+                        for (int e = 0; e < DPL; ++e) {
+                            kx[jj][e] = coh_ld_f(rn, (ko + e) * 4);
+                            vx[jj][e] = coh_ld_f(rn, (ko + P.KVD + e) * 4);
+                        }
+                    }
+                };
+                auto bad_new = [&]() __attribute__((always_inline)) {
+                    unsigned bad = 0;
+#pragma unroll
+                    for (int e = 0; e < DPL; ++e) bad |= (unsigned)(__float_as_uint(q[e]) == PS_SENT);
+#pragma unroll
+                    for (int jj = 0; jj < 16; ++jj)
+#pragma unroll
+                        for (int e = 0; e < DPL; ++e)
+                            bad |= (unsigned)(__float_as_uint(kx[jj][e]) == PS_SENT) | (unsigned)(__float_as_uint(vx[jj][e]) == PS_SENT);
+                    return bad;
+                };
+                issue_new();
+                if (!__all(!bad_new())) {
+                    int spins = 0;
+                    do issue_new(); while (!__all(!bad_new()) && spin_again(P, spins));
+                }
+                float sc[16], mn = -INFINITY;
+#pragma unroll
+                for (int jj = 0; jj < 16; ++jj) {
+                    sc[jj] = -INFINITY;
+                    if (jj <= i) {                   // wavefront-uniform: row i sees the rows 0 .. i of this step
+                        float part = 0.f;
+#pragma unroll
+                        for (int e = 0; e < DPL; ++e) part += q[e] * kx[jj][e];
+                        sc[jj] = wave_sum(part) * P.inv_sqrt_d;
+                        mn = fmaxf(mn, sc[jj]);
+                    }
+                }
+                float ln = 0.f, on[DPL];
+#pragma unroll
+                for (int e = 0; e < DPL; ++e) on[e] = 0.f;
+#pragma unroll
+                for (int jj = 0; jj < 16; ++jj) {
+                    if (jj <= i) {
+                        const float pj = expf(sc[jj] - mn);
+                        ln += pj;
+#pragma unroll
+                        for (int e = 0; e < DPL; ++e) on[e] += pj * vx[jj][e];
+                    }
+                }
+#pragma unroll
+                for (int e = 0; e < DPL; ++e) sO[wave * D + DPL * lane + e] = on[e];
+                if (lane == 0) { sM[wave] = mn; sL[wave] = ln; }
+            }
+            __syncthreads();
+            if (active) {
+                const float mg = sM[myrow], lg = sL[myrow];
+                const float mnew = fmaxf(mrun, mg);
+                const float so = expf(mrun - mnew), sn = expf(mg - mnew);
+                num0 = num0 * so + sO[myrow * D + 2 * dp] * sn;
+                num1 = num1 * so + sO[myrow * D + 2 * dp + 1] * sn;
+                den = den * so + lg * sn;
+                mrun = mnew;
             }
         }
         if (active) {

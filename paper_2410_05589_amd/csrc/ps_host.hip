@@ -51,6 +51,7 @@ struct ps_draft_ctx {
     int* counters;
     int n_counters;
     int plan_override[PH_COUNT][2];   // K-slices, wavefronts per tile from PS_DRAFT_PLAN (0 = automatic)
+    int attn_sep_override;            // PS_DRAFT_ATTN_SEP=0/1: who takes this step's rows in the attention (-1 = automatic)
     size_t off_frag[PH_COUNT], off_ssqf[PH_COUNT];
     bool profile;
     unsigned long long* timeline;
@@ -257,6 +258,10 @@ extern "C" int ps_draft_init(ps_draft_ctx** out, const ps_draft_config* config, 
     ctx->lm_part = (float*)(base + L.lm_part);
     ctx->logits_ws = (float*)(base + L.logits_ws);
     parse_plan_override(ctx);
+    {
+        const char* e = getenv("PS_DRAFT_ATTN_SEP");
+        ctx->attn_sep_override = (e && (e[0] == '0' || e[0] == '1')) ? e[0] - '0' : -1;
+    }
     ctx->profile = false;
     ctx->timeline = nullptr;
 
@@ -469,14 +474,24 @@ extern "C" int ps_draft_step(ps_draft_ctx* ctx, const ps_draft_step_args* a, voi
     // attention work items: (sequence, kv head, block of ch keys)
     const int ra = (c.n_heads / c.n_kv_heads) * M;
     const int ch = PS_ATTN_KEYS * PS_ATTN_NK;
-    int items = 0;
-    for (int b = 0; b < a->batch; ++b) items += c.n_kv_heads * ((a->kv_len[b] + M + ch - 1) / ch);
-    P.attn_items = items; P.attn_single = ra <= 16;
+    // The M rows of this step normally belong to the last key block of their sequence.  When they alone
+    // make up that block (or spill into one more) and leaving them out spares the workgroups a whole
+    // round of work items, the merge items take them instead (at most 16 rows: they are kept in registers).
+    int items = 0, items_wo = 0;
+    for (int b = 0; b < a->batch; ++b) {
+        items += c.n_kv_heads * ((a->kv_len[b] + M + ch - 1) / ch);
+        items_wo += c.n_kv_heads * ((a->kv_len[b] + ch - 1) / ch);
+    }
+    bool sep = M <= 16 && (items_wo + ctx->n_cu - 1) / ctx->n_cu < (items + ctx->n_cu - 1) / ctx->n_cu;
+    if (ctx->attn_sep_override >= 0 && M <= 16) sep = ctx->attn_sep_override != 0;
+    if (sep) items = items_wo;
+    const int tail = sep ? 0 : M;
+    P.attn_items = items; P.attn_single = ra <= 16; P.attn_sep = sep ? 1 : 0; P.attn_tail = tail;
     {   // sequences that span several key blocks are put together by (sequence, kv head, 8 rows) work items
         const int rt = (ra + PS_WAVES - 1) / PS_WAVES;
         int mi = 0;
         for (int b = 0; b < a->batch; ++b)
-            if ((a->kv_len[b] + M + ch - 1) / ch > 1) mi += c.n_kv_heads * rt;
+            if (sep || (a->kv_len[b] + tail + ch - 1) / ch > 1) mi += c.n_kv_heads * rt;
         P.attn_merge_items = mi;
         const int want = items > mi ? items : mi;
         P.attn_nwg = want < ctx->n_cu ? want : ctx->n_cu;

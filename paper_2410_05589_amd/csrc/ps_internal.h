@@ -98,6 +98,10 @@ struct StepParams {
     // attention work list
     int attn_items, attn_nwg;   // work items; workgroups of the attention kernel (multi mode)
     int attn_single;        // the g*M query rows of a kv head fit in one pass of 16
+    // The rows written in this step are either the tail of the sequence's last key block (attn_tail = M,
+    // attn_sep = 0), or no block's business: then the work items that put the blocks together also do
+    // the attention over these rows (attn_tail = 0, attn_sep = 1; see ps_draft_step for when)
+    int attn_tail, attn_sep;
     int attn_merge_items;   // (sequence, kv head, 8 query rows) of the sequences that span several key blocks
     int fused_nwg, fused_lds;
     long long kv_off[PS_MAX_ROWS];

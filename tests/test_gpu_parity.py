@@ -91,6 +91,20 @@ def test_every_k_split_of_the_gemm_engine(plan, monkeypatch):
     _run_case(wl3, label="plan " + plan + " (42 rows)")
 
 
+def test_new_rows_left_to_the_merge_items():
+    """When this step's rows alone would make up one more key block per sequence and that block would
+    cost the workgroups a second round of attention work items (more items than compute units), the
+    merge items take these rows instead.  8 sequences x 8 kv heads, KV lengths that are multiples of the
+    block size (one of them 0): 256 block items instead of 320."""
+    shape = small_shape("bf16", hidden=1024, n_heads=8, n_kv_heads=8, head_dim=128, ffn=1376, vocab=2000)
+    wl = Workload("sep", shape, batch=8, kv_len=(0, 1024, 512, 512, 512, 512, 512, 512), n_new=1, k=5, topk=8, seed=33)
+    _run_case(wl)
+    # grouped queries: 2 query heads per kv head, 9 rows -> 18 query rows per kv head (two passes of 16)
+    shape2 = small_shape("bf16", hidden=1024, n_heads=16, n_kv_heads=8, head_dim=64, ffn=1376, vocab=2000)
+    wl2 = Workload("sep gqa", shape2, batch=4, kv_len=(1024,) * 4, n_new=1, k=8, topk=8, seed=34)
+    _run_case(wl2)
+
+
 def test_changing_shapes_on_one_context():
     """Row layout, column tiles and K-slice plan change from step to step on ONE context: exchange-buffer
     slots a step does not write must never look written to a later step (two alternating copies)."""
