@@ -410,6 +410,35 @@ static bool make_desc(PhaseDesc* d, int ph, int T, int Kt, int K, int rows, int 
     return false;
 }
 
+// Testing aid, not declared in the public header; runs on the host alone.  For a configuration and the
+// shape of a step it reports how ps_draft_step would cut up the five GEMM phases on a device with
+// n_cu compute units and lds_limit bytes of LDS per workgroup (persistent-kernel mode): per phase
+// PS_PLAN_FIELDS ints {T, Kt, K, rows, kw_log, s_log, Gs, per_round, rounds, piece_groups, npieces, lds_bytes}.
+#define PS_PLAN_FIELDS 12
+extern "C" __attribute__((visibility("default"))) int ps_draft_debug_plan(const ps_draft_config* c, int batch, int n_new,
+                                                                          int k, int all_rows, int n_cu, int lds_limit,
+                                                                          int* out) {
+    if (!c || !out) return PS_ERR_NULL;
+    const int st = validate_config(c);
+    if (st != PS_OK) return st;
+    if (batch < 1 || batch > c->max_batch || n_new < 1 || n_new > c->max_new || k < 0 || k > c->k_max) return PS_ERR_SHAPE;
+    if (n_cu < 1 || n_cu > 1024 || lds_limit < 64 * 1024 || lds_limit > PS_LDS_BYTES) return PS_ERR_SHAPE;
+    const int M = n_new + k, Mtot = batch * M, Rtot = batch * (all_rows ? M : k + 1);
+    const int none[2] = {0, 0};
+    int T[PH_COUNT], Kt[PH_COUNT], K[PH_COUNT];
+    phase_dims(c, T, Kt, K);
+    for (int ph = 0; ph < PH_COUNT; ++ph) {
+        PhaseDesc d;
+        const int rows = ph == PH_LMHEAD ? Rtot : Mtot;
+        if (!make_desc(&d, ph, T[ph], Kt[ph], K[ph], rows, (Mtot + 15) / 16, c->dtype == PS_BF16, n_cu, none, lds_limit))
+            return PS_ERR_UNSUPPORTED;
+        const int v[PS_PLAN_FIELDS] = {d.T, d.Kt, d.K, d.rows, d.kw_log, d.s_log, d.Gs, d.per_round, d.rounds,
+                                       d.piece_groups, d.npieces, d.lds_bytes};
+        for (int i = 0; i < PS_PLAN_FIELDS; ++i) out[ph * PS_PLAN_FIELDS + i] = v[i];
+    }
+    return PS_OK;
+}
+
 extern "C" int ps_draft_step(ps_draft_ctx* ctx, const ps_draft_step_args* a, void* stream) {
     if (!ctx || !a) return PS_ERR_NULL;
     const ps_draft_config& c = ctx->cfg;

@@ -133,3 +133,85 @@ def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(B, "LIB_PATH", "/nonexistent/libps_draft.so")
     with pytest.raises(RuntimeError, match="no CPU fallback"):
         B.load_library()
+
+
+PLAN_FIELDS = ("T", "Kt", "K", "rows", "kw_log", "s_log", "Gs", "per_round", "rounds", "piece_groups", "npieces",
+               "lds_bytes")
+PS_U, PS_WAVES = 8, 8
+
+
+def _plan(lib, cfg, batch, n_new, k, n_cu=256, lds=160 * 1024, all_rows=0):
+    lib.ps_draft_debug_plan.restype = ctypes.c_int
+    out = (ctypes.c_int * (5 * len(PLAN_FIELDS)))()
+    st = lib.ps_draft_debug_plan(ctypes.byref(cfg), batch, n_new, k, all_rows, n_cu, lds, out)
+    if st != B.PS_OK:
+        return st, None
+    vals = list(out)
+    n = len(PLAN_FIELDS)
+    return st, [dict(zip(PLAN_FIELDS, vals[p * n:(p + 1) * n])) for p in range(5)]
+
+
+def _check_plan(cfg, plans, batch, n_new, k, n_cu, lds):
+    """What the device code relies on (it has no bounds checks of its own for these)."""
+    esz_step = 32 if cfg.dtype == B.PS_BF16 else 16          # elements per 64-byte step
+    for ph, d in enumerate(plans):
+        tag = (ph, d, batch, n_new, k, n_cu, lds)
+        S, KW = 1 << d["s_log"], 1 << d["kw_log"]
+        assert d["Kt"] % PS_U == 0 and d["Kt"] * esz_step >= d["K"] > (d["Kt"] - PS_U) * esz_step, tag
+        assert 1 <= KW <= PS_WAVES and 1 <= S <= 8, tag
+        if ph == 4:
+            assert S == 1, tag                                 # the LM head keeps a row's logits in one workgroup
+            assert min(n_cu, d["T"]) <= 512, tag               # one thread per workgroup in the final merge
+        assert d["Gs"] == n_cu >> d["s_log"] and d["Gs"] >= 1, tag
+        assert d["per_round"] == d["Gs"] * (PS_WAVES >> d["kw_log"]), tag
+        assert d["rounds"] == -(-d["T"] // d["per_round"]), tag    # every tile is taken exactly once
+        ng = d["Kt"] // PS_U
+        sizes = [((ng * (s + 1)) >> d["s_log"]) - ((ng * s) >> d["s_log"]) for s in range(S)]
+        pg, npc = d["piece_groups"], d["npieces"]
+        assert min(sizes) >= 1 and pg >= KW, tag
+        for sz in sizes:
+            assert -(-sz // pg) == npc, tag                    # the slices walk through their pieces in step
+            assert sz - (npc - 1) * pg >= KW, tag              # every piece gives each wavefront of a tile a group
+        assert d["lds_bytes"] <= lds, tag
+        arrays = 2 if cfg.dtype == B.PS_BF16 else 1
+        assert d["lds_bytes"] >= d["rows"] * arrays * pg * PS_U * 64, tag   # the piece of the panel fits
+
+
+def test_phase_plans_of_the_five_workloads(lib):
+    for name, wl in WORKLOADS.items():
+        n_max = max(wl.n_new_mix) if wl.n_new_mix else wl.n_new
+        cfg = B.make_config(wl.shape, max_batch=wl.batch, max_new=n_max, max_positions=8192, max_topk=wl.topk, k_max=wl.k)
+        for n_new in (sorted(set(wl.n_new_mix)) if wl.n_new_mix else [wl.n_new]):
+            st, plans = _plan(lib, cfg, wl.batch, n_new, wl.k)
+            assert st == B.PS_OK, (name, n_new)
+            _check_plan(cfg, plans, wl.batch, n_new, wl.k, 256, 160 * 1024)
+
+
+def test_phase_plans_over_a_sweep_of_shapes_and_devices(lib):
+    import random
+    rnd = random.Random(7)
+    checked = 0
+    for _ in range(400):
+        dtype = rnd.choice(["bf16", "f32"])
+        mul = 32 if dtype == "bf16" else 16
+        head_dim = rnd.choice([64, 128])
+        n_kv = rnd.choice([1, 2, 4, 8])
+        n_heads = n_kv * rnd.choice([1, 2, 4])
+        hidden = n_heads * head_dim
+        ffn = mul * rnd.randint(1, 500)
+        vocab = rnd.randint(16, 200000)
+        shape = small_shape(dtype, hidden=hidden, n_heads=n_heads, n_kv_heads=n_kv, head_dim=head_dim, ffn=ffn, vocab=vocab)
+        k = rnd.randint(0, 8)
+        n_new = rnd.randint(1, 6)
+        grp = n_heads // n_kv
+        batch = rnd.randint(1, max(1, min(8, 64 // (n_new + k), 64 // (grp * (n_new + k)) if grp * (n_new + k) <= 64 else 1)))
+        if grp * (n_new + k) > 64 or batch * (n_new + k) > 64:
+            continue
+        cfg = B.make_config(shape, max_batch=batch, max_new=n_new, max_positions=4096, max_topk=8, k_max=max(k, 1))
+        for n_cu, lds in ((256, 160 * 1024), (256, 64 * 1024), (304, 160 * 1024), (80, 64 * 1024), (7, 96 * 1024)):
+            st, plans = _plan(lib, cfg, batch, n_new, k, n_cu=n_cu, lds=lds, all_rows=rnd.randint(0, 1))
+            assert st in (B.PS_OK, B.PS_ERR_UNSUPPORTED), (st, hidden, ffn, vocab)
+            if st == B.PS_OK:
+                _check_plan(cfg, plans, batch, n_new, k, n_cu, lds)
+                checked += 1
+    assert checked > 500
