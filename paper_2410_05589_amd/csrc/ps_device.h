@@ -775,7 +775,7 @@ __device__ __forceinline__ void gemm_phase(const StepParams& P, int wg, int wave
     // While the workgroup waits for its activations the memory is idle: besides the PS_U KiB per
     // wavefront that are already on their way into registers (wb), the next PS_PF * 8 KiB of the
     // wavefront's first weight stream are pulled into the L2 of this XCD, one 4-byte load per
-    // 128-byte line.  The values are not used; they stay registers until the panel is staged.
+    // 128-byte line (PS_PF is the most; the host says how many of these 8-KiB pieces: D.pf).  The values are not used; they stay registers until the panel is staged.
     unsigned pf[PS_PF > 0 ? PS_PF : 1];
     if (PS_PF > 0 && tile_index(D, 0, slot, j) < D.T) {
         int a0, n;
@@ -784,7 +784,7 @@ __device__ __forceinline__ void gemm_phase(const StepParams& P, int wg, int wave
 #pragma unroll
         for (int i = 0; i < PS_PF; ++i) {
             const int ln = min(64 * i + (lane16 >> 4), lines - 1);
-            pf[i] = lines > 0 ? *reinterpret_cast<const unsigned*>(wp0 + PS_U * PS_WS + (size_t)ln * 128) : 0u;
+            pf[i] = (lines > 0 && i < D.pf) ? *reinterpret_cast<const unsigned*>(wp0 + PS_U * PS_WS + (size_t)ln * 128) : 0u;
         }
     }
 

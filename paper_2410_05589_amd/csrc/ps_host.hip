@@ -404,6 +404,11 @@ static bool make_desc(PhaseDesc* d, int ph, int T, int Kt, int K, int rows, int 
             while ((1 << g2) < pg * PS_U * 4 && (1 << g2) < PS_WG_THREADS) ++g2;
             d->g2_log = g2;
             d->lds_bytes = fixed + rows * arrays * d->rs + 256;
+            // The longer the wait for the activations (the more of them the previous phase has to
+            // produce), the more weights fit into it: one 8-KiB piece per wavefront for up to ~110 KB of
+            // fp32 activations, two beyond, unless there are several column tiles of rows (then the
+            // workgroups' reads of the panels already keep the L2s busy).  Measured on c1 .. c4.
+            d->pf = (mt == 1 && (long long)rows * K * 4 > 110 * 1024) ? 2 : 1;
             return true;
         }
     }

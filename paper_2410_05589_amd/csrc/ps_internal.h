@@ -20,7 +20,7 @@
 #define PS_U 8             // 16-byte weight loads in flight per lane (PS_U KiB per wavefront)
 #endif
 #ifndef PS_PF
-#define PS_PF 1            // 8-KiB pieces of its first weight stream a wavefront pulls into the L2 while it waits
+#define PS_PF 2            // at most this many 8-KiB pieces of its first weight stream a wavefront pulls into the L2 while it waits
 #endif
 #define PS_U_MAX 32        // packed weight buffers are padded by this many KiB (streaming reads ahead)
 #define PS_LDS_BYTES (160 * 1024)
@@ -61,6 +61,7 @@ struct PhaseDesc {
     int g2_log;        // staging: log2 of the threads laid along the contraction dimension
     int src_ld;        // elements between rows of src
     int lds_bytes;     // dynamic LDS the phase needs
+    int pf;            // 8-KiB pieces of the first stream to pull into the L2 during the wait for the panel (<= PS_PF)
     const void* gain;  // RMSNorm gain (config dtype)
     const float* src;  // exchanged fp32 activations the phase reads (QKV reads x / mask_emb instead)
     const char* wpack; // the phase's matrices, prepacked at init in streaming order
