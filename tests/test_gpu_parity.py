@@ -105,6 +105,26 @@ def test_new_rows_left_to_the_merge_items():
     _run_case(wl2)
 
 
+def test_two_contexts_take_turns_on_one_stream():
+    """Two drafters of different shape and type (own workspaces, own step counters) stepping alternately."""
+    shape_a = small_shape("bf16", hidden=512, n_heads=4, n_kv_heads=4, head_dim=128, ffn=1024, vocab=3001)
+    shape_b = small_shape("f32", vocab=1500)
+    wl_a = Workload("ctx a", shape_a, batch=2, kv_len=(150, 31), n_new=2, k=4, topk=8, seed=35)
+    wl_b = Workload("ctx b", shape_b, batch=1, kv_len=(77,), n_new=1, k=5, topk=4, seed=36)
+    wa, wb = inputs.make_weights(shape_a, wl_a.seed), inputs.make_weights(shape_b, wl_b.seed)
+    da = _drafter(shape_a, wa, max_batch=2, max_new=2, max_positions=200, k_max=4)
+    db = _drafter(shape_b, wb, max_batch=1, max_new=1, max_positions=100, k_max=5)
+    for rep in range(3):
+        inp_a = inputs.make_step_inputs(Workload("ctx a", shape_a, batch=2, kv_len=(150, 31), n_new=2, k=4, topk=8, seed=40 + rep))
+        inp_b = inputs.make_step_inputs(Workload("ctx b", shape_b, batch=1, kv_len=(77,), n_new=1, k=5, topk=4, seed=50 + rep))
+        res_a = run_gpu_step(da, inp_a, 2, 4, 8)
+        res_b = run_gpu_step(db, inp_b, 1, 5, 4)
+        compare_with_oracle(shape_a, res_a, oracle_step(shape_a, wa, inp_a, 2, 4, 8), inp_a, 2, 4, 8)
+        compare_with_oracle(shape_b, res_b, oracle_step(shape_b, wb, inp_b, 1, 5, 4), inp_b, 1, 5, 4)
+    da.close()
+    db.close()
+
+
 def test_changing_shapes_on_one_context():
     """Row layout, column tiles and K-slice plan change from step to step on ONE context: exchange-buffer
     slots a step does not write must never look written to a later step (two alternating copies)."""
