@@ -775,7 +775,8 @@ __device__ __forceinline__ void gemm_phase(const StepParams& P, int wg, int wave
     // While the workgroup waits for its activations the memory is idle: besides the PS_U KiB per
     // wavefront that are already on their way into registers (wb), the next PS_PF * 8 KiB of the
     // wavefront's first weight stream are pulled into the L2 of this XCD, one 4-byte load per
-    // 128-byte line (PS_PF is the most; the host says how many of these 8-KiB pieces: D.pf).  The values are not used; they stay registers until the panel is staged.
+    // 128-byte line (PS_PF is the most; the host says how many of these 8-KiB pieces: D.pf).  The
+    // values are not used; they stay registers until the panel is staged.
     unsigned pf[PS_PF > 0 ? PS_PF : 1];
     if (PS_PF > 0 && tile_index(D, 0, slot, j) < D.T) {
         int a0, n;
