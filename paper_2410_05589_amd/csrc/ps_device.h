@@ -194,6 +194,34 @@ __device__ __forceinline__ void sx_st1(const SxBuf& b, unsigned i, float v) {
     coh_st4(b.cur, i * 4, __float_as_uint(v));
     coh_st4(b.alt, i * 4, PS_SENT);
 }
+// The row buffers may hold rows of an earlier, larger step beyond this step's Mtot rows (the host
+// keeps count: P.rows_reset rows may have been written since the buffers were last cleared).  Nobody
+// touches those rows in this step, and whoever writes a row resets it in the other copy - but only the
+// rows of this step.  So all workgroups together mark rows [Mtot, rows_reset) of the other copy "not
+// written" here; the next step, which may have more rows again, then finds its whole copy clean.
+__device__ __forceinline__ void sx_reset_rows_beyond(const StepParams& P, int wg, int nwg) {
+    if (P.rows_reset <= P.Mtot) return;
+    const unsigned par = ps_seq() & 1u;
+    const u32x4 sent = {PS_SENT, PS_SENT, PS_SENT, PS_SENT};
+    const float* bufs[6] = {P.q_buf, P.kvnew, P.o_buf, P.y_buf, P.u_buf, P.y2_buf};
+    const int lds[6] = {P.QD, 2 * P.KVD, P.QD, P.H, P.F, P.H};      // elements per row: multiples of 4
+#pragma unroll
+    for (int i = 0; i < 6; ++i) {
+        const rsrc_t alt = make_rsrc(reinterpret_cast<const char*>(bufs[i]) + (1u - par) * P.act_bytes);
+        const unsigned lo = (unsigned)P.Mtot * lds[i], hi = (unsigned)P.rows_reset * lds[i];
+        for (unsigned e = lo + 4u * (wg * PS_WG_THREADS + threadIdx.x); e < hi; e += 4u * nwg * PS_WG_THREADS)
+            coh_st16(alt, e * 4, sent);
+    }
+    if (wg == 0) {   // the K-slices' sums of squares: [slice][PS_MAX_ROWS] per phase
+        for (int ph = 0; ph < PH_COUNT; ++ph) {
+            if (!P.ph[ph].ssq_frag) continue;
+            const rsrc_t alt = make_rsrc(reinterpret_cast<const char*>(P.ph[ph].ssq_frag) + (1u - par) * P.act_bytes);
+            const int nrow = P.rows_reset - P.Mtot;
+            for (int x = threadIdx.x; x < 8 * nrow; x += PS_WG_THREADS)
+                coh_st4(alt, (unsigned)((x / nrow) * PS_MAX_ROWS + P.Mtot + x % nrow) * 4, PS_SENT);
+        }
+    }
+}
 __device__ __forceinline__ bool sx_ok(u32x4 x) {
     return x[0] != PS_SENT && x[1] != PS_SENT && x[2] != PS_SENT && x[3] != PS_SENT;
 }
@@ -1820,6 +1848,7 @@ template <typename WT, int D, int NK, bool SINGLE>
 __global__ void __launch_bounds__(PS_WG_THREADS) attn_kernel(const StepParams P) {
     extern __shared__ __attribute__((aligned(256))) char smem[];
     step_begin(P, false);
+    sx_reset_rows_beyond(P, blockIdx.x, gridDim.x);
     attn_phase<WT, D, NK, SINGLE>(P, blockIdx.x, gridDim.x, __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), smem);
 }
 
@@ -1873,6 +1902,7 @@ __global__ void __launch_bounds__(PS_WG_THREADS, 1) fused_kernel(const StepParam
     // output row m is merged by workgroup m mod gridDim.x
     stamp(P, wg, 40);
     for (int m = wg; m < P.Rtot; m += gridDim.x) lm_merge_row(P, m, wave, smem + 256);
+    sx_reset_rows_beyond(P, wg, gridDim.x);   // here most workgroups have nothing left to do
     step_end(P, ticket, gridDim.x);
     stamp(P, wg, 62);
     stamp_wall(P, wg, 63);

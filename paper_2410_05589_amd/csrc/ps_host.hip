@@ -44,7 +44,7 @@ struct ps_draft_ctx {
     char* act_base;                   // two copies of the activation buffers, act_bytes each
     size_t act_bytes;
     size_t off_q, off_o, off_y, off_u, off_y2, off_kvnew;   // offsets inside one copy
-    int last_shape[3];                // batch, n_new, k of the previous step
+    int rows_dirty;                   // most activation rows a step has used since the exchange buffers were last cleared
     unsigned last_frag_sig;           // column tiles and K-slices per phase of the previous step
     size_t act_small;                 // bytes of a copy whose slots in use depend on the shape only
     char* wpack[PH_COUNT];
@@ -248,7 +248,7 @@ extern "C" int ps_draft_init(ps_draft_ctx** out, const ps_draft_config* config, 
     ctx->off_q = L.off_q; ctx->off_o = L.off_o; ctx->off_y = L.off_y; ctx->off_u = L.off_u;
     ctx->off_y2 = L.off_y2; ctx->off_kvnew = L.off_kvnew;
     for (int ph = 0; ph < PH_COUNT; ++ph) { ctx->off_frag[ph] = L.off_frag[ph]; ctx->off_ssqf[ph] = L.off_ssqf[ph]; }
-    ctx->last_shape[0] = ctx->last_shape[1] = ctx->last_shape[2] = -1;
+    ctx->rows_dirty = 0;
     ctx->last_frag_sig = 0; ctx->act_small = L.act_small;
     ctx->attn_acc = (float*)(base + L.attn_acc);
     ctx->attn_ml = (float*)(base + L.attn_ml);
@@ -489,16 +489,18 @@ extern "C" int ps_draft_step(ps_draft_ctx* ctx, const ps_draft_step_args* a, voi
     P.act_bytes = (long long)ctx->act_bytes;
     P.q_buf = (float*)(act0 + ctx->off_q); P.o_buf = (float*)(act0 + ctx->off_o); P.y_buf = (float*)(act0 + ctx->off_y);
     P.u_buf = (float*)(act0 + ctx->off_u); P.y2_buf = (float*)(act0 + ctx->off_y2); P.kvnew = (float*)(act0 + ctx->off_kvnew);
-    // A step only resets the elements it writes: when the row layout changes, elements the previous
-    // step did not touch could still look written, so the part of both copies whose slots depend on the
-    // rows is cleared first (the K-slice fragments further down, once the plan is known).
-    if (ctx->last_shape[0] != a->batch || ctx->last_shape[1] != a->n_new || ctx->last_shape[2] != a->k) {
-        if (ctx->last_shape[0] >= 0)
-            for (int cp = 0; cp < 2; ++cp)
-                if (!hip_ok(hipMemsetAsync(act0 + (size_t)cp * ctx->act_bytes, 0xFF, ctx->act_small, (hipStream_t)stream), "hipMemsetAsync"))
-                    return PS_ERR_DEVICE;
-        ctx->last_shape[0] = a->batch; ctx->last_shape[1] = a->n_new; ctx->last_shape[2] = a->k;
+    // A step resets, in the copy the next step uses, the rows it writes and the rows one step's worth
+    // further up (see SxBuf).  So a step with fewer rows than an earlier one needs no clearing as long as
+    // it has at least half as many; below that, the part of both copies that is laid out by rows is
+    // cleared first (the K-slice fragments further down, once the plan is known).
+    if (P.Mtot > ctx->rows_dirty) ctx->rows_dirty = P.Mtot;
+    if (ctx->rows_dirty > 2 * P.Mtot) {
+        for (int cp = 0; cp < 2; ++cp)
+            if (!hip_ok(hipMemsetAsync(act0 + (size_t)cp * ctx->act_bytes, 0xFF, ctx->act_small, (hipStream_t)stream), "hipMemsetAsync"))
+                return PS_ERR_DEVICE;
+        ctx->rows_dirty = P.Mtot;
     }
+    P.rows_reset = ctx->rows_dirty;
     P.logits_store = a->logits ? a->logits : (a->probs ? ctx->logits_ws : nullptr);
     P.top_ids = a->top_ids; P.top_p = a->top_p; P.lse = a->lse; P.probs = a->probs; P.hidden_out = a->hidden_out;
     for (int b = 0; b < a->batch; ++b) {
@@ -550,11 +552,15 @@ extern "C" int ps_draft_step(ps_draft_ctx* ctx, const ps_draft_step_args* a, voi
         unsigned sig = (unsigned)((P.Mtot + 15) / 16);
         for (int ph = 0; ph < PH_COUNT; ++ph) sig = sig * 8u + (unsigned)P.ph[ph].s_log + 1u;
         if (sig != ctx->last_frag_sig) {
-            if (ctx->last_frag_sig != 0)
+            // (the slices' sums of squares lie among the row buffers: everything is cleared)
+            if (ctx->last_frag_sig != 0) {
                 for (int cp = 0; cp < 2; ++cp)
-                    if (!hip_ok(hipMemsetAsync(ctx->act_base + (size_t)cp * ctx->act_bytes + ctx->act_small, 0xFF,
-                                               ctx->act_bytes - ctx->act_small, (hipStream_t)stream), "hipMemsetAsync"))
+                    if (!hip_ok(hipMemsetAsync(ctx->act_base + (size_t)cp * ctx->act_bytes, 0xFF, ctx->act_bytes,
+                                               (hipStream_t)stream), "hipMemsetAsync"))
                         return PS_ERR_DEVICE;
+                ctx->rows_dirty = P.Mtot;
+                P.rows_reset = P.Mtot;
+            }
             ctx->last_frag_sig = sig;
         }
     }

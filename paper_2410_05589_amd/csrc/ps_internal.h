@@ -73,6 +73,7 @@ struct StepParams {
     // shape
     int H, nq, nkv, d, F, V, QD, KVD;
     int B, n_new, k, M, Mtot, R, Rtot, all_rows, topk;
+    int rows_reset;    // >= Mtot, <= 2 Mtot: rows of the exchange buffers that may hold values of earlier steps
     int final_norm, max_positions;
     float eps, inv_sqrt_d;
     // weights and step inputs (config dtype)
