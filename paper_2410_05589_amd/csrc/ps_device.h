@@ -1037,9 +1037,9 @@ __global__ void __launch_bounds__(256) pack_kernel(const StepParams P, int T, in
 // 0 .. kv_len[b] + i (its own and earlier rows of this step included; Algorithm 1: distribution
 // j is conditioned on [MASK]_1..j only).
 //
-// Each wavefront takes NK groups of 16 keys of the chunk (CH = 128 NK keys; NK = PS_ATTN_NK = 1:
-// two groups per wavefront were measured to be no faster, and their registers do not fit beside the
-// weight loads the persistent kernel keeps in flight).  Scores are one MFMA tile per 16 keys and 16 query rows: the
+// Each wavefront takes NK groups of 16 keys of the chunk (CH = 128 NK keys).  NK = 2 halves the
+// number of work items; the host asks for it when that lets every workgroup get by with a single
+// item (its registers only fit without the requests for a following item).  Scores are one MFMA tile per 16 keys and 16 query rows: the
 // keys' K rows are the 16-row operand, loaded straight from the cache in its storage type; the
 // query rows (fp32, split into bf16 high + low parts like every activation) are the 16-column
 // operand.  The row maxima of the eight wavefronts meet in LDS, so all of them exponentiate
@@ -1481,7 +1481,7 @@ __device__ __forceinline__ void attn_phase(const StepParams& P, int wg, int nwg,
     };
     if (wg + nwg >= P.attn_items) {
         if (wg < P.attn_items) do_item(wg, cur, false, std::false_type());
-    } else {
+    } else if constexpr (NK == 1) {   // (the host uses two key groups per wavefront only when no workgroup gets a second item)
         for (int item = wg; item < P.attn_items; item += nwg) {
             const bool has_next = item + nwg < P.attn_items;
             do_item(item, has_next ? attn_decode(P, item + nwg, CH_LOG) : cur, has_next, std::true_type());
@@ -1884,8 +1884,12 @@ __global__ void __launch_bounds__(PS_WG_THREADS, 1) fused_kernel(const StepParam
     gemm_phase<WT, MT, PH_QKV>(P, wg, wave, smem, wb, first_stream(P, PH_OPROJ, wg, wave), my_seq);
     __syncthreads();
     stamp(P, wg, 32);
-    if (P.attn_single) attn_phase<WT, D, PS_ATTN_NK, true>(P, wg, gridDim.x, wave, smem);
-    else attn_phase<WT, D, PS_ATTN_NK, false>(P, wg, gridDim.x, wave, smem);
+    switch (2 * P.attn_nk + P.attn_single) {
+        case 2: attn_phase<WT, D, 1, false>(P, wg, gridDim.x, wave, smem); break;
+        case 3: attn_phase<WT, D, 1, true>(P, wg, gridDim.x, wave, smem); break;
+        case 4: attn_phase<WT, D, 2, false>(P, wg, gridDim.x, wave, smem); break;
+        default: attn_phase<WT, D, 2, true>(P, wg, gridDim.x, wave, smem); break;
+    }
     __syncthreads();
     stamp(P, wg, 36);
     // the ticket (see step_read) is taken here: the next thing this workgroup does is wait for the

@@ -115,7 +115,7 @@ static WsLayout ws_layout(const ps_draft_config* c) {
     const size_t rows = (size_t)c->max_batch * (c->max_new + c->k_max);
     const size_t qd = (size_t)c->n_heads * c->head_dim;
     const int grp = c->n_heads / c->n_kv_heads;
-    const int ch = PS_ATTN_KEYS * PS_ATTN_NK;
+    const int ch = PS_ATTN_KEYS;   // the smaller key block: the most work items
     const size_t max_items = (size_t)c->max_batch * c->n_kv_heads * ((c->max_positions + ch - 1) / ch);
     const size_t ra = (size_t)grp * (c->max_new + c->k_max);
     size_t off = 0;
@@ -509,7 +509,7 @@ extern "C" int ps_draft_step(ps_draft_ctx* ctx, const ps_draft_step_args* a, voi
     }
     // attention work items: (sequence, kv head, block of ch keys)
     const int ra = (c.n_heads / c.n_kv_heads) * M;
-    const int ch = PS_ATTN_KEYS * PS_ATTN_NK;
+    int ch = PS_ATTN_KEYS;
     // The M rows of this step normally belong to the last key block of their sequence.  When they alone
     // make up that block (or spill into one more) and leaving them out spares the workgroups a whole
     // round of work items, the merge items take them instead (at most 16 rows: they are kept in registers).
@@ -522,7 +522,15 @@ extern "C" int ps_draft_step(ps_draft_ctx* ctx, const ps_draft_step_args* a, voi
     if (ctx->attn_sep_override >= 0 && M <= 16) sep = ctx->attn_sep_override != 0;
     if (sep) items = items_wo;
     const int tail = sep ? 0 : M;
-    P.attn_items = items; P.attn_single = ra <= 16; P.attn_sep = sep ? 1 : 0; P.attn_tail = tail;
+    // Key blocks of twice the size (two groups of 16 keys per wavefront) when the workgroups still face
+    // more than one round of work items and that way every one of them gets at most a single item
+    int nk = 1;
+    if (items > ctx->n_cu && ps_attn_lds_bytes(c.head_dim, 2) <= ctx->lds_limit) {
+        int items2 = 0;
+        for (int b = 0; b < a->batch; ++b) items2 += c.n_kv_heads * ((a->kv_len[b] + tail + 2 * ch - 1) / (2 * ch));
+        if (items2 <= ctx->n_cu) { nk = 2; ch *= 2; items = items2; }
+    }
+    P.attn_items = items; P.attn_single = ra <= 16; P.attn_sep = sep ? 1 : 0; P.attn_tail = tail; P.attn_nk = nk;
     {   // sequences that span several key blocks are put together by (sequence, kv head, 8 rows) work items
         const int rt = (ra + PS_WAVES - 1) / PS_WAVES;
         int mi = 0;
@@ -572,7 +580,7 @@ extern "C" int ps_draft_step(ps_draft_ctx* ctx, const ps_draft_step_args* a, voi
     P.timeline = ctx->timeline;
 
     // the persistent kernel needs the largest LDS footprint of its phases and one workgroup per CU
-    int lds = ps_attn_lds_bytes(c.head_dim, PS_ATTN_NK);
+    int lds = ps_attn_lds_bytes(c.head_dim, nk);
     for (int ph = 0; ph < PH_COUNT; ++ph) {
         if (P.ph[ph].lds_bytes > lds) lds = P.ph[ph].lds_bytes;
     }

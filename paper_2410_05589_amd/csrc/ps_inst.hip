@@ -37,8 +37,13 @@ static kernel_fn fused_fn(int mt) {
     }
 }
 
-static kernel_fn attn_fn(int single) {
-    return single ? attn_kernel<WT_, D_, PS_ATTN_NK, true> : attn_kernel<WT_, D_, PS_ATTN_NK, false>;
+static kernel_fn attn_fn(int nk, int single) {
+    switch (2 * nk + (single ? 1 : 0)) {
+        case 2: return attn_kernel<WT_, D_, 1, false>;
+        case 3: return attn_kernel<WT_, D_, 1, true>;
+        case 4: return attn_kernel<WT_, D_, 2, false>;
+        default: return attn_kernel<WT_, D_, 2, true>;
+    }
 }
 
 static hipError_t prepare(int lds_limit) {
@@ -53,10 +58,10 @@ static hipError_t prepare(int lds_limit) {
                                 hipFuncAttributeMaxDynamicSharedMemorySize, lds_limit);
         if (e != hipSuccess) return e;
     }
-    if (ps_attn_lds_bytes(D_, PS_ATTN_NK) > lds_limit) return hipErrorInvalidValue;
-    for (int single = 0; single < 2; ++single) {
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_fn(single)), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                ps_attn_lds_bytes(D_, PS_ATTN_NK));
+    if (ps_attn_lds_bytes(D_, 2) > lds_limit) return hipErrorInvalidValue;
+    for (int v = 2; v < 6; ++v) {
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_fn(v >> 1, v & 1)), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                ps_attn_lds_bytes(D_, v >> 1));
         if (e != hipSuccess) return e;
     }
     return hipSuccess;
@@ -76,7 +81,7 @@ static hipError_t launch_multi(const StepParams& P, hipStream_t stream, hipEvent
     hipError_t e;
     if ((e = mark()) != hipSuccess) return e;
     if ((e = gemm(PH_QKV, mt_all)) != hipSuccess) return e;
-    hipLaunchKernelGGL(attn_fn(P.attn_single), dim3(P.attn_nwg), dim3(PS_WG_THREADS), ps_attn_lds_bytes(D_, PS_ATTN_NK), stream, P);
+    hipLaunchKernelGGL(attn_fn(P.attn_nk, P.attn_single), dim3(P.attn_nwg), dim3(PS_WG_THREADS), ps_attn_lds_bytes(D_, P.attn_nk), stream, P);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     if ((e = mark()) != hipSuccess) return e;
     if ((e = gemm(PH_OPROJ, mt_all)) != hipSuccess) return e;

@@ -27,9 +27,8 @@
 static_assert((1 << PS_WAVES_LOG) == PS_WAVES, "PS_WAVES_LOG");
 static_assert((PS_U & (PS_U - 1)) == 0 && PS_U <= PS_U_MAX, "PS_U");
 
-// Attention work items cover PS_ATTN_KEYS * PS_ATTN_NK keys of one (sequence, kv head): every wavefront
-// takes PS_ATTN_NK groups of 16 keys.  LDS an item needs (see AttnCfg in ps_device.h):
-#define PS_ATTN_NK 1
+// Attention work items cover PS_ATTN_KEYS * nk keys of one (sequence, kv head): every wavefront
+// takes nk = 1 or 2 groups of 16 keys.  LDS an item needs (see AttnCfg in ps_device.h):
 #define PS_ATTN_KEYS (16 * PS_WAVES)
 #define PS_ATTN_KEYS_LOG (4 + PS_WAVES_LOG)
 constexpr int ps_attn_lds_bytes(int d, int nk) {
@@ -100,6 +99,7 @@ struct StepParams {
     // attention work list
     int attn_items, attn_nwg;   // work items; workgroups of the attention kernel (multi mode)
     int attn_single;        // the g*M query rows of a kv head fit in one pass of 16
+    int attn_nk;            // groups of 16 keys per wavefront and work item (1 or 2)
     // The rows written in this step are either the tail of the sequence's last key block (attn_tail = M,
     // attn_sep = 0), or no block's business: then the work items that put the blocks together also do
     // the attention over these rows (attn_tail = 0, attn_sep = 1; see ps_draft_step for when)

@@ -105,6 +105,17 @@ def test_new_rows_left_to_the_merge_items():
     _run_case(wl2)
 
 
+def test_key_blocks_of_twice_the_size():
+    """More attention work items than compute units with 128-key blocks, no more than that with 256-key
+    blocks: every wavefront then takes two groups of 16 keys.  One pass of query rows, and two (GQA)."""
+    shape = small_shape("bf16", hidden=1024, n_heads=8, n_kv_heads=8, head_dim=128, ffn=1376, vocab=2000)
+    wl = Workload("nk2", shape, batch=8, kv_len=(600, 513, 700, 640, 520, 767, 600, 650), n_new=1, k=5, topk=8, seed=37)
+    _run_case(wl)
+    shape2 = small_shape("bf16", hidden=1024, n_heads=16, n_kv_heads=8, head_dim=64, ffn=1376, vocab=2000)
+    wl2 = Workload("nk2 gqa", shape2, batch=7, kv_len=(600, 513, 700, 640, 520, 767, 600), n_new=1, k=8, topk=8, seed=38)
+    _run_case(wl2)
+
+
 def test_two_contexts_take_turns_on_one_stream():
     """Two drafters of different shape and type (own workspaces, own step counters) stepping alternately."""
     shape_a = small_shape("bf16", hidden=512, n_heads=4, n_kv_heads=4, head_dim=128, ffn=1024, vocab=3001)
