@@ -22,7 +22,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 PEAK_HBM_GBS = 8000.0   # MI355X HBM3E, published peak
-MEASURED_TRAFFIC = {("c1", "fused"): 713434459}
+MEASURED_TRAFFIC = {("c1", "fused"): 713460870}
 
 
 def algorithmic_bytes(wl, kv_len, n_new, k):
