@@ -1887,8 +1887,7 @@ __global__ void __launch_bounds__(PS_WG_THREADS, 1) fused_kernel(const StepParam
     switch (2 * P.attn_nk + P.attn_single) {
         case 2: attn_phase<WT, D, 1, false>(P, wg, gridDim.x, wave, smem); break;
         case 3: attn_phase<WT, D, 1, true>(P, wg, gridDim.x, wave, smem); break;
-        case 4: attn_phase<WT, D, 2, false>(P, wg, gridDim.x, wave, smem); break;
-        default: attn_phase<WT, D, 2, true>(P, wg, gridDim.x, wave, smem); break;
+        default: attn_phase<WT, D, 2, true>(P, wg, gridDim.x, wave, smem); break;   // (host: two key groups only with a single pass)
     }
     __syncthreads();
     stamp(P, wg, 36);

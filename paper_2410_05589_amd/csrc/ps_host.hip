@@ -525,7 +525,7 @@ extern "C" int ps_draft_step(ps_draft_ctx* ctx, const ps_draft_step_args* a, voi
     // Key blocks of twice the size (two groups of 16 keys per wavefront) when the workgroups still face
     // more than one round of work items and that way every one of them gets at most a single item
     int nk = 1;
-    if (items > ctx->n_cu && ps_attn_lds_bytes(c.head_dim, 2) <= ctx->lds_limit) {
+    if (items > ctx->n_cu && ra <= 16 && ps_attn_lds_bytes(c.head_dim, 2) <= ctx->lds_limit) {
         int items2 = 0;
         for (int b = 0; b < a->batch; ++b) items2 += c.n_kv_heads * ((a->kv_len[b] + tail + 2 * ch - 1) / (2 * ch));
         if (items2 <= ctx->n_cu) { nk = 2; ch *= 2; items = items2; }

@@ -41,8 +41,7 @@ static kernel_fn attn_fn(int nk, int single) {
     switch (2 * nk + (single ? 1 : 0)) {
         case 2: return attn_kernel<WT_, D_, 1, false>;
         case 3: return attn_kernel<WT_, D_, 1, true>;
-        case 4: return attn_kernel<WT_, D_, 2, false>;
-        default: return attn_kernel<WT_, D_, 2, true>;
+        default: return attn_kernel<WT_, D_, 2, true>;   // (host: two key groups only with a single pass)
     }
 }
 
@@ -60,6 +59,7 @@ static hipError_t prepare(int lds_limit) {
     }
     if (ps_attn_lds_bytes(D_, 2) > lds_limit) return hipErrorInvalidValue;
     for (int v = 2; v < 6; ++v) {
+        if (v == 4) continue;
         e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_fn(v >> 1, v & 1)), hipFuncAttributeMaxDynamicSharedMemorySize,
                                 ps_attn_lds_bytes(D_, v >> 1));
         if (e != hipSuccess) return e;
