@@ -1,0 +1,86 @@
+/*
+ * ps_verify.h - C ABI of the steps that follow the parallel draft step in Algorithm 1:
+ * building the draft token tree from the drafter's top-k output, and the acceptance walk
+ * over that tree against the target model's distributions.  Same library as ps_draft.h
+ * (libps_draft.so), same conventions: extern "C", plain pointers and sizes, int status
+ * (ps_status of ps_draft.h: 0 = OK, negative = error), nothing is enqueued on an error,
+ * no allocation, no host synchronisation, asynchronous on the given hipStream_t.
+ * Pointers marked DEVICE are device memory owned by the caller, HOST ones are read before
+ * the call returns.
+ */
+#ifndef PS_VERIFY_H
+#define PS_VERIFY_H
+#include <stdint.h>
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define PS_TREE_MAX_NODES 64
+
+/*
+ * The shape of a draft tree (Algorithm 1: the tree N; Section 4.2): node 0 is the root (the
+ * last token of the prefix), parent[0] = -1, and 0 <= parent[s] < s for every other node, so
+ * a node's children follow it and are tried in ascending index.  A node at depth t >= 1
+ * carries a token proposed by draft row t-1, i.e. by q(. | x_<n, [MASK]_1..t-1); rank[s] says
+ * which of that row's top-k tokens (0 = most probable; rank[0] is ignored).  Both arrays are
+ * HOST memory of n_nodes entries, 1 <= n_nodes <= PS_TREE_MAX_NODES, and are copied.
+ */
+typedef struct ps_tree_shape {
+    int32_t n_nodes;
+    const int32_t* parent;
+    const int32_t* rank;
+} ps_tree_shape;
+
+/*
+ * Tree construction (Algorithm 1, "Draft future token tree N"): tokens[b][s] =
+ * top_ids[b][depth(s) - 1][rank[s]] for s >= 1 and -1 for the root.
+ *   top_ids  DEVICE [batch][rows][topk] int32: ps_draft_step's output (rows = k+1 draft rows)
+ *   tokens   DEVICE [batch][n_nodes] int32, written
+ * Errors: PS_ERR_NULL; PS_ERR_SHAPE (batch < 1, a malformed tree, a depth beyond rows, a rank
+ * outside [0, topk)); PS_ERR_DEVICE.
+ */
+int ps_tree_tokens(const ps_tree_shape* tree, int32_t batch, int32_t rows, int32_t topk,
+                   const int32_t* top_ids, int32_t* tokens, void* stream);
+
+/*
+ * The acceptance walk of Algorithm 1 (its inner loops and the final draw), once per sequence,
+ * in float64 on the float32 inputs.  Starting at the root with P = p[0]: the children s of
+ * the current node are tried in ascending index; child s with token x = tokens[s] at depth t is
+ * accepted when r[s] < min(1, P(x) / q[t-1](x)) (a proposal with q(x) = 0 counts as ratio 1);
+ * then the walk moves to s and P = p[s].  A rejected child leaves P = the positive part of
+ * P - q[t-1], divided by its sum.  When the current node has no child left to try, the last
+ * token is drawn from P by inversion with r[0]: the number of token ids whose cumulative sum
+ * of P (in id order) is <= r[0] * sum(P), at most vocab-1.
+ *   tokens      DEVICE [batch][n_nodes] int32 (entry 0 ignored); a token outside [0, vocab)
+ *               is treated as rejected and leaves P unchanged
+ *   q           DEVICE [batch][rows][vocab] float32: the drafter's distributions
+ *               (ps_draft_step's probs); rows >= the tree's depth
+ *   p           DEVICE [batch][n_nodes][vocab] float32: the target's next-token distribution
+ *               after the path to each node (entry 0: after the prefix alone)
+ *   r           DEVICE [batch][n_nodes] float32 uniform numbers in [0, 1)
+ *   residual    DEVICE scratch, batch * vocab doubles, 8-byte aligned
+ *   n_accepted  DEVICE [batch] int32, written: accepted draft tokens
+ *   path        DEVICE [batch][rows] int32, written: the accepted nodes, then -1
+ *   out_tokens  DEVICE [batch][rows + 1] int32, written: the accepted tokens, the last drawn
+ *               token, then -1
+ * Calls that share `residual` must not overlap in time.
+ * Errors: PS_ERR_NULL; PS_ERR_SHAPE (batch < 1, vocab < 1, a malformed tree, a depth beyond
+ * rows); PS_ERR_DEVICE.
+ */
+typedef struct ps_verify_args {
+    int32_t batch, rows, vocab;
+    const int32_t* tokens;
+    const float* q;
+    const float* p;
+    const float* r;
+    double* residual;
+    int32_t* n_accepted;
+    int32_t* path;
+    int32_t* out_tokens;
+} ps_verify_args;
+int ps_verify_walk(const ps_tree_shape* tree, const ps_verify_args* args, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PS_VERIFY_H */

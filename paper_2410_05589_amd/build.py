@@ -10,8 +10,8 @@ LIB_PATH = os.path.join(PKG_DIR, "libps_draft.so")
 CSRC = os.path.join(PKG_DIR, "csrc")
 BUILD_DIR = os.path.join(PKG_DIR, "_build")
 HEADERS = [os.path.join(CSRC, "ps_internal.h"), os.path.join(CSRC, "ps_device.h"),
-           os.path.join(ROOT, "include", "ps_draft.h")]
-SOURCES = [os.path.join(CSRC, "ps_host.hip"), os.path.join(CSRC, "ps_inst.hip")]
+           os.path.join(ROOT, "include", "ps_draft.h"), os.path.join(ROOT, "include", "ps_verify.h")]
+SOURCES = [os.path.join(CSRC, "ps_host.hip"), os.path.join(CSRC, "ps_inst.hip"), os.path.join(CSRC, "ps_verify.hip")]
 # the device code is instantiated once per (storage type, head_dim)
 INSTANCES = [("f32_d64", 0, 64), ("f32_d128", 0, 128), ("bf16_d64", 1, 64), ("bf16_d128", 1, 128)]
 
@@ -46,7 +46,8 @@ def build_library(verbose=True, jobs=4):
               # scratch-memory load and the persistent kernel runs ~40 % slower.
               "-mllvm", "-instcombine-max-copied-from-constant-users=10000",
               "-I", os.path.join(ROOT, "include"), "-I", CSRC] + os.environ.get("PS_BUILD_DEFS", "").split()
-    units = [(os.path.join(BUILD_DIR, "ps_host.o"), [os.path.join(CSRC, "ps_host.hip")])]
+    units = [(os.path.join(BUILD_DIR, "ps_host.o"), [os.path.join(CSRC, "ps_host.hip")]),
+             (os.path.join(BUILD_DIR, "ps_verify.o"), [os.path.join(CSRC, "ps_verify.hip")])]
     for name, bf, d in INSTANCES:
         units.append((os.path.join(BUILD_DIR, "ps_inst_%s.o" % name),
                       ["-DPS_INST_NAME=%s" % name, "-DPS_INST_BF16=%d" % bf, "-DPS_INST_D=%d" % d,

@@ -115,3 +115,53 @@ def make_step_inputs(workload, kv_len=None, n_new=None, k=None, slack=0, sub=0):
     x = _normal(workload.seed, "x", (len(kv_len), n_new, s.hidden), 1.0, 0.0, s.dtype, sub=sub)
     return {"x": x, "k_cache": kc, "v_cache": vc, "kv_offsets": off,
             "kv_len": np.asarray(kv_len, dtype=np.int32), "n_new": n_new, "k": k}
+
+
+# ---------------------------------------------------------------- draft tree and acceptance walk
+def draft_tree(fanout):
+    """Static draft tree: fanout[t] = how many of draft row t's top tokens every node of depth t gets
+    as children (node 0 = root).  Returns (parent, rank), nodes in breadth-first order, a node's
+    children in ascending rank."""
+    parent, rank, level = [-1], [0], [0]
+    for f in fanout:
+        nxt = []
+        for u in level:
+            for j in range(f):
+                parent.append(u)
+                rank.append(j)
+                nxt.append(len(parent) - 1)
+        level = nxt
+    return np.array(parent, dtype=np.int32), np.array(rank, dtype=np.int32)
+
+
+def verify_inputs(seed, batch, parent, rank, rows, topk, vocab, agreement=0.7, concentration=0.05):
+    """Seeded inputs of a tree build + acceptance walk (numbers only: no step of the walk is taken here).
+
+    The drafter's distributions q [batch, rows, vocab] are peaked (a Dirichlet with a small
+    concentration, like a language model's); top_ids are q's largest entries per row (ties to the lower
+    id); the target's distribution after a node of depth t is `agreement` times draft row t (so
+    proposals of the next depth are often accepted) plus (1 - agreement) times an independent peaked
+    draw; r is uniform in [0, 1).  Everything is float32 as stored; nothing needs to sum to exactly 1.
+    """
+    g = np.random.Generator(np.random.Philox(key=[int(seed), 9001]))
+    n = len(parent)
+    depth = np.zeros(n, dtype=np.int64)
+    for s in range(1, n):
+        depth[s] = depth[parent[s]] + 1
+
+    def peaked(shape_prefix):
+        a = g.standard_gamma(concentration, size=tuple(shape_prefix) + (vocab,)) + 1e-12
+        return a / a.sum(axis=-1, keepdims=True)
+
+    q = peaked((batch, rows))
+    other = peaked((batch, n))
+    p = np.empty((batch, n, vocab))
+    for s in range(n):
+        t = int(depth[s])
+        p[:, s] = agreement * q[:, t] + (1.0 - agreement) * other[:, s] if t < rows else other[:, s]
+    q32 = q.astype(np.float32)
+    order = np.lexsort((np.broadcast_to(np.arange(vocab), q32.shape), -q32), axis=-1)
+    top_ids = order[..., :topk].astype(np.int32)
+    r = g.random((batch, n)).astype(np.float32)
+    r = np.minimum(r, np.float32(1.0 - 2.0 ** -24))
+    return {"q": q32, "p": p.astype(np.float32), "r": r, "top_ids": np.ascontiguousarray(top_ids)}

@@ -1,0 +1,149 @@
+"""GPU parity of the tree construction and the acceptance walk (through the C ABI) against the CPU oracle.
+
+Both sides decide in float64 on the same float32 inputs; they differ only in the order of the sums
+over the vocabulary (relative 1e-13 at most).  So accepted nodes, accepted tokens and the last drawn
+token must be bit-exact wherever the oracle's decision margins exceed MARGIN; a sample whose margin is
+smaller is not compared (and there must be almost none).
+"""
+import numpy as np
+import pytest
+
+from oracle import verify_walk as vw
+from paper_2410_05589_amd import binding as B
+from paper_2410_05589_amd import inputs
+from paper_2410_05589_amd import verify as VF
+
+pytestmark = pytest.mark.gpu
+MARGIN = 1e-9
+
+
+def _run_gpu(parent, rank, inp, rows, topk, tokens_override=None):
+    import torch
+    dev = torch.device("cuda:0")
+    batch, n, vocab = inp["p"].shape
+    tree = VF.make_tree(parent, rank)
+    top_ids = torch.from_numpy(inp["top_ids"]).to(dev)
+    tokens = torch.full((batch, n), -5, dtype=torch.int32, device=dev)
+    stream = torch.cuda.current_stream().cuda_stream
+    st = VF.ps_tree_tokens(tree, batch, rows, topk, top_ids.data_ptr(), tokens.data_ptr(), stream)
+    assert st == B.PS_OK, B.ps_draft_strerror(st)
+    if tokens_override is not None:
+        torch.cuda.synchronize()
+        built = tokens.cpu().numpy()
+        tokens = torch.from_numpy(np.ascontiguousarray(tokens_override, dtype=np.int32)).to(dev)
+    q = torch.from_numpy(inp["q"]).to(dev)
+    p = torch.from_numpy(inp["p"]).to(dev)
+    r = torch.from_numpy(inp["r"]).to(dev)
+    residual = torch.full((batch, vocab), float("nan"), dtype=torch.float64, device=dev)
+    n_acc = torch.full((batch,), -7, dtype=torch.int32, device=dev)
+    path = torch.full((batch, rows), -7, dtype=torch.int32, device=dev)
+    out_tokens = torch.full((batch, rows + 1), -7, dtype=torch.int32, device=dev)
+    a = VF.ps_verify_args()
+    a.batch, a.rows, a.vocab = batch, rows, vocab
+    a.tokens, a.q, a.p, a.r = tokens.data_ptr(), q.data_ptr(), p.data_ptr(), r.data_ptr()
+    a.residual, a.n_accepted, a.path, a.out_tokens = residual.data_ptr(), n_acc.data_ptr(), path.data_ptr(), out_tokens.data_ptr()
+    st = VF.ps_verify_walk(tree, a, stream)
+    assert st == B.PS_OK, B.ps_draft_strerror(st)
+    torch.cuda.synchronize()
+    return {"tokens": tokens.cpu().numpy() if tokens_override is None else built, "n_accepted": n_acc.cpu().numpy(),
+            "path": path.cpu().numpy(), "out_tokens": out_tokens.cpu().numpy()}
+
+
+def _check(parent, rank, inp, rows, topk, label, tokens_override=None, oracle_tokens=None):
+    print("case", label, "nodes", len(parent), "rows", rows, "vocab", inp["p"].shape[2], "batch", inp["p"].shape[0], flush=True)
+    gpu = _run_gpu(parent, rank, inp, rows, topk, tokens_override)
+    batch = inp["p"].shape[0]
+    compared = 0
+    for b in range(batch):
+        want_tokens = vw.tree_tokens(inp["top_ids"][b], parent, rank)
+        assert gpu["tokens"][b].tolist() == want_tokens.tolist(), (label, b)
+        walk_tokens = want_tokens if oracle_tokens is None else oracle_tokens[b]
+        ref = vw.acceptance_walk(parent, walk_tokens, inp["q"][b], inp["p"][b], inp["r"][b])
+        if ref["accept_margin"] <= MARGIN or ref["cdf_margin"] <= MARGIN:
+            continue
+        compared += 1
+        na = ref["n_accepted"]
+        assert gpu["n_accepted"][b] == na, (label, b)
+        assert gpu["path"][b].tolist() == ref["path"] + [-1] * (rows - na), (label, b)
+        assert gpu["out_tokens"][b].tolist() == ref["tokens"] + [-1] * (rows - na), (label, b)
+    assert compared >= batch - 1 - batch // 16, (label, compared)
+    return gpu
+
+
+TREES = {
+    "chain": [1, 1, 1, 1, 1],
+    "wide": [8],
+    "bushy": [4, 2, 2, 1, 1],          # 61 nodes
+    "two levels": [3, 3],
+}
+
+
+@pytest.mark.parametrize("tree", sorted(TREES))
+@pytest.mark.parametrize("vocab", [1000, 5003, 32000])
+def test_walk_matches_oracle(tree, vocab):
+    parent, rank = inputs.draft_tree(TREES[tree])
+    rows = len(TREES[tree]) + 1
+    for seed, agreement in ((1, 0.7), (2, 0.2), (3, 0.97)):
+        inp = inputs.verify_inputs(100 * seed + vocab % 97, 6, parent, rank, rows, 8, vocab, agreement=agreement)
+        _check(parent, rank, inp, rows, 8, "%s V%d agreement %.2f" % (tree, vocab, agreement))
+
+
+def test_walk_at_the_largest_sizes():
+    # Llama-3 vocabulary, the most nodes the interface takes, batch 8: the oracle walks every sequence
+    parent, rank = inputs.draft_tree([7, 2, 2, 1])     # 1 + 7 + 14 + 28 + 28 = 78 > 64: cut to 64 nodes
+    parent, rank = parent[:64], rank[:64]
+    inp = inputs.verify_inputs(7, 8, parent, rank, 9, 8, 128256, agreement=0.8)
+    _check(parent, rank, inp, 9, 8, "largest")
+
+
+def test_root_only_tree_just_draws_a_token():
+    parent, rank = np.array([-1], dtype=np.int32), np.array([0], dtype=np.int32)
+    inp = inputs.verify_inputs(5, 4, parent, rank, 1, 4, 777)
+    inp["r"][0, 0] = 0.0
+    inp["r"][1, 0] = np.float32(1.0 - 2.0 ** -24)
+    gpu = _check(parent, rank, inp, 1, 4, "root only")
+    assert gpu["n_accepted"].tolist() == [0, 0, 0, 0]
+    first = int(np.flatnonzero(inp["p"][0, 0] > 0)[0])
+    assert gpu["out_tokens"][0, 0] == first              # u = 0 draws the first token with probability > 0
+
+
+def test_token_outside_the_vocabulary_is_skipped():
+    parent, rank = inputs.draft_tree([3, 1])
+    inp = inputs.verify_inputs(6, 5, parent, rank, 3, 8, 2000, agreement=0.9)
+    tokens = np.stack([vw.tree_tokens(inp["top_ids"][b], parent, rank) for b in range(5)])
+    tokens[:, 1] = 2000          # first child of the root: out of range
+    tokens[:, 2] = -3
+    # the oracle sees the same tree without these two nodes (and without the child of node 1)
+    keep = [0, 3, 6]
+    sub_parent = np.array([-1, 0, 1], dtype=np.int32)
+    gpu = _run_gpu(parent, rank, inp, 3, 8, tokens_override=tokens)
+    for b in range(5):
+        ref = vw.acceptance_walk(sub_parent, tokens[b, keep], inp["q"][b], inp["p"][b][keep], inp["r"][b][keep])
+        if ref["accept_margin"] <= MARGIN or ref["cdf_margin"] <= MARGIN:
+            continue
+        assert gpu["n_accepted"][b] == ref["n_accepted"]
+        assert gpu["path"][b, :ref["n_accepted"]].tolist() == [keep[s] for s in ref["path"]]
+        assert gpu["out_tokens"][b, :ref["n_accepted"] + 1].tolist() == ref["tokens"]
+
+
+def test_walk_after_a_draft_step_end_to_end():
+    # the drafter's own output feeds the tree: top_ids and probs of a c0-sized step
+    from paper_2410_05589_amd.configs import WORKLOADS
+    from tests.gpu_util import run_gpu_step
+    wl = WORKLOADS["c0"]
+    w = inputs.make_weights(wl.shape, wl.seed)
+    inp = inputs.make_step_inputs(wl, kv_len=[64, 40])
+    drafter = B.Drafter(wl.shape, w, max_batch=2, max_new=wl.n_new, max_positions=256, max_topk=4)
+    res = run_gpu_step(drafter, inp, wl.n_new, wl.k, 4)
+    rows = wl.k + 1
+    parent, rank = inputs.draft_tree([3, 2, 1, 1, 1])
+    vin = inputs.verify_inputs(9, 2, parent, rank, rows, 4, wl.shape.vocab, agreement=0.0)
+    q = res["probs"].reshape(2, rows, wl.shape.vocab).astype(np.float32)
+    vin["q"] = q
+    vin["top_ids"] = res["top_ids"].reshape(2, rows, 4).astype(np.int32)
+    # a target that mostly agrees with the drafter's next row
+    depth = vw.tree_depths(parent)
+    for s in range(len(parent)):
+        if depth[s] < rows:
+            vin["p"][:, s] = (0.8 * q[:, depth[s]] + 0.2 * vin["p"][:, s]).astype(np.float32)
+    _check(parent, rank, vin, rows, 4, "after a draft step")

@@ -1,0 +1,78 @@
+"""CPU tests of the tree / acceptance-walk entry points: exported as the header declares, struct
+layouts match, and host-side validation reports errors before anything touches a device."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2410_05589_amd import binding as B
+from paper_2410_05589_amd import verify as VF
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "ps_verify.h")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(B.LIB_PATH):
+        from paper_2410_05589_amd.build import build_library
+        build_library(verbose=False)
+    return B.load_library()
+
+
+def _header_code():
+    return re.sub(r"/\*.*?\*/", "", open(HEADER).read(), flags=re.S)
+
+
+def test_every_declared_symbol_is_exported(lib):
+    declared = sorted(set(re.findall(r"\bint\s+(ps_[a-z_]+)\s*\(", _header_code())))
+    assert declared == sorted(VF.EXPORTED_SYMBOLS)
+    for name in declared:
+        assert getattr(lib, name) is not None
+
+
+def test_struct_layouts_match_header():
+    code = _header_code()
+    body = code[code.index("typedef struct ps_tree_shape {"):code.index("} ps_tree_shape;")]
+    assert re.findall(r"\b([a-z_]+);", body) == [f[0] for f in VF.ps_tree_shape._fields_]
+    body = code[code.index("typedef struct ps_verify_args {"):code.index("} ps_verify_args;")]
+    names = [n for line in re.findall(r"[^;{]+;", body) for n in re.findall(r"\*?\s*([a-z_]+)\s*[,;]", line)]
+    assert names == [f[0] for f in VF.ps_verify_args._fields_]
+    assert int(re.search(r"#define PS_TREE_MAX_NODES (\d+)", code).group(1)) == VF.PS_TREE_MAX_NODES
+
+
+def _args(**kw):
+    a = VF.ps_verify_args()
+    a.batch, a.rows, a.vocab = 1, 3, 100
+    for n in ("tokens", "q", "p", "r", "residual", "n_accepted", "path", "out_tokens"):
+        setattr(a, n, 0x100000)
+    for k, v in kw.items():
+        setattr(a, k, v)
+    return a
+
+
+def test_walk_rejects_bad_arguments_on_the_host(lib):
+    good = VF.make_tree([-1, 0, 0, 1], [0, 0, 1, 0])
+    assert VF.ps_verify_walk(None, _args(), None) == B.PS_ERR_NULL
+    assert VF.ps_verify_walk(good, None, None) == B.PS_ERR_NULL
+    for n in ("tokens", "q", "p", "r", "residual", "n_accepted", "path", "out_tokens"):
+        assert VF.ps_verify_walk(good, _args(**{n: None}), None) == B.PS_ERR_NULL, n
+    for kw in (dict(batch=0), dict(rows=0), dict(vocab=0), dict(residual=0x100004), dict(rows=1)):   # rows=1: depth 2 > rows
+        assert VF.ps_verify_walk(good, _args(**kw), None) == B.PS_ERR_SHAPE, kw
+    for parent in ([0, 0], [-1, 1], [-1, -1], [-1, 0, 3], [-1] + [0] * 64, []):
+        t = VF.make_tree(np.array(parent, dtype=np.int32), np.zeros(len(parent), dtype=np.int32))
+        assert VF.ps_verify_walk(t, _args(rows=64), None) == B.PS_ERR_SHAPE, parent
+
+
+def test_tree_tokens_rejects_bad_arguments_on_the_host(lib):
+    good = VF.make_tree([-1, 0, 0, 1], [0, 0, 1, 0])
+    assert VF.ps_tree_tokens(None, 1, 3, 4, 0x1000, 0x1000, None) == B.PS_ERR_NULL
+    assert VF.ps_tree_tokens(good, 1, 3, 4, None, 0x1000, None) == B.PS_ERR_NULL
+    assert VF.ps_tree_tokens(good, 1, 3, 4, 0x1000, None, None) == B.PS_ERR_NULL
+    assert VF.ps_tree_tokens(VF.make_tree([-1, 0]), 1, 3, 4, 0x1000, 0x1000, None) == B.PS_ERR_NULL   # no ranks
+    for batch, rows, topk in ((0, 3, 4), (1, 0, 4), (1, 3, 0), (1, 1, 4), (1, 3, 1)):   # (1,1,4): depth 2 > rows; (1,3,1): rank 1 >= topk
+        assert VF.ps_tree_tokens(good, batch, rows, topk, 0x1000, 0x1000, None) == B.PS_ERR_SHAPE, (batch, rows, topk)
+    bad_rank = VF.make_tree([-1, 0], [0, -1])
+    assert VF.ps_tree_tokens(bad_rank, 1, 3, 4, 0x1000, 0x1000, None) == B.PS_ERR_SHAPE
