@@ -45,6 +45,81 @@ def algorithmic_bytes(wl, kv_len, n_new, k):
     return per
 
 
+def verify_walk_report(torch, with_oracle, calls=200):
+    """Tree construction + acceptance walk (the step after the draft step in Algorithm 1) on a tree of the
+    c1 drafter's shape: 61 nodes (fan-out 4, 2, 2, 1, 1 over the k+1 = 6 draft rows), vocabulary 32000,
+    one sequence, a target that agrees with the drafter's next row to 70 %.  Latency per call from HIP
+    events over `calls` back-to-back calls; bytes = what the walk has to touch (per rejection: P, q and
+    the new residual; the final draw: P once), counted on the oracle's walk of the same inputs."""
+    from paper_2410_05589_amd import inputs
+    from paper_2410_05589_amd import verify as VF
+    dev = torch.device("cuda:0")
+    fan, rows, vocab, topk, batch = [4, 2, 2, 1, 1], 6, 32000, 8, 1
+    parent, rank = inputs.draft_tree(fan)
+    inp = inputs.verify_inputs(1, batch, parent, rank, rows, topk, vocab, agreement=0.7)
+    n = len(parent)
+    tree = VF.make_tree(parent, rank)
+    top_ids = torch.from_numpy(inp["top_ids"]).to(dev)
+    tokens = torch.zeros((batch, n), dtype=torch.int32, device=dev)
+    q, p, r = (torch.from_numpy(inp[x]).to(dev) for x in ("q", "p", "r"))
+    residual = torch.zeros((batch, vocab), dtype=torch.float64, device=dev)
+    n_acc = torch.zeros((batch,), dtype=torch.int32, device=dev)
+    path = torch.zeros((batch, rows), dtype=torch.int32, device=dev)
+    out_tokens = torch.zeros((batch, rows + 1), dtype=torch.int32, device=dev)
+    a = VF.ps_verify_args()
+    a.batch, a.rows, a.vocab = batch, rows, vocab
+    a.tokens, a.q, a.p, a.r = tokens.data_ptr(), q.data_ptr(), p.data_ptr(), r.data_ptr()
+    a.residual, a.n_accepted, a.path, a.out_tokens = (residual.data_ptr(), n_acc.data_ptr(), path.data_ptr(),
+                                                      out_tokens.data_ptr())
+    stream = torch.cuda.current_stream().cuda_stream
+
+    def build():
+        st = VF.ps_tree_tokens(tree, batch, rows, topk, top_ids.data_ptr(), tokens.data_ptr(), stream)
+        assert st == 0, st
+
+    def walk():
+        st = VF.ps_verify_walk(tree, a, stream)
+        assert st == 0, st
+
+    def timed(fns):
+        for _ in range(20):
+            for f in fns:
+                f()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(calls):
+            for f in fns:
+                f()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / calls
+
+    both_us = timed([build, walk])
+    walk_us = timed([walk])
+    rep = {"workload": "tree of 61 nodes (fan-out 4,2,2,1,1), 6 draft rows, V 32000, batch 1, target agrees 70 %",
+           "latency_us_tree_and_walk": round(both_us, 2), "latency_us_walk": round(walk_us, 2), "calls": calls,
+           "dtype": "f64", "n_accepted": int(n_acc.cpu().numpy()[0])}
+    if with_oracle:
+        from oracle import verify_walk as vw
+        tok = vw.tree_tokens(inp["top_ids"][0], parent, rank)
+        c0 = time.perf_counter()
+        ref = vw.acceptance_walk(parent, tok, inp["q"][0], inp["p"][0], inp["r"][0])
+        cpu_s = time.perf_counter() - c0
+        nbytes = vocab * (16 * ref["rejected_from_row"] + 20 * ref["rejected_from_residual"]
+                          + (4 if ref["final_from_row"] else 8))
+        gbs = nbytes / (walk_us * 1e-6) / 1e9
+        rep.update({"agrees_with_oracle": bool(out_tokens.cpu().numpy()[0, :len(ref["tokens"])].tolist() == ref["tokens"]),
+                    "rejections": ref["rejected_from_row"] + ref["rejected_from_residual"],
+                    "roofline": {"bound": "hbm", "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                                 "frac": round(gbs / PEAK_HBM_GBS, 5), "algorithmic_bytes_per_launch": int(nbytes),
+                                 "traffic": None,
+                                 "note": "one workgroup per sequence: bound by latency and one CU's bandwidth, not by HBM"},
+                    "cpu_baseline": {"value": round(cpu_s * 1e6, 1), "unit": "us per walk", "cores": 1, "kind": "oracle",
+                                     "sample": "one walk of the same inputs (numpy float64)"}})
+    return rep
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -229,6 +304,7 @@ def main():
                                                                                        len(os.sched_getaffinity(0))),
                                   "top1_agreement_with_gpu": agree}
     drafter.close()
+    result["next_rows"] = {"verify_walk": verify_walk_report(torch, not args.no_cpu_baseline)}
     print(json.dumps(result))
 
 

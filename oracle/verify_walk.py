@@ -73,7 +73,8 @@ def acceptance_walk(parent, tokens, q, p, r):
     r [N] uniform numbers.  Returns a dict: path (accepted nodes), tokens (accepted tokens and
     the last drawn one), n_accepted, and the margins of every decision (distance of r from the
     acceptance ratio; distance of the inversion target from the nearest cumulative sum, relative
-    to the total) so that a comparison can tell forced differences from rounding.
+    to the total) so that a comparison can tell forced differences from rounding; and how many
+    rejections met P as a row of p or as a residual (for counting the bytes a walk has to touch).
     """
     parent = np.asarray(parent, dtype=np.int64)
     N = len(parent)
@@ -83,6 +84,7 @@ def acceptance_walk(parent, tokens, q, p, r):
     u = 0
     P = p[0].copy()
     path, out_tokens, margins = [], [], []
+    fresh, rejected = True, {True: 0, False: 0}              # bookkeeping only: is P still a row of p?
     while True:
         H = [s for s in range(N) if parent[s] == u]          # children, ascending index
         if not H:
@@ -99,8 +101,11 @@ def acceptance_walk(parent, tokens, q, p, r):
                 out_tokens.append(x)
                 u = s
                 P = p[s].copy()
+                fresh = True
                 moved = True
                 break
+            rejected[fresh] += 1
+            fresh = False
             res = np.maximum(P - qt, 0.0)
             tot = float(np.sum(res))
             P = res / tot if tot > 0.0 else res
@@ -113,4 +118,5 @@ def acceptance_walk(parent, tokens, q, p, r):
     cdf_margin = float(np.min(np.abs(c - target))) / max(float(np.sum(P)), 1e-300)
     out_tokens.append(x_next)
     return {"path": path, "tokens": out_tokens, "n_accepted": len(path),
-            "accept_margin": min(margins) if margins else 1.0, "cdf_margin": cdf_margin, "final_P": P}
+            "accept_margin": min(margins) if margins else 1.0, "cdf_margin": cdf_margin, "final_P": P,
+            "rejected_from_row": rejected[True], "rejected_from_residual": rejected[False], "final_from_row": fresh}

@@ -5,7 +5,10 @@
 // Only what is a vector operation over the vocabulary is spread over the threads: the residual
 // (P - q)+ with its sum, and the final draw by inversion (chunk sums, a scan over the chunks, a count).
 // The tree's shape travels in the kernel arguments, so nothing is copied or allocated per call.
-// All arithmetic is float64; P is kept as (unnormalised vector, its sum) and divided where it is read.
+// All arithmetic is float64; P is kept as (unnormalised vector, 1 / its sum) and scaled where it is read.
+// What a test needs while P is still the target's own row (the token, r, P(x), q(x)) is fetched for all
+// nodes at once when the kernel starts, so a walk without rejections reads the vocabulary only for the
+// final draw.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -65,77 +68,179 @@ __device__ __forceinline__ double block_exclusive_scan(double v, double* s_red, 
     return base + inc - v;
 }
 
-__global__ void __launch_bounds__(WALK_THREADS) verify_walk_kernel(const WalkParams W) {
-    __shared__ double s_red[WALK_WAVES];
-    const int b = blockIdx.x, tid = threadIdx.x, V = W.vocab, N = W.t.n_nodes;
-    const int32_t* tokens = W.tokens + (size_t)b * N;
-    const float* q = W.q + (size_t)b * W.rows * V;
-    const float* p = W.p + (size_t)b * N * V;
-    const float* r = W.r + (size_t)b * N;
-    double* res = W.residual + (size_t)b * V;
+// W consecutive vocabulary entries as one load (W = 4 needs vocab % 4 == 0 and 16-byte aligned rows)
+template <int W> struct Vec;
+template <> struct Vec<1> { typedef float f; typedef double d; };
+template <> struct Vec<4> { typedef float4 f; typedef double4 d; };
+template <int W> __device__ __forceinline__ void widen(const typename Vec<W>::f& v, double (&o)[W]);
+template <> __device__ __forceinline__ void widen<1>(const float& v, double (&o)[1]) { o[0] = (double)v; }
+template <> __device__ __forceinline__ void widen<4>(const float4& v, double (&o)[4]) {
+    o[0] = (double)v.x; o[1] = (double)v.y; o[2] = (double)v.z; o[3] = (double)v.w;
+}
+template <int W> __device__ __forceinline__ void unpack(const typename Vec<W>::d& v, double (&o)[W]);
+template <> __device__ __forceinline__ void unpack<1>(const double& v, double (&o)[1]) { o[0] = v; }
+template <> __device__ __forceinline__ void unpack<4>(const double4& v, double (&o)[4]) { o[0] = v.x; o[1] = v.y; o[2] = v.z; o[3] = v.w; }
+template <int W> __device__ __forceinline__ typename Vec<W>::d pack(const double (&o)[W]);
+template <> __device__ __forceinline__ double pack<1>(const double (&o)[1]) { return o[0]; }
+template <> __device__ __forceinline__ double4 pack<4>(const double (&o)[4]) { return make_double4(o[0], o[1], o[2], o[3]); }
 
-    // P = fresh ? p[u] : res / tot.  Every thread takes every decision itself, from the same values.
+// The distribution P the walk holds: the target's row pu as it is (fresh), or res * inv_tot
+struct PState {
+    const float* pu;
+    bool fresh;
+    double inv_tot;
+};
+
+// P <- (P - qt)+ (not yet divided by its sum) into res; returns this thread's part of the sum.  Entries are
+// dealt to the threads W at a time, interleaved; UN loads per array are in flight before the first is used.
+template <int W>
+__device__ __forceinline__ double residual_pass(const PState P, double* __restrict__ res, const float* __restrict__ qt, int V) {
+    typedef typename Vec<W>::f VF;
+    typedef typename Vec<W>::d VD;
+    constexpr int UN = W == 4 ? 4 : 8;   // (registers: 1024 threads leave 128 per thread)
+    const int nvec = V / W;   // (W = 4: V % 4 == 0)
+    double local = 0.0;
+    for (int j0 = threadIdx.x; j0 < nvec; j0 += WALK_THREADS * UN) {
+        VF pv[UN], qv[UN];
+        VD rv[UN];
+#pragma unroll
+        for (int k = 0; k < UN; ++k) {
+            const int j = j0 + k * WALK_THREADS;
+            if (j < nvec) {
+                qv[k] = reinterpret_cast<const VF*>(qt)[j];
+                if (P.fresh) pv[k] = reinterpret_cast<const VF*>(P.pu)[j];
+                else rv[k] = reinterpret_cast<const VD*>(res)[j];
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < UN; ++k) {
+            const int j = j0 + k * WALK_THREADS;
+            if (j < nvec) {
+                double a[W], b[W];
+                if (P.fresh) widen<W>(pv[k], a);
+                else {
+                    unpack<W>(rv[k], a);
+#pragma unroll
+                    for (int e = 0; e < W; ++e) a[e] *= P.inv_tot;
+                }
+                widen<W>(qv[k], b);
+#pragma unroll
+                for (int e = 0; e < W; ++e) {
+                    a[e] = fmax(a[e] - b[e], 0.0);
+                    local += a[e];
+                }
+                reinterpret_cast<VD*>(res)[j] = pack<W>(a);
+            }
+        }
+    }
+    return local;
+}
+
+// The entries [c0, c1) of P (c0, c1 multiples of W) one after the other: f(value) in id order
+template <int W, typename F>
+__device__ __forceinline__ void for_chunk(const PState P, const double* __restrict__ res, int c0, int c1, F f) {
+    typedef typename Vec<W>::f VF;
+    typedef typename Vec<W>::d VD;
+    constexpr int UN = W == 4 ? 4 : 8;   // (registers: 1024 threads leave 128 per thread)
+    for (int j0 = c0 / W; j0 < c1 / W; j0 += UN) {
+        VF pv[UN];
+        VD rv[UN];
+#pragma unroll
+        for (int k = 0; k < UN; ++k) {
+            if (j0 + k < c1 / W) {
+                if (P.fresh) pv[k] = reinterpret_cast<const VF*>(P.pu)[j0 + k];
+                else rv[k] = reinterpret_cast<const VD*>(res)[j0 + k];
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < UN; ++k) {
+            if (j0 + k < c1 / W) {
+                double a[W];
+                if (P.fresh) widen<W>(pv[k], a);
+                else unpack<W>(rv[k], a);
+#pragma unroll
+                for (int e = 0; e < W; ++e) f(P.fresh ? a[e] : a[e] * P.inv_tot);
+            }
+        }
+    }
+}
+
+template <int W>
+__global__ void __launch_bounds__(WALK_THREADS) verify_walk_kernel(const WalkParams Wp) {
+    __shared__ double s_red[WALK_WAVES];
+    __shared__ int s_tok[PS_TREE_MAX_NODES];
+    __shared__ float s_r[PS_TREE_MAX_NODES], s_px[PS_TREE_MAX_NODES], s_qx[PS_TREE_MAX_NODES];
+    const int b = blockIdx.x, tid = threadIdx.x, V = Wp.vocab, N = Wp.t.n_nodes;
+    const float* q = Wp.q + (size_t)b * Wp.rows * V;
+    const float* p = Wp.p + (size_t)b * N * V;
+    double* res = Wp.residual + (size_t)b * V;
+
+    // Per node, in one round of loads: its token, its uniform number, and what a test of the node reads
+    // while P is still the target's own row at its parent: P(x) and q(x).
+    if (tid < N) {
+        const int x = Wp.tokens[(size_t)b * N + tid];
+        const bool ok = tid > 0 && (unsigned)x < (unsigned)V;
+        s_tok[tid] = ok ? x : -1;
+        s_r[tid] = Wp.r[(size_t)b * N + tid];
+        s_px[tid] = ok ? p[(size_t)Wp.t.parent[tid] * V + x] : 0.f;
+        s_qx[tid] = ok ? q[(size_t)(Wp.t.depth[tid] - 1) * V + x] : 0.f;
+    }
+    __syncthreads();
+
+    // Every thread takes every decision itself, from the same values.
     int u = 0, n_acc = 0;
-    bool fresh = true;
-    double tot = 1.0;
-    auto P_at = [&](int i) -> double { return fresh ? (double)p[(size_t)u * V + i] : res[i] / tot; };
+    PState P{p, true, 1.0};
     int s = 1;
     while (s < N) {   // the children of u lie behind it; they are met in ascending index
-        if (W.t.parent[s] != u) { ++s; continue; }
-        const int x = tokens[s];
+        if (Wp.t.parent[s] != u) { ++s; continue; }
+        const int x = s_tok[s];
         bool accept = false;
-        if ((unsigned)x < (unsigned)V) {
-            const float* qt = q + (size_t)(W.t.depth[s] - 1) * V;
-            const double Px = P_at(x), qx = (double)qt[x];
+        if (x >= 0) {
+            const float* qt = q + (size_t)(Wp.t.depth[s] - 1) * V;
+            const double Px = P.fresh ? (double)s_px[s] : res[x] * P.inv_tot, qx = (double)s_qx[s];
             const double ratio = qx > 0.0 ? fmin(1.0, Px / qx) : 1.0;
-            accept = (double)r[s] < ratio;
+            accept = (double)s_r[s] < ratio;
             if (!accept) {
                 __syncthreads();   // everyone has read P(x) before P changes
-                double local = 0.0;
-                for (int i = tid; i < V; i += WALK_THREADS) {
-                    const double v = fmax(P_at(i) - (double)qt[i], 0.0);
-                    res[i] = v;
-                    local += v;
-                }
-                const double t = block_sum(local, s_red);   // (its barriers also publish res)
-                tot = t > 0.0 ? t : 1.0;
-                fresh = false;
+                const double t = block_sum(residual_pass<W>(P, res, qt, V), s_red);   // (its barriers also publish res)
+                P.fresh = false;
+                P.inv_tot = t > 0.0 ? 1.0 / t : 1.0;
             }
         }
         if (accept) {
             if (tid == 0) {
-                W.path[(size_t)b * W.rows + n_acc] = s;
-                W.out_tokens[(size_t)b * (W.rows + 1) + n_acc] = x;
+                Wp.path[(size_t)b * Wp.rows + n_acc] = s;
+                Wp.out_tokens[(size_t)b * (Wp.rows + 1) + n_acc] = x;
             }
             ++n_acc;
             u = s;
-            fresh = true;
-            tot = 1.0;
+            P = PState{p + (size_t)u * V, true, 1.0};
             s = u + 1;
         } else {
             ++s;
         }
     }
 
-    // the last token: inversion of the cumulative sum in token-id order
-    const int chunk = (V + WALK_THREADS - 1) / WALK_THREADS;
+    // the last token: inversion of the cumulative sum in token-id order; thread t holds a run of ids
+    int chunk = (V + WALK_THREADS - 1) / WALK_THREADS;
+    chunk = (chunk + W - 1) / W * W;
     const int c0 = min(V, tid * chunk), c1 = min(V, c0 + chunk);
     double local = 0.0;
-    for (int i = c0; i < c1; ++i) local += P_at(i);
+    for_chunk<W>(P, res, c0, c1, [&](double v) { local += v; });
     double total;
     double run = block_exclusive_scan(local, s_red, total);
-    const double target = (double)r[0] * total;
+    const double target = (double)s_r[0] * total;
     double cnt = 0.0;
-    for (int i = c0; i < c1; ++i) {
-        run += P_at(i);
+    for_chunk<W>(P, res, c0, c1, [&](double v) {
+        run += v;
         if (run <= target) cnt += 1.0;
-    }
+    });
     const int n = (int)block_sum(cnt, s_red);   // (a count below 2^53: exact)
     if (tid == 0) {
-        W.out_tokens[(size_t)b * (W.rows + 1) + n_acc] = n < V - 1 ? n : V - 1;
-        for (int i = n_acc + 1; i <= W.rows; ++i) W.out_tokens[(size_t)b * (W.rows + 1) + i] = -1;
-        for (int i = n_acc; i < W.rows; ++i) W.path[(size_t)b * W.rows + i] = -1;
-        W.n_accepted[b] = n_acc;
+        Wp.out_tokens[(size_t)b * (Wp.rows + 1) + n_acc] = n < V - 1 ? n : V - 1;
+        for (int i = n_acc + 1; i <= Wp.rows; ++i) Wp.out_tokens[(size_t)b * (Wp.rows + 1) + i] = -1;
+        for (int i = n_acc; i < Wp.rows; ++i) Wp.path[(size_t)b * Wp.rows + i] = -1;
+        Wp.n_accepted[b] = n_acc;
     }
 }
 
@@ -196,6 +301,9 @@ extern "C" int ps_verify_walk(const ps_tree_shape* tree, const ps_verify_args* a
     W.rows = a->rows; W.vocab = a->vocab;
     W.tokens = a->tokens; W.q = a->q; W.p = a->p; W.r = a->r; W.residual = a->residual;
     W.n_accepted = a->n_accepted; W.path = a->path; W.out_tokens = a->out_tokens;
-    hipLaunchKernelGGL(verify_walk_kernel, dim3(a->batch), dim3(WALK_THREADS), 0, (hipStream_t)stream, W);
+    // whole vectors of four entries when every row of q, p and the scratch starts on a 16-byte boundary
+    const bool vec = a->vocab % 4 == 0 && (((uintptr_t)a->q | (uintptr_t)a->p) & 15) == 0 && ((uintptr_t)a->residual & 31) == 0;
+    if (vec) hipLaunchKernelGGL(verify_walk_kernel<4>, dim3(a->batch), dim3(WALK_THREADS), 0, (hipStream_t)stream, W);
+    else hipLaunchKernelGGL(verify_walk_kernel<1>, dim3(a->batch), dim3(WALK_THREADS), 0, (hipStream_t)stream, W);
     return hipGetLastError() == hipSuccess ? PS_OK : PS_ERR_DEVICE;
 }
