@@ -39,16 +39,18 @@ struct TokensParams {
 };
 
 // sum over the workgroup, the same in every thread: lanes pairwise, then the wavefronts in order
+template <int NWAVES = WALK_WAVES>
 __device__ __forceinline__ double block_sum(double v, double* s_red) {
     for (int o = 32; o > 0; o >>= 1) v += __shfl_down(v, o);
     __syncthreads();   // s_red may still be read from the previous use
     if ((threadIdx.x & 63) == 0) s_red[threadIdx.x >> 6] = v;
     __syncthreads();
     double t = 0.0;
-    for (int w = 0; w < WALK_WAVES; ++w) t += s_red[w];
+    for (int w = 0; w < NWAVES; ++w) t += s_red[w];
     return t;
 }
 // exclusive prefix sum over the threads in thread order; total = the sum over all of them
+template <int NWAVES = WALK_WAVES>
 __device__ __forceinline__ double block_exclusive_scan(double v, double* s_red, double& total) {
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     double inc = v;
@@ -61,7 +63,7 @@ __device__ __forceinline__ double block_exclusive_scan(double v, double* s_red, 
     __syncthreads();
     double base = 0.0;
     total = 0.0;
-    for (int i = 0; i < WALK_WAVES; ++i) {
+    for (int i = 0; i < NWAVES; ++i) {
         if (i < w) base += s_red[i];
         total += s_red[i];
     }
@@ -244,6 +246,182 @@ __global__ void __launch_bounds__(WALK_THREADS) verify_walk_kernel(const WalkPar
     }
 }
 
+// The same walk for vocabularies of at most REG_EPT * REG_THREADS entries (a multiple of 4, rows 16-byte
+// aligned): P lives in registers, so a rejection only reads its row of q (and, the first time at a node, the
+// target's row) and the scratch buffer is not touched.  The vocabulary is cut into slabs of 4 * REG_THREADS
+// entries; thread t holds entries [4t, 4t + 4) of every slab, so all loads are contiguous across a wavefront.
+// P(x) of a residual goes from the thread that holds it to the others through LDS.  The final draw finds
+// the slab in which the cumulative sum passes the target from the slabs' totals, then scans that slab.
+constexpr int REG_EPT = 32, REG_THREADS = 1024, REG_WAVES = REG_THREADS / 64, REG_SLABS = REG_EPT / 4;
+__global__ void __launch_bounds__(REG_THREADS) verify_walk_reg_kernel(const WalkParams Wp) {
+    __shared__ double s_red[REG_WAVES];
+    __shared__ double s_part[REG_SLABS][REG_WAVES];
+    __shared__ double s_bc;
+    __shared__ int s_tok[PS_TREE_MAX_NODES];
+    __shared__ float s_r[PS_TREE_MAX_NODES], s_px[PS_TREE_MAX_NODES], s_qx[PS_TREE_MAX_NODES];
+    const int b = blockIdx.x, tid = threadIdx.x, V = Wp.vocab, N = Wp.t.n_nodes;
+    const float* q = Wp.q + (size_t)b * Wp.rows * V;
+    const float* p = Wp.p + (size_t)b * N * V;
+    if (tid < N) {
+        const int x = Wp.tokens[(size_t)b * N + tid];
+        const bool ok = tid > 0 && (unsigned)x < (unsigned)V;
+        s_tok[tid] = ok ? x : -1;
+        s_r[tid] = Wp.r[(size_t)b * N + tid];
+        s_px[tid] = ok ? p[(size_t)Wp.t.parent[tid] * V + x] : 0.f;
+        s_qx[tid] = ok ? q[(size_t)(Wp.t.depth[tid] - 1) * V + x] : 0.f;
+    }
+    __syncthreads();
+
+    const int nvec = V / 4;                      // float4 units; this thread's: tid + REG_THREADS * k
+    double Pr[REG_EPT];                          // P (to be scaled by inv_tot) once it is no longer a row of p:
+                                                 // Pr[4k + e] = entry 4 (tid + REG_THREADS k) + e, 0 beyond V
+    int u = 0, n_acc = 0;
+    bool fresh = true;
+    double inv_tot = 1.0;
+    // Pr <- the target's row at u (P = that row: inv_tot = 1)
+    auto load_row = [&]() {
+        const float4* pu4 = reinterpret_cast<const float4*>(p + (size_t)u * V);
+        float4 pv[REG_SLABS];
+#pragma unroll
+        for (int k = 0; k < REG_SLABS; ++k) {
+            const int j = tid + REG_THREADS * k;
+            pv[k] = j < nvec ? pu4[j] : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+#pragma unroll
+        for (int k = 0; k < REG_SLABS; ++k) {
+            Pr[4 * k] = (double)pv[k].x; Pr[4 * k + 1] = (double)pv[k].y;
+            Pr[4 * k + 2] = (double)pv[k].z; Pr[4 * k + 3] = (double)pv[k].w;
+        }
+    };
+    // Pr <- (Pr * inv_tot - qt)+; returns this thread's part of the sum
+    auto subtract = [&](const float* __restrict__ qt) -> double {
+        const float4* q4 = reinterpret_cast<const float4*>(qt);
+        float4 qv[REG_SLABS];
+#pragma unroll
+        for (int k = 0; k < REG_SLABS; ++k) {
+            const int j = tid + REG_THREADS * k;
+            qv[k] = j < nvec ? q4[j] : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+        double local = 0.0;
+#pragma unroll
+        for (int k = 0; k < REG_SLABS; ++k) {
+            const float qe[4] = {qv[k].x, qv[k].y, qv[k].z, qv[k].w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const double v = fmax(Pr[4 * k + e] * inv_tot - (double)qe[e], 0.0);
+                Pr[4 * k + e] = v;
+                local += v;
+            }
+        }
+        return local;
+    };
+
+    int s = 1;
+    while (s < N) {
+        if (Wp.t.parent[s] != u) { ++s; continue; }
+        const int x = s_tok[s];
+        bool accept = false;
+        if (x >= 0) {
+            double Px;
+            if (fresh) {
+                Px = (double)s_px[s];
+            } else {
+                const int j = x >> 2;   // unit j is slab j / REG_THREADS of thread j % REG_THREADS
+                if (tid == (j & (REG_THREADS - 1))) {
+                    const int idx = 4 * (j / REG_THREADS) + (x & 3);
+                    double v = 0.0;
+#pragma unroll
+                    for (int e = 0; e < REG_EPT; ++e)
+                        if (e == idx) v = Pr[e];
+                    s_bc = v * inv_tot;
+                }
+                __syncthreads();   // (the next write of s_bc lies behind the barriers of a block_sum)
+                Px = s_bc;
+            }
+            const double qx = (double)s_qx[s];
+            const double ratio = qx > 0.0 ? fmin(1.0, Px / qx) : 1.0;
+            accept = (double)s_r[s] < ratio;
+            if (!accept) {
+                if (fresh) load_row();
+                fresh = false;
+                const double t = block_sum<REG_WAVES>(subtract(q + (size_t)(Wp.t.depth[s] - 1) * V), s_red);
+                inv_tot = t > 0.0 ? 1.0 / t : 1.0;
+            }
+        }
+        if (accept) {
+            if (tid == 0) {
+                Wp.path[(size_t)b * Wp.rows + n_acc] = s;
+                Wp.out_tokens[(size_t)b * (Wp.rows + 1) + n_acc] = x;
+            }
+            ++n_acc;
+            u = s;
+            fresh = true;
+            inv_tot = 1.0;
+            s = u + 1;
+        } else {
+            ++s;
+        }
+    }
+
+    // The last token.  Totals of the slabs (each wavefront adds up its part of every slab, the wavefronts'
+    // parts meet in LDS), the slab ks in which the cumulative sum first exceeds the target, then the
+    // cumulative sum inside that slab in id order.
+    if (fresh) load_row();
+    const int lane = tid & 63, wave = tid >> 6;
+#pragma unroll
+    for (int k = 0; k < REG_SLABS; ++k) {
+        double v = 0.0;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            Pr[4 * k + e] *= inv_tot;   // (1 for a row of p: exact)
+            v += Pr[4 * k + e];
+        }
+        for (int o = 32; o > 0; o >>= 1) v += __shfl_down(v, o);
+        if (lane == 0) s_part[k][wave] = v;
+    }
+    __syncthreads();
+    double slab_tot[REG_SLABS], total = 0.0;
+#pragma unroll
+    for (int k = 0; k < REG_SLABS; ++k) {
+        double t = 0.0;
+        for (int w = 0; w < REG_WAVES; ++w) t += s_part[k][w];
+        slab_tot[k] = t;
+        total += t;
+    }
+    const double target = (double)s_r[0] * total;
+    const int n_slabs = (nvec + REG_THREADS - 1) / REG_THREADS;
+    int ks = n_slabs - 1;
+    double base = 0.0, cum = 0.0;
+    bool found = false;
+#pragma unroll
+    for (int k = 0; k < REG_SLABS; ++k) {
+        if (k < n_slabs && !found) {
+            if (cum + slab_tot[k] > target || k == n_slabs - 1) { ks = k; base = cum; found = true; }
+            cum += slab_tot[k];
+        }
+    }
+    double mine[4] = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+    for (int k = 0; k < REG_SLABS; ++k)
+        if (k == ks) { mine[0] = Pr[4 * k]; mine[1] = Pr[4 * k + 1]; mine[2] = Pr[4 * k + 2]; mine[3] = Pr[4 * k + 3]; }
+    double dummy;
+    double run = base + block_exclusive_scan<REG_WAVES>(mine[0] + mine[1] + mine[2] + mine[3], s_red, dummy);
+    const int id0 = 4 * (tid + REG_THREADS * ks);
+    double cnt = 0.0;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        run += mine[e];
+        if (id0 + e < V && run <= target) cnt += 1.0;
+    }
+    const int n = 4 * REG_THREADS * ks + (int)block_sum<REG_WAVES>(cnt, s_red);   // every id of the slabs before ks counts
+    if (tid == 0) {
+        Wp.out_tokens[(size_t)b * (Wp.rows + 1) + n_acc] = n < V - 1 ? n : V - 1;
+        for (int i = n_acc + 1; i <= Wp.rows; ++i) Wp.out_tokens[(size_t)b * (Wp.rows + 1) + i] = -1;
+        for (int i = n_acc; i < Wp.rows; ++i) Wp.path[(size_t)b * Wp.rows + i] = -1;
+        Wp.n_accepted[b] = n_acc;
+    }
+}
+
 __global__ void __launch_bounds__(PS_TREE_MAX_NODES) tree_tokens_kernel(const TokensParams T) {
     const int b = blockIdx.x, s = threadIdx.x;
     if (s >= T.t.n_nodes) return;
@@ -303,7 +481,9 @@ extern "C" int ps_verify_walk(const ps_tree_shape* tree, const ps_verify_args* a
     W.n_accepted = a->n_accepted; W.path = a->path; W.out_tokens = a->out_tokens;
     // whole vectors of four entries when every row of q, p and the scratch starts on a 16-byte boundary
     const bool vec = a->vocab % 4 == 0 && (((uintptr_t)a->q | (uintptr_t)a->p) & 15) == 0 && ((uintptr_t)a->residual & 31) == 0;
-    if (vec) hipLaunchKernelGGL(verify_walk_kernel<4>, dim3(a->batch), dim3(WALK_THREADS), 0, (hipStream_t)stream, W);
+    if (vec && a->vocab <= REG_EPT * REG_THREADS)
+        hipLaunchKernelGGL(verify_walk_reg_kernel, dim3(a->batch), dim3(REG_THREADS), 0, (hipStream_t)stream, W);
+    else if (vec) hipLaunchKernelGGL(verify_walk_kernel<4>, dim3(a->batch), dim3(WALK_THREADS), 0, (hipStream_t)stream, W);
     else hipLaunchKernelGGL(verify_walk_kernel<1>, dim3(a->batch), dim3(WALK_THREADS), 0, (hipStream_t)stream, W);
     return hipGetLastError() == hipSuccess ? PS_OK : PS_ERR_DEVICE;
 }
