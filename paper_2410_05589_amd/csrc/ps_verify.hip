@@ -22,6 +22,7 @@ constexpr int WALK_THREADS = 1024, WALK_WAVES = WALK_THREADS / 64;
 struct TreeDev {
     int n_nodes, max_depth;
     int parent[PS_TREE_MAX_NODES], depth[PS_TREE_MAX_NODES], rank[PS_TREE_MAX_NODES];
+    int first_child[PS_TREE_MAX_NODES], next_sibling[PS_TREE_MAX_NODES];   // children in ascending index; -1 = none
 };
 struct WalkParams {
     TreeDev t;
@@ -68,6 +69,30 @@ __device__ __forceinline__ double block_exclusive_scan(double v, double* s_red, 
         total += s_red[i];
     }
     return base + inc - v;
+}
+
+// What the walk needs per node, fetched by one thread per node in one round of loads and left in LDS: the
+// node's links (read one after the other from the kernel arguments they would cost a scalar-cache miss
+// each), its token (-1 if outside the vocabulary), its uniform number, and what a test of the node reads
+// while P is still the target's own row at its parent: P(x) and q(x).
+struct NodeLds {
+    int tok[PS_TREE_MAX_NODES], first[PS_TREE_MAX_NODES], next[PS_TREE_MAX_NODES], depth[PS_TREE_MAX_NODES];
+    float r[PS_TREE_MAX_NODES], px[PS_TREE_MAX_NODES], qx[PS_TREE_MAX_NODES];
+};
+__device__ __forceinline__ void load_nodes(const WalkParams& Wp, int b, const float* q, const float* p, NodeLds& L) {
+    const int tid = threadIdx.x, V = Wp.vocab, N = Wp.t.n_nodes;
+    if (tid < N) {
+        const int x = Wp.tokens[(size_t)b * N + tid];
+        const bool ok = tid > 0 && (unsigned)x < (unsigned)V;
+        L.tok[tid] = ok ? x : -1;
+        L.first[tid] = Wp.t.first_child[tid];
+        L.next[tid] = Wp.t.next_sibling[tid];
+        L.depth[tid] = Wp.t.depth[tid];
+        L.r[tid] = Wp.r[(size_t)b * N + tid];
+        L.px[tid] = ok ? p[(size_t)Wp.t.parent[tid] * V + x] : 0.f;
+        L.qx[tid] = ok ? q[(size_t)(Wp.t.depth[tid] - 1) * V + x] : 0.f;
+    }
+    __syncthreads();
 }
 
 // W consecutive vocabulary entries as one load (W = 4 needs vocab % 4 == 0 and 16-byte aligned rows)
@@ -170,38 +195,25 @@ __device__ __forceinline__ void for_chunk(const PState P, const double* __restri
 template <int W>
 __global__ void __launch_bounds__(WALK_THREADS) verify_walk_kernel(const WalkParams Wp) {
     __shared__ double s_red[WALK_WAVES];
-    __shared__ int s_tok[PS_TREE_MAX_NODES];
-    __shared__ float s_r[PS_TREE_MAX_NODES], s_px[PS_TREE_MAX_NODES], s_qx[PS_TREE_MAX_NODES];
+    __shared__ NodeLds L;
     const int b = blockIdx.x, tid = threadIdx.x, V = Wp.vocab, N = Wp.t.n_nodes;
     const float* q = Wp.q + (size_t)b * Wp.rows * V;
     const float* p = Wp.p + (size_t)b * N * V;
     double* res = Wp.residual + (size_t)b * V;
-
-    // Per node, in one round of loads: its token, its uniform number, and what a test of the node reads
-    // while P is still the target's own row at its parent: P(x) and q(x).
-    if (tid < N) {
-        const int x = Wp.tokens[(size_t)b * N + tid];
-        const bool ok = tid > 0 && (unsigned)x < (unsigned)V;
-        s_tok[tid] = ok ? x : -1;
-        s_r[tid] = Wp.r[(size_t)b * N + tid];
-        s_px[tid] = ok ? p[(size_t)Wp.t.parent[tid] * V + x] : 0.f;
-        s_qx[tid] = ok ? q[(size_t)(Wp.t.depth[tid] - 1) * V + x] : 0.f;
-    }
-    __syncthreads();
+    load_nodes(Wp, b, q, p, L);
 
     // Every thread takes every decision itself, from the same values.
     int u = 0, n_acc = 0;
     PState P{p, true, 1.0};
-    int s = 1;
-    while (s < N) {   // the children of u lie behind it; they are met in ascending index
-        if (Wp.t.parent[s] != u) { ++s; continue; }
-        const int x = s_tok[s];
+    int s = L.first[0];
+    while (s >= 0) {   // the children of u in ascending index
+        const int x = L.tok[s];
         bool accept = false;
         if (x >= 0) {
-            const float* qt = q + (size_t)(Wp.t.depth[s] - 1) * V;
-            const double Px = P.fresh ? (double)s_px[s] : res[x] * P.inv_tot, qx = (double)s_qx[s];
+            const float* qt = q + (size_t)(L.depth[s] - 1) * V;
+            const double Px = P.fresh ? (double)L.px[s] : res[x] * P.inv_tot, qx = (double)L.qx[s];
             const double ratio = qx > 0.0 ? fmin(1.0, Px / qx) : 1.0;
-            accept = (double)s_r[s] < ratio;
+            accept = (double)L.r[s] < ratio;
             if (!accept) {
                 __syncthreads();   // everyone has read P(x) before P changes
                 const double t = block_sum(residual_pass<W>(P, res, qt, V), s_red);   // (its barriers also publish res)
@@ -217,9 +229,9 @@ __global__ void __launch_bounds__(WALK_THREADS) verify_walk_kernel(const WalkPar
             ++n_acc;
             u = s;
             P = PState{p + (size_t)u * V, true, 1.0};
-            s = u + 1;
+            s = L.first[u];
         } else {
-            ++s;
+            s = L.next[s];
         }
     }
 
@@ -231,7 +243,7 @@ __global__ void __launch_bounds__(WALK_THREADS) verify_walk_kernel(const WalkPar
     for_chunk<W>(P, res, c0, c1, [&](double v) { local += v; });
     double total;
     double run = block_exclusive_scan(local, s_red, total);
-    const double target = (double)s_r[0] * total;
+    const double target = (double)L.r[0] * total;
     double cnt = 0.0;
     for_chunk<W>(P, res, c0, c1, [&](double v) {
         run += v;
@@ -257,20 +269,11 @@ __global__ void __launch_bounds__(REG_THREADS) verify_walk_reg_kernel(const Walk
     __shared__ double s_red[REG_WAVES];
     __shared__ double s_part[REG_SLABS][REG_WAVES];
     __shared__ double s_bc;
-    __shared__ int s_tok[PS_TREE_MAX_NODES];
-    __shared__ float s_r[PS_TREE_MAX_NODES], s_px[PS_TREE_MAX_NODES], s_qx[PS_TREE_MAX_NODES];
+    __shared__ NodeLds L;
     const int b = blockIdx.x, tid = threadIdx.x, V = Wp.vocab, N = Wp.t.n_nodes;
     const float* q = Wp.q + (size_t)b * Wp.rows * V;
     const float* p = Wp.p + (size_t)b * N * V;
-    if (tid < N) {
-        const int x = Wp.tokens[(size_t)b * N + tid];
-        const bool ok = tid > 0 && (unsigned)x < (unsigned)V;
-        s_tok[tid] = ok ? x : -1;
-        s_r[tid] = Wp.r[(size_t)b * N + tid];
-        s_px[tid] = ok ? p[(size_t)Wp.t.parent[tid] * V + x] : 0.f;
-        s_qx[tid] = ok ? q[(size_t)(Wp.t.depth[tid] - 1) * V + x] : 0.f;
-    }
-    __syncthreads();
+    load_nodes(Wp, b, q, p, L);
 
     const int nvec = V / 4;                      // float4 units; this thread's: tid + REG_THREADS * k
     double Pr[REG_EPT];                          // P (to be scaled by inv_tot) once it is no longer a row of p:
@@ -316,15 +319,14 @@ __global__ void __launch_bounds__(REG_THREADS) verify_walk_reg_kernel(const Walk
         return local;
     };
 
-    int s = 1;
-    while (s < N) {
-        if (Wp.t.parent[s] != u) { ++s; continue; }
-        const int x = s_tok[s];
+    int s = L.first[0];
+    while (s >= 0) {   // the children of u in ascending index
+        const int x = L.tok[s];
         bool accept = false;
         if (x >= 0) {
             double Px;
             if (fresh) {
-                Px = (double)s_px[s];
+                Px = (double)L.px[s];
             } else {
                 const int j = x >> 2;   // unit j is slab j / REG_THREADS of thread j % REG_THREADS
                 if (tid == (j & (REG_THREADS - 1))) {
@@ -338,13 +340,13 @@ __global__ void __launch_bounds__(REG_THREADS) verify_walk_reg_kernel(const Walk
                 __syncthreads();   // (the next write of s_bc lies behind the barriers of a block_sum)
                 Px = s_bc;
             }
-            const double qx = (double)s_qx[s];
+            const double qx = (double)L.qx[s];
             const double ratio = qx > 0.0 ? fmin(1.0, Px / qx) : 1.0;
-            accept = (double)s_r[s] < ratio;
+            accept = (double)L.r[s] < ratio;
             if (!accept) {
                 if (fresh) load_row();
                 fresh = false;
-                const double t = block_sum<REG_WAVES>(subtract(q + (size_t)(Wp.t.depth[s] - 1) * V), s_red);
+                const double t = block_sum<REG_WAVES>(subtract(q + (size_t)(L.depth[s] - 1) * V), s_red);
                 inv_tot = t > 0.0 ? 1.0 / t : 1.0;
             }
         }
@@ -357,9 +359,9 @@ __global__ void __launch_bounds__(REG_THREADS) verify_walk_reg_kernel(const Walk
             u = s;
             fresh = true;
             inv_tot = 1.0;
-            s = u + 1;
+            s = L.first[u];
         } else {
-            ++s;
+            s = L.next[s];
         }
     }
 
@@ -388,7 +390,7 @@ __global__ void __launch_bounds__(REG_THREADS) verify_walk_reg_kernel(const Walk
         slab_tot[k] = t;
         total += t;
     }
-    const double target = (double)s_r[0] * total;
+    const double target = (double)L.r[0] * total;
     const int n_slabs = (nvec + REG_THREADS - 1) / REG_THREADS;
     int ks = n_slabs - 1;
     double base = 0.0, cum = 0.0;
@@ -438,7 +440,9 @@ int load_tree(const ps_tree_shape* tree, int rows, int topk, TreeDev* out) {
     if (N < 1 || N > PS_TREE_MAX_NODES || tree->parent[0] != -1) return PS_ERR_SHAPE;
     out->n_nodes = N;
     out->max_depth = 0;
-    for (int s = 0; s < PS_TREE_MAX_NODES; ++s) { out->parent[s] = -1; out->depth[s] = 0; out->rank[s] = 0; }
+    for (int s = 0; s < PS_TREE_MAX_NODES; ++s) {
+        out->parent[s] = -1; out->depth[s] = 0; out->rank[s] = 0; out->first_child[s] = -1; out->next_sibling[s] = -1;
+    }
     for (int s = 1; s < N; ++s) {
         const int pa = tree->parent[s];
         if (pa < 0 || pa >= s) return PS_ERR_SHAPE;
@@ -450,6 +454,10 @@ int load_tree(const ps_tree_shape* tree, int rows, int topk, TreeDev* out) {
             if (tree->rank[s] < 0 || tree->rank[s] >= topk) return PS_ERR_SHAPE;
             out->rank[s] = tree->rank[s];
         }
+    }
+    for (int s = N - 1; s >= 1; --s) {   // prepending in descending order leaves every list ascending
+        out->next_sibling[s] = out->first_child[out->parent[s]];
+        out->first_child[out->parent[s]] = s;
     }
     return PS_OK;
 }
