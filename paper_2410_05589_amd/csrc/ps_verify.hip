@@ -39,10 +39,42 @@ struct TokensParams {
     int32_t* tokens;
 };
 
-// sum over the workgroup, the same in every thread: lanes pairwise, then the wavefronts in order
+// Wavefront-wide sums of doubles with DPP lane exchanges (a row = 16 lanes); a lane without a source
+// receives 0.0 and adds nothing.  The order of the additions is fixed.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ double dpp_f64(double v) {
+    const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(v), CTRL, ROW_MASK, 0xF, false);
+    const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(v), CTRL, ROW_MASK, 0xF, false);
+    return __hiloint2double(hi, lo);
+}
+__device__ __forceinline__ double lane63(double v) {
+    return __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(v), 63), __builtin_amdgcn_readlane(__double2loint(v), 63));
+}
+// the sum over the wavefront, in every lane
+__device__ __forceinline__ double wave_sum_f64(double v) {
+    v += dpp_f64<0xB1, 0xF>(v);    // quad_perm [1,0,3,2]
+    v += dpp_f64<0x4E, 0xF>(v);    // quad_perm [2,3,0,1]
+    v += dpp_f64<0x141, 0xF>(v);   // row_half_mirror
+    v += dpp_f64<0x140, 0xF>(v);   // row_mirror: every lane holds its row's sum
+    v += dpp_f64<0x142, 0xA>(v);   // row_bcast:15 into rows 1 and 3
+    v += dpp_f64<0x143, 0xC>(v);   // row_bcast:31 into rows 2 and 3: lane 63 holds the total
+    return lane63(v);
+}
+// inclusive prefix sum over the lanes of the wavefront
+__device__ __forceinline__ double wave_inclusive_scan_f64(double v) {
+    v += dpp_f64<0x111, 0xF>(v);   // row_shr:1
+    v += dpp_f64<0x112, 0xF>(v);   // row_shr:2
+    v += dpp_f64<0x114, 0xF>(v);   // row_shr:4
+    v += dpp_f64<0x118, 0xF>(v);   // row_shr:8: prefix sums inside every row
+    v += dpp_f64<0x142, 0xA>(v);   // rows 1 and 3 add the total of the row before
+    v += dpp_f64<0x143, 0xC>(v);   // rows 2 and 3 add the total of rows 0 and 1
+    return v;
+}
+
+// sum over the workgroup, the same in every thread: inside the wavefronts, then the wavefronts in order
 template <int NWAVES = WALK_WAVES>
 __device__ __forceinline__ double block_sum(double v, double* s_red) {
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_down(v, o);
+    v = wave_sum_f64(v);
     __syncthreads();   // s_red may still be read from the previous use
     if ((threadIdx.x & 63) == 0) s_red[threadIdx.x >> 6] = v;
     __syncthreads();
@@ -54,11 +86,7 @@ __device__ __forceinline__ double block_sum(double v, double* s_red) {
 template <int NWAVES = WALK_WAVES>
 __device__ __forceinline__ double block_exclusive_scan(double v, double* s_red, double& total) {
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-    double inc = v;
-    for (int o = 1; o < 64; o <<= 1) {
-        const double t = __shfl_up(inc, o);
-        if (lane >= o) inc += t;
-    }
+    const double inc = wave_inclusive_scan_f64(v);
     __syncthreads();
     if (lane == 63) s_red[w] = inc;
     __syncthreads();
@@ -378,7 +406,7 @@ __global__ void __launch_bounds__(REG_THREADS) verify_walk_reg_kernel(const Walk
             Pr[4 * k + e] *= inv_tot;   // (1 for a row of p: exact)
             v += Pr[4 * k + e];
         }
-        for (int o = 32; o > 0; o >>= 1) v += __shfl_down(v, o);
+        v = wave_sum_f64(v);
         if (lane == 0) s_part[k][wave] = v;
     }
     __syncthreads();
