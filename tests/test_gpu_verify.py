@@ -147,3 +147,65 @@ def test_walk_after_a_draft_step_end_to_end():
         if depth[s] < rows:
             vin["p"][:, s] = (0.8 * q[:, depth[s]] + 0.2 * vin["p"][:, s]).astype(np.float32)
     _check(parent, rank, vin, rows, 4, "after a draft step")
+
+
+def test_tree_and_walk_replayed_from_a_graph():
+    """Both calls allocate and copy nothing, so they can be captured; replays with new inputs written into
+    the captured buffers are each compared with the oracle, with eager calls in between."""
+    import torch
+    dev = torch.device("cuda:0")
+    for vocab in (32000, 40004):          # P in registers / P in the scratch buffer
+        parent, rank = inputs.draft_tree([3, 2, 2, 1])
+        rows, topk, batch, n = 5, 8, 3, len(parent)
+        tree = VF.make_tree(parent, rank)
+        inp = inputs.verify_inputs(20, batch, parent, rank, rows, topk, vocab)
+        top_ids = torch.from_numpy(inp["top_ids"]).to(dev)
+        tokens = torch.zeros((batch, n), dtype=torch.int32, device=dev)
+        q, p, r = (torch.from_numpy(inp[x]).to(dev) for x in ("q", "p", "r"))
+        residual = torch.zeros((batch, vocab), dtype=torch.float64, device=dev)
+        n_acc = torch.zeros((batch,), dtype=torch.int32, device=dev)
+        path = torch.zeros((batch, rows), dtype=torch.int32, device=dev)
+        out_tokens = torch.zeros((batch, rows + 1), dtype=torch.int32, device=dev)
+        a = VF.ps_verify_args()
+        a.batch, a.rows, a.vocab = batch, rows, vocab
+        a.tokens, a.q, a.p, a.r = tokens.data_ptr(), q.data_ptr(), p.data_ptr(), r.data_ptr()
+        a.residual, a.n_accepted, a.path, a.out_tokens = (residual.data_ptr(), n_acc.data_ptr(), path.data_ptr(),
+                                                          out_tokens.data_ptr())
+
+        def both(stream):
+            assert VF.ps_tree_tokens(tree, batch, rows, topk, top_ids.data_ptr(), tokens.data_ptr(), stream) == B.PS_OK
+            assert VF.ps_verify_walk(tree, a, stream) == B.PS_OK
+
+        def check(cur, label):
+            torch.cuda.synchronize()
+            got_n, got_path, got_tok = n_acc.cpu().numpy(), path.cpu().numpy(), out_tokens.cpu().numpy()
+            for b in range(batch):
+                tok = vw.tree_tokens(cur["top_ids"][b], parent, rank)
+                ref = vw.acceptance_walk(parent, tok, cur["q"][b], cur["p"][b], cur["r"][b])
+                if ref["accept_margin"] <= MARGIN or ref["cdf_margin"] <= MARGIN:
+                    continue
+                na = ref["n_accepted"]
+                assert got_n[b] == na, (label, b)
+                assert got_path[b].tolist() == ref["path"] + [-1] * (rows - na), (label, b)
+                assert got_tok[b].tolist() == ref["tokens"] + [-1] * (rows - na), (label, b)
+
+        both(torch.cuda.current_stream().cuda_stream)        # eager first
+        check(inp, "eager V%d" % vocab)
+        side = torch.cuda.Stream()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(graph, stream=side):
+                both(side.cuda_stream)
+        torch.cuda.synchronize()
+        for rep in range(4):
+            cur = inputs.verify_inputs(30 + rep, batch, parent, rank, rows, topk, vocab, agreement=(0.3, 0.9, 0.6, 0.75)[rep])
+            top_ids.copy_(torch.from_numpy(cur["top_ids"])); q.copy_(torch.from_numpy(cur["q"]))
+            p.copy_(torch.from_numpy(cur["p"])); r.copy_(torch.from_numpy(cur["r"]))
+            n_acc.fill_(-7); path.fill_(-7); out_tokens.fill_(-7); tokens.fill_(-7)
+            torch.cuda.synchronize()
+            print("replay", rep, "vocab", vocab, flush=True)
+            graph.replay()
+            check(cur, "replay %d V%d" % (rep, vocab))
+            if rep % 2 == 0:
+                both(torch.cuda.current_stream().cuda_stream)
+                check(cur, "eager after replay %d V%d" % (rep, vocab))
