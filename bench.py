@@ -49,8 +49,9 @@ def verify_walk_report(torch, with_oracle, calls=200):
     """Tree construction + acceptance walk (the step after the draft step in Algorithm 1) on a tree of the
     c1 drafter's shape: 61 nodes (fan-out 4, 2, 2, 1, 1 over the k+1 = 6 draft rows), vocabulary 32000,
     one sequence, a target that agrees with the drafter's next row to 70 %.  Latency per call from HIP
-    events over `calls` back-to-back calls; bytes = what the walk has to touch (per rejection: P, q and
-    the new residual; the final draw: P once), counted on the oracle's walk of the same inputs."""
+    events over `calls` back-to-back calls; bytes = what the walk has to read when P stays on chip (first
+    rejection at a node: the target's row and the draft row; further ones: the draft row; the final draw: the
+    target's row if P is still that row), counted on the oracle's walk of the same inputs."""
     from paper_2410_05589_amd import inputs
     from paper_2410_05589_amd import verify as VF
     dev = torch.device("cuda:0")
@@ -62,15 +63,13 @@ def verify_walk_report(torch, with_oracle, calls=200):
     top_ids = torch.from_numpy(inp["top_ids"]).to(dev)
     tokens = torch.zeros((batch, n), dtype=torch.int32, device=dev)
     q, p, r = (torch.from_numpy(inp[x]).to(dev) for x in ("q", "p", "r"))
-    residual = torch.zeros((batch, vocab), dtype=torch.float64, device=dev)
     n_acc = torch.zeros((batch,), dtype=torch.int32, device=dev)
     path = torch.zeros((batch, rows), dtype=torch.int32, device=dev)
     out_tokens = torch.zeros((batch, rows + 1), dtype=torch.int32, device=dev)
     a = VF.ps_verify_args()
     a.batch, a.rows, a.vocab = batch, rows, vocab
     a.tokens, a.q, a.p, a.r = tokens.data_ptr(), q.data_ptr(), p.data_ptr(), r.data_ptr()
-    a.residual, a.n_accepted, a.path, a.out_tokens = (residual.data_ptr(), n_acc.data_ptr(), path.data_ptr(),
-                                                      out_tokens.data_ptr())
+    a.n_accepted, a.path, a.out_tokens = n_acc.data_ptr(), path.data_ptr(), out_tokens.data_ptr()
     stream = torch.cuda.current_stream().cuda_stream
 
     def build():
@@ -106,8 +105,8 @@ def verify_walk_report(torch, with_oracle, calls=200):
         c0 = time.perf_counter()
         ref = vw.acceptance_walk(parent, tok, inp["q"][0], inp["p"][0], inp["r"][0])
         cpu_s = time.perf_counter() - c0
-        nbytes = vocab * (16 * ref["rejected_from_row"] + 20 * ref["rejected_from_residual"]
-                          + (4 if ref["final_from_row"] else 8))
+        nbytes = vocab * (8 * ref["rejected_from_row"] + 4 * ref["rejected_from_residual"]
+                          + (4 if ref["final_from_row"] else 0))
         gbs = nbytes / (walk_us * 1e-6) / 1e9
         rep.update({"agrees_with_oracle": bool(out_tokens.cpu().numpy()[0, :len(ref["tokens"])].tolist() == ref["tokens"]),
                     "rejections": ref["rejected_from_row"] + ref["rejected_from_residual"],

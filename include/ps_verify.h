@@ -58,14 +58,14 @@ int ps_tree_tokens(const ps_tree_shape* tree, int32_t batch, int32_t rows, int32
  *   p           DEVICE [batch][n_nodes][vocab] float32: the target's next-token distribution
  *               after the path to each node (entry 0: after the prefix alone)
  *   r           DEVICE [batch][n_nodes] float32 uniform numbers in [0, 1)
- *   residual    DEVICE scratch, batch * vocab doubles, 8-byte aligned
  *   n_accepted  DEVICE [batch] int32, written: accepted draft tokens
  *   path        DEVICE [batch][rows] int32, written: the accepted nodes, then -1
  *   out_tokens  DEVICE [batch][rows + 1] int32, written: the accepted tokens, the last drawn
  *               token, then -1
- * Calls that share `residual` must not overlap in time.
+ * No scratch memory is needed.  vocab may be at most 262144 (1048576 when vocab % 4 == 0 and q and p are
+ * 16-byte aligned).
  * Errors: PS_ERR_NULL; PS_ERR_SHAPE (batch < 1, vocab < 1, a malformed tree, a depth beyond
- * rows); PS_ERR_DEVICE.
+ * rows); PS_ERR_UNSUPPORTED (vocab too large); PS_ERR_DEVICE.
  */
 typedef struct ps_verify_args {
     int32_t batch, rows, vocab;
@@ -73,7 +73,6 @@ typedef struct ps_verify_args {
     const float* q;
     const float* p;
     const float* r;
-    double* residual;
     int32_t* n_accepted;
     int32_t* path;
     int32_t* out_tokens;

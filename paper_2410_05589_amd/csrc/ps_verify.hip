@@ -3,12 +3,13 @@
 // The walk is sequential by nature (each test depends on the outcome of the one before), so one
 // workgroup of 1024 threads walks one sequence's tree; the sequences of a batch run side by side.
 // Only what is a vector operation over the vocabulary is spread over the threads: the residual
-// (P - q)+ with its sum, and the final draw by inversion (chunk sums, a scan over the chunks, a count).
-// The tree's shape travels in the kernel arguments, so nothing is copied or allocated per call.
-// All arithmetic is float64; P is kept as (unnormalised vector, 1 / its sum) and scaled where it is read.
-// What a test needs while P is still the target's own row (the token, r, P(x), q(x)) is fetched for all
-// nodes at once when the kernel starts, so a walk without rejections reads the vocabulary only for the
-// final draw.
+// (P - q)+ with its sum, and the final draw by inversion (totals per slab of the vocabulary, then a scan
+// inside one slab).  The tree's shape travels in the kernel arguments, so nothing is copied or allocated
+// per call, and no scratch memory is used.  All arithmetic is float64; P is kept unscaled with 1 / its sum
+// beside it.  What a test needs while P is still the target's own row (the token, r, P(x), q(x)) is fetched
+// for all nodes at once when the kernel starts, so a walk without rejections reads the vocabulary only for
+// the final draw.  Two kernels: P in registers for vocabularies up to 32768 entries, P recomputed from the
+// target's and the drafter's rows for larger ones.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -29,7 +30,6 @@ struct WalkParams {
     int rows, vocab;
     const int32_t* tokens;
     const float *q, *p, *r;
-    double* residual;
     int32_t *n_accepted, *path, *out_tokens;
 };
 struct TokensParams {
@@ -125,128 +125,80 @@ __device__ __forceinline__ void load_nodes(const WalkParams& Wp, int b, const fl
 
 // W consecutive vocabulary entries as one load (W = 4 needs vocab % 4 == 0 and 16-byte aligned rows)
 template <int W> struct Vec;
-template <> struct Vec<1> { typedef float f; typedef double d; };
-template <> struct Vec<4> { typedef float4 f; typedef double4 d; };
+template <> struct Vec<1> { typedef float f; };
+template <> struct Vec<4> { typedef float4 f; };
 template <int W> __device__ __forceinline__ void widen(const typename Vec<W>::f& v, double (&o)[W]);
 template <> __device__ __forceinline__ void widen<1>(const float& v, double (&o)[1]) { o[0] = (double)v; }
 template <> __device__ __forceinline__ void widen<4>(const float4& v, double (&o)[4]) {
     o[0] = (double)v.x; o[1] = (double)v.y; o[2] = (double)v.z; o[3] = (double)v.w;
 }
-template <int W> __device__ __forceinline__ void unpack(const typename Vec<W>::d& v, double (&o)[W]);
-template <> __device__ __forceinline__ void unpack<1>(const double& v, double (&o)[1]) { o[0] = v; }
-template <> __device__ __forceinline__ void unpack<4>(const double4& v, double (&o)[4]) { o[0] = v.x; o[1] = v.y; o[2] = v.z; o[3] = v.w; }
-template <int W> __device__ __forceinline__ typename Vec<W>::d pack(const double (&o)[W]);
-template <> __device__ __forceinline__ double pack<1>(const double (&o)[1]) { return o[0]; }
-template <> __device__ __forceinline__ double4 pack<4>(const double (&o)[4]) { return make_double4(o[0], o[1], o[2], o[3]); }
 
-// The distribution P the walk holds: the target's row pu as it is (fresh), or res * inv_tot
-struct PState {
-    const float* pu;
-    bool fresh;
-    double inv_tot;
-};
-
-// P <- (P - qt)+ (not yet divided by its sum) into res; returns this thread's part of the sum.  Entries are
-// dealt to the threads W at a time, interleaved; UN loads per array are in flight before the first is used.
-template <int W>
-__device__ __forceinline__ double residual_pass(const PState P, double* __restrict__ res, const float* __restrict__ qt, int V) {
-    typedef typename Vec<W>::f VF;
-    typedef typename Vec<W>::d VD;
-    constexpr int UN = W == 4 ? 4 : 8;   // (registers: 1024 threads leave 128 per thread)
-    const int nvec = V / W;   // (W = 4: V % 4 == 0)
-    double local = 0.0;
-    for (int j0 = threadIdx.x; j0 < nvec; j0 += WALK_THREADS * UN) {
-        VF pv[UN], qv[UN];
-        VD rv[UN];
-#pragma unroll
-        for (int k = 0; k < UN; ++k) {
-            const int j = j0 + k * WALK_THREADS;
-            if (j < nvec) {
-                qv[k] = reinterpret_cast<const VF*>(qt)[j];
-                if (P.fresh) pv[k] = reinterpret_cast<const VF*>(P.pu)[j];
-                else rv[k] = reinterpret_cast<const VD*>(res)[j];
-            }
-        }
-#pragma unroll
-        for (int k = 0; k < UN; ++k) {
-            const int j = j0 + k * WALK_THREADS;
-            if (j < nvec) {
-                double a[W], b[W];
-                if (P.fresh) widen<W>(pv[k], a);
-                else {
-                    unpack<W>(rv[k], a);
-#pragma unroll
-                    for (int e = 0; e < W; ++e) a[e] *= P.inv_tot;
-                }
-                widen<W>(qv[k], b);
-#pragma unroll
-                for (int e = 0; e < W; ++e) {
-                    a[e] = fmax(a[e] - b[e], 0.0);
-                    local += a[e];
-                }
-                reinterpret_cast<VD*>(res)[j] = pack<W>(a);
-            }
-        }
-    }
-    return local;
-}
-
-// The entries [c0, c1) of P (c0, c1 multiples of W) one after the other: f(value) in id order
-template <int W, typename F>
-__device__ __forceinline__ void for_chunk(const PState P, const double* __restrict__ res, int c0, int c1, F f) {
-    typedef typename Vec<W>::f VF;
-    typedef typename Vec<W>::d VD;
-    constexpr int UN = W == 4 ? 4 : 8;   // (registers: 1024 threads leave 128 per thread)
-    for (int j0 = c0 / W; j0 < c1 / W; j0 += UN) {
-        VF pv[UN];
-        VD rv[UN];
-#pragma unroll
-        for (int k = 0; k < UN; ++k) {
-            if (j0 + k < c1 / W) {
-                if (P.fresh) pv[k] = reinterpret_cast<const VF*>(P.pu)[j0 + k];
-                else rv[k] = reinterpret_cast<const VD*>(res)[j0 + k];
-            }
-        }
-#pragma unroll
-        for (int k = 0; k < UN; ++k) {
-            if (j0 + k < c1 / W) {
-                double a[W];
-                if (P.fresh) widen<W>(pv[k], a);
-                else unpack<W>(rv[k], a);
-#pragma unroll
-                for (int e = 0; e < W; ++e) f(P.fresh ? a[e] : a[e] * P.inv_tot);
-            }
-        }
-    }
-}
-
+// The walk for any vocabulary: nothing of P is stored.  All children of a node are proposals of the same
+// draft row q_t, so after J rejections at a node the residual is an elementwise function of the target's row
+// p and q_t alone: R_0 = p, R_j = (R_{j-1} c_{j-1} - q_t)+ with c_0 = 1 and c_j = 1 / sum(R_j), and P = R_J c_J.
+// A rejection therefore reads the two rows (8 bytes per entry), re-applies the J steps in registers and adds
+// up (J steps per entry for the J-th rejection at a node: fine for the few children a draft tree's node has);
+// P(x) for a test is the same recurrence on the two numbers fetched when the kernel started.  The final
+// draw cuts the vocabulary into slabs of W * WALK_THREADS entries: totals per slab first, then the cumulative
+// sum inside the slab in which it passes the target.
+constexpr int WALK_MAX_SLABS = 256;
 template <int W>
 __global__ void __launch_bounds__(WALK_THREADS) verify_walk_kernel(const WalkParams Wp) {
+    typedef typename Vec<W>::f VF;
     __shared__ double s_red[WALK_WAVES];
+    __shared__ double s_c[PS_TREE_MAX_NODES + 1];
+    __shared__ double s_part[WALK_MAX_SLABS][WALK_WAVES];
     __shared__ NodeLds L;
     const int b = blockIdx.x, tid = threadIdx.x, V = Wp.vocab, N = Wp.t.n_nodes;
+    const int lane = tid & 63, wave = tid >> 6;
     const float* q = Wp.q + (size_t)b * Wp.rows * V;
     const float* p = Wp.p + (size_t)b * N * V;
-    double* res = Wp.residual + (size_t)b * V;
     load_nodes(Wp, b, q, p, L);
+    s_c[0] = 1.0;   // (every thread writes the same value and reads it back itself: no barrier needed)
 
-    // Every thread takes every decision itself, from the same values.
+    // R_J of one entry; every thread takes every decision itself, from the same values
+    int J = 0;
+    auto residual = [&](double v, double qe) -> double {
+        for (int t = 0; t < J; ++t) v = fmax(v * s_c[t] - qe, 0.0);
+        return v;
+    };
+    const int nvec = V / W;               // (W = 4: V % 4 == 0); this thread's: tid + WALK_THREADS * k
+    constexpr int UN = 4;                 // vectors of each row on their way at once (8: measured slower)
     int u = 0, n_acc = 0;
-    PState P{p, true, 1.0};
     int s = L.first[0];
     while (s >= 0) {   // the children of u in ascending index
         const int x = L.tok[s];
         bool accept = false;
         if (x >= 0) {
-            const float* qt = q + (size_t)(L.depth[s] - 1) * V;
-            const double Px = P.fresh ? (double)L.px[s] : res[x] * P.inv_tot, qx = (double)L.qx[s];
+            const double qx = (double)L.qx[s];
+            const double Px = residual((double)L.px[s], qx) * s_c[J];
             const double ratio = qx > 0.0 ? fmin(1.0, Px / qx) : 1.0;
             accept = (double)L.r[s] < ratio;
             if (!accept) {
-                __syncthreads();   // everyone has read P(x) before P changes
-                const double t = block_sum(residual_pass<W>(P, res, qt, V), s_red);   // (its barriers also publish res)
-                P.fresh = false;
-                P.inv_tot = t > 0.0 ? 1.0 / t : 1.0;
+                ++J;
+                const VF* pu = reinterpret_cast<const VF*>(p + (size_t)u * V);
+                const VF* qt = reinterpret_cast<const VF*>(q + (size_t)(L.depth[s] - 1) * V);
+                double local = 0.0;
+                for (int j0 = tid; j0 < nvec; j0 += WALK_THREADS * UN) {
+                    VF pv[UN], qv[UN];
+#pragma unroll
+                    for (int k = 0; k < UN; ++k) {
+                        const int j = j0 + k * WALK_THREADS;
+                        if (j < nvec) { pv[k] = pu[j]; qv[k] = qt[j]; }
+                    }
+#pragma unroll
+                    for (int k = 0; k < UN; ++k) {
+                        if (j0 + k * WALK_THREADS < nvec) {
+                            double a[W], c[W];
+                            widen<W>(pv[k], a);
+                            widen<W>(qv[k], c);
+#pragma unroll
+                            for (int e = 0; e < W; ++e) local += residual(a[e], c[e]);
+                        }
+                    }
+                }
+                const double t = block_sum(local, s_red);
+                s_c[J] = t > 0.0 ? 1.0 / t : 1.0;
             }
         }
         if (accept) {
@@ -256,28 +208,81 @@ __global__ void __launch_bounds__(WALK_THREADS) verify_walk_kernel(const WalkPar
             }
             ++n_acc;
             u = s;
-            P = PState{p + (size_t)u * V, true, 1.0};
+            J = 0;
             s = L.first[u];
         } else {
             s = L.next[s];
         }
     }
 
-    // the last token: inversion of the cumulative sum in token-id order; thread t holds a run of ids
-    int chunk = (V + WALK_THREADS - 1) / WALK_THREADS;
-    chunk = (chunk + W - 1) / W * W;
-    const int c0 = min(V, tid * chunk), c1 = min(V, c0 + chunk);
-    double local = 0.0;
-    for_chunk<W>(P, res, c0, c1, [&](double v) { local += v; });
-    double total;
-    double run = block_exclusive_scan(local, s_red, total);
+    // The last token.  P = R_J c_J at node u; its children's draft row is row depth(u) of q (unused if J = 0).
+    const VF* pu = reinterpret_cast<const VF*>(p + (size_t)u * V);
+    const VF* qt = reinterpret_cast<const VF*>(q + (size_t)(J > 0 ? L.depth[u] : 0) * V);
+    const double cJ = s_c[J];
+    auto P_of = [&](int j, double (&o)[W]) {   // entries of vector j (j < nvec)
+        double a[W], c[W];
+        widen<W>(pu[j], a);
+        if (J > 0) widen<W>(qt[j], c);
+#pragma unroll
+        for (int e = 0; e < W; ++e) o[e] = (J > 0 ? residual(a[e], c[e]) : a[e]) * cJ;
+    };
+    const int n_slabs = (nvec + WALK_THREADS - 1) / WALK_THREADS;   // <= WALK_MAX_SLABS (host)
+    constexpr int UF = 8;                 // slabs whose rows are on their way at once
+    for (int k0 = 0; k0 < n_slabs; k0 += UF) {
+        VF pv[UF], qv[UF];
+#pragma unroll
+        for (int i = 0; i < UF; ++i) {
+            const int j = tid + WALK_THREADS * (k0 + i);
+            if (j < nvec) {
+                pv[i] = pu[j];
+                if (J > 0) qv[i] = qt[j];
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < UF; ++i) {
+            const int j = tid + WALK_THREADS * (k0 + i);
+            double v = 0.0;
+            if (j < nvec) {
+                double a[W], c[W];
+                widen<W>(pv[i], a);
+                if (J > 0) widen<W>(qv[i], c);
+#pragma unroll
+                for (int e = 0; e < W; ++e) v += (J > 0 ? residual(a[e], c[e]) : a[e]) * cJ;
+            }
+            v = wave_sum_f64(v);
+            if (lane == 0 && k0 + i < n_slabs) s_part[k0 + i][wave] = v;
+        }
+    }
+    __syncthreads();
+    double total = 0.0;
+    for (int k = 0; k < n_slabs; ++k)
+        for (int w = 0; w < WALK_WAVES; ++w) total += s_part[k][w];
     const double target = (double)L.r[0] * total;
+    int ks = n_slabs - 1;
+    double base = 0.0, cum = 0.0;
+    for (int k = 0; k < n_slabs; ++k) {
+        double t = 0.0;
+        for (int w = 0; w < WALK_WAVES; ++w) t += s_part[k][w];
+        if (cum + t > target || k == n_slabs - 1) { ks = k; base = cum; break; }
+        cum += t;
+    }
+    double mine[W];
+#pragma unroll
+    for (int e = 0; e < W; ++e) mine[e] = 0.0;
+    const int jm = tid + WALK_THREADS * ks;
+    if (jm < nvec) P_of(jm, mine);
+    double mysum = 0.0;
+#pragma unroll
+    for (int e = 0; e < W; ++e) mysum += mine[e];
+    double dummy;
+    double run = base + block_exclusive_scan(mysum, s_red, dummy);
     double cnt = 0.0;
-    for_chunk<W>(P, res, c0, c1, [&](double v) {
-        run += v;
-        if (run <= target) cnt += 1.0;
-    });
-    const int n = (int)block_sum(cnt, s_red);   // (a count below 2^53: exact)
+#pragma unroll
+    for (int e = 0; e < W; ++e) {
+        run += mine[e];
+        if (jm < nvec && run <= target) cnt += 1.0;
+    }
+    const int n = W * WALK_THREADS * ks + (int)block_sum(cnt, s_red);   // every id of the slabs before ks counts
     if (tid == 0) {
         Wp.out_tokens[(size_t)b * (Wp.rows + 1) + n_acc] = n < V - 1 ? n : V - 1;
         for (int i = n_acc + 1; i <= Wp.rows; ++i) Wp.out_tokens[(size_t)b * (Wp.rows + 1) + i] = -1;
@@ -506,17 +511,19 @@ extern "C" int ps_tree_tokens(const ps_tree_shape* tree, int32_t batch, int32_t 
 
 extern "C" int ps_verify_walk(const ps_tree_shape* tree, const ps_verify_args* a, void* stream) {
     if (!a) return PS_ERR_NULL;
-    if (!a->tokens || !a->q || !a->p || !a->r || !a->residual || !a->n_accepted || !a->path || !a->out_tokens)
+    if (!a->tokens || !a->q || !a->p || !a->r || !a->n_accepted || !a->path || !a->out_tokens)
         return PS_ERR_NULL;
-    if (a->batch < 1 || a->rows < 1 || a->vocab < 1 || ((uintptr_t)a->residual & 7)) return PS_ERR_SHAPE;
+    if (a->batch < 1 || a->rows < 1 || a->vocab < 1) return PS_ERR_SHAPE;
     WalkParams W;
     const int st = load_tree(tree, a->rows, 0, &W.t);
     if (st != PS_OK) return st;
     W.rows = a->rows; W.vocab = a->vocab;
-    W.tokens = a->tokens; W.q = a->q; W.p = a->p; W.r = a->r; W.residual = a->residual;
+    W.tokens = a->tokens; W.q = a->q; W.p = a->p; W.r = a->r;
     W.n_accepted = a->n_accepted; W.path = a->path; W.out_tokens = a->out_tokens;
-    // whole vectors of four entries when every row of q, p and the scratch starts on a 16-byte boundary
-    const bool vec = a->vocab % 4 == 0 && (((uintptr_t)a->q | (uintptr_t)a->p) & 15) == 0 && ((uintptr_t)a->residual & 31) == 0;
+    // whole vectors of four entries when every row of q and p starts on a 16-byte boundary
+    const bool vec = a->vocab % 4 == 0 && (((uintptr_t)a->q | (uintptr_t)a->p) & 15) == 0;
+    const long long slabs = ((long long)a->vocab / (vec ? 4 : 1) + WALK_THREADS - 1) / WALK_THREADS;
+    if (slabs > WALK_MAX_SLABS) return PS_ERR_UNSUPPORTED;
     if (vec && a->vocab <= REG_EPT * REG_THREADS)
         hipLaunchKernelGGL(verify_walk_reg_kernel, dim3(a->batch), dim3(REG_THREADS), 0, (hipStream_t)stream, W);
     else if (vec) hipLaunchKernelGGL(verify_walk_kernel<4>, dim3(a->batch), dim3(WALK_THREADS), 0, (hipStream_t)stream, W);

@@ -34,14 +34,13 @@ def _run_gpu(parent, rank, inp, rows, topk, tokens_override=None):
     q = torch.from_numpy(inp["q"]).to(dev)
     p = torch.from_numpy(inp["p"]).to(dev)
     r = torch.from_numpy(inp["r"]).to(dev)
-    residual = torch.full((batch, vocab), float("nan"), dtype=torch.float64, device=dev)
     n_acc = torch.full((batch,), -7, dtype=torch.int32, device=dev)
     path = torch.full((batch, rows), -7, dtype=torch.int32, device=dev)
     out_tokens = torch.full((batch, rows + 1), -7, dtype=torch.int32, device=dev)
     a = VF.ps_verify_args()
     a.batch, a.rows, a.vocab = batch, rows, vocab
     a.tokens, a.q, a.p, a.r = tokens.data_ptr(), q.data_ptr(), p.data_ptr(), r.data_ptr()
-    a.residual, a.n_accepted, a.path, a.out_tokens = residual.data_ptr(), n_acc.data_ptr(), path.data_ptr(), out_tokens.data_ptr()
+    a.n_accepted, a.path, a.out_tokens = n_acc.data_ptr(), path.data_ptr(), out_tokens.data_ptr()
     st = VF.ps_verify_walk(tree, a, stream)
     assert st == B.PS_OK, B.ps_draft_strerror(st)
     torch.cuda.synchronize()
@@ -154,7 +153,7 @@ def test_tree_and_walk_replayed_from_a_graph():
     the captured buffers are each compared with the oracle, with eager calls in between."""
     import torch
     dev = torch.device("cuda:0")
-    for vocab in (32000, 40004):          # P in registers / P in the scratch buffer
+    for vocab in (32000, 40004):          # P in registers / P recomputed from the two rows
         parent, rank = inputs.draft_tree([3, 2, 2, 1])
         rows, topk, batch, n = 5, 8, 3, len(parent)
         tree = VF.make_tree(parent, rank)
@@ -162,15 +161,13 @@ def test_tree_and_walk_replayed_from_a_graph():
         top_ids = torch.from_numpy(inp["top_ids"]).to(dev)
         tokens = torch.zeros((batch, n), dtype=torch.int32, device=dev)
         q, p, r = (torch.from_numpy(inp[x]).to(dev) for x in ("q", "p", "r"))
-        residual = torch.zeros((batch, vocab), dtype=torch.float64, device=dev)
         n_acc = torch.zeros((batch,), dtype=torch.int32, device=dev)
         path = torch.zeros((batch, rows), dtype=torch.int32, device=dev)
         out_tokens = torch.zeros((batch, rows + 1), dtype=torch.int32, device=dev)
         a = VF.ps_verify_args()
         a.batch, a.rows, a.vocab = batch, rows, vocab
         a.tokens, a.q, a.p, a.r = tokens.data_ptr(), q.data_ptr(), p.data_ptr(), r.data_ptr()
-        a.residual, a.n_accepted, a.path, a.out_tokens = (residual.data_ptr(), n_acc.data_ptr(), path.data_ptr(),
-                                                          out_tokens.data_ptr())
+        a.n_accepted, a.path, a.out_tokens = n_acc.data_ptr(), path.data_ptr(), out_tokens.data_ptr()
 
         def both(stream):
             assert VF.ps_tree_tokens(tree, batch, rows, topk, top_ids.data_ptr(), tokens.data_ptr(), stream) == B.PS_OK

@@ -46,7 +46,7 @@ def test_struct_layouts_match_header():
 def _args(**kw):
     a = VF.ps_verify_args()
     a.batch, a.rows, a.vocab = 1, 3, 100
-    for n in ("tokens", "q", "p", "r", "residual", "n_accepted", "path", "out_tokens"):
+    for n in ("tokens", "q", "p", "r", "n_accepted", "path", "out_tokens"):
         setattr(a, n, 0x100000)
     for k, v in kw.items():
         setattr(a, k, v)
@@ -57,10 +57,12 @@ def test_walk_rejects_bad_arguments_on_the_host(lib):
     good = VF.make_tree([-1, 0, 0, 1], [0, 0, 1, 0])
     assert VF.ps_verify_walk(None, _args(), None) == B.PS_ERR_NULL
     assert VF.ps_verify_walk(good, None, None) == B.PS_ERR_NULL
-    for n in ("tokens", "q", "p", "r", "residual", "n_accepted", "path", "out_tokens"):
+    for n in ("tokens", "q", "p", "r", "n_accepted", "path", "out_tokens"):
         assert VF.ps_verify_walk(good, _args(**{n: None}), None) == B.PS_ERR_NULL, n
-    for kw in (dict(batch=0), dict(rows=0), dict(vocab=0), dict(residual=0x100004), dict(rows=1)):   # rows=1: depth 2 > rows
+    for kw in (dict(batch=0), dict(rows=0), dict(vocab=0), dict(rows=1)):   # rows=1: depth 2 > rows
         assert VF.ps_verify_walk(good, _args(**kw), None) == B.PS_ERR_SHAPE, kw
+    assert VF.ps_verify_walk(good, _args(vocab=1048580), None) == B.PS_ERR_UNSUPPORTED
+    assert VF.ps_verify_walk(good, _args(vocab=262145), None) == B.PS_ERR_UNSUPPORTED      # odd: one entry per load
     for parent in ([0, 0], [-1, 1], [-1, -1], [-1, 0, 3], [-1] + [0] * 64, []):
         t = VF.make_tree(np.array(parent, dtype=np.int32), np.zeros(len(parent), dtype=np.int32))
         assert VF.ps_verify_walk(t, _args(rows=64), None) == B.PS_ERR_SHAPE, parent
