@@ -62,8 +62,12 @@ int ps_tree_tokens(const ps_tree_shape* tree, int32_t batch, int32_t rows, int32
  *   path        DEVICE [batch][rows] int32, written: the accepted nodes, then -1
  *   out_tokens  DEVICE [batch][rows + 1] int32, written: the accepted tokens, the last drawn
  *               token, then -1
- * No scratch memory is needed.  vocab may be at most 262144 (1048576 when vocab % 4 == 0 and q and p are
- * 16-byte aligned).
+ * No scratch memory is passed in.  vocab may be at most 262144 (1048576 when vocab % 4 == 0 and q and p
+ * are 16-byte aligned).  For vocab > 32768 (vocab % 4 == 0, aligned rows, batch <= 64, enough compute units)
+ * several workgroups share a sequence and exchange their partial sums through about 1 MB of device memory
+ * that belongs to the library: such calls on one device must not overlap in time (calls on one stream never
+ * do).  Should that exchange ever time out (it cannot while every workgroup of the launch gets a compute
+ * unit), n_accepted[b] = -2 marks the sequence and its other outputs are undefined.
  * Errors: PS_ERR_NULL; PS_ERR_SHAPE (batch < 1, vocab < 1, a malformed tree, a depth beyond
  * rows); PS_ERR_UNSUPPORTED (vocab too large); PS_ERR_DEVICE.
  */

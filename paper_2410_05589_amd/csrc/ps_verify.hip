@@ -13,6 +13,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "ps_draft.h"
 #include "ps_verify.h"
 
@@ -31,6 +33,7 @@ struct WalkParams {
     const int32_t* tokens;
     const float *q, *p, *r;
     int32_t *n_accepted, *path, *out_tokens;
+    int slabs_per_wg;     // several workgroups per sequence: slabs of the vocabulary each of them takes
 };
 struct TokensParams {
     TreeDev t;
@@ -141,20 +144,80 @@ template <> __device__ __forceinline__ void widen<4>(const float4& v, double (&o
 // P(x) for a test is the same recurrence on the two numbers fetched when the kernel started.  The final
 // draw cuts the vocabulary into slabs of W * WALK_THREADS entries: totals per slab first, then the cumulative
 // sum inside the slab in which it passes the target.
+//
+// MULTI: gridDim.x workgroups share a sequence (blockIdx.y); workgroup g takes slabs [g S, (g + 1) S) of the
+// vocabulary for every sum and all of them take every decision.  A sum over the vocabulary is then the sum, in
+// workgroup order, of the workgroups' parts, which they leave for each other in g_xch (device memory of the
+// library, one slot per sequence, round and workgroup; a slot is two 8-byte units {half of the double, tag},
+// written and read with agent-scope atomics).  The tag is the sequence slot's launch count + 1: it is kept in
+// device memory (g_epoch), read by every workgroup when it starts and advanced by the workgroup that finishes
+// the sequence - by then all of them have read it - so a launch replayed from a graph gets new tags too.
+// Every wait is bounded; a workgroup whose wait runs out marks the sequence as failed (n_accepted = -2) and
+// leaves.  All workgroups of a launch must be resident at once (the host launches at most one per compute
+// unit), and launches that use g_xch must not overlap in time.
 constexpr int WALK_MAX_SLABS = 256;
-template <int W>
+constexpr int XCH_SEQS = 64, XCH_ROUNDS = PS_TREE_MAX_NODES + 1, XCH_WGS = 16, XCH_SPINS = 1 << 20;
+static __device__ unsigned long long g_xch[XCH_SEQS][XCH_ROUNDS][XCH_WGS][2];
+static __device__ unsigned g_epoch[XCH_SEQS];
+
+// all workgroups of sequence b: the sum over g of their `mine`, the same in every thread; false if a wait ran out
+__device__ __forceinline__ bool xch_sum(double mine, int b, int rnd, unsigned tag, double* s_x, double& sum) {
+    const int g = blockIdx.x, G = gridDim.x, tid = threadIdx.x;
+    if (tid == 0) {
+        const unsigned long long bits = (unsigned long long)__double_as_longlong(mine);
+        __hip_atomic_store(&g_xch[b][rnd][g][0], ((bits & 0xFFFFFFFFull) << 32) | tag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(&g_xch[b][rnd][g][1], ((bits >> 32) << 32) | tag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    if (tid < G) {
+        unsigned long long lo = 0, hi = 0;
+        int spins = 0;
+        for (;;) {
+            lo = __hip_atomic_load(&g_xch[b][rnd][tid][0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            hi = __hip_atomic_load(&g_xch[b][rnd][tid][1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (((unsigned)lo == tag && (unsigned)hi == tag) || ++spins > XCH_SPINS) break;
+            __builtin_amdgcn_s_sleep(2);
+        }
+        const bool ok = (unsigned)lo == tag && (unsigned)hi == tag;
+        s_x[tid] = ok ? __longlong_as_double((long long)((lo >> 32) | ((hi >> 32) << 32))) : 0.0;
+        if (!ok) s_x[XCH_WGS] = 1.0;
+    }
+    __syncthreads();
+    sum = 0.0;
+    for (int i = 0; i < G; ++i) sum += s_x[i];
+    const bool good = s_x[XCH_WGS] == 0.0;
+    __syncthreads();   // s_x is written again in the next round
+    return good;
+}
+
+template <int W, bool MULTI>
 __global__ void __launch_bounds__(WALK_THREADS) verify_walk_kernel(const WalkParams Wp) {
     typedef typename Vec<W>::f VF;
     __shared__ double s_red[WALK_WAVES];
     __shared__ double s_c[PS_TREE_MAX_NODES + 1];
     __shared__ double s_part[WALK_MAX_SLABS][WALK_WAVES];
+    __shared__ double s_x[XCH_WGS + 1];
     __shared__ NodeLds L;
-    const int b = blockIdx.x, tid = threadIdx.x, V = Wp.vocab, N = Wp.t.n_nodes;
+    const int b = MULTI ? blockIdx.y : blockIdx.x, g = MULTI ? blockIdx.x : 0;
+    const int tid = threadIdx.x, V = Wp.vocab, N = Wp.t.n_nodes;
     const int lane = tid & 63, wave = tid >> 6;
+    __shared__ unsigned s_tag;
+    if (tid == 0) {                     // (both read after the barrier in load_nodes at the earliest)
+        s_x[XCH_WGS] = 0.0;
+        unsigned t = MULTI ? __hip_atomic_load(&g_epoch[b], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1u : 1u;
+        s_tag = t ? t : 1u;             // 0 is what slots never written hold
+    }
+    int rnd = 0;
     const float* q = Wp.q + (size_t)b * Wp.rows * V;
     const float* p = Wp.p + (size_t)b * N * V;
     load_nodes(Wp, b, q, p, L);
     s_c[0] = 1.0;   // (every thread writes the same value and reads it back itself: no barrier needed)
+    const unsigned tag = s_tag;
+    auto fail = [&]() {   // a wait ran out: the sequence is marked, its tag is used up
+        if (tid == 0) {
+            Wp.n_accepted[b] = -2;
+            __hip_atomic_store(&g_epoch[b], tag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    };
 
     // R_J of one entry; every thread takes every decision itself, from the same values
     int J = 0;
@@ -162,7 +225,12 @@ __global__ void __launch_bounds__(WALK_THREADS) verify_walk_kernel(const WalkPar
         for (int t = 0; t < J; ++t) v = fmax(v * s_c[t] - qe, 0.0);
         return v;
     };
-    const int nvec = V / W;               // (W = 4: V % 4 == 0); this thread's: tid + WALK_THREADS * k
+    const int nvec_all = V / W;           // (W = 4: V % 4 == 0)
+    const int n_slabs_all = (nvec_all + WALK_THREADS - 1) / WALK_THREADS;   // <= WALK_MAX_SLABS (host)
+    // this workgroup's slabs [slab0, slab0 + n_slabs) and vectors [jlo, nvec); this thread's: jlo + tid + WALK_THREADS * k
+    const int slab0 = MULTI ? g * Wp.slabs_per_wg : 0;
+    const int n_slabs = MULTI ? min(Wp.slabs_per_wg, n_slabs_all - slab0) : n_slabs_all;
+    const int jlo = slab0 * WALK_THREADS, nvec = min(nvec_all, jlo + n_slabs * WALK_THREADS);
     constexpr int UN = 4;                 // vectors of each row on their way at once (8: measured slower)
     int u = 0, n_acc = 0;
     int s = L.first[0];
@@ -179,7 +247,7 @@ __global__ void __launch_bounds__(WALK_THREADS) verify_walk_kernel(const WalkPar
                 const VF* pu = reinterpret_cast<const VF*>(p + (size_t)u * V);
                 const VF* qt = reinterpret_cast<const VF*>(q + (size_t)(L.depth[s] - 1) * V);
                 double local = 0.0;
-                for (int j0 = tid; j0 < nvec; j0 += WALK_THREADS * UN) {
+                for (int j0 = jlo + tid; j0 < nvec; j0 += WALK_THREADS * UN) {
                     VF pv[UN], qv[UN];
 #pragma unroll
                     for (int k = 0; k < UN; ++k) {
@@ -197,12 +265,16 @@ __global__ void __launch_bounds__(WALK_THREADS) verify_walk_kernel(const WalkPar
                         }
                     }
                 }
-                const double t = block_sum(local, s_red);
+                double t = block_sum(local, s_red);
+                if (MULTI && !xch_sum(t, b, rnd++, tag, s_x, t)) {
+                    fail();
+                    return;
+                }
                 s_c[J] = t > 0.0 ? 1.0 / t : 1.0;
             }
         }
         if (accept) {
-            if (tid == 0) {
+            if (tid == 0 && g == 0) {
                 Wp.path[(size_t)b * Wp.rows + n_acc] = s;
                 Wp.out_tokens[(size_t)b * (Wp.rows + 1) + n_acc] = x;
             }
@@ -226,13 +298,12 @@ __global__ void __launch_bounds__(WALK_THREADS) verify_walk_kernel(const WalkPar
 #pragma unroll
         for (int e = 0; e < W; ++e) o[e] = (J > 0 ? residual(a[e], c[e]) : a[e]) * cJ;
     };
-    const int n_slabs = (nvec + WALK_THREADS - 1) / WALK_THREADS;   // <= WALK_MAX_SLABS (host)
     constexpr int UF = 8;                 // slabs whose rows are on their way at once
     for (int k0 = 0; k0 < n_slabs; k0 += UF) {
         VF pv[UF], qv[UF];
 #pragma unroll
         for (int i = 0; i < UF; ++i) {
-            const int j = tid + WALK_THREADS * (k0 + i);
+            const int j = jlo + tid + WALK_THREADS * (k0 + i);
             if (j < nvec) {
                 pv[i] = pu[j];
                 if (J > 0) qv[i] = qt[j];
@@ -240,7 +311,7 @@ __global__ void __launch_bounds__(WALK_THREADS) verify_walk_kernel(const WalkPar
         }
 #pragma unroll
         for (int i = 0; i < UF; ++i) {
-            const int j = tid + WALK_THREADS * (k0 + i);
+            const int j = jlo + tid + WALK_THREADS * (k0 + i);
             double v = 0.0;
             if (j < nvec) {
                 double a[W], c[W];
@@ -257,9 +328,29 @@ __global__ void __launch_bounds__(WALK_THREADS) verify_walk_kernel(const WalkPar
     double total = 0.0;
     for (int k = 0; k < n_slabs; ++k)
         for (int w = 0; w < WALK_WAVES; ++w) total += s_part[k][w];
+    double before = 0.0;                  // the cumulative sum in front of this workgroup's slabs
+    if (MULTI) {
+        // the workgroups' totals: the draw falls to the first workgroup whose cumulative sum exceeds the
+        // target (the last one if none does); the others are done
+        const double mine_total = total;
+        if (!xch_sum(mine_total, b, rnd++, tag, s_x, total)) {
+            fail();
+            return;
+        }
+        // (s_x was overwritten by nobody since: xch_sum ends with a barrier and this is the last round)
+        const double tgt = (double)L.r[0] * total;
+        int owner = (int)gridDim.x - 1;
+        double cumg = 0.0;
+        for (int i = 0; i < (int)gridDim.x; ++i) {
+            if (cumg + s_x[i] > tgt || i == (int)gridDim.x - 1) { owner = i; break; }
+            cumg += s_x[i];
+        }
+        if (g != owner) return;
+        before = cumg;
+    }
     const double target = (double)L.r[0] * total;
     int ks = n_slabs - 1;
-    double base = 0.0, cum = 0.0;
+    double base = before, cum = before;
     for (int k = 0; k < n_slabs; ++k) {
         double t = 0.0;
         for (int w = 0; w < WALK_WAVES; ++w) t += s_part[k][w];
@@ -269,7 +360,7 @@ __global__ void __launch_bounds__(WALK_THREADS) verify_walk_kernel(const WalkPar
     double mine[W];
 #pragma unroll
     for (int e = 0; e < W; ++e) mine[e] = 0.0;
-    const int jm = tid + WALK_THREADS * ks;
+    const int jm = jlo + tid + WALK_THREADS * ks;
     if (jm < nvec) P_of(jm, mine);
     double mysum = 0.0;
 #pragma unroll
@@ -282,12 +373,13 @@ __global__ void __launch_bounds__(WALK_THREADS) verify_walk_kernel(const WalkPar
         run += mine[e];
         if (jm < nvec && run <= target) cnt += 1.0;
     }
-    const int n = W * WALK_THREADS * ks + (int)block_sum(cnt, s_red);   // every id of the slabs before ks counts
+    const int n = W * WALK_THREADS * (slab0 + ks) + (int)block_sum(cnt, s_red);   // every id of the slabs before counts
     if (tid == 0) {
         Wp.out_tokens[(size_t)b * (Wp.rows + 1) + n_acc] = n < V - 1 ? n : V - 1;
         for (int i = n_acc + 1; i <= Wp.rows; ++i) Wp.out_tokens[(size_t)b * (Wp.rows + 1) + i] = -1;
         for (int i = n_acc; i < Wp.rows; ++i) Wp.path[(size_t)b * Wp.rows + i] = -1;
         Wp.n_accepted[b] = n_acc;
+        if (MULTI) __hip_atomic_store(&g_epoch[b], tag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
 }
 
@@ -465,6 +557,19 @@ __global__ void __launch_bounds__(PS_TREE_MAX_NODES) tree_tokens_kernel(const To
     T.tokens[(size_t)b * T.t.n_nodes + s] = tok;
 }
 
+// compute units of the current device (0 if it cannot be asked): asked once per process and device
+int compute_units() {
+    static std::atomic<int> cached[64];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 0;
+    int n = cached[dev].load();
+    if (n == 0) {
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) n = -1;
+        cached[dev].store(n);
+    }
+    return n > 0 ? n : 0;
+}
+
 // copies and checks a tree; rank is checked against topk when topk > 0
 int load_tree(const ps_tree_shape* tree, int rows, int topk, TreeDev* out) {
     if (!tree || !tree->parent) return PS_ERR_NULL;
@@ -524,9 +629,22 @@ extern "C" int ps_verify_walk(const ps_tree_shape* tree, const ps_verify_args* a
     const bool vec = a->vocab % 4 == 0 && (((uintptr_t)a->q | (uintptr_t)a->p) & 15) == 0;
     const long long slabs = ((long long)a->vocab / (vec ? 4 : 1) + WALK_THREADS - 1) / WALK_THREADS;
     if (slabs > WALK_MAX_SLABS) return PS_ERR_UNSUPPORTED;
-    if (vec && a->vocab <= REG_EPT * REG_THREADS)
+    W.slabs_per_wg = (int)slabs;
+    if (vec && a->vocab <= REG_EPT * REG_THREADS) {
         hipLaunchKernelGGL(verify_walk_reg_kernel, dim3(a->batch), dim3(REG_THREADS), 0, (hipStream_t)stream, W);
-    else if (vec) hipLaunchKernelGGL(verify_walk_kernel<4>, dim3(a->batch), dim3(WALK_THREADS), 0, (hipStream_t)stream, W);
-    else hipLaunchKernelGGL(verify_walk_kernel<1>, dim3(a->batch), dim3(WALK_THREADS), 0, (hipStream_t)stream, W);
+    } else if (vec) {
+        // several workgroups per sequence (4 slabs each, at most XCH_WGS) when all of them get a compute unit
+        int per = 4;
+        while ((slabs + per - 1) / per > XCH_WGS) ++per;
+        const int G = (int)((slabs + per - 1) / per);
+        if (G > 1 && a->batch <= XCH_SEQS && (long long)a->batch * G <= compute_units()) {
+            W.slabs_per_wg = per;
+            hipLaunchKernelGGL((verify_walk_kernel<4, true>), dim3(G, a->batch), dim3(WALK_THREADS), 0, (hipStream_t)stream, W);
+        } else {
+            hipLaunchKernelGGL((verify_walk_kernel<4, false>), dim3(a->batch), dim3(WALK_THREADS), 0, (hipStream_t)stream, W);
+        }
+    } else {
+        hipLaunchKernelGGL((verify_walk_kernel<1, false>), dim3(a->batch), dim3(WALK_THREADS), 0, (hipStream_t)stream, W);
+    }
     return hipGetLastError() == hipSuccess ? PS_OK : PS_ERR_DEVICE;
 }

@@ -206,3 +206,10 @@ def test_tree_and_walk_replayed_from_a_graph():
             if rep % 2 == 0:
                 both(torch.cuda.current_stream().cuda_stream)
                 check(cur, "eager after replay %d V%d" % (rep, vocab))
+
+
+def test_large_vocabulary_with_more_sequences_than_compute_units_allow_to_split():
+    # 64 sequences x 8 workgroups would need 512 compute units: every sequence is walked by one workgroup
+    parent, rank = inputs.draft_tree([2])
+    inp = inputs.verify_inputs(12, 64, parent, rank, 2, 4, 131072, agreement=0.5)
+    _check(parent, rank, inp, 2, 4, "large vocabulary, one workgroup per sequence")
