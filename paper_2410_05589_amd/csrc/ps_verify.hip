@@ -34,6 +34,8 @@ struct WalkParams {
     const float *q, *p, *r;
     int32_t *n_accepted, *path, *out_tokens;
     int slabs_per_wg;     // several workgroups per sequence: slabs of the vocabulary each of them takes
+    int spin_limit;       // ... polls before a wait for another workgroup's sum is given up
+    int ghosts;           // ... workgroups waited for that do not exist (0; tests of the give-up path: 1)
 };
 struct TokensParams {
     TreeDev t;
@@ -161,24 +163,24 @@ static __device__ unsigned long long g_xch[XCH_SEQS][XCH_ROUNDS][XCH_WGS][2];
 static __device__ unsigned g_epoch[XCH_SEQS];
 
 // all workgroups of sequence b: the sum over g of their `mine`, the same in every thread; false if a wait ran out
-__device__ __forceinline__ bool xch_sum(double mine, int b, int rnd, unsigned tag, double* s_x, double& sum) {
+__device__ __forceinline__ bool xch_sum(const WalkParams& Wp, double mine, int b, int rnd, unsigned tag, double* s_x, double& sum) {
     const int g = blockIdx.x, G = gridDim.x, tid = threadIdx.x;
     if (tid == 0) {
         const unsigned long long bits = (unsigned long long)__double_as_longlong(mine);
         __hip_atomic_store(&g_xch[b][rnd][g][0], ((bits & 0xFFFFFFFFull) << 32) | tag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         __hip_atomic_store(&g_xch[b][rnd][g][1], ((bits >> 32) << 32) | tag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
-    if (tid < G) {
+    if (tid < G + Wp.ghosts) {
         unsigned long long lo = 0, hi = 0;
         int spins = 0;
         for (;;) {
             lo = __hip_atomic_load(&g_xch[b][rnd][tid][0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             hi = __hip_atomic_load(&g_xch[b][rnd][tid][1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            if (((unsigned)lo == tag && (unsigned)hi == tag) || ++spins > XCH_SPINS) break;
+            if (((unsigned)lo == tag && (unsigned)hi == tag) || ++spins > Wp.spin_limit) break;
             __builtin_amdgcn_s_sleep(2);
         }
         const bool ok = (unsigned)lo == tag && (unsigned)hi == tag;
-        s_x[tid] = ok ? __longlong_as_double((long long)((lo >> 32) | ((hi >> 32) << 32))) : 0.0;
+        if (tid < G) s_x[tid] = ok ? __longlong_as_double((long long)((lo >> 32) | ((hi >> 32) << 32))) : 0.0;
         if (!ok) s_x[XCH_WGS] = 1.0;
     }
     __syncthreads();
@@ -266,7 +268,7 @@ __global__ void __launch_bounds__(WALK_THREADS) verify_walk_kernel(const WalkPar
                     }
                 }
                 double t = block_sum(local, s_red);
-                if (MULTI && !xch_sum(t, b, rnd++, tag, s_x, t)) {
+                if (MULTI && !xch_sum(Wp, t, b, rnd++, tag, s_x, t)) {
                     fail();
                     return;
                 }
@@ -333,7 +335,7 @@ __global__ void __launch_bounds__(WALK_THREADS) verify_walk_kernel(const WalkPar
         // the workgroups' totals: the draw falls to the first workgroup whose cumulative sum exceeds the
         // target (the last one if none does); the others are done
         const double mine_total = total;
-        if (!xch_sum(mine_total, b, rnd++, tag, s_x, total)) {
+        if (!xch_sum(Wp, mine_total, b, rnd++, tag, s_x, total)) {
             fail();
             return;
         }
@@ -600,7 +602,18 @@ int load_tree(const ps_tree_shape* tree, int rows, int topk, TreeDev* out) {
     return PS_OK;
 }
 
+// test hook (see ps_verify_debug_exchange)
+std::atomic<int> g_spin_limit{XCH_SPINS}, g_ghosts{0};
+
 }   // namespace
+
+// Testing aid, not declared in the public header: the following multi-workgroup walks give up a wait after
+// `spins` polls (<= 0: the default) and wait for `ghosts` (0 or 1) workgroups per sequence that do not exist,
+// so the give-up path can be exercised while every kernel still ends normally.
+extern "C" __attribute__((visibility("default"))) void ps_verify_debug_exchange(int spins, int ghosts) {
+    g_spin_limit = spins > 0 ? spins : XCH_SPINS;
+    g_ghosts = ghosts == 1 ? 1 : 0;
+}
 
 extern "C" int ps_tree_tokens(const ps_tree_shape* tree, int32_t batch, int32_t rows, int32_t topk,
                               const int32_t* top_ids, int32_t* tokens, void* stream) {
@@ -630,6 +643,8 @@ extern "C" int ps_verify_walk(const ps_tree_shape* tree, const ps_verify_args* a
     const long long slabs = ((long long)a->vocab / (vec ? 4 : 1) + WALK_THREADS - 1) / WALK_THREADS;
     if (slabs > WALK_MAX_SLABS) return PS_ERR_UNSUPPORTED;
     W.slabs_per_wg = (int)slabs;
+    W.spin_limit = g_spin_limit;
+    W.ghosts = 0;
     if (vec && a->vocab <= REG_EPT * REG_THREADS) {
         hipLaunchKernelGGL(verify_walk_reg_kernel, dim3(a->batch), dim3(REG_THREADS), 0, (hipStream_t)stream, W);
     } else if (vec) {
@@ -639,6 +654,7 @@ extern "C" int ps_verify_walk(const ps_tree_shape* tree, const ps_verify_args* a
         const int G = (int)((slabs + per - 1) / per);
         if (G > 1 && a->batch <= XCH_SEQS && (long long)a->batch * G <= compute_units()) {
             W.slabs_per_wg = per;
+            W.ghosts = G < XCH_WGS ? (int)g_ghosts : 0;
             hipLaunchKernelGGL((verify_walk_kernel<4, true>), dim3(G, a->batch), dim3(WALK_THREADS), 0, (hipStream_t)stream, W);
         } else {
             hipLaunchKernelGGL((verify_walk_kernel<4, false>), dim3(a->batch), dim3(WALK_THREADS), 0, (hipStream_t)stream, W);
