@@ -45,17 +45,19 @@ def algorithmic_bytes(wl, kv_len, n_new, k):
     return per
 
 
-def verify_walk_report(torch, with_oracle, calls=200):
+def verify_walk_report(torch, with_oracle, vocab=32000, k=5, calls=200):
     """Tree construction + acceptance walk (the step after the draft step in Algorithm 1) on a tree of the
-    c1 drafter's shape: 61 nodes (fan-out 4, 2, 2, 1, 1 over the k+1 = 6 draft rows), vocabulary 32000,
-    one sequence, a target that agrees with the drafter's next row to 70 %.  Latency per call from HIP
+    workload's drafter: 61 nodes (fan-out 4, 2, 2, 1, 1 over the k+1 = 6 draft rows) for k = 5, 46 nodes
+    (fan-out 3, 2, 1, ...) for k = 8; the workload's vocabulary; one sequence; a target that agrees with the
+    drafter's next row to 70 %.  Latency per call from HIP
     events over `calls` back-to-back calls; bytes = what the walk has to read when P stays on chip (first
     rejection at a node: the target's row and the draft row; further ones: the draft row; the final draw: the
     target's row if P is still that row), counted on the oracle's walk of the same inputs."""
     from paper_2410_05589_amd import inputs
     from paper_2410_05589_amd import verify as VF
     dev = torch.device("cuda:0")
-    fan, rows, vocab, topk, batch = [4, 2, 2, 1, 1], 6, 32000, 8, 1
+    fan = ([4, 2, 2, 1, 1] + [1] * 8)[:k] if k <= 5 else ([3, 2] + [1] * 8)[:k]
+    rows, topk, batch = k + 1, 8, 1
     parent, rank = inputs.draft_tree(fan)
     inp = inputs.verify_inputs(1, batch, parent, rank, rows, topk, vocab, agreement=0.7)
     n = len(parent)
@@ -96,7 +98,8 @@ def verify_walk_report(torch, with_oracle, calls=200):
 
     both_us = timed([build, walk])
     walk_us = timed([walk])
-    rep = {"workload": "tree of 61 nodes (fan-out 4,2,2,1,1), 6 draft rows, V 32000, batch 1, target agrees 70 %",
+    rep = {"workload": "tree of %d nodes (fan-out %s), %d draft rows, V %d, batch 1, target agrees 70 %%"
+                       % (n, ",".join(str(f) for f in fan), rows, vocab),
            "latency_us_tree_and_walk": round(both_us, 2), "latency_us_walk": round(walk_us, 2), "calls": calls,
            "dtype": "f64", "n_accepted": int(n_acc.cpu().numpy()[0])}
     if with_oracle:
@@ -113,7 +116,7 @@ def verify_walk_report(torch, with_oracle, calls=200):
                     "roofline": {"bound": "hbm", "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
                                  "frac": round(gbs / PEAK_HBM_GBS, 5), "algorithmic_bytes_per_launch": int(nbytes),
                                  "traffic": None,
-                                 "note": "one workgroup per sequence: bound by latency and one CU's bandwidth, not by HBM"},
+                                 "note": "a chain of dependent steps on one compute unit (8 for V 128256) per sequence: bound by latency, not by HBM"},
                     "cpu_baseline": {"value": round(cpu_s * 1e6, 1), "unit": "us per walk", "cores": 1, "kind": "oracle",
                                      "sample": "one walk of the same inputs (numpy float64)"}})
     return rep
@@ -303,7 +306,7 @@ def main():
                                                                                        len(os.sched_getaffinity(0))),
                                   "top1_agreement_with_gpu": agree}
     drafter.close()
-    result["next_rows"] = {"verify_walk": verify_walk_report(torch, not args.no_cpu_baseline)}
+    result["next_rows"] = {"verify_walk": verify_walk_report(torch, not args.no_cpu_baseline, vocab=shape.vocab, k=wl.k)}
     print(json.dumps(result))
 
 
