@@ -52,7 +52,10 @@ int ps_tree_tokens(const ps_tree_shape* tree, int32_t batch, int32_t rows, int32
  * token is drawn from P by inversion with r[0]: the number of token ids whose cumulative sum
  * of P (in id order) is <= r[0] * sum(P), at most vocab-1.
  *   tokens      DEVICE [batch][n_nodes] int32 (entry 0 ignored); a token outside [0, vocab)
- *               is treated as rejected and leaves P unchanged
+ *               is treated as rejected and leaves P unchanged.  May be NULL when top_ids is
+ *               given: node s then carries top_ids[b][depth(s) - 1][rank[s]], what
+ *               ps_tree_tokens would have written (tree->rank is needed then)
+ *   top_ids     DEVICE [batch][rows][topk] int32 or NULL; read only when tokens is NULL
  *   q           DEVICE [batch][rows][vocab] float32: the drafter's distributions
  *               (ps_draft_step's probs); rows >= the tree's depth
  *   p           DEVICE [batch][n_nodes][vocab] float32: the target's next-token distribution
@@ -69,7 +72,8 @@ int ps_tree_tokens(const ps_tree_shape* tree, int32_t batch, int32_t rows, int32
  * do).  Should that exchange ever time out (it cannot while every workgroup of the launch gets a compute
  * unit), n_accepted[b] = -2 marks the sequence and its other outputs are undefined.
  * Errors: PS_ERR_NULL; PS_ERR_SHAPE (batch < 1, vocab < 1, a malformed tree, a depth beyond
- * rows); PS_ERR_UNSUPPORTED (vocab too large); PS_ERR_DEVICE.
+ * rows; without tokens: topk < 1 or a rank outside [0, topk)); PS_ERR_UNSUPPORTED (vocab too
+ * large); PS_ERR_DEVICE.
  */
 typedef struct ps_verify_args {
     int32_t batch, rows, vocab;
@@ -80,6 +84,8 @@ typedef struct ps_verify_args {
     int32_t* n_accepted;
     int32_t* path;
     int32_t* out_tokens;
+    const int32_t* top_ids;
+    int32_t topk;
 } ps_verify_args;
 int ps_verify_walk(const ps_tree_shape* tree, const ps_verify_args* args, void* stream);
 

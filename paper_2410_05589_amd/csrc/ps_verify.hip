@@ -30,7 +30,9 @@ struct TreeDev {
 struct WalkParams {
     TreeDev t;
     int rows, vocab;
-    const int32_t* tokens;
+    const int32_t* tokens;   // or NULL: the tokens come from top_ids
+    const int32_t* top_ids;
+    int topk;
     const float *q, *p, *r;
     int32_t *n_accepted, *path, *out_tokens;
     int slabs_per_wg;     // several workgroups per sequence: slabs of the vocabulary each of them takes
@@ -115,7 +117,9 @@ struct NodeLds {
 __device__ __forceinline__ void load_nodes(const WalkParams& Wp, int b, const float* q, const float* p, NodeLds& L) {
     const int tid = threadIdx.x, V = Wp.vocab, N = Wp.t.n_nodes;
     if (tid < N) {
-        const int x = Wp.tokens[(size_t)b * N + tid];
+        int x = -1;
+        if (Wp.tokens) x = Wp.tokens[(size_t)b * N + tid];
+        else if (tid > 0) x = Wp.top_ids[((size_t)b * Wp.rows + (Wp.t.depth[tid] - 1)) * Wp.topk + Wp.t.rank[tid]];
         const bool ok = tid > 0 && (unsigned)x < (unsigned)V;
         L.tok[tid] = ok ? x : -1;
         L.first[tid] = Wp.t.first_child[tid];
@@ -629,14 +633,14 @@ extern "C" int ps_tree_tokens(const ps_tree_shape* tree, int32_t batch, int32_t 
 
 extern "C" int ps_verify_walk(const ps_tree_shape* tree, const ps_verify_args* a, void* stream) {
     if (!a) return PS_ERR_NULL;
-    if (!a->tokens || !a->q || !a->p || !a->r || !a->n_accepted || !a->path || !a->out_tokens)
+    if ((!a->tokens && !a->top_ids) || !a->q || !a->p || !a->r || !a->n_accepted || !a->path || !a->out_tokens)
         return PS_ERR_NULL;
-    if (a->batch < 1 || a->rows < 1 || a->vocab < 1) return PS_ERR_SHAPE;
+    if (a->batch < 1 || a->rows < 1 || a->vocab < 1 || (!a->tokens && a->topk < 1)) return PS_ERR_SHAPE;
     WalkParams W;
-    const int st = load_tree(tree, a->rows, 0, &W.t);
+    const int st = load_tree(tree, a->rows, a->tokens ? 0 : a->topk, &W.t);   // (ranks are needed without tokens)
     if (st != PS_OK) return st;
     W.rows = a->rows; W.vocab = a->vocab;
-    W.tokens = a->tokens; W.q = a->q; W.p = a->p; W.r = a->r;
+    W.tokens = a->tokens; W.top_ids = a->tokens ? nullptr : a->top_ids; W.topk = a->topk; W.q = a->q; W.p = a->p; W.r = a->r;
     W.n_accepted = a->n_accepted; W.path = a->path; W.out_tokens = a->out_tokens;
     // whole vectors of four entries when every row of q and p starts on a 16-byte boundary
     const bool vec = a->vocab % 4 == 0 && (((uintptr_t)a->q | (uintptr_t)a->p) & 15) == 0;

@@ -19,7 +19,7 @@ class ps_verify_args(ctypes.Structure):
     _fields_ = [("batch", ctypes.c_int32), ("rows", ctypes.c_int32), ("vocab", ctypes.c_int32),
                 ("tokens", ctypes.c_void_p), ("q", ctypes.c_void_p), ("p", ctypes.c_void_p), ("r", ctypes.c_void_p),
                 ("n_accepted", ctypes.c_void_p), ("path", ctypes.c_void_p),
-                ("out_tokens", ctypes.c_void_p)]
+                ("out_tokens", ctypes.c_void_p), ("top_ids", ctypes.c_void_p), ("topk", ctypes.c_int32)]
 
 
 _ready = False

@@ -44,8 +44,19 @@ def _run_gpu(parent, rank, inp, rows, topk, tokens_override=None):
     st = VF.ps_verify_walk(tree, a, stream)
     assert st == B.PS_OK, B.ps_draft_strerror(st)
     torch.cuda.synchronize()
-    return {"tokens": tokens.cpu().numpy() if tokens_override is None else built, "n_accepted": n_acc.cpu().numpy(),
-            "path": path.cpu().numpy(), "out_tokens": out_tokens.cpu().numpy()}
+    res = {"tokens": tokens.cpu().numpy() if tokens_override is None else built, "n_accepted": n_acc.cpu().numpy(),
+           "path": path.cpu().numpy(), "out_tokens": out_tokens.cpu().numpy()}
+    if tokens_override is None:
+        # the same walk with the tokens taken straight from top_ids (no ps_tree_tokens): identical outputs
+        n_acc.fill_(-7); path.fill_(-7); out_tokens.fill_(-7)
+        a.tokens, a.top_ids, a.topk = None, top_ids.data_ptr(), topk
+        st = VF.ps_verify_walk(tree, a, stream)
+        assert st == B.PS_OK, B.ps_draft_strerror(st)
+        torch.cuda.synchronize()
+        assert np.array_equal(n_acc.cpu().numpy(), res["n_accepted"])
+        assert np.array_equal(path.cpu().numpy(), res["path"])
+        assert np.array_equal(out_tokens.cpu().numpy(), res["out_tokens"])
+    return res
 
 
 def _check(parent, rank, inp, rows, topk, label, tokens_override=None, oracle_tokens=None):

@@ -61,6 +61,11 @@ def test_walk_rejects_bad_arguments_on_the_host(lib):
         assert VF.ps_verify_walk(good, _args(**{n: None}), None) == B.PS_ERR_NULL, n
     for kw in (dict(batch=0), dict(rows=0), dict(vocab=0), dict(rows=1)):   # rows=1: depth 2 > rows
         assert VF.ps_verify_walk(good, _args(**kw), None) == B.PS_ERR_SHAPE, kw
+    # without tokens the walk reads top_ids: both missing, no topk, no ranks, a rank beyond topk
+    assert VF.ps_verify_walk(good, _args(tokens=None), None) == B.PS_ERR_NULL
+    assert VF.ps_verify_walk(good, _args(tokens=None, top_ids=0x1000, topk=0), None) == B.PS_ERR_SHAPE
+    assert VF.ps_verify_walk(VF.make_tree([-1, 0]), _args(tokens=None, top_ids=0x1000, topk=4), None) == B.PS_ERR_NULL
+    assert VF.ps_verify_walk(good, _args(tokens=None, top_ids=0x1000, topk=1), None) == B.PS_ERR_SHAPE
     assert VF.ps_verify_walk(good, _args(vocab=1048580), None) == B.PS_ERR_UNSUPPORTED
     assert VF.ps_verify_walk(good, _args(vocab=262145), None) == B.PS_ERR_UNSUPPORTED      # odd: one entry per load
     for parent in ([0, 0], [-1, 1], [-1, -1], [-1, 0, 3], [-1] + [0] * 64, []):
