@@ -243,3 +243,64 @@ def test_a_wait_that_runs_out_marks_the_sequence_and_the_next_call_is_fine():
         lib.ps_verify_debug_exchange(0, 0)
     assert gpu["n_accepted"].tolist() == [-2, -2]
     _check(parent, rank, inp, 3, 8, "after a wait that ran out")
+
+
+def test_tokens_emitted_by_the_gpu_walk_follow_the_target_distribution():
+    """Section 4.2's claim on the device path itself: with children that are independent samples of q, the first
+    token the walk emits is distributed as the target's p(. | prefix), and the second, given the first, as the
+    target's distribution after it.  32768 walks of a 3 x 2 tree over 8 tokens (512 launches of 64 sequences)."""
+    import torch
+    dev = torch.device("cuda:0")
+    V, batch, launches = 8, 64, 512
+    g = np.random.default_rng(77)
+    p_root = g.dirichlet(np.full(V, 0.7))
+    p_after = g.dirichlet(np.full(V, 0.7), size=V)
+    noise = g.dirichlet(np.full(V, 0.7), size=2)
+    q_rows = np.stack([0.5 * p_root + 0.5 * noise[0], 0.5 * p_after.mean(axis=0) + 0.5 * noise[1]]).astype(np.float32)
+    q64 = q_rows.astype(np.float64)
+    parent = np.array([-1, 0, 0, 0, 1, 1, 2, 2, 3, 3], dtype=np.int32)
+    depth = vw.tree_depths(parent)
+    n, rows = len(parent), 2
+    tree = VF.make_tree(parent, np.zeros(n, dtype=np.int32))
+    p_root32, p_after32 = p_root.astype(np.float32), p_after.astype(np.float32)
+    q = torch.from_numpy(np.broadcast_to(q_rows, (batch, rows, V)).copy()).to(dev)
+    tokens = torch.zeros((batch, n), dtype=torch.int32, device=dev)
+    p = torch.zeros((batch, n, V), dtype=torch.float32, device=dev)
+    r = torch.zeros((batch, n), dtype=torch.float32, device=dev)
+    n_acc = torch.zeros((batch,), dtype=torch.int32, device=dev)
+    path = torch.zeros((batch, rows), dtype=torch.int32, device=dev)
+    out_tokens = torch.zeros((batch, rows + 1), dtype=torch.int32, device=dev)
+    a = VF.ps_verify_args()
+    a.batch, a.rows, a.vocab = batch, rows, V
+    a.tokens, a.q, a.p, a.r = tokens.data_ptr(), q.data_ptr(), p.data_ptr(), r.data_ptr()
+    a.n_accepted, a.path, a.out_tokens = n_acc.data_ptr(), path.data_ptr(), out_tokens.data_ptr()
+    stream = torch.cuda.current_stream().cuda_stream
+    first = np.zeros(V)
+    second = np.zeros((V, V))
+    accepted = 0
+    for it in range(launches):
+        tok = np.full((batch, n), -1, dtype=np.int32)
+        for s in range(1, n):                        # children: independent samples of their depth's draft row
+            tok[:, s] = g.choice(V, size=batch, p=q64[depth[s] - 1] / q64[depth[s] - 1].sum())
+        pp = np.empty((batch, n, V), dtype=np.float32)
+        pp[:, 0] = p_root32
+        pp[:, 1:] = p_after32[tok[:, 1:]]
+        tokens.copy_(torch.from_numpy(tok)); p.copy_(torch.from_numpy(pp))
+        r.copy_(torch.from_numpy(np.minimum(g.random((batch, n)), 1.0 - 2.0 ** -24).astype(np.float32)))
+        assert VF.ps_verify_walk(tree, a, stream) == B.PS_OK
+        torch.cuda.synchronize()
+        out, na = out_tokens.cpu().numpy(), n_acc.cpu().numpy()
+        accepted += int(na.sum())
+        np.add.at(first, out[:, 0], 1)
+        has2 = na >= 1                               # a second token exists after at least one accepted one
+        np.add.at(second, (out[has2, 0], out[has2, 1]), 1)
+    trials = batch * launches
+    assert accepted > 0.5 * trials
+    f = first / trials
+    assert np.all(np.abs(f - p_root) < 4.5 * np.sqrt(p_root * (1 - p_root) / trials) + 1e-6), (f, p_root)
+    for x in range(V):
+        m = second[x].sum()
+        if m < 400:
+            continue
+        fx = second[x] / m
+        assert np.all(np.abs(fx - p_after[x]) < 4.5 * np.sqrt(p_after[x] * (1 - p_after[x]) / m) + 1e-6), (x, fx, p_after[x])
