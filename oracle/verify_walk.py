@@ -21,9 +21,10 @@ unused slot, draws the last token); the last token is drawn by inversion of the 
 sum in token-id order: the number of ids whose cumulative sum is <= r[0] * total, at most
 V-1.
 
-Pins (tests/test_oracle_verify.py, CPU): emitted tokens follow the target distribution when
-the children are independent samples of q (Monte Carlo over the oracle, Section 4.2's
-claim of a preserved output distribution); p == q accepts every first child; a proposal
+Pins (tests/test_oracle_verify.py, CPU): the first three emitted tokens follow the target
+distribution when the children are independent samples of q (Monte Carlo over the oracle,
+Section 4.2's claim of a preserved output distribution; the same check fails for planted
+mistakes); p == q accepts every first child; a proposal
 the target gives probability 0 is always rejected; inversion against numpy.searchsorted;
 tree tokens against a hand-written example.
 """

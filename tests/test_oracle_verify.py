@@ -2,7 +2,9 @@
 
 The main pin is the property the algorithm exists for: when the children of every node are
 independent samples of the draft distribution of their depth, the tokens the walk emits are
-distributed exactly as if the target model had generated them one by one.
+distributed exactly as if the target model had generated them one by one (checked on the
+first three emitted tokens; a second test plants mistakes in the oracle and shows that this
+check fails for each of them).
 """
 import numpy as np
 
@@ -13,19 +15,20 @@ def _dirichlet(g, n, V, conc=0.7):
     return g.dirichlet(np.full(V, conc), size=n)
 
 
-def test_emitted_tokens_follow_the_target_distribution():
+def _emitted_token_statistics(trials, seed=11):
     # target: first-order Markov chain over V tokens; drafter: one distribution per depth (it does
     # not see the path, like the parallel drafter); tree: 3 children of the root, 2 children each
-    V, trials = 4, 30000
-    g = np.random.default_rng(11)
+    V = 4
+    g = np.random.default_rng(seed)
     p_root = _dirichlet(g, 1, V)[0]
     p_after = _dirichlet(g, V, V)            # p_after[a] = target distribution after token a
     noise = _dirichlet(g, 2, V)
     q = np.stack([0.5 * p_root + 0.5 * noise[0], 0.5 * p_after.mean(axis=0) + 0.5 * noise[1]])   # a drafter that is half right
     parent = np.array([-1, 0, 0, 0, 1, 1, 2, 2, 3, 3])
-    depth = vw.tree_depths(parent)
+    depth = [0, 1, 1, 1, 2, 2, 2, 2, 2, 2]           # (written out: independent of the oracle)
     first = np.zeros(V)
     second = np.zeros((V, V))
+    third = np.zeros((V, V))
     n_acc = 0
     for _ in range(trials):
         tokens = np.array([-1] + [g.choice(V, p=q[depth[s] - 1]) for s in range(1, len(parent))])
@@ -34,15 +37,47 @@ def test_emitted_tokens_follow_the_target_distribution():
         first[out["tokens"][0]] += 1
         if len(out["tokens"]) > 1:
             second[out["tokens"][0], out["tokens"][1]] += 1
+        if len(out["tokens"]) > 2:                   # (the target is a Markov chain: the third follows the second)
+            third[out["tokens"][1], out["tokens"][2]] += 1
         n_acc += out["n_accepted"]
-    assert n_acc > 0.5 * trials                      # the tree is actually used
-    f = first / trials
-    assert np.all(np.abs(f - p_root) < 4.5 * np.sqrt(p_root * (1 - p_root) / trials)), (f, p_root)
-    for a in range(V):
-        n = second[a].sum()
-        assert n > 500
-        fa = second[a] / n
-        assert np.all(np.abs(fa - p_after[a]) < 4.5 * np.sqrt(p_after[a] * (1 - p_after[a]) / n)), (a, fa, p_after[a])
+    # worst deviation of an observed frequency from the target's probability, in standard deviations
+    worst = float(np.max(np.abs(first / trials - p_root) / np.sqrt(p_root * (1 - p_root) / trials)))
+    for counts in (second, third):
+        for a in range(V):
+            n = counts[a].sum()
+            if n > 0.01 * trials:
+                sd = np.sqrt(p_after[a] * (1 - p_after[a]) / n)
+                worst = max(worst, float(np.max(np.abs(counts[a] / n - p_after[a]) / sd)))
+    return n_acc / trials, worst
+
+
+def test_emitted_tokens_follow_the_target_distribution():
+    accepted_per_walk, worst = _emitted_token_statistics(30000)
+    assert accepted_per_walk > 0.5                   # the tree is actually used
+    assert worst < 4.5, worst
+
+
+def test_the_distribution_pin_catches_planted_mistakes(monkeypatch):
+    """The same statistics on an oracle with one step spoiled (planted here, on the CPU) are far off."""
+    class NoClip:                                    # (P - q)+ without the positive part
+        def __getattr__(self, name):
+            return (lambda x, y: x) if name == "maximum" else getattr(np, name)
+    monkeypatch.setattr(vw, "np", NoClip())
+    assert _emitted_token_statistics(8000)[1] > 8.0
+    monkeypatch.undo()
+    real_depths = vw.tree_depths                     # every depth reads the first draft row
+    monkeypatch.setattr(vw, "tree_depths", lambda parent: np.minimum(real_depths(parent), 1))
+    assert _emitted_token_statistics(8000)[1] > 8.0
+    monkeypatch.undo()
+    class NoSum:                                     # the residual is not normalised (its sum is taken as 1)
+        def __getattr__(self, name):
+            return (lambda x: 1.0) if name == "sum" else getattr(np, name)
+    monkeypatch.setattr(vw, "np", NoSum())
+    assert _emitted_token_statistics(8000)[1] > 8.0
+    monkeypatch.undo()
+    real_draw = vw.draw_by_inversion                 # the last token always drawn with u = 0.5
+    monkeypatch.setattr(vw, "draw_by_inversion", lambda P, u: real_draw(P, 0.5))
+    assert _emitted_token_statistics(8000)[1] > 8.0
 
 
 def test_single_child_chain_accepts_with_probability_sum_min_p_q():
