@@ -1,14 +1,29 @@
 #!/usr/bin/env python3
 """Benchmark of the parallel draft step on one MI355X.
 
-    python bench.py --gpus 1 --steps K --warmup W [--workload c1]
+    python bench.py --gpus 1 --steps K --warmup W [--workload all|c0|c1|c2|c3|c4]
 
-A "step" is one ps_draft_step: one forward of the one-layer drafter over n_new real rows
-plus k [MASK] rows against the KV cache, LM head with fused softmax/top-k included.  All
-inputs are seeded, synthetic and resident in HBM before the timed region.  Prints ONE JSON
-line: draft tokens/s (k+1 tokens per sequence per step), step latency, the HBM roofline of
-the dominant kernel (the LM-head GEMM, timed live with HIP events on the launch stream) and
-of the whole step, and the CPU oracle timed on this machine's host cores as a baseline.
+A "step" is one ps_draft_step: one forward of the one-layer drafter over n_new real rows plus k [MASK]
+rows against the KV cache, LM head with fused softmax/top-k included; in the default mode it is ONE launch of
+the persistent kernel.  All inputs are seeded, synthetic and resident in HBM before the timed region.
+
+By default every bf16 workload (c1 7B, c2 13B with the accepted-length mix, c3 batch 8, c4 Llama-3-8B shape)
+is timed in turn, K steps each after W warm-up steps, and ONE JSON line is printed whose headline figures
+(value, ms_per_step, config, roofline, cpu_baseline) are those of the largest workload, c4; the key
+"workloads" carries the same figures for each of them, "c0_latency_us" the tiny fp32 correctness workload's
+latency, "stream_read" what a plain streaming read of HBM reaches on this machine.  Per workload:
+  * draft tokens/s (k+1 tokens per sequence per step) and latency from the host clock around the K steps,
+  * per-step latency percentiles and the persistent kernel's average duration from HIP events on the launch
+    stream, and with them the HBM roofline: algorithmic bytes (weights once + valid K/V once + new K/V rows
+    once) / duration / 8 TB/s,
+  * the HBM traffic per launch that rocprofv3's FETCH_SIZE / WRITE_SIZE counters showed for the same command
+    (profiles/hbm_traffic.txt, written from the runs that profiles/*_hbm_traffic.md document),
+  * the CPU oracle timed on this machine's host cores on the same inputs, as a baseline.
+
+Aids for the profiles (all run committed code only):
+    --calibrate-copy          a copy kernel of known size, to scale the profiler's counters
+    --summarize DB [DB ...]   per-kernel durations / counter values of rocprofv3 result databases
+    --timeline                per-stretch clock stamps of the persistent kernel (a -DPS_TIMELINE build)
 """
 import argparse
 import json
@@ -22,7 +37,9 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 PEAK_HBM_GBS = 8000.0   # MI355X HBM3E, published peak
-MEASURED_TRAFFIC = {("c1", "fused"): 713460870}
+BENCH_WORKLOADS = ("c1", "c2", "c3", "c4")
+HEADLINE = "c4"         # the largest single-GPU workload
+TRAFFIC_TABLE = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
 
 
 def algorithmic_bytes(wl, kv_len, n_new, k):
@@ -43,6 +60,283 @@ def algorithmic_bytes(wl, kv_len, n_new, k):
     per["kv_write"] = len(kv_len) * 2 * m * s.kv_dim * esz
     per["total"] = sum(per.values())
     return per
+
+
+def load_traffic_table():
+    """profiles/hbm_traffic.txt: lines `workload mode fetch_bytes write_bytes` (HBM bytes per launch of the
+    dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled with the copy kernel)."""
+    table = {}
+    if os.path.exists(TRAFFIC_TABLE):
+        for line in open(TRAFFIC_TABLE):
+            f = line.split("#")[0].split()
+            if len(f) == 4:
+                table[(f[0], f[1])] = int(f[2]) + int(f[3])
+    return table
+
+
+def workload_label(wl, kv_len, mix, n_new_mean):
+    s = wl.shape
+    return ("%s: 1 decoder layer H%d %dq/%dkv x%d F%d V%d, batch %d, KV %s, n_new %s, k %d, topk %d"
+            % (wl.name, s.hidden, s.n_heads, s.n_kv_heads, s.head_dim, s.ffn, s.vocab, wl.batch,
+               list(kv_len) if wl.batch > 1 else kv_len[0],
+               "mix %s (mean %.2f)" % (list(wl.n_new_mix), n_new_mean) if mix else wl.n_new, wl.k, wl.topk))
+
+
+def setup_workload(torch, wl, steps):
+    from paper_2410_05589_amd import binding as B
+    from paper_2410_05589_amd import inputs
+    shape = wl.shape
+    kv_len = inputs.draw_kv_len(wl)
+    mix = inputs.draw_n_new_mix(wl, steps) if wl.n_new_mix else None
+    max_new = max(wl.n_new_mix) if wl.n_new_mix else wl.n_new
+    w = inputs.make_weights(shape, wl.seed)
+    drafter = B.Drafter(shape, w, max_batch=wl.batch, max_new=max_new,
+                        max_positions=max(kv_len) + max_new + wl.k, max_topk=wl.topk, k_max=wl.k)
+    # one input set per distinct n_new (the accepted-length mix of c2); the cache is reset by keeping kv_len
+    # fixed, so every step rewrites the same n_new + k rows
+    variants = {}
+    for n_new in sorted(set(mix)) if mix else [wl.n_new]:
+        inp = inputs.make_step_inputs(wl, kv_len=kv_len, n_new=n_new, k=wl.k)
+        dev = {n: B.to_device(inp[n], shape.dtype) for n in ("x", "k_cache", "v_cache")}
+        outs = drafter.alloc_outputs(wl.batch, n_new, wl.k, wl.topk)
+        a = drafter.make_args(dev["x"], dev["k_cache"], dev["v_cache"], inp["kv_offsets"], inp["kv_len"],
+                              n_new, wl.k, wl.topk, outs)
+        variants[n_new] = (a, inp, outs)
+    seq = mix if mix else [wl.n_new] * steps
+    return w, drafter, variants, seq, kv_len, mix, max_new
+
+
+def measure_workload(torch, wl, args, traffic_table, with_oracle, kernel_timing):
+    """Times `args.steps` steps of one workload after `args.warmup` warm-up steps; returns its report."""
+    from paper_2410_05589_amd import binding as B
+    shape = wl.shape
+    w, drafter, variants, seq, kv_len, mix, max_new = setup_workload(torch, wl, args.steps + args.warmup)
+    stream = torch.cuda.current_stream()
+    for i in range(args.warmup):
+        drafter.step(variants[seq[i]][0])
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    ev0.record(stream)
+    for i in range(args.steps):
+        drafter.step(variants[seq[args.warmup + i]][0])
+    ev1.record(stream)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    ev_ms = ev0.elapsed_time(ev1) / args.steps
+    tokens_per_step = wl.batch * (wl.k + 1)
+    value = tokens_per_step / (ms_per_step * 1e-3)
+    timed = seq[args.warmup:]
+    n_new_mean = float(np.mean(timed))
+    bytes_mean = float(np.mean([algorithmic_bytes(wl, kv_len, n, wl.k)["total"] for n in timed]))
+    per = algorithmic_bytes(wl, kv_len, seq[-1], wl.k)
+
+    # ---- per-kernel durations, live, with HIP events on the launch stream (second region of steps)
+    kernel_us = roofline = per_step_us = None
+    if kernel_timing:
+        ksteps = min(args.steps, 200)
+        evs = [[torch.cuda.Event(enable_timing=True) for _ in range(B.PS_PROFILE_EVENTS)] for _ in range(ksteps)]
+        for row in evs:
+            for e in row:
+                e.record(stream)          # creates the underlying hipEvent_t
+        torch.cuda.synchronize()
+        for i in range(ksteps):
+            st = B.ps_draft_set_profile_events(drafter.ctx, [e.cuda_event for e in evs[i]])
+            assert st == B.PS_OK
+            drafter.step(variants[seq[args.warmup + i]][0])
+        B.ps_draft_set_profile_events(drafter.ctx, None)
+        torch.cuda.synchronize()
+        acc = np.zeros(B.PS_PROFILE_EVENTS - 1)
+        per_step = []
+        for row in evs:
+            for j in range(B.PS_PROFILE_EVENTS - 1):
+                acc[j] += row[j].elapsed_time(row[j + 1])
+            # fused: events 0 and 1 bracket the one kernel of the step; multi: first to last event = all its kernels
+            per_step.append(row[0].elapsed_time(row[1 if args.mode == "fused" else -1]) * 1e3)
+        per_step_us = {q: round(float(np.percentile(per_step, p)), 2) for q, p in (("p10", 10), ("median", 50), ("p90", 90))}
+        kernel_us = {n: float(acc[j] / ksteps * 1e3) for j, n in enumerate(B.PROFILE_KERNELS)}
+        dname = "bf16_t" if shape.dtype == "bf16" else "float"
+        mt = (wl.batch * (max_new + wl.k) + 15) // 16
+        if args.mode == "fused":
+            dom_us = float(acc[0] / ksteps * 1e3)   # events 0 and 1 bracket the single launch
+            kernel_us = {"fused_kernel": dom_us}
+            dom_bytes = float(np.mean([algorithmic_bytes(wl, kv_len, n, wl.k)["total"] for n in timed[:ksteps]]))
+            kname = "fused_kernel<%s, %d, %d>" % (dname, shape.head_dim, mt)
+        else:
+            dom_us = kernel_us["lmhead"]
+            dom_bytes = per["lmhead"]
+            kname = "gemm_kernel<%s, %d, 4>  (LM head)" % (dname, (wl.batch * (wl.k + 1) + 15) // 16)
+        achieved = dom_bytes / (dom_us * 1e-6) / 1e9
+        roofline = {"bound": "hbm", "kernel": kname, "achieved": round(achieved, 1), "peak": PEAK_HBM_GBS,
+                    "unit": "GB/s", "frac": round(achieved / PEAK_HBM_GBS, 4),
+                    "traffic": traffic_table.get((wl.name, args.mode)),
+                    "algorithmic_bytes_per_launch": int(dom_bytes), "avg_launch_us": round(dom_us, 2)}
+
+    # ---- the same step captured once in a HIP graph and replayed (only when every step has the same n_new)
+    graph_us = None
+    if kernel_timing and not mix:
+        a0 = variants[wl.n_new][0]
+        side = torch.cuda.Stream()
+        graph = torch.cuda.CUDAGraph()
+        torch.cuda.synchronize()
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(graph, stream=side):
+                drafter.step(a0, stream=side)
+        torch.cuda.synchronize()
+        for _ in range(min(args.warmup, 20)):
+            graph.replay()
+        torch.cuda.synchronize()
+        g0 = time.perf_counter()
+        for _ in range(args.steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        graph_us = (time.perf_counter() - g0) * 1e6 / args.steps
+    status = drafter.last_status()
+
+    step_gbs = bytes_mean / (ms_per_step * 1e-3) / 1e9
+    rep = {
+        "value": round(value, 1), "unit": "tokens/s", "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 5), "dtype": shape.dtype,
+        "config": {"workload": workload_label(wl, kv_len, mix, n_new_mean), "tokens_per_step": tokens_per_step},
+        "latency_us": round(ms_per_step * 1e3, 2),
+        "latency_us_hip_events": round(ev_ms * 1e3, 2),
+        "latency_us_per_step_events": per_step_us,
+        "latency_us_graph_replay": round(graph_us, 2) if graph_us else None,
+        "step_roofline": {"algorithmic_bytes": int(bytes_mean), "achieved_GBps": round(step_gbs, 1),
+                          "peak_GBps": PEAK_HBM_GBS, "frac": round(step_gbs / PEAK_HBM_GBS, 4),
+                          "roofline_latency_us": round(bytes_mean / PEAK_HBM_GBS / 1e3, 2)},
+        "kernel_us": {n: round(v, 2) for n, v in kernel_us.items()} if kernel_us else None,
+        "roofline": roofline,
+        "status_after_run": B.ps_draft_strerror(status),
+    }
+    if with_oracle:
+        from oracle import ps_oracle
+        try:
+            from threadpoolctl import threadpool_info
+            threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+        except Exception:
+            threads = 1
+        a, inp, outs = variants[seq[-1]]
+        n_new = seq[-1]
+        times = []
+        for _ in range(args.oracle_steps):
+            c0 = time.perf_counter()
+            ref = ps_oracle.draft_step(shape, w, inp["x"], inp["k_cache"], inp["v_cache"], inp["kv_offsets"], inp["kv_len"],
+                                       n_new, wl.k, wl.topk)
+            times.append(time.perf_counter() - c0)
+        best = float(np.mean(times))
+        torch.cuda.synchronize()
+        gpu_top1 = outs["top_ids"].cpu().numpy()[..., 0]   # sanity: the timed GPU step agrees with the oracle on the top-1 tokens
+        agree = float((gpu_top1 == ref["top_ids"][..., 0]).mean())
+        rep["cpu_baseline"] = {"value": round(tokens_per_step / best, 2), "unit": "tokens/s", "cores": int(threads),
+                               "kind": "oracle", "sample": "%d full steps of the same workload (numpy float64, "
+                               "mean %.2f s per step, host cores available %d)" % (args.oracle_steps, best,
+                                                                                    len(os.sched_getaffinity(0))),
+                               "top1_agreement_with_gpu": agree}
+    drafter.close()
+    return rep
+
+
+def stream_read_report(torch, mib=1536, iters=20):
+    """A plain streaming read of `mib` MiB of HBM (larger than the 256 MB Infinity Cache) with the weight
+    streams' access pattern and nothing else (ps_measure_stream_read): the read rate this machine gives."""
+    from paper_2410_05589_amd import debug as DBG
+    n = mib << 20
+    buf = torch.ones(n, dtype=torch.uint8, device="cuda:0")
+    stream = torch.cuda.current_stream()
+    for _ in range(3):
+        assert DBG.ps_measure_stream_read(buf.data_ptr(), n, stream.cuda_stream) == 0
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(stream)
+    for _ in range(iters):
+        DBG.ps_measure_stream_read(buf.data_ptr(), n, stream.cuda_stream)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    us = e0.elapsed_time(e1) * 1e3 / iters
+    gbs = n / (us * 1e-6) / 1e9
+    return {"GBps": round(gbs, 1), "frac_of_peak": round(gbs / PEAK_HBM_GBS, 4), "bytes": n, "us": round(us, 2),
+            "kernel": "stream_read_kernel (16-byte non-temporal loads, 8 in flight per lane, one workgroup of 512 per CU)"}
+
+
+def calibrate_copy(torch, mib, iters):
+    """Runs the copy kernel of known size (exactly `mib` MiB read and written per launch): under rocprofv3
+    --pmc FETCH_SIZE (then WRITE_SIZE), true KiB / counter is the factor for the other kernels' counters."""
+    from paper_2410_05589_amd import debug as DBG
+    n = mib << 20
+    src = torch.ones(n, dtype=torch.uint8, device="cuda:0")
+    dst = torch.zeros(n, dtype=torch.uint8, device="cuda:0")
+    stream = torch.cuda.current_stream().cuda_stream
+    torch.cuda.synchronize()
+    for _ in range(iters):
+        assert DBG.ps_measure_copy(dst.data_ptr(), src.data_ptr(), n, stream) == 0
+    torch.cuda.synchronize()
+    print("copy_kernel: %d MiB read and %d MiB written per launch, %d launches" % (mib, mib, iters))
+
+
+def summarize(paths):
+    """Per-kernel durations (kernel trace) and per-kernel counter averages (--pmc) of rocprofv3 databases."""
+    import re
+    import sqlite3
+    for path in paths:
+        c = sqlite3.connect(path)
+        tables = [r[0] for r in c.execute("select name from sqlite_master where type in ('table', 'view')")]
+        print("== %s" % path)
+        if "kernels" in tables:
+            rows = c.execute("select name, count(*), avg(end-start), min(end-start), max(end-start), sum(end-start) "
+                             "from kernels group by name order by sum(end-start) desc").fetchall()
+            tot = sum(r[5] for r in rows) or 1
+            print("%-70s %6s %10s %10s %10s %6s" % ("kernel", "calls", "avg_us", "min_us", "max_us", "pct"))
+            for r in rows:
+                n = re.sub(r"\(.*", "", re.sub(r"\(anonymous namespace\)::", "", r[0]))
+                print("%-70s %6d %10.2f %10.2f %10.2f %6.1f" % (n[:70], r[1], r[2] / 1e3, r[3] / 1e3, r[4] / 1e3, 100 * r[5] / tot))
+        if "counters_collection" in tables:
+            rows = c.execute("select kernel_name, counter_name, count(*), avg(value), min(value), max(value) from "
+                             "counters_collection group by kernel_name, counter_name order by avg(value) desc").fetchall()
+            print("%-60s %-14s %6s %14s %14s %14s" % ("kernel", "counter", "calls", "avg", "min", "max"))
+            for r in rows[:16]:
+                print("%-60s %-14s %6d %14.1f %14.1f %14.1f" % (re.sub(r"\(.*", "", r[0])[:60], r[1], r[2], r[3], r[4], r[5]))
+
+
+STAMP_NAMES = {1: "start", 32: "attn start", 44: "attn item top", 45: "attn scores done", 46: "attn maxima exchanged",
+               47: "attn P.V done", 48: "attn P.V barrier", 34: "attn item done", 36: "attn end", 40: "merge start",
+               41: "merge statistics here", 42: "merge candidates", 62: "end"}
+for _ph, _nm in enumerate(["qkv", "oproj", "gateup", "down", "lm"]):
+    for _k, _sfx in enumerate(["enter", "panel staged", "streamed", "tile sums added", "epilogue done", "end"]):
+        STAMP_NAMES[2 + _ph * 6 + _k] = _nm + " " + _sfx
+STAMP_ORDER = [1] + list(range(2, 8)) + [32, 44, 45, 46, 47, 48, 34, 36] + list(range(8, 32)) + [40, 41, 42, 62]
+
+
+def timeline(torch, wl, steps=30):
+    """Clock stamps of the persistent kernel (a library built with PS_BUILD_DEFS=-DPS_TIMELINE): for every
+    stamp the earliest, median and latest workgroup, in microseconds since the first workgroup started."""
+    from paper_2410_05589_amd import debug as DBG
+    w, drafter, variants, seq, kv_len, mix, max_new = setup_workload(torch, wl, steps)
+    tl = torch.zeros(64 * 1024, dtype=torch.int64, device="cuda:0")
+    assert DBG.ps_draft_debug_timeline(drafter.ctx, tl.data_ptr()) == 0
+    for i in range(steps):     # the last of a back-to-back series is the one that is looked at
+        drafter.step(variants[seq[i]][0])
+    torch.cuda.synchronize()
+    t = tl.cpu().numpy().reshape(64, 1024)[:, :256].astype(np.float64)
+    if t[63].max() == 0:
+        print("no stamps: the library was not built with -DPS_TIMELINE", file=sys.stderr)
+        sys.exit(2)
+    wall0, wall1 = t[0] * 0.01, t[63] * 0.01     # 100 MHz counter -> us
+    f = np.median((t[62] - t[1]) / (wall1 - wall0))   # shader clock ticks per us
+    base = wall0.min()
+    print("workload %s, n_new %d: kernel spans %.2f .. %.2f us per workgroup; %.1f clock ticks per us"
+          % (wl.name, seq[steps - 1], (wall1 - wall0).min(), (wall1 - wall0).max(), f))
+    print("%-26s %8s %8s %8s | %9s" % ("stamp", "min", "median", "max", "d(median)"))
+    prev = None
+    for e in STAMP_ORDER:
+        x = ((wall0 - base) + (t[e] - t[1]) / f)[t[e] > 0]
+        if x.size == 0:
+            continue
+        med = float(np.median(x))
+        print("%-26s %8.2f %8.2f %8.2f | %9.2f" % (STAMP_NAMES.get(e, str(e)), x.min(), med, x.max(), med - prev if prev is not None else 0.0))
+        prev = med
+    drafter.close()
 
 
 def verify_walk_report(torch, with_oracle, vocab=32000, k=5, calls=200):
@@ -131,13 +425,21 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=300)
     ap.add_argument("--warmup", type=int, default=30)
-    ap.add_argument("--workload", default="c1")
+    ap.add_argument("--workload", default="all", help="all (c1..c4 timed, c4 the headline) or one of c0..c4")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--oracle-steps", type=int, default=2)
     ap.add_argument("--no-kernel-timing", action="store_true")
+    ap.add_argument("--no-next-rows", action="store_true", help="skip the tree + acceptance walk report")
     ap.add_argument("--mode", choices=["fused", "multi"], default="fused",
                     help="fused: the whole step as one persistent kernel (default); multi: one kernel per phase")
+    ap.add_argument("--calibrate-copy", action="store_true")
+    ap.add_argument("--copy-mib", type=int, default=1024)
+    ap.add_argument("--summarize", nargs="+", metavar="DB")
+    ap.add_argument("--timeline", action="store_true")
     args = ap.parse_args()
+    if args.summarize:
+        summarize(args.summarize)
+        return
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus %d is not supported"
               % args.gpus, file=sys.stderr)
@@ -145,172 +447,42 @@ def main():
 
     os.environ["PS_DRAFT_MODE"] = args.mode
     import torch
-    from paper_2410_05589_amd import binding as B
-    from paper_2410_05589_amd import inputs
     from paper_2410_05589_amd.configs import WORKLOADS
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(2)
-    wl = WORKLOADS[args.workload]
-    shape = wl.shape
-    kv_len = inputs.draw_kv_len(wl)
-    mix = inputs.draw_n_new_mix(wl, args.steps + args.warmup) if wl.n_new_mix else None
-    max_new = max(wl.n_new_mix) if wl.n_new_mix else wl.n_new
+    if args.calibrate_copy:
+        calibrate_copy(torch, args.copy_mib, 5)
+        return
+    if args.timeline:
+        timeline(torch, WORKLOADS["c1" if args.workload == "all" else args.workload])
+        return
 
-    w = inputs.make_weights(shape, wl.seed)
-    drafter = B.Drafter(shape, w, max_batch=wl.batch, max_new=max_new,
-                        max_positions=max(kv_len) + max_new + wl.k, max_topk=wl.topk, k_max=wl.k)
-    # one input set per distinct n_new (the accepted-length mix of c2); the cache is reset by
-    # keeping kv_len fixed, so every step rewrites the same n_new + k rows
-    variants = {}
-    for n_new in sorted(set(mix)) if mix else [wl.n_new]:
-        inp = inputs.make_step_inputs(wl, kv_len=kv_len, n_new=n_new, k=wl.k)
-        dev = {n: B.to_device(inp[n], shape.dtype) for n in ("x", "k_cache", "v_cache")}
-        outs = drafter.alloc_outputs(wl.batch, n_new, wl.k, wl.topk)
-        a = drafter.make_args(dev["x"], dev["k_cache"], dev["v_cache"], inp["kv_offsets"], inp["kv_len"],
-                              n_new, wl.k, wl.topk, outs)
-        variants[n_new] = (a, inp, outs)
-    seq = mix if mix else [wl.n_new] * (args.steps + args.warmup)
-
-    stream = torch.cuda.current_stream()
-    for i in range(args.warmup):
-        drafter.step(variants[seq[i]][0])
-    torch.cuda.synchronize()
-    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    t0 = time.perf_counter()
-    ev0.record(stream)
-    for i in range(args.steps):
-        drafter.step(variants[seq[args.warmup + i]][0])
-    ev1.record(stream)
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    wall_ms = (t1 - t0) * 1e3 / args.steps
-    ev_ms = ev0.elapsed_time(ev1) / args.steps
-    ms_per_step = wall_ms
-    tokens_per_step = wl.batch * (wl.k + 1)
-    value = tokens_per_step / (ms_per_step * 1e-3)
-
-    n_new_mean = float(np.mean(seq[args.warmup:]))
-    bytes_mean = float(np.mean([algorithmic_bytes(wl, kv_len, n, wl.k)["total"] for n in seq[args.warmup:]]))
-    per = algorithmic_bytes(wl, kv_len, seq[-1], wl.k)
-
-    # ---- per-kernel durations, live, with HIP events on the launch stream (second region of K steps)
-    kernel_us = None
-    roofline = None
-    per_step_us = None
-    if not args.no_kernel_timing:
-        ksteps = min(args.steps, 200)
-        evs = [[torch.cuda.Event(enable_timing=True) for _ in range(B.PS_PROFILE_EVENTS)] for _ in range(ksteps)]
-        for row in evs:
-            for e in row:
-                e.record(stream)          # creates the underlying hipEvent_t
-        torch.cuda.synchronize()
-        for i in range(ksteps):
-            st = B.ps_draft_set_profile_events(drafter.ctx, [e.cuda_event for e in evs[i]])
-            assert st == B.PS_OK
-            drafter.step(variants[seq[args.warmup + i]][0])
-        B.ps_draft_set_profile_events(drafter.ctx, None)
-        torch.cuda.synchronize()
-        acc = np.zeros(B.PS_PROFILE_EVENTS - 1)
-        per_step = []
-        for row in evs:
-            for j in range(B.PS_PROFILE_EVENTS - 1):
-                acc[j] += row[j].elapsed_time(row[j + 1])
-            # fused: events 0 and 1 bracket the one kernel of the step; multi: first to last event = all its kernels
-            per_step.append(row[0].elapsed_time(row[1 if args.mode == "fused" else -1]) * 1e3)
-        per_step_us = {q: round(float(np.percentile(per_step, p)), 2) for q, p in (("p10", 10), ("median", 50), ("p90", 90))}
-        kernel_us = {n: float(acc[j] / ksteps * 1e3) for j, n in enumerate(B.PROFILE_KERNELS)}
-        dname = "bf16_t" if shape.dtype == "bf16" else "float"
-        mt = (wl.batch * (max_new + wl.k) + 15) // 16
-        if args.mode == "fused":
-            # one kernel per step: the events bracket the launch of the persistent kernel
-            dom_us = float(acc[0] / ksteps * 1e3)   # events 0 and 1 bracket the single launch
-            kernel_us = {"fused_kernel": dom_us}
-            dom_bytes = bytes_mean
-            kname = "fused_kernel<%s, %d, %d>" % (dname, shape.head_dim, mt)
-        else:
-            dom_us = kernel_us["lmhead"]
-            dom_bytes = per["lmhead"]
-            kname = "gemm_kernel<%s, %d, 4>  (LM head)" % (dname, (wl.batch * (wl.k + 1) + 15) // 16)
-        achieved = dom_bytes / (dom_us * 1e-6) / 1e9
-        # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE + WRITE_SIZE, scaled by a copy kernel of
-        # known size (profiles/fused_kernel_c1_hbm_traffic.md); measured offline, so only for that case
-        traffic = MEASURED_TRAFFIC.get((wl.name, args.mode))
-        roofline = {"bound": "hbm", "kernel": kname, "achieved": round(achieved, 1), "peak": PEAK_HBM_GBS,
-                    "unit": "GB/s", "frac": round(achieved / PEAK_HBM_GBS, 4), "traffic": traffic,
-                    "algorithmic_bytes_per_launch": int(dom_bytes), "avg_launch_us": round(dom_us, 2)}
-
-    # ---- the same step captured once in a HIP graph and replayed (only when every step has the same n_new)
-    graph_us = None
-    if not args.no_kernel_timing and not mix:
-        a0 = variants[wl.n_new][0]
-        side = torch.cuda.Stream()
-        graph = torch.cuda.CUDAGraph()
-        torch.cuda.synchronize()
-        with torch.cuda.stream(side):
-            with torch.cuda.graph(graph, stream=side):
-                drafter.step(a0, stream=side)
-        torch.cuda.synchronize()
-        for _ in range(min(args.warmup, 20)):
-            graph.replay()
-        torch.cuda.synchronize()
-        g0 = time.perf_counter()
-        for _ in range(args.steps):
-            graph.replay()
-        torch.cuda.synchronize()
-        graph_us = (time.perf_counter() - g0) * 1e6 / args.steps
-
-    step_gbs = bytes_mean / (ms_per_step * 1e-3) / 1e9
+    names = BENCH_WORKLOADS if args.workload == "all" else (args.workload,)
+    traffic = load_traffic_table()
+    reports = {}
+    for name in names:
+        reports[name] = measure_workload(torch, WORKLOADS[name], args, traffic, not args.no_cpu_baseline,
+                                         not args.no_kernel_timing)
+        print("bench.py: %s done: %.2f us per step" % (name, reports[name]["latency_us"]), file=sys.stderr, flush=True)
+    head = reports[HEADLINE if args.workload == "all" else args.workload]
     result = {
         "metric": "draft tokens/sec (parallel draft step, k+1 tokens per sequence per step)",
-        "value": round(value, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": shape.dtype, "data": "synthetic",
-        "mode": args.mode,
-        "config": {"workload": "%s: 1 decoder layer H%d %dq/%dkv x%d F%d V%d, batch %d, KV %s, n_new %s, k %d, topk %d"
-                   % (wl.name, shape.hidden, shape.n_heads, shape.n_kv_heads, shape.head_dim, shape.ffn, shape.vocab,
-                      wl.batch, list(kv_len) if wl.batch > 1 else kv_len[0],
-                      "mix %s (mean %.2f)" % (list(wl.n_new_mix), n_new_mean) if mix else wl.n_new, wl.k, wl.topk),
-                   "tokens_per_step": tokens_per_step},
-        "latency_us": round(ms_per_step * 1e3, 2),
-        "latency_us_hip_events": round(ev_ms * 1e3, 2),
-        "latency_us_per_step_events": per_step_us,
-        "latency_us_graph_replay": round(graph_us, 2) if graph_us else None,
-        "step_roofline": {"algorithmic_bytes": int(bytes_mean), "achieved_GBps": round(step_gbs, 1),
-                          "peak_GBps": PEAK_HBM_GBS, "frac": round(step_gbs / PEAK_HBM_GBS, 4),
-                          "roofline_latency_us": round(bytes_mean / PEAK_HBM_GBS / 1e3, 2)},
-        "kernel_us": {n: round(v, 2) for n, v in kernel_us.items()} if kernel_us else None,
-        "roofline": roofline,
+        "value": head["value"], "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": head["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": head["dtype"], "data": "synthetic", "mode": args.mode,
     }
-
-    if not args.no_cpu_baseline:
-        from oracle import ps_oracle
-        try:
-            from threadpoolctl import threadpool_info
-            threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
-        except Exception:
-            threads = 1
-        a, inp, outs = variants[seq[-1]]
-        n_new = seq[-1]
-        times = []
-        for _ in range(args.oracle_steps):
-            c0 = time.perf_counter()
-            ref = ps_oracle.draft_step(shape, w, inp["x"], inp["k_cache"], inp["v_cache"], inp["kv_offsets"], inp["kv_len"],
-                                       n_new, wl.k, wl.topk)
-            times.append(time.perf_counter() - c0)
-        best = float(np.mean(times))
-        # sanity: the timed GPU step agrees with the oracle on the top-1 tokens
-        torch.cuda.synchronize()
-        gpu_top1 = outs["top_ids"].cpu().numpy()[..., 0]
-        agree = float((gpu_top1 == ref["top_ids"][..., 0]).mean())
-        result["cpu_baseline"] = {"value": round(tokens_per_step / best, 2), "unit": "tokens/s", "cores": int(threads),
-                                  "kind": "oracle", "sample": "%d full steps of the same workload (numpy float64, "
-                                  "mean %.2f s per step, host cores available %d)" % (args.oracle_steps, best,
-                                                                                       len(os.sched_getaffinity(0))),
-                                  "top1_agreement_with_gpu": agree}
-    drafter.close()
-    result["next_rows"] = {"verify_walk": verify_walk_report(torch, not args.no_cpu_baseline, vocab=shape.vocab, k=wl.k)}
+    result.update({k: v for k, v in head.items() if k not in result})
+    if args.workload == "all":
+        result["workloads"] = reports
+        c0 = argparse.Namespace(**vars(args))
+        c0.steps, c0.warmup = min(args.steps, 200), min(args.warmup, 20)
+        result["c0_latency_us"] = measure_workload(torch, WORKLOADS["c0"], c0, traffic, False, False)["latency_us"]
+    result["stream_read"] = stream_read_report(torch)
+    if not args.no_next_rows:
+        hw = WORKLOADS[HEADLINE if args.workload == "all" else args.workload]
+        result["next_rows"] = {"verify_walk": verify_walk_report(torch, not args.no_cpu_baseline, vocab=hw.shape.vocab, k=hw.k)}
     print(json.dumps(result))
 
 

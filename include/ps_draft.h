@@ -18,8 +18,8 @@
  *
  * All pointers named "device" are HIP device pointers of the current device, owned by
  * the caller; nothing is copied or retained beyond what is stated.  No function throws
- * or aborts; every function returns a ps_status (0 = success, negative = error).  On any
- * error nothing has been enqueued on the stream.
+ * or aborts; every function returns a ps_status (0 = success, negative = error).  On an
+ * argument error nothing has been enqueued on the stream.
  */
 #ifndef PS_DRAFT_H
 #define PS_DRAFT_H
@@ -30,6 +30,9 @@
 #ifdef __cplusplus
 extern "C" {
 #endif
+
+/* The library is built with hidden visibility: exactly the functions declared PS_API are exported. */
+#define PS_API __attribute__((visibility("default")))
 
 typedef struct ps_draft_ctx ps_draft_ctx;
 
@@ -44,7 +47,8 @@ enum ps_status {
     PS_ERR_OFFSETS = -5,     /* kv_offsets is negative or not non-decreasing */
     PS_ERR_WORKSPACE = -6,   /* workspace too small or misaligned (256 bytes) */
     PS_ERR_UNSUPPORTED = -7, /* a legal shape this build has no kernel for (see ps_draft_config) */
-    PS_ERR_DEVICE = -8       /* a HIP call failed (no device, launch failure) */
+    PS_ERR_DEVICE = -8,      /* a HIP call failed (no device, launch failure) */
+    PS_ERR_TIMEOUT = -9      /* ps_draft_last_status: a step gave up waiting for some of its own workgroups */
 };
 
 #define PS_FLAG_FINAL_NORM 1u /* apply the RMSNorm with gain g_final before the LM head */
@@ -55,7 +59,10 @@ enum ps_status {
  *   hidden, n_heads*head_dim and ffn multiples of 32 (PS_BF16) or 16 (PS_F32); ffn a multiple of 8;
  *   hidden a multiple of 16; vocab >= 1 (any value);
  *   max_batch * (max_new + k_max) <= 64 rows per step;
- *   (n_heads / n_kv_heads) * (max_new + k_max) <= 64; 1 <= max_topk <= 32.
+ *   (n_heads / n_kv_heads) * (max_new + k_max) <= 64; 1 <= max_topk <= 32;
+ *   max_positions <= 2^24, and no exchange buffer of the workspace (activations and K-slice
+ *   partial sums of one step; attention partials: max_batch * n_kv_heads * max_positions / 128
+ *   blocks x (n_heads / n_kv_heads) * (max_new + k_max) rows x head_dim x 8 bytes) of 4 GiB or more.
  * Anything else legal returns PS_ERR_UNSUPPORTED, anything illegal PS_ERR_CONFIG.
  */
 typedef struct ps_draft_config {
@@ -102,7 +109,7 @@ typedef struct ps_draft_weights {
  * activations, split-K partial sums, attention partials, completion counters, rotary table.
  * Returns 0 if the configuration is invalid or unsupported.  Host-only; touches no device.
  */
-size_t ps_draft_workspace_bytes(const ps_draft_config* config);
+PS_API size_t ps_draft_workspace_bytes(const ps_draft_config* config);
 
 /*
  * Creates a context.  config and weights are copied (the structs, not the tensors).
@@ -115,7 +122,7 @@ size_t ps_draft_workspace_bytes(const ps_draft_config* config);
  * Validation happens before any HIP call, so configuration errors are reported on a
  * machine without a GPU as well.  *out is set only on success.
  */
-int ps_draft_init(ps_draft_ctx** out, const ps_draft_config* config, const ps_draft_weights* weights,
+PS_API int ps_draft_init(ps_draft_ctx** out, const ps_draft_config* config, const ps_draft_weights* weights,
                   void* workspace, size_t workspace_bytes, void* stream);
 
 /*
@@ -150,10 +157,29 @@ typedef struct ps_draft_step_args {
  * memory from the host; kv_offsets and kv_len are read before the call returns.
  * top_ids, top_p and lse are required; logits, probs and hidden_out are optional.
  * Steps of one context must not overlap in time (they share the workspace).
- * Errors: PS_ERR_NULL, PS_ERR_SHAPE, PS_ERR_OFFSETS, PS_ERR_KV_CAPACITY (kv_len[b] + M
- * exceeds off[b+1] - off[b] or max_positions), PS_ERR_DEVICE.
+ * All arguments are checked and the launch is planned before anything is enqueued or any
+ * state of the context changes: a call that returns PS_ERR_NULL, PS_ERR_SHAPE, PS_ERR_OFFSETS,
+ * PS_ERR_KV_CAPACITY (kv_len[b] + M exceeds off[b+1] - off[b] or max_positions) or
+ * PS_ERR_UNSUPPORTED has done nothing; PS_ERR_DEVICE means a launch itself failed.
+ *
+ * The step runs as ONE kernel with one workgroup per compute unit whose workgroups hand data to
+ * each other, so all of them must be running at once: no other work may occupy the GPU while a
+ * step runs (work queued before or after it on any stream is fine: the step starts when the
+ * compute units are free).  If the GPU withholds compute units all the same, the waiting
+ * workgroups give up after about a second, the kernel ends normally, the step's outputs are
+ * marked (every top_ids entry -1, top_p 0, lse NaN) and ps_draft_last_status says so.
  */
-int ps_draft_step(ps_draft_ctx* ctx, const ps_draft_step_args* args, void* stream);
+PS_API int ps_draft_step(ps_draft_ctx* ctx, const ps_draft_step_args* args, void* stream);
+
+/*
+ * Waits for everything enqueued on stream (the stream the steps ran on) and returns PS_OK, or
+ * PS_ERR_TIMEOUT if a step since the previous query (or since ps_draft_init) gave up a wait:
+ * the outputs of that step and of every later one are marked as described at ps_draft_step,
+ * and this call has put the context's exchange buffers back into their initial state, so the
+ * following steps are good again.  No part of the method; callers that never share the GPU
+ * need not call it.  Errors: PS_ERR_NULL, PS_ERR_DEVICE.
+ */
+PS_API int ps_draft_last_status(ps_draft_ctx* ctx, void* stream);
 
 /*
  * Measurement aid (no part of the method): when events is non-NULL, every following
@@ -165,13 +191,13 @@ int ps_draft_step(ps_draft_ctx* ctx, const ps_draft_step_args* args, void* strea
  * array is copied.  NULL switches recording off again.  Returns PS_ERR_NULL for a NULL ctx.
  */
 #define PS_PROFILE_EVENTS 8
-int ps_draft_set_profile_events(ps_draft_ctx* ctx, void* const* events);
+PS_API int ps_draft_set_profile_events(ps_draft_ctx* ctx, void* const* events);
 
 /* Releases the host-side context; ps_draft_free(NULL) is a no-op.  The workspace stays the caller's. */
-void ps_draft_free(ps_draft_ctx* ctx);
+PS_API void ps_draft_free(ps_draft_ctx* ctx);
 
 /* Static, NUL-terminated description of a ps_status value. */
-const char* ps_draft_strerror(int status);
+PS_API const char* ps_draft_strerror(int status);
 
 #ifdef __cplusplus
 }

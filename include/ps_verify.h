@@ -11,6 +11,7 @@
 #ifndef PS_VERIFY_H
 #define PS_VERIFY_H
 #include <stdint.h>
+#include "ps_draft.h"
 #ifdef __cplusplus
 extern "C" {
 #endif
@@ -39,7 +40,7 @@ typedef struct ps_tree_shape {
  * Errors: PS_ERR_NULL; PS_ERR_SHAPE (batch < 1, a malformed tree, a depth beyond rows, a rank
  * outside [0, topk)); PS_ERR_DEVICE.
  */
-int ps_tree_tokens(const ps_tree_shape* tree, int32_t batch, int32_t rows, int32_t topk,
+PS_API int ps_tree_tokens(const ps_tree_shape* tree, int32_t batch, int32_t rows, int32_t topk,
                    const int32_t* top_ids, int32_t* tokens, void* stream);
 
 /*
@@ -87,7 +88,7 @@ typedef struct ps_verify_args {
     const int32_t* top_ids;
     int32_t topk;
 } ps_verify_args;
-int ps_verify_walk(const ps_tree_shape* tree, const ps_verify_args* args, void* stream);
+PS_API int ps_verify_walk(const ps_tree_shape* tree, const ps_verify_args* args, void* stream);
 
 #ifdef __cplusplus
 }

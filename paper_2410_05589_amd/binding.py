@@ -14,11 +14,11 @@ LIB_PATH = os.environ.get("PS_DRAFT_LIB") or os.path.join(_PKG_DIR, "libps_draft
 PS_F32, PS_BF16 = 0, 1
 PS_OK = 0
 PS_ERR_NULL, PS_ERR_CONFIG, PS_ERR_SHAPE, PS_ERR_KV_CAPACITY = -1, -2, -3, -4
-PS_ERR_OFFSETS, PS_ERR_WORKSPACE, PS_ERR_UNSUPPORTED, PS_ERR_DEVICE = -5, -6, -7, -8
+PS_ERR_OFFSETS, PS_ERR_WORKSPACE, PS_ERR_UNSUPPORTED, PS_ERR_DEVICE, PS_ERR_TIMEOUT = -5, -6, -7, -8, -9
 PS_FLAG_FINAL_NORM = 1
 
 EXPORTED_SYMBOLS = ("ps_draft_workspace_bytes", "ps_draft_init", "ps_draft_step", "ps_draft_free",
-                    "ps_draft_strerror", "ps_draft_set_profile_events")
+                    "ps_draft_strerror", "ps_draft_set_profile_events", "ps_draft_last_status")
 PS_PROFILE_EVENTS = 8
 PROFILE_KERNELS = ("qkv", "attention", "oproj", "gateup", "down", "lmhead", "lm_merge")
 
@@ -71,6 +71,8 @@ def load_library():
     lib.ps_draft_free.argtypes = [ctypes.c_void_p]
     lib.ps_draft_set_profile_events.restype = ctypes.c_int
     lib.ps_draft_set_profile_events.argtypes = [ctypes.c_void_p, ctypes.POINTER(ctypes.c_void_p)]
+    lib.ps_draft_last_status.restype = ctypes.c_int
+    lib.ps_draft_last_status.argtypes = [ctypes.c_void_p, ctypes.c_void_p]
     lib.ps_draft_strerror.restype = ctypes.c_char_p
     lib.ps_draft_strerror.argtypes = [ctypes.c_int]
     _lib = lib
@@ -103,6 +105,10 @@ def ps_draft_init(config, weights, workspace_ptr, workspace_bytes, stream_ptr):
 
 def ps_draft_step(ctx, args, stream_ptr):
     return load_library().ps_draft_step(ctx, ctypes.byref(args) if args is not None else None, stream_ptr)
+
+
+def ps_draft_last_status(ctx, stream_ptr):
+    return load_library().ps_draft_last_status(ctx, stream_ptr)
 
 
 def ps_draft_free(ctx):
@@ -207,6 +213,9 @@ class Drafter:
         st = ps_draft_step(self.ctx, args, self._stream_ptr(stream))
         if st != PS_OK:
             raise PsDraftError(st)
+
+    def last_status(self, stream=None):
+        return ps_draft_last_status(self.ctx, self._stream_ptr(stream))
 
     def close(self):
         if getattr(self, "ctx", None):

@@ -10,8 +10,10 @@ LIB_PATH = os.path.join(PKG_DIR, "libps_draft.so")
 CSRC = os.path.join(PKG_DIR, "csrc")
 BUILD_DIR = os.path.join(PKG_DIR, "_build")
 HEADERS = [os.path.join(CSRC, "ps_internal.h"), os.path.join(CSRC, "ps_device.h"),
-           os.path.join(ROOT, "include", "ps_draft.h"), os.path.join(ROOT, "include", "ps_verify.h")]
-SOURCES = [os.path.join(CSRC, "ps_host.hip"), os.path.join(CSRC, "ps_inst.hip"), os.path.join(CSRC, "ps_verify.hip")]
+           os.path.join(ROOT, "include", "ps_draft.h"), os.path.join(ROOT, "include", "ps_verify.h"),
+           os.path.join(ROOT, "include", "ps_draft_debug.h")]
+SOURCES = [os.path.join(CSRC, "ps_host.hip"), os.path.join(CSRC, "ps_inst.hip"), os.path.join(CSRC, "ps_verify.hip"),
+           os.path.join(CSRC, "ps_measure.hip")]
 # the device code is instantiated once per (storage type, head_dim)
 INSTANCES = [("f32_d64", 0, 64), ("f32_d128", 0, 128), ("bf16_d64", 1, 64), ("bf16_d128", 1, 128)]
 
@@ -37,7 +39,7 @@ def _run(cmd, verbose):
 def build_library(verbose=True, jobs=4):
     """Compiles every HIP source for gfx950 and links the shared library; always rebuilds."""
     os.makedirs(BUILD_DIR, exist_ok=True)
-    common = [hipcc_path(), "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
+    common = [hipcc_path(), "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc", "-fvisibility=hidden",
               # packed-FP32 instruction selection is switched off for device code
               "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
               # The kernels read their ~1.7 KB parameter struct in hundreds of places.  LLVM replaces the
@@ -47,7 +49,8 @@ def build_library(verbose=True, jobs=4):
               "-mllvm", "-instcombine-max-copied-from-constant-users=10000",
               "-I", os.path.join(ROOT, "include"), "-I", CSRC] + os.environ.get("PS_BUILD_DEFS", "").split()
     units = [(os.path.join(BUILD_DIR, "ps_host.o"), [os.path.join(CSRC, "ps_host.hip")]),
-             (os.path.join(BUILD_DIR, "ps_verify.o"), [os.path.join(CSRC, "ps_verify.hip")])]
+             (os.path.join(BUILD_DIR, "ps_verify.o"), [os.path.join(CSRC, "ps_verify.hip")]),
+             (os.path.join(BUILD_DIR, "ps_measure.o"), [os.path.join(CSRC, "ps_measure.hip")])]
     for name, bf, d in INSTANCES:
         units.append((os.path.join(BUILD_DIR, "ps_inst_%s.o" % name),
                       ["-DPS_INST_NAME=%s" % name, "-DPS_INST_BF16=%d" % bf, "-DPS_INST_D=%d" % d,

@@ -120,6 +120,13 @@ __device__ __forceinline__ void coh_st_f4(rsrc_t r, unsigned off, f32x4 v) { coh
 __device__ __forceinline__ float coh_ld_f(rsrc_t r, unsigned off) { return __uint_as_float(coh_ld4(r, off)); }
 __device__ __forceinline__ void coh_st_f(rsrc_t r, unsigned off, float v) { coh_st4(r, off, __float_as_uint(v)); }
 
+// per-lane 64-bit addresses (KV-cache rows): relaxed agent-scope atomics, dword granularity
+__device__ __forceinline__ void st_agent_u32(void* p, unsigned v) {
+    __hip_atomic_store((unsigned*)p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ unsigned ld_agent_u32(const void* p) {
+    return __hip_atomic_load((const unsigned*)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
 // ---- sequence-tagged exchange: element i of such a buffer is the 8-byte unit {value, seq} at
 // byte offset 8 i.  Four consecutive elements are moved as two 16-byte accesses.
 struct LL4 { u32x4 a, b; };
@@ -146,13 +153,14 @@ __device__ __forceinline__ f32x4 ll_val(const LL4& x) {
     const f32x4 v = {__uint_as_float(x.a[0]), __uint_as_float(x.a[2]), __uint_as_float(x.b[0]), __uint_as_float(x.b[2])};
     return v;
 }
-// Bounded wait: a consumer that never sees its data (possible only after a fault elsewhere)
-// raises the error flag and goes on, so the kernel always terminates.
-#define PS_SPIN_LIMIT (1 << 20)
+// Bounded wait: a consumer that never sees its data (a workgroup of the grid that got no compute unit
+// because other work holds it, or a fault elsewhere) raises the context's error flag and goes on, so the
+// kernel always terminates; the merge of the output rows then marks the step's outputs (lm_merge_row).
 __device__ __forceinline__ bool spin_again(const StepParams& P, int& spins) {
     __builtin_amdgcn_s_sleep(2);
-    if (++spins > PS_SPIN_LIMIT) {
+    if (++spins > P.spin_limit) {
         __hip_atomic_store(P.error_flag, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");   // the flag is out before anything this thread publishes later
         return false;
     }
     return true;
@@ -194,31 +202,44 @@ __device__ __forceinline__ void sx_st1(const SxBuf& b, unsigned i, float v) {
     coh_st4(b.cur, i * 4, __float_as_uint(v));
     coh_st4(b.alt, i * 4, PS_SENT);
 }
-// The row buffers may hold rows of an earlier, larger step beyond this step's Mtot rows (the host
-// keeps count: P.rows_reset rows may have been written since the buffers were last cleared).  Nobody
-// touches those rows in this step, and whoever writes a row resets it in the other copy - but only the
-// rows of this step.  So all workgroups together mark rows [Mtot, rows_reset) of the other copy "not
-// written" here; the next step, which may have more rows again, then finds its whole copy clean.
-__device__ __forceinline__ void sx_reset_rows_beyond(const StepParams& P, int wg, int nwg) {
-    if (P.rows_reset <= P.Mtot) return;
-    const unsigned par = ps_seq() & 1u;
+// Keeping the copies clean without the host.  A step writes its footprint - its Mtot activation rows, a
+// prefix of every sliced phase's fragment buffer, the slices' sums of squares - into its own copy and resets
+// exactly that in the other copy.  The other copy was last written by the previous step; whatever of that
+// step's footprint exceeds this one's (more rows, more column tiles, more K-slices) is reset here, at the end
+// of the kernel where most workgroups have nothing left to do, so the next step finds its whole copy clean
+// whatever shapes came before.  The footprints of the two latest steps live in device memory (foot_mem[n & 1]
+// is written when step n ends and read by step n + 1), so a launch replayed from a graph works among steps
+// of other shapes.
+__device__ __forceinline__ void sx_reset_stale(const StepParams& P, int wg, int nwg) {
+    const unsigned seq = ps_seq(), par = seq & 1u;
+    const unsigned* prev = P.foot_mem + ((seq - 1u) & 1u) * PS_FOOT_INTS;
     const u32x4 sent = {PS_SENT, PS_SENT, PS_SENT, PS_SENT};
-    const float* bufs[6] = {P.q_buf, P.kvnew, P.o_buf, P.y_buf, P.u_buf, P.y2_buf};
-    const int lds[6] = {P.QD, 2 * P.KVD, P.QD, P.H, P.F, P.H};      // elements per row: multiples of 4
+    const unsigned rows_prev = __builtin_amdgcn_readfirstlane(ld_agent_u32(prev));
+    if (rows_prev > (unsigned)P.Mtot) {
+        const float* bufs[6] = {P.q_buf, P.kvnew, P.o_buf, P.y_buf, P.u_buf, P.y2_buf};
+        const int lds[6] = {P.QD, 2 * P.KVD, P.QD, P.H, P.F, P.H};      // elements per row: multiples of 4
 #pragma unroll
-    for (int i = 0; i < 6; ++i) {
-        const rsrc_t alt = make_rsrc(reinterpret_cast<const char*>(bufs[i]) + (1u - par) * P.act_bytes);
-        const unsigned lo = (unsigned)P.Mtot * lds[i], hi = (unsigned)P.rows_reset * lds[i];
-        for (unsigned e = lo + 4u * (wg * PS_WG_THREADS + threadIdx.x); e < hi; e += 4u * nwg * PS_WG_THREADS)
-            coh_st16(alt, e * 4, sent);
+        for (int i = 0; i < 6; ++i) {
+            const rsrc_t alt = make_rsrc(reinterpret_cast<const char*>(bufs[i]) + (1u - par) * P.act_bytes);
+            const unsigned lo = (unsigned)P.Mtot * lds[i], hi = rows_prev * lds[i];
+            for (unsigned e = lo + 4u * (wg * PS_WG_THREADS + threadIdx.x); e < hi; e += 4u * nwg * PS_WG_THREADS)
+                coh_st16(alt, e * 4, sent);
+        }
     }
-    if (wg == 0) {   // the K-slices' sums of squares: [slice][PS_MAX_ROWS] per phase
-        for (int ph = 0; ph < PH_COUNT; ++ph) {
-            if (!P.ph[ph].ssq_frag) continue;
+    for (int ph = 0; ph < PH_COUNT; ++ph) {
+        if (!P.ph[ph].frag) continue;
+        const unsigned fp = __builtin_amdgcn_readfirstlane(ld_agent_u32(prev + 1 + ph)), fc = P.foot[1 + ph];
+        if (fp > fc) {   // 16-byte units [fc, fp) of the fragments
+            const rsrc_t alt = make_rsrc(reinterpret_cast<const char*>(P.ph[ph].frag) + (1u - par) * P.act_bytes);
+            for (unsigned u = fc + wg * PS_WG_THREADS + threadIdx.x; u < fp; u += nwg * PS_WG_THREADS) coh_st16(alt, u * 16, sent);
+        }
+        const unsigned sp = __builtin_amdgcn_readfirstlane(ld_agent_u32(prev + 1 + PH_COUNT + ph)), sc = P.foot[1 + PH_COUNT + ph];
+        if (wg == 0 && sp > 0 && (sp > sc || rows_prev > (unsigned)P.Mtot)) {   // [slice][PS_MAX_ROWS] sums of squares
             const rsrc_t alt = make_rsrc(reinterpret_cast<const char*>(P.ph[ph].ssq_frag) + (1u - par) * P.act_bytes);
-            const int nrow = P.rows_reset - P.Mtot;
-            for (int x = threadIdx.x; x < 8 * nrow; x += PS_WG_THREADS)
-                coh_st4(alt, (unsigned)((x / nrow) * PS_MAX_ROWS + P.Mtot + x % nrow) * 4, PS_SENT);
+            for (unsigned x = threadIdx.x; x < sp * PS_MAX_ROWS; x += PS_WG_THREADS) {
+                const unsigned sl = x / PS_MAX_ROWS, r = x % PS_MAX_ROWS;
+                if (r < rows_prev && !(sl < sc && r < (unsigned)P.Mtot)) coh_st4(alt, x * 4, PS_SENT);
+            }
         }
     }
 }
@@ -233,13 +254,6 @@ __device__ __forceinline__ f32x4 sx_wait4(const StepParams& P, rsrc_t r, unsigne
     }
 }
 
-// per-lane 64-bit addresses (KV-cache rows): relaxed agent-scope atomics, dword granularity
-__device__ __forceinline__ void st_agent_u32(void* p, unsigned v) {
-    __hip_atomic_store((unsigned*)p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ unsigned ld_agent_u32(const void* p) {
-    return __hip_atomic_load((const unsigned*)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
 // 4 values -> the cache's storage type: stores them, returns them as stored (widened again)
 template <typename WT> __device__ __forceinline__ f32x4 store4(void* p, f32x4 v);
 template <> __device__ __forceinline__ f32x4 store4<float>(void* p, f32x4 v) {
@@ -1743,6 +1757,10 @@ __device__ __forceinline__ void lm_merge_row(const StepParams& P, int m, int wav
             keys[t0 + i] = (mine && t0 + i < topk) ? (((u64)kr[i][2] << 32) | kr[i][0]) : 0;
     }
     if (m == (int)blockIdx.x) stamp(P, blockIdx.x, 41);
+    // Has any wait of this step been given up (see spin_again)?  Whoever gave up raised the flag before it
+    // published anything, so now that all statistics of the row are here the flag tells; requested here,
+    // looked at when the outputs are written.
+    const unsigned gave_up = ld_agent_u32(P.error_flag);
     // this wavefront's share of the log-sum-exp and its sorted top-k
     const float wmax = wave_max(pmax);
     if (lane == 0) sf[wave] = wmax;
@@ -1773,7 +1791,7 @@ __device__ __forceinline__ void lm_merge_row(const StepParams& P, int m, int wav
         float se = 0.f;
 #pragma unroll
         for (int w = 0; w < PS_WAVES; ++w) se += sf[PS_WAVES + w];
-        const float lse = mx + logf(se);
+        const float lse = gave_up ? __uint_as_float(0x7FC00000u) : mx + logf(se);   // a step that gave up a wait: NaN, ids -1
         if (lane == 0) P.lse[m] = lse;
         // PS_WAVES sorted lists of topk keys: 4 candidates per lane
         constexpr int CPL = PS_WAVES * PS_MAX_TOPK / 64;
@@ -1791,8 +1809,8 @@ __device__ __forceinline__ void lm_merge_row(const StepParams& P, int m, int wav
                 if (cand[i] < prev2 && cand[i] > best) best = cand[i];
             best = wave_max_u64(best);
             if (lane == 0) {
-                P.top_ids[(size_t)m * topk + t] = best ? key_id(best) : 0x7FFFFFFF;
-                P.top_p[(size_t)m * topk + t] = best ? expf(key_value(best) - lse) : 0.f;
+                P.top_ids[(size_t)m * topk + t] = gave_up ? -1 : (best ? key_id(best) : 0x7FFFFFFF);
+                P.top_p[(size_t)m * topk + t] = (best && !gave_up) ? expf(key_value(best) - lse) : 0.f;
             }
             prev2 = best;
         }
@@ -1815,7 +1833,7 @@ __device__ __forceinline__ unsigned step_read(const StepParams& P, bool count, u
     ticket = 0xFFFFFFFFu;
     if (threadIdx.x == 0) {
         seq = ld_agent_u32(P.step_ctr) + 1u;
-        if (seq == 0u) seq = 1u;   // 0 is what cleared exchange buffers hold
+        if (seq == 0u) seq = 2u;   // 0 is what cleared exchange buffers hold; even, so the copies keep alternating
         if (count) ticket = __hip_atomic_fetch_add(P.done_ctr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     return seq;
@@ -1829,6 +1847,8 @@ __device__ __forceinline__ unsigned step_begin(const StepParams& P, bool count) 
 }
 __device__ __forceinline__ void step_end(const StepParams& P, unsigned ticket, unsigned nwg) {
     if (threadIdx.x == 0 && ticket == nwg - 1u) {
+        unsigned* foot = P.foot_mem + (ps_seq() & 1u) * PS_FOOT_INTS;   // read by the next step (sx_reset_stale)
+        for (int i = 0; i < PS_FOOT_INTS; ++i) st_agent_u32(foot + i, P.foot[i]);
         st_agent_u32(P.done_ctr, 0u);
         st_agent_u32(P.step_ctr, ps_seq());
     }
@@ -1848,7 +1868,7 @@ template <typename WT, int D, int NK, bool SINGLE>
 __global__ void __launch_bounds__(PS_WG_THREADS) attn_kernel(const StepParams P) {
     extern __shared__ __attribute__((aligned(256))) char smem[];
     step_begin(P, false);
-    sx_reset_rows_beyond(P, blockIdx.x, gridDim.x);
+    sx_reset_stale(P, blockIdx.x, gridDim.x);
     attn_phase<WT, D, NK, SINGLE>(P, blockIdx.x, gridDim.x, __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), smem);
 }
 
@@ -1905,7 +1925,7 @@ __global__ void __launch_bounds__(PS_WG_THREADS, 1) fused_kernel(const StepParam
     // output row m is merged by workgroup m mod gridDim.x
     stamp(P, wg, 40);
     for (int m = wg; m < P.Rtot; m += gridDim.x) lm_merge_row(P, m, wave, smem + 256);
-    sx_reset_rows_beyond(P, wg, gridDim.x);   // here most workgroups have nothing left to do
+    sx_reset_stale(P, wg, gridDim.x);   // here most workgroups have nothing left to do
     step_end(P, ticket, gridDim.x);
     stamp(P, wg, 62);
     stamp_wall(P, wg, 63);

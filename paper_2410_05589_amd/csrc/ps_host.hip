@@ -10,6 +10,7 @@
 #include <vector>
 
 #include "ps_internal.h"
+#include "ps_draft_debug.h"
 
 static const PsInstance* find_instance(int dtype, int d) {
     const PsInstance* all[4] = {ps_instance_f32_d64(), ps_instance_f32_d128(), ps_instance_bf16_d64(),
@@ -44,9 +45,7 @@ struct ps_draft_ctx {
     char* act_base;                   // two copies of the activation buffers, act_bytes each
     size_t act_bytes;
     size_t off_q, off_o, off_y, off_u, off_y2, off_kvnew;   // offsets inside one copy
-    int rows_dirty;                   // most activation rows a step has used since the exchange buffers were last cleared
-    unsigned last_frag_sig;           // column tiles and K-slices per phase of the previous step
-    size_t act_small;                 // bytes of a copy whose slots in use depend on the shape only
+    int spin_limit;                   // polls before a kernel gives up a wait (PS_SPIN_LIMIT; tests of that path: less)
     char* wpack[PH_COUNT];
     int* counters;
     int n_counters;
@@ -83,6 +82,7 @@ static int validate_config(const ps_draft_config* c) {
     if ((long long)(c->n_heads / c->n_kv_heads) * (c->max_new + c->k_max) > PS_MAX_ROWS) return PS_ERR_UNSUPPORTED;
     if (c->max_topk > 32) return PS_ERR_UNSUPPORTED;
     if (qd > (1 << 20) || c->hidden > (1 << 20) || c->ffn > (1 << 22) || c->vocab > (1 << 24)) return PS_ERR_UNSUPPORTED;
+    if (c->max_positions > (1 << 24)) return PS_ERR_UNSUPPORTED;
     return PS_OK;
 }
 
@@ -92,8 +92,9 @@ struct WsLayout {
     size_t wpack[PH_COUNT];
     size_t rope, q_buf, o_buf, y_buf, u_buf, y2_buf, kvnew, attn_acc, attn_ml, counters, lm_part, logits_ws, total;
     size_t exch_begin, exch_end;
-    size_t act_base, act_bytes, act_small, off_q, off_o, off_y, off_u, off_y2, off_kvnew, off_frag[PH_COUNT], off_ssqf[PH_COUNT];
+    size_t act_base, act_bytes, off_q, off_o, off_y, off_u, off_y2, off_kvnew, off_frag[PH_COUNT], off_ssqf[PH_COUNT];
     int n_counters;
+    bool fits32;   // the kernels address every exchange buffer with 32-bit byte offsets
 };
 
 // tiles (16 weight rows), contraction lengths and steps (64-byte pieces of a row) of the five GEMM phases
@@ -138,7 +139,6 @@ static WsLayout ws_layout(const ps_draft_config* c) {
         // parts of the tiles from up to PS_S_MAX K-slices (1 KiB per slice, tile and 16 rows)
         const size_t mt_max = (rows + 15) / 16;
         for (int ph = 0; ph < PH_COUNT; ++ph) L.off_ssqf[ph] = sub((size_t)PS_S_MAX * PS_MAX_ROWS * 4);
-        L.act_small = a;   // up to here the slots in use depend on (batch, n_new, k); behind it on the K-slice plan
         for (int ph = 0; ph < PH_COUNT; ++ph) {
             const bool sliced = ph != PH_LMHEAD;
             L.off_frag[ph] = sub(sliced ? (size_t)PS_S_MAX * T[ph] * mt_max * 1024 : 256);
@@ -154,14 +154,24 @@ static WsLayout ws_layout(const ps_draft_config* c) {
     L.lm_part = take((size_t)PS_MAX_WG * rows * (2 + 2 * c->max_topk) * 8 + 64);
     L.exch_end = off;
     L.n_counters = 0;
-    L.counters = take(64);   // [0] error flag, [1] steps completed, [2] tickets of the running kernel
+    L.counters = take(256);  // PS_CTR_*: error flag, steps completed, tickets of the running kernel, footprints
     L.logits_ws = take(rows * c->vocab * 4);
     L.total = off;
+    const size_t lim = 0xFFFFFFF0ull;
+    L.fits32 = L.act_bytes <= lim && L.lm_part - L.attn_acc <= lim && L.exch_end - L.lm_part <= lim;
     return L;
+}
+static_assert(PS_CTR_WORDS * 4 <= 256, "counters");
+
+// a valid configuration whose exchange buffers the kernels can address
+static int check_config(const ps_draft_config* c) {
+    const int st = validate_config(c);
+    if (st != PS_OK) return st;
+    return ws_layout(c).fits32 ? PS_OK : PS_ERR_UNSUPPORTED;
 }
 
 extern "C" size_t ps_draft_workspace_bytes(const ps_draft_config* config) {
-    if (validate_config(config) != PS_OK) return 0;
+    if (check_config(config) != PS_OK) return 0;
     return ws_layout(config).total;
 }
 
@@ -176,6 +186,7 @@ extern "C" const char* ps_draft_strerror(int status) {
         case PS_ERR_WORKSPACE: return "workspace too small or not 256-byte aligned";
         case PS_ERR_UNSUPPORTED: return "shape not supported by this build";
         case PS_ERR_DEVICE: return "HIP device error";
+        case PS_ERR_TIMEOUT: return "a step gave up waiting for its own workgroups (other work held the GPU?)";
         default: return "unknown status";
     }
 }
@@ -201,7 +212,7 @@ static void parse_plan_override(ps_draft_ctx* ctx) {
 extern "C" int ps_draft_init(ps_draft_ctx** out, const ps_draft_config* config, const ps_draft_weights* weights,
                              void* workspace, size_t workspace_bytes, void* stream) {
     if (!out || !config || !weights) return PS_ERR_NULL;
-    int st = validate_config(config);
+    int st = check_config(config);
     if (st != PS_OK) return st;
     const ps_draft_weights* w = weights;
     if (!w->g_in || !w->wq || !w->wk || !w->wv || !w->wo || !w->g_post || !w->w_gate || !w->w_up || !w->w_down || !w->w_lm)
@@ -236,6 +247,11 @@ extern "C" int ps_draft_init(ps_draft_ctx** out, const ps_draft_config* config, 
     {
         const char* mode = getenv("PS_DRAFT_MODE");   // "multi": one kernel per phase (profiling, fallback)
         ctx->fused = coop && !(mode && strcmp(mode, "multi") == 0);
+        // the persistent kernel's workgroups wait for each other: a device that cannot hold one of them per
+        // compute unit (as this build assumes) runs the step as one kernel per phase instead
+        int per_cu = 0;
+        if (ctx->fused && (inst->fused_resident(1, lds_limit < 84 * 1024 ? lds_limit : 84 * 1024, &per_cu) != hipSuccess || per_cu < 1))
+            ctx->fused = 0;
     }
     ctx->lds_limit = lds_limit;
     ctx->n_cu = prop.multiProcessorCount;
@@ -248,8 +264,7 @@ extern "C" int ps_draft_init(ps_draft_ctx** out, const ps_draft_config* config, 
     ctx->off_q = L.off_q; ctx->off_o = L.off_o; ctx->off_y = L.off_y; ctx->off_u = L.off_u;
     ctx->off_y2 = L.off_y2; ctx->off_kvnew = L.off_kvnew;
     for (int ph = 0; ph < PH_COUNT; ++ph) { ctx->off_frag[ph] = L.off_frag[ph]; ctx->off_ssqf[ph] = L.off_ssqf[ph]; }
-    ctx->rows_dirty = 0;
-    ctx->last_frag_sig = 0; ctx->act_small = L.act_small;
+    ctx->spin_limit = PS_SPIN_LIMIT;
     ctx->attn_acc = (float*)(base + L.attn_acc);
     ctx->attn_ml = (float*)(base + L.attn_ml);
     ctx->exch_begin = L.exch_begin; ctx->exch_end = L.exch_end;
@@ -280,7 +295,7 @@ extern "C" int ps_draft_init(ps_draft_ctx** out, const ps_draft_config* config, 
     // sequence numbers start at 1: cleared exchange buffers never look valid
     if (e == hipSuccess) e = hipMemsetAsync(base + L.exch_begin, 0, L.exch_end - L.exch_begin, s);
     if (e == hipSuccess) e = hipMemsetAsync(ctx->act_base, 0xFF, 2 * L.act_bytes, s);   // both copies: nothing written yet
-    if (e == hipSuccess) e = hipMemsetAsync(ctx->counters, 0, 64, s);
+    if (e == hipSuccess) e = hipMemsetAsync(ctx->counters, 0, 256, s);
     {   // copy the five weight matrices into streaming order
         StepParams P;
         memset(&P, 0, sizeof(P));
@@ -305,12 +320,34 @@ extern "C" int ps_draft_init(ps_draft_ctx** out, const ps_draft_config* config, 
 
 extern "C" void ps_draft_free(ps_draft_ctx* ctx) { delete ctx; }
 
-// Debugging aid, not declared in the public header: device buffer of 64 x 1024 uint64 receiving
-// per-workgroup clock stamps of the following steps (NULL = off; builds with -DPS_TIMELINE only).
-extern "C" __attribute__((visibility("default"))) int ps_draft_debug_timeline(ps_draft_ctx* ctx, void* buf) {
+// see ps_draft_debug.h
+extern "C" int ps_draft_debug_timeline(ps_draft_ctx* ctx, void* buf) {
     if (!ctx) return PS_ERR_NULL;
     ctx->timeline = (unsigned long long*)buf;
     return PS_OK;
+}
+extern "C" int ps_draft_debug_spin_limit(ps_draft_ctx* ctx, int spins) {
+    if (!ctx) return PS_ERR_NULL;
+    ctx->spin_limit = spins > 0 ? spins : PS_SPIN_LIMIT;
+    return PS_OK;
+}
+
+// Waits for the stream and reports whether a step since the previous query gave up a wait.  After such a
+// step the exchange buffers may hold anything: they, the flag and the footprints are put back into
+// their initial state (the step counter keeps running, so old tags stay invalid).
+extern "C" int ps_draft_last_status(ps_draft_ctx* ctx, void* stream) {
+    if (!ctx) return PS_ERR_NULL;
+    hipStream_t s = (hipStream_t)stream;
+    int flag = 0;
+    if (!hip_ok(hipMemcpyAsync(&flag, ctx->counters + PS_CTR_ERROR, sizeof(int), hipMemcpyDeviceToHost, s), "hipMemcpyAsync")) return PS_ERR_DEVICE;
+    if (!hip_ok(hipStreamSynchronize(s), "hipStreamSynchronize")) return PS_ERR_DEVICE;
+    if (!flag) return PS_OK;
+    hipError_t e = hipMemsetAsync(ctx->act_base, 0xFF, 2 * ctx->act_bytes, s);
+    if (e == hipSuccess) e = hipMemsetAsync(ctx->counters + PS_CTR_ERROR, 0, sizeof(int), s);
+    if (e == hipSuccess) e = hipMemsetAsync(ctx->counters + PS_CTR_DONE, 0, (PS_CTR_WORDS - PS_CTR_DONE) * sizeof(int), s);
+    if (e == hipSuccess) e = hipStreamSynchronize(s);
+    if (!hip_ok(e, "resetting the exchange buffers")) return PS_ERR_DEVICE;
+    return PS_ERR_TIMEOUT;
 }
 
 extern "C" int ps_draft_set_profile_events(ps_draft_ctx* ctx, void* const* events) {
@@ -415,16 +452,11 @@ static bool make_desc(PhaseDesc* d, int ph, int T, int Kt, int K, int rows, int 
     return false;
 }
 
-// Testing aid, not declared in the public header; runs on the host alone.  For a configuration and the
-// shape of a step it reports how ps_draft_step would cut up the five GEMM phases on a device with
-// n_cu compute units and lds_limit bytes of LDS per workgroup (persistent-kernel mode): per phase
-// PS_PLAN_FIELDS ints {T, Kt, K, rows, kw_log, s_log, Gs, per_round, rounds, piece_groups, npieces, lds_bytes}.
-#define PS_PLAN_FIELDS 12
-extern "C" __attribute__((visibility("default"))) int ps_draft_debug_plan(const ps_draft_config* c, int batch, int n_new,
-                                                                          int k, int all_rows, int n_cu, int lds_limit,
-                                                                          int* out) {
+// see ps_draft_debug.h
+extern "C" int ps_draft_debug_plan(const ps_draft_config* c, int batch, int n_new, int k, int all_rows, int n_cu, int lds_limit,
+                                   int* out) {
     if (!c || !out) return PS_ERR_NULL;
-    const int st = validate_config(c);
+    const int st = check_config(c);
     if (st != PS_OK) return st;
     if (batch < 1 || batch > c->max_batch || n_new < 1 || n_new > c->max_new || k < 0 || k > c->k_max) return PS_ERR_SHAPE;
     if (n_cu < 1 || n_cu > 1024 || lds_limit < 64 * 1024 || lds_limit > PS_LDS_BYTES) return PS_ERR_SHAPE;
@@ -479,28 +511,18 @@ extern "C" int ps_draft_step(ps_draft_ctx* ctx, const ps_draft_step_args* a, voi
     P.lm_part = ctx->lm_part;
     P.m_magic = 0xFFFFFFFFu / (unsigned)M + 1u;   // ceil(2^32 / M); M = 1 is handled on the device
     P.tph_log = c.head_dim == 128 ? 3 : 2;
-    P.error_flag = ctx->counters;
+    P.error_flag = ctx->counters + PS_CTR_ERROR;
     // The step's sequence number is kept on the device (ctx->counters[1], advanced by the kernels), so a
     // captured launch can be replayed.  The exchange buffers exist twice, step n uses copy n & 1; the
     // pointers here are those of copy 0.
-    P.step_ctr = (unsigned*)ctx->counters + 1;
-    P.done_ctr = (unsigned*)ctx->counters + 2;
+    P.step_ctr = (unsigned*)ctx->counters + PS_CTR_STEP;
+    P.done_ctr = (unsigned*)ctx->counters + PS_CTR_DONE;
     char* const act0 = ctx->act_base;
     P.act_bytes = (long long)ctx->act_bytes;
     P.q_buf = (float*)(act0 + ctx->off_q); P.o_buf = (float*)(act0 + ctx->off_o); P.y_buf = (float*)(act0 + ctx->off_y);
     P.u_buf = (float*)(act0 + ctx->off_u); P.y2_buf = (float*)(act0 + ctx->off_y2); P.kvnew = (float*)(act0 + ctx->off_kvnew);
-    // A step resets, in the copy the next step uses, the rows it writes and the rows one step's worth
-    // further up (see SxBuf).  So a step with fewer rows than an earlier one needs no clearing as long as
-    // it has at least half as many; below that, the part of both copies that is laid out by rows is
-    // cleared first (the K-slice fragments further down, once the plan is known).
-    if (P.Mtot > ctx->rows_dirty) ctx->rows_dirty = P.Mtot;
-    if (ctx->rows_dirty > 2 * P.Mtot) {
-        for (int cp = 0; cp < 2; ++cp)
-            if (!hip_ok(hipMemsetAsync(act0 + (size_t)cp * ctx->act_bytes, 0xFF, ctx->act_small, (hipStream_t)stream), "hipMemsetAsync"))
-                return PS_ERR_DEVICE;
-        ctx->rows_dirty = P.Mtot;
-    }
-    P.rows_reset = ctx->rows_dirty;
+    P.spin_limit = ctx->spin_limit;
+    P.foot_mem = (unsigned*)ctx->counters + PS_CTR_FOOT;
     P.logits_store = a->logits ? a->logits : (a->probs ? ctx->logits_ws : nullptr);
     P.top_ids = a->top_ids; P.top_p = a->top_p; P.lse = a->lse; P.probs = a->probs; P.hidden_out = a->hidden_out;
     for (int b = 0; b < a->batch; ++b) {
@@ -556,28 +578,21 @@ extern "C" int ps_draft_step(ps_draft_ctx* ctx, const ps_draft_step_args* a, voi
         P.ph[ph].frag = (float*)(ctx->act_base + ctx->off_frag[ph]);
         P.ph[ph].ssq_frag = (float*)(ctx->act_base + ctx->off_ssqf[ph]);
     }
-    {   // which fragment slots a step uses depends on the column tiles and the K-slices of each phase
-        unsigned sig = (unsigned)((P.Mtot + 15) / 16);
-        for (int ph = 0; ph < PH_COUNT; ++ph) sig = sig * 8u + (unsigned)P.ph[ph].s_log + 1u;
-        if (sig != ctx->last_frag_sig) {
-            // (the slices' sums of squares lie among the row buffers: everything is cleared)
-            if (ctx->last_frag_sig != 0) {
-                for (int cp = 0; cp < 2; ++cp)
-                    if (!hip_ok(hipMemsetAsync(ctx->act_base + (size_t)cp * ctx->act_bytes, 0xFF, ctx->act_bytes,
-                                               (hipStream_t)stream), "hipMemsetAsync"))
-                        return PS_ERR_DEVICE;
-                ctx->rows_dirty = P.Mtot;
-                P.rows_reset = P.Mtot;
-            }
-            ctx->last_frag_sig = sig;
-        }
-    }
     P.ph[PH_QKV].norm = 1; P.ph[PH_QKV].gain = P.g_in; P.ph[PH_QKV].src = nullptr; P.ph[PH_QKV].src_ld = P.H;
     P.ph[PH_OPROJ].src = P.o_buf; P.ph[PH_OPROJ].src_ld = P.QD;
     P.ph[PH_GATEUP].norm = 1; P.ph[PH_GATEUP].gain = P.g_post; P.ph[PH_GATEUP].src = P.y_buf; P.ph[PH_GATEUP].src_ld = P.H;
     P.ph[PH_DOWN].src = P.u_buf; P.ph[PH_DOWN].src_ld = P.F;
     P.ph[PH_LMHEAD].norm = P.final_norm; P.ph[PH_LMHEAD].gain = P.g_final; P.ph[PH_LMHEAD].src = P.y2_buf; P.ph[PH_LMHEAD].src_ld = P.H;
     P.timeline = ctx->timeline;
+    // what this step leaves in the sentinel-coded buffers of its copy (see sx_reset_stale in ps_device.h)
+    P.foot[0] = (unsigned)P.Mtot;
+    for (int ph = 0; ph < PH_COUNT; ++ph) {
+        const PhaseDesc& d = P.ph[ph];
+        const bool sliced = ph != PH_LMHEAD && d.s_log > 0;
+        const int mt = (P.Mtot + 15) / 16;
+        P.foot[1 + ph] = sliced ? (unsigned)(1 << d.s_log) * (unsigned)d.T * (unsigned)mt * 64u : 0u;
+        P.foot[1 + PH_COUNT + ph] = (sliced && d.norm) ? 1u << d.s_log : 0u;
+    }
 
     // the persistent kernel needs the largest LDS footprint of its phases and one workgroup per CU
     int lds = ps_attn_lds_bytes(c.head_dim, nk);

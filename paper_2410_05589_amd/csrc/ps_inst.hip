@@ -105,6 +105,10 @@ static hipError_t launch_fused(const StepParams& P, hipStream_t stream) {
     return hipGetLastError();
 }
 
+static hipError_t fused_resident(int mt, int lds, int* per_cu) {
+    return hipOccupancyMaxActiveBlocksPerMultiprocessor(per_cu, reinterpret_cast<const void*>(fused_fn(mt)), PS_WG_THREADS, (size_t)lds);
+}
+
 static hipError_t launch_probs(const StepParams& P, hipStream_t stream) {
     hipLaunchKernelGGL(probs_kernel, dim3((P.V + 255) / 256 < 256 ? (P.V + 255) / 256 : 256, P.Rtot), dim3(256), 0,
                        stream, P);
@@ -132,7 +136,7 @@ static hipError_t pack(const StepParams& P, int ph, int T, int Kt, int Kreal, ch
 const PsInstance* PS_CAT(ps_instance_, PS_INST_NAME)() {
     static const PsInstance inst = {
         PS_INST_BF16 ? PS_BF16 : PS_F32, PS_INST_D,
-        prepare, launch_multi, launch_fused, launch_probs, pack,
+        prepare, launch_multi, launch_fused, launch_probs, fused_resident, pack,
     };
     return &inst;
 }

@@ -36,6 +36,16 @@ constexpr int ps_attn_lds_bytes(int d, int nk) {
 }
 
 enum { PH_QKV = 0, PH_OPROJ = 1, PH_GATEUP = 2, PH_DOWN = 3, PH_LMHEAD = 4, PH_COUNT = 5 };
+// Footprint of a step in the sentinel-coded exchange buffers: [0] activation rows, [1 + ph] 16-byte units of
+// phase ph's K-slice fragments, [1 + PH_COUNT + ph] K-slices that left sums of squares (0 = none)
+#define PS_FOOT_INTS (1 + 2 * PH_COUNT)
+// Device counters of a context (32-bit words): error flag, steps completed, tickets, then the footprints
+#define PS_CTR_ERROR 0
+#define PS_CTR_STEP 1
+#define PS_CTR_DONE 2
+#define PS_CTR_FOOT 4
+#define PS_CTR_WORDS (PS_CTR_FOOT + 2 * PS_FOOT_INTS)
+#define PS_SPIN_LIMIT (1 << 20)
 
 // How one weight-streaming GEMM phase is cut up.  A "tile" is 16 weight rows; a "step" is the
 // 64-byte piece of a weight row one MFMA group consumes (32 bf16 or 16 f32 elements); a "group"
@@ -72,7 +82,7 @@ struct StepParams {
     // shape
     int H, nq, nkv, d, F, V, QD, KVD;
     int B, n_new, k, M, Mtot, R, Rtot, all_rows, topk;
-    int rows_reset;    // >= Mtot, <= 2 Mtot: rows of the exchange buffers that may hold values of earlier steps
+    int spin_limit;    // polls after which a wait for exchanged data is given up (see spin_again)
     int final_norm, max_positions;
     float eps, inv_sqrt_d;
     // weights and step inputs (config dtype)
@@ -87,6 +97,10 @@ struct StepParams {
     float* kvnew;      // [Mtot][2][KVD] this step's K and V rows as stored in the cache
     long long act_bytes;   // distance between the two copies
     unsigned *step_ctr, *done_ctr;   // steps completed so far; tickets of the running kernel (see step_begin)
+    // What a step leaves behind in the sentinel-coded buffers of its copy (see sx_reset_stale): foot is this
+    // step's footprint, foot_mem the device-side record [2][PS_FOOT_INTS] of the two latest steps' footprints.
+    unsigned foot[PS_FOOT_INTS];
+    unsigned* foot_mem;
     // Buffers below hold 8-byte units {value, tag}: element counts.
     float* attn_acc;   // [items][g*M][d] unnormalised partial outputs
     float* attn_ml;    // [items][g*M][2] (running max, sum of exponentials)
@@ -121,6 +135,8 @@ struct PsInstance {
     hipError_t (*launch_multi)(const StepParams& P, hipStream_t stream, hipEvent_t* events);
     hipError_t (*launch_fused)(const StepParams& P, hipStream_t stream);
     hipError_t (*launch_probs)(const StepParams& P, hipStream_t stream);
+    // workgroups of the persistent kernel (mt column tiles, lds bytes of dynamic LDS) a compute unit can hold
+    hipError_t (*fused_resident)(int mt, int lds, int* per_cu);
     // copies one phase's weight matrix (T tiles x Kt steps, of which the first Kreal hold weights
     // and the rest zeros) into streaming order at dst (T*Kt KiB)
     hipError_t (*pack)(const StepParams& P, int ph, int T, int Kt, int Kreal, char* dst, hipStream_t stream);

@@ -17,6 +17,7 @@
 
 #include "ps_draft.h"
 #include "ps_verify.h"
+#include "ps_draft_debug.h"
 
 namespace {
 
@@ -611,10 +612,8 @@ std::atomic<int> g_spin_limit{XCH_SPINS}, g_ghosts{0};
 
 }   // namespace
 
-// Testing aid, not declared in the public header: the following multi-workgroup walks give up a wait after
-// `spins` polls (<= 0: the default) and wait for `ghosts` (0 or 1) workgroups per sequence that do not exist,
-// so the give-up path can be exercised while every kernel still ends normally.
-extern "C" __attribute__((visibility("default"))) void ps_verify_debug_exchange(int spins, int ghosts) {
+// see ps_draft_debug.h
+extern "C" void ps_verify_debug_exchange(int spins, int ghosts) {
     g_spin_limit = spins > 0 ? spins : XCH_SPINS;
     g_ghosts = ghosts == 1 ? 1 : 0;
 }

@@ -230,17 +230,14 @@ def test_a_wait_that_runs_out_marks_the_sequence_and_the_next_call_is_fine():
     """Several workgroups per sequence: with the test hook every workgroup also waits for one that does not
     exist, with a short limit, so every wait is given up: the kernel ends normally, n_accepted = -2.  The
     call after it (hook off) gives the oracle's result."""
-    import ctypes
-    lib = B.load_library()
-    lib.ps_verify_debug_exchange.restype = None
-    lib.ps_verify_debug_exchange.argtypes = [ctypes.c_int, ctypes.c_int]
+    from paper_2410_05589_amd import debug as DBG
     parent, rank = inputs.draft_tree([3, 2])
     inp = inputs.verify_inputs(44, 2, parent, rank, 3, 8, 40004, agreement=0.1)   # rejections are certain
-    lib.ps_verify_debug_exchange(200, 1)
+    DBG.ps_verify_debug_exchange(200, 1)
     try:
         gpu = _run_gpu(parent, rank, inp, 3, 8)
     finally:
-        lib.ps_verify_debug_exchange(0, 0)
+        DBG.ps_verify_debug_exchange(0, 0)
     assert gpu["n_accepted"].tolist() == [-2, -2]
     _check(parent, rank, inp, 3, 8, "after a wait that ran out")
 

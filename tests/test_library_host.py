@@ -7,6 +7,7 @@ import re
 import pytest
 
 from paper_2410_05589_amd import binding as B
+from paper_2410_05589_amd import debug as DBG
 from paper_2410_05589_amd.configs import WORKLOADS, small_shape
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
@@ -20,17 +21,30 @@ def lib():
     return B.load_library()
 
 
-def _declared_functions():
-    text = open(os.path.join(ROOT, "include", "ps_draft.h")).read()
+def _declared_functions(header):
+    text = open(os.path.join(ROOT, "include", header)).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(ps_draft_[a-z_]+)\s*\(", text)))
+    return sorted(set(re.findall(r"\bPS_API\s+[a-z_ ]+\*?\s+(ps_[a-z_]+)\s*\(", text)))
 
 
 def test_every_declared_symbol_is_exported(lib):
-    declared = _declared_functions()
+    declared = _declared_functions("ps_draft.h")
     assert sorted(B.EXPORTED_SYMBOLS) == declared
     for name in declared:
         assert getattr(lib, name) is not None
+    debug = _declared_functions("ps_draft_debug.h")
+    assert sorted(DBG.EXPORTED_SYMBOLS) == debug
+    for name in debug:
+        assert getattr(lib, name) is not None
+
+
+def test_nothing_else_is_exported(lib):
+    """The dynamic symbol table holds exactly the ps_* functions the three headers declare."""
+    import subprocess
+    out = subprocess.run(["nm", "-D", "--defined-only", B.LIB_PATH], stdout=subprocess.PIPE, text=True, check=True).stdout
+    exported = sorted(l.split()[-1] for l in out.splitlines() if l.split()[-1].startswith("ps_"))
+    declared = sorted(sum((_declared_functions(h) for h in ("ps_draft.h", "ps_verify.h", "ps_draft_debug.h")), []))
+    assert exported == declared
 
 
 def test_struct_layouts_match_header():
@@ -88,6 +102,21 @@ def test_config_validation(lib):
         assert st == B.PS_ERR_UNSUPPORTED, kw
 
 
+def test_exchange_buffers_the_kernels_cannot_address_are_refused(lib):
+    """The kernels use 32-bit byte offsets into every exchange buffer: a legal configuration whose attention
+    partials (or any other exchange buffer) would reach 4 GiB is unsupported, not silently wrapped."""
+    ok = _cfg(max_batch=4, max_positions=1 << 15)
+    assert B.ps_draft_workspace_bytes(ok) > 0
+    for kw in (dict(max_batch=4, max_positions=1 << 20), dict(max_positions=(1 << 24) + 1)):
+        c = _cfg(**kw)
+        assert B.ps_draft_workspace_bytes(c) == 0, kw
+        w = B.ps_draft_weights()
+        for n in B.WEIGHT_NAMES:
+            setattr(w, n, 0x1000)
+        assert B.ps_draft_init(c, w, 0x100000, 1 << 44, None)[0] == B.PS_ERR_UNSUPPORTED, kw
+        assert DBG.ps_draft_debug_plan(c, 1, 1, 5, 0, 256, 160 * 1024)[0] == B.PS_ERR_UNSUPPORTED, kw
+
+
 def test_init_null_and_workspace_errors(lib):
     c = _cfg()
     w = B.ps_draft_weights()
@@ -115,16 +144,21 @@ def test_init_null_and_workspace_errors(lib):
 def test_step_and_free_with_null_context(lib):
     a = B.ps_draft_step_args()
     assert B.ps_draft_step(None, a, None) == B.PS_ERR_NULL
+    assert B.ps_draft_last_status(None, None) == B.PS_ERR_NULL
+    assert DBG.ps_draft_debug_spin_limit(None, 1) == B.PS_ERR_NULL
+    assert DBG.ps_measure_stream_read(None, 1024, None) == B.PS_ERR_NULL
+    assert DBG.ps_measure_stream_read(0x1000, 1000, None) == B.PS_ERR_SHAPE
+    assert DBG.ps_measure_copy(0x1000, 0x2000, 8, None) == B.PS_ERR_SHAPE
     B.ps_draft_free(None)
 
 
 def test_strerror(lib):
     seen = set()
-    for st in range(0, -9, -1):
+    for st in range(0, -10, -1):
         s = B.ps_draft_strerror(st)
         assert s and s != "unknown status"
         seen.add(s)
-    assert len(seen) == 9
+    assert len(seen) == 10
     assert B.ps_draft_strerror(-99) == "unknown status"
 
 
@@ -135,20 +169,12 @@ def test_missing_library_fails_loudly(monkeypatch):
         B.load_library()
 
 
-PLAN_FIELDS = ("T", "Kt", "K", "rows", "kw_log", "s_log", "Gs", "per_round", "rounds", "piece_groups", "npieces",
-               "lds_bytes")
 PS_U, PS_WAVES = 8, 8
 
 
 def _plan(lib, cfg, batch, n_new, k, n_cu=256, lds=160 * 1024, all_rows=0):
-    lib.ps_draft_debug_plan.restype = ctypes.c_int
-    out = (ctypes.c_int * (5 * len(PLAN_FIELDS)))()
-    st = lib.ps_draft_debug_plan(ctypes.byref(cfg), batch, n_new, k, all_rows, n_cu, lds, out)
-    if st != B.PS_OK:
-        return st, None
-    vals = list(out)
-    n = len(PLAN_FIELDS)
-    return st, [dict(zip(PLAN_FIELDS, vals[p * n:(p + 1) * n])) for p in range(5)]
+    st, plans = DBG.ps_draft_debug_plan(cfg, batch, n_new, k, all_rows, n_cu, lds)
+    return (st, plans) if st == B.PS_OK else (st, None)
 
 
 def _check_plan(cfg, plans, batch, n_new, k, n_cu, lds):

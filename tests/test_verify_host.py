@@ -27,7 +27,7 @@ def _header_code():
 
 
 def test_every_declared_symbol_is_exported(lib):
-    declared = sorted(set(re.findall(r"\bint\s+(ps_[a-z_]+)\s*\(", _header_code())))
+    declared = sorted(set(re.findall(r"\bPS_API\s+int\s+(ps_[a-z_]+)\s*\(", _header_code())))
     assert declared == sorted(VF.EXPORTED_SYMBOLS)
     for name in declared:
         assert getattr(lib, name) is not None
