@@ -66,12 +66,18 @@ PS_API int ps_tree_tokens(const ps_tree_shape* tree, int32_t batch, int32_t rows
  *   path        DEVICE [batch][rows] int32, written: the accepted nodes, then -1
  *   out_tokens  DEVICE [batch][rows + 1] int32, written: the accepted tokens, the last drawn
  *               token, then -1
- * No scratch memory is passed in.  vocab may be at most 262144 (1048576 when vocab % 4 == 0 and q and p
- * are 16-byte aligned).  For vocab > 32768 (vocab % 4 == 0, aligned rows, batch <= 64, enough compute units)
- * several workgroups share a sequence and exchange their partial sums through about 1 MB of device memory
- * that belongs to the library: such calls on one device must not overlap in time (calls on one stream never
- * do).  Should that exchange ever time out (it cannot while every workgroup of the launch gets a compute
- * unit), n_accepted[b] = -2 marks the sequence and its other outputs are undefined.
+ *   workspace   DEVICE, optional (NULL = none): exchange memory for large vocabularies, at least
+ *               ps_verify_workspace_bytes(batch, vocab) bytes, 256-byte aligned, owned by the caller,
+ *               set to zero once before its first use and then left to the library (it may be
+ *               used with any batch up to the one it was sized for)
+ * vocab may be at most 262144 (1048576 when vocab % 4 == 0 and q and p are 16-byte aligned).
+ * For vocab > 32768 (vocab % 4 == 0, aligned rows, batch * workgroups per sequence <= compute units) several
+ * workgroups share a sequence and exchange their partial sums through device memory: the workspace if one is
+ * given (calls with different workspaces may overlap in time), else, for batch <= 64, about 1 MB that belongs to
+ * the library: calls that use the library's memory on one device must not overlap in time (calls on one stream
+ * never do).  Without either, one workgroup walks each sequence (slower, same results).  Should the exchange
+ * ever time out (it cannot while every workgroup of the launch gets a compute unit), n_accepted[b] = -2 marks
+ * the sequence and its other outputs are undefined.
  * Errors: PS_ERR_NULL; PS_ERR_SHAPE (batch < 1, vocab < 1, a malformed tree, a depth beyond
  * rows; without tokens: topk < 1 or a rank outside [0, topk)); PS_ERR_UNSUPPORTED (vocab too
  * large); PS_ERR_DEVICE.
@@ -87,8 +93,28 @@ typedef struct ps_verify_args {
     int32_t* out_tokens;
     const int32_t* top_ids;
     int32_t topk;
+    void* workspace;
+    size_t workspace_bytes;
 } ps_verify_args;
 PS_API int ps_verify_walk(const ps_tree_shape* tree, const ps_verify_args* args, void* stream);
+
+/* Bytes of exchange memory ps_verify_walk can use for this batch and vocabulary (0: none needed).  Host only. */
+PS_API size_t ps_verify_workspace_bytes(int32_t batch, int32_t vocab);
+
+/*
+ * ps_verify_walk for callers that cannot allocate device memory or hand any in: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid allocation.  Same arguments (args->workspace is
+ * ignored), same results, same kernels; it allocates nothing, on the host or on the device.  The exchange
+ * memory that large vocabularies need is a fixed array inside the library, 1,065,472 bytes, of which every GPU
+ * the library runs on holds its own copy until the process ends.  Limits (beyond them PS_ERR_UNSUPPORTED, never
+ * a silent slower path): when vocab > 32768 with vocab % 4 == 0 and aligned rows, batch <= 64 and
+ * batch * workgroups per sequence (ceil(vocab / 16384), at most 16) <= compute units.  All calls on one GPU
+ * share that array, which keeps what the last call left (tagged with a per-sequence launch count that lives in
+ * the array too, so old contents are never taken for data): calls of this function, and calls of ps_verify_walk
+ * without a workspace, that overlap in time on one GPU race with each other; calls on one stream never overlap.
+ * The first call on a device asks the runtime for the array's address: make it outside graph capture.
+ */
+PS_API int ps_verify_walk_static(const ps_tree_shape* tree, const ps_verify_args* args, void* stream);
 
 #ifdef __cplusplus
 }

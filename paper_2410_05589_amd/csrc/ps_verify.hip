@@ -36,7 +36,9 @@ struct WalkParams {
     int topk;
     const float *q, *p, *r;
     int32_t *n_accepted, *path, *out_tokens;
-    int slabs_per_wg;     // several workgroups per sequence: slabs of the vocabulary each of them takes
+    unsigned long long* xch;   // several workgroups per sequence: per sequence [XCH_ROUNDS][XCH_WGS][2] exchange slots and a
+                               // launch count (the caller's workspace or the library's own memory) ...
+    int slabs_per_wg;     // ... slabs of the vocabulary each of them takes
     int spin_limit;       // ... polls before a wait for another workgroup's sum is given up
     int ghosts;           // ... workgroups waited for that do not exist (0; tests of the give-up path: 1)
 };
@@ -154,33 +156,52 @@ template <> __device__ __forceinline__ void widen<4>(const float4& v, double (&o
 //
 // MULTI: gridDim.x workgroups share a sequence (blockIdx.y); workgroup g takes slabs [g S, (g + 1) S) of the
 // vocabulary for every sum and all of them take every decision.  A sum over the vocabulary is then the sum, in
-// workgroup order, of the workgroups' parts, which they leave for each other in g_xch (device memory of the
-// library, one slot per sequence, round and workgroup; a slot is two 8-byte units {half of the double, tag},
-// written and read with agent-scope atomics).  The tag is the sequence slot's launch count + 1: it is kept in
-// device memory (g_epoch), read by every workgroup when it starts and advanced by the workgroup that finishes
-// the sequence - by then all of them have read it - so a launch replayed from a graph gets new tags too.
-// Every wait is bounded; a workgroup whose wait runs out marks the sequence as failed (n_accepted = -2) and
-// leaves.  All workgroups of a launch must be resident at once (the host launches at most one per compute
-// unit), and launches that use g_xch must not overlap in time.
+// workgroup order, of the workgroups' parts, which they leave for each other in exchange memory (Wp.xch: one
+// slot per sequence, round and workgroup; a slot is two 8-byte units {half of the double, tag}, written and
+// read with agent-scope atomics).  The tag is the sequence slot's launch count + 1: it is kept in device memory
+// (xch_epoch), read by every workgroup when it starts and advanced by the workgroup that finishes the sequence -
+// by then all of them have read it - so a launch replayed from a graph gets new tags too, and whatever an
+// earlier call left in the slots is never taken for data.  Every wait is bounded; a workgroup whose wait runs
+// out marks the sequence as failed (n_accepted = -2) and leaves.  All workgroups of a launch must be resident at
+// once (the host launches at most one per compute unit), and launches that share exchange memory must not
+// overlap in time.
 constexpr int WALK_MAX_SLABS = 256;
 constexpr int XCH_SEQS = 64, XCH_ROUNDS = PS_TREE_MAX_NODES + 1, XCH_WGS = 16, XCH_SPINS = 1 << 20;
-static __device__ unsigned long long g_xch[XCH_SEQS][XCH_ROUNDS][XCH_WGS][2];
-static __device__ unsigned g_epoch[XCH_SEQS];
+constexpr size_t XCH_SLOT_WORDS = (size_t)XCH_ROUNDS * XCH_WGS * 2;       // 8-byte words of slots per sequence
+constexpr size_t XCH_SEQ_WORDS = XCH_SLOT_WORDS + 1;                      // ... and one for the launch count
+// bytes for `batch` sequences (a sequence's block does not depend on the batch it is used with)
+constexpr size_t xch_bytes(size_t batch) { return (batch * XCH_SEQ_WORDS * 8 + 255) / 256 * 256; }
+
+// The library's own exchange memory, for XCH_SEQS sequences: used when the caller passes no workspace, and by
+// ps_verify_walk_static.  Zero when the code object is loaded (launch counts start at 0); every GPU holds its
+// own copy.  Host code must not use the array's name as an address: scratch_ptr() asks the runtime for the
+// address of the current device's copy once and keeps it.
+constexpr size_t SCRATCH_BYTES = xch_bytes(XCH_SEQS);
+static __device__ __align__(256) unsigned char scratch[SCRATCH_BYTES];
+
+__device__ __forceinline__ unsigned long long* xch_slot(const WalkParams& Wp, int b, int rnd, int g) {
+    return Wp.xch + (size_t)b * XCH_SEQ_WORDS + ((size_t)rnd * XCH_WGS + g) * 2;
+}
+__device__ __forceinline__ unsigned* xch_epoch(const WalkParams& Wp, int b) {
+    return reinterpret_cast<unsigned*>(Wp.xch + (size_t)b * XCH_SEQ_WORDS + XCH_SLOT_WORDS);
+}
 
 // all workgroups of sequence b: the sum over g of their `mine`, the same in every thread; false if a wait ran out
 __device__ __forceinline__ bool xch_sum(const WalkParams& Wp, double mine, int b, int rnd, unsigned tag, double* s_x, double& sum) {
     const int g = blockIdx.x, G = gridDim.x, tid = threadIdx.x;
     if (tid == 0) {
         const unsigned long long bits = (unsigned long long)__double_as_longlong(mine);
-        __hip_atomic_store(&g_xch[b][rnd][g][0], ((bits & 0xFFFFFFFFull) << 32) | tag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __hip_atomic_store(&g_xch[b][rnd][g][1], ((bits >> 32) << 32) | tag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        unsigned long long* mine_slot = xch_slot(Wp, b, rnd, g);
+        __hip_atomic_store(mine_slot, ((bits & 0xFFFFFFFFull) << 32) | tag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(mine_slot + 1, ((bits >> 32) << 32) | tag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     if (tid < G + Wp.ghosts) {
         unsigned long long lo = 0, hi = 0;
+        const unsigned long long* theirs = xch_slot(Wp, b, rnd, tid);
         int spins = 0;
         for (;;) {
-            lo = __hip_atomic_load(&g_xch[b][rnd][tid][0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            hi = __hip_atomic_load(&g_xch[b][rnd][tid][1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            lo = __hip_atomic_load(theirs, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            hi = __hip_atomic_load(theirs + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             if (((unsigned)lo == tag && (unsigned)hi == tag) || ++spins > Wp.spin_limit) break;
             __builtin_amdgcn_s_sleep(2);
         }
@@ -210,7 +231,7 @@ __global__ void __launch_bounds__(WALK_THREADS) verify_walk_kernel(const WalkPar
     __shared__ unsigned s_tag;
     if (tid == 0) {                     // (both read after the barrier in load_nodes at the earliest)
         s_x[XCH_WGS] = 0.0;
-        unsigned t = MULTI ? __hip_atomic_load(&g_epoch[b], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1u : 1u;
+        unsigned t = MULTI ? __hip_atomic_load(xch_epoch(Wp, b), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1u : 1u;
         s_tag = t ? t : 1u;             // 0 is what slots never written hold
     }
     int rnd = 0;
@@ -222,7 +243,7 @@ __global__ void __launch_bounds__(WALK_THREADS) verify_walk_kernel(const WalkPar
     auto fail = [&]() {   // a wait ran out: the sequence is marked, its tag is used up
         if (tid == 0) {
             Wp.n_accepted[b] = -2;
-            __hip_atomic_store(&g_epoch[b], tag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(xch_epoch(Wp, b), tag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
     };
 
@@ -386,7 +407,7 @@ __global__ void __launch_bounds__(WALK_THREADS) verify_walk_kernel(const WalkPar
         for (int i = n_acc + 1; i <= Wp.rows; ++i) Wp.out_tokens[(size_t)b * (Wp.rows + 1) + i] = -1;
         for (int i = n_acc; i < Wp.rows; ++i) Wp.path[(size_t)b * Wp.rows + i] = -1;
         Wp.n_accepted[b] = n_acc;
-        if (MULTI) __hip_atomic_store(&g_epoch[b], tag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (MULTI) __hip_atomic_store(xch_epoch(Wp, b), tag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
 }
 
@@ -630,7 +651,39 @@ extern "C" int ps_tree_tokens(const ps_tree_shape* tree, int32_t batch, int32_t 
     return hipGetLastError() == hipSuccess ? PS_OK : PS_ERR_DEVICE;
 }
 
-extern "C" int ps_verify_walk(const ps_tree_shape* tree, const ps_verify_args* a, void* stream) {
+namespace {
+
+// Address of the current device's copy of `scratch`: asked from the runtime on the first call on that device
+// (with that device current) and kept; every GPU holds its own copy at its own address.
+int scratch_ptr(unsigned char** out) {
+    static std::atomic<unsigned char*> ptrs[64];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return PS_ERR_DEVICE;
+    unsigned char* p = ptrs[dev].load();
+    if (!p) {
+        void* q = nullptr;
+        if (hipGetSymbolAddress(&q, HIP_SYMBOL(scratch)) != hipSuccess || !q) return PS_ERR_DEVICE;
+        p = static_cast<unsigned char*>(q);
+        ptrs[dev].store(p);
+    }
+    *out = p;
+    return PS_OK;
+}
+
+// vocabularies that take the exchange between workgroups: whole vectors of four entries, more than the
+// register kernel holds; slabs of the vocabulary per workgroup and workgroups per sequence
+bool wants_exchange(int vocab, bool aligned, int* per, int* G) {
+    if (vocab % 4 != 0 || !aligned || vocab <= REG_EPT * REG_THREADS) return false;
+    const long long slabs = ((long long)vocab / 4 + WALK_THREADS - 1) / WALK_THREADS;
+    int p = 4;
+    while ((slabs + p - 1) / p > XCH_WGS) ++p;
+    *per = p;
+    *G = (int)((slabs + p - 1) / p);
+    return *G > 1;
+}
+
+// static_only: the entry point that allocates nothing and takes no workspace (see ps_verify_walk_static)
+int walk_impl(const ps_tree_shape* tree, const ps_verify_args* a, void* stream, bool static_only) {
     if (!a) return PS_ERR_NULL;
     if ((!a->tokens && !a->top_ids) || !a->q || !a->p || !a->r || !a->n_accepted || !a->path || !a->out_tokens)
         return PS_ERR_NULL;
@@ -641,21 +694,37 @@ extern "C" int ps_verify_walk(const ps_tree_shape* tree, const ps_verify_args* a
     W.rows = a->rows; W.vocab = a->vocab;
     W.tokens = a->tokens; W.top_ids = a->tokens ? nullptr : a->top_ids; W.topk = a->topk; W.q = a->q; W.p = a->p; W.r = a->r;
     W.n_accepted = a->n_accepted; W.path = a->path; W.out_tokens = a->out_tokens;
+    W.xch = nullptr;
     // whole vectors of four entries when every row of q and p starts on a 16-byte boundary
-    const bool vec = a->vocab % 4 == 0 && (((uintptr_t)a->q | (uintptr_t)a->p) & 15) == 0;
+    const bool aligned = (((uintptr_t)a->q | (uintptr_t)a->p) & 15) == 0;
+    const bool vec = a->vocab % 4 == 0 && aligned;
     const long long slabs = ((long long)a->vocab / (vec ? 4 : 1) + WALK_THREADS - 1) / WALK_THREADS;
     if (slabs > WALK_MAX_SLABS) return PS_ERR_UNSUPPORTED;
     W.slabs_per_wg = (int)slabs;
     W.spin_limit = g_spin_limit;
     W.ghosts = 0;
+    int per = 0, G = 1;
+    const bool exchange = wants_exchange(a->vocab, aligned, &per, &G);
+    if (static_only) {
+        // this entry point never falls back silently: beyond what the library's own memory holds it says so
+        if (exchange && (a->batch > XCH_SEQS || (long long)a->batch * G > compute_units())) return PS_ERR_UNSUPPORTED;
+    }
     if (vec && a->vocab <= REG_EPT * REG_THREADS) {
         hipLaunchKernelGGL(verify_walk_reg_kernel, dim3(a->batch), dim3(REG_THREADS), 0, (hipStream_t)stream, W);
     } else if (vec) {
         // several workgroups per sequence (4 slabs each, at most XCH_WGS) when all of them get a compute unit
-        int per = 4;
-        while ((slabs + per - 1) / per > XCH_WGS) ++per;
-        const int G = (int)((slabs + per - 1) / per);
-        if (G > 1 && a->batch <= XCH_SEQS && (long long)a->batch * G <= compute_units()) {
+        // and there is exchange memory: the caller's workspace, else the library's own for up to XCH_SEQS sequences
+        unsigned char* mem = nullptr;
+        if (exchange && (long long)a->batch * G <= compute_units()) {
+            if (!static_only && a->workspace && a->workspace_bytes >= xch_bytes(a->batch) && ((uintptr_t)a->workspace & 255) == 0)
+                mem = static_cast<unsigned char*>(a->workspace);
+            else if (a->batch <= XCH_SEQS && scratch_ptr(&mem) != PS_OK) {
+                if (static_only) return PS_ERR_DEVICE;
+                mem = nullptr;
+            }
+        }
+        if (mem) {
+            W.xch = reinterpret_cast<unsigned long long*>(mem);
             W.slabs_per_wg = per;
             W.ghosts = G < XCH_WGS ? (int)g_ghosts : 0;
             hipLaunchKernelGGL((verify_walk_kernel<4, true>), dim3(G, a->batch), dim3(WALK_THREADS), 0, (hipStream_t)stream, W);
@@ -666,4 +735,20 @@ extern "C" int ps_verify_walk(const ps_tree_shape* tree, const ps_verify_args* a
         hipLaunchKernelGGL((verify_walk_kernel<1, false>), dim3(a->batch), dim3(WALK_THREADS), 0, (hipStream_t)stream, W);
     }
     return hipGetLastError() == hipSuccess ? PS_OK : PS_ERR_DEVICE;
+}
+
+}   // namespace
+
+extern "C" size_t ps_verify_workspace_bytes(int32_t batch, int32_t vocab) {
+    int per = 0, G = 1;
+    if (batch < 1 || vocab < 1 || !wants_exchange(vocab, true, &per, &G)) return 0;
+    return xch_bytes((size_t)batch);
+}
+
+extern "C" int ps_verify_walk(const ps_tree_shape* tree, const ps_verify_args* a, void* stream) {
+    return walk_impl(tree, a, stream, false);
+}
+
+extern "C" int ps_verify_walk_static(const ps_tree_shape* tree, const ps_verify_args* a, void* stream) {
+    return walk_impl(tree, a, stream, true);
 }

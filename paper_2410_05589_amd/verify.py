@@ -7,7 +7,7 @@ import numpy as np
 from . import binding as B
 
 PS_TREE_MAX_NODES = 64
-EXPORTED_SYMBOLS = ("ps_tree_tokens", "ps_verify_walk")
+EXPORTED_SYMBOLS = ("ps_tree_tokens", "ps_verify_walk", "ps_verify_workspace_bytes", "ps_verify_walk_static")
 
 
 class ps_tree_shape(ctypes.Structure):
@@ -19,7 +19,8 @@ class ps_verify_args(ctypes.Structure):
     _fields_ = [("batch", ctypes.c_int32), ("rows", ctypes.c_int32), ("vocab", ctypes.c_int32),
                 ("tokens", ctypes.c_void_p), ("q", ctypes.c_void_p), ("p", ctypes.c_void_p), ("r", ctypes.c_void_p),
                 ("n_accepted", ctypes.c_void_p), ("path", ctypes.c_void_p),
-                ("out_tokens", ctypes.c_void_p), ("top_ids", ctypes.c_void_p), ("topk", ctypes.c_int32)]
+                ("out_tokens", ctypes.c_void_p), ("top_ids", ctypes.c_void_p), ("topk", ctypes.c_int32),
+                ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t)]
 
 
 _ready = False
@@ -34,6 +35,10 @@ def _lib():
                                        ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
         lib.ps_verify_walk.restype = ctypes.c_int
         lib.ps_verify_walk.argtypes = [ctypes.POINTER(ps_tree_shape), ctypes.POINTER(ps_verify_args), ctypes.c_void_p]
+        lib.ps_verify_walk_static.restype = ctypes.c_int
+        lib.ps_verify_walk_static.argtypes = lib.ps_verify_walk.argtypes
+        lib.ps_verify_workspace_bytes.restype = ctypes.c_size_t
+        lib.ps_verify_workspace_bytes.argtypes = [ctypes.c_int32, ctypes.c_int32]
         _ready = True
     return lib
 
@@ -61,3 +66,12 @@ def ps_tree_tokens(tree, batch, rows, topk, top_ids_ptr, tokens_ptr, stream_ptr)
 def ps_verify_walk(tree, args, stream_ptr):
     return _lib().ps_verify_walk(ctypes.byref(tree) if tree is not None else None,
                                  ctypes.byref(args) if args is not None else None, stream_ptr)
+
+
+def ps_verify_walk_static(tree, args, stream_ptr):
+    return _lib().ps_verify_walk_static(ctypes.byref(tree) if tree is not None else None,
+                                        ctypes.byref(args) if args is not None else None, stream_ptr)
+
+
+def ps_verify_workspace_bytes(batch, vocab):
+    return int(_lib().ps_verify_workspace_bytes(batch, vocab))

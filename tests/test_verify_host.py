@@ -27,7 +27,7 @@ def _header_code():
 
 
 def test_every_declared_symbol_is_exported(lib):
-    declared = sorted(set(re.findall(r"\bPS_API\s+int\s+(ps_[a-z_]+)\s*\(", _header_code())))
+    declared = sorted(set(re.findall(r"\bPS_API\s+[a-z_]+\s+(ps_[a-z_]+)\s*\(", _header_code())))
     assert declared == sorted(VF.EXPORTED_SYMBOLS)
     for name in declared:
         assert getattr(lib, name) is not None
@@ -71,6 +71,31 @@ def test_walk_rejects_bad_arguments_on_the_host(lib):
     for parent in ([0, 0], [-1, 1], [-1, -1], [-1, 0, 3], [-1] + [0] * 64, []):
         t = VF.make_tree(np.array(parent, dtype=np.int32), np.zeros(len(parent), dtype=np.int32))
         assert VF.ps_verify_walk(t, _args(rows=64), None) == B.PS_ERR_SHAPE, parent
+
+
+def test_static_walk_validates_like_the_walk_and_never_falls_back(lib):
+    """The entry point that allocates nothing: same argument checks; a batch beyond what the library's own
+    exchange memory holds is an error there, not a slower path."""
+    good = VF.make_tree([-1, 0, 0, 1], [0, 0, 1, 0])
+    assert VF.ps_verify_walk_static(None, _args(), None) == B.PS_ERR_NULL
+    assert VF.ps_verify_walk_static(good, None, None) == B.PS_ERR_NULL
+    for n in ("tokens", "q", "p", "r", "n_accepted", "path", "out_tokens"):
+        assert VF.ps_verify_walk_static(good, _args(**{n: None}), None) == B.PS_ERR_NULL, n
+    for kw in (dict(batch=0), dict(rows=0), dict(vocab=0), dict(rows=1)):
+        assert VF.ps_verify_walk_static(good, _args(**kw), None) == B.PS_ERR_SHAPE, kw
+    assert VF.ps_verify_walk_static(good, _args(vocab=1048580), None) == B.PS_ERR_UNSUPPORTED
+    assert VF.ps_verify_walk_static(good, _args(vocab=128256, batch=65), None) == B.PS_ERR_UNSUPPORTED
+    assert VF.ps_verify_walk_static(good, _args(vocab=65536, batch=200), None) == B.PS_ERR_UNSUPPORTED
+
+
+def test_workspace_bytes(lib):
+    assert VF.ps_verify_workspace_bytes(8, 32000) == 0          # P stays in registers: nothing to exchange
+    assert VF.ps_verify_workspace_bytes(8, 32768) == 0
+    assert VF.ps_verify_workspace_bytes(8, 50001) == 0          # odd: one workgroup per sequence
+    assert VF.ps_verify_workspace_bytes(0, 128256) == 0
+    one, eight = VF.ps_verify_workspace_bytes(1, 128256), VF.ps_verify_workspace_bytes(8, 128256)
+    assert one % 256 == 0 and eight % 256 == 0 and 0 < one < eight <= 8 * one
+    assert VF.ps_verify_workspace_bytes(64, 128256) == 1065472  # the size of the library's own array (stated in the header)
 
 
 def test_tree_tokens_rejects_bad_arguments_on_the_host(lib):
