@@ -311,6 +311,39 @@ __device__ __forceinline__ u64 wave_max_u64(u64 v) {
     return ((u64)hi << 32) | lo;
 }
 
+// The same reductions over a DPP row (16 lanes): four exchanges, the result in every lane of the row
+#define PS_DPP_ROW_STEPS(COMBINE)                                                    \
+    COMBINE(0xB1, 0xF)  /* quad_perm [1,0,3,2] */                                    \
+    COMBINE(0x4E, 0xF)  /* quad_perm [2,3,0,1] */                                    \
+    COMBINE(0x141, 0xF) /* row_half_mirror */                                        \
+    COMBINE(0x140, 0xF) /* row_mirror */
+__device__ __forceinline__ float row_sum(float v) {
+#define PS_C(CTRL, RM) { const float o = __uint_as_float(dpp_u32<CTRL, RM>(0u, __float_as_uint(v))); v += o; }
+    PS_DPP_ROW_STEPS(PS_C)
+#undef PS_C
+    return v;
+}
+__device__ __forceinline__ unsigned row_max_u32(unsigned v) {
+#define PS_C(CTRL, RM) { const unsigned o = dpp_u32<CTRL, RM>(0u, v); v = o > v ? o : v; }
+    PS_DPP_ROW_STEPS(PS_C)
+#undef PS_C
+    return v;
+}
+__device__ __forceinline__ float row_max(float v) {
+    const unsigned u = __float_as_uint(v);
+    const unsigned m = row_max_u32(u ^ ((u >> 31) ? 0xFFFFFFFFu : 0x80000000u));
+    return __uint_as_float(m ^ ((m >> 31) ? 0x80000000u : 0xFFFFFFFFu));
+}
+__device__ __forceinline__ u64 row_max_u64(u64 v) {
+    const unsigned hi = row_max_u32((unsigned)(v >> 32));
+    const unsigned lo = row_max_u32((unsigned)(v >> 32) == hi ? (unsigned)v : 0u);
+    return ((u64)hi << 32) | lo;
+}
+// over LPR = 64 (the wavefront) or 16 (a row) lanes
+template <int LPR> __device__ __forceinline__ float grp_sum(float v) { if constexpr (LPR == 64) return wave_sum(v); else return row_sum(v); }
+template <int LPR> __device__ __forceinline__ float grp_max(float v) { if constexpr (LPR == 64) return wave_max(v); else return row_max(v); }
+template <int LPR> __device__ __forceinline__ u64 grp_max_u64(u64 v) { if constexpr (LPR == 64) return wave_max_u64(v); else return row_max_u64(v); }
+
 // ---- top-k keys: (logit, id) packed so that unsigned comparison orders by larger logit first,
 // equal logits by lower id.  Key 0 means "none".
 __device__ __forceinline__ u64 make_key(float v, int id) {
@@ -410,14 +443,22 @@ __device__ __forceinline__ int lm_src_row(const StepParams& P, int r) {
 // B operands (activation columns) of one step for all column tiles, read from the LDS panel
 template <typename WT, int MT> struct BRegs { uint4 h[MT]; uint4 l[MT]; };
 
+// (the panel's addresses are kept as LDS pointers, not generic ones: a generic pointer that the compiler
+// cannot trace back to LDS becomes a flat load, which counts as a global-memory operation and makes every
+// wait in the streaming loop wait for all the weight loads in flight)
+typedef const __attribute__((address_space(3))) char* lds_cptr;
+__device__ __forceinline__ uint4 ld16_lds(lds_cptr p) {
+    const u32x4 v = *reinterpret_cast<const __attribute__((address_space(3))) u32x4*>(p);
+    return make_uint4(v[0], v[1], v[2], v[3]);
+}
 template <typename WT, int MT>
-__device__ __forceinline__ void load_b(BRegs<WT, MT>& b, const char* const (&pa)[MT], const int (&pinc)[MT],
+__device__ __forceinline__ void load_b(BRegs<WT, MT>& b, const lds_cptr (&pa)[MT], const int (&pinc)[MT],
                                        const int (&plo)[MT], int t) {
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
-        const char* p = pa[mt] + t * pinc[mt];
-        b.h[mt] = ld16(p);
-        if constexpr (Traits<WT>::BF) b.l[mt] = ld16(p + plo[mt]);
+        const lds_cptr p = pa[mt] + t * pinc[mt];
+        b.h[mt] = ld16_lds(p);
+        if constexpr (Traits<WT>::BF) b.l[mt] = ld16_lds(p + plo[mt]);
     }
 }
 
@@ -459,7 +500,7 @@ __device__ __forceinline__ void preload_weights(uint4 (&wb)[PS_U], const char* b
 // head of that stream.  Every load is unconditional and only the oldest is waited for.
 template <typename WT, int MT>
 __device__ __forceinline__ void consume_weights(uint4 (&wb)[PS_U], const char* wp, int n, const char* next_wp, int lane16,
-                                                const char* const (&pa)[MT], const int (&pinc)[MT],
+                                                const lds_cptr (&pa)[MT], const int (&pinc)[MT],
                                                 const int (&plo)[MT], f32x4 (&acc)[MT]) {
     constexpr int U = PS_U;
     BRegs<WT, MT> bc, bn;
@@ -762,6 +803,68 @@ __device__ __forceinline__ void stage_piece(const StepParams& P, const PhaseDesc
     }
 }
 
+// Softmax statistics and top-k of the logits a workgroup holds in LDS (s_lm[local tile][row][16]) for its
+// vocabulary tiles: per output row the maximum, the sum of exponentials against it and the topk largest keys
+// in order go to lm_part as tagged data.  LPR lanes share a row; the keys are unique, so "the largest key below
+// the previous winner" enumerates them in order.
+template <int LPR>
+__device__ __forceinline__ void lm_local_stats(const StepParams& P, const PhaseDesc& D, int j, int rows, const float* s_lm,
+                                               int wave, int lane, int sl_log, int SL) {
+    constexpr int GPW = 64 / LPR;               // rows a wavefront works on at a time
+    constexpr int EPL = LPR == 64 ? 8 : 16;     // elements per lane kept in registers (more: re-read from LDS)
+    const int n_el = D.rounds * SL * 16;
+    const int li = lane & (LPR - 1), grp = lane / LPR;
+    const int topk = P.topk;
+    const rsrc_t rl = make_rsrc(P.lm_part);
+    const unsigned stride = 2 + 2 * topk;       // tagged elements: max, sum exp, topk keys (low, high word)
+    const unsigned seq = ps_seq();
+    for (int m0 = wave; m0 < rows; m0 += PS_WAVES * GPW) {
+        const int mm = m0 + grp * PS_WAVES;
+        const bool live = mm < rows;
+        const int m = live ? mm : m0;           // lanes without a row of their own repeat the wavefront's first (and store nothing)
+        u64 keys[EPL];
+        float mx = -INFINITY;
+#pragma unroll
+        for (int i = 0; i < EPL; ++i) {
+            const int x = li + LPR * i;
+            keys[i] = 0;
+            if (x < n_el) {
+                const int lt = x >> 4;
+                const float v = s_lm[(lt * rows + m) * 16 + (x & 15)];
+                const int id = 16 * tile_index(D, lt >> sl_log, lt & (SL - 1), j) + (x & 15);
+                if (v > -INFINITY) { keys[i] = make_key(v, id); mx = fmaxf(mx, v); }
+            }
+        }
+        for (int x = li + LPR * EPL; x < n_el; x += LPR) mx = fmaxf(mx, s_lm[((x >> 4) * rows + m) * 16 + (x & 15)]);
+        mx = grp_max<LPR>(mx);
+        float se = 0.f;
+        if (mx > -INFINITY)
+            for (int x = li; x < n_el; x += LPR) se += expf(s_lm[((x >> 4) * rows + m) * 16 + (x & 15)] - mx);
+        se = grp_sum<LPR>(se);
+        const unsigned obase = (unsigned)((j * rows + m) * stride);
+        if (live && li < 2) ll_st1(rl, obase + li, li ? se : mx, seq);
+        const int nepl = min(EPL, (n_el + LPR - 1) / LPR);   // registers per lane that hold elements
+        u64 prev = ~0ull;
+        for (int t = 0; t < topk; ++t) {
+            u64 best = 0;
+#pragma unroll
+            for (int i = 0; i < EPL; ++i)
+                if (i < nepl && keys[i] < prev && keys[i] > best) best = keys[i];
+            for (int x = li + LPR * EPL; x < n_el; x += LPR) {
+                const int lt = x >> 4;
+                const float v = s_lm[(lt * rows + m) * 16 + (x & 15)];
+                const int id = 16 * tile_index(D, lt >> sl_log, lt & (SL - 1), j) + (x & 15);
+                const u64 kx = v > -INFINITY ? make_key(v, id) : 0;
+                if (kx < prev && kx > best) best = kx;
+            }
+            best = grp_max_u64<LPR>(best);
+            if (live && li < 2)
+                ll_st1(rl, obase + 2 + 2 * t + li, __uint_as_float(li ? (unsigned)(best >> 32) : (unsigned)best), seq);
+            prev = best ? best : 0;   // 0: list exhausted, every later entry is "none"
+        }
+    }
+}
+
 // One phase for one workgroup.  wb: the wavefront's weight-load registers.  On entry they hold
 // the preloaded head of first_stream(ph); on exit they hold PS_U loads from after_wp (the head of
 // whatever this wavefront streams next, or any readable address).
@@ -803,13 +906,13 @@ __device__ __forceinline__ void gemm_phase(const StepParams& P, int wg, int wave
     }
 
     // per-lane panel addressing: column c of column tile mt is activation row 16 mt + c
-    const char* pa[MT];
+    lds_cptr pa[MT];
     int pinc[MT], plo[MT];
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
         const int m = 16 * mt + c;
-        if (m < rows) { pa[mt] = s_pa + m * RS + kb * 16; pinc[mt] = 64; plo[mt] = (int)(s_pb - s_pa); }
-        else { pa[mt] = s_zero + kb * 16; pinc[mt] = 0; plo[mt] = 0; }
+        if (m < rows) { pa[mt] = (lds_cptr)(s_pa + m * RS + kb * 16); pinc[mt] = 64; plo[mt] = (int)(s_pb - s_pa); }
+        else { pa[mt] = (lds_cptr)(s_zero + kb * 16); pinc[mt] = 0; plo[mt] = 0; }
     }
     int sg_lo, sg_hi;
     slice_groups(D, s, sg_lo, sg_hi);
@@ -862,7 +965,7 @@ __device__ __forceinline__ void gemm_phase(const StepParams& P, int wg, int wave
                 } else if (rd + 1 < D.rounds && tile_index(D, rd + 1, slot, j) < D.T) {
                     next_wp = stream_ptr(D, tile_index(D, rd + 1, slot, j), sg_lo, min(D.piece_groups, sg_hi - sg_lo), kw, na, nn);
                 }
-                const char* pa_t[MT];
+                lds_cptr pa_t[MT];
 #pragma unroll
                 for (int mt = 0; mt < MT; ++mt) pa_t[mt] = pa[mt] + a0 * pinc[mt];
                 consume_weights<WT, MT>(wb, wp, n, next_wp, lane16, pa_t, pinc, plo, acc);
@@ -973,56 +1076,12 @@ __device__ __forceinline__ void gemm_phase(const StepParams& P, int wg, int wave
     if (!streamed) preload_weights(wb, after_wp, lane16);   // keep the contract on wb
 
     if (ph == PH_LMHEAD) {
-        // per-workgroup softmax statistics and top-k over the logits held in LDS: one wavefront per row
+        // per-workgroup softmax statistics and top-k over the logits held in LDS: a whole wavefront takes a
+        // row; with more rows than wavefronts 16 lanes do (four rows per wavefront at a time) as long as a
+        // lane's share of the row's logits fits its registers
         __syncthreads();
-        const int n_el = D.rounds * SL * 16;
-        const int topk = P.topk;
-        const rsrc_t rl = make_rsrc(P.lm_part);
-        const unsigned stride = 2 + 2 * topk;   // tagged elements: max, sum exp, topk keys (low, high word)
-        const unsigned seq = ps_seq();
-        for (int m = wave; m < rows; m += PS_WAVES) {
-            constexpr int EPL = 8;   // elements per lane kept in registers (more: re-read from LDS)
-            u64 keys[EPL];
-            float mx = -INFINITY;
-#pragma unroll
-            for (int i = 0; i < EPL; ++i) {
-                const int x = lane + 64 * i;
-                keys[i] = 0;
-                if (x < n_el) {
-                    const int lt = x >> 4;
-                    const float v = s_lm[(lt * rows + m) * 16 + (x & 15)];
-                    const int id = 16 * tile_index(D, lt >> sl_log, lt & (SL - 1), j) + (x & 15);
-                    if (v > -INFINITY) { keys[i] = make_key(v, id); mx = fmaxf(mx, v); }
-                }
-            }
-            for (int x = lane + 64 * EPL; x < n_el; x += 64) mx = fmaxf(mx, s_lm[((x >> 4) * rows + m) * 16 + (x & 15)]);
-            mx = wave_max(mx);
-            float se = 0.f;
-            if (mx > -INFINITY)
-                for (int x = lane; x < n_el; x += 64) se += expf(s_lm[((x >> 4) * rows + m) * 16 + (x & 15)] - mx);
-            se = wave_sum(se);
-            const unsigned obase = (unsigned)((j * rows + m) * stride);
-            if (lane < 2) ll_st1(rl, obase + lane, lane ? se : mx, seq);
-            const int nepl = min(EPL, (n_el + 63) >> 6);   // registers per lane that hold elements
-            u64 prev = ~0ull;   // keys are unique: the next winner is the largest key below the previous one
-            for (int t = 0; t < topk; ++t) {
-                u64 best = 0;
-#pragma unroll
-                for (int i = 0; i < EPL; ++i)
-                    if (i < nepl && keys[i] < prev && keys[i] > best) best = keys[i];
-                for (int x = lane + 64 * EPL; x < n_el; x += 64) {
-                    const int lt = x >> 4;
-                    const float v = s_lm[(lt * rows + m) * 16 + (x & 15)];
-                    const int id = 16 * tile_index(D, lt >> sl_log, lt & (SL - 1), j) + (x & 15);
-                    const u64 kx = v > -INFINITY ? make_key(v, id) : 0;
-                    if (kx < prev && kx > best) best = kx;
-                }
-                best = wave_max_u64(best);
-                if (lane < 2)
-                    ll_st1(rl, obase + 2 + 2 * t + lane, __uint_as_float(lane ? (unsigned)(best >> 32) : (unsigned)best), seq);
-                prev = best ? best : 0;   // 0: list exhausted, every later entry is "none"
-            }
-        }
+        if (rows > PS_WAVES && D.rounds * SL * 16 <= 16 * 16) lm_local_stats<16>(P, D, j, rows, s_lm, wave, lane, sl_log, SL);
+        else lm_local_stats<64>(P, D, j, rows, s_lm, wave, lane, sl_log, SL);
     }
     stamp(P, wg, 2 + ph * 6 + 5);
 }
@@ -1512,6 +1571,7 @@ __device__ __forceinline__ void attn_phase(const StepParams& P, int wg, int nwg,
     constexpr int PP = D / 2;                        // column pairs per row
     const int RT = (Ra + MR - 1) / MR;
     float* sW = sP;                                  // [MR][GRP] weights (the probabilities' area: same size)
+    constexpr int SEP_ML = 64;                       // (max, sum) of the step's own rows: sM / sL [SEP_ML + row], beside the groups' [row]
     for (int mi = wg; mi < P.attn_merge_items; mi += nwg) {
         int b = 0, rem = mi, nch = 0, item_base = 0;
         for (;; ++b) {
@@ -1527,6 +1587,78 @@ __device__ __forceinline__ void attn_phase(const StepParams& P, int wg, int nwg,
         const int myrow = tid / PP, dp = tid - myrow * PP;
         const bool active = myrow < nr;
         float num0 = 0.f, num1 = 0.f, den = 0.f, mrun = -INFINITY;
+        if (P.attn_sep) {
+            // The rows written in this step are not part of any block: wavefront w works out row w's
+            // attention over them (at most 16 keys, a lane owns DPL columns of q, K and V, the dot
+            // products are wavefront sums); the result is folded in after the blocks like one more group of
+            // them.  This comes first: its inputs (the QKV phase's outputs) are there long before the last
+            // block's partial results, so it runs while those are still being produced.
+            __syncthreads();                         // the previous item is done with the output area
+            if (wave < nr) {
+                const int rho = r0 + wave;
+                const int gi = row_seq(P, rho), i = rho - gi * P.M;
+                const rsrc_t rq = make_rsrc(act_ptr(P, P.q_buf)), rn = make_rsrc(act_ptr(P, P.kvnew));
+                const unsigned qo = (unsigned)((size_t)(b * P.M + i) * P.QD + (hk * grp + gi) * D + DPL * lane);
+                float q[DPL], kx[16][DPL], vx[16][DPL];
+                auto issue_new = [&]() __attribute__((always_inline)) {
+#pragma unroll
+                    for (int e = 0; e < DPL; ++e) q[e] = coh_ld_f(rq, (qo + e) * 4);
+#pragma unroll
+                    for (int jj = 0; jj < 16; ++jj) {
+                        const int jc = jj < P.M ? jj : P.M - 1;     // clamped: every load is unconditional
+                        const unsigned ko = (unsigned)(((size_t)(b * P.M + jc) * 2) * P.KVD + hk * D + DPL * lane);
+#pragma unroll
+                        for (int e = 0; e < DPL; ++e) {
+                            kx[jj][e] = coh_ld_f(rn, (ko + e) * 4);
+                            vx[jj][e] = coh_ld_f(rn, (ko + P.KVD + e) * 4);
+                        }
+                    }
+                };
+                auto bad_new = [&]() __attribute__((always_inline)) {
+                    unsigned bad = 0;
+#pragma unroll
+                    for (int e = 0; e < DPL; ++e) bad |= (unsigned)(__float_as_uint(q[e]) == PS_SENT);
+#pragma unroll
+                    for (int jj = 0; jj < 16; ++jj)
+#pragma unroll
+                        for (int e = 0; e < DPL; ++e)
+                            bad |= (unsigned)(__float_as_uint(kx[jj][e]) == PS_SENT) | (unsigned)(__float_as_uint(vx[jj][e]) == PS_SENT);
+                    return bad;
+                };
+                issue_new();
+                if (!__all(!bad_new())) {
+                    int spins = 0;
+                    do issue_new(); while (!__all(!bad_new()) && spin_again(P, spins));
+                }
+                float sc[16], mn = -INFINITY;
+#pragma unroll
+                for (int jj = 0; jj < 16; ++jj) {
+                    sc[jj] = -INFINITY;
+                    if (jj <= i) {                   // wavefront-uniform: row i sees the rows 0 .. i of this step
+                        float part = 0.f;
+#pragma unroll
+                        for (int e = 0; e < DPL; ++e) part += q[e] * kx[jj][e];
+                        sc[jj] = wave_sum(part) * P.inv_sqrt_d;
+                        mn = fmaxf(mn, sc[jj]);
+                    }
+                }
+                float ln = 0.f, on[DPL];
+#pragma unroll
+                for (int e = 0; e < DPL; ++e) on[e] = 0.f;
+#pragma unroll
+                for (int jj = 0; jj < 16; ++jj) {
+                    if (jj <= i) {
+                        const float pj = expf(sc[jj] - mn);
+                        ln += pj;
+#pragma unroll
+                        for (int e = 0; e < DPL; ++e) on[e] += pj * vx[jj][e];
+                    }
+                }
+#pragma unroll
+                for (int e = 0; e < DPL; ++e) sO[wave * D + DPL * lane + e] = on[e];
+                if (lane == 0) { sM[SEP_ML + wave] = mn; sL[SEP_ML + wave] = ln; }
+            }
+        }
         for (int g0 = 0; g0 < nch; g0 += GRP) {
             const int gn = min(GRP, nch - g0);
             __syncthreads();                         // the weights of the previous group (or item) are no longer read
@@ -1617,77 +1749,10 @@ __device__ __forceinline__ void attn_phase(const StepParams& P, int wg, int nwg,
             }
         }
         if (P.attn_sep) {
-            // The rows written in this step are not part of any block: wavefront w works out row w's
-            // attention over them (at most 16 keys, a lane owns DPL columns of q, K and V, the dot
-            // products are wavefront sums) and the result is folded in like one more group of blocks.
-            __syncthreads();                         // sM, sL and the output area are free
-            if (wave < nr) {
-                const int rho = r0 + wave;
-                const int gi = row_seq(P, rho), i = rho - gi * P.M;
-                const rsrc_t rq = make_rsrc(act_ptr(P, P.q_buf)), rn = make_rsrc(act_ptr(P, P.kvnew));
-                const unsigned qo = (unsigned)((size_t)(b * P.M + i) * P.QD + (hk * grp + gi) * D + DPL * lane);
-                float q[DPL], kx[16][DPL], vx[16][DPL];
-                auto issue_new = [&]() __attribute__((always_inline)) {
-#pragma unroll
-                    for (int e = 0; e < DPL; ++e) q[e] = coh_ld_f(rq, (qo + e) * 4);
-#pragma unroll
-                    for (int jj = 0; jj < 16; ++jj) {
-                        const int jc = jj < P.M ? jj : P.M - 1;     // clamped: every load is unconditional
-                        const unsigned ko = (unsigned)(((size_t)(b * P.M + jc) * 2) * P.KVD + hk * D + DPL * lane);
-#pragma unroll
-                        for (int e = 0; e < DPL; ++e) {
-                            kx[jj][e] = coh_ld_f(rn, (ko + e) * 4);
-                            vx[jj][e] = coh_ld_f(rn, (ko + P.KVD + e) * 4);
-                        }
-                    }
-                };
-                auto bad_new = [&]() __attribute__((always_inline)) {
-                    unsigned bad = 0;
-#pragma unroll
-                    for (int e = 0; e < DPL; ++e) bad |= (unsigned)(__float_as_uint(q[e]) == PS_SENT);
-#pragma unroll
-                    for (int jj = 0; jj < 16; ++jj)
-#pragma unroll
-                        for (int e = 0; e < DPL; ++e)
-                            bad |= (unsigned)(__float_as_uint(kx[jj][e]) == PS_SENT) | (unsigned)(__float_as_uint(vx[jj][e]) == PS_SENT);
-                    return bad;
-                };
-                issue_new();
-                if (!__all(!bad_new())) {
-                    int spins = 0;
-                    do issue_new(); while (!__all(!bad_new()) && spin_again(P, spins));
-                }
-                float sc[16], mn = -INFINITY;
-#pragma unroll
-                for (int jj = 0; jj < 16; ++jj) {
-                    sc[jj] = -INFINITY;
-                    if (jj <= i) {                   // wavefront-uniform: row i sees the rows 0 .. i of this step
-                        float part = 0.f;
-#pragma unroll
-                        for (int e = 0; e < DPL; ++e) part += q[e] * kx[jj][e];
-                        sc[jj] = wave_sum(part) * P.inv_sqrt_d;
-                        mn = fmaxf(mn, sc[jj]);
-                    }
-                }
-                float ln = 0.f, on[DPL];
-#pragma unroll
-                for (int e = 0; e < DPL; ++e) on[e] = 0.f;
-#pragma unroll
-                for (int jj = 0; jj < 16; ++jj) {
-                    if (jj <= i) {
-                        const float pj = expf(sc[jj] - mn);
-                        ln += pj;
-#pragma unroll
-                        for (int e = 0; e < DPL; ++e) on[e] += pj * vx[jj][e];
-                    }
-                }
-#pragma unroll
-                for (int e = 0; e < DPL; ++e) sO[wave * D + DPL * lane + e] = on[e];
-                if (lane == 0) { sM[wave] = mn; sL[wave] = ln; }
-            }
+            // fold in the attention over the rows written in this step (worked out first, see above)
             __syncthreads();
             if (active) {
-                const float mg = sM[myrow], lg = sL[myrow];
+                const float mg = sM[SEP_ML + myrow], lg = sL[SEP_ML + myrow];
                 const float mnew = fmaxf(mrun, mg);
                 const float so = expf(mrun - mnew), sn = expf(mg - mnew);
                 num0 = num0 * so + sO[myrow * D + 2 * dp] * sn;
@@ -1756,7 +1821,7 @@ __device__ __forceinline__ void lm_merge_row(const StepParams& P, int m, int wav
         for (int i = 0; i < KB; ++i)
             keys[t0 + i] = (mine && t0 + i < topk) ? (((u64)kr[i][2] << 32) | kr[i][0]) : 0;
     }
-    if (m == (int)blockIdx.x) stamp(P, blockIdx.x, 41);
+    stamp(P, blockIdx.x, 41);
     // Has any wait of this step been given up (see spin_again)?  Whoever gave up raised the flag before it
     // published anything, so now that all statistics of the row are here the flag tells; requested here,
     // looked at when the outputs are written.
@@ -1786,7 +1851,7 @@ __device__ __forceinline__ void lm_merge_row(const StepParams& P, int m, int wav
     const float wsum = wave_sum(pmax > -INFINITY ? psum * expf(pmax - mx) : 0.f);
     if (lane == 0) sf[PS_WAVES + wave] = wsum;
     __syncthreads();
-    if (m == (int)blockIdx.x) stamp(P, blockIdx.x, 42);
+    stamp(P, blockIdx.x, 42);
     if (wave == 0) {
         float se = 0.f;
 #pragma unroll
@@ -1922,9 +1987,10 @@ __global__ void __launch_bounds__(PS_WG_THREADS, 1) fused_kernel(const StepParam
     __syncthreads();
     gemm_phase<WT, MT, PH_LMHEAD>(P, wg, wave, smem, wb, P.ph[PH_QKV].wpack);
     __syncthreads();
-    // output row m is merged by workgroup m mod gridDim.x
+    // output row m is merged by the m-th workgroup from the end: the last workgroups have the fewest
+    // vocabulary tiles (the last round of tiles is not full), so they are the first to be ready for it
     stamp(P, wg, 40);
-    for (int m = wg; m < P.Rtot; m += gridDim.x) lm_merge_row(P, m, wave, smem + 256);
+    for (int m = (int)gridDim.x - 1 - wg; m < P.Rtot; m += gridDim.x) lm_merge_row(P, m, wave, smem + 256);
     sx_reset_stale(P, wg, gridDim.x);   // here most workgroups have nothing left to do
     step_end(P, ticket, gridDim.x);
     stamp(P, wg, 62);
