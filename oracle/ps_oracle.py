@@ -97,7 +97,7 @@ def top_k(logits_row, k):
 
 # ---------------------------------------------------------------- the draft step
 def draft_step(shape, weights, x, k_cache, v_cache, kv_offsets, kv_len, n_new, k, topk,
-               all_rows=False, return_attn=False):
+               all_rows=False, return_attn=False, x_is_float=False):
     """One parallel draft step for a batch of independent sequences.
 
     shape      : object with hidden, n_heads, n_kv_heads, head_dim, ffn, vocab, dtype,
@@ -105,6 +105,7 @@ def draft_step(shape, weights, x, k_cache, v_cache, kv_offsets, kv_len, n_new, k
     weights    : dict of stored tensors (g_in, wq, wk, wv, wo, g_post, w_gate, w_up,
                  w_down, g_final, w_lm, mask_emb), row-major [out, in]
     x          : [B, n_new, hidden] stored hidden states of the newly accepted positions
+                 (x_is_float: float64 values instead, e.g. the output of oracle.input_stage.fused_input)
     k_cache, v_cache : [total_positions, n_kv_heads, head_dim] stored; K is post-RoPE.
                  NOT modified; updated copies are returned.
     kv_offsets : [B+1]; sequence b owns rows [off[b], off[b+1])
@@ -117,8 +118,8 @@ def draft_step(shape, weights, x, k_cache, v_cache, kv_offsets, kv_len, n_new, k
     grp = nq // nkv
     B = len(kv_len)
     M = n_new + k
-    W = {name: widen(w, dt) for name, w in weights.items()}
-    X = widen(x, dt)
+    W = {name: widen(w, dt) for name, w in weights.items() if w is not None}
+    X = np.asarray(x, dtype=np.float64) if x_is_float else widen(x, dt)
     kc = np.array(k_cache, copy=True)
     vc = np.array(v_cache, copy=True)
     rows = list(range(M)) if all_rows else list(range(n_new - 1, M))

@@ -16,7 +16,8 @@ import numpy as np
 _TENSOR_IDS = {
     "g_in": 1, "wq": 2, "wk": 3, "wv": 4, "wo": 5, "g_post": 6, "w_gate": 7, "w_up": 8,
     "w_down": 9, "g_final": 10, "w_lm": 11, "mask_emb": 12, "x": 13, "k_cache": 14,
-    "v_cache": 15, "kv_len": 16, "n_new_mix": 17,
+    "v_cache": 15, "kv_len": 16, "n_new_mix": 17, "embed": 18, "w_fc": 19, "b_fc": 20, "token_ids": 21,
+    "features": 22, "uniforms": 23,
 }
 
 
@@ -69,6 +70,29 @@ def make_weights(shape, seed):
         "mask_emb": _normal(seed, "mask_emb", (s.k_max, s.hidden), 1.0, 0.0, dt),
     }
     return w
+
+
+def make_input_stage_weights(shape, seed, fc=True, bias=True):
+    """The shared embedding table ~ N(0, 1) like the hidden states it stands for, and the input projection
+    [H, 2H] ~ N(0, 0.02) * (1 / sqrt(2 H) / 0.02 ...) scaled so that its output has about unit scale, with a
+    bias ~ N(0, 0.02); bf16 tensors as uint16 bits."""
+    s, dt = shape, shape.dtype
+    w = {"embed": _normal(seed, "embed", (s.vocab, s.hidden), 1.0, 0.0, dt)}
+    if fc:
+        w["w_fc"] = _normal(seed, "w_fc", (s.hidden, 2 * s.hidden), float(1.0 / np.sqrt(2.0 * s.hidden)), 0.0, dt)
+        if bias:
+            w["b_fc"] = _normal(seed, "b_fc", (s.hidden,), 0.02, 0.0, dt)
+    return w
+
+
+def make_input_stage_inputs(workload, n_new=None, sub=0):
+    """Token ids uniform in [0, V) and target features ~ N(0, 1) for the real rows of a step."""
+    s = workload.shape
+    n_new = workload.n_new if n_new is None else n_new
+    g = _rng(workload.seed, "token_ids", sub)
+    ids = g.integers(0, s.vocab, size=(workload.batch, n_new)).astype(np.int32)
+    feats = _normal(workload.seed, "features", (workload.batch, n_new, s.hidden), 1.0, 0.0, s.dtype, sub=sub)
+    return {"token_ids": ids, "features": feats}
 
 
 def draw_kv_len(workload):
