@@ -339,6 +339,57 @@ def timeline(torch, wl, steps=30):
     drafter.close()
 
 
+def input_stage_report(torch, name="c1", steps=200, warmup=20):
+    """The draft step with its input stage fused in (Section 4.3), on workload `name`: token ids instead of hidden
+    states (the real rows are gathered from the shared embedding table), and token ids + target features through
+    the fully connected layer (a small-M GEMM kernel in front of the persistent kernel).  Latency per step from HIP
+    events; algorithmic bytes = the step's + what the input stage has to read (the projection's weights once, the
+    gathered embedding rows, the features)."""
+    from paper_2410_05589_amd import binding as B
+    from paper_2410_05589_amd import inputs
+    from paper_2410_05589_amd.configs import WORKLOADS
+    wl = WORKLOADS[name]
+    shape = wl.shape
+    esz = 2 if shape.dtype == "bf16" else 4
+    w = inputs.make_weights(shape, wl.seed)
+    w.update(inputs.make_input_stage_weights(shape, wl.seed))
+    kv_len = inputs.draw_kv_len(wl)
+    inp = inputs.make_step_inputs(wl, kv_len=kv_len)
+    tin = inputs.make_input_stage_inputs(wl)
+    d = B.Drafter(shape, w, max_batch=wl.batch, max_new=wl.n_new, max_positions=max(kv_len) + wl.m, max_topk=wl.topk, k_max=wl.k)
+    dev = {n: B.to_device(inp[n], shape.dtype) for n in ("x", "k_cache", "v_cache")}
+    tok = torch.from_numpy(tin["token_ids"]).to("cuda:0")
+    feat = B.to_device(tin["features"], shape.dtype)
+    outs = d.alloc_outputs(wl.batch, wl.n_new, wl.k, wl.topk)
+    base = algorithmic_bytes(wl, kv_len, wl.n_new, wl.k)["total"]
+    rows = wl.batch * wl.n_new
+    modes = {"hidden_states": (dict(x=dev["x"]), base),
+             "token_ids": (dict(x=None, token_ids=tok), base),     # (the gathered rows replace the x rows: same bytes)
+             "token_ids_and_features": (dict(x=None, token_ids=tok, features=feat),
+                                        base + (2 * shape.hidden * shape.hidden + shape.hidden + rows * shape.hidden) * esz)}
+    rep = {"workload": name}
+    stream = torch.cuda.current_stream()
+    for mode, (kw, nbytes) in modes.items():
+        a = d.make_args(kw.pop("x"), dev["k_cache"], dev["v_cache"], inp["kv_offsets"], inp["kv_len"], wl.n_new, wl.k, wl.topk, outs, **kw)
+        for _ in range(warmup):
+            d.step(a)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(steps):
+            d.step(a)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) * 1e3 / steps
+        gbs = nbytes / (us * 1e-6) / 1e9
+        rep[mode] = {"latency_us": round(us, 2), "algorithmic_bytes": int(nbytes),
+                     "roofline": {"bound": "hbm", "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                                  "frac": round(gbs / PEAK_HBM_GBS, 4), "traffic": None}}
+    assert d.last_status() == 0
+    d.close()
+    return rep
+
+
 def verify_walk_report(torch, with_oracle, vocab=32000, k=5, calls=200):
     """Tree construction + acceptance walk (the step after the draft step in Algorithm 1) on a tree of the
     workload's drafter: 61 nodes (fan-out 4, 2, 2, 1, 1 over the k+1 = 6 draft rows) for k = 5, 46 nodes
@@ -482,7 +533,8 @@ def main():
     result["stream_read"] = stream_read_report(torch)
     if not args.no_next_rows:
         hw = WORKLOADS[HEADLINE if args.workload == "all" else args.workload]
-        result["next_rows"] = {"verify_walk": verify_walk_report(torch, not args.no_cpu_baseline, vocab=hw.shape.vocab, k=hw.k)}
+        result["next_rows"] = {"verify_walk": verify_walk_report(torch, not args.no_cpu_baseline, vocab=hw.shape.vocab, k=hw.k),
+                               "input_stage": input_stage_report(torch)}
     print(json.dumps(result))
 
 

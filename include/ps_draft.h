@@ -52,6 +52,7 @@ enum ps_status {
 };
 
 #define PS_FLAG_FINAL_NORM 1u /* apply the RMSNorm with gain g_final before the LM head */
+#define PS_FLAG_INPUT_FC 2u   /* the drafter has the input projection w_fc (feature-fusion input mode, see ps_draft_step_args) */
 
 /*
  * Shape of the drafter layer and bounds of the step.  Supported by this build:
@@ -101,6 +102,14 @@ typedef struct ps_draft_weights {
     const void* g_final;  /* [H]                 gain of the final RMSNorm (may be NULL without PS_FLAG_FINAL_NORM) */
     const void* w_lm;     /* [V, H]              LM head shared with the target model */
     const void* mask_emb; /* [k_max, H]          embeddings of [MASK]_1..[MASK]_k_max (may be NULL if k_max == 0) */
+    /* Input stage (Section 4.3).  The drafter shares the target's embedding layer, frozen, to which the k [MASK]
+     * tokens were added (mask_emb above are those added rows).  In the feature-level variant (EAGLE integration)
+     * a fully connected layer maps [f ; e] - the target's last-layer hidden state f of a position and the
+     * embedding e of its token - to the drafter's input. */
+    const void* embed;    /* [V, H]              shared embedding table (NULL: steps must pass hidden states x) */
+    const void* w_fc;     /* [H, 2H]             input projection: columns 0..H-1 multiply f, H..2H-1 multiply e
+                                                 (required with PS_FLAG_INPUT_FC, else ignored) */
+    const void* b_fc;     /* [H]                 its bias, or NULL for none */
 } ps_draft_weights;
 
 /*
@@ -138,7 +147,8 @@ typedef struct ps_draft_step_args {
     int32_t k;      /* 0..k_max: [MASK] slots appended (k = 0 is an ordinary decode step) */
     int32_t topk;   /* 1..min(max_topk, vocab): candidates per output row (token tree fan-out, Appendix A.3) */
     int32_t out_rows;
-    const void* x;  /* device [batch, n_new, H], config.dtype: hidden states of the new real positions */
+    const void* x;  /* device [batch, n_new, H], config.dtype: hidden states of the new real positions
+                       (NULL when token_ids is given) */
     void* k_cache;  /* device [total_positions, n_kv_heads, d], config.dtype; keys stored after rotary embedding */
     void* v_cache;  /* device, same layout.  Rows off[b]+kv_len[b] .. +M-1 of both are overwritten. */
     const int64_t* kv_offsets; /* HOST [batch+1], in positions: sequence b owns cache rows [off[b], off[b+1]) */
@@ -149,6 +159,15 @@ typedef struct ps_draft_step_args {
     float* logits;     /* device [batch, rows, V] or NULL */
     float* probs;      /* device [batch, rows, V] or NULL: softmax(logits) */
     float* hidden_out; /* device [batch, M, H] or NULL: layer output before the final norm */
+    /* Input stage fused into the step (Section 4.3), instead of x:
+     *   token_ids alone     the real rows are rows token_ids[b][i] of weights.embed (Medusa integration: the
+     *                       drafter reads token embeddings; [MASK] rows are the added embedding rows mask_emb);
+     *   token_ids, features the real rows are w_fc . [features[b][i] ; embed[token_ids[b][i]]] (+ b_fc), computed in
+     *                       float32 and never rounded to config.dtype (EAGLE integration; needs PS_FLAG_INPUT_FC).
+     *                       The caller pairs feature and token as its drafter was trained; [MASK] rows are mask_emb
+     *                       as they are (a learned [MASK] input needs no projection). */
+    const int32_t* token_ids; /* device [batch, n_new] in [0, V), or NULL */
+    const void* features;     /* device [batch, n_new, H], config.dtype, or NULL */
 } ps_draft_step_args;
 
 /*
@@ -156,6 +175,8 @@ typedef struct ps_draft_step_args {
  * without waiting.  Performs no allocation, no host synchronisation and reads no device
  * memory from the host; kv_offsets and kv_len are read before the call returns.
  * top_ids, top_p and lse are required; logits, probs and hidden_out are optional.
+ * Exactly one of x and token_ids must be given (else PS_ERR_NULL / PS_ERR_SHAPE); token ids are not
+ * range-checked (they are device data): an id outside [0, V) reads outside the embedding table.
  * Steps of one context must not overlap in time (they share the workspace).
  * All arguments are checked and the launch is planned before anything is enqueued or any
  * state of the context changes: a call that returns PS_ERR_NULL, PS_ERR_SHAPE, PS_ERR_OFFSETS,

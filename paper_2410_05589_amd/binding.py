@@ -16,6 +16,7 @@ PS_OK = 0
 PS_ERR_NULL, PS_ERR_CONFIG, PS_ERR_SHAPE, PS_ERR_KV_CAPACITY = -1, -2, -3, -4
 PS_ERR_OFFSETS, PS_ERR_WORKSPACE, PS_ERR_UNSUPPORTED, PS_ERR_DEVICE, PS_ERR_TIMEOUT = -5, -6, -7, -8, -9
 PS_FLAG_FINAL_NORM = 1
+PS_FLAG_INPUT_FC = 2
 
 EXPORTED_SYMBOLS = ("ps_draft_workspace_bytes", "ps_draft_init", "ps_draft_step", "ps_draft_free",
                     "ps_draft_strerror", "ps_draft_set_profile_events", "ps_draft_last_status")
@@ -31,10 +32,11 @@ class ps_draft_config(ctypes.Structure):
 
 
 WEIGHT_NAMES = ("g_in", "wq", "wk", "wv", "wo", "g_post", "w_gate", "w_up", "w_down", "g_final", "w_lm", "mask_emb")
+INPUT_WEIGHT_NAMES = ("embed", "w_fc", "b_fc")       # optional: the input stage
 
 
 class ps_draft_weights(ctypes.Structure):
-    _fields_ = [(n, ctypes.c_void_p) for n in WEIGHT_NAMES]
+    _fields_ = [(n, ctypes.c_void_p) for n in WEIGHT_NAMES + INPUT_WEIGHT_NAMES]
 
 
 class ps_draft_step_args(ctypes.Structure):
@@ -43,7 +45,8 @@ class ps_draft_step_args(ctypes.Structure):
                 ("x", ctypes.c_void_p), ("k_cache", ctypes.c_void_p), ("v_cache", ctypes.c_void_p),
                 ("kv_offsets", ctypes.POINTER(ctypes.c_int64)), ("kv_len", ctypes.POINTER(ctypes.c_int32)),
                 ("top_ids", ctypes.c_void_p), ("top_p", ctypes.c_void_p), ("lse", ctypes.c_void_p),
-                ("logits", ctypes.c_void_p), ("probs", ctypes.c_void_p), ("hidden_out", ctypes.c_void_p)]
+                ("logits", ctypes.c_void_p), ("probs", ctypes.c_void_p), ("hidden_out", ctypes.c_void_p),
+                ("token_ids", ctypes.c_void_p), ("features", ctypes.c_void_p)]
 
 
 _lib = None
@@ -124,7 +127,7 @@ def ps_draft_set_profile_events(ctx, event_handles):
 
 
 # ------------------------------------------------------------------ marshalling helpers
-def make_config(shape, max_batch, max_new, max_positions, max_topk, k_max=None):
+def make_config(shape, max_batch, max_new, max_positions, max_topk, k_max=None, input_fc=False):
     c = ps_draft_config()
     c.hidden, c.n_heads, c.n_kv_heads, c.head_dim = shape.hidden, shape.n_heads, shape.n_kv_heads, shape.head_dim
     c.ffn, c.vocab = shape.ffn, shape.vocab
@@ -132,7 +135,7 @@ def make_config(shape, max_batch, max_new, max_positions, max_topk, k_max=None):
     c.max_batch, c.max_new, c.max_positions, c.max_topk = max_batch, max_new, max_positions, max_topk
     c.dtype = PS_BF16 if shape.dtype == "bf16" else PS_F32
     c.rms_eps, c.rope_base = shape.rms_eps, shape.rope_base
-    c.flags = PS_FLAG_FINAL_NORM if shape.final_norm else 0
+    c.flags = (PS_FLAG_FINAL_NORM if shape.final_norm else 0) | (PS_FLAG_INPUT_FC if input_fc else 0)
     return c
 
 
@@ -161,10 +164,12 @@ class Drafter:
         import torch
         self.torch = torch
         self.shape, self.device = shape, device
-        self.config = make_config(shape, max_batch, max_new, max_positions, max_topk, k_max=k_max)
-        self.weights_dev = {n: to_device(weights_np[n], shape.dtype, device) for n in WEIGHT_NAMES}
+        self.config = make_config(shape, max_batch, max_new, max_positions, max_topk, k_max=k_max,
+                                  input_fc="w_fc" in weights_np)
+        names = WEIGHT_NAMES + tuple(n for n in INPUT_WEIGHT_NAMES if n in weights_np)
+        self.weights_dev = {n: to_device(weights_np[n], shape.dtype, device) for n in names}
         self.weights = ps_draft_weights()
-        for n in WEIGHT_NAMES:
+        for n in names:
             setattr(self.weights, n, self.weights_dev[n].data_ptr())
         nbytes = ps_draft_workspace_bytes(self.config)
         if nbytes == 0:
@@ -195,11 +200,17 @@ class Drafter:
             o["hidden_out"] = t.empty((batch, n_new + k, self.shape.hidden), dtype=t.float32, device=self.device)
         return o
 
-    def make_args(self, x, k_cache, v_cache, kv_offsets, kv_len, n_new, k, topk, outputs, all_rows=False):
-        """Builds the argument struct; keeps the host arrays alive on the struct."""
+    def make_args(self, x, k_cache, v_cache, kv_offsets, kv_len, n_new, k, topk, outputs, all_rows=False,
+                  token_ids=None, features=None):
+        """Builds the argument struct; keeps the host arrays alive on the struct.  x: hidden states, or None
+        when token_ids (and features) are given."""
         a = ps_draft_step_args()
         a.batch, a.n_new, a.k, a.topk, a.out_rows = len(kv_len), n_new, k, topk, 1 if all_rows else 0
-        a.x, a.k_cache, a.v_cache = x.data_ptr(), k_cache.data_ptr(), v_cache.data_ptr()
+        a.x = x.data_ptr() if x is not None else None
+        a.k_cache, a.v_cache = k_cache.data_ptr(), v_cache.data_ptr()
+        a.token_ids = token_ids.data_ptr() if token_ids is not None else None
+        a.features = features.data_ptr() if features is not None else None
+        a._keep_in = (token_ids, features)
         off = np.ascontiguousarray(kv_offsets, dtype=np.int64)
         ln = np.ascontiguousarray(kv_len, dtype=np.int32)
         a._keep = (off, ln, x, k_cache, v_cache, outputs)

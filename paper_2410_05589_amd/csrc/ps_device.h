@@ -176,7 +176,6 @@ struct SxBuf { rsrc_t cur, alt; };
 // graph launch never change): thread 0 of every workgroup reads the counter when the kernel
 // starts and leaves number = counter + 1 in LDS (step_begin); the last workgroup to do so
 // advances the counter for the next launch (step_end).
-#define PS_LDS_SEQ 16       // LDS bytes [0, 256) are reserved for this in every phase's layout
 typedef __attribute__((address_space(3))) unsigned lds_u32;
 __device__ __forceinline__ unsigned ps_seq() {
     return __builtin_amdgcn_readfirstlane(*(const lds_u32*)(unsigned)PS_LDS_SEQ);
@@ -216,10 +215,11 @@ __device__ __forceinline__ void sx_reset_stale(const StepParams& P, int wg, int 
     const u32x4 sent = {PS_SENT, PS_SENT, PS_SENT, PS_SENT};
     const unsigned rows_prev = __builtin_amdgcn_readfirstlane(ld_agent_u32(prev));
     if (rows_prev > (unsigned)P.Mtot) {
-        const float* bufs[6] = {P.q_buf, P.kvnew, P.o_buf, P.y_buf, P.u_buf, P.y2_buf};
-        const int lds[6] = {P.QD, 2 * P.KVD, P.QD, P.H, P.F, P.H};      // elements per row: multiples of 4
+        const float* bufs[7] = {P.q_buf, P.kvnew, P.o_buf, P.y_buf, P.u_buf, P.y2_buf, P.x_buf};
+        const int lds[7] = {P.QD, 2 * P.KVD, P.QD, P.H, P.F, P.H, P.H};   // elements per row: multiples of 4
 #pragma unroll
-        for (int i = 0; i < 6; ++i) {
+        for (int i = 0; i < 7; ++i) {
+            if (!bufs[i]) continue;
             const rsrc_t alt = make_rsrc(reinterpret_cast<const char*>(bufs[i]) + (1u - par) * P.act_bytes);
             const unsigned lo = (unsigned)P.Mtot * lds[i], hi = rows_prev * lds[i];
             for (unsigned e = lo + 4u * (wg * PS_WG_THREADS + threadIdx.x); e < hi; e += 4u * nwg * PS_WG_THREADS)
@@ -363,14 +363,20 @@ __device__ __forceinline__ int key_id(u64 k) { return 0x7FFFFFFF - (int)(unsigne
 __device__ __forceinline__ int row_seq(const StepParams& P, int m) {
     return P.M == 1 ? m : (int)__umulhi((unsigned)m, P.m_magic);
 }
+// token id of real row (b, i) (token-id input modes)
+__device__ __forceinline__ int tok_of(const StepParams& P, int b, int i) {
+    return __builtin_amdgcn_readfirstlane(P.token_ids[b * P.n_new + i]);
+}
+// 4 elements of row m of Z from column e on, as floats.  Real rows: the caller's hidden states, a row of the
+// embedding table, or the input projection's output (exchanged fp32, complete since that kernel ended).
 template <typename WT>
-__device__ __forceinline__ const char* z_ptr(const StepParams& P, int m, int e) {
+__device__ __forceinline__ f32x4 load_z4(const StepParams& P, int m, int e) {
     const int b = row_seq(P, m), i = m - b * P.M;
-    const char* base;
-    long long off;
-    if (i < P.n_new) { base = (const char*)P.x; off = ((long long)(b * P.n_new + i)) * P.H + e; }
-    else { base = (const char*)P.mask_emb; off = ((long long)(i - P.n_new)) * P.H + e; }
-    return base + off * Traits<WT>::ESZ;
+    if (i >= P.n_new) return load4<WT>((const char*)P.mask_emb + ((long long)(i - P.n_new) * P.H + e) * Traits<WT>::ESZ);
+    if (P.in_mode == PS_IN_HIDDEN) return load4<WT>((const char*)P.x + ((long long)(b * P.n_new + i) * P.H + e) * Traits<WT>::ESZ);
+    if (P.in_mode == PS_IN_TOKENS)
+        return load4<WT>((const char*)P.embed + ((long long)P.token_ids[b * P.n_new + i] * P.H + e) * Traits<WT>::ESZ);
+    return *reinterpret_cast<const f32x4*>(act_ptr(P, P.x_buf) + ((size_t)m * P.H + e) * 4);
 }
 
 // Debugging aid (builds with -DPS_TIMELINE only): thread 0 of every workgroup notes the shader
@@ -423,6 +429,8 @@ __device__ __forceinline__ const char* weight_row_ptr(const StepParams& P, int t
                        : (const char*)P.w_up + (size_t)(8 * tau + i - 8) * P.H * ESZ;
     } else if (PH == PH_DOWN) {
         return (const char*)P.w_down + (size_t)(16 * tau + i) * P.F * ESZ;
+    } else if (PH == PH_FC) {
+        return (const char*)P.w_fc + (size_t)(16 * tau + i) * (2 * P.H) * ESZ;
     } else {
         int row = 16 * tau + i;
         if (row >= P.V) row = P.V - 1;   // ragged last vocabulary tile: clamp, masked in the epilogue
@@ -605,8 +613,26 @@ __device__ __forceinline__ void epilogue_oproj(const StepParams& P, int tau, int
     for (int mt = 0; mt < MT; ++mt) {
         const int m = 16 * mt + c;
         if (m >= P.Mtot) continue;
-        const f32x4 z = load4<WT>(z_ptr<WT>(P, m, n));
+        const f32x4 z = load_z4<WT>(P, m, n);
         sx_st4(ry, (unsigned)((size_t)m * P.H + n), z + acc[mt]);
+    }
+}
+
+// input projection (Section 4.3, EAGLE integration): panel row r is real row (b, i) = (r / n_new, r % n_new);
+// its output is row b M + i of Z, exchanged as fp32
+template <typename WT, int MT>
+__device__ __forceinline__ void epilogue_fc(const StepParams& P, int tau, int lane, f32x4 (&acc)[MT]) {
+    const int c = lane & 15, q = lane >> 4;
+    const int n = 16 * tau + 4 * q;
+    const SxBuf rx = sx_buf(P, P.x_buf);
+    f32x4 bias = {0.f, 0.f, 0.f, 0.f};
+    if (P.b_fc) bias = load4<WT>((const char*)P.b_fc + (size_t)n * Traits<WT>::ESZ);
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+        const int r = 16 * mt + c;
+        if (r >= P.B * P.n_new) continue;
+        const int b = P.n_new == 1 ? r : (int)__umulhi((unsigned)r, P.n_magic), i = r - b * P.n_new;
+        sx_st4(rx, (unsigned)((size_t)(b * P.M + i) * P.H + n), acc[mt] + bias);
     }
 }
 
@@ -681,9 +707,9 @@ __host__ __device__ inline int panel_row_stride(int panel_steps) {
     return len + ((64 - (len & 255)) + 256) % 256;
 }
 // LDS layout of a GEMM phase (bytes from the start of dynamic LDS)
-#define PS_LDS_SSQ 256      // [64 rows][8] partial sums of squares (RMSNorm); bytes [0, 256): see PS_LDS_SEQ
-#define PS_LDS_ZERO 2304    // 64 zero bytes: B operand of unused MFMA columns
-#define PS_LDS_RED 2560     // [wavefronts][MT][64 lanes] f32x4: partial sums of wavefronts sharing a tile
+#define PS_LDS_SSQ PS_LDS_BASE   // [64 rows][8] partial sums of squares (RMSNorm); bytes below: see PS_LDS_BASE
+#define PS_LDS_ZERO (PS_LDS_BASE + 2048)    // 64 zero bytes: B operand of unused MFMA columns
+#define PS_LDS_RED (PS_LDS_BASE + 2304)     // [wavefronts][MT][64 lanes] f32x4: partial sums of wavefronts sharing a tile
 __host__ __device__ inline int panel_offset(int mt) { return PS_LDS_RED + PS_WAVES * mt * 1024; }
 
 typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
@@ -708,7 +734,7 @@ __device__ __forceinline__ void stage_piece(const StepParams& P, const PhaseDesc
     constexpr int KSTEP = Traits<WT>::KSTEP, GE = Traits<WT>::GE, ESZ = Traits<WT>::ESZ;
     constexpr int NL = GE / 4;                       // 16-byte loads per group of exchanged fp32
     constexpr int RB = 8;                            // rows per thread requested before any is used
-    constexpr bool from_x = PH == PH_QKV;            // the step's input rows, complete at launch
+    constexpr bool from_x = PH == PH_QKV || PH == PH_FC;   // the step's inputs, complete at launch
     const int tid = threadIdx.x, lane = tid & 63;
     float* s_ssq = reinterpret_cast<float*>(smem + PS_LDS_SSQ);
     const int G = nsteps * 4;
@@ -719,7 +745,17 @@ __device__ __forceinline__ void stage_piece(const StepParams& P, const PhaseDesc
     const int wsub = wave & ((G2 >> 6) - 1);
     const int rows = D.rows, K = D.K, RS = D.rs, ld = D.src_ld;
     const bool norm = PH == PH_QKV || PH == PH_GATEUP || (PH == PH_LMHEAD && D.norm != 0);
-    const rsrc_t rs = make_rsrc(from_x ? P.x : (const void*)act_ptr(P, D.src)), rmask = make_rsrc(P.mask_emb);
+    const int in_mode = P.in_mode;
+    // where the rows come from.  QKV: the real rows of Z by input mode (see StepParams), the [MASK] rows from
+    // mask_emb; input projection: features (columns < H) and the tokens' embedding rows (columns >= H)
+    const rsrc_t rs = make_rsrc(PH == PH_FC ? P.features
+                                : PH != PH_QKV ? (const void*)act_ptr(P, D.src)
+                                : in_mode == PS_IN_HIDDEN ? P.x : in_mode == PS_IN_TOKENS ? P.embed : (const void*)act_ptr(P, P.x_buf));
+    const rsrc_t rmask = make_rsrc(PH == PH_FC ? P.embed : P.mask_emb);
+    // is row r of the QKV panel an fp32 row (the input projection's output)?
+    auto fused_row = [&](int r) __attribute__((always_inline)) {
+        return PH == PH_QKV && in_mode == PS_IN_FUSED && r - row_seq(P, r) * P.M < P.n_new;
+    };
     for (int gc = 0; gc < G; gc += G2) {
         const int gi = gc + gi0;
         const bool gvalid = gi < G;
@@ -736,12 +772,26 @@ __device__ __forceinline__ void stage_piece(const StepParams& P, const PhaseDesc
 #pragma unroll
                 for (int i = 0; i < RB; ++i) {
                     const int r = min(rb + nrt * i, rows - 1);   // clamped: every load is unconditional
-                    if (from_x) {
-                        // row r of Z = [x rows ; mask embeddings] of its sequence
+                    if (PH == PH_QKV) {
+                        // row r of Z = [real rows ; mask embeddings] of its sequence
                         const int b = row_seq(P, r), ii = r - b * P.M;
-                        raw[i][0] = ii < P.n_new
-                            ? __builtin_amdgcn_raw_buffer_load_b128(rs, kkc * ESZ, (b * P.n_new + ii) * P.H * ESZ, 0)
-                            : __builtin_amdgcn_raw_buffer_load_b128(rmask, kkc * ESZ, (ii - P.n_new) * P.H * ESZ, 0);
+                        if (ii >= P.n_new) {
+                            raw[i][0] = __builtin_amdgcn_raw_buffer_load_b128(rmask, kkc * ESZ, (ii - P.n_new) * P.H * ESZ, 0);
+                        } else if (in_mode == PS_IN_HIDDEN) {
+                            raw[i][0] = __builtin_amdgcn_raw_buffer_load_b128(rs, kkc * ESZ, (b * P.n_new + ii) * P.H * ESZ, 0);
+                        } else if (in_mode == PS_IN_TOKENS) {
+                            raw[i][0] = __builtin_amdgcn_raw_buffer_load_b128(rs, kkc * ESZ, tok_of(P, b, ii) * P.H * ESZ, 0);
+                        } else {
+#pragma unroll
+                            for (int h = 0; h < NL; ++h)
+                                raw[i][h] = __builtin_amdgcn_raw_buffer_load_b128(rs, (kkc + 4 * h) * 4, (b * P.M + ii) * P.H * 4, PS_SC1);
+                        }
+                    } else if (PH == PH_FC) {
+                        // real row r = (b, ii): [features ; embedding of its token]
+                        const int b = P.n_new == 1 ? r : (int)__umulhi((unsigned)r, P.n_magic), ii = r - b * P.n_new;
+                        raw[i][0] = kkc < P.H
+                            ? __builtin_amdgcn_raw_buffer_load_b128(rs, kkc * ESZ, r * P.H * ESZ, 0)
+                            : __builtin_amdgcn_raw_buffer_load_b128(rmask, (kkc - P.H) * ESZ, tok_of(P, b, ii) * P.H * ESZ, 0);
                     } else {
                         const int srow = PH == PH_LMHEAD ? lm_src_row(P, r) : r;
 #pragma unroll
@@ -762,7 +812,7 @@ __device__ __forceinline__ void stage_piece(const StepParams& P, const PhaseDesc
                 const int r = rb + nrt * i;
                 if (r >= rows) continue;
                 float v[GE];
-                if (from_x) {
+                if (from_x && !fused_row(r)) {
                     unpack_group<WT>(make_uint4(raw[i][0][0], raw[i][0][1], raw[i][0][2], raw[i][0][3]), v);
                 } else {
 #pragma unroll
@@ -893,7 +943,8 @@ __device__ __forceinline__ void gemm_phase(const StepParams& P, int wg, int wave
     const int nsub = (1 << D.g2_log) >> 6;                       // entries of s_ssq per row
     const bool norm = PH == PH_QKV || PH == PH_GATEUP || (PH == PH_LMHEAD && D.norm != 0);
 
-    stamp(P, wg, 2 + ph * 6 + 0);
+    constexpr int SB = PH == PH_FC ? 50 : 2 + PH * 6;   // this phase's clock stamps (timeline builds)
+    stamp(P, wg, SB + 0);
     if (j >= D.T) {                   // more workgroup columns than tiles: nothing to do in this phase
         preload_weights(wb, after_wp, lane16);
         if (publish_seq) *(lds_u32*)(unsigned)PS_LDS_SEQ = publish_seq;
@@ -952,7 +1003,7 @@ __device__ __forceinline__ void gemm_phase(const StepParams& P, int wg, int wave
                 if (rd == 0 && pc == 0) {
 #pragma unroll
                     for (int i = 0; i < (PS_PF > 0 ? PS_PF : 0); ++i) asm volatile("" ::"v"(pf[i]));
-                    stamp(P, wg, 2 + ph * 6 + 1);
+                    stamp(P, wg, SB + 1);
                 }
             }
             if (valid) {
@@ -972,7 +1023,7 @@ __device__ __forceinline__ void gemm_phase(const StepParams& P, int wg, int wave
                 streamed = true;
             }
         }
-        if (rd == D.rounds - 1) stamp(P, wg, 2 + ph * 6 + 2);
+        if (rd == D.rounds - 1) stamp(P, wg, SB + 2);
 
         // wavefronts sharing the tile: wavefront kw = 0 adds the others' partial sums in order
         if (KW > 1) {
@@ -990,7 +1041,7 @@ __device__ __forceinline__ void gemm_phase(const StepParams& P, int wg, int wave
             }
             if (rd + 1 < D.rounds) __syncthreads();
         }
-        if (rd == D.rounds - 1) stamp(P, wg, 2 + ph * 6 + 3);
+        if (rd == D.rounds - 1) stamp(P, wg, SB + 3);
 
         if (valid && kw == 0) {
             if (sliceable && S > 1) {
@@ -1021,6 +1072,7 @@ __device__ __forceinline__ void gemm_phase(const StepParams& P, int wg, int wave
                     case PH_OPROJ: epilogue_oproj<WT, MT>(P, tau, lane, acc); break;
                     case PH_GATEUP: epilogue_gateup<WT, MT>(P, tau, lane, acc); break;
                     case PH_DOWN: epilogue_down<WT, MT>(P, tau, lane, acc); break;
+                    case PH_FC: epilogue_fc<WT, MT>(P, tau, lane, acc); break;
                     default: epilogue_lm<WT, MT>(P, tau, lane, acc, s_lm, rd * SL + slot); break;
                 }
             }
@@ -1068,11 +1120,12 @@ __device__ __forceinline__ void gemm_phase(const StepParams& P, int wg, int wave
                 case PH_QKV: epilogue_qkv<WT, MT>(P, tau, lane, acc); break;
                 case PH_OPROJ: epilogue_oproj<WT, MT>(P, tau, lane, acc); break;
                 case PH_GATEUP: epilogue_gateup<WT, MT>(P, tau, lane, acc); break;
+                case PH_FC: epilogue_fc<WT, MT>(P, tau, lane, acc); break;
                 default: epilogue_down<WT, MT>(P, tau, lane, acc); break;
             }
         }
     }
-    stamp(P, wg, 2 + ph * 6 + 4);
+    stamp(P, wg, SB + 4);
     if (!streamed) preload_weights(wb, after_wp, lane16);   // keep the contract on wb
 
     if (ph == PH_LMHEAD) {
@@ -1083,7 +1136,7 @@ __device__ __forceinline__ void gemm_phase(const StepParams& P, int wg, int wave
         if (rows > PS_WAVES && D.rounds * SL * 16 <= 16 * 16) lm_local_stats<16>(P, D, j, rows, s_lm, wave, lane, sl_log, SL);
         else lm_local_stats<64>(P, D, j, rows, s_lm, wave, lane, sl_log, SL);
     }
-    stamp(P, wg, 2 + ph * 6 + 5);
+    stamp(P, wg, SB + 5);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -1125,7 +1178,7 @@ __global__ void __launch_bounds__(256) pack_kernel(const StepParams P, int T, in
 template <typename WT, int D, int NK> struct AttnCfg {
     static constexpr int CH = PS_ATTN_KEYS * NK;
     static constexpr int CH_LOG = PS_ATTN_KEYS_LOG + (NK == 2 ? 1 : 0);
-    static constexpr int OFF_M = 256;                                // [waves][16] row maxima
+    static constexpr int OFF_M = PS_LDS_BASE;                                // [waves][16] row maxima
     static constexpr int OFF_L = OFF_M + PS_WAVES * 16 * 4;          // [waves][16] row sums
     static constexpr int OFF_P = OFF_L + PS_WAVES * 16 * 4;          // [waves][NK][16 rows][16 keys]
     static constexpr int OFF_O = OFF_P + PS_WAVES * NK * 16 * 16 * 4;   // [waves][16 rows][D]
@@ -1940,7 +1993,7 @@ __global__ void __launch_bounds__(PS_WG_THREADS) attn_kernel(const StepParams P)
 static __global__ void __launch_bounds__(PS_WG_THREADS) lm_merge_kernel(const StepParams P) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
     const unsigned ticket = step_begin(P, true);   // the last kernel of a step in this mode
-    lm_merge_row(P, blockIdx.x, __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), smem + 256);
+    lm_merge_row(P, blockIdx.x, __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), smem + PS_LDS_BASE);
     step_end(P, ticket, gridDim.x);
 }
 
@@ -1990,7 +2043,7 @@ __global__ void __launch_bounds__(PS_WG_THREADS, 1) fused_kernel(const StepParam
     // output row m is merged by the m-th workgroup from the end: the last workgroups have the fewest
     // vocabulary tiles (the last round of tiles is not full), so they are the first to be ready for it
     stamp(P, wg, 40);
-    for (int m = (int)gridDim.x - 1 - wg; m < P.Rtot; m += gridDim.x) lm_merge_row(P, m, wave, smem + 256);
+    for (int m = (int)gridDim.x - 1 - wg; m < P.Rtot; m += gridDim.x) lm_merge_row(P, m, wave, smem + PS_LDS_BASE);
     sx_reset_stale(P, wg, gridDim.x);   // here most workgroups have nothing left to do
     step_end(P, ticket, gridDim.x);
     stamp(P, wg, 62);

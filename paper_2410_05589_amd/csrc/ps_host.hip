@@ -44,7 +44,7 @@ struct ps_draft_ctx {
     size_t exch_begin, exch_end;      // workspace range of the tagged exchange buffers (cleared at init)
     char* act_base;                   // two copies of the activation buffers, act_bytes each
     size_t act_bytes;
-    size_t off_q, off_o, off_y, off_u, off_y2, off_kvnew;   // offsets inside one copy
+    size_t off_q, off_o, off_y, off_u, off_y2, off_kvnew, off_x;   // offsets inside one copy
     int spin_limit;                   // polls before a kernel gives up a wait (PS_SPIN_LIMIT; tests of that path: less)
     char* wpack[PH_COUNT];
     int* counters;
@@ -71,7 +71,7 @@ static int validate_config(const ps_draft_config* c) {
     if (c->head_dim % 2 != 0) return PS_ERR_CONFIG;
     if (!(c->rms_eps >= 0.f) || !(c->rope_base > 0.f)) return PS_ERR_CONFIG;
     if (c->max_positions < c->max_new + c->k_max) return PS_ERR_CONFIG;
-    if (c->flags & ~PS_FLAG_FINAL_NORM) return PS_ERR_CONFIG;
+    if (c->flags & ~(PS_FLAG_FINAL_NORM | PS_FLAG_INPUT_FC)) return PS_ERR_CONFIG;
     // what this build has kernels for
     const int kmul = c->dtype == PS_BF16 ? 32 : 16;
     const long long qd = (long long)c->n_heads * c->head_dim;
@@ -92,7 +92,7 @@ struct WsLayout {
     size_t wpack[PH_COUNT];
     size_t rope, q_buf, o_buf, y_buf, u_buf, y2_buf, kvnew, attn_acc, attn_ml, counters, lm_part, logits_ws, total;
     size_t exch_begin, exch_end;
-    size_t act_base, act_bytes, off_q, off_o, off_y, off_u, off_y2, off_kvnew, off_frag[PH_COUNT], off_ssqf[PH_COUNT];
+    size_t act_base, act_bytes, off_q, off_o, off_y, off_u, off_y2, off_kvnew, off_x, off_frag[PH_COUNT], off_ssqf[PH_COUNT];
     int n_counters;
     bool fits32;   // the kernels address every exchange buffer with 32-bit byte offsets
 };
@@ -106,7 +106,10 @@ static void phase_dims(const ps_draft_config* c, int* T, int* Kt, int* K = nullp
     T[PH_GATEUP] = c->ffn / 8; Kt[PH_GATEUP] = c->hidden / kstep;
     T[PH_DOWN] = c->hidden / 16; Kt[PH_DOWN] = c->ffn / kstep;
     T[PH_LMHEAD] = (c->vocab + 15) / 16; Kt[PH_LMHEAD] = c->hidden / kstep;
-    if (K) { K[PH_QKV] = K[PH_GATEUP] = K[PH_LMHEAD] = c->hidden; K[PH_OPROJ] = qd; K[PH_DOWN] = c->ffn; }
+    // the input projection [H, 2H] exists only with PS_FLAG_INPUT_FC
+    const bool fc = (c->flags & PS_FLAG_INPUT_FC) != 0;
+    T[PH_FC] = fc ? c->hidden / 16 : 0; Kt[PH_FC] = fc ? 2 * c->hidden / kstep : 0;
+    if (K) { K[PH_QKV] = K[PH_GATEUP] = K[PH_LMHEAD] = c->hidden; K[PH_OPROJ] = qd; K[PH_DOWN] = c->ffn; K[PH_FC] = 2 * c->hidden; }
 }
 // steps per tile in the packed matrices: whole groups of PS_U steps
 static int padded_steps(int kt) { return (kt + PS_U - 1) / PS_U * PS_U; }
@@ -136,6 +139,7 @@ static WsLayout ws_layout(const ps_draft_config* c) {
         L.off_u = sub(rows * c->ffn * 4);
         L.off_y2 = sub(rows * c->hidden * 4);
         L.off_kvnew = sub(rows * 2 * (size_t)c->n_kv_heads * c->head_dim * 4);
+        L.off_x = sub((c->flags & PS_FLAG_INPUT_FC) ? rows * c->hidden * 4 : 0);
         // parts of the tiles from up to PS_S_MAX K-slices (1 KiB per slice, tile and 16 rows)
         const size_t mt_max = (rows + 15) / 16;
         for (int ph = 0; ph < PH_COUNT; ++ph) L.off_ssqf[ph] = sub((size_t)PS_S_MAX * PS_MAX_ROWS * 4);
@@ -197,7 +201,7 @@ static void parse_plan_override(ps_draft_ctx* ctx) {
     memset(ctx->plan_override, 0, sizeof(ctx->plan_override));
     const char* e = getenv("PS_DRAFT_PLAN");
     if (!e) return;
-    static const char* names[PH_COUNT] = {"qkv", "oproj", "gateup", "down", "lm"};
+    static const char* names[PH_COUNT] = {"qkv", "oproj", "gateup", "down", "lm", "fc"};
     for (int ph = 0; ph < PH_COUNT; ++ph) {
         const char* p = strstr(e, names[ph]);
         if (!p) continue;
@@ -219,7 +223,11 @@ extern "C" int ps_draft_init(ps_draft_ctx** out, const ps_draft_config* config, 
         return PS_ERR_NULL;
     if ((config->flags & PS_FLAG_FINAL_NORM) && !w->g_final) return PS_ERR_NULL;
     if (config->k_max > 0 && !w->mask_emb) return PS_ERR_NULL;
+    if ((config->flags & PS_FLAG_INPUT_FC) && (!w->w_fc || !w->embed)) return PS_ERR_NULL;
     if (!workspace) return PS_ERR_NULL;
+    // rows of the embedding table are addressed with 32-bit byte offsets
+    if (w->embed && (unsigned long long)config->vocab * config->hidden * (config->dtype == PS_BF16 ? 2 : 4) > 0xFFFFFFF0ull)
+        return PS_ERR_UNSUPPORTED;
     const WsLayout L = ws_layout(config);
     if (workspace_bytes < L.total || ((uintptr_t)workspace & 255)) return PS_ERR_WORKSPACE;
 
@@ -262,7 +270,7 @@ extern "C" int ps_draft_init(ps_draft_ctx** out, const ps_draft_config* config, 
     ctx->rope = (float2*)(base + L.rope);
     ctx->act_base = base + L.act_base; ctx->act_bytes = L.act_bytes;
     ctx->off_q = L.off_q; ctx->off_o = L.off_o; ctx->off_y = L.off_y; ctx->off_u = L.off_u;
-    ctx->off_y2 = L.off_y2; ctx->off_kvnew = L.off_kvnew;
+    ctx->off_y2 = L.off_y2; ctx->off_kvnew = L.off_kvnew; ctx->off_x = L.off_x;
     for (int ph = 0; ph < PH_COUNT; ++ph) { ctx->off_frag[ph] = L.off_frag[ph]; ctx->off_ssqf[ph] = L.off_ssqf[ph]; }
     ctx->spin_limit = PS_SPIN_LIMIT;
     ctx->attn_acc = (float*)(base + L.attn_acc);
@@ -302,10 +310,11 @@ extern "C" int ps_draft_init(ps_draft_ctx** out, const ps_draft_config* config, 
         P.H = config->hidden; P.nq = config->n_heads; P.nkv = config->n_kv_heads; P.d = config->head_dim;
         P.F = config->ffn; P.V = config->vocab; P.QD = config->n_heads * config->head_dim;
         P.wq = w->wq; P.wk = w->wk; P.wv = w->wv; P.wo = w->wo; P.w_gate = w->w_gate; P.w_up = w->w_up;
-        P.w_down = w->w_down; P.w_lm = w->w_lm;
+        P.w_down = w->w_down; P.w_lm = w->w_lm; P.w_fc = w->w_fc;
         int T[PH_COUNT], Kt[PH_COUNT];
         phase_dims(config, T, Kt);
         for (int ph = 0; ph < PH_COUNT && e == hipSuccess; ++ph) {
+            if (T[ph] == 0) continue;
             const int ktp = padded_steps(Kt[ph]);
             e = inst->pack(P, ph, T[ph], ktp, Kt[ph], ctx->wpack[ph], s);
             // the streaming loop reads up to PS_U KiB past the last tile: make that zeros, not stale memory
@@ -368,7 +377,7 @@ int panel_row_stride_host(int panel_steps) {
     const int len = panel_steps * 64;
     return len + ((64 - (len & 255)) + 256) % 256;
 }
-static int panel_offset_host(int mt) { return 2560 + PS_WAVES * mt * 1024; }   // see PS_LDS_RED in ps_device.h
+static int panel_offset_host(int mt) { return PS_LDS_BASE + 2304 + PS_WAVES * mt * 1024; }   // see PS_LDS_RED in ps_device.h
 
 // Cuts one GEMM phase: T tiles x Kt steps (K elements) over nwg workgroups of PS_WAVES wavefronts.
 //
@@ -393,7 +402,7 @@ static bool make_desc(PhaseDesc* d, int ph, int T, int Kt, int K, int rows, int 
     // that needs only 1/S of the panel stages it in far fewer pieces.
     int s_log = 0;
     const bool whole_fits = (long long)rows * arrays * panel_row_stride_host(ktp) <= lds_limit - panel_offset_host(mt) - 256;
-    if (ph == PH_OPROJ || ph == PH_DOWN || (ph != PH_LMHEAD && !whole_fits))
+    if (ph == PH_OPROJ || ph == PH_DOWN || ph == PH_FC || (ph != PH_LMHEAD && !whole_fits))
         while (s_log < 3 && (2 << s_log) <= NG && (2 << s_log) <= nwg) ++s_log;
     if (override_[0] > 0 && ph != PH_LMHEAD) {
         s_log = 0;
@@ -464,7 +473,7 @@ extern "C" int ps_draft_debug_plan(const ps_draft_config* c, int batch, int n_ne
     const int none[2] = {0, 0};
     int T[PH_COUNT], Kt[PH_COUNT], K[PH_COUNT];
     phase_dims(c, T, Kt, K);
-    for (int ph = 0; ph < PH_COUNT; ++ph) {
+    for (int ph = 0; ph <= PH_LMHEAD; ++ph) {
         PhaseDesc d;
         const int rows = ph == PH_LMHEAD ? Rtot : Mtot;
         if (!make_desc(&d, ph, T[ph], Kt[ph], K[ph], rows, (Mtot + 15) / 16, c->dtype == PS_BF16, n_cu, none, lds_limit))
@@ -483,8 +492,23 @@ extern "C" int ps_draft_step(ps_draft_ctx* ctx, const ps_draft_step_args* a, voi
         return PS_ERR_SHAPE;
     if (a->topk < 1 || a->topk > c.max_topk || a->topk > c.vocab) return PS_ERR_SHAPE;
     if (a->out_rows != 0 && a->out_rows != 1) return PS_ERR_SHAPE;
-    if (!a->x || !a->k_cache || !a->v_cache || !a->kv_offsets || !a->kv_len || !a->top_ids || !a->top_p || !a->lse)
+    if (!a->k_cache || !a->v_cache || !a->kv_offsets || !a->kv_len || !a->top_ids || !a->top_p || !a->lse)
         return PS_ERR_NULL;
+    // where the real rows come from: hidden states x, or token ids (with the embedding table given at init),
+    // or token ids and features (with the input projection given at init)
+    int in_mode = PS_IN_HIDDEN;
+    if (a->token_ids) {
+        if (a->x) return PS_ERR_SHAPE;                       // one or the other
+        if (!ctx->w.embed) return PS_ERR_NULL;
+        in_mode = PS_IN_TOKENS;
+        if (a->features) {
+            if (!(c.flags & PS_FLAG_INPUT_FC)) return PS_ERR_SHAPE;
+            in_mode = PS_IN_FUSED;
+        }
+    } else {
+        if (!a->x) return PS_ERR_NULL;
+        if (a->features) return PS_ERR_SHAPE;                // features go with token ids
+    }
     const int M = a->n_new + a->k;
     for (int b = 0; b < a->batch; ++b) {
         if (a->kv_offsets[b] < 0 || a->kv_offsets[b + 1] < a->kv_offsets[b]) return PS_ERR_OFFSETS;
@@ -507,6 +531,9 @@ extern "C" int ps_draft_step(ps_draft_ctx* ctx, const ps_draft_step_args* a, voi
     P.g_post = ctx->w.g_post; P.w_gate = ctx->w.w_gate; P.w_up = ctx->w.w_up; P.w_down = ctx->w.w_down;
     P.g_final = ctx->w.g_final; P.w_lm = ctx->w.w_lm; P.mask_emb = ctx->w.mask_emb;
     P.x = a->x; P.kc = a->k_cache; P.vc = a->v_cache;
+    P.in_mode = in_mode; P.token_ids = a->token_ids; P.features = a->features;
+    P.embed = ctx->w.embed; P.w_fc = ctx->w.w_fc; P.b_fc = ctx->w.b_fc;
+    P.n_magic = 0xFFFFFFFFu / (unsigned)a->n_new + 1u;
     P.rope = ctx->rope; P.attn_acc = ctx->attn_acc; P.attn_ml = ctx->attn_ml;
     P.lm_part = ctx->lm_part;
     P.m_magic = 0xFFFFFFFFu / (unsigned)M + 1u;   // ceil(2^32 / M); M = 1 is handled on the device
@@ -521,6 +548,7 @@ extern "C" int ps_draft_step(ps_draft_ctx* ctx, const ps_draft_step_args* a, voi
     P.act_bytes = (long long)ctx->act_bytes;
     P.q_buf = (float*)(act0 + ctx->off_q); P.o_buf = (float*)(act0 + ctx->off_o); P.y_buf = (float*)(act0 + ctx->off_y);
     P.u_buf = (float*)(act0 + ctx->off_u); P.y2_buf = (float*)(act0 + ctx->off_y2); P.kvnew = (float*)(act0 + ctx->off_kvnew);
+    P.x_buf = (c.flags & PS_FLAG_INPUT_FC) ? (float*)(act0 + ctx->off_x) : nullptr;
     P.spin_limit = ctx->spin_limit;
     P.foot_mem = (unsigned*)ctx->counters + PS_CTR_FOOT;
     P.logits_store = a->logits ? a->logits : (a->probs ? ctx->logits_ws : nullptr);
@@ -569,9 +597,10 @@ extern "C" int ps_draft_step(ps_draft_ctx* ctx, const ps_draft_step_args* a, voi
     int T[PH_COUNT], Kt[PH_COUNT], K[PH_COUNT];
     phase_dims(&c, T, Kt, K);
     for (int ph = 0; ph < PH_COUNT; ++ph) {
-        const int rows = ph == PH_LMHEAD ? P.Rtot : P.Mtot;
+        if (T[ph] == 0) continue;                            // (no input projection in this configuration)
+        const int rows = ph == PH_LMHEAD ? P.Rtot : ph == PH_FC ? a->batch * a->n_new : P.Mtot;
         // the persistent kernel runs every phase with the column tiles of the widest one
-        const int mt = (ctx->fused ? P.Mtot + 15 : rows + 15) / 16;
+        const int mt = ((ctx->fused && ph != PH_FC) ? P.Mtot + 15 : rows + 15) / 16;
         if (!make_desc(&P.ph[ph], ph, T[ph], Kt[ph], K[ph], rows, mt, bf, nwg, ctx->plan_override[ph], ctx->lds_limit))
             return PS_ERR_UNSUPPORTED;
         P.ph[ph].wpack = ctx->wpack[ph];
@@ -588,8 +617,8 @@ extern "C" int ps_draft_step(ps_draft_ctx* ctx, const ps_draft_step_args* a, voi
     P.foot[0] = (unsigned)P.Mtot;
     for (int ph = 0; ph < PH_COUNT; ++ph) {
         const PhaseDesc& d = P.ph[ph];
-        const bool sliced = ph != PH_LMHEAD && d.s_log > 0;
-        const int mt = (P.Mtot + 15) / 16;
+        const bool sliced = ph != PH_LMHEAD && d.s_log > 0 && d.T > 0 && (ph != PH_FC || in_mode == PS_IN_FUSED);
+        const int mt = ((ph == PH_FC ? d.rows : P.Mtot) + 15) / 16;
         P.foot[1 + ph] = sliced ? (unsigned)(1 << d.s_log) * (unsigned)d.T * (unsigned)mt * 64u : 0u;
         P.foot[1 + PH_COUNT + ph] = (sliced && d.norm) ? 1u << d.s_log : 0u;
     }
@@ -599,7 +628,7 @@ extern "C" int ps_draft_step(ps_draft_ctx* ctx, const ps_draft_step_args* a, voi
     for (int ph = 0; ph < PH_COUNT; ++ph) {
         if (P.ph[ph].lds_bytes > lds) lds = P.ph[ph].lds_bytes;
     }
-    if (lds < 256 + 8192 + 128) lds = 256 + 8192 + 128;   // end-of-step merge scratch
+    if (lds < PS_LDS_BASE + 8192 + 128) lds = PS_LDS_BASE + 8192 + 128;   // end-of-step merge scratch
     if (lds < 84 * 1024 && ctx->lds_limit >= 84 * 1024) lds = 84 * 1024;   // more than half a CU's LDS: one workgroup per CU
 #ifdef PS_TIMELINE
     lds = ctx->lds_limit;   // the stamps live in the top 512 bytes of LDS
@@ -607,6 +636,7 @@ extern "C" int ps_draft_step(ps_draft_ctx* ctx, const ps_draft_step_args* a, voi
     P.fused_nwg = nwg; P.fused_lds = lds;
     hipStream_t st = (hipStream_t)stream;
     hipEvent_t* ev = ctx->profile ? ctx->events : nullptr;
+    if (in_mode == PS_IN_FUSED && !hip_ok(ctx->inst->launch_fc(P, st), "kernel launch")) return PS_ERR_DEVICE;
     if (ctx->fused && lds <= ctx->lds_limit) {
         if (ev && !hip_ok(hipEventRecord(ev[0], st), "hipEventRecord")) return PS_ERR_DEVICE;
         if (!hip_ok(ctx->inst->launch_fused(P, st), "kernel launch")) return PS_ERR_DEVICE;

@@ -25,6 +25,7 @@ static kernel_fn gemm_fn_ph(int ph, int mt) {
         case PH_OPROJ: return gemm_fn<PH_OPROJ>(mt);
         case PH_GATEUP: return gemm_fn<PH_GATEUP>(mt);
         case PH_DOWN: return gemm_fn<PH_DOWN>(mt);
+        case PH_FC: return gemm_fn<PH_FC>(mt);
         default: return gemm_fn<PH_LMHEAD>(mt);
     }
 }
@@ -88,7 +89,7 @@ static hipError_t launch_multi(const StepParams& P, hipStream_t stream, hipEvent
     if ((e = gemm(PH_GATEUP, mt_all)) != hipSuccess) return e;
     if ((e = gemm(PH_DOWN, mt_all)) != hipSuccess) return e;
     if ((e = gemm(PH_LMHEAD, mt_lm)) != hipSuccess) return e;
-    hipLaunchKernelGGL(lm_merge_kernel, dim3(P.Rtot), dim3(PS_WG_THREADS), PS_MERGE_BYTES + 256, stream, P);
+    hipLaunchKernelGGL(lm_merge_kernel, dim3(P.Rtot), dim3(PS_WG_THREADS), PS_MERGE_BYTES + PS_LDS_BASE, stream, P);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     return mark();
 }
@@ -102,6 +103,13 @@ static hipError_t launch_multi(const StepParams& P, hipStream_t stream, hipEvent
 static hipError_t launch_fused(const StepParams& P, hipStream_t stream) {
     const int mt = (P.Mtot + 15) / 16;
     hipLaunchKernelGGL(fused_fn(mt), dim3(P.fused_nwg), dim3(PS_WG_THREADS), (unsigned)P.fused_lds, stream, P);
+    return hipGetLastError();
+}
+
+// the input projection of the feature-fusion input mode: a kernel of its own in front of the step
+static hipError_t launch_fc(const StepParams& P, hipStream_t stream) {
+    const PhaseDesc& pl = P.ph[PH_FC];
+    hipLaunchKernelGGL(gemm_fn_ph(PH_FC, (pl.rows + 15) / 16), dim3(pl.nwg), dim3(PS_WG_THREADS), pl.lds_bytes, stream, P);
     return hipGetLastError();
 }
 
@@ -123,6 +131,7 @@ static hipError_t pack(const StepParams& P, int ph, int T, int Kt, int Kreal, ch
         case PH_OPROJ: f = pack_kernel<WT_, PH_OPROJ>; break;
         case PH_GATEUP: f = pack_kernel<WT_, PH_GATEUP>; break;
         case PH_DOWN: f = pack_kernel<WT_, PH_DOWN>; break;
+        case PH_FC: f = pack_kernel<WT_, PH_FC>; break;
         default: f = pack_kernel<WT_, PH_LMHEAD>; break;
     }
     const size_t units = (size_t)T * Kt;
@@ -136,7 +145,7 @@ static hipError_t pack(const StepParams& P, int ph, int T, int Kt, int Kreal, ch
 const PsInstance* PS_CAT(ps_instance_, PS_INST_NAME)() {
     static const PsInstance inst = {
         PS_INST_BF16 ? PS_BF16 : PS_F32, PS_INST_D,
-        prepare, launch_multi, launch_fused, launch_probs, fused_resident, pack,
+        prepare, launch_multi, launch_fused, launch_probs, launch_fc, fused_resident, pack,
     };
     return &inst;
 }

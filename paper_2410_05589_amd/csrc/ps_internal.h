@@ -24,6 +24,13 @@
 #endif
 #define PS_U_MAX 32        // packed weight buffers are padded by this many KiB (streaming reads ahead)
 #define PS_LDS_BYTES (160 * 1024)
+// The first PS_LDS_BASE bytes of dynamic LDS are the same in every phase's layout: what a workgroup reads once
+// when the kernel starts and keeps for the whole step (see ps_device.h): the step's sequence number, the
+// sequences' cache lengths, the token ids of the real rows.
+#define PS_LDS_BASE 1024
+#define PS_LDS_SEQ 16        // the step's sequence number (see ps_seq)
+#define PS_LDS_KVLEN 256     // int[PS_MAX_ROWS]: valid cache positions per sequence
+#define PS_LDS_TOK 512       // int[PS_MAX_ROWS]: token id per real row (token-id input modes)
 static_assert((1 << PS_WAVES_LOG) == PS_WAVES, "PS_WAVES_LOG");
 static_assert((PS_U & (PS_U - 1)) == 0 && PS_U <= PS_U_MAX, "PS_U");
 
@@ -32,10 +39,13 @@ static_assert((PS_U & (PS_U - 1)) == 0 && PS_U <= PS_U_MAX, "PS_U");
 #define PS_ATTN_KEYS (16 * PS_WAVES)
 #define PS_ATTN_KEYS_LOG (4 + PS_WAVES_LOG)
 constexpr int ps_attn_lds_bytes(int d, int nk) {
-    return 256 + 2 * PS_WAVES * 16 * 4 + PS_WAVES * nk * 16 * 16 * 4 + PS_WAVES * 16 * d * 4 + 16 * d * 4;
+    return PS_LDS_BASE + 2 * PS_WAVES * 16 * 4 + PS_WAVES * nk * 16 * 16 * 4 + PS_WAVES * 16 * d * 4 + 16 * d * 4;
 }
 
-enum { PH_QKV = 0, PH_OPROJ = 1, PH_GATEUP = 2, PH_DOWN = 3, PH_LMHEAD = 4, PH_COUNT = 5 };
+// The five GEMM phases of the step, and the input projection of the feature-fusion input mode (a kernel of
+// its own in front of the step, built from the same engine)
+enum { PH_QKV = 0, PH_OPROJ = 1, PH_GATEUP = 2, PH_DOWN = 3, PH_LMHEAD = 4, PH_FC = 5, PH_COUNT = 6 };
+enum { PS_IN_HIDDEN = 0, PS_IN_TOKENS = 1, PS_IN_FUSED = 2 };   // where the real rows of Z come from
 // Footprint of a step in the sentinel-coded exchange buffers: [0] activation rows, [1 + ph] 16-byte units of
 // phase ph's K-slice fragments, [1 + PH_COUNT + ph] K-slices that left sums of squares (0 = none)
 #define PS_FOOT_INTS (1 + 2 * PH_COUNT)
@@ -86,8 +96,16 @@ struct StepParams {
     int final_norm, max_positions;
     float eps, inv_sqrt_d;
     // weights and step inputs (config dtype)
-    const void *g_in, *wq, *wk, *wv, *wo, *g_post, *w_gate, *w_up, *w_down, *g_final, *w_lm, *mask_emb;
+    const void *g_in, *wq, *wk, *wv, *wo, *g_post, *w_gate, *w_up, *w_down, *g_final, *w_lm, *mask_emb, *w_fc;
     const void* x;
+    // input stage (Section 4.3): in_mode PS_IN_TOKENS: real row (b, i) is row token_ids[b][i] of the shared
+    // embedding table; PS_IN_FUSED: it is w_fc . [features[b][i] ; that embedding row] (+ b_fc), worked out by the
+    // input-projection kernel into x_buf (fp32, coded like the other activations); [MASK] rows always come from mask_emb
+    int in_mode;
+    unsigned n_magic;            // ceil(2^32 / n_new)
+    const int32_t* token_ids;
+    const void *features, *embed, *b_fc;
+    float* x_buf;                // [Mtot][H]
     void *kc, *vc;
     // workspace
     const float2* rope; // [max_positions][d/2] (cos, sin)
@@ -135,6 +153,7 @@ struct PsInstance {
     hipError_t (*launch_multi)(const StepParams& P, hipStream_t stream, hipEvent_t* events);
     hipError_t (*launch_fused)(const StepParams& P, hipStream_t stream);
     hipError_t (*launch_probs)(const StepParams& P, hipStream_t stream);
+    hipError_t (*launch_fc)(const StepParams& P, hipStream_t stream);
     // workgroups of the persistent kernel (mt column tiles, lds bytes of dynamic LDS) a compute unit can hold
     hipError_t (*fused_resident)(int mt, int lds, int* per_cu);
     // copies one phase's weight matrix (T tiles x Kt steps, of which the first Kreal hold weights

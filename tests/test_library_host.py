@@ -54,7 +54,7 @@ def test_struct_layouts_match_header():
     names = re.findall(r"\b(?:int32_t|float|uint32_t)\s+([a-z_]+);", body)
     assert names == [f[0] for f in B.ps_draft_config._fields_]
     body = text[text.index("typedef struct ps_draft_weights {"):text.index("} ps_draft_weights;")]
-    assert re.findall(r"const void\*\s+([a-z_]+);", body) == list(B.WEIGHT_NAMES)
+    assert re.findall(r"const void\*\s+([a-z_]+);", body) == list(B.WEIGHT_NAMES + B.INPUT_WEIGHT_NAMES)
     body = text[text.index("typedef struct ps_draft_step_args {"):text.index("} ps_draft_step_args;")]
     names = re.findall(r"\b(?:int32_t\*?|float\*|const void\*|void\*|const int64_t\*|const int32_t\*)\s+\*?([a-z_]+)[;,]", body)
     fields = [f[0] for f in B.ps_draft_step_args._fields_]
