@@ -390,6 +390,44 @@ def input_stage_report(torch, name="c1", steps=200, warmup=20):
     return rep
 
 
+def sampling_report(torch, name="c1", steps=200, warmup=20):
+    """The draft step with the sampling epilogue on (temperature 1, one Gumbel-max draw per output row inside
+    the persistent kernel) against the same step without it, on workload `name`; the draw adds no bytes."""
+    from paper_2410_05589_amd import binding as B
+    from paper_2410_05589_amd import inputs
+    from paper_2410_05589_amd.configs import WORKLOADS
+    wl = WORKLOADS[name]
+    shape = wl.shape
+    w = inputs.make_weights(shape, wl.seed)
+    kv_len = inputs.draw_kv_len(wl)
+    inp = inputs.make_step_inputs(wl, kv_len=kv_len)
+    d = B.Drafter(shape, w, max_batch=wl.batch, max_new=wl.n_new, max_positions=max(kv_len) + wl.m, max_topk=wl.topk, k_max=wl.k)
+    dev = {n: B.to_device(inp[n], shape.dtype) for n in ("x", "k_cache", "v_cache")}
+    nbytes = algorithmic_bytes(wl, kv_len, wl.n_new, wl.k)["total"]
+    rep = {"workload": name}
+    stream = torch.cuda.current_stream()
+    for mode, sample in (("top_k_only", False), ("with_draw", True)):
+        outs = d.alloc_outputs(wl.batch, wl.n_new, wl.k, wl.topk, sample=sample)
+        a = d.make_args(dev["x"], dev["k_cache"], dev["v_cache"], inp["kv_offsets"], inp["kv_len"], wl.n_new, wl.k, wl.topk, outs,
+                        temperature=1.0, sample_seed=2024)
+        for _ in range(warmup):
+            d.step(a)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(steps):
+            d.step(a)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) * 1e3 / steps
+        gbs = nbytes / (us * 1e-6) / 1e9
+        rep[mode] = {"latency_us": round(us, 2),
+                     "roofline": {"bound": "hbm", "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                                  "frac": round(gbs / PEAK_HBM_GBS, 4), "traffic": None}}
+    d.close()
+    return rep
+
+
 def verify_walk_report(torch, with_oracle, vocab=32000, k=5, calls=200):
     """Tree construction + acceptance walk (the step after the draft step in Algorithm 1) on a tree of the
     workload's drafter: 61 nodes (fan-out 4, 2, 2, 1, 1 over the k+1 = 6 draft rows) for k = 5, 46 nodes
@@ -534,7 +572,7 @@ def main():
     if not args.no_next_rows:
         hw = WORKLOADS[HEADLINE if args.workload == "all" else args.workload]
         result["next_rows"] = {"verify_walk": verify_walk_report(torch, not args.no_cpu_baseline, vocab=hw.shape.vocab, k=hw.k),
-                               "input_stage": input_stage_report(torch)}
+                               "input_stage": input_stage_report(torch), "sampling": sampling_report(torch)}
     print(json.dumps(result))
 
 

@@ -168,6 +168,24 @@ typedef struct ps_draft_step_args {
      *                       as they are (a learned [MASK] input needs no projection). */
     const int32_t* token_ids; /* device [batch, n_new] in [0, V), or NULL */
     const void* features;     /* device [batch, n_new, H], config.dtype, or NULL */
+    /* Sampling epilogue (Algorithm 1 draws the draft tokens from the draft distributions; the T = 1 rows of
+     * Table 1).  The softmax of every output row is taken over logits / temperature: lse, top_p, probs and the
+     * draw below are those of the tempered distribution; `logits` stays the untempered LM-head output.
+     * With sample_ids, one token per output row is drawn from that distribution inside the step's kernel by the
+     * Gumbel-max construction: argmax_i (logit_i / T + g_i), g_i = -log(-log(u_i)), where u_i for output row m
+     * (0 <= m < batch * rows) and token i is ((h >> 9) + 0.5) 2^-23 with h = three rounds of MurmurHash3's 32-bit
+     * finaliser fmix32: h = fmix32(fmix32(fmix32(seed_lo + 0x9E3779B9 (m + 1)) ^ seed_hi) ^ (i * 0x9E3779B1 +
+     * 0x7F4A7C15)) modulo 2^32; equal values go to the lower id.  The same seed gives the same draws: pass a new
+     * one every step. */
+    float temperature;        /* > 0; 0 stands for 1 */
+    uint64_t sample_seed;
+    int32_t* sample_ids;      /* device [batch, rows] or NULL: the drawn token per output row */
+    float* sample_p;          /* device [batch, rows] or NULL: its probability under the tempered distribution */
+    /* The sequences' lengths in DEVICE memory ([batch] int32, or NULL): when given, the kernel takes every
+     * length from there and kv_len (host) only states upper bounds, kv_len_dev[b] <= kv_len[b], which the
+     * capacity checks and the launch plan use.  A step captured in a HIP graph can then be replayed while the
+     * caller advances the lengths on the device (by n_new per step, up to the bound it was captured with). */
+    const int32_t* kv_len_dev;
 } ps_draft_step_args;
 
 /*

@@ -46,7 +46,9 @@ class ps_draft_step_args(ctypes.Structure):
                 ("kv_offsets", ctypes.POINTER(ctypes.c_int64)), ("kv_len", ctypes.POINTER(ctypes.c_int32)),
                 ("top_ids", ctypes.c_void_p), ("top_p", ctypes.c_void_p), ("lse", ctypes.c_void_p),
                 ("logits", ctypes.c_void_p), ("probs", ctypes.c_void_p), ("hidden_out", ctypes.c_void_p),
-                ("token_ids", ctypes.c_void_p), ("features", ctypes.c_void_p)]
+                ("token_ids", ctypes.c_void_p), ("features", ctypes.c_void_p),
+                ("temperature", ctypes.c_float), ("sample_seed", ctypes.c_uint64),
+                ("sample_ids", ctypes.c_void_p), ("sample_p", ctypes.c_void_p), ("kv_len_dev", ctypes.c_void_p)]
 
 
 _lib = None
@@ -186,7 +188,7 @@ class Drafter:
         s = stream if stream is not None else self.torch.cuda.current_stream(self.device)
         return ctypes.c_void_p(s.cuda_stream)
 
-    def alloc_outputs(self, batch, n_new, k, topk, all_rows=False, logits=False, probs=False, hidden=False):
+    def alloc_outputs(self, batch, n_new, k, topk, all_rows=False, logits=False, probs=False, hidden=False, sample=False):
         t = self.torch
         rows = (n_new + k) if all_rows else (k + 1)
         o = {"top_ids": t.empty((batch, rows, topk), dtype=t.int32, device=self.device),
@@ -196,12 +198,15 @@ class Drafter:
             o["logits"] = t.empty((batch, rows, self.shape.vocab), dtype=t.float32, device=self.device)
         if probs:
             o["probs"] = t.empty((batch, rows, self.shape.vocab), dtype=t.float32, device=self.device)
+        if sample:
+            o["sample_ids"] = t.empty((batch, rows), dtype=t.int32, device=self.device)
+            o["sample_p"] = t.empty((batch, rows), dtype=t.float32, device=self.device)
         if hidden:
             o["hidden_out"] = t.empty((batch, n_new + k, self.shape.hidden), dtype=t.float32, device=self.device)
         return o
 
     def make_args(self, x, k_cache, v_cache, kv_offsets, kv_len, n_new, k, topk, outputs, all_rows=False,
-                  token_ids=None, features=None):
+                  token_ids=None, features=None, temperature=0.0, sample_seed=0, kv_len_dev=None):
         """Builds the argument struct; keeps the host arrays alive on the struct.  x: hidden states, or None
         when token_ids (and features) are given."""
         a = ps_draft_step_args()
@@ -210,7 +215,11 @@ class Drafter:
         a.k_cache, a.v_cache = k_cache.data_ptr(), v_cache.data_ptr()
         a.token_ids = token_ids.data_ptr() if token_ids is not None else None
         a.features = features.data_ptr() if features is not None else None
-        a._keep_in = (token_ids, features)
+        a._keep_in = (token_ids, features, kv_len_dev)
+        a.temperature, a.sample_seed = temperature, sample_seed
+        a.kv_len_dev = kv_len_dev.data_ptr() if kv_len_dev is not None else None
+        for n in ("sample_ids", "sample_p"):
+            setattr(a, n, outputs[n].data_ptr() if n in outputs else None)
         off = np.ascontiguousarray(kv_offsets, dtype=np.int64)
         ln = np.ascontiguousarray(kv_len, dtype=np.int32)
         a._keep = (off, ln, x, k_cache, v_cache, outputs)

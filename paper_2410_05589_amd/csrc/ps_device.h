@@ -180,6 +180,24 @@ typedef __attribute__((address_space(3))) unsigned lds_u32;
 __device__ __forceinline__ unsigned ps_seq() {
     return __builtin_amdgcn_readfirstlane(*(const lds_u32*)(unsigned)PS_LDS_SEQ);
 }
+// The sequences' cache lengths: every workgroup copies them into LDS when the kernel starts (kv_fill), from
+// the kernel arguments or, if the caller keeps them in device memory (so that a replayed graph can move on),
+// from there.  Readers come after at least one barrier.
+typedef __attribute__((address_space(3))) int lds_i32;
+__device__ __forceinline__ void kv_fill(const StepParams& P) {
+    if (threadIdx.x >= 64) return;
+    const int lane = threadIdx.x;
+    int v = 0;
+    if (P.kv_len_dev) {
+        if (lane < P.B) v = __builtin_nontemporal_load(P.kv_len_dev + lane);
+    } else {
+        for (int b = 0; b < P.B; ++b) v = lane == b ? P.kv_len[b] : v;   // (uniform index: the arguments stay scalar data)
+    }
+    if (lane < P.B) ((lds_i32*)(unsigned)PS_LDS_KVLEN)[lane] = v;
+}
+__device__ __forceinline__ int kvlen(int b) { return ((const lds_i32*)(unsigned)PS_LDS_KVLEN)[b]; }
+__device__ __forceinline__ int kvlen_u(int b) { return __builtin_amdgcn_readfirstlane(kvlen(b)); }   // wavefront-uniform b
+
 // Exchange buffers exist twice; P holds the addresses in copy 0, step n uses copy n & 1
 __device__ __forceinline__ const char* act_ptr(const StepParams& P, const void* copy0) {
     return reinterpret_cast<const char*>(copy0) + (ps_seq() & 1u) * P.act_bytes;
@@ -356,6 +374,23 @@ __device__ __forceinline__ float key_value(u64 k) {
     return __uint_as_float(ord ^ ((ord >> 31) ? 0x80000000u : 0xFFFFFFFFu));
 }
 __device__ __forceinline__ int key_id(u64 k) { return 0x7FFFFFFF - (int)(unsigned)k; }
+
+// The draw of the sampling epilogue (Algorithm 1's draft line samples from the draft distributions): the
+// Gumbel-max construction, token = argmax_i (z_i + g_i) with g_i = -log(-log(u_i)), which is an exact sample of
+// softmax(z).  u_i for output row `row` and token `id` comes from a counter-based generator: three rounds of
+// MurmurHash3's 32-bit finaliser over the seed's low word plus 0x9E3779B9 (row + 1), then the seed's high word,
+// then id * 0x9E3779B1 + 0x7F4A7C15; u = ((h >> 9) + 0.5) 2^-23 lies in (0, 1) and is exact in float32.
+__device__ __forceinline__ unsigned fmix32(unsigned h) {
+    h ^= h >> 16; h *= 0x85EBCA6Bu; h ^= h >> 13; h *= 0xC2B2AE35u; h ^= h >> 16;
+    return h;
+}
+__device__ __forceinline__ float gumbel_of(const StepParams& P, int row, int id) {
+    unsigned x = fmix32(P.seed_lo + 0x9E3779B9u * (unsigned)(row + 1));
+    x = fmix32(x ^ P.seed_hi);
+    x = fmix32(x ^ ((unsigned)id * 0x9E3779B1u + 0x7F4A7C15u));
+    const float u = ((float)(x >> 9) + 0.5f) * 1.1920928955078125e-07f;
+    return -logf(-logf(u));
+}
 
 // Row m of the step's activation matrix Z = [x rows ; mask embeddings] (Section 4.1: the k
 // [MASK] tokens are appended after the sequence), element offset e.
@@ -579,7 +614,7 @@ __device__ __forceinline__ void epilogue_qkv(const StepParams& P, int tau, int l
         const int m = 16 * mt + c;
         if (m >= P.Mtot) continue;
         const int b = row_seq(P, m), i = m - b * P.M;
-        const int pos = P.kv_len[b] + i;             // positions continue after the valid cache rows
+        const int pos = kvlen(b) + i;                // positions continue after the valid cache rows
         f32x4 o = v;
         if (hh < P.nq + P.nkv) {
             const float2* cs = P.rope + (size_t)pos * half + jb;
@@ -684,7 +719,7 @@ __device__ __forceinline__ void epilogue_lm(const StepParams& P, int tau, int la
     for (int mt = 0; mt < MT; ++mt) {
         const int m = 16 * mt + c;
         if (m >= P.Rtot) continue;
-        f32x4 o = acc[mt];
+        f32x4 o = acc[mt] * P.inv_temp;      // what softmax, top-k and the draw see: logits / temperature
 #pragma unroll
         for (int r = 0; r < 4; ++r)
             if (n + r >= P.V) o[r] = -INFINITY;
@@ -692,7 +727,7 @@ __device__ __forceinline__ void epilogue_lm(const StepParams& P, int tau, int la
         if (P.logits_store) {
 #pragma unroll
             for (int r = 0; r < 4; ++r)
-                if (n + r < P.V) P.logits_store[(size_t)m * P.V + n + r] = o[r];
+                if (n + r < P.V) P.logits_store[(size_t)m * P.V + n + r] = acc[mt][r];
         }
     }
 }
@@ -866,7 +901,7 @@ __device__ __forceinline__ void lm_local_stats(const StepParams& P, const PhaseD
     const int li = lane & (LPR - 1), grp = lane / LPR;
     const int topk = P.topk;
     const rsrc_t rl = make_rsrc(P.lm_part);
-    const unsigned stride = 2 + 2 * topk;       // tagged elements: max, sum exp, topk keys (low, high word)
+    const unsigned stride = 4 + 2 * topk;       // tagged elements: max, sum exp, topk keys (low, high word), the draw's key
     const unsigned seq = ps_seq();
     for (int m0 = wave; m0 < rows; m0 += PS_WAVES * GPW) {
         const int mm = m0 + grp * PS_WAVES;
@@ -911,6 +946,26 @@ __device__ __forceinline__ void lm_local_stats(const StepParams& P, const PhaseD
             if (live && li < 2)
                 ll_st1(rl, obase + 2 + 2 * t + li, __uint_as_float(li ? (unsigned)(best >> 32) : (unsigned)best), seq);
             prev = best ? best : 0;   // 0: list exhausted, every later entry is "none"
+        }
+        if (P.sample_ids) {   // the workgroup's best perturbed logit (see gumbel_of)
+            u64 gbest = 0;
+#pragma unroll
+            for (int i = 0; i < EPL; ++i)
+                if (i < nepl && keys[i]) {
+                    const int id = key_id(keys[i]);
+                    const u64 kx = make_key(key_value(keys[i]) + gumbel_of(P, m, id), id);
+                    gbest = kx > gbest ? kx : gbest;
+                }
+            for (int x = li + LPR * EPL; x < n_el; x += LPR) {
+                const int lt = x >> 4;
+                const float v = s_lm[(lt * rows + m) * 16 + (x & 15)];
+                const int id = 16 * tile_index(D, lt >> sl_log, lt & (SL - 1), j) + (x & 15);
+                const u64 kx = v > -INFINITY ? make_key(v + gumbel_of(P, m, id), id) : 0;
+                gbest = kx > gbest ? kx : gbest;
+            }
+            gbest = grp_max_u64<LPR>(gbest);
+            if (live && li < 2)
+                ll_st1(rl, obase + 2 + 2 * topk + li, __uint_as_float(li ? (unsigned)(gbest >> 32) : (unsigned)gbest), seq);
         }
     }
 }
@@ -1194,11 +1249,11 @@ __device__ __forceinline__ AttnItem attn_decode(const StepParams& P, int item, i
     AttnItem it;
     int b = 0, rem = item, nch = 0;
     for (;; ++b) {
-        nch = (P.kv_len[b] + P.attn_tail + (1 << ch_log) - 1) >> ch_log;
+        nch = (kvlen_u(b) + P.attn_tail + (1 << ch_log) - 1) >> ch_log;
         if (rem < nch * P.nkv) break;
         rem -= nch * P.nkv;
     }
-    it.b = b; it.nch = nch; it.hk = rem / nch; it.ch = rem - it.hk * nch; it.L = P.kv_len[b];
+    it.b = b; it.nch = nch; it.hk = rem / nch; it.ch = rem - it.hk * nch; it.L = kvlen_u(b);
     return it;
 }
 
@@ -1408,7 +1463,17 @@ __device__ __forceinline__ void attn_phase(const StepParams& P, int wg, int nwg,
     // again, in a loop.
     AttnItem cur = {0, 0, 0, 1, 0};
     const int wkey = 16 * NK * wave;                // this wavefront's keys within a chunk: wkey .. wkey + 16 NK - 1
-    if (wg < P.attn_items) {
+    // work items: the host's counts, unless the lengths are device data (then the host only knew upper bounds)
+    int n_items = P.attn_items, n_merge = P.attn_merge_items;
+    if (P.kv_len_dev) {
+        n_items = 0; n_merge = 0;
+        for (int b = 0; b < P.B; ++b) {
+            const int nch = (kvlen_u(b) + P.attn_tail + CH - 1) >> CH_LOG;
+            n_items += nch * P.nkv;
+            if (nch > 1 || P.attn_sep) n_merge += P.nkv * ((Ra + PS_WAVES - 1) / PS_WAVES);
+        }
+    }
+    if (wg < n_items) {
         cur = attn_decode(P, wg, CH_LOG);
 #pragma unroll
         for (int j = 0; j < NK; ++j) attn_load_k<WT, D>(P, cur, cur.ch * CH + wkey + 16 * j, lane, kreg[j]);
@@ -1605,11 +1670,11 @@ __device__ __forceinline__ void attn_phase(const StepParams& P, int wg, int nwg,
         cur = nx;
         stamp(P, wg, 34);
     };
-    if (wg + nwg >= P.attn_items) {
-        if (wg < P.attn_items) do_item(wg, cur, false, std::false_type());
+    if (wg + nwg >= n_items) {
+        if (wg < n_items) do_item(wg, cur, false, std::false_type());
     } else if constexpr (NK == 1) {   // (the host uses two key groups per wavefront only when no workgroup gets a second item)
-        for (int item = wg; item < P.attn_items; item += nwg) {
-            const bool has_next = item + nwg < P.attn_items;
+        for (int item = wg; item < n_items; item += nwg) {
+            const bool has_next = item + nwg < n_items;
             do_item(item, has_next ? attn_decode(P, item + nwg, CH_LOG) : cur, has_next, std::true_type());
         }
     }
@@ -1625,10 +1690,10 @@ __device__ __forceinline__ void attn_phase(const StepParams& P, int wg, int nwg,
     const int RT = (Ra + MR - 1) / MR;
     float* sW = sP;                                  // [MR][GRP] weights (the probabilities' area: same size)
     constexpr int SEP_ML = 64;                       // (max, sum) of the step's own rows: sM / sL [SEP_ML + row], beside the groups' [row]
-    for (int mi = wg; mi < P.attn_merge_items; mi += nwg) {
+    for (int mi = wg; mi < n_merge; mi += nwg) {
         int b = 0, rem = mi, nch = 0, item_base = 0;
         for (;; ++b) {
-            nch = (P.kv_len[b] + P.attn_tail + CH - 1) >> CH_LOG;
+            nch = (kvlen_u(b) + P.attn_tail + CH - 1) >> CH_LOG;
             const int n = (nch > 1 || P.attn_sep) ? P.nkv * RT : 0;
             if (rem < n) break;
             rem -= n;
@@ -1832,21 +1897,22 @@ __device__ __forceinline__ void attn_phase(const StepParams& P, int wg, int nwg,
 // sk: LDS scratch of PS_MERGE_BYTES.
 // ------------------------------------------------------------------------------------------
 #define PS_MAX_TOPK 32
-#define PS_MERGE_BYTES (PS_WAVES * PS_MAX_TOPK * 8 + PS_WAVES * 8)
+#define PS_MERGE_BYTES (PS_WAVES * PS_MAX_TOPK * 8 + PS_WAVES * 8 + PS_WAVES * 8)
 __device__ __forceinline__ void lm_merge_row(const StepParams& P, int m, int wave, char* scratch) {
     const int tid = threadIdx.x, lane = tid & 63;
     const int nparts = min(P.ph[PH_LMHEAD].nwg, P.ph[PH_LMHEAD].T);   // workgroups that had vocabulary tiles
     const int topk = P.topk;
-    const unsigned stride = 2 + 2 * topk;                  // tagged elements per (workgroup, row)
+    const unsigned stride = 4 + 2 * topk;                  // tagged elements per (workgroup, row)
     const unsigned pstride = (unsigned)P.Rtot * stride;
     const rsrc_t rl = make_rsrc(P.lm_part);
     const unsigned seq = ps_seq();
     u64* sk = reinterpret_cast<u64*>(scratch);                              // [waves][PS_MAX_TOPK] keys
     float* sf = reinterpret_cast<float*>(scratch + PS_WAVES * PS_MAX_TOPK * 8);   // [waves] max, [waves] sum
+    u64* sg = reinterpret_cast<u64*>(scratch + PS_WAVES * PS_MAX_TOPK * 8 + PS_WAVES * 8);   // [waves] the draw's keys
     const bool mine = tid < nparts;                        // host: nparts <= PS_WG_THREADS
     const unsigned base = ((unsigned)m * stride + (mine ? tid : 0) * pstride) * 8;   // bytes
     constexpr int KB = 8;                                  // keys requested per round trip
-    u64 keys[PS_MAX_TOPK];
+    u64 keys[PS_MAX_TOPK], gkey = 0;
     float pmax = -INFINITY, psum = 0.f;
 #pragma unroll
     for (int t0 = 0; t0 < PS_MAX_TOPK; t0 += KB) {
@@ -1855,7 +1921,7 @@ __device__ __forceinline__ void lm_merge_row(const StepParams& P, int m, int wav
             for (int i = 0; i < KB; ++i) keys[t0 + i] = 0;
             continue;
         }
-        u32x4 hd, kr[KB];
+        u32x4 hd, kr[KB], gk;
         int spins = 0;
         for (;;) {
             hd = coh_ld16(rl, base);                       // {max, tag, sum, tag}
@@ -1864,12 +1930,13 @@ __device__ __forceinline__ void lm_merge_row(const StepParams& P, int m, int wav
                 const int t = t0 + i < topk ? t0 + i : topk - 1;
                 kr[i] = coh_ld16(rl, base + (2 + 2 * t) * 8);   // {low, tag, high, tag}
             }
-            unsigned bad = (unsigned)(hd[1] != seq) | (unsigned)(hd[3] != seq);   // all loads first, then all checks
+            gk = coh_ld16(rl, base + ((t0 == 0 && P.sample_ids) ? 2 + 2 * topk : 0) * 8);   // the draw's key (else the head again)
+            unsigned bad = (unsigned)(hd[1] != seq) | (unsigned)(hd[3] != seq) | (unsigned)(gk[1] != seq) | (unsigned)(gk[3] != seq);   // all loads first, then all checks
 #pragma unroll
             for (int i = 0; i < KB; ++i) bad |= (unsigned)(kr[i][1] != seq) | (unsigned)(kr[i][3] != seq);
             if (__all(!bad || !mine) || !spin_again(P, spins)) break;
         }
-        if (t0 == 0 && mine) { pmax = __uint_as_float(hd[0]); psum = __uint_as_float(hd[2]); }
+        if (t0 == 0 && mine) { pmax = __uint_as_float(hd[0]); psum = __uint_as_float(hd[2]); gkey = ((u64)gk[2] << 32) | gk[0]; }
 #pragma unroll
         for (int i = 0; i < KB; ++i)
             keys[t0 + i] = (mine && t0 + i < topk) ? (((u64)kr[i][2] << 32) | kr[i][0]) : 0;
@@ -1882,6 +1949,10 @@ __device__ __forceinline__ void lm_merge_row(const StepParams& P, int m, int wav
     // this wavefront's share of the log-sum-exp and its sorted top-k
     const float wmax = wave_max(pmax);
     if (lane == 0) sf[wave] = wmax;
+    if (P.sample_ids) {
+        const u64 wg_best = wave_max_u64(gkey);
+        if (lane == 0) sg[wave] = wg_best;
+    }
     u64 prev = ~0ull;
     for (int t = 0; t < topk; ++t) {
         u64 best = 0;
@@ -1911,6 +1982,15 @@ __device__ __forceinline__ void lm_merge_row(const StepParams& P, int m, int wav
         for (int w = 0; w < PS_WAVES; ++w) se += sf[PS_WAVES + w];
         const float lse = gave_up ? __uint_as_float(0x7FC00000u) : mx + logf(se);   // a step that gave up a wait: NaN, ids -1
         if (lane == 0) P.lse[m] = lse;
+        if (P.sample_ids && lane == 0) {
+            u64 best = 0;
+#pragma unroll
+            for (int w = 0; w < PS_WAVES; ++w) best = sg[w] > best ? sg[w] : best;
+            const int id = key_id(best);
+            // the winner's own logit: its perturbed value minus its Gumbel number
+            P.sample_ids[m] = (gave_up || !best) ? -1 : id;
+            if (P.sample_p) P.sample_p[m] = (gave_up || !best) ? 0.f : expf(key_value(best) - gumbel_of(P, m, id) - lse);
+        }
         // PS_WAVES sorted lists of topk keys: 4 candidates per lane
         constexpr int CPL = PS_WAVES * PS_MAX_TOPK / 64;
         u64 cand[CPL];
@@ -1960,6 +2040,7 @@ __device__ __forceinline__ unsigned step_begin(const StepParams& P, bool count) 
     unsigned ticket;
     const unsigned seq = step_read(P, count, ticket);
     if (threadIdx.x == 0) *(lds_u32*)(unsigned)PS_LDS_SEQ = seq;
+    kv_fill(P);
     __syncthreads();
     return ticket;
 }
@@ -2001,7 +2082,7 @@ static __global__ void __launch_bounds__(256) probs_kernel(const StepParams P) {
     const int m = blockIdx.y;
     const float lse = P.lse[m];
     for (int n = blockIdx.x * 256 + threadIdx.x; n < P.V; n += gridDim.x * 256)
-        P.probs[(size_t)m * P.V + n] = expf(P.logits_store[(size_t)m * P.V + n] - lse);
+        P.probs[(size_t)m * P.V + n] = expf(P.logits_store[(size_t)m * P.V + n] * P.inv_temp - lse);
 }
 
 // The whole step in one persistent kernel: gridDim.x workgroups, all resident.  No grid-wide
@@ -2018,6 +2099,7 @@ __global__ void __launch_bounds__(PS_WG_THREADS, 1) fused_kernel(const StepParam
     stamp(P, wg, 1);
     unsigned ticket;
     const unsigned my_seq = step_read(P, false, ticket);
+    kv_fill(P);                                  // (read after the first phase's barriers at the earliest)
     preload_weights(wb, first_stream(P, PH_QKV, wg, wave), lane * 16);
     gemm_phase<WT, MT, PH_QKV>(P, wg, wave, smem, wb, first_stream(P, PH_OPROJ, wg, wave), my_seq);
     __syncthreads();

@@ -155,7 +155,7 @@ static WsLayout ws_layout(const ps_draft_config* c) {
     L.exch_begin = off;
     L.attn_acc = take(max_items * ra * c->head_dim * 8);
     L.attn_ml = take(max_items * ra * 2 * 8);
-    L.lm_part = take((size_t)PS_MAX_WG * rows * (2 + 2 * c->max_topk) * 8 + 64);
+    L.lm_part = take((size_t)PS_MAX_WG * rows * (4 + 2 * c->max_topk) * 8 + 64);
     L.exch_end = off;
     L.n_counters = 0;
     L.counters = take(256);  // PS_CTR_*: error flag, steps completed, tickets of the running kernel, footprints
@@ -509,6 +509,8 @@ extern "C" int ps_draft_step(ps_draft_ctx* ctx, const ps_draft_step_args* a, voi
         if (!a->x) return PS_ERR_NULL;
         if (a->features) return PS_ERR_SHAPE;                // features go with token ids
     }
+    if (!(a->temperature >= 0.f) || a->temperature > 1e30f) return PS_ERR_SHAPE;   // 0 stands for 1
+    if (a->sample_p && !a->sample_ids) return PS_ERR_NULL;
     const int M = a->n_new + a->k;
     for (int b = 0; b < a->batch; ++b) {
         if (a->kv_offsets[b] < 0 || a->kv_offsets[b + 1] < a->kv_offsets[b]) return PS_ERR_OFFSETS;
@@ -531,6 +533,9 @@ extern "C" int ps_draft_step(ps_draft_ctx* ctx, const ps_draft_step_args* a, voi
     P.g_post = ctx->w.g_post; P.w_gate = ctx->w.w_gate; P.w_up = ctx->w.w_up; P.w_down = ctx->w.w_down;
     P.g_final = ctx->w.g_final; P.w_lm = ctx->w.w_lm; P.mask_emb = ctx->w.mask_emb;
     P.x = a->x; P.kc = a->k_cache; P.vc = a->v_cache;
+    P.inv_temp = a->temperature > 0.f ? 1.0f / a->temperature : 1.0f;
+    P.seed_lo = (unsigned)(a->sample_seed & 0xFFFFFFFFull); P.seed_hi = (unsigned)(a->sample_seed >> 32);
+    P.sample_ids = a->sample_ids; P.sample_p = a->sample_p; P.kv_len_dev = a->kv_len_dev;
     P.in_mode = in_mode; P.token_ids = a->token_ids; P.features = a->features;
     P.embed = ctx->w.embed; P.w_fc = ctx->w.w_fc; P.b_fc = ctx->w.b_fc;
     P.n_magic = 0xFFFFFFFFu / (unsigned)a->n_new + 1u;

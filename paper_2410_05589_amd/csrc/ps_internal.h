@@ -95,6 +95,14 @@ struct StepParams {
     int spin_limit;    // polls after which a wait for exchanged data is given up (see spin_again)
     int final_norm, max_positions;
     float eps, inv_sqrt_d;
+    // sampling epilogue: logits are divided by the temperature before softmax, top-k probabilities and the
+    // draw; sample_ids != NULL asks for one Gumbel-max draw per output row with the counter-based generator
+    // (see gumbel_of in ps_device.h)
+    float inv_temp;
+    unsigned seed_lo, seed_hi;
+    int32_t* sample_ids;
+    float* sample_p;
+    const int32_t* kv_len_dev;   // the sequences' lengths in device memory (then kv_len[] below holds upper bounds), or NULL
     // weights and step inputs (config dtype)
     const void *g_in, *wq, *wk, *wv, *wo, *g_post, *w_gate, *w_up, *w_down, *g_final, *w_lm, *mask_emb, *w_fc;
     const void* x;

@@ -56,9 +56,9 @@ def test_struct_layouts_match_header():
     body = text[text.index("typedef struct ps_draft_weights {"):text.index("} ps_draft_weights;")]
     assert re.findall(r"const void\*\s+([a-z_]+);", body) == list(B.WEIGHT_NAMES + B.INPUT_WEIGHT_NAMES)
     body = text[text.index("typedef struct ps_draft_step_args {"):text.index("} ps_draft_step_args;")]
-    names = re.findall(r"\b(?:int32_t\*?|float\*|const void\*|void\*|const int64_t\*|const int32_t\*)\s+\*?([a-z_]+)[;,]", body)
-    fields = [f[0] for f in B.ps_draft_step_args._fields_]
-    assert set(fields) <= set(names) | {"v_cache", "top_p", "lse", "probs", "hidden_out"}
+    body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
+    names = [n for line in re.findall(r"[^;{]+;", body) for n in re.findall(r"\*?\s*\**([a-z_]+)\s*[,;]", line)]
+    assert names == [f[0] for f in B.ps_draft_step_args._fields_]
     assert ctypes.sizeof(B.ps_draft_config) == 15 * 4
 
 
