@@ -117,6 +117,19 @@ def test_root_only_tree_just_draws_a_token():
     assert gpu["out_tokens"][0, 0] == first              # u = 0 draws the first token with probability > 0
 
 
+def test_proposals_the_drafter_gave_no_mass():
+    """q(x) = 0 at proposed tokens counts as ratio 1 (accepted for every r < 1), in both kernels' paths."""
+    for vocab, batch in ((32000, 6), (65536, 3)):
+        parent, rank = inputs.draft_tree([3, 2])
+        inp = inputs.verify_inputs(55 + vocab % 7, batch, parent, rank, 3, 8, vocab, agreement=0.3)
+        tok = np.stack([vw.tree_tokens(inp["top_ids"][b], parent, rank) for b in range(batch)])
+        for b in range(batch):
+            for s in (1, 3, 4, 7):                 # some first children, some later ones, both depths
+                inp["q"][b, 0 if s <= 3 else 1, tok[b, s]] = 0.0
+        gpu = _check(parent, rank, inp, 3, 8, "q(x) = 0, V %d" % vocab)
+        assert (gpu["n_accepted"] >= 1).all()      # node 1 carries a token with q = 0: always accepted
+
+
 def test_token_outside_the_vocabulary_is_skipped():
     parent, rank = inputs.draft_tree([3, 1])
     inp = inputs.verify_inputs(6, 5, parent, rank, 3, 8, 2000, agreement=0.9)

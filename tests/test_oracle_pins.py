@@ -428,3 +428,36 @@ def test_planted_mistakes_are_caught():
     kc2[1:8] = kk[:7]; vc2[1:8] = vv[:7]; kc2[0] = kk[0]; vc2[0] = vv[0]
     bad = orc.draft_step(shape, w, x, kc2, vc2, np.array([0, cap + 1]), np.array([8]), 2, 3, topk=3, all_rows=True)
     assert np.abs(bad["logits"][0] - logits[7:]).max() > 1e-3
+
+
+def test_one_ulp_flips_of_new_cache_rows_move_logits_by_less_than_the_gpu_tests_allow(monkeypatch):
+    """Evidence for the bound the GPU parity tests put on bf16 logits (5e-3, tests/gpu_util.py).  The step
+    rounds its new K/V rows to bf16 before attention reads them; a device that computes those rows in float32
+    lands on the neighbouring bf16 value wherever the exact value sits within float32 error of a rounding
+    boundary (measured on the device: about 0.3 % of the new elements).  Here that is planted in the oracle at
+    the 7B shape - 1 % of the new elements moved by one unit in the last place, three times the measured rate -
+    and the logits move by more than the arithmetic error of the device path (5e-5) but stay below the bound."""
+    from paper_2410_05589_amd.configs import WORKLOADS
+    wl = WORKLOADS["c1"]
+    shape = wl.shape
+    w = inputs.make_weights(shape, wl.seed)
+    inp = inputs.make_step_inputs(wl)
+    args = (shape, w, inp["x"], inp["k_cache"], inp["v_cache"], inp["kv_offsets"], inp["kv_len"], wl.n_new, wl.k, wl.topk)
+    ref = orc.draft_step(*args)
+    exact = orc.round_to_storage
+    rng = np.random.default_rng(0)
+
+    def flipped(a, dt):
+        r = exact(a, dt)
+        if dt != "bf16":
+            return r
+        hit = rng.random(r.shape) < 0.01
+        step = np.where(rng.random(r.shape) < 0.5, 1, -1)
+        return np.where(hit, (r.astype(np.int32) + step).astype(np.uint16), r)
+
+    monkeypatch.setattr(orc, "round_to_storage", flipped)
+    out = orc.draft_step(*args)
+    moved = float(np.abs(out["logits"] - ref["logits"]).max())
+    n_flipped = int((out["k_cache"] != ref["k_cache"]).sum() + (out["v_cache"] != ref["v_cache"]).sum())
+    assert n_flipped > 200
+    assert 5e-5 < moved < 5e-3, moved

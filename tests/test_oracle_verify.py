@@ -142,3 +142,31 @@ def test_tree_tokens_of_a_hand_made_tree():
     rank = np.array([0, 0, 1, 0, 2, 1, 1])
     assert vw.tree_depths(parent).tolist() == [0, 1, 1, 2, 2, 2, 3]
     assert vw.tree_tokens(top_ids, parent, rank).tolist() == [-1, 10, 11, 20, 22, 21, 31]
+
+
+def test_a_proposal_the_drafter_gave_no_mass_counts_as_ratio_one():
+    """The reading for q(x) = 0 (the paper does not say): the limit of min(1, P(x) / q) as q -> 0+ for a token
+    the target supports.  Pinned against that limit - the same walk with q(x) a denormal instead of 0 takes
+    the same decisions - and against its consequences: such a child is accepted for every r < 1, the walk moves
+    on to it, and P becomes the target's row at it."""
+    V = 6
+    g = np.random.default_rng(21)
+    parent = np.array([-1, 0, 0, 1])
+    tokens = np.array([-1, 2, 4, 5])
+    p = _dirichlet(g, 4, V)
+    q = _dirichlet(g, 2, V)
+    q[0, 2] = 0.0
+    q[0] /= q[0].sum()
+    q_tiny = q.copy()
+    q_tiny[0, 2] = 5e-324
+    for trial in range(200):
+        r = g.random(4)
+        r[1] = 1.0 - 2.0 ** -24 if trial == 0 else r[1]         # even the largest r a float32 uniform can be
+        a = vw.acceptance_walk(parent, tokens, q, p, r)
+        b = vw.acceptance_walk(parent, tokens, q_tiny, p, r)
+        assert a["path"] == b["path"] and a["tokens"] == b["tokens"]
+        assert a["path"][0] == 1 and a["tokens"][0] == 2         # node 1 (token 2, q = 0) is always accepted
+        if a["n_accepted"] == 1:
+            # its child was rejected: the final draw comes from the residual of the target's row AT NODE 1
+            res = np.maximum(p[1] - q[1], 0.0)
+            np.testing.assert_allclose(a["final_P"], res / res.sum(), rtol=1e-12)
