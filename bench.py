@@ -428,6 +428,54 @@ def sampling_report(torch, name="c1", steps=200, warmup=20):
     return rep
 
 
+def group_attention_report(torch, with_oracle, T=2048, k=4, heads=32, d=128, calls=20):
+    """The attention of group-wise parallel training (Section 4.1) for one training sequence of T tokens laid out
+    as T parallel groups of k + 1 rows, the 7B drafter's 32 heads x 128, bf16.  A dense contraction: its bound is
+    the MFMA peak; FLOPs = 4 d per visible (query, key) pair and head (scores and P.V)."""
+    from paper_2410_05589_amd import binding as B
+    from paper_2410_05589_amd import inputs
+    from paper_2410_05589_amd import train as TR
+    inp = inputs.make_group_attention_inputs(1, 1, T, k, heads, heads, d, "bf16")
+    a = TR.make_args(1, T, k, heads, heads, d, "bf16", 10000.0)
+    q, kk, v = (B.to_device(inp[n], "bf16") for n in ("q", "k", "v"))
+    out = torch.empty((1, T * (k + 1), heads, d), dtype=torch.float32, device="cuda:0")
+    ws = torch.empty(TR.ps_group_attention_workspace_bytes(a) + 256, dtype=torch.uint8, device="cuda:0")
+    a.q, a.k_, a.v, a.out = q.data_ptr(), kk.data_ptr(), v.data_ptr(), out.data_ptr()
+    a.workspace, a.workspace_bytes = (ws.data_ptr() + 255) & ~255, ws.numel() - 256
+    stream = torch.cuda.current_stream()
+    for _ in range(3):
+        assert TR.ps_group_attention(a, stream.cuda_stream) == 0
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(stream)
+    for _ in range(calls):
+        TR.ps_group_attention(a, stream.cuda_stream)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    us = e0.elapsed_time(e1) * 1e3 / calls
+    pairs = (k + 1) * T * (T + 1) // 2 + T * k * (k + 1) // 2
+    flops = 4.0 * d * pairs * heads
+    tf = flops / (us * 1e-6) / 1e12
+    rep = {"workload": "T %d tokens x (1 + %d [MASK]) = %d rows, %d heads x %d, bf16, 1 sequence" % (T, k, T * (k + 1), heads, d),
+           "latency_us": round(us, 1), "visible_pairs_per_head": pairs, "dtype": "bf16",
+           "roofline": {"bound": "mfma", "achieved": round(tf, 2), "peak": 2500.0, "unit": "TFLOP/s", "frac": round(tf / 2500.0, 4),
+                        "traffic": None, "flops_per_launch": flops,
+                        "note": "scores run on the matrix cores, P.V still on the vector ALU (fp32 peak 157.3 TFLOP/s)"}}
+    if with_oracle:
+        from oracle import group_attention as ga
+        Ts = 96                                    # the oracle on the first 96 tokens (480 rows) of 4 heads
+        c0 = time.perf_counter()
+        want = ga.group_attention(inp["q"][0][:Ts * (k + 1), :4], inp["k"][0][:Ts * (k + 1), :4], inp["v"][0][:Ts * (k + 1), :4],
+                                  Ts, k, 10000.0, "bf16")
+        cpu_s = time.perf_counter() - c0
+        got = out.cpu().numpy()[0, :Ts * (k + 1), :4]
+        spairs = ((k + 1) * Ts * (Ts + 1) // 2 + Ts * k * (k + 1) // 2) * 4
+        rep["cpu_baseline"] = {"value": round(4.0 * d * spairs / cpu_s / 1e9, 3), "unit": "GFLOP/s", "cores": 1, "kind": "oracle",
+                               "sample": "the first %d tokens of 4 heads (numpy float64, %.2f s)" % (Ts, cpu_s)}
+        rep["max_abs_error_vs_oracle_on_sample"] = float(np.abs(got - want).max())
+    return rep
+
+
 def verify_walk_report(torch, with_oracle, vocab=32000, k=5, calls=200):
     """Tree construction + acceptance walk (the step after the draft step in Algorithm 1) on a tree of the
     workload's drafter: 61 nodes (fan-out 4, 2, 2, 1, 1 over the k+1 = 6 draft rows) for k = 5, 46 nodes
@@ -572,7 +620,8 @@ def main():
     if not args.no_next_rows:
         hw = WORKLOADS[HEADLINE if args.workload == "all" else args.workload]
         result["next_rows"] = {"verify_walk": verify_walk_report(torch, not args.no_cpu_baseline, vocab=hw.shape.vocab, k=hw.k),
-                               "input_stage": input_stage_report(torch), "sampling": sampling_report(torch)}
+                               "input_stage": input_stage_report(torch), "sampling": sampling_report(torch),
+                               "group_attention": group_attention_report(torch, not args.no_cpu_baseline)}
     print(json.dumps(result))
 
 

@@ -11,9 +11,9 @@ CSRC = os.path.join(PKG_DIR, "csrc")
 BUILD_DIR = os.path.join(PKG_DIR, "_build")
 HEADERS = [os.path.join(CSRC, "ps_internal.h"), os.path.join(CSRC, "ps_device.h"),
            os.path.join(ROOT, "include", "ps_draft.h"), os.path.join(ROOT, "include", "ps_verify.h"),
-           os.path.join(ROOT, "include", "ps_draft_debug.h")]
+           os.path.join(ROOT, "include", "ps_draft_debug.h"), os.path.join(ROOT, "include", "ps_train.h")]
 SOURCES = [os.path.join(CSRC, "ps_host.hip"), os.path.join(CSRC, "ps_inst.hip"), os.path.join(CSRC, "ps_verify.hip"),
-           os.path.join(CSRC, "ps_measure.hip")]
+           os.path.join(CSRC, "ps_measure.hip"), os.path.join(CSRC, "ps_train.hip")]
 # the device code is instantiated once per (storage type, head_dim)
 INSTANCES = [("f32_d64", 0, 64), ("f32_d128", 0, 128), ("bf16_d64", 1, 64), ("bf16_d128", 1, 128)]
 
@@ -50,7 +50,8 @@ def build_library(verbose=True, jobs=4):
               "-I", os.path.join(ROOT, "include"), "-I", CSRC] + os.environ.get("PS_BUILD_DEFS", "").split()
     units = [(os.path.join(BUILD_DIR, "ps_host.o"), [os.path.join(CSRC, "ps_host.hip")]),
              (os.path.join(BUILD_DIR, "ps_verify.o"), [os.path.join(CSRC, "ps_verify.hip")]),
-             (os.path.join(BUILD_DIR, "ps_measure.o"), [os.path.join(CSRC, "ps_measure.hip")])]
+             (os.path.join(BUILD_DIR, "ps_measure.o"), [os.path.join(CSRC, "ps_measure.hip")]),
+             (os.path.join(BUILD_DIR, "ps_train.o"), [os.path.join(CSRC, "ps_train.hip")])]
     for name, bf, d in INSTANCES:
         units.append((os.path.join(BUILD_DIR, "ps_inst_%s.o" % name),
                       ["-DPS_INST_NAME=%s" % name, "-DPS_INST_BF16=%d" % bf, "-DPS_INST_D=%d" % d,

@@ -1,0 +1,291 @@
+// Attention of group-wise parallel training (see include/ps_train.h; Section 4.1).
+//
+// Three kernels per call: the rotary table (cos, sin of position * base^(-2j/d) in double precision), the
+// rotation of q (to float32) and k (to the storage type, rounded as the inference path caches keys), and the
+// attention itself.
+//
+// The attention kernel never touches a key the mask hides.  A query tile is a whole number of parallel groups
+// (as many as fit into 16 rows); what its rows may see are (a) real tokens of groups up to their own - these
+// are gathered with a stride of k + 1 rows, 16 per key tile - and (b) [MASK] tokens of their own group, which
+// all lie inside the query tile's own 16 rows: one more key tile.  The wavefronts of a workgroup take the key
+// tiles in turn, each with its own running maximum, sum and output (online softmax); their results meet in LDS
+// at the end.  Scores are one MFMA tile per key tile (the keys' rows are the 16-row operand, straight from
+// memory; the 16 query rows, split into bf16 high and low parts, the 16-column operand in LDS); P.V is plain
+// FMA work: a lane owns head_dim / 64 output columns for all 16 rows.
+#include "ps_device.h"
+#include "ps_train.h"
+
+namespace {
+
+constexpr int GA_THREADS = 256, GA_WAVES = GA_THREADS / 64;
+
+struct GaParams {
+    int seqs, T, k, nq, nkv, rows, gpt, ntiles;   // gpt: groups per query tile
+    float inv_sqrt_d;
+    const void *q, *k_, *v;
+    float* out;
+    float2* table;      // [T + k][d / 2]
+    float* q_rot;       // [seqs][rows][nq][d]
+    void* k_rot;        // [seqs][rows][nkv][d] storage type
+    double log_base;
+};
+
+template <int D>
+__global__ void __launch_bounds__(256) ga_table_kernel(const GaParams P) {
+    const int n = (P.T + P.k) * (D / 2);
+    for (int x = blockIdx.x * 256 + threadIdx.x; x < n; x += gridDim.x * 256) {
+        const int pos = x / (D / 2), j = x - pos * (D / 2);
+        const double a = (double)pos * exp(-2.0 * j / D * P.log_base);
+        P.table[x] = make_float2((float)cos(a), (float)sin(a));
+    }
+}
+
+// one thread per (row, head, pair of 4 + 4 elements j..j+3, j+d/2..): q heads first, then k heads
+template <typename WT, int D>
+__global__ void __launch_bounds__(256) ga_rope_kernel(const GaParams P) {
+    constexpr int ESZ = Traits<WT>::ESZ, Q4 = D / 8;     // groups of 4 pairs per head
+    const long long n = (long long)P.seqs * P.rows * (P.nq + P.nkv) * Q4;
+    for (long long x = (long long)blockIdx.x * 256 + threadIdx.x; x < n; x += (long long)gridDim.x * 256) {
+        const int g4 = (int)(x % Q4);
+        long long y = x / Q4;
+        const int h = (int)(y % (P.nq + P.nkv));
+        const long long sr = y / (P.nq + P.nkv);           // seq * rows + row
+        const int row = (int)(sr % P.rows);
+        const int pos = row / (P.k + 1) + row % (P.k + 1);  // group + slot
+        const bool isq = h < P.nq;
+        const size_t base = isq ? ((size_t)sr * P.nq + h) * D : ((size_t)sr * P.nkv + (h - P.nq)) * D;
+        const char* src = (const char*)(isq ? P.q : P.k_);
+        const f32x4 a = load4<WT>(src + (base + 4 * g4) * ESZ), b = load4<WT>(src + (base + D / 2 + 4 * g4) * ESZ);
+        f32x4 ra, rb;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const float2 t = P.table[(size_t)pos * (D / 2) + 4 * g4 + e];
+            ra[e] = a[e] * t.x - b[e] * t.y;
+            rb[e] = b[e] * t.x + a[e] * t.y;
+        }
+        if (isq) {
+            *reinterpret_cast<f32x4*>(P.q_rot + base + 4 * g4) = ra;
+            *reinterpret_cast<f32x4*>(P.q_rot + base + D / 2 + 4 * g4) = rb;
+        } else {
+            store4<WT>((char*)P.k_rot + (base + 4 * g4) * ESZ, ra);
+            store4<WT>((char*)P.k_rot + (base + D / 2 + 4 * g4) * ESZ, rb);
+        }
+    }
+}
+
+template <typename WT, int D>
+__global__ void __launch_bounds__(GA_THREADS) ga_attn_kernel(const GaParams P) {
+    constexpr bool BF = Traits<WT>::BF;
+    constexpr int ESZ = Traits<WT>::ESZ, KSTEP = Traits<WT>::KSTEP, STEPS = D / KSTEP, DPL = D / 64;
+    constexpr int OFF_Q = 0;                                // 16 query rows as MFMA operands (hi, lo): 16 * D * 4 bytes
+    constexpr int OFF_P = OFF_Q + 16 * D * 4;               // [waves][16 rows][16 keys] probabilities
+    constexpr int OFF_A = OFF_P + GA_WAVES * 16 * 16 * 4;   // [waves][16] rescale factors of the running output
+    constexpr int OFF_ML = OFF_A + GA_WAVES * 16 * 4;       // [waves][16][2] final (max, sum)
+    constexpr int OFF_O = OFF_ML + GA_WAVES * 16 * 2 * 4;   // [waves][16][D] final outputs
+    __shared__ __attribute__((aligned(16))) char smem[OFF_O + GA_WAVES * 16 * D * 4];
+    typedef typename VRaw<WT, DPL>::type raw_t;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int c = lane & 15, kb = lane >> 4;
+    const int tile = P.ntiles - 1 - (int)blockIdx.x;        // the tiles with the most keys start first
+    const int h = blockIdx.y, seq = blockIdx.z, hk = h / (P.nq / P.nkv);
+    const int K1 = P.k + 1;
+    const int g0 = tile * P.gpt, ng = min(P.gpt, P.T - g0), nrows = ng * K1, r0 = g0 * K1;
+    const int g_last = g0 + ng - 1;
+    char* sQ = smem + OFF_Q;
+    float* sP = reinterpret_cast<float*>(smem + OFF_P) + wave * 256;
+    float* sA = reinterpret_cast<float*>(smem + OFF_A) + wave * 16;
+    float* sML = reinterpret_cast<float*>(smem + OFF_ML);
+    float* sO = reinterpret_cast<float*>(smem + OFF_O);
+
+    // ---- the query rows (rotated, float32) into LDS as the 16-column MFMA operand; rows beyond the tile repeat the last
+    const float* qbase = P.q_rot + ((size_t)seq * P.rows * P.nq + h) * D;
+    for (int t2 = tid; t2 < 16 * (D / 4); t2 += GA_THREADS) {
+        const int r = min(t2 / (D / 4), nrows - 1), g4 = t2 % (D / 4);
+        const u32x4 x = *reinterpret_cast<const u32x4*>(qbase + (size_t)(r0 + r) * P.nq * D + 4 * g4);
+        attn_store_q<WT, D>(sQ, t2, x);
+    }
+    __syncthreads();
+    BRegs<WT, 1> bq[STEPS];
+#pragma unroll
+    for (int t = 0; t < STEPS; ++t) {
+        if constexpr (BF) {
+            bq[t].h[0] = ld16(sQ + (2 * t * 64 + lane) * 16);
+            bq[t].l[0] = ld16(sQ + ((2 * t + 1) * 64 + lane) * 16);
+        } else {
+            bq[t].h[0] = ld16(sQ + (t * 64 + lane) * 16);
+        }
+    }
+    // this lane's query (column c of the score tile): group and slot
+    const int qr = min(c, nrows - 1), qg = g0 + qr / K1, qs = qr % K1;
+    const bool qlive = c < nrows;
+
+    const char* kbase = (const char*)P.k_rot + ((size_t)seq * P.rows * P.nkv + hk) * D * ESZ;
+    const char* vbase = (const char*)P.v + ((size_t)seq * P.rows * P.nkv + hk) * D * ESZ;
+    const size_t rstride = (size_t)P.nkv * D * ESZ;        // bytes between layout rows
+    const int n_real = (g_last >> 4) + 1;                   // key tiles of real tokens; one more tile: the tile's own [MASK] rows
+    float m_run = -INFINITY, l_run = 0.f;                   // of query c (the same in the four lanes that share it)
+    float o[16][DPL];
+#pragma unroll
+    for (int rr = 0; rr < 16; ++rr)
+#pragma unroll
+        for (int e = 0; e < DPL; ++e) o[rr][e] = 0.f;
+
+    for (int kt = wave; kt <= n_real; kt += GA_WAVES) {
+        const bool own = kt == n_real;                      // the [MASK] tokens of the tile's own groups
+        if (own && P.k == 0) break;
+        // layout row of key j of this tile (clamped to a row that exists)
+        auto key_row = [&](int j) __attribute__((always_inline)) {
+            return own ? r0 + min(j, nrows - 1) : min(16 * kt + j, g_last) * K1;
+        };
+        uint4 kreg[STEPS];
+        const char* krow = kbase + (size_t)key_row(c) * rstride + kb * 16;
+#pragma unroll
+        for (int t = 0; t < STEPS; ++t) kreg[t] = ld16(krow + t * 64);
+        raw_t vraw[16];
+#pragma unroll
+        for (int j = 0; j < 16; ++j)
+            vraw[j] = *reinterpret_cast<const raw_t*>(vbase + (size_t)key_row(j) * rstride + (size_t)DPL * lane * ESZ);
+        f32x4 acc[1] = {f32x4{0.f, 0.f, 0.f, 0.f}};
+#pragma unroll
+        for (int t = 0; t < STEPS; ++t) mma_step<WT, 1>(kreg[t], bq[t], acc);
+        // scores of keys 4 kb .. 4 kb + 3 for query c, masked
+        float sc[4], mt = -INFINITY;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int j = 4 * kb + r;
+            bool vis;
+            if (own) {
+                const int kg = g0 + j / K1, ks = j % K1;
+                vis = j < nrows && ks > 0 && kg == qg && ks <= qs;       // a [MASK] token of the query's own group, not after it
+            } else {
+                vis = 16 * kt + j <= qg;                                  // the real token of a group up to the query's own
+            }
+            sc[r] = (vis && qlive) ? acc[0][r] * P.inv_sqrt_d : -INFINITY;
+            mt = fmaxf(mt, sc[r]);
+        }
+        mt = fmaxf(mt, __shfl_xor(mt, 16, 64));
+        mt = fmaxf(mt, __shfl_xor(mt, 32, 64));
+        const float m_new = fmaxf(m_run, mt);
+        const float alpha = m_new > -INFINITY ? expf(m_run - m_new) : 1.f;   // exp(-inf) = 0 when nothing was seen before
+        f32x4 pr;
+        float ls = 0.f;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            pr[r] = sc[r] > -INFINITY ? expf(sc[r] - m_new) : 0.f;
+            ls += pr[r];
+        }
+        ls += __shfl_xor(ls, 16, 64);
+        ls += __shfl_xor(ls, 32, 64);
+        l_run = l_run * alpha + ls;
+        m_run = m_new;
+        *reinterpret_cast<f32x4*>(sP + c * 16 + 4 * kb) = pr;
+        if (kb == 0) sA[c] = alpha;
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");   // written and read by this wavefront only
+        __builtin_amdgcn_wave_barrier();
+        float v[16][DPL];
+#pragma unroll
+        for (int j = 0; j < 16; ++j) widen_v(vraw[j], v[j]);
+#pragma unroll
+        for (int rr = 0; rr < 16; ++rr) {
+            if (rr < nrows) {                               // wavefront-uniform
+                const float a = sA[rr];
+                const f32x4* prow = reinterpret_cast<const f32x4*>(sP + rr * 16);
+#pragma unroll
+                for (int e = 0; e < DPL; ++e) o[rr][e] *= a;
+#pragma unroll
+                for (int k4 = 0; k4 < 4; ++k4) {
+                    const f32x4 p4 = prow[k4];
+#pragma unroll
+                    for (int r = 0; r < 4; ++r)
+#pragma unroll
+                        for (int e = 0; e < DPL; ++e) o[rr][e] += p4[r] * v[4 * k4 + r][e];
+                }
+            }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+        __builtin_amdgcn_wave_barrier();                    // the next tile overwrites the probabilities
+    }
+    // ---- the wavefronts' results meet in LDS
+    if (kb == 0) { sML[(wave * 16 + c) * 2] = m_run; sML[(wave * 16 + c) * 2 + 1] = l_run; }
+#pragma unroll
+    for (int rr = 0; rr < 16; ++rr)
+#pragma unroll
+        for (int e = 0; e < DPL; ++e) sO[(wave * 16 + rr) * D + DPL * lane + e] = o[rr][e];
+    __syncthreads();
+    float* obase = P.out + ((size_t)seq * P.rows * P.nq + h) * D;
+    for (int x = tid; x < nrows * D; x += GA_THREADS) {
+        const int rr = x / D, dd = x - rr * D;
+        float M = -INFINITY;
+#pragma unroll
+        for (int w = 0; w < GA_WAVES; ++w) M = fmaxf(M, sML[(w * 16 + rr) * 2]);
+        float num = 0.f, den = 0.f;
+#pragma unroll
+        for (int w = 0; w < GA_WAVES; ++w) {
+            const float mw = sML[(w * 16 + rr) * 2];
+            const float f = mw > -INFINITY ? expf(mw - M) : 0.f;
+            num += sO[(w * 16 + rr) * D + dd] * f;
+            den += sML[(w * 16 + rr) * 2 + 1] * f;
+        }
+        obase[(size_t)(r0 + rr) * P.nq * D + dd] = num / den;   // (every row sees at least its own real token: den > 0)
+    }
+}
+
+size_t a256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+int check(const ps_group_attn_args* a) {
+    if (!a) return PS_ERR_NULL;
+    if (a->seqs < 1 || a->tokens < 1 || a->k < 0 || a->n_heads < 1 || a->n_kv_heads < 1 || a->head_dim < 1) return PS_ERR_SHAPE;
+    if (a->dtype != PS_F32 && a->dtype != PS_BF16) return PS_ERR_SHAPE;
+    if (a->n_heads % a->n_kv_heads != 0 || !(a->rope_base > 0.f)) return PS_ERR_SHAPE;
+    if (a->head_dim != 64 && a->head_dim != 128) return PS_ERR_UNSUPPORTED;
+    if (a->k > 15 || (long long)a->tokens + a->k > (1 << 20)) return PS_ERR_UNSUPPORTED;
+    if (a->n_heads > 65535 || a->seqs > 65535) return PS_ERR_UNSUPPORTED;
+    return PS_OK;
+}
+
+struct GaLayout { size_t table, q_rot, k_rot, total; };
+GaLayout layout(const ps_group_attn_args* a) {
+    GaLayout L;
+    const size_t rows = (size_t)a->tokens * (a->k + 1), esz = a->dtype == PS_BF16 ? 2 : 4;
+    L.table = 0;
+    L.q_rot = a256((size_t)(a->tokens + a->k) * (a->head_dim / 2) * sizeof(float2));
+    L.k_rot = L.q_rot + a256((size_t)a->seqs * rows * a->n_heads * a->head_dim * 4);
+    L.total = L.k_rot + a256((size_t)a->seqs * rows * a->n_kv_heads * a->head_dim * esz);
+    return L;
+}
+
+template <typename WT, int D>
+int launch(const GaParams& P, hipStream_t s) {
+    const long long nrope = (long long)P.seqs * P.rows * (P.nq + P.nkv) * (D / 8);
+    hipLaunchKernelGGL((ga_table_kernel<D>), dim3(min(1024, ((P.T + P.k) * (D / 2) + 255) / 256)), dim3(256), 0, s, P);
+    hipLaunchKernelGGL((ga_rope_kernel<WT, D>), dim3((unsigned)min(65535LL, (nrope + 255) / 256)), dim3(256), 0, s, P);
+    hipLaunchKernelGGL((ga_attn_kernel<WT, D>), dim3(P.ntiles, P.nq, P.seqs), dim3(GA_THREADS), 0, s, P);
+    return hipGetLastError() == hipSuccess ? PS_OK : PS_ERR_DEVICE;
+}
+
+}   // namespace
+
+extern "C" size_t ps_group_attention_workspace_bytes(const ps_group_attn_args* a) {
+    return check(a) == PS_OK ? layout(a).total : 0;
+}
+
+extern "C" int ps_group_attention(const ps_group_attn_args* a, void* stream) {
+    const int st = check(a);
+    if (st != PS_OK) return st;
+    if (!a->q || !a->k_ || !a->v || !a->out || !a->workspace) return PS_ERR_NULL;
+    const GaLayout L = layout(a);
+    if (a->workspace_bytes < L.total || ((uintptr_t)a->workspace & 255)) return PS_ERR_WORKSPACE;
+    GaParams P;
+    P.seqs = a->seqs; P.T = a->tokens; P.k = a->k; P.nq = a->n_heads; P.nkv = a->n_kv_heads;
+    P.rows = a->tokens * (a->k + 1);
+    P.gpt = 16 / (a->k + 1);
+    P.ntiles = (a->tokens + P.gpt - 1) / P.gpt;
+    P.inv_sqrt_d = (float)(1.0 / sqrt((double)a->head_dim));
+    P.q = a->q; P.k_ = a->k_; P.v = a->v; P.out = a->out;
+    char* ws = (char*)a->workspace;
+    P.table = (float2*)(ws + L.table); P.q_rot = (float*)(ws + L.q_rot); P.k_rot = ws + L.k_rot;
+    P.log_base = log((double)a->rope_base);
+    hipStream_t s = (hipStream_t)stream;
+    if (a->dtype == PS_BF16) return a->head_dim == 128 ? launch<bf16_t, 128>(P, s) : launch<bf16_t, 64>(P, s);
+    return a->head_dim == 128 ? launch<float, 128>(P, s) : launch<float, 64>(P, s);
+}

@@ -17,7 +17,7 @@ _TENSOR_IDS = {
     "g_in": 1, "wq": 2, "wk": 3, "wv": 4, "wo": 5, "g_post": 6, "w_gate": 7, "w_up": 8,
     "w_down": 9, "g_final": 10, "w_lm": 11, "mask_emb": 12, "x": 13, "k_cache": 14,
     "v_cache": 15, "kv_len": 16, "n_new_mix": 17, "embed": 18, "w_fc": 19, "b_fc": 20, "token_ids": 21,
-    "features": 22, "uniforms": 23,
+    "features": 22, "uniforms": 23, "train_q": 24, "train_k": 25, "train_v": 26,
 }
 
 
@@ -93,6 +93,14 @@ def make_input_stage_inputs(workload, n_new=None, sub=0):
     ids = g.integers(0, s.vocab, size=(workload.batch, n_new)).astype(np.int32)
     feats = _normal(workload.seed, "features", (workload.batch, n_new, s.hidden), 1.0, 0.0, s.dtype, sub=sub)
     return {"token_ids": ids, "features": feats}
+
+
+def make_group_attention_inputs(seed, seqs, tokens, k, n_heads, n_kv_heads, head_dim, dtype):
+    """q, k, v ~ N(0, 1) of a training sequence laid out as parallel groups: [seqs, tokens (k + 1), heads, d]."""
+    rows = tokens * (k + 1)
+    return {"q": _normal(seed, "train_q", (seqs, rows, n_heads, head_dim), 1.0, 0.0, dtype),
+            "k": _normal(seed, "train_k", (seqs, rows, n_kv_heads, head_dim), 1.0, 0.0, dtype),
+            "v": _normal(seed, "train_v", (seqs, rows, n_kv_heads, head_dim), 1.0, 0.0, dtype)}
 
 
 def draw_kv_len(workload):

@@ -1,0 +1,82 @@
+"""GPU parity of the group-wise training attention (Section 4.1) through the C ABI against the CPU oracle,
+element by element.  Tolerance: the kernel accumulates in float32 with queries split into bf16 high and low
+parts (about 1e-5 relative); keys are rounded to the storage type after the rotary embedding on both sides, so
+where the float32 and the float64 rotation fall on different sides of a rounding boundary a key moves by one
+unit in the last place (bf16: 2^-8 of one element of one key), which moves a score by up to ~1e-2 |q_j k_j| /
+sqrt(d) and an output by a few 1e-4: outputs are compared to 2e-3 (bf16) / 2e-5 (f32) of the largest value."""
+import numpy as np
+import pytest
+
+from oracle import group_attention as ga
+from paper_2410_05589_amd import binding as B
+from paper_2410_05589_amd import inputs
+from paper_2410_05589_amd import train as TR
+
+pytestmark = pytest.mark.gpu
+
+
+def run_gpu(inp, seqs, T, k, nq, nkv, d, dtype, base=10000.0):
+    import torch
+    a = TR.make_args(seqs, T, k, nq, nkv, d, dtype, base)
+    q, kk, v = (B.to_device(inp[n], dtype) for n in ("q", "k", "v"))
+    out = torch.full((seqs, T * (k + 1), nq, d), -12345.0, dtype=torch.float32, device="cuda:0")
+    ws = torch.empty(TR.ps_group_attention_workspace_bytes(a) + 256, dtype=torch.uint8, device="cuda:0")
+    a.q, a.k_, a.v, a.out = q.data_ptr(), kk.data_ptr(), v.data_ptr(), out.data_ptr()
+    a.workspace = (ws.data_ptr() + 255) & ~255
+    a.workspace_bytes = ws.numel() - 256
+    st = TR.ps_group_attention(a, torch.cuda.current_stream().cuda_stream)
+    assert st == B.PS_OK, B.ps_draft_strerror(st)
+    torch.cuda.synchronize()
+    return out.cpu().numpy()
+
+
+def _case(seqs, T, k, nq, nkv, d, dtype, seed, base=10000.0):
+    print("case seqs", seqs, "T", T, "k", k, "heads", nq, nkv, "d", d, dtype, flush=True)
+    inp = inputs.make_group_attention_inputs(seed, seqs, T, k, nq, nkv, d, dtype)
+    got = run_gpu(inp, seqs, T, k, nq, nkv, d, dtype, base)
+    worst = 0.0
+    for s in range(seqs):
+        want = ga.group_attention(inp["q"][s], inp["k"][s], inp["v"][s], T, k, base, dtype)
+        err = float(np.abs(got[s] - want).max())
+        worst = max(worst, err)
+        assert err <= (2e-5 if dtype == "f32" else 2e-3) * np.abs(want).max(), (s, err)
+    print("    max abs error", worst, flush=True)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_small_shapes_ragged_tiles(dtype):
+    _case(2, 37, 4, 4, 2, 64, dtype, 1)          # 3 groups per query tile, a ragged last tile, GQA
+    _case(1, 50, 2, 2, 2, 128, dtype, 2)         # 5 groups per tile
+    _case(1, 21, 7, 2, 1, 64, dtype, 3)          # 2 groups per tile: 16 rows exactly
+    _case(1, 9, 15, 2, 2, 64, dtype, 4)          # one group per tile
+    _case(1, 70, 0, 4, 4, 64, dtype, 5)          # k = 0: ordinary causal attention
+    _case(1, 1, 4, 2, 2, 64, dtype, 6)           # a single token
+
+
+def test_longer_sequence_and_other_rope_base_bf16():
+    _case(1, 300, 4, 8, 2, 128, "bf16", 7, base=500000.0)
+
+
+def test_sampled_rows_at_the_benchmark_size():
+    """T 2048, k 4, 32 heads x 128 (the 7B drafter's layer), bf16: rows the oracle works out one by one."""
+    T, k, nq, d = 2048, 4, 32, 128
+    inp = inputs.make_group_attention_inputs(8, 1, T, k, nq, nq, d, "bf16")
+    got = run_gpu(inp, 1, T, k, nq, nq, d, "bf16")
+    from oracle.ps_oracle import rope, round_to_storage, widen
+    g = np.random.default_rng(0)
+    rows = sorted(set([0, 1, 4, 5, T * (k + 1) - 1, T * (k + 1) - 5] + [int(x) for x in g.integers(0, T * (k + 1), 10)]))
+    heads = [0, 13, 31]
+    pos_all = np.arange(T * (k + 1)) // (k + 1) + np.arange(T * (k + 1)) % (k + 1)
+    K = {h: widen(round_to_storage(rope(widen(inp["k"][0][:, h:h + 1], "bf16"), pos_all, 10000.0), "bf16"), "bf16")[:, 0] for h in heads}
+    for i in rows:
+        gi, si = divmod(i, k + 1)
+        cols = [gg * (k + 1) for gg in range(gi + 1)] + [gi * (k + 1) + ss for ss in range(1, si + 1)]   # what the row may see
+        for h in heads:
+            qv = rope(widen(inp["q"][0][i:i + 1, h:h + 1], "bf16"), pos_all[i:i + 1], 10000.0)[0, 0]
+            s = K[h][cols] @ qv / np.sqrt(d)
+            p = np.exp(s - s.max())
+            want = (p / p.sum()) @ widen(inp["v"][0][cols, h], "bf16")
+            err = float(np.abs(got[0, i, h] - want).max())
+            assert err <= 2e-3 * max(1.0, np.abs(want).max()), (i, h, err)
+    # property at any size: every output row is a convex combination of value rows
+    assert np.isfinite(got).all() and np.abs(got).max() <= np.abs(widen(inp["v"], "bf16")).max() + 1e-3
