@@ -296,7 +296,8 @@ def summarize(paths):
                              "counters_collection group by kernel_name, counter_name order by avg(value) desc").fetchall()
             print("%-60s %-14s %6s %14s %14s %14s" % ("kernel", "counter", "calls", "avg", "min", "max"))
             for r in rows[:16]:
-                print("%-60s %-14s %6d %14.1f %14.1f %14.1f" % (re.sub(r"\(.*", "", r[0])[:60], r[1], r[2], r[3], r[4], r[5]))
+                n = re.sub(r"\(.*", "", re.sub(r"\(anonymous namespace\)::", "", r[0]))
+                print("%-60s %-14s %6d %14.1f %14.1f %14.1f" % (n[:60], r[1], r[2], r[3], r[4], r[5]))
 
 
 STAMP_NAMES = {1: "start", 32: "attn start", 44: "attn item top", 45: "attn scores done", 46: "attn maxima exchanged",

@@ -2095,6 +2095,10 @@ __global__ void __launch_bounds__(PS_WG_THREADS, 1) fused_kernel(const StepParam
     const int wg = blockIdx.x, lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     uint4 wb[PS_U];
+#ifdef PS_TIMELINE
+    if (threadIdx.x < 64) *tl_slot(threadIdx.x) = 0;    // a stamp nobody takes reads as 0
+    __syncthreads();
+#endif
     stamp_wall(P, wg, 0);
     stamp(P, wg, 1);
     unsigned ticket;
