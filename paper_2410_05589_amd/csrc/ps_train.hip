@@ -10,8 +10,12 @@
 // all lie inside the query tile's own 16 rows: one more key tile.  The wavefronts of a workgroup take the key
 // tiles in turn, each with its own running maximum, sum and output (online softmax); their results meet in LDS
 // at the end.  Scores are one MFMA tile per key tile (the keys' rows are the 16-row operand, straight from
-// memory; the 16 query rows, split into bf16 high and low parts, the 16-column operand in LDS); P.V is plain
-// FMA work: a lane owns head_dim / 64 output columns for all 16 rows.
+// memory; the 16 query rows, split into bf16 high and low parts, the 16-column operand in LDS).  P.V for bf16
+// values is MFMA work too: the score tile comes out of the matrix core with a lane holding four consecutive keys of
+// one query, which is exactly the 16-row operand layout of v_mfma_f32_16x16x16_bf16 (P, split into high and low
+// parts); the other operand needs four consecutive keys of one value column per lane, so the wavefront passes its
+// 16 value rows through LDS with the rows of a key pair interleaved (one dword = the same column of two keys).
+// float32 values take plain FMAs: a lane owns head_dim / 64 output columns for all 16 rows.
 #include "ps_device.h"
 #include "ps_train.h"
 
@@ -29,6 +33,11 @@ struct GaParams {
     void* k_rot;        // [seqs][rows][nkv][d] storage type
     double log_base;
 };
+
+// LDS data that one wavefront writes and the same wavefront reads: its LDS operations complete in order, so
+// all that is needed is that the compiler keeps the order too and that the writes have left the queue.  (A
+// workgroup-scope fence would also wait for every global load in flight - the next tile's, requested ahead.)
+__device__ __forceinline__ void lds_sync_wave() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
 
 template <int D>
 __global__ void __launch_bounds__(256) ga_table_kernel(const GaParams P) {
@@ -82,7 +91,9 @@ __global__ void __launch_bounds__(GA_THREADS) ga_attn_kernel(const GaParams P) {
     constexpr int OFF_A = OFF_P + GA_WAVES * 16 * 16 * 4;   // [waves][16] rescale factors of the running output
     constexpr int OFF_ML = OFF_A + GA_WAVES * 16 * 4;       // [waves][16][2] final (max, sum)
     constexpr int OFF_O = OFF_ML + GA_WAVES * 16 * 2 * 4;   // [waves][16][D] final outputs
-    __shared__ __attribute__((aligned(16))) char smem[OFF_O + GA_WAVES * 16 * D * 4];
+    constexpr int VSTR = D + 8;                             // dwords between key pairs of the staged values (no bank conflicts)
+    constexpr int OFF_V = OFF_O + GA_WAVES * 16 * D * 4;    // [waves][8 key pairs][VSTR] dwords: (value of key 2m, value of key 2m+1)
+    __shared__ __attribute__((aligned(16))) char smem[OFF_V + (BF ? GA_WAVES * 8 * VSTR * 4 : 0)];
     typedef typename VRaw<WT, DPL>::type raw_t;
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int c = lane & 15, kb = lane >> 4;
@@ -96,6 +107,8 @@ __global__ void __launch_bounds__(GA_THREADS) ga_attn_kernel(const GaParams P) {
     float* sA = reinterpret_cast<float*>(smem + OFF_A) + wave * 16;
     float* sML = reinterpret_cast<float*>(smem + OFF_ML);
     float* sO = reinterpret_cast<float*>(smem + OFF_O);
+    unsigned* sV = reinterpret_cast<unsigned*>(smem + OFF_V) + wave * 8 * VSTR;
+    typedef short s16x4 __attribute__((ext_vector_type(4)));
 
     // ---- the query rows (rotated, float32) into LDS as the 16-column MFMA operand; rows beyond the tile repeat the last
     const float* qbase = P.q_rot + ((size_t)seq * P.rows * P.nq + h) * D;
@@ -124,27 +137,47 @@ __global__ void __launch_bounds__(GA_THREADS) ga_attn_kernel(const GaParams P) {
     const size_t rstride = (size_t)P.nkv * D * ESZ;        // bytes between layout rows
     const int n_real = (g_last >> 4) + 1;                   // key tiles of real tokens; one more tile: the tile's own [MASK] rows
     float m_run = -INFINITY, l_run = 0.f;                   // of query c (the same in the four lanes that share it)
-    float o[16][DPL];
+    float o[BF ? 1 : 16][DPL];                               // float32 values: this lane's columns of all 16 rows
+    f32x4 oacc[D / 16];                                     // bf16 values: MFMA tiles, lane (c, kb): column 16 j + c of rows 4 kb .. 4 kb + 3
 #pragma unroll
-    for (int rr = 0; rr < 16; ++rr)
+    for (int rr = 0; rr < (BF ? 1 : 16); ++rr)
 #pragma unroll
         for (int e = 0; e < DPL; ++e) o[rr][e] = 0.f;
+#pragma unroll
+    for (int j = 0; j < D / 16; ++j) oacc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    for (int kt = wave; kt <= n_real; kt += GA_WAVES) {
+    // layout row of key j of key tile t (clamped to a row that exists); tile n_real holds the [MASK] rows of the
+    // query tile's own groups
+    auto key_row = [&](int t, int j) __attribute__((always_inline)) {
+        return t >= n_real ? r0 + min(j, nrows - 1) : min(16 * t + j, g_last) * K1;
+    };
+    constexpr int CBN = D / 16;                             // column blocks of 16
+    const int vm = lane / CBN, vcb = lane % CBN;            // bf16 values: this lane's key pair and column block (lanes < 8 CBN)
+    // The loads of a key tile: K rows as the MFMA operand (lane (c, kb): bytes [64 t + 16 kb, +16) of key c), and
+    // the value rows.  They are requested one tile ahead, while the previous tile is worked on.
+    auto load_tile = [&](int t, uint4 (&kreg)[STEPS], uint4 (&va)[2], uint4 (&vb)[2], raw_t (&vraw)[BF ? 1 : 16]) __attribute__((always_inline)) {
+        const char* krow = kbase + (size_t)key_row(t, c) * rstride + kb * 16;
+#pragma unroll
+        for (int st = 0; st < STEPS; ++st) kreg[st] = ld16(krow + st * 64);
+        if constexpr (BF) {
+            const int mm = min(vm, 7);
+            const char* pa_ = vbase + (size_t)key_row(t, 2 * mm) * rstride + vcb * 32;
+            const char* pb_ = vbase + (size_t)key_row(t, 2 * mm + 1) * rstride + vcb * 32;
+            va[0] = ld16(pa_); va[1] = ld16(pa_ + 16);
+            vb[0] = ld16(pb_); vb[1] = ld16(pb_ + 16);
+        } else {
+#pragma unroll
+            for (int j = 0; j < 16; ++j)
+                vraw[j] = *reinterpret_cast<const raw_t*>(vbase + (size_t)key_row(t, j) * rstride + (size_t)DPL * lane * ESZ);
+        }
+    };
+    const int n_tiles = n_real + (P.k > 0 ? 1 : 0);         // real-token tiles, then the own-[MASK] tile
+    uint4 kreg[STEPS], va[2], vb[2], kreg_n[STEPS], va_n[2], vb_n[2];
+    raw_t vraw[BF ? 1 : 16], vraw_n[BF ? 1 : 16];
+    load_tile(min(wave, n_tiles - 1), kreg, va, vb, vraw);
+    for (int kt = wave; kt < n_tiles; kt += GA_WAVES) {
         const bool own = kt == n_real;                      // the [MASK] tokens of the tile's own groups
-        if (own && P.k == 0) break;
-        // layout row of key j of this tile (clamped to a row that exists)
-        auto key_row = [&](int j) __attribute__((always_inline)) {
-            return own ? r0 + min(j, nrows - 1) : min(16 * kt + j, g_last) * K1;
-        };
-        uint4 kreg[STEPS];
-        const char* krow = kbase + (size_t)key_row(c) * rstride + kb * 16;
-#pragma unroll
-        for (int t = 0; t < STEPS; ++t) kreg[t] = ld16(krow + t * 64);
-        raw_t vraw[16];
-#pragma unroll
-        for (int j = 0; j < 16; ++j)
-            vraw[j] = *reinterpret_cast<const raw_t*>(vbase + (size_t)key_row(j) * rstride + (size_t)DPL * lane * ESZ);
+        load_tile(min(kt + GA_WAVES, n_tiles - 1), kreg_n, va_n, vb_n, vraw_n);   // (beyond the last: a repeat nobody uses)
         f32x4 acc[1] = {f32x4{0.f, 0.f, 0.f, 0.f}};
 #pragma unroll
         for (int t = 0; t < STEPS; ++t) mma_step<WT, 1>(kreg[t], bq[t], acc);
@@ -180,37 +213,82 @@ __global__ void __launch_bounds__(GA_THREADS) ga_attn_kernel(const GaParams P) {
         m_run = m_new;
         *reinterpret_cast<f32x4*>(sP + c * 16 + 4 * kb) = pr;
         if (kb == 0) sA[c] = alpha;
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");   // written and read by this wavefront only
+        lds_sync_wave();                                    // written and read by this wavefront only
         __builtin_amdgcn_wave_barrier();
-        float v[16][DPL];
+        if constexpr (BF) {
+            // the value rows into LDS, the two keys of a pair interleaved column by column
+            if (vm < 8) {
+                unsigned ov[16];
 #pragma unroll
-        for (int j = 0; j < 16; ++j) widen_v(vraw[j], v[j]);
+                for (int w = 0; w < 8; ++w) {
+                    const unsigned a2 = w < 4 ? (&va[0].x)[w] : (&va[1].x)[w - 4], b2 = w < 4 ? (&vb[0].x)[w] : (&vb[1].x)[w - 4];
+                    ov[2 * w] = (a2 & 0xFFFFu) | (b2 << 16);
+                    ov[2 * w + 1] = (a2 >> 16) | (b2 & 0xFFFF0000u);
+                }
+                uint4* dst = reinterpret_cast<uint4*>(sV + vm * VSTR + 16 * vcb);
 #pragma unroll
-        for (int rr = 0; rr < 16; ++rr) {
-            if (rr < nrows) {                               // wavefront-uniform
-                const float a = sA[rr];
-                const f32x4* prow = reinterpret_cast<const f32x4*>(sP + rr * 16);
+                for (int w = 0; w < 4; ++w) dst[w] = make_uint4(ov[4 * w], ov[4 * w + 1], ov[4 * w + 2], ov[4 * w + 3]);
+            }
+            lds_sync_wave();
+            __builtin_amdgcn_wave_barrier();
+            // P (query c, keys 4 kb .. 4 kb + 3) as the 16-row operand, split into bf16 high and low parts
+            const unsigned h01 = pack_bf16x2(pr[0], pr[1]), h23 = pack_bf16x2(pr[2], pr[3]);
+            const unsigned l01 = pack_bf16x2(pr[0] - __uint_as_float(h01 << 16), pr[1] - __uint_as_float(h01 & 0xFFFF0000u));
+            const unsigned l23 = pack_bf16x2(pr[2] - __uint_as_float(h23 << 16), pr[3] - __uint_as_float(h23 & 0xFFFF0000u));
+            const s16x4 ph_ = __builtin_bit_cast(s16x4, make_uint2(h01, h23)), pl_ = __builtin_bit_cast(s16x4, make_uint2(l01, l23));
+            const f32x4 al = *reinterpret_cast<const f32x4*>(sA + 4 * kb);   // rescale factors of rows 4 kb .. 4 kb + 3
 #pragma unroll
-                for (int e = 0; e < DPL; ++e) o[rr][e] *= a;
-#pragma unroll
-                for (int k4 = 0; k4 < 4; ++k4) {
-                    const f32x4 p4 = prow[k4];
-#pragma unroll
-                    for (int r = 0; r < 4; ++r)
-#pragma unroll
-                        for (int e = 0; e < DPL; ++e) o[rr][e] += p4[r] * v[4 * k4 + r][e];
+            for (int j = 0; j < D / 16; ++j) {
+                // values of keys 4 kb .. 4 kb + 3, column 16 j + c: the key pairs 2 kb and 2 kb + 1
+                const unsigned w0 = sV[(2 * kb) * VSTR + 16 * j + c], w1 = sV[(2 * kb + 1) * VSTR + 16 * j + c];
+                const s16x4 vv = __builtin_bit_cast(s16x4, make_uint2(w0, w1));
+                f32x4 t = oacc[j] * al;
+                t = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(ph_, vv, t, 0, 0, 0);
+                oacc[j] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pl_, vv, t, 0, 0, 0);
+            }
+        } else {
+            float v[16][DPL];
+    #pragma unroll
+            for (int j = 0; j < 16; ++j) widen_v(vraw[j], v[j]);
+    #pragma unroll
+            for (int rr = 0; rr < 16; ++rr) {
+                if (rr < nrows) {                               // wavefront-uniform
+                    const float a = sA[rr];
+                    const f32x4* prow = reinterpret_cast<const f32x4*>(sP + rr * 16);
+    #pragma unroll
+                    for (int e = 0; e < DPL; ++e) o[rr][e] *= a;
+    #pragma unroll
+                    for (int k4 = 0; k4 < 4; ++k4) {
+                        const f32x4 p4 = prow[k4];
+    #pragma unroll
+                        for (int r = 0; r < 4; ++r)
+    #pragma unroll
+                            for (int e = 0; e < DPL; ++e) o[rr][e] += p4[r] * v[4 * k4 + r][e];
+                    }
                 }
             }
         }
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+        lds_sync_wave();
         __builtin_amdgcn_wave_barrier();                    // the next tile overwrites the probabilities
+#pragma unroll
+        for (int st = 0; st < STEPS; ++st) kreg[st] = kreg_n[st];
+        va[0] = va_n[0]; va[1] = va_n[1]; vb[0] = vb_n[0]; vb[1] = vb_n[1];
+#pragma unroll
+        for (int j = 0; j < (BF ? 1 : 16); ++j) vraw[j] = vraw_n[j];
     }
     // ---- the wavefronts' results meet in LDS
     if (kb == 0) { sML[(wave * 16 + c) * 2] = m_run; sML[(wave * 16 + c) * 2 + 1] = l_run; }
+    if constexpr (BF) {
 #pragma unroll
-    for (int rr = 0; rr < 16; ++rr)
+        for (int j = 0; j < D / 16; ++j)
 #pragma unroll
-        for (int e = 0; e < DPL; ++e) sO[(wave * 16 + rr) * D + DPL * lane + e] = o[rr][e];
+            for (int r = 0; r < 4; ++r) sO[(wave * 16 + 4 * kb + r) * D + 16 * j + c] = oacc[j][r];
+    } else {
+#pragma unroll
+        for (int rr = 0; rr < 16; ++rr)
+#pragma unroll
+            for (int e = 0; e < DPL; ++e) sO[(wave * 16 + rr) * D + DPL * lane + e] = o[rr][e];
+    }
     __syncthreads();
     float* obase = P.out + ((size_t)seq * P.rows * P.nq + h) * D;
     for (int x = tid; x < nrows * D; x += GA_THREADS) {
