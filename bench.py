@@ -300,8 +300,9 @@ def summarize(paths):
                 print("%-60s %-14s %6d %14.1f %14.1f %14.1f" % (n[:60], r[1], r[2], r[3], r[4], r[5]))
 
 
-STAMP_NAMES = {1: "start", 32: "attn start", 44: "attn item top", 45: "attn scores done", 46: "attn maxima exchanged",
-               47: "attn P.V done", 48: "attn P.V barrier", 34: "attn item done", 36: "attn end", 40: "merge start",
+# (attention stamps: those of the bf16 kernels; 46 is taken by the float32 kernels only)
+STAMP_NAMES = {1: "start", 32: "attn start", 44: "attn unit top", 45: "attn query rows placed", 46: "attn maxima exchanged",
+               47: "attn key groups done", 48: "attn unit done", 34: "attn units done", 36: "attn end", 40: "merge start",
                41: "merge statistics here", 42: "merge candidates", 62: "end"}
 for _ph, _nm in enumerate(["qkv", "oproj", "gateup", "down", "lm"]):
     for _k, _sfx in enumerate(["enter", "panel staged", "streamed", "tile sums added", "epilogue done", "end"]):

@@ -1425,6 +1425,237 @@ __device__ __forceinline__ void attn_place_q(const StepParams& P, const AttnItem
     attn_store_q<WT, D>(sq, tid, qx);
 }
 
+// ------------------------------------------------------------------------------------------
+// Sequences cut into several key blocks: the work items that put the blocks' partial results together.
+// sM, sL: at least 72 floats each; sW: [PS_WAVES][256] floats; sO: [PS_WAVES][D] floats.
+// ------------------------------------------------------------------------------------------
+// key blocks of sequence b.  V2 (see attn_phase2): blocks of cache keys, the rows of this step ride on the
+// last one (an empty cache still has that one); else the blocks cover valid rows + attn_tail
+template <bool V2> __device__ __forceinline__ int attn_nch(const StepParams& P, int b, int ch_log) {
+    const int CH = 1 << ch_log;
+    if constexpr (V2) return max(1, (kvlen_u(b) + CH - 1) >> ch_log);
+    else return (kvlen_u(b) + P.attn_tail + CH - 1) >> ch_log;
+}
+template <typename WT, int D, bool V2>
+__device__ __forceinline__ void attn_merge(const StepParams& P, int wg, int nwg, int wave, int n_merge, int ch_log,
+                                           float* sM, float* sL, float* sW, float* sO) {
+    constexpr int DPL = D / 64;                     // output columns per lane
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int grp = P.nq / P.nkv;
+    const int Ra = grp * P.M;
+    const rsrc_t racc = make_rsrc(P.attn_acc), rml = make_rsrc(P.attn_ml);
+    const SxBuf ro = sx_buf(P, P.o_buf);
+    const unsigned seq = ps_seq();
+    const bool sep = !V2 && P.attn_sep;
+    // ---- sequences cut into several blocks: put the blocks' partial results together.  One work
+    // item = (sequence, kv head, 8 query rows).  Wavefront w turns the (max, sum) pairs of row w
+    // into one weight per block (in LDS); then thread (row, column pair) adds up the blocks'
+    // outputs with these weights, 16 blocks per round of loads.  Blocks are taken in groups of
+    // 256; groups are folded with a running maximum, so any number of blocks works.
+    constexpr int MR = PS_WAVES;                     // rows per work item: one wavefront per row
+    constexpr int GRP = 256, CB = 16;
+    constexpr int PP = D / 2;                        // column pairs per row
+    const int RT = (Ra + MR - 1) / MR;
+    constexpr int SEP_ML = 64;                       // (max, sum) of the step's own rows: sM / sL [SEP_ML + row], beside the groups' [row]
+    for (int mi = wg; mi < n_merge; mi += nwg) {
+        int b = 0, rem = mi, nch = 0, item_base = 0;
+        for (;; ++b) {
+            nch = attn_nch<V2>(P, b, ch_log);
+            const int n = (nch > 1 || sep) ? P.nkv * RT : 0;
+            if (rem < n) break;
+            rem -= n;
+            item_base += nch * P.nkv;
+        }
+        const int hk = rem / RT, rt = rem - hk * RT;
+        const int item0 = item_base + hk * nch;      // block 0 of this (b, hk)
+        const int r0 = rt * MR, nr = min(MR, Ra - r0);
+        const int myrow = tid / PP, dp = tid - myrow * PP;
+        const bool active = myrow < nr;
+        float num0 = 0.f, num1 = 0.f, den = 0.f, mrun = -INFINITY;
+        if (sep) {
+            // The rows written in this step are not part of any block: wavefront w works out row w's
+            // attention over them (at most 16 keys, a lane owns DPL columns of q, K and V, the dot
+            // products are wavefront sums); the result is folded in after the blocks like one more group of
+            // them.  This comes first: its inputs (the QKV phase's outputs) are there long before the last
+            // block's partial results, so it runs while those are still being produced.
+            __syncthreads();                         // the previous item is done with the output area
+            if (wave < nr) {
+                const int rho = r0 + wave;
+                const int gi = row_seq(P, rho), i = rho - gi * P.M;
+                const rsrc_t rq = make_rsrc(act_ptr(P, P.q_buf)), rn = make_rsrc(act_ptr(P, P.kvnew));
+                const unsigned qo = (unsigned)((size_t)(b * P.M + i) * P.QD + (hk * grp + gi) * D + DPL * lane);
+                float q[DPL], kx[16][DPL], vx[16][DPL];
+                auto issue_new = [&]() __attribute__((always_inline)) {
+#pragma unroll
+                    for (int e = 0; e < DPL; ++e) q[e] = coh_ld_f(rq, (qo + e) * 4);
+#pragma unroll
+                    for (int jj = 0; jj < 16; ++jj) {
+                        const int jc = jj < P.M ? jj : P.M - 1;     // clamped: every load is unconditional
+                        const unsigned ko = (unsigned)(((size_t)(b * P.M + jc) * 2) * P.KVD + hk * D + DPL * lane);
+#pragma unroll
+                        for (int e = 0; e < DPL; ++e) {
+                            kx[jj][e] = coh_ld_f(rn, (ko + e) * 4);
+                            vx[jj][e] = coh_ld_f(rn, (ko + P.KVD + e) * 4);
+                        }
+                    }
+                };
+                auto bad_new = [&]() __attribute__((always_inline)) {
+                    unsigned bad = 0;
+#pragma unroll
+                    for (int e = 0; e < DPL; ++e) bad |= (unsigned)(__float_as_uint(q[e]) == PS_SENT);
+#pragma unroll
+                    for (int jj = 0; jj < 16; ++jj)
+#pragma unroll
+                        for (int e = 0; e < DPL; ++e)
+                            bad |= (unsigned)(__float_as_uint(kx[jj][e]) == PS_SENT) | (unsigned)(__float_as_uint(vx[jj][e]) == PS_SENT);
+                    return bad;
+                };
+                issue_new();
+                if (!__all(!bad_new())) {
+                    int spins = 0;
+                    do issue_new(); while (!__all(!bad_new()) && spin_again(P, spins));
+                }
+                float sc[16], mn = -INFINITY;
+#pragma unroll
+                for (int jj = 0; jj < 16; ++jj) {
+                    sc[jj] = -INFINITY;
+                    if (jj <= i) {                   // wavefront-uniform: row i sees the rows 0 .. i of this step
+                        float part = 0.f;
+#pragma unroll
+                        for (int e = 0; e < DPL; ++e) part += q[e] * kx[jj][e];
+                        sc[jj] = wave_sum(part) * P.inv_sqrt_d;
+                        mn = fmaxf(mn, sc[jj]);
+                    }
+                }
+                float ln = 0.f, on[DPL];
+#pragma unroll
+                for (int e = 0; e < DPL; ++e) on[e] = 0.f;
+#pragma unroll
+                for (int jj = 0; jj < 16; ++jj) {
+                    if (jj <= i) {
+                        const float pj = expf(sc[jj] - mn);
+                        ln += pj;
+#pragma unroll
+                        for (int e = 0; e < DPL; ++e) on[e] += pj * vx[jj][e];
+                    }
+                }
+#pragma unroll
+                for (int e = 0; e < DPL; ++e) sO[wave * D + DPL * lane + e] = on[e];
+                if (lane == 0) { sM[SEP_ML + wave] = mn; sL[SEP_ML + wave] = ln; }
+            }
+        }
+        for (int g0 = 0; g0 < nch; g0 += GRP) {
+            const int gn = min(GRP, nch - g0);
+            __syncthreads();                         // the weights of the previous group (or item) are no longer read
+            // Both kinds of loads are requested at once, the (max, sum) pairs first: the outputs of the
+            // first 16 blocks are on their way while the weights are worked out.  The first look at
+            // either is straight-line code (see the query rows above); only a failed look loops.
+            u32x4 ml[GRP / 64];
+            u32x4 av[CB];
+            const int rho_w = r0 + (wave < nr ? wave : 0);
+            auto issue_ml = [&]() __attribute__((always_inline)) {
+#pragma unroll
+                for (int q = 0; q < GRP / 64; ++q) {
+                    const int cx = lane + 64 * q;
+                    const int cc = g0 + (cx < gn ? cx : gn - 1);
+                    ml[q] = coh_ld16(rml, (unsigned)(((size_t)(item0 + cc) * Ra + rho_w) * 2) * 8);   // {max, tag, sum, tag}
+                }
+            };
+            auto bad_ml = [&]() __attribute__((always_inline)) {
+                unsigned bad = 0;
+#pragma unroll
+                for (int q = 0; q < GRP / 64; ++q) bad |= (unsigned)(ml[q][1] != seq) | (unsigned)(ml[q][3] != seq);
+                return bad;
+            };
+            auto issue_av = [&](int cb) __attribute__((always_inline)) {
+#pragma unroll
+                for (int i = 0; i < CB; ++i) {
+                    const int cc = g0 + (cb + i < gn ? cb + i : gn - 1);
+                    const int rho = r0 + (active ? myrow : 0);
+                    av[i] = coh_ld16(racc, (unsigned)(((size_t)(item0 + cc) * Ra + rho) * D + 2 * dp) * 8);   // {o, tag, o', tag}
+                }
+            };
+            auto bad_av = [&]() __attribute__((always_inline)) {
+                unsigned bad = 0;
+#pragma unroll
+                for (int i = 0; i < CB; ++i) bad |= (unsigned)(av[i][1] != seq) | (unsigned)(av[i][3] != seq);
+                return bad;
+            };
+            if (wave < nr) issue_ml();
+            issue_av(0);
+            if (wave < nr) {
+                if (!__all(!bad_ml())) {
+                    int spins = 0;
+                    do issue_ml(); while (!__all(!bad_ml()) && spin_again(P, spins));
+                }
+                float mloc = -INFINITY;
+#pragma unroll
+                for (int q = 0; q < GRP / 64; ++q)
+                    if (lane + 64 * q < gn && __uint_as_float(ml[q][2]) > 0.f) mloc = fmaxf(mloc, __uint_as_float(ml[q][0]));
+                const float mg = wave_max(mloc);
+                float lsum = 0.f;
+#pragma unroll
+                for (int q = 0; q < GRP / 64; ++q) {
+                    const float l_c = __uint_as_float(ml[q][2]);
+                    const float w = (lane + 64 * q < gn && l_c > 0.f) ? expf(__uint_as_float(ml[q][0]) - mg) : 0.f;
+                    sW[wave * GRP + lane + 64 * q] = w;
+                    lsum += l_c * w;
+                }
+                lsum = wave_sum(lsum);
+                if (lane == 0) { sM[wave] = mg; sL[wave] = lsum; }
+            }
+            __syncthreads();
+            float o0 = 0.f, o1 = 0.f;
+            for (int cb = 0; cb < gn; cb += CB) {
+                if (cb > 0) issue_av(cb);
+                if (!__all(!bad_av() || !active)) {
+                    int spins = 0;
+                    do issue_av(cb); while (!__all(!bad_av() || !active) && spin_again(P, spins));
+                }
+#pragma unroll
+                for (int i = 0; i < CB; ++i) {
+                    if (cb + i < gn && active) {
+                        const float w = sW[myrow * GRP + cb + i];
+                        o0 += __uint_as_float(av[i][0]) * w;
+                        o1 += __uint_as_float(av[i][2]) * w;
+                    }
+                }
+            }
+            if (active) {
+                const float mg = sM[myrow], lg = sL[myrow];
+                if (lg > 0.f) {
+                    const float mnew = fmaxf(mrun, mg);
+                    const float so = expf(mrun - mnew), sn = expf(mg - mnew);   // exp(-inf) = 0 at the start
+                    num0 = num0 * so + o0 * sn;
+                    num1 = num1 * so + o1 * sn;
+                    den = den * so + lg * sn;
+                    mrun = mnew;
+                }
+            }
+        }
+        if (sep) {
+            // fold in the attention over the rows written in this step (worked out first, see above)
+            __syncthreads();
+            if (active) {
+                const float mg = sM[SEP_ML + myrow], lg = sL[SEP_ML + myrow];
+                const float mnew = fmaxf(mrun, mg);
+                const float so = expf(mrun - mnew), sn = expf(mg - mnew);
+                num0 = num0 * so + sO[myrow * D + 2 * dp] * sn;
+                num1 = num1 * so + sO[myrow * D + 2 * dp + 1] * sn;
+                den = den * so + lg * sn;
+                mrun = mnew;
+            }
+        }
+        if (active) {
+            const int rho = r0 + myrow;
+            const int gi = row_seq(P, rho), i = rho - gi * P.M;
+            const unsigned oi = (unsigned)((size_t)(b * P.M + i) * P.QD + (hk * grp + gi) * D + 2 * dp);
+            sx_st1(ro, oi, num0 / den);
+            sx_st1(ro, oi + 1, num1 / den);
+        }
+    }
+}
+
 template <typename WT, int D, int NK, bool SINGLE>
 __device__ __forceinline__ void attn_phase(const StepParams& P, int wg, int nwg, int wave, char* smem) {
     typedef AttnCfg<WT, D, NK> C;
@@ -1679,214 +1910,346 @@ __device__ __forceinline__ void attn_phase(const StepParams& P, int wg, int nwg,
         }
     }
 
-    // ---- sequences cut into several blocks: put the blocks' partial results together.  One work
-    // item = (sequence, kv head, 8 query rows).  Wavefront w turns the (max, sum) pairs of row w
-    // into one weight per block (in LDS); then thread (row, column pair) adds up the blocks'
-    // outputs with these weights, 16 blocks per round of loads.  Blocks are taken in groups of
-    // 256; groups are folded with a running maximum, so any number of blocks works.
-    constexpr int MR = PS_WAVES;                     // rows per work item: one wavefront per row
-    constexpr int GRP = 256, CB = 16;
-    constexpr int PP = D / 2;                        // column pairs per row
-    const int RT = (Ra + MR - 1) / MR;
-    float* sW = sP;                                  // [MR][GRP] weights (the probabilities' area: same size)
-    constexpr int SEP_ML = 64;                       // (max, sum) of the step's own rows: sM / sL [SEP_ML + row], beside the groups' [row]
-    for (int mi = wg; mi < n_merge; mi += nwg) {
-        int b = 0, rem = mi, nch = 0, item_base = 0;
-        for (;; ++b) {
-            nch = (kvlen_u(b) + P.attn_tail + CH - 1) >> CH_LOG;
-            const int n = (nch > 1 || P.attn_sep) ? P.nkv * RT : 0;
-            if (rem < n) break;
-            rem -= n;
-            item_base += nch * P.nkv;
-        }
-        const int hk = rem / RT, rt = rem - hk * RT;
-        const int item0 = item_base + hk * nch;      // block 0 of this (b, hk)
-        const int r0 = rt * MR, nr = min(MR, Ra - r0);
-        const int myrow = tid / PP, dp = tid - myrow * PP;
-        const bool active = myrow < nr;
-        float num0 = 0.f, num1 = 0.f, den = 0.f, mrun = -INFINITY;
-        if (P.attn_sep) {
-            // The rows written in this step are not part of any block: wavefront w works out row w's
-            // attention over them (at most 16 keys, a lane owns DPL columns of q, K and V, the dot
-            // products are wavefront sums); the result is folded in after the blocks like one more group of
-            // them.  This comes first: its inputs (the QKV phase's outputs) are there long before the last
-            // block's partial results, so it runs while those are still being produced.
-            __syncthreads();                         // the previous item is done with the output area
-            if (wave < nr) {
-                const int rho = r0 + wave;
-                const int gi = row_seq(P, rho), i = rho - gi * P.M;
-                const rsrc_t rq = make_rsrc(act_ptr(P, P.q_buf)), rn = make_rsrc(act_ptr(P, P.kvnew));
-                const unsigned qo = (unsigned)((size_t)(b * P.M + i) * P.QD + (hk * grp + gi) * D + DPL * lane);
-                float q[DPL], kx[16][DPL], vx[16][DPL];
-                auto issue_new = [&]() __attribute__((always_inline)) {
-#pragma unroll
-                    for (int e = 0; e < DPL; ++e) q[e] = coh_ld_f(rq, (qo + e) * 4);
-#pragma unroll
-                    for (int jj = 0; jj < 16; ++jj) {
-                        const int jc = jj < P.M ? jj : P.M - 1;     // clamped: every load is unconditional
-                        const unsigned ko = (unsigned)(((size_t)(b * P.M + jc) * 2) * P.KVD + hk * D + DPL * lane);
-#pragma unroll
-                        for (int e = 0; e < DPL; ++e) {
-                            kx[jj][e] = coh_ld_f(rn, (ko + e) * 4);
-                            vx[jj][e] = coh_ld_f(rn, (ko + P.KVD + e) * 4);
-                        }
-                    }
-                };
-                auto bad_new = [&]() __attribute__((always_inline)) {
-                    unsigned bad = 0;
-#pragma unroll
-                    for (int e = 0; e < DPL; ++e) bad |= (unsigned)(__float_as_uint(q[e]) == PS_SENT);
-#pragma unroll
-                    for (int jj = 0; jj < 16; ++jj)
-#pragma unroll
-                        for (int e = 0; e < DPL; ++e)
-                            bad |= (unsigned)(__float_as_uint(kx[jj][e]) == PS_SENT) | (unsigned)(__float_as_uint(vx[jj][e]) == PS_SENT);
-                    return bad;
-                };
-                issue_new();
-                if (!__all(!bad_new())) {
-                    int spins = 0;
-                    do issue_new(); while (!__all(!bad_new()) && spin_again(P, spins));
-                }
-                float sc[16], mn = -INFINITY;
-#pragma unroll
-                for (int jj = 0; jj < 16; ++jj) {
-                    sc[jj] = -INFINITY;
-                    if (jj <= i) {                   // wavefront-uniform: row i sees the rows 0 .. i of this step
-                        float part = 0.f;
-#pragma unroll
-                        for (int e = 0; e < DPL; ++e) part += q[e] * kx[jj][e];
-                        sc[jj] = wave_sum(part) * P.inv_sqrt_d;
-                        mn = fmaxf(mn, sc[jj]);
-                    }
-                }
-                float ln = 0.f, on[DPL];
-#pragma unroll
-                for (int e = 0; e < DPL; ++e) on[e] = 0.f;
-#pragma unroll
-                for (int jj = 0; jj < 16; ++jj) {
-                    if (jj <= i) {
-                        const float pj = expf(sc[jj] - mn);
-                        ln += pj;
-#pragma unroll
-                        for (int e = 0; e < DPL; ++e) on[e] += pj * vx[jj][e];
-                    }
-                }
-#pragma unroll
-                for (int e = 0; e < DPL; ++e) sO[wave * D + DPL * lane + e] = on[e];
-                if (lane == 0) { sM[SEP_ML + wave] = mn; sL[SEP_ML + wave] = ln; }
-            }
-        }
-        for (int g0 = 0; g0 < nch; g0 += GRP) {
-            const int gn = min(GRP, nch - g0);
-            __syncthreads();                         // the weights of the previous group (or item) are no longer read
-            // Both kinds of loads are requested at once, the (max, sum) pairs first: the outputs of the
-            // first 16 blocks are on their way while the weights are worked out.  The first look at
-            // either is straight-line code (see the query rows above); only a failed look loops.
-            u32x4 ml[GRP / 64];
-            u32x4 av[CB];
-            const int rho_w = r0 + (wave < nr ? wave : 0);
-            auto issue_ml = [&]() __attribute__((always_inline)) {
-#pragma unroll
-                for (int q = 0; q < GRP / 64; ++q) {
-                    const int cx = lane + 64 * q;
-                    const int cc = g0 + (cx < gn ? cx : gn - 1);
-                    ml[q] = coh_ld16(rml, (unsigned)(((size_t)(item0 + cc) * Ra + rho_w) * 2) * 8);   // {max, tag, sum, tag}
-                }
-            };
-            auto bad_ml = [&]() __attribute__((always_inline)) {
-                unsigned bad = 0;
-#pragma unroll
-                for (int q = 0; q < GRP / 64; ++q) bad |= (unsigned)(ml[q][1] != seq) | (unsigned)(ml[q][3] != seq);
-                return bad;
-            };
-            auto issue_av = [&](int cb) __attribute__((always_inline)) {
-#pragma unroll
-                for (int i = 0; i < CB; ++i) {
-                    const int cc = g0 + (cb + i < gn ? cb + i : gn - 1);
-                    const int rho = r0 + (active ? myrow : 0);
-                    av[i] = coh_ld16(racc, (unsigned)(((size_t)(item0 + cc) * Ra + rho) * D + 2 * dp) * 8);   // {o, tag, o', tag}
-                }
-            };
-            auto bad_av = [&]() __attribute__((always_inline)) {
-                unsigned bad = 0;
-#pragma unroll
-                for (int i = 0; i < CB; ++i) bad |= (unsigned)(av[i][1] != seq) | (unsigned)(av[i][3] != seq);
-                return bad;
-            };
-            if (wave < nr) issue_ml();
-            issue_av(0);
-            if (wave < nr) {
-                if (!__all(!bad_ml())) {
-                    int spins = 0;
-                    do issue_ml(); while (!__all(!bad_ml()) && spin_again(P, spins));
-                }
-                float mloc = -INFINITY;
-#pragma unroll
-                for (int q = 0; q < GRP / 64; ++q)
-                    if (lane + 64 * q < gn && __uint_as_float(ml[q][2]) > 0.f) mloc = fmaxf(mloc, __uint_as_float(ml[q][0]));
-                const float mg = wave_max(mloc);
-                float lsum = 0.f;
-#pragma unroll
-                for (int q = 0; q < GRP / 64; ++q) {
-                    const float l_c = __uint_as_float(ml[q][2]);
-                    const float w = (lane + 64 * q < gn && l_c > 0.f) ? expf(__uint_as_float(ml[q][0]) - mg) : 0.f;
-                    sW[wave * GRP + lane + 64 * q] = w;
-                    lsum += l_c * w;
-                }
-                lsum = wave_sum(lsum);
-                if (lane == 0) { sM[wave] = mg; sL[wave] = lsum; }
-            }
-            __syncthreads();
-            float o0 = 0.f, o1 = 0.f;
-            for (int cb = 0; cb < gn; cb += CB) {
-                if (cb > 0) issue_av(cb);
-                if (!__all(!bad_av() || !active)) {
-                    int spins = 0;
-                    do issue_av(cb); while (!__all(!bad_av() || !active) && spin_again(P, spins));
-                }
-#pragma unroll
-                for (int i = 0; i < CB; ++i) {
-                    if (cb + i < gn && active) {
-                        const float w = sW[myrow * GRP + cb + i];
-                        o0 += __uint_as_float(av[i][0]) * w;
-                        o1 += __uint_as_float(av[i][2]) * w;
-                    }
-                }
-            }
-            if (active) {
-                const float mg = sM[myrow], lg = sL[myrow];
-                if (lg > 0.f) {
-                    const float mnew = fmaxf(mrun, mg);
-                    const float so = expf(mrun - mnew), sn = expf(mg - mnew);   // exp(-inf) = 0 at the start
-                    num0 = num0 * so + o0 * sn;
-                    num1 = num1 * so + o1 * sn;
-                    den = den * so + lg * sn;
-                    mrun = mnew;
-                }
-            }
-        }
-        if (P.attn_sep) {
-            // fold in the attention over the rows written in this step (worked out first, see above)
-            __syncthreads();
-            if (active) {
-                const float mg = sM[SEP_ML + myrow], lg = sL[SEP_ML + myrow];
-                const float mnew = fmaxf(mrun, mg);
-                const float so = expf(mrun - mnew), sn = expf(mg - mnew);
-                num0 = num0 * so + sO[myrow * D + 2 * dp] * sn;
-                num1 = num1 * so + sO[myrow * D + 2 * dp + 1] * sn;
-                den = den * so + lg * sn;
-                mrun = mnew;
-            }
-        }
-        if (active) {
-            const int rho = r0 + myrow;
-            const int gi = row_seq(P, rho), i = rho - gi * P.M;
-            const unsigned oi = (unsigned)((size_t)(b * P.M + i) * P.QD + (hk * grp + gi) * D + 2 * dp);
-            sx_st1(ro, oi, num0 / den);
-            sx_st1(ro, oi + 1, num1 / den);
+    attn_merge<WT, D, false>(P, wg, nwg, wave, n_merge, CH_LOG, sM, sL, sP, sO);
+}
+
+// ------------------------------------------------------------------------------------------
+// attention, bf16 storage.  One work unit = (sequence b, kv head hk, block ch of 2^ch_log cache keys, pass of
+// 16 query rows); the rows written in this step ride on the sequence's last block.  The wavefronts of the
+// workgroup take the block's groups of 16 keys in turn, each with its own running maximum, sum and output
+// (online softmax), the next group's K and V rows requested one group ahead; their results meet in LDS once,
+// at the end of the unit.  Scores are one MFMA tile per group (K rows = the 16-row operand straight from the
+// cache, the query rows split into bf16 high + low parts = the 16-column operand in LDS).  P.V is MFMA work
+// too: the score tile leaves the matrix core with a lane holding four consecutive keys of one query row,
+// which is the 16-row operand layout of v_mfma_f32_16x16x16_bf16 (P, split into high and low parts); the
+// other operand needs four consecutive keys of one value column per lane, so a wavefront passes its 16 value
+// rows through LDS with the two rows of a key pair interleaved (one dword = the same column of two keys).
+// The host picks the block size so that the units fill the compute units once; a sequence that is a single
+// block hands its rows straight to the output projection, else (max, sum, output) per block go to memory
+// and attn_merge puts them together.
+// ------------------------------------------------------------------------------------------
+// LDS data that one wavefront writes and the same wavefront reads: its LDS operations complete in order, so
+// all that is needed is that the compiler keeps the order too and that the writes have left the queue.  (A
+// workgroup-scope fence would also wait for every global load in flight - the next group's, requested ahead.)
+__device__ __forceinline__ void lds_sync_wave() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
+
+template <int D> struct Attn2Cfg {
+    static constexpr int G = 2;                                          // groups of 16 keys a wavefront works on at a time
+    static constexpr int VSTR = D + 8;                                   // dwords between key pairs of the staged values (no bank conflicts)
+    static constexpr int OSTR = D + 4;                                   // floats between rows of a wavefront's output
+    static constexpr int OFF_Q = PS_LDS_BASE;                            // 16 query rows as MFMA operands (hi, lo)
+    static constexpr int OFF_V = OFF_Q + 16 * D * 4;                     // [waves][G][8 key pairs][VSTR] dwords
+    static constexpr int OFF_A = OFF_V + PS_WAVES * G * 8 * VSTR * 4;    // [waves][16] rescale factors of the running output
+    static constexpr int OFF_ML = OFF_A + PS_WAVES * 16 * 4;             // [waves][16][2] final (max, sum); attn_merge: sM, sL
+    static constexpr int OFF_O = OFF_ML + PS_WAVES * 16 * 2 * 4;         // [waves][16][OSTR] final outputs; attn_merge: weights
+    static constexpr int LDS = OFF_O + PS_WAVES * 16 * OSTR * 4;
+    static_assert(LDS == ps_attn2_lds_bytes(D), "host and device agree on the layout");
+    static_assert(PS_WAVES * 16 * OSTR >= PS_WAVES * 256 + PS_WAVES * D, "attn_merge's weights and rows fit the output area");
+};
+
+// block item -> (sequence, kv head, block): the blocks of a sequence are those of attn_nch<true>
+__device__ __forceinline__ AttnItem attn_decode2(const StepParams& P, int item, int ch_log) {
+    AttnItem it;
+    int b = 0, rem = item, nch = 0;
+    for (;; ++b) {
+        nch = attn_nch<true>(P, b, ch_log);
+        if (rem < nch * P.nkv || b + 1 >= P.B) break;
+        rem -= nch * P.nkv;
+    }
+    it.b = b; it.nch = nch; it.hk = rem / nch; it.ch = rem - it.hk * nch; it.L = kvlen_u(b);
+    return it;
+}
+
+// Maximum / sum over the four lanes (c, 0 .. 3) that share a query row c, returned to all four: two row swaps
+// (v_permlane32_swap exchanges the upper half of one register with the lower half of another, v_permlane16_swap
+// the odd 16-lane rows of one with the even rows of another; fed the same value twice they yield the value of
+// lane ^ 32 resp. lane ^ 16 beside the lane's own)
+__device__ __forceinline__ float quad_rows_max(float v) {
+    auto a = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    v = fmaxf(__uint_as_float(a[0]), __uint_as_float(a[1]));
+    auto b = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return fmaxf(__uint_as_float(b[0]), __uint_as_float(b[1]));
+}
+__device__ __forceinline__ float quad_rows_sum(float v) {
+    auto a = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    v = __uint_as_float(a[0]) + __uint_as_float(a[1]);
+    auto b = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return __uint_as_float(b[0]) + __uint_as_float(b[1]);
+}
+
+// K rows (MFMA operand) and value rows of one group of 16 keys, as they come from memory
+template <int STEPS> struct KvRegs { uint4 k[STEPS]; uint4 va[2], vb[2]; };
+
+template <typename WT, int D>
+__device__ __forceinline__ void attn_phase2(const StepParams& P, int wg, int nwg, int wave, char* smem) {
+    static_assert(Traits<WT>::BF, "bf16 storage");
+    typedef Attn2Cfg<D> C;
+    constexpr int STEPS = D / 32;                   // MFMA steps along the head dimension
+    constexpr int CBN = D / 16;                     // blocks of 16 output columns
+    constexpr int VSTR = C::VSTR, OSTR = C::OSTR, G = C::G;
+    constexpr float LOG2E = 1.4426950408889634f, LN2 = 0.6931471805599453f;
+    typedef short s16x4 __attribute__((ext_vector_type(4)));
+    typedef KvRegs<STEPS> Kv;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int c = lane & 15, kb = lane >> 4;
+    const int grp = P.nq / P.nkv;
+    const int Ra = grp * P.M;
+    const int ch_log = P.attn_ch_log, CH = 1 << ch_log, npass = P.attn_npass;
+    const float scale2 = P.inv_sqrt_d * LOG2E;     // scores are kept in units of ln 2: exponentials are v_exp_f32
+    char* sQ = smem + C::OFF_Q;
+    unsigned* sV = reinterpret_cast<unsigned*>(smem + C::OFF_V) + wave * G * 8 * VSTR;
+    float* sA = reinterpret_cast<float*>(smem + C::OFF_A) + wave * 16;
+    float* sML = reinterpret_cast<float*>(smem + C::OFF_ML);
+    float* sO = reinterpret_cast<float*>(smem + C::OFF_O);
+    const rsrc_t racc = make_rsrc(P.attn_acc), rml = make_rsrc(P.attn_ml), rn = make_rsrc(act_ptr(P, P.kvnew));
+    const SxBuf ro = sx_buf(P, P.o_buf);
+    const unsigned seq = ps_seq();
+    const int vm = min(lane / CBN, 7), vcb = lane % CBN;   // this lane's key pair and column block of the value rows
+    const bool vlive = lane / CBN < 8;
+
+    // work units and merge items: the host's counts, unless the lengths are device data (then it only knew upper bounds)
+    int n_units = P.attn_units, n_merge = P.attn_merge_items;
+    if (P.kv_len_dev) {
+        n_units = 0; n_merge = 0;
+        for (int b = 0; b < P.B; ++b) {
+            const int nch = attn_nch<true>(P, b, ch_log);
+            n_units += nch * P.nkv * npass;
+            if (nch > 1) n_merge += P.nkv * ((Ra + PS_WAVES - 1) / PS_WAVES);
         }
     }
+    const int n_items = npass == 1 ? n_units : (int)__umulhi((unsigned)n_units, P.pass_magic);
+    for (int u = wg; u < n_units; u += nwg) {
+        // unit -> (pass, block item), the passes of a block n_items units apart (workgroups on the same XCD when that
+        // is a multiple of 8: they read the same K and V rows)
+        int item = u, pass = 0;
+        while (item >= n_items) { item -= n_items; ++pass; }
+        const AttnItem it = attn_decode2(P, item, ch_log);
+        const int r0 = 16 * pass, nr = min(16, Ra - r0);
+        const int k_lo = it.ch << ch_log, k_hi = min(it.L, k_lo + CH);
+        const int ncs = (k_hi - k_lo + 15) >> 4;                    // groups of 16 cache keys (none: empty cache)
+        const int nts = it.ch == it.nch - 1 ? (P.M + 15) >> 4 : 0;  // groups of rows written in this step
+        const size_t cache_row0 = (size_t)P.kv_off[it.b] * P.nkv + it.hk;   // in units of D elements
+        stamp(P, wg, 44);
+
+        // K rows of cache keys key0 .. key0 + 15 as the MFMA operand (lane (c, kb): bytes [64 t + 16 kb, +16) of key
+        // c) and the value rows (lane (vm, vcb): columns [16 vcb, +16) of keys 2 vm and 2 vm + 1); keys beyond the
+        // block are clamped (masked later)
+        auto load_cache = [&](int s, Kv& r) __attribute__((always_inline)) {
+            const int key0 = k_lo + 16 * s, k_last = max(k_hi - 1, 0);
+            const int kp = min(key0 + c, k_last);
+            const char* krow = (const char*)P.kc + ((cache_row0 + (size_t)kp * P.nkv) * D) * 2 + kb * 16;
+#pragma unroll
+            for (int t = 0; t < STEPS; ++t) r.k[t] = ld16(krow + t * 64);
+            const int pa = min(key0 + 2 * vm, k_last), pb = min(key0 + 2 * vm + 1, k_last);
+            const char* pa_ = (const char*)P.vc + ((cache_row0 + (size_t)pa * P.nkv) * D) * 2 + vcb * 32;
+            const char* pb_ = (const char*)P.vc + ((cache_row0 + (size_t)pb * P.nkv) * D) * 2 + vcb * 32;
+            r.va[0] = ld16(pa_); r.va[1] = ld16(pa_ + 16);
+            r.vb[0] = ld16(pb_); r.vb[1] = ld16(pb_ + 16);
+        };
+        // the same for rows 16 ts .. 16 ts + 15 of this step: from the exchange buffer, once the QKV phase has
+        // published them (fp32, exactly representable in bf16: they were rounded when they went to the cache)
+        auto load_tail = [&](int ts, Kv& r) __attribute__((always_inline)) {
+            const int jk = min(16 * ts + c, P.M - 1);
+            const int ja = min(16 * ts + 2 * vm, P.M - 1), jb = min(16 * ts + 2 * vm + 1, P.M - 1);
+            const unsigned kbase = (unsigned)(((size_t)(it.b * P.M + jk) * 2) * P.KVD + it.hk * D + kb * 8);
+            const unsigned abase = (unsigned)(((size_t)(it.b * P.M + ja) * 2 + 1) * P.KVD + it.hk * D + vcb * 16);
+            const unsigned bbase = (unsigned)(((size_t)(it.b * P.M + jb) * 2 + 1) * P.KVD + it.hk * D + vcb * 16);
+            u32x4 kx[STEPS][2], ax[4], bx[4];
+            int spins = 0;
+            for (;;) {
+#pragma unroll
+                for (int t = 0; t < STEPS; ++t)
+#pragma unroll
+                    for (int h = 0; h < 2; ++h) kx[t][h] = coh_ld16(rn, (kbase + 32 * t + 4 * h) * 4);
+#pragma unroll
+                for (int h = 0; h < 4; ++h) { ax[h] = coh_ld16(rn, (abase + 4 * h) * 4); bx[h] = coh_ld16(rn, (bbase + 4 * h) * 4); }
+                unsigned bad = 0;   // all loads first, then all checks: no wait between the loads
+#pragma unroll
+                for (int t = 0; t < STEPS; ++t) bad |= (unsigned)!sx_ok(kx[t][0]) | (unsigned)!sx_ok(kx[t][1]);
+#pragma unroll
+                for (int h = 0; h < 4; ++h) bad |= (unsigned)!sx_ok(ax[h]) | (unsigned)!sx_ok(bx[h]);
+                if (__all(!bad) || !spin_again(P, spins)) break;
+            }
+            auto pk = [](u32x4 lo, u32x4 hi) __attribute__((always_inline)) {
+                return make_uint4(pack_bf16x2(__uint_as_float(lo[0]), __uint_as_float(lo[1])), pack_bf16x2(__uint_as_float(lo[2]), __uint_as_float(lo[3])),
+                                  pack_bf16x2(__uint_as_float(hi[0]), __uint_as_float(hi[1])), pack_bf16x2(__uint_as_float(hi[2]), __uint_as_float(hi[3])));
+            };
+#pragma unroll
+            for (int t = 0; t < STEPS; ++t) r.k[t] = pk(kx[t][0], kx[t][1]);
+            r.va[0] = pk(ax[0], ax[1]); r.va[1] = pk(ax[2], ax[3]);
+            r.vb[0] = pk(bx[0], bx[1]); r.vb[1] = pk(bx[2], bx[3]);
+        };
+
+        // A wavefront works on G = 2 groups at a time (groups s and s + 8 of the block), and the K and V rows of the
+        // next two are requested while it does: two sets of registers take turns.  Every request is unconditional
+        // (beyond the last group it repeats a row of the block: nobody uses it), so that the waits in front of the
+        // uses count exactly the younger requests and leave them in flight.
+        Kv ra[G], rb[G];
+#pragma unroll
+        for (int g = 0; g < G; ++g) load_cache(wave + g * PS_WAVES, ra[g]);      // ahead of the wait for the query rows
+        u32x4 qx = attn_issue_q<WT, D>(P, it, r0, Ra, grp, tid);
+#pragma unroll
+        for (int g = 0; g < G; ++g) load_cache(wave + (G + g) * PS_WAVES, rb[g]);
+        attn_place_q<WT, D>(P, it, r0, Ra, grp, tid, qx, sQ);
+        __syncthreads();                                             // (also: the previous unit's results have been read)
+        stamp(P, wg, 45);
+        // this lane's query row (column c of the score tile) and its index among the M rows of its sequence
+        const bool qlive = c < nr;
+        const int rho_c = min(r0 + c, Ra - 1);
+        const int qi = rho_c - row_seq(P, rho_c) * P.M;
+        float m_run = -INFINITY, l_run = 0.f;                        // of query c (the same in the four lanes that share it); m in units of ln 2
+        f32x4 oacc[CBN];                                             // lane (c, kb): column 16 j + c of rows 4 kb .. 4 kb + 3
+#pragma unroll
+        for (int j = 0; j < CBN; ++j) oacc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+        // NG groups of 16 keys at once.  TAIL: rows base .. base + 15 of this step (row qi sees rows <= qi); else
+        // cache positions base + 128 g .. + 15 (every row of the step sees all valid cache positions)
+        auto process = [&](const Kv* r, int base, auto NG_, auto TAIL) __attribute__((always_inline)) {
+            constexpr bool tail = decltype(TAIL)::value;
+            constexpr int NG = decltype(NG_)::value;
+            f32x4 acc[NG][1];
+#pragma unroll
+            for (int g = 0; g < NG; ++g) acc[g][0] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int t = 0; t < STEPS; ++t) {
+                BRegs<WT, 1> bq;                                     // the query rows (read per step: registers are scarce)
+                bq.h[0] = ld16(sQ + (2 * t * 64 + lane) * 16);
+                bq.l[0] = ld16(sQ + ((2 * t + 1) * 64 + lane) * 16);
+#pragma unroll
+                for (int g = 0; g < NG; ++g) mma_step<WT, 1>(r[g].k[t], bq, acc[g]);
+            }
+            float sc[NG][4], mt = -INFINITY;
+#pragma unroll
+            for (int g = 0; g < NG; ++g)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int j = base + 16 * PS_WAVES * g + 4 * kb + e;
+                    const bool vis = qlive && (tail ? (j <= qi && j < P.M) : j < k_hi);
+                    sc[g][e] = vis ? acc[g][0][e] * scale2 : -INFINITY;
+                    mt = fmaxf(mt, sc[g][e]);
+                }
+            mt = quad_rows_max(mt);
+            const float m_new = fmaxf(m_run, mt);
+            const float alpha = m_new > -INFINITY ? __builtin_amdgcn_exp2f(m_run - m_new) : 1.f;   // 2^-inf = 0 when nothing was seen before
+            const float m_use = m_new > -INFINITY ? m_new : 0.f;     // (all masked: every exponent is -inf)
+            f32x4 pr[NG];
+            float ls = 0.f;
+#pragma unroll
+            for (int g = 0; g < NG; ++g)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    pr[g][e] = __builtin_amdgcn_exp2f(sc[g][e] - m_use);
+                    ls += pr[g][e];
+                }
+            ls = quad_rows_sum(ls);
+            l_run = l_run * alpha + ls;
+            m_run = m_new;
+            if (kb == 0) sA[c] = alpha;
+            // the value rows into LDS, the two keys of a pair interleaved column by column
+            if (vlive) {
+#pragma unroll
+                for (int g = 0; g < NG; ++g) {
+                    unsigned ov[16];
+#pragma unroll
+                    for (int w = 0; w < 8; ++w) {
+                        const unsigned a2 = w < 4 ? (&r[g].va[0].x)[w] : (&r[g].va[1].x)[w - 4], b2 = w < 4 ? (&r[g].vb[0].x)[w] : (&r[g].vb[1].x)[w - 4];
+                        ov[2 * w] = __builtin_amdgcn_perm(b2, a2, 0x05040100u);       // (low half of a2, low half of b2)
+                        ov[2 * w + 1] = __builtin_amdgcn_perm(b2, a2, 0x07060302u);   // (high half of a2, high half of b2)
+                    }
+                    uint4* dst = reinterpret_cast<uint4*>(sV + (g * 8 + vm) * VSTR + 16 * vcb);
+#pragma unroll
+                    for (int w = 0; w < 4; ++w) dst[w] = make_uint4(ov[4 * w], ov[4 * w + 1], ov[4 * w + 2], ov[4 * w + 3]);
+                }
+            }
+            lds_sync_wave();                                         // written and read by this wavefront only
+            __builtin_amdgcn_wave_barrier();
+            // rescale the running output (rows 4 kb .. 4 kb + 3) unless no row's maximum moved
+            const f32x4 al = *reinterpret_cast<const f32x4*>(sA + 4 * kb);
+            if (__any(alpha != 1.f)) {
+#pragma unroll
+                for (int j = 0; j < CBN; ++j) oacc[j] *= al;
+            }
+#pragma unroll
+            for (int g = 0; g < NG; ++g) {
+                // P (query c, keys 4 kb .. 4 kb + 3) as the 16-row operand, split into bf16 high and low parts
+                const unsigned h01 = pack_bf16x2(pr[g][0], pr[g][1]), h23 = pack_bf16x2(pr[g][2], pr[g][3]);
+                const unsigned l01 = pack_bf16x2(pr[g][0] - __uint_as_float(h01 << 16), pr[g][1] - __uint_as_float(h01 & 0xFFFF0000u));
+                const unsigned l23 = pack_bf16x2(pr[g][2] - __uint_as_float(h23 << 16), pr[g][3] - __uint_as_float(h23 & 0xFFFF0000u));
+                const s16x4 ph_ = __builtin_bit_cast(s16x4, make_uint2(h01, h23)), pl_ = __builtin_bit_cast(s16x4, make_uint2(l01, l23));
+#pragma unroll
+                for (int j = 0; j < CBN; ++j) {
+                    // values of keys 4 kb .. 4 kb + 3, column 16 j + c: the key pairs 2 kb and 2 kb + 1
+                    const unsigned w0 = sV[(g * 8 + 2 * kb) * VSTR + 16 * j + c], w1 = sV[(g * 8 + 2 * kb + 1) * VSTR + 16 * j + c];
+                    const s16x4 vv = __builtin_bit_cast(s16x4, make_uint2(w0, w1));
+                    const f32x4 t = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(ph_, vv, oacc[j], 0, 0, 0);
+                    oacc[j] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pl_, vv, t, 0, 0, 0);
+                }
+            }
+            lds_sync_wave();
+            __builtin_amdgcn_wave_barrier();                         // the next groups overwrite the staged values
+        };
+        typedef std::integral_constant<int, G> NGG;
+        typedef std::integral_constant<int, 1> NG1;
+        // ra holds groups (s, s + 8), rb groups (s + 16, s + 24); requests only while ra has a successor, so a
+        // block of up to 32 groups requests nothing it does not use
+        int s = wave;
+        for (; s + 2 * G * PS_WAVES < ncs; s += 2 * G * PS_WAVES) {
+            process(ra, k_lo + 16 * s, NGG(), std::false_type());
+#pragma unroll
+            for (int g = 0; g < G; ++g) load_cache(s + (2 * G + g) * PS_WAVES, ra[g]);
+            process(rb, k_lo + 16 * (s + G * PS_WAVES), NGG(), std::false_type());
+#pragma unroll
+            for (int g = 0; g < G; ++g) load_cache(s + (3 * G + g) * PS_WAVES, rb[g]);
+        }
+        if (s < ncs) process(ra, k_lo + 16 * s, NGG(), std::false_type());
+        if (s + G * PS_WAVES < ncs) process(rb, k_lo + 16 * (s + G * PS_WAVES), NGG(), std::false_type());
+        // the rows of this step come last (they are the last to arrive), taken by the wavefronts next in turn
+        for (int ts = 0; ts < nts; ++ts) {
+            if (((ncs + ts) & (PS_WAVES - 1)) != wave) continue;
+            load_tail(ts, ra[0]);
+            process(ra, 16 * ts, NG1(), std::true_type());
+        }
+        stamp(P, wg, 47);
+        // ---- the wavefronts' results meet in LDS
+        if (kb == 0) { sML[(wave * 16 + c) * 2] = m_run; sML[(wave * 16 + c) * 2 + 1] = l_run; }
+#pragma unroll
+        for (int j = 0; j < CBN; ++j)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) sO[(wave * 16 + 4 * kb + e) * OSTR + 16 * j + c] = oacc[j][e];
+        __syncthreads();
+        for (int x = tid; x < nr * (D / 4); x += PS_WG_THREADS) {
+            const int rr = x / (D / 4), dd = 4 * (x - rr * (D / 4));
+            float mx = -INFINITY;
+#pragma unroll
+            for (int w = 0; w < PS_WAVES; ++w) mx = fmaxf(mx, sML[(w * 16 + rr) * 2]);
+            f32x4 num = {0.f, 0.f, 0.f, 0.f};
+            float den = 0.f;
+#pragma unroll
+            for (int w = 0; w < PS_WAVES; ++w) {
+                const float mw = sML[(w * 16 + rr) * 2];
+                const float f = mw > -INFINITY ? __builtin_amdgcn_exp2f(mw - mx) : 0.f;
+                num += *reinterpret_cast<const f32x4*>(sO + (w * 16 + rr) * OSTR + dd) * f;
+                den += sML[(w * 16 + rr) * 2 + 1] * f;
+            }
+            const int rho = r0 + rr;
+            const int gi = row_seq(P, rho), i = rho - gi * P.M;
+            if (it.nch == 1) {
+                // the only block: normalise and hand the row to the output projection (every row sees at least itself)
+                sx_st4(ro, (unsigned)((size_t)(it.b * P.M + i) * P.QD + (it.hk * grp + gi) * D + dd), num * (1.0f / den));
+            } else {
+                // partial (max, sum, unnormalised output) of this block, as tagged data; the maximum in natural units
+                ll_st4(racc, (unsigned)(((size_t)item * Ra + rho) * D + dd), num, seq);
+                if (dd == 0) {
+                    ll_st1(rml, (unsigned)(((size_t)item * Ra + rho) * 2), mx * LN2, seq);
+                    ll_st1(rml, (unsigned)(((size_t)item * Ra + rho) * 2 + 1), den, seq);
+                }
+            }
+        }
+        stamp(P, wg, 48);
+    }
+    stamp(P, wg, 34);
+    float* sM = sML;
+    attn_merge<WT, D, true>(P, wg, nwg, wave, n_merge, ch_log, sM, sM + 128, sO, sO + PS_WAVES * 256);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -2071,6 +2434,14 @@ __global__ void __launch_bounds__(PS_WG_THREADS) attn_kernel(const StepParams P)
     attn_phase<WT, D, NK, SINGLE>(P, blockIdx.x, gridDim.x, __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), smem);
 }
 
+template <typename WT, int D>
+__global__ void __launch_bounds__(PS_WG_THREADS) attn2_kernel(const StepParams P) {
+    extern __shared__ __attribute__((aligned(256))) char smem[];
+    step_begin(P, false);
+    sx_reset_stale(P, blockIdx.x, gridDim.x);
+    attn_phase2<WT, D>(P, blockIdx.x, gridDim.x, __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), smem);
+}
+
 static __global__ void __launch_bounds__(PS_WG_THREADS) lm_merge_kernel(const StepParams P) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
     const unsigned ticket = step_begin(P, true);   // the last kernel of a step in this mode
@@ -2105,13 +2476,20 @@ __global__ void __launch_bounds__(PS_WG_THREADS, 1) fused_kernel(const StepParam
     const unsigned my_seq = step_read(P, false, ticket);
     kv_fill(P);                                  // (read after the first phase's barriers at the earliest)
     preload_weights(wb, first_stream(P, PH_QKV, wg, wave), lane * 16);
-    gemm_phase<WT, MT, PH_QKV>(P, wg, wave, smem, wb, first_stream(P, PH_OPROJ, wg, wave), my_seq);
+    // (bf16 storage: the attention needs the registers; the output projection's first weight loads are
+    // requested after it - a workgroup without attention work gets there at once)
+    gemm_phase<WT, MT, PH_QKV>(P, wg, wave, smem, wb, Traits<WT>::BF ? P.ph[PH_OPROJ].wpack : first_stream(P, PH_OPROJ, wg, wave), my_seq);
     __syncthreads();
     stamp(P, wg, 32);
-    switch (2 * P.attn_nk + P.attn_single) {
-        case 2: attn_phase<WT, D, 1, false>(P, wg, gridDim.x, wave, smem); break;
-        case 3: attn_phase<WT, D, 1, true>(P, wg, gridDim.x, wave, smem); break;
-        default: attn_phase<WT, D, 2, true>(P, wg, gridDim.x, wave, smem); break;   // (host: two key groups only with a single pass)
+    if constexpr (Traits<WT>::BF) {
+        attn_phase2<WT, D>(P, wg, gridDim.x, wave, smem);
+        preload_weights(wb, first_stream(P, PH_OPROJ, wg, wave), lane * 16);
+    } else {
+        switch (2 * P.attn_nk + P.attn_single) {
+            case 2: attn_phase<WT, D, 1, false>(P, wg, gridDim.x, wave, smem); break;
+            case 3: attn_phase<WT, D, 1, true>(P, wg, gridDim.x, wave, smem); break;
+            default: attn_phase<WT, D, 2, true>(P, wg, gridDim.x, wave, smem); break;   // (host: two key groups only with a single pass)
+        }
     }
     __syncthreads();
     stamp(P, wg, 36);

@@ -51,6 +51,7 @@ struct ps_draft_ctx {
     int n_counters;
     int plan_override[PH_COUNT][2];   // K-slices, wavefronts per tile from PS_DRAFT_PLAN (0 = automatic)
     int attn_sep_override;            // PS_DRAFT_ATTN_SEP=0/1: who takes this step's rows in the attention (-1 = automatic)
+    int attn_nk_override;             // PS_DRAFT_ATTN_NK=1/2/4/8/16: groups of 16 keys per wavefront and block, bf16 storage (0 = automatic)
     size_t off_frag[PH_COUNT], off_ssqf[PH_COUNT];
     bool profile;
     unsigned long long* timeline;
@@ -284,6 +285,9 @@ extern "C" int ps_draft_init(ps_draft_ctx** out, const ps_draft_config* config, 
     {
         const char* e = getenv("PS_DRAFT_ATTN_SEP");
         ctx->attn_sep_override = (e && (e[0] == '0' || e[0] == '1')) ? e[0] - '0' : -1;
+        const char* e2 = getenv("PS_DRAFT_ATTN_NK");
+        const int nk_ov = e2 ? atoi(e2) : 0;
+        ctx->attn_nk_override = (nk_ov >= 1 && nk_ov <= (1 << PS_ATTN2_NK_LOG_MAX) && (nk_ov & (nk_ov - 1)) == 0) ? nk_ov : 0;
     }
     ctx->profile = false;
     ctx->timeline = nullptr;
@@ -586,6 +590,7 @@ extern "C" int ps_draft_step(ps_draft_ctx* ctx, const ps_draft_step_args* a, voi
         if (items2 <= ctx->n_cu) { nk = 2; ch *= 2; items = items2; }
     }
     P.attn_items = items; P.attn_single = ra <= 16; P.attn_sep = sep ? 1 : 0; P.attn_tail = tail; P.attn_nk = nk;
+    const bool attn2 = c.dtype == PS_BF16;   // bf16 storage: attn_phase2 (ps_device.h)
     {   // sequences that span several key blocks are put together by (sequence, kv head, 8 rows) work items
         const int rt = (ra + PS_WAVES - 1) / PS_WAVES;
         int mi = 0;
@@ -593,6 +598,48 @@ extern "C" int ps_draft_step(ps_draft_ctx* ctx, const ps_draft_step_args* a, voi
             if (sep || (a->kv_len[b] + tail + ch - 1) / ch > 1) mi += c.n_kv_heads * rt;
         P.attn_merge_items = mi;
         const int want = items > mi ? items : mi;
+        P.attn_nwg = want < ctx->n_cu ? want : ctx->n_cu;
+    }
+    if (attn2) {
+        // Work units = (sequence, kv head, block of 128 NK cache keys, pass of 16 query rows); the rows of this step
+        // ride on a sequence's last block.  NK (a power of two) is chosen by a small cost model in microseconds,
+        // measured on c1 .. c4: a unit costs about 2 + 1 per group of 16 keys a wavefront takes in turn (two at
+        // a time), the workgroups take ceil(units / compute units) rounds of them, and a sequence of several
+        // blocks costs one more exchange through memory (the merge items).
+        const int npass = (ra + 15) / 16, rt = (ra + PS_WAVES - 1) / PS_WAVES;
+        int best_log = 0;
+        double best = 1e30;
+        for (int lg = 0; lg <= PS_ATTN2_NK_LOG_MAX; ++lg) {
+            if (ctx->attn_nk_override > 0 && (1 << lg) != ctx->attn_nk_override) continue;
+            const int chl = PS_ATTN_KEYS_LOG + lg;
+            long long units = 0;
+            int groups = 1;
+            bool merge = false;
+            for (int b = 0; b < a->batch; ++b) {
+                const int L = a->kv_len[b];
+                int nch = (int)(((long long)L + (1 << chl) - 1) >> chl);
+                if (nch < 1) nch = 1;
+                units += (long long)c.n_kv_heads * nch * npass;
+                merge = merge || nch > 1;
+                const int g = ((L < (1 << chl) ? L : (1 << chl)) + 15) / 16 + (M + 15) / 16;
+                if (g > groups) groups = g;
+            }
+            const long long rounds = (units + ctx->n_cu - 1) / ctx->n_cu;
+            const double cost = (double)rounds * (2.0 + 1.0 * ((groups + PS_WAVES - 1) / PS_WAVES)) + (merge ? 5.0 : 0.0);
+            if (cost < best - 1e-9) { best = cost; best_log = lg; }
+        }
+        const int chl = PS_ATTN_KEYS_LOG + best_log;
+        int items2 = 0, mi = 0;
+        for (int b = 0; b < a->batch; ++b) {
+            int nch = (int)(((long long)a->kv_len[b] + (1 << chl) - 1) >> chl);
+            if (nch < 1) nch = 1;
+            items2 += c.n_kv_heads * nch;
+            if (nch > 1) mi += c.n_kv_heads * rt;
+        }
+        P.attn_ch_log = chl; P.attn_npass = npass; P.pass_magic = 0xFFFFFFFFu / (unsigned)npass + 1u;
+        P.attn_items = items2; P.attn_units = items2 * npass; P.attn_merge_items = mi;
+        P.attn_sep = 0; P.attn_tail = 0; P.attn_nk = 1;
+        const int want = P.attn_units > mi ? P.attn_units : mi;
         P.attn_nwg = want < ctx->n_cu ? want : ctx->n_cu;
     }
 
@@ -629,7 +676,7 @@ extern "C" int ps_draft_step(ps_draft_ctx* ctx, const ps_draft_step_args* a, voi
     }
 
     // the persistent kernel needs the largest LDS footprint of its phases and one workgroup per CU
-    int lds = ps_attn_lds_bytes(c.head_dim, nk);
+    int lds = attn2 ? ps_attn2_lds_bytes(c.head_dim) : ps_attn_lds_bytes(c.head_dim, nk);
     for (int ph = 0; ph < PH_COUNT; ++ph) {
         if (P.ph[ph].lds_bytes > lds) lds = P.ph[ph].lds_bytes;
     }

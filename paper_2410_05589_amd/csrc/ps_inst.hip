@@ -39,12 +39,18 @@ static kernel_fn fused_fn(int mt) {
 }
 
 static kernel_fn attn_fn(int nk, int single) {
+#if PS_INST_BF16
+    return attn2_kernel<WT_, D_>;
+#endif
     switch (2 * nk + (single ? 1 : 0)) {
         case 2: return attn_kernel<WT_, D_, 1, false>;
         case 3: return attn_kernel<WT_, D_, 1, true>;
         default: return attn_kernel<WT_, D_, 2, true>;   // (host: two key groups only with a single pass)
     }
 }
+
+// dynamic LDS of the attention kernel (bf16 storage: one variant, see attn_phase2)
+static int attn_lds(int nk) { return PS_INST_BF16 ? ps_attn2_lds_bytes(D_) : ps_attn_lds_bytes(D_, nk); }
 
 static hipError_t prepare(int lds_limit) {
     hipError_t e;
@@ -58,11 +64,11 @@ static hipError_t prepare(int lds_limit) {
                                 hipFuncAttributeMaxDynamicSharedMemorySize, lds_limit);
         if (e != hipSuccess) return e;
     }
-    if (ps_attn_lds_bytes(D_, 2) > lds_limit) return hipErrorInvalidValue;
+    if (attn_lds(2) > lds_limit) return hipErrorInvalidValue;
     for (int v = 2; v < 6; ++v) {
         if (v == 4) continue;
         e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_fn(v >> 1, v & 1)), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                ps_attn_lds_bytes(D_, v >> 1));
+                                attn_lds(v >> 1));
         if (e != hipSuccess) return e;
     }
     return hipSuccess;
@@ -82,7 +88,7 @@ static hipError_t launch_multi(const StepParams& P, hipStream_t stream, hipEvent
     hipError_t e;
     if ((e = mark()) != hipSuccess) return e;
     if ((e = gemm(PH_QKV, mt_all)) != hipSuccess) return e;
-    hipLaunchKernelGGL(attn_fn(P.attn_nk, P.attn_single), dim3(P.attn_nwg), dim3(PS_WG_THREADS), ps_attn_lds_bytes(D_, P.attn_nk), stream, P);
+    hipLaunchKernelGGL(attn_fn(P.attn_nk, P.attn_single), dim3(P.attn_nwg), dim3(PS_WG_THREADS), attn_lds(P.attn_nk), stream, P);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     if ((e = mark()) != hipSuccess) return e;
     if ((e = gemm(PH_OPROJ, mt_all)) != hipSuccess) return e;

@@ -42,6 +42,12 @@ constexpr int ps_attn_lds_bytes(int d, int nk) {
     return PS_LDS_BASE + 2 * PS_WAVES * 16 * 4 + PS_WAVES * nk * 16 * 16 * 4 + PS_WAVES * 16 * d * 4 + 16 * d * 4;
 }
 
+// bf16 storage (attn_phase2 in ps_device.h; Attn2Cfg): query operands, staged value rows, rescale factors, (max, sum), outputs
+constexpr int ps_attn2_lds_bytes(int d) {
+    return PS_LDS_BASE + 16 * d * 4 + PS_WAVES * 2 * 8 * (d + 8) * 4 + PS_WAVES * 16 * 4 + PS_WAVES * 16 * 2 * 4 + PS_WAVES * 16 * (d + 4) * 4;
+}
+#define PS_ATTN2_NK_LOG_MAX 4   // at most 16 groups of 16 keys per wavefront and block: blocks of up to 2048 cache keys
+
 // The five GEMM phases of the step, and the input projection of the feature-fusion input mode (a kernel of
 // its own in front of the step, built from the same engine)
 enum { PH_QKV = 0, PH_OPROJ = 1, PH_GATEUP = 2, PH_DOWN = 3, PH_LMHEAD = 4, PH_FC = 5, PH_COUNT = 6 };
@@ -145,6 +151,10 @@ struct StepParams {
     // the attention over these rows (attn_tail = 0, attn_sep = 1; see ps_draft_step for when)
     int attn_tail, attn_sep;
     int attn_merge_items;   // (sequence, kv head, 8 query rows) of the sequences that span several key blocks
+    // bf16 storage (attn_phase2): blocks of 2^attn_ch_log cache keys, passes of 16 query rows per kv head,
+    // work units = blocks x passes
+    int attn_ch_log, attn_npass, attn_units;
+    unsigned pass_magic;    // ceil(2^32 / attn_npass)
     int fused_nwg, fused_lds;
     long long kv_off[PS_MAX_ROWS];
     int kv_len[PS_MAX_ROWS];

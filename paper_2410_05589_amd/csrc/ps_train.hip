@@ -34,11 +34,6 @@ struct GaParams {
     double log_base;
 };
 
-// LDS data that one wavefront writes and the same wavefront reads: its LDS operations complete in order, so
-// all that is needed is that the compiler keeps the order too and that the writes have left the queue.  (A
-// workgroup-scope fence would also wait for every global load in flight - the next tile's, requested ahead.)
-__device__ __forceinline__ void lds_sync_wave() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
-
 template <int D>
 __global__ void __launch_bounds__(256) ga_table_kernel(const GaParams P) {
     const int n = (P.T + P.k) * (D / 2);

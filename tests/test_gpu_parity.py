@@ -91,27 +91,31 @@ def test_every_k_split_of_the_gemm_engine(plan, monkeypatch):
     _run_case(wl3, label="plan " + plan + " (42 rows)")
 
 
-def test_new_rows_left_to_the_merge_items():
-    """When this step's rows alone would make up one more key block per sequence and that block would
-    cost the workgroups a second round of attention work items (more items than compute units), the
-    merge items take these rows instead.  8 sequences x 8 kv heads, KV lengths that are multiples of the
-    block size (one of them 0): 256 block items instead of 320."""
-    shape = small_shape("bf16", hidden=1024, n_heads=8, n_kv_heads=8, head_dim=128, ffn=1376, vocab=2000)
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_new_rows_left_to_the_merge_items(dtype):
+    """float32 kernels: when this step's rows alone would make up one more key block per sequence and that
+    block would cost the workgroups a second round of attention work items (more items than compute units),
+    the merge items take these rows instead.  8 sequences x 8 kv heads, KV lengths that are multiples of the
+    block size (one of them 0): 256 block items instead of 320.  (The bf16 kernels always let the rows ride
+    on the last block of cache keys: the same shapes, an empty cache among them.)"""
+    shape = small_shape(dtype, hidden=1024, n_heads=8, n_kv_heads=8, head_dim=128, ffn=1376, vocab=2000)
     wl = Workload("sep", shape, batch=8, kv_len=(0, 1024, 512, 512, 512, 512, 512, 512), n_new=1, k=5, topk=8, seed=33)
     _run_case(wl)
     # grouped queries: 2 query heads per kv head, 9 rows -> 18 query rows per kv head (two passes of 16)
-    shape2 = small_shape("bf16", hidden=1024, n_heads=16, n_kv_heads=8, head_dim=64, ffn=1376, vocab=2000)
+    shape2 = small_shape(dtype, hidden=1024, n_heads=16, n_kv_heads=8, head_dim=64, ffn=1376, vocab=2000)
     wl2 = Workload("sep gqa", shape2, batch=4, kv_len=(1024,) * 4, n_new=1, k=8, topk=8, seed=34)
     _run_case(wl2)
 
 
-def test_key_blocks_of_twice_the_size():
-    """More attention work items than compute units with 128-key blocks, no more than that with 256-key
-    blocks: every wavefront then takes two groups of 16 keys.  One pass of query rows, and two (GQA)."""
-    shape = small_shape("bf16", hidden=1024, n_heads=8, n_kv_heads=8, head_dim=128, ffn=1376, vocab=2000)
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_key_blocks_of_twice_the_size(dtype):
+    """float32 kernels: more attention work items than compute units with 128-key blocks, no more than that
+    with 256-key blocks: every wavefront then takes two groups of 16 keys.  One pass of query rows, and two
+    (GQA).  (bf16 kernels: the host picks blocks of 128 .. 2048 keys; several blocks per sequence here.)"""
+    shape = small_shape(dtype, hidden=1024, n_heads=8, n_kv_heads=8, head_dim=128, ffn=1376, vocab=2000)
     wl = Workload("nk2", shape, batch=8, kv_len=(600, 513, 700, 640, 520, 767, 600, 650), n_new=1, k=5, topk=8, seed=37)
     _run_case(wl)
-    shape2 = small_shape("bf16", hidden=1024, n_heads=16, n_kv_heads=8, head_dim=64, ffn=1376, vocab=2000)
+    shape2 = small_shape(dtype, hidden=1024, n_heads=16, n_kv_heads=8, head_dim=64, ffn=1376, vocab=2000)
     wl2 = Workload("nk2 gqa", shape2, batch=7, kv_len=(600, 513, 700, 640, 520, 767, 600), n_new=1, k=8, topk=8, seed=38)
     _run_case(wl2)
 
@@ -162,11 +166,33 @@ def test_maximum_rows_and_topk():
     _run_case(wl, all_rows=True, topk=1, label="64 rows, all decoded, top-1")
 
 
-def test_very_long_sequence_many_key_blocks():
-    # 33000 keys = 258 attention blocks: more than one group of 256 blocks in the combination pass
-    shape = small_shape("bf16", hidden=256, n_heads=4, n_kv_heads=2, head_dim=64, ffn=704, vocab=1024)
+@pytest.mark.parametrize("dtype,nk", [("f32", None), ("bf16", None), ("bf16", "1")])
+def test_very_long_sequence_many_key_blocks(dtype, nk, monkeypatch):
+    # 33000 keys = 258 attention blocks of 128 keys (the float32 kernels' size; the bf16 kernels' when forced):
+    # more than one group of 256 blocks in the combination pass; bf16 by itself: 17 blocks of 2048 keys
+    if nk:
+        monkeypatch.setenv("PS_DRAFT_ATTN_NK", nk)
+    shape = small_shape(dtype, hidden=256, n_heads=4, n_kv_heads=2, head_dim=64, ffn=704, vocab=1024)
     wl = Workload("long", shape, batch=2, kv_len=(33000, 2100), n_new=1, k=4, topk=4, seed=33)
     _run_case(wl)
+
+
+@pytest.mark.parametrize("nk", ["1", "2", "4", "8", "16"])
+def test_every_block_size_of_the_bf16_attention(nk, monkeypatch):
+    """The bf16 attention works on blocks of 128 NK cache keys per work unit (NK groups of 16 keys per wavefront,
+    two at a time); the library picks NK, PS_DRAFT_ATTN_NK forces it.  Ragged batch with an empty cache, lengths
+    around the block sizes and a long sequence; one pass of query rows (head_dim 128), then three passes (GQA, 4
+    query heads per kv head x 9 rows, head_dim 64) and rows of the step spilling into a second group of 16 (17 rows)."""
+    monkeypatch.setenv("PS_DRAFT_ATTN_NK", nk)
+    shape = small_shape("bf16", hidden=512, n_heads=4, n_kv_heads=4, head_dim=128, ffn=1024, vocab=1000)
+    wl = Workload("blocks", shape, batch=7, kv_len=(0, 1, 127, 128, 129, 2049, 700), n_new=1, k=5, topk=4, seed=61)
+    _run_case(wl, label="NK " + nk)
+    shape2 = small_shape("bf16", hidden=512, n_heads=8, n_kv_heads=2, head_dim=64, ffn=1024, vocab=1000)
+    wl2 = Workload("blocks gqa", shape2, batch=3, kv_len=(15, 300, 4100), n_new=1, k=8, topk=4, seed=62)
+    _run_case(wl2, label="NK " + nk + " (three passes)")
+    shape3 = small_shape("bf16", hidden=512, n_heads=4, n_kv_heads=2, head_dim=64, ffn=1024, vocab=1000)
+    wl3 = Workload("blocks 17 rows", shape3, batch=2, kv_len=(250, 31), n_new=9, k=8, topk=4, seed=63)
+    _run_case(wl3, label="NK " + nk + " (17 rows per sequence)")
 
 
 def test_without_final_norm():
