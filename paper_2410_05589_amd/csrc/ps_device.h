@@ -2169,20 +2169,38 @@ __device__ __forceinline__ void attn_phase2(const StepParams& P, int wg, int nwg
 #pragma unroll
                 for (int j = 0; j < CBN; ++j) oacc[j] *= al;
             }
+            // P (query c, keys 4 kb .. 4 kb + 3 of every group) as the 16-row operand, split into bf16 high and low parts
+            unsigned ph2[NG][2], pl2[NG][2];
 #pragma unroll
             for (int g = 0; g < NG; ++g) {
-                // P (query c, keys 4 kb .. 4 kb + 3) as the 16-row operand, split into bf16 high and low parts
-                const unsigned h01 = pack_bf16x2(pr[g][0], pr[g][1]), h23 = pack_bf16x2(pr[g][2], pr[g][3]);
-                const unsigned l01 = pack_bf16x2(pr[g][0] - __uint_as_float(h01 << 16), pr[g][1] - __uint_as_float(h01 & 0xFFFF0000u));
-                const unsigned l23 = pack_bf16x2(pr[g][2] - __uint_as_float(h23 << 16), pr[g][3] - __uint_as_float(h23 & 0xFFFF0000u));
-                const s16x4 ph_ = __builtin_bit_cast(s16x4, make_uint2(h01, h23)), pl_ = __builtin_bit_cast(s16x4, make_uint2(l01, l23));
+                ph2[g][0] = pack_bf16x2(pr[g][0], pr[g][1]); ph2[g][1] = pack_bf16x2(pr[g][2], pr[g][3]);
+                pl2[g][0] = pack_bf16x2(pr[g][0] - __uint_as_float(ph2[g][0] << 16), pr[g][1] - __uint_as_float(ph2[g][0] & 0xFFFF0000u));
+                pl2[g][1] = pack_bf16x2(pr[g][2] - __uint_as_float(ph2[g][1] << 16), pr[g][3] - __uint_as_float(ph2[g][1] & 0xFFFF0000u));
+            }
+            if constexpr (NG == 2) {
+                // two groups = 32 keys: one v_mfma_f32_16x16x32_bf16 per part and column block; its contraction index
+                // 8 kb + e is key 4 kb + e of the first group (e < 4) or key 4 kb + e - 4 of the second
+                const bf16x8 pa = __builtin_bit_cast(bf16x8, make_uint4(ph2[0][0], ph2[0][1], ph2[1][0], ph2[1][1]));
+                const bf16x8 pb = __builtin_bit_cast(bf16x8, make_uint4(pl2[0][0], pl2[0][1], pl2[1][0], pl2[1][1]));
 #pragma unroll
                 for (int j = 0; j < CBN; ++j) {
-                    // values of keys 4 kb .. 4 kb + 3, column 16 j + c: the key pairs 2 kb and 2 kb + 1
-                    const unsigned w0 = sV[(g * 8 + 2 * kb) * VSTR + 16 * j + c], w1 = sV[(g * 8 + 2 * kb + 1) * VSTR + 16 * j + c];
-                    const s16x4 vv = __builtin_bit_cast(s16x4, make_uint2(w0, w1));
-                    const f32x4 t = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(ph_, vv, oacc[j], 0, 0, 0);
-                    oacc[j] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pl_, vv, t, 0, 0, 0);
+                    const bf16x8 vv = __builtin_bit_cast(bf16x8, make_uint4(sV[(2 * kb) * VSTR + 16 * j + c], sV[(2 * kb + 1) * VSTR + 16 * j + c],
+                                                                            sV[(8 + 2 * kb) * VSTR + 16 * j + c], sV[(8 + 2 * kb + 1) * VSTR + 16 * j + c]));
+                    const f32x4 t = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa, vv, oacc[j], 0, 0, 0);
+                    oacc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pb, vv, t, 0, 0, 0);
+                }
+            } else {
+#pragma unroll
+                for (int g = 0; g < NG; ++g) {
+                    const s16x4 ph_ = __builtin_bit_cast(s16x4, make_uint2(ph2[g][0], ph2[g][1])), pl_ = __builtin_bit_cast(s16x4, make_uint2(pl2[g][0], pl2[g][1]));
+#pragma unroll
+                    for (int j = 0; j < CBN; ++j) {
+                        // values of keys 4 kb .. 4 kb + 3, column 16 j + c: the key pairs 2 kb and 2 kb + 1
+                        const unsigned w0 = sV[(g * 8 + 2 * kb) * VSTR + 16 * j + c], w1 = sV[(g * 8 + 2 * kb + 1) * VSTR + 16 * j + c];
+                        const s16x4 vv = __builtin_bit_cast(s16x4, make_uint2(w0, w1));
+                        const f32x4 t = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(ph_, vv, oacc[j], 0, 0, 0);
+                        oacc[j] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pl_, vv, t, 0, 0, 0);
+                    }
                 }
             }
             lds_sync_wave();
