@@ -2525,8 +2525,10 @@ __global__ void __launch_bounds__(PS_WG_THREADS, 1) fused_kernel(const StepParam
     // output row m is merged by the m-th workgroup from the end: the last workgroups have the fewest
     // vocabulary tiles (the last round of tiles is not full), so they are the first to be ready for it
     stamp(P, wg, 40);
+    // here most workgroups have nothing left to do, and those that merge an output row would only wait for the
+    // slowest workgroup's statistics
+    sx_reset_stale(P, wg, gridDim.x);
     for (int m = (int)gridDim.x - 1 - wg; m < P.Rtot; m += gridDim.x) lm_merge_row(P, m, wave, smem + PS_LDS_BASE);
-    sx_reset_stale(P, wg, gridDim.x);   // here most workgroups have nothing left to do
     step_end(P, ticket, gridDim.x);
     stamp(P, wg, 62);
     stamp_wall(P, wg, 63);
