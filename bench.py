@@ -462,7 +462,7 @@ def group_attention_report(torch, with_oracle, T=2048, k=4, heads=32, d=128, cal
            "latency_us": round(us, 1), "visible_pairs_per_head": pairs, "dtype": "bf16",
            "roofline": {"bound": "mfma", "achieved": round(tf, 2), "peak": 2500.0, "unit": "TFLOP/s", "frac": round(tf / 2500.0, 4),
                         "traffic": None, "flops_per_launch": flops,
-                        "note": "scores run on the matrix cores, P.V still on the vector ALU (fp32 peak 157.3 TFLOP/s)"}}
+                        "note": "scores and P.V on the matrix cores, every operand split into bf16 high + low parts (2 MFMAs per product); a query tile fills 5..15 of an MFMA tile's 16 rows"}}
     if with_oracle:
         from oracle import group_attention as ga
         Ts = 96                                    # the oracle on the first 96 tokens (480 rows) of 4 heads
