@@ -186,6 +186,13 @@ typedef struct ps_draft_step_args {
      * capacity checks and the launch plan use.  A step captured in a HIP graph can then be replayed while the
      * caller advances the lengths on the device (by n_new per step, up to the bound it was captured with). */
     const int32_t* kv_len_dev;
+    /* Sequences of one batch that accepted different numbers of tokens (Section 3: a verification round yields
+     * 1..gamma+1 tokens per sequence).  HOST [batch] or NULL: sequence b has n_new_seq[b] real rows, 1 <=
+     * n_new_seq[b] <= n_new; they are the LAST n_new_seq[b] of its n_new slots in x / token_ids / features (the
+     * slots in front of them are not read); its rows get positions kv_len[b] .. kv_len[b] + n_new_seq[b] + k - 1
+     * and only those cache rows are written.  Output rows are laid out as for n_new (out_rows == 1: the rows of the
+     * unused slots, and their rows of hidden_out, are unspecified).  NULL: every sequence has n_new real rows. */
+    const int32_t* n_new_seq;
 } ps_draft_step_args;
 
 /*
@@ -198,7 +205,7 @@ typedef struct ps_draft_step_args {
  * Steps of one context must not overlap in time (they share the workspace).
  * All arguments are checked and the launch is planned before anything is enqueued or any
  * state of the context changes: a call that returns PS_ERR_NULL, PS_ERR_SHAPE, PS_ERR_OFFSETS,
- * PS_ERR_KV_CAPACITY (kv_len[b] + M exceeds off[b+1] - off[b] or max_positions) or
+ * PS_ERR_KV_CAPACITY (kv_len[b] + the sequence's rows exceed off[b+1] - off[b] or max_positions) or
  * PS_ERR_UNSUPPORTED has done nothing; PS_ERR_DEVICE means a launch itself failed.
  *
  * The step runs as ONE kernel with one workgroup per compute unit whose workgroups hand data to

@@ -48,7 +48,8 @@ class ps_draft_step_args(ctypes.Structure):
                 ("logits", ctypes.c_void_p), ("probs", ctypes.c_void_p), ("hidden_out", ctypes.c_void_p),
                 ("token_ids", ctypes.c_void_p), ("features", ctypes.c_void_p),
                 ("temperature", ctypes.c_float), ("sample_seed", ctypes.c_uint64),
-                ("sample_ids", ctypes.c_void_p), ("sample_p", ctypes.c_void_p), ("kv_len_dev", ctypes.c_void_p)]
+                ("sample_ids", ctypes.c_void_p), ("sample_p", ctypes.c_void_p), ("kv_len_dev", ctypes.c_void_p),
+                ("n_new_seq", ctypes.POINTER(ctypes.c_int32))]
 
 
 _lib = None
@@ -206,7 +207,7 @@ class Drafter:
         return o
 
     def make_args(self, x, k_cache, v_cache, kv_offsets, kv_len, n_new, k, topk, outputs, all_rows=False,
-                  token_ids=None, features=None, temperature=0.0, sample_seed=0, kv_len_dev=None):
+                  token_ids=None, features=None, temperature=0.0, sample_seed=0, kv_len_dev=None, n_new_seq=None):
         """Builds the argument struct; keeps the host arrays alive on the struct.  x: hidden states, or None
         when token_ids (and features) are given."""
         a = ps_draft_step_args()
@@ -222,7 +223,9 @@ class Drafter:
             setattr(a, n, outputs[n].data_ptr() if n in outputs else None)
         off = np.ascontiguousarray(kv_offsets, dtype=np.int64)
         ln = np.ascontiguousarray(kv_len, dtype=np.int32)
-        a._keep = (off, ln, x, k_cache, v_cache, outputs)
+        nn = None if n_new_seq is None else np.ascontiguousarray(n_new_seq, dtype=np.int32)
+        a.n_new_seq = nn.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)) if nn is not None else None
+        a._keep = (off, ln, nn, x, k_cache, v_cache, outputs)
         a.kv_offsets = off.ctypes.data_as(ctypes.POINTER(ctypes.c_int64))
         a.kv_len = ln.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))
         for n in ("top_ids", "top_p", "lse", "logits", "probs", "hidden_out"):

@@ -193,9 +193,14 @@ __device__ __forceinline__ void kv_fill(const StepParams& P) {
     } else {
         for (int b = 0; b < P.B; ++b) v = lane == b ? P.kv_len[b] : v;   // (uniform index: the arguments stay scalar data)
     }
-    if (lane < P.B) ((lds_i32*)(unsigned)PS_LDS_KVLEN)[lane] = v;
+    int sk = 0;
+    for (int b = 0; b < P.B; ++b) sk = lane == b ? P.skip[b] : sk;
+    if (lane < P.B) { ((lds_i32*)(unsigned)PS_LDS_KVLEN)[lane] = v; ((lds_i32*)(unsigned)PS_LDS_SKIP)[lane] = sk; }
 }
 __device__ __forceinline__ int kvlen(int b) { return ((const lds_i32*)(unsigned)PS_LDS_KVLEN)[b]; }
+// unused leading slots of sequence b's real rows (see StepParams::skip); readers come after a barrier
+__device__ __forceinline__ int skipof(int b) { return ((const lds_i32*)(unsigned)PS_LDS_SKIP)[b]; }
+__device__ __forceinline__ int skipof_u(int b) { return __builtin_amdgcn_readfirstlane(skipof(b)); }
 __device__ __forceinline__ int kvlen_u(int b) { return __builtin_amdgcn_readfirstlane(kvlen(b)); }   // wavefront-uniform b
 
 // Exchange buffers exist twice; P holds the addresses in copy 0, step n uses copy n & 1
@@ -273,17 +278,18 @@ __device__ __forceinline__ f32x4 sx_wait4(const StepParams& P, rsrc_t r, unsigne
 }
 
 // 4 values -> the cache's storage type: stores them, returns them as stored (widened again)
-template <typename WT> __device__ __forceinline__ f32x4 store4(void* p, f32x4 v);
-template <> __device__ __forceinline__ f32x4 store4<float>(void* p, f32x4 v) {
-    *reinterpret_cast<f32x4*>(p) = v;
+// (do_store false: only the rounding)
+template <typename WT> __device__ __forceinline__ f32x4 store4(void* p, f32x4 v, bool do_store = true);
+template <> __device__ __forceinline__ f32x4 store4<float>(void* p, f32x4 v, bool do_store) {
+    if (do_store) *reinterpret_cast<f32x4*>(p) = v;
     return v;
 }
-template <> __device__ __forceinline__ f32x4 store4<bf16_t>(void* p, f32x4 v) {
+template <> __device__ __forceinline__ f32x4 store4<bf16_t>(void* p, f32x4 v, bool do_store) {
     const unsigned b0 = f32_to_bf16(v[0]), b1 = f32_to_bf16(v[1]), b2 = f32_to_bf16(v[2]), b3 = f32_to_bf16(v[3]);
     uint2 o;
     o.x = b0 | (b1 << 16);
     o.y = b2 | (b3 << 16);
-    *reinterpret_cast<uint2*>(p) = o;
+    if (do_store) *reinterpret_cast<uint2*>(p) = o;
     const f32x4 r = {bf16_to_f32(b0), bf16_to_f32(b1), bf16_to_f32(b2), bf16_to_f32(b3)};
     return r;
 }
@@ -408,6 +414,7 @@ template <typename WT>
 __device__ __forceinline__ f32x4 load_z4(const StepParams& P, int m, int e) {
     const int b = row_seq(P, m), i = m - b * P.M;
     if (i >= P.n_new) return load4<WT>((const char*)P.mask_emb + ((long long)(i - P.n_new) * P.H + e) * Traits<WT>::ESZ);
+    if (i < skipof(b)) return f32x4{0.f, 0.f, 0.f, 0.f};   // an unused slot: a zero row
     if (P.in_mode == PS_IN_HIDDEN) return load4<WT>((const char*)P.x + ((long long)(b * P.n_new + i) * P.H + e) * Traits<WT>::ESZ);
     if (P.in_mode == PS_IN_TOKENS)
         return load4<WT>((const char*)P.embed + ((long long)P.token_ids[b * P.n_new + i] * P.H + e) * Traits<WT>::ESZ);
@@ -614,7 +621,8 @@ __device__ __forceinline__ void epilogue_qkv(const StepParams& P, int tau, int l
         const int m = 16 * mt + c;
         if (m >= P.Mtot) continue;
         const int b = row_seq(P, m), i = m - b * P.M;
-        const int pos = kvlen(b) + i;                // positions continue after the valid cache rows
+        const int sk = skipof(b);                    // unused leading slots of the sequence: they get no cache rows
+        const int pos = max(kvlen(b) + i - sk, 0);   // positions continue after the valid cache rows
         f32x4 o = v;
         if (hh < P.nq + P.nkv) {
             const float2* cs = P.rope + (size_t)pos * half + jb;
@@ -633,7 +641,7 @@ __device__ __forceinline__ void epilogue_qkv(const StepParams& P, int tau, int l
             const int hk = isk ? hh - P.nq : hh - P.nq - P.nkv;
             char* cache = (char*)(isk ? P.kc : P.vc);
             const size_t e = ((size_t)(P.kv_off[b] + pos) * P.nkv + hk) * P.d + f;
-            const f32x4 stored = store4<WT>(cache + e * Traits<WT>::ESZ, o);
+            const f32x4 stored = store4<WT>(cache + e * Traits<WT>::ESZ, o, i >= sk);
             sx_st4(rn, (unsigned)(((size_t)m * 2 + (isk ? 0 : 1)) * P.KVD + hk * P.d + f), stored);
         }
     }
@@ -815,7 +823,8 @@ __device__ __forceinline__ void stage_piece(const StepParams& P, const PhaseDesc
                         } else if (in_mode == PS_IN_HIDDEN) {
                             raw[i][0] = __builtin_amdgcn_raw_buffer_load_b128(rs, kkc * ESZ, (b * P.n_new + ii) * P.H * ESZ, 0);
                         } else if (in_mode == PS_IN_TOKENS) {
-                            raw[i][0] = __builtin_amdgcn_raw_buffer_load_b128(rs, kkc * ESZ, tok_of(P, b, ii) * P.H * ESZ, 0);
+                            const int tok = ii < P.skip[b] ? 0 : tok_of(P, b, ii);   // (an unused slot's token id is not read)
+                            raw[i][0] = __builtin_amdgcn_raw_buffer_load_b128(rs, kkc * ESZ, tok * P.H * ESZ, 0);
                         } else {
 #pragma unroll
                             for (int h = 0; h < NL; ++h)
@@ -824,9 +833,10 @@ __device__ __forceinline__ void stage_piece(const StepParams& P, const PhaseDesc
                     } else if (PH == PH_FC) {
                         // real row r = (b, ii): [features ; embedding of its token]
                         const int b = P.n_new == 1 ? r : (int)__umulhi((unsigned)r, P.n_magic), ii = r - b * P.n_new;
+                        const int tok = ii < P.skip[b] ? 0 : tok_of(P, b, ii);
                         raw[i][0] = kkc < P.H
                             ? __builtin_amdgcn_raw_buffer_load_b128(rs, kkc * ESZ, r * P.H * ESZ, 0)
-                            : __builtin_amdgcn_raw_buffer_load_b128(rmask, (kkc - P.H) * ESZ, tok_of(P, b, ii) * P.H * ESZ, 0);
+                            : __builtin_amdgcn_raw_buffer_load_b128(rmask, (kkc - P.H) * ESZ, tok * P.H * ESZ, 0);
                     } else {
                         const int srow = PH == PH_LMHEAD ? lm_src_row(P, r) : r;
 #pragma unroll
@@ -855,10 +865,17 @@ __device__ __forceinline__ void stage_piece(const StepParams& P, const PhaseDesc
 #pragma unroll
                         for (int j = 0; j < 4; ++j) v[4 * h + j] = __uint_as_float(raw[i][h][j]);
                 }
+                // (the step's input rows of slots a sequence does not use are zero rows; the host array is read: this
+                // runs before the workgroup's first barrier)
+                bool zero_row = !live;
+                if (PH == PH_QKV) {
+                    const int b = row_seq(P, r), ii = r - b * P.M;
+                    zero_row = zero_row || ii < P.skip[b];
+                }
                 float ss = 0.f;
 #pragma unroll
                 for (int e = 0; e < GE; ++e) {
-                    if (!live) v[e] = 0.f;
+                    if (zero_row) v[e] = 0.f;
                     if (norm) { ss += v[e] * v[e]; v[e] *= gn[e]; }
                 }
                 if (gvalid) {
@@ -1482,6 +1499,7 @@ __device__ __forceinline__ void attn_merge(const StepParams& P, int wg, int nwg,
             if (wave < nr) {
                 const int rho = r0 + wave;
                 const int gi = row_seq(P, rho), i = rho - gi * P.M;
+                const int sk = skipof_u(b), i_hi = max(i, sk);   // the row sees rows sk .. max(i, sk) of this step
                 const rsrc_t rq = make_rsrc(act_ptr(P, P.q_buf)), rn = make_rsrc(act_ptr(P, P.kvnew));
                 const unsigned qo = (unsigned)((size_t)(b * P.M + i) * P.QD + (hk * grp + gi) * D + DPL * lane);
                 float q[DPL], kx[16][DPL], vx[16][DPL];
@@ -1519,7 +1537,7 @@ __device__ __forceinline__ void attn_merge(const StepParams& P, int wg, int nwg,
 #pragma unroll
                 for (int jj = 0; jj < 16; ++jj) {
                     sc[jj] = -INFINITY;
-                    if (jj <= i) {                   // wavefront-uniform: row i sees the rows 0 .. i of this step
+                    if (jj >= sk && jj <= i_hi) {    // wavefront-uniform
                         float part = 0.f;
 #pragma unroll
                         for (int e = 0; e < DPL; ++e) part += q[e] * kx[jj][e];
@@ -1532,7 +1550,7 @@ __device__ __forceinline__ void attn_merge(const StepParams& P, int wg, int nwg,
                 for (int e = 0; e < DPL; ++e) on[e] = 0.f;
 #pragma unroll
                 for (int jj = 0; jj < 16; ++jj) {
-                    if (jj <= i) {
+                    if (jj >= sk && jj <= i_hi) {
                         const float pj = expf(sc[jj] - mn);
                         ln += pj;
 #pragma unroll
@@ -1722,6 +1740,7 @@ __device__ __forceinline__ void attn_phase(const StepParams& P, int wg, int nwg,
         const int b = cur.b, hk = cur.hk, ch = cur.ch, nch = cur.nch, L = cur.L;
         const int key0 = ch * CH + wkey;            // this wavefront's keys: positions key0 .. key0 + 16 NK - 1
         const int end = L + P.attn_tail;            // positions the blocks cover (see attn_sep)
+        const int sk = skipof_u(b);
         stamp(P, wg, 44);
 
         for (int r0 = 0; r0 < (SINGLE ? 16 : Ra); r0 += 16) {       // 16 query rows per pass
@@ -1761,7 +1780,9 @@ __device__ __forceinline__ void attn_phase(const StepParams& P, int wg, int nwg,
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
                     const int pos = key0 + 16 * j + 4 * kb + r;
-                    const bool vis = r0 + c < Ra && pos < end && pos <= L + i;
+                    // (row i sees the cache and rows sk .. i of this step, sk = the sequence's unused slots; a row of an
+                    // unused slot sees what the first used one does, so that it stays finite)
+                    const bool vis = r0 + c < Ra && pos < end && pos <= L + max(i, sk) && (pos < L || pos >= L + sk);
                     sc[j][r] = vis ? acc[j][0][r] * P.inv_sqrt_d : -INFINITY;
                     mloc = fmaxf(mloc, sc[j][r]);
                 }
@@ -2095,6 +2116,7 @@ __device__ __forceinline__ void attn_phase2(const StepParams& P, int wg, int nwg
         stamp(P, wg, 45);
         // this lane's query row (column c of the score tile) and its index among the M rows of its sequence
         const bool qlive = c < nr;
+        const int sk = skipof_u(it.b);               // unused leading slots of the sequence: no keys; their rows see what the first used row does
         const int rho_c = min(r0 + c, Ra - 1);
         const int qi = rho_c - row_seq(P, rho_c) * P.M;
         float m_run = -INFINITY, l_run = 0.f;                        // of query c (the same in the four lanes that share it); m in units of ln 2
@@ -2102,7 +2124,7 @@ __device__ __forceinline__ void attn_phase2(const StepParams& P, int wg, int nwg
 #pragma unroll
         for (int j = 0; j < CBN; ++j) oacc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-        // NG groups of 16 keys at once.  TAIL: rows base .. base + 15 of this step (row qi sees rows <= qi); else
+        // NG groups of 16 keys at once.  TAIL: rows base .. base + 15 of this step (row qi sees rows sk .. qi); else
         // cache positions base + 128 g .. + 15 (every row of the step sees all valid cache positions)
         auto process = [&](const Kv* r, int base, auto NG_, auto TAIL) __attribute__((always_inline)) {
             constexpr bool tail = decltype(TAIL)::value;
@@ -2124,7 +2146,7 @@ __device__ __forceinline__ void attn_phase2(const StepParams& P, int wg, int nwg
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     const int j = base + 16 * PS_WAVES * g + 4 * kb + e;
-                    const bool vis = qlive && (tail ? (j <= qi && j < P.M) : j < k_hi);
+                    const bool vis = qlive && (tail ? (j >= sk && j <= max(qi, sk) && j < P.M) : j < k_hi);
                     sc[g][e] = vis ? acc[g][0][e] * scale2 : -INFINITY;
                     mt = fmaxf(mt, sc[g][e]);
                 }

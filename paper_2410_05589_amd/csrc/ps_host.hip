@@ -521,8 +521,11 @@ extern "C" int ps_draft_step(ps_draft_ctx* ctx, const ps_draft_step_args* a, voi
     }
     for (int b = 0; b < a->batch; ++b) {
         if (a->kv_len[b] < 0) return PS_ERR_SHAPE;
-        if ((long long)a->kv_len[b] + M > a->kv_offsets[b + 1] - a->kv_offsets[b]) return PS_ERR_KV_CAPACITY;
-        if ((long long)a->kv_len[b] + M > c.max_positions) return PS_ERR_KV_CAPACITY;
+        // rows of sequence b: its accepted tokens (n_new, or fewer with n_new_seq) and the k [MASK] slots
+        if (a->n_new_seq && (a->n_new_seq[b] < 1 || a->n_new_seq[b] > a->n_new)) return PS_ERR_SHAPE;
+        const int Mb = (a->n_new_seq ? a->n_new_seq[b] : a->n_new) + a->k;
+        if ((long long)a->kv_len[b] + Mb > a->kv_offsets[b + 1] - a->kv_offsets[b]) return PS_ERR_KV_CAPACITY;
+        if ((long long)a->kv_len[b] + Mb > c.max_positions) return PS_ERR_KV_CAPACITY;
     }
 
     StepParams P;
@@ -565,6 +568,7 @@ extern "C" int ps_draft_step(ps_draft_ctx* ctx, const ps_draft_step_args* a, voi
     for (int b = 0; b < a->batch; ++b) {
         P.kv_off[b] = a->kv_offsets[b];
         P.kv_len[b] = a->kv_len[b];
+        P.skip[b] = a->n_new_seq ? a->n_new - a->n_new_seq[b] : 0;
     }
     // attention work items: (sequence, kv head, block of ch keys)
     const int ra = (c.n_heads / c.n_kv_heads) * M;

@@ -26,11 +26,11 @@
 #define PS_LDS_BYTES (160 * 1024)
 // The first PS_LDS_BASE bytes of dynamic LDS are the same in every phase's layout: what a workgroup reads once
 // when the kernel starts and keeps for the whole step (see ps_device.h): the step's sequence number, the
-// sequences' cache lengths, the token ids of the real rows.
+// sequences' cache lengths and unused slots.
 #define PS_LDS_BASE 1024
 #define PS_LDS_SEQ 16        // the step's sequence number (see ps_seq)
 #define PS_LDS_KVLEN 256     // int[PS_MAX_ROWS]: valid cache positions per sequence
-#define PS_LDS_TOK 512       // int[PS_MAX_ROWS]: token id per real row (token-id input modes)
+#define PS_LDS_SKIP 512      // int[PS_MAX_ROWS]: unused leading slots of real rows per sequence (see StepParams::skip)
 static_assert((1 << PS_WAVES_LOG) == PS_WAVES, "PS_WAVES_LOG");
 static_assert((PS_U & (PS_U - 1)) == 0 && PS_U <= PS_U_MAX, "PS_U");
 
@@ -158,6 +158,10 @@ struct StepParams {
     int fused_nwg, fused_lds;
     long long kv_off[PS_MAX_ROWS];
     int kv_len[PS_MAX_ROWS];
+    // Sequences that accepted fewer than n_new tokens: sequence b uses the last n_new - skip[b] of its n_new slots
+    // of real rows.  The rows of the unused slots run through the step as zero rows that nobody sees: they are
+    // no keys, get no cache rows, and the positions of the sequence's rows start at kv_len[b] behind them.
+    int skip[PS_MAX_ROWS];
     unsigned m_magic, r_magic;   // ceil(2^32 / M), ceil(2^32 / R): row -> sequence without a division
     int tph_log;                 // log2(head_dim / 16): QKV tile -> head
     PhaseDesc ph[PH_COUNT];

@@ -8,7 +8,7 @@ from paper_2410_05589_amd import inputs
 ID_GAP = 1e-3   # token ids must match wherever the oracle's logit gaps exceed this
 
 
-def run_gpu_step(drafter, inp, n_new, k, topk, all_rows=False, want=("logits", "probs", "hidden")):
+def run_gpu_step(drafter, inp, n_new, k, topk, all_rows=False, want=("logits", "probs", "hidden"), n_new_seq=None):
     """One ps_draft_step on copies of the caches; returns numpy outputs and the updated caches."""
     import torch
     dt = drafter.shape.dtype
@@ -19,7 +19,8 @@ def run_gpu_step(drafter, inp, n_new, k, topk, all_rows=False, want=("logits", "
                                  logits="logits" in want, probs="probs" in want, hidden="hidden" in want)
     for t in outs.values():
         t.fill_(-12345) if t.dtype != torch.int32 else t.fill_(-7)
-    args = drafter.make_args(x, kc, vc, inp["kv_offsets"], inp["kv_len"], n_new, k, topk, outs, all_rows=all_rows)
+    args = drafter.make_args(x, kc, vc, inp["kv_offsets"], inp["kv_len"], n_new, k, topk, outs, all_rows=all_rows,
+                             n_new_seq=n_new_seq)
     drafter.step(args)
     torch.cuda.synchronize()
     res = {n: t.cpu().numpy() for n, t in outs.items()}

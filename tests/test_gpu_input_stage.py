@@ -14,7 +14,7 @@ from oracle import ps_oracle as orc
 pytestmark = pytest.mark.gpu
 
 
-def _step(d, shape, inp, tin, n_new, k, topk, mode):
+def _step(d, shape, inp, tin, n_new, k, topk, mode, n_new_seq=None):
     import torch
     dt = shape.dtype
     kc, vc = B.to_device(inp["k_cache"], dt), B.to_device(inp["v_cache"], dt)
@@ -24,7 +24,8 @@ def _step(d, shape, inp, tin, n_new, k, topk, mode):
     tok = torch.from_numpy(tin["token_ids"]).to("cuda:0") if mode != "hidden" else None
     feat = B.to_device(tin["features"], dt) if mode == "fused" else None
     x = B.to_device(inp["x"], dt) if mode == "hidden" else None
-    a = d.make_args(x, kc, vc, inp["kv_offsets"], inp["kv_len"], n_new, k, topk, outs, token_ids=tok, features=feat)
+    a = d.make_args(x, kc, vc, inp["kv_offsets"], inp["kv_len"], n_new, k, topk, outs, token_ids=tok, features=feat,
+                    n_new_seq=n_new_seq)
     d.step(a)
     torch.cuda.synchronize()
     res = {n: t.cpu().numpy() for n, t in outs.items()}
@@ -70,6 +71,46 @@ def test_many_rows_bf16():
     shape = small_shape("bf16", hidden=1024, n_heads=8, n_kv_heads=8, head_dim=128, ffn=2752, vocab=4000)
     _case(Workload("in-rows", shape, batch=8, kv_len=(128, 700, 77, 130, 1, 500, 300, 64), n_new=6, k=2, topk=8, seed=84),
           modes=("fused", "tokens"))
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_sequences_with_different_accepted_lengths(dtype):
+    """n_new_seq with token ids (and features): the token ids of the slots a sequence does not use are never
+    looked up (they are far outside the table here) and their features (huge here) leak nowhere.  Every sequence
+    against the oracle's step of that sequence alone."""
+    shape = small_shape(dtype, vocab=2069)
+    n_new, k, topk = 3, 4, 5
+    kv, nseq = (5, 300, 129, 0), (2, 1, 3, 1)
+    wl = Workload("in-ragged", shape, batch=len(kv), kv_len=kv, n_new=n_new, k=k, topk=topk, seed=86)
+    w = inputs.make_weights(shape, wl.seed)
+    w.update(inputs.make_input_stage_weights(shape, wl.seed))
+    inp = inputs.make_step_inputs(wl)
+    tin = inputs.make_input_stage_inputs(wl)
+    tok, feat = tin["token_ids"].copy(), tin["features"].copy()
+    for b, nb in enumerate(nseq):
+        tok[b, :n_new - nb] = 2 ** 30
+        feat[b, :n_new - nb] = inputs.f32_to_bf16_bits(np.full((1, shape.hidden), 3.0e4, np.float32)) if dtype == "bf16" else 3.0e4
+    bad = dict(tin, token_ids=tok, features=feat)
+    d = B.Drafter(shape, w, max_batch=len(kv), max_new=n_new, max_positions=max(kv) + n_new + k, max_topk=8, k_max=k)
+    off = inp["kv_offsets"]
+    for mode in ("tokens", "fused", "tokens"):
+        res = _step(d, shape, inp, bad, n_new, k, topk, mode, n_new_seq=np.array(nseq, dtype=np.int32))
+        for b, nb in enumerate(nseq):
+            t_b = tin["token_ids"][b:b + 1, n_new - nb:]
+            if mode == "tokens":
+                x_b, is_float = ist.embed_tokens(w["embed"], t_b), False
+            else:
+                x_b, is_float = ist.fused_input(tin["features"][b:b + 1, n_new - nb:], w["embed"], t_b, w["w_fc"], w.get("b_fc"), shape.dtype), True
+            one = dict(k_cache=inp["k_cache"][off[b]:off[b + 1]], v_cache=inp["v_cache"][off[b]:off[b + 1]],
+                       kv_offsets=np.array([0, off[b + 1] - off[b]], dtype=np.int64), kv_len=inp["kv_len"][b:b + 1])
+            ref = orc.draft_step(shape, w, x_b, one["k_cache"], one["v_cache"], one["kv_offsets"], one["kv_len"], nb, k, topk,
+                                 x_is_float=is_float)
+            got = {n: res[n][b:b + 1] for n in ("top_ids", "top_p", "lse", "logits", "probs")}
+            got["hidden_out"] = res["hidden_out"][b:b + 1, n_new - nb:]
+            got["k_cache"], got["v_cache"] = res["k_cache"][off[b]:off[b + 1]], res["v_cache"][off[b]:off[b + 1]]
+            print(mode, "sequence", b, "n_new", nb, compare_with_oracle(shape, got, ref, one, nb, k, topk), flush=True)
+    assert d.last_status() == B.PS_OK
+    d.close()
 
 
 @pytest.mark.parametrize("name", ["c1", "c4"])

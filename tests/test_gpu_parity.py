@@ -5,6 +5,8 @@ logit gaps exceed 1e-3; logits within max-abs 1e-4 (f32) or 2e-2 relative to max
 (bf16).  The tests additionally require the logit error to stay below half the id gap,
 which is what makes the id guarantee hold.
 """
+import ctypes
+
 import numpy as np
 import pytest
 
@@ -193,6 +195,38 @@ def test_every_block_size_of_the_bf16_attention(nk, monkeypatch):
     shape3 = small_shape("bf16", hidden=512, n_heads=4, n_kv_heads=2, head_dim=64, ffn=1024, vocab=1000)
     wl3 = Workload("blocks 17 rows", shape3, batch=2, kv_len=(250, 31), n_new=9, k=8, topk=4, seed=63)
     _run_case(wl3, label="NK " + nk + " (17 rows per sequence)")
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_sequences_with_different_accepted_lengths(dtype):
+    """n_new_seq: the sequences of one batch accepted 1 .. n_new tokens each (Section 3: a verification round yields
+    1..gamma+1 tokens per sequence).  Sequence b uses the last n_new_seq[b] of its n_new slots; the slots in front
+    hold huge values here, which must not leak anywhere.  Every sequence is compared with the oracle's step of
+    that sequence alone with its own n_new (the oracle pins batch == each sequence alone): outputs, hidden rows,
+    the cache rows written and the ones left alone.  Several key blocks, an empty cache, grouped queries."""
+    shape = small_shape(dtype, hidden=512, n_heads=8, n_kv_heads=4, head_dim=64, ffn=1024, vocab=1500)
+    n_new, k, topk = 4, 3, 4
+    kv = (300, 0, 129, 17, 640)
+    nseq = (1, 4, 2, 3, 1)
+    wl = Workload("ragged n_new", shape, batch=len(kv), kv_len=kv, n_new=n_new, k=k, topk=topk, seed=71)
+    w = inputs.make_weights(shape, wl.seed)
+    inp = inputs.make_step_inputs(wl)
+    x = inp["x"].copy()
+    for b, nb in enumerate(nseq):      # poison the unused slots (finite: the interface asks for finite inputs)
+        x[b, :n_new - nb] = inputs.f32_to_bf16_bits(np.full((1, shape.hidden), 3.0e4, np.float32)) if dtype == "bf16" else 3.0e4
+    inp = dict(inp, x=x)
+    d = _drafter(shape, w, max_batch=len(kv), max_new=n_new, max_positions=max(kv) + n_new + k, k_max=k)
+    res = run_gpu_step(d, inp, n_new, k, topk, n_new_seq=np.array(nseq, dtype=np.int32))
+    off = inp["kv_offsets"]
+    for b, nb in enumerate(nseq):
+        one = dict(x=inp["x"][b:b + 1, n_new - nb:], k_cache=inp["k_cache"][off[b]:off[b + 1]], v_cache=inp["v_cache"][off[b]:off[b + 1]],
+                   kv_offsets=np.array([0, off[b + 1] - off[b]], dtype=np.int64), kv_len=inp["kv_len"][b:b + 1])
+        ref = oracle_step(shape, w, one, nb, k, topk)
+        got = {n: res[n][b:b + 1] for n in ("top_ids", "top_p", "lse", "logits", "probs")}
+        got["hidden_out"] = res["hidden_out"][b:b + 1, n_new - nb:]
+        got["k_cache"], got["v_cache"] = res["k_cache"][off[b]:off[b + 1]], res["v_cache"][off[b]:off[b + 1]]
+        print("sequence", b, "n_new", nb, compare_with_oracle(shape, got, ref, one, nb, k, topk), flush=True)
+    d.close()
 
 
 def test_without_final_norm():
@@ -401,6 +435,11 @@ def test_step_argument_errors_enqueue_nothing():
     assert status(out_rows=2) == B.PS_ERR_SHAPE
     assert status(x=None) == B.PS_ERR_NULL
     assert status(top_ids=None) == B.PS_ERR_NULL
+    keep = [np.array(v, dtype=np.int32) for v in ((1, 0), (1, 3))]
+    as_ptr = lambda arr: arr.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))   # noqa: E731
+    assert status(n_new=2, n_new_seq=as_ptr(keep[0])) == B.PS_ERR_SHAPE         # 0 accepted tokens
+    assert status(n_new=2, n_new_seq=as_ptr(keep[1])) == B.PS_ERR_SHAPE         # more than n_new
+    assert status(n_new=2) == B.PS_ERR_KV_CAPACITY                                # 20 + 2 + 3 rows do not fit sequence 1's 24 cache rows
     assert status(ln=np.array([10, 21], dtype=np.int32)) == B.PS_ERR_KV_CAPACITY
     assert status(ln=np.array([10, -1], dtype=np.int32)) == B.PS_ERR_SHAPE
     assert status(off=np.array([0, 30, 20], dtype=np.int64)) == B.PS_ERR_OFFSETS
