@@ -27,6 +27,15 @@ PS_API int ps_draft_debug_plan(const ps_draft_config* config, int batch, int n_n
                         int lds_limit, int* out);
 
 /*
+ * Host only.  How ps_draft_step would cut up the attention of a step over bf16 caches (PS_ERR_UNSUPPORTED for
+ * float32) for sequences of kv_len[0 .. batch) valid positions on a device with n_cu compute units: out[4] =
+ * {NK: groups of 16 keys per wavefront and block (blocks of 128 NK cache keys), work units (blocks x passes of 16
+ * query rows), blocks, merge items (0: every sequence is a single block and hands its rows on directly)}.
+ */
+PS_API int ps_draft_debug_attn_plan(const ps_draft_config* config, int batch, const int32_t* kv_len, int n_new, int k,
+                             int n_cu, int* out);
+
+/*
  * The following steps of ctx give up a wait for data of another workgroup after `spins` polls
  * (<= 0: the default, about a second).  With 1 every wait whose data is not there at the first
  * look is given up at once: the kernel still ends normally, the step's outputs are marked

@@ -489,6 +489,63 @@ extern "C" int ps_draft_debug_plan(const ps_draft_config* c, int batch, int n_ne
     return PS_OK;
 }
 
+// The bf16 attention's work (attn_phase2 in ps_device.h).  Work units = (sequence, kv head, block of 128 NK cache
+// keys, pass of 16 query rows); the rows of this step ride on a sequence's last block.  NK (a power of two) is chosen
+// by a small cost model in microseconds, measured on the benchmark's workloads: a unit costs about 2 + 1 per group of
+// 16 keys a wavefront takes in turn (two at a time), the workgroups take ceil(units / compute units) rounds of them,
+// and a sequence of several blocks costs one more exchange through memory (the merge items).
+struct Attn2Plan { int ch_log, npass, items, merge_items; };
+static Attn2Plan plan_attn2(const int32_t* kv_len, int batch, int n_kv_heads, int ra, int M, int n_cu, int nk_override) {
+    const int npass = (ra + 15) / 16, rt = (ra + PS_WAVES - 1) / PS_WAVES;
+    int best_log = 0;
+    double best = 1e30;
+    for (int lg = 0; lg <= PS_ATTN2_NK_LOG_MAX; ++lg) {
+        if (nk_override > 0 && (1 << lg) != nk_override) continue;
+        const int chl = PS_ATTN_KEYS_LOG + lg;
+        long long units = 0;
+        int groups = 1;
+        bool merge = false;
+        for (int b = 0; b < batch; ++b) {
+            const int L = kv_len[b];
+            int nch = (int)(((long long)L + (1 << chl) - 1) >> chl);
+            if (nch < 1) nch = 1;
+            units += (long long)n_kv_heads * nch * npass;
+            merge = merge || nch > 1;
+            const int g = ((L < (1 << chl) ? L : (1 << chl)) + 15) / 16 + (M + 15) / 16;
+            if (g > groups) groups = g;
+        }
+        const long long rounds = (units + n_cu - 1) / n_cu;
+        const double cost = (double)rounds * (2.0 + 1.0 * ((groups + PS_WAVES - 1) / PS_WAVES)) + (merge ? 5.0 : 0.0);
+        if (cost < best - 1e-9) { best = cost; best_log = lg; }
+    }
+    Attn2Plan ap;
+    ap.ch_log = PS_ATTN_KEYS_LOG + best_log; ap.npass = npass; ap.items = 0; ap.merge_items = 0;
+    for (int b = 0; b < batch; ++b) {
+        int nch = (int)(((long long)kv_len[b] + (1 << ap.ch_log) - 1) >> ap.ch_log);
+        if (nch < 1) nch = 1;
+        ap.items += n_kv_heads * nch;
+        if (nch > 1) ap.merge_items += n_kv_heads * rt;
+    }
+    return ap;
+}
+
+// see ps_draft_debug.h
+extern "C" int ps_draft_debug_attn_plan(const ps_draft_config* c, int batch, const int32_t* kv_len, int n_new, int k, int n_cu,
+                                        int* out) {
+    if (!c || !kv_len || !out) return PS_ERR_NULL;
+    const int st = check_config(c);
+    if (st != PS_OK) return st;
+    if (batch < 1 || batch > c->max_batch || n_new < 1 || n_new > c->max_new || k < 0 || k > c->k_max) return PS_ERR_SHAPE;
+    if (n_cu < 1 || n_cu > 1024) return PS_ERR_SHAPE;
+    if (c->dtype != PS_BF16) return PS_ERR_UNSUPPORTED;
+    for (int b = 0; b < batch; ++b)
+        if (kv_len[b] < 0 || (long long)kv_len[b] + n_new + k > c->max_positions) return PS_ERR_KV_CAPACITY;
+    const int M = n_new + k;
+    const Attn2Plan ap = plan_attn2(kv_len, batch, c->n_kv_heads, (c->n_heads / c->n_kv_heads) * M, M, n_cu, 0);
+    out[0] = 1 << (ap.ch_log - PS_ATTN_KEYS_LOG); out[1] = ap.items * ap.npass; out[2] = ap.items; out[3] = ap.merge_items;
+    return PS_OK;
+}
+
 extern "C" int ps_draft_step(ps_draft_ctx* ctx, const ps_draft_step_args* a, void* stream) {
     if (!ctx || !a) return PS_ERR_NULL;
     const ps_draft_config& c = ctx->cfg;
@@ -605,45 +662,11 @@ extern "C" int ps_draft_step(ps_draft_ctx* ctx, const ps_draft_step_args* a, voi
         P.attn_nwg = want < ctx->n_cu ? want : ctx->n_cu;
     }
     if (attn2) {
-        // Work units = (sequence, kv head, block of 128 NK cache keys, pass of 16 query rows); the rows of this step
-        // ride on a sequence's last block.  NK (a power of two) is chosen by a small cost model in microseconds,
-        // measured on c1 .. c4: a unit costs about 2 + 1 per group of 16 keys a wavefront takes in turn (two at
-        // a time), the workgroups take ceil(units / compute units) rounds of them, and a sequence of several
-        // blocks costs one more exchange through memory (the merge items).
-        const int npass = (ra + 15) / 16, rt = (ra + PS_WAVES - 1) / PS_WAVES;
-        int best_log = 0;
-        double best = 1e30;
-        for (int lg = 0; lg <= PS_ATTN2_NK_LOG_MAX; ++lg) {
-            if (ctx->attn_nk_override > 0 && (1 << lg) != ctx->attn_nk_override) continue;
-            const int chl = PS_ATTN_KEYS_LOG + lg;
-            long long units = 0;
-            int groups = 1;
-            bool merge = false;
-            for (int b = 0; b < a->batch; ++b) {
-                const int L = a->kv_len[b];
-                int nch = (int)(((long long)L + (1 << chl) - 1) >> chl);
-                if (nch < 1) nch = 1;
-                units += (long long)c.n_kv_heads * nch * npass;
-                merge = merge || nch > 1;
-                const int g = ((L < (1 << chl) ? L : (1 << chl)) + 15) / 16 + (M + 15) / 16;
-                if (g > groups) groups = g;
-            }
-            const long long rounds = (units + ctx->n_cu - 1) / ctx->n_cu;
-            const double cost = (double)rounds * (2.0 + 1.0 * ((groups + PS_WAVES - 1) / PS_WAVES)) + (merge ? 5.0 : 0.0);
-            if (cost < best - 1e-9) { best = cost; best_log = lg; }
-        }
-        const int chl = PS_ATTN_KEYS_LOG + best_log;
-        int items2 = 0, mi = 0;
-        for (int b = 0; b < a->batch; ++b) {
-            int nch = (int)(((long long)a->kv_len[b] + (1 << chl) - 1) >> chl);
-            if (nch < 1) nch = 1;
-            items2 += c.n_kv_heads * nch;
-            if (nch > 1) mi += c.n_kv_heads * rt;
-        }
-        P.attn_ch_log = chl; P.attn_npass = npass; P.pass_magic = 0xFFFFFFFFu / (unsigned)npass + 1u;
-        P.attn_items = items2; P.attn_units = items2 * npass; P.attn_merge_items = mi;
+        const Attn2Plan ap = plan_attn2(a->kv_len, a->batch, c.n_kv_heads, ra, M, ctx->n_cu, ctx->attn_nk_override);
+        P.attn_ch_log = ap.ch_log; P.attn_npass = ap.npass; P.pass_magic = 0xFFFFFFFFu / (unsigned)ap.npass + 1u;
+        P.attn_items = ap.items; P.attn_units = ap.items * ap.npass; P.attn_merge_items = ap.merge_items;
         P.attn_sep = 0; P.attn_tail = 0; P.attn_nk = 1;
-        const int want = P.attn_units > mi ? P.attn_units : mi;
+        const int want = P.attn_units > ap.merge_items ? P.attn_units : ap.merge_items;
         P.attn_nwg = want < ctx->n_cu ? want : ctx->n_cu;
     }
 

@@ -7,7 +7,7 @@ from . import binding as B
 PS_PLAN_FIELDS = 12
 PLAN_FIELD_NAMES = ("T", "Kt", "K", "rows", "kw_log", "s_log", "Gs", "per_round", "rounds", "piece_groups",
                     "npieces", "lds_bytes")
-EXPORTED_SYMBOLS = ("ps_draft_debug_plan", "ps_draft_debug_spin_limit", "ps_draft_debug_timeline",
+EXPORTED_SYMBOLS = ("ps_draft_debug_plan", "ps_draft_debug_attn_plan", "ps_draft_debug_spin_limit", "ps_draft_debug_timeline",
                     "ps_verify_debug_exchange", "ps_measure_stream_read", "ps_measure_copy")
 
 _ready = False
@@ -19,6 +19,9 @@ def _lib():
     if not _ready:
         lib.ps_draft_debug_plan.restype = ctypes.c_int
         lib.ps_draft_debug_plan.argtypes = [ctypes.POINTER(B.ps_draft_config)] + [ctypes.c_int] * 6 + [ctypes.POINTER(ctypes.c_int)]
+        lib.ps_draft_debug_attn_plan.restype = ctypes.c_int
+        lib.ps_draft_debug_attn_plan.argtypes = [ctypes.POINTER(B.ps_draft_config), ctypes.c_int, ctypes.POINTER(ctypes.c_int32),
+                                                 ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.POINTER(ctypes.c_int)]
         lib.ps_draft_debug_spin_limit.restype = ctypes.c_int
         lib.ps_draft_debug_spin_limit.argtypes = [ctypes.c_void_p, ctypes.c_int]
         lib.ps_draft_debug_timeline.restype = ctypes.c_int
@@ -39,6 +42,14 @@ def ps_draft_debug_plan(config, batch, n_new, k, all_rows, n_cu, lds_limit):
     st = _lib().ps_draft_debug_plan(ctypes.byref(config), batch, n_new, k, all_rows, n_cu, lds_limit, out)
     plans = [dict(zip(PLAN_FIELD_NAMES, out[ph * PS_PLAN_FIELDS:(ph + 1) * PS_PLAN_FIELDS])) for ph in range(5)]
     return st, plans
+
+
+def ps_draft_debug_attn_plan(config, kv_len, n_new, k, n_cu):
+    """Returns (status, {"nk", "units", "blocks", "merge_items"})."""
+    ln = (ctypes.c_int32 * len(kv_len))(*[int(v) for v in kv_len])
+    out = (ctypes.c_int * 4)()
+    st = _lib().ps_draft_debug_attn_plan(ctypes.byref(config), len(kv_len), ln, n_new, k, n_cu, out)
+    return st, dict(zip(("nk", "units", "blocks", "merge_items"), out[:4]))
 
 
 def ps_draft_debug_spin_limit(ctx, spins):

@@ -213,6 +213,51 @@ def test_phase_plans_of_the_five_workloads(lib):
             _check_plan(cfg, plans, wl.batch, n_new, wl.k, 256, 160 * 1024)
 
 
+def test_attention_plans_of_the_bf16_workloads_and_of_a_sweep(lib):
+    """The bf16 attention's blocks (host logic of ps_draft_step): the block sizes the timed workloads were measured
+    fastest with; and for random batches on several device sizes what the device code relies on: the blocks cover
+    every sequence, merge items exist exactly when some sequence spans several blocks, and a block size is only
+    raised while that spares the workgroups a round of units or the merge."""
+    import random
+    from paper_2410_05589_amd import inputs
+    expect = {"c1": (4, 32, 0), "c2": (2, 160, 40), "c4": (4, 192, 40)}
+    for name, (nk, units, merges) in expect.items():
+        wl = WORKLOADS[name]
+        cfg = B.make_config(wl.shape, max_batch=wl.batch, max_new=6, max_positions=8192, max_topk=wl.topk, k_max=wl.k)
+        st, ap = DBG.ps_draft_debug_attn_plan(cfg, wl.kv_len, wl.n_new, wl.k, 256)
+        assert st == B.PS_OK and (ap["nk"], ap["units"], ap["merge_items"]) == (nk, units, merges), (name, ap)
+    wl = WORKLOADS["c3"]
+    cfg = B.make_config(wl.shape, max_batch=wl.batch, max_new=1, max_positions=8192, max_topk=wl.topk, k_max=wl.k)
+    st, ap = DBG.ps_draft_debug_attn_plan(cfg, inputs.draw_kv_len(wl), wl.n_new, wl.k, 256)
+    assert st == B.PS_OK and ap == {"nk": 16, "units": 256, "blocks": 256, "merge_items": 0}, ap
+    f32 = B.make_config(WORKLOADS["c0"].shape, max_batch=1, max_new=1, max_positions=128, max_topk=4, k_max=4)
+    assert DBG.ps_draft_debug_attn_plan(f32, (64,), 1, 4, 256)[0] == B.PS_ERR_UNSUPPORTED
+    rnd = random.Random(11)
+    for _ in range(300):
+        n_kv = rnd.choice([1, 2, 4, 8])
+        grp = rnd.choice([1, 2, 4])
+        shape = small_shape("bf16", hidden=n_kv * grp * 64, n_heads=n_kv * grp, n_kv_heads=n_kv, head_dim=64, ffn=1024, vocab=1000)
+        n_new, k = rnd.randint(1, 4), rnd.randint(0, 4)
+        M = n_new + k
+        batch = rnd.randint(1, max(1, min(8, 64 // (grp * M))))
+        kv = [rnd.choice([0, 1, 127, 128, 129, rnd.randint(0, 40000)]) for _ in range(batch)]
+        cfg = B.make_config(shape, max_batch=batch, max_new=n_new, max_positions=40000 + M, max_topk=8, k_max=max(k, 1))
+        n_cu = rnd.choice([256, 304, 80, 7])
+        st, ap = DBG.ps_draft_debug_attn_plan(cfg, kv, n_new, k, n_cu)
+        assert st == B.PS_OK, (st, kv)
+        ch = 128 * ap["nk"]
+        assert ap["nk"] in (1, 2, 4, 8, 16)
+        nch = [max(1, -(-l // ch)) for l in kv]
+        npass = -(-grp * M // 16)
+        assert ap["blocks"] == n_kv * sum(nch) and ap["units"] == ap["blocks"] * npass, (ap, kv)
+        assert ap["merge_items"] == n_kv * -(-grp * M // 8) * sum(1 for n in nch if n > 1), (ap, kv)
+        if ap["nk"] > 1:   # the next smaller size would cost a round of units more, or is the one that needs the merge
+            nch2 = [max(1, -(-l // (ch // 2))) for l in kv]
+            more_rounds = -(-n_kv * sum(nch2) * npass // n_cu) > -(-ap["units"] // n_cu)
+            assert more_rounds or (max(nch2) > 1 and max(nch) == 1) or max(nch2) > 1, (ap, kv)
+    assert DBG.ps_draft_debug_attn_plan(cfg, kv, n_new, k, 0)[0] == B.PS_ERR_SHAPE
+
+
 def test_phase_plans_over_a_sweep_of_shapes_and_devices(lib):
     import random
     rnd = random.Random(7)
