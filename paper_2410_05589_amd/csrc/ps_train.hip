@@ -15,7 +15,9 @@
 // one query, which is exactly the 16-row operand layout of v_mfma_f32_16x16x16_bf16 (P, split into high and low
 // parts); the other operand needs four consecutive keys of one value column per lane, so the wavefront passes its
 // 16 value rows through LDS with the rows of a key pair interleaved (one dword = the same column of two keys).
-// float32 values take plain FMAs: a lane owns head_dim / 64 output columns for all 16 rows.
+// A wavefront works on two key tiles at a time (one softmax update per 32 keys, one v_mfma_f32_16x16x32_bf16 per
+// part and 16 output columns) and refills the tiles' registers as soon as they are consumed.
+// float32 values take plain FMAs, a key tile at a time: a lane owns head_dim / 64 output columns for all 16 rows.
 #include "ps_device.h"
 #include "ps_train.h"
 
@@ -78,17 +80,21 @@ __global__ void __launch_bounds__(256) ga_rope_kernel(const GaParams P) {
 }
 
 template <typename WT, int D>
-__global__ void __launch_bounds__(GA_THREADS) ga_attn_kernel(const GaParams P) {
+__global__ void __launch_bounds__(GA_THREADS, Traits<WT>::BF ? 3 : 2) ga_attn_kernel(const GaParams P) {   // workgroups per compute unit
     constexpr bool BF = Traits<WT>::BF;
     constexpr int ESZ = Traits<WT>::ESZ, KSTEP = Traits<WT>::KSTEP, STEPS = D / KSTEP, DPL = D / 64;
     constexpr int OFF_Q = 0;                                // 16 query rows as MFMA operands (hi, lo): 16 * D * 4 bytes
-    constexpr int OFF_P = OFF_Q + 16 * D * 4;               // [waves][16 rows][16 keys] probabilities
-    constexpr int OFF_A = OFF_P + GA_WAVES * 16 * 16 * 4;   // [waves][16] rescale factors of the running output
+    constexpr int OFF_P = OFF_Q + 16 * D * 4;               // float32 values: [waves][16 rows][16 keys] probabilities
+    constexpr int OFF_A = OFF_P + (BF ? 0 : GA_WAVES * 16 * 16 * 4);   // [waves][16] rescale factors of the running output
     constexpr int OFF_ML = OFF_A + GA_WAVES * 16 * 4;       // [waves][16][2] final (max, sum)
-    constexpr int OFF_O = OFF_ML + GA_WAVES * 16 * 2 * 4;   // [waves][16][D] final outputs
     constexpr int VSTR = D + 8;                             // dwords between key pairs of the staged values (no bank conflicts)
-    constexpr int OFF_V = OFF_O + GA_WAVES * 16 * D * 4;    // [waves][8 key pairs][VSTR] dwords: (value of key 2m, value of key 2m+1)
-    __shared__ __attribute__((aligned(16))) char smem[OFF_V + (BF ? GA_WAVES * 8 * VSTR * 4 : 0)];
+    // bf16 values: [waves][2 key tiles][8 key pairs][VSTR] dwords (value of key 2m, value of key 2m+1); a wavefront's
+    // final output [16][D] takes the place of its staged values (which it alone uses).  float32: [waves][16][D] outputs
+    constexpr int OSTRIDE = BF ? 2 * 8 * VSTR : 16 * D;     // floats between the wavefronts' output areas
+    static_assert(!BF || 2 * 8 * VSTR >= 16 * D, "a wavefront's outputs fit its staging area");
+    constexpr int OFF_O = OFF_ML + GA_WAVES * 16 * 2 * 4;
+    constexpr int OFF_V = OFF_O;
+    __shared__ __attribute__((aligned(16))) char smem[OFF_O + GA_WAVES * OSTRIDE * 4];
     typedef typename VRaw<WT, DPL>::type raw_t;
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int c = lane & 15, kb = lane >> 4;
@@ -102,7 +108,7 @@ __global__ void __launch_bounds__(GA_THREADS) ga_attn_kernel(const GaParams P) {
     float* sA = reinterpret_cast<float*>(smem + OFF_A) + wave * 16;
     float* sML = reinterpret_cast<float*>(smem + OFF_ML);
     float* sO = reinterpret_cast<float*>(smem + OFF_O);
-    unsigned* sV = reinterpret_cast<unsigned*>(smem + OFF_V) + wave * 8 * VSTR;
+    unsigned* sV = reinterpret_cast<unsigned*>(smem + OFF_V) + wave * 2 * 8 * VSTR;
     typedef short s16x4 __attribute__((ext_vector_type(4)));
 
     // ---- the query rows (rotated, float32) into LDS as the 16-column MFMA operand; rows beyond the tile repeat the last
@@ -167,6 +173,124 @@ __global__ void __launch_bounds__(GA_THREADS) ga_attn_kernel(const GaParams P) {
         }
     };
     const int n_tiles = n_real + (P.k > 0 ? 1 : 0);         // real-token tiles, then the own-[MASK] tile
+    if constexpr (BF) {
+        // bf16 values: a wavefront works on two key tiles at a time (tiles kt and kt + 4 of the query tile's list),
+        // with the K and V rows of the next two requested meanwhile (two sets of registers take turns, every request
+        // unconditional: beyond the last tile it repeats it and nobody uses it).  Scores in units of ln 2 (the
+        // exponentials are single v_exp_f32); the maxima and sums of the four lanes that share a query row are
+        // exchanged with row swaps; the 32 keys of the two tiles feed one v_mfma_f32_16x16x32_bf16 per part (P high,
+        // P low) and 16 output columns; the running output is rescaled only when a maximum moved.
+        constexpr float LOG2E = 1.4426950408889634f;
+        const float scale2 = P.inv_sqrt_d * LOG2E;
+        struct KvT { uint4 k[STEPS]; uint4 va[2], vb[2]; };
+        const int vmm = min(vm, 7);
+        // (requests beyond the last tile repeat it: nobody uses them)
+        auto load_k = [&](int t, KvT& r) __attribute__((always_inline)) {
+            const char* krow = kbase + (size_t)key_row(min(t, n_tiles - 1), c) * rstride + kb * 16;
+#pragma unroll
+            for (int st = 0; st < STEPS; ++st) r.k[st] = ld16(krow + st * 64);
+        };
+        auto load_v = [&](int t, KvT& r) __attribute__((always_inline)) {
+            const int tc = min(t, n_tiles - 1);
+            const char* pa_ = vbase + (size_t)key_row(tc, 2 * vmm) * rstride + vcb * 32;
+            const char* pb_ = vbase + (size_t)key_row(tc, 2 * vmm + 1) * rstride + vcb * 32;
+            r.va[0] = ld16(pa_); r.va[1] = ld16(pa_ + 16);
+            r.vb[0] = ld16(pb_); r.vb[1] = ld16(pb_ + 16);
+        };
+        // is key j of tile t visible to this lane's query?
+        auto visible = [&](int t, int j) __attribute__((always_inline)) {
+            if (t < n_real) return 16 * t + j <= qg;                          // the real token of a group up to the query's own
+            if (t >= n_tiles) return false;
+            const int kg = g0 + j / K1, ks = j % K1;                          // a [MASK] token of the query's own group, not after it
+            return j < nrows && ks > 0 && kg == qg && ks <= qs;
+        };
+        // the pair of tiles (t0, t0 + 4); its registers are refilled with the pair (t0 + 8, t0 + 12) as soon as they are
+        // consumed: the K rows after the score MFMAs, the V rows once they are staged in LDS
+        auto process2 = [&](KvT (&r)[2], int t0) __attribute__((always_inline)) {
+            f32x4 acc[2][1];
+#pragma unroll
+            for (int g = 0; g < 2; ++g) acc[g][0] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int t = 0; t < STEPS; ++t) {
+                BRegs<WT, 1> bqt;                            // the query rows (read per step: registers are scarce)
+                bqt.h[0] = ld16(sQ + (2 * t * 64 + lane) * 16);
+                bqt.l[0] = ld16(sQ + ((2 * t + 1) * 64 + lane) * 16);
+#pragma unroll
+                for (int g = 0; g < 2; ++g) mma_step<WT, 1>(r[g].k[t], bqt, acc[g]);
+            }
+            load_k(t0 + 2 * GA_WAVES, r[0]); load_k(t0 + 3 * GA_WAVES, r[1]);
+            float sc[2][4], mt = -INFINITY;
+#pragma unroll
+            for (int g = 0; g < 2; ++g)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    sc[g][e] = (qlive && visible(t0 + GA_WAVES * g, 4 * kb + e)) ? acc[g][0][e] * scale2 : -INFINITY;
+                    mt = fmaxf(mt, sc[g][e]);
+                }
+            mt = quad_rows_max(mt);
+            const float m_new = fmaxf(m_run, mt);
+            const float alpha = m_new > -INFINITY ? __builtin_amdgcn_exp2f(m_run - m_new) : 1.f;
+            const float m_use = m_new > -INFINITY ? m_new : 0.f;
+            f32x4 pr[2];
+            float ls = 0.f;
+#pragma unroll
+            for (int g = 0; g < 2; ++g)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    pr[g][e] = __builtin_amdgcn_exp2f(sc[g][e] - m_use);
+                    ls += pr[g][e];
+                }
+            ls = quad_rows_sum(ls);
+            l_run = l_run * alpha + ls;
+            m_run = m_new;
+            if (kb == 0) sA[c] = alpha;
+            if (vm < 8) {                                   // the value rows into LDS, the two keys of a pair interleaved
+#pragma unroll
+                for (int g = 0; g < 2; ++g) {
+                    unsigned ov[16];
+#pragma unroll
+                    for (int w = 0; w < 8; ++w) {
+                        const unsigned a2 = w < 4 ? (&r[g].va[0].x)[w] : (&r[g].va[1].x)[w - 4], b2 = w < 4 ? (&r[g].vb[0].x)[w] : (&r[g].vb[1].x)[w - 4];
+                        ov[2 * w] = __builtin_amdgcn_perm(b2, a2, 0x05040100u);
+                        ov[2 * w + 1] = __builtin_amdgcn_perm(b2, a2, 0x07060302u);
+                    }
+                    uint4* dst = reinterpret_cast<uint4*>(sV + (g * 8 + vm) * VSTR + 16 * vcb);
+#pragma unroll
+                    for (int w = 0; w < 4; ++w) dst[w] = make_uint4(ov[4 * w], ov[4 * w + 1], ov[4 * w + 2], ov[4 * w + 3]);
+                }
+            }
+            load_v(t0 + 2 * GA_WAVES, r[0]); load_v(t0 + 3 * GA_WAVES, r[1]);
+            lds_sync_wave();
+            __builtin_amdgcn_wave_barrier();
+            const f32x4 al = *reinterpret_cast<const f32x4*>(sA + 4 * kb);
+            if (__any(alpha != 1.f)) {
+#pragma unroll
+                for (int j = 0; j < D / 16; ++j) oacc[j] *= al;
+            }
+            unsigned ph2[2][2], pl2[2][2];
+#pragma unroll
+            for (int g = 0; g < 2; ++g) {
+                ph2[g][0] = pack_bf16x2(pr[g][0], pr[g][1]); ph2[g][1] = pack_bf16x2(pr[g][2], pr[g][3]);
+                pl2[g][0] = pack_bf16x2(pr[g][0] - __uint_as_float(ph2[g][0] << 16), pr[g][1] - __uint_as_float(ph2[g][0] & 0xFFFF0000u));
+                pl2[g][1] = pack_bf16x2(pr[g][2] - __uint_as_float(ph2[g][1] << 16), pr[g][3] - __uint_as_float(ph2[g][1] & 0xFFFF0000u));
+            }
+            const bf16x8 pa = __builtin_bit_cast(bf16x8, make_uint4(ph2[0][0], ph2[0][1], ph2[1][0], ph2[1][1]));
+            const bf16x8 pb = __builtin_bit_cast(bf16x8, make_uint4(pl2[0][0], pl2[0][1], pl2[1][0], pl2[1][1]));
+#pragma unroll
+            for (int j = 0; j < D / 16; ++j) {
+                const bf16x8 vv = __builtin_bit_cast(bf16x8, make_uint4(sV[(2 * kb) * VSTR + 16 * j + c], sV[(2 * kb + 1) * VSTR + 16 * j + c],
+                                                                        sV[(8 + 2 * kb) * VSTR + 16 * j + c], sV[(8 + 2 * kb + 1) * VSTR + 16 * j + c]));
+                const f32x4 t = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa, vv, oacc[j], 0, 0, 0);
+                oacc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pb, vv, t, 0, 0, 0);
+            }
+            lds_sync_wave();
+            __builtin_amdgcn_wave_barrier();
+        };
+        KvT ra[2];
+        load_k(wave, ra[0]); load_k(wave + GA_WAVES, ra[1]);
+        load_v(wave, ra[0]); load_v(wave + GA_WAVES, ra[1]);
+        for (int kt = wave; kt < n_tiles; kt += 2 * GA_WAVES) process2(ra, kt);
+    } else {
     uint4 kreg[STEPS], va[2], vb[2], kreg_n[STEPS], va_n[2], vb_n[2];
     raw_t vraw[BF ? 1 : 16], vraw_n[BF ? 1 : 16];
     load_tile(min(wave, n_tiles - 1), kreg, va, vb, vraw);
@@ -271,18 +395,19 @@ __global__ void __launch_bounds__(GA_THREADS) ga_attn_kernel(const GaParams P) {
 #pragma unroll
         for (int j = 0; j < (BF ? 1 : 16); ++j) vraw[j] = vraw_n[j];
     }
+    }
     // ---- the wavefronts' results meet in LDS
     if (kb == 0) { sML[(wave * 16 + c) * 2] = m_run; sML[(wave * 16 + c) * 2 + 1] = l_run; }
     if constexpr (BF) {
 #pragma unroll
         for (int j = 0; j < D / 16; ++j)
 #pragma unroll
-            for (int r = 0; r < 4; ++r) sO[(wave * 16 + 4 * kb + r) * D + 16 * j + c] = oacc[j][r];
+            for (int r = 0; r < 4; ++r) sO[wave * OSTRIDE + (4 * kb + r) * D + 16 * j + c] = oacc[j][r];
     } else {
 #pragma unroll
         for (int rr = 0; rr < 16; ++rr)
 #pragma unroll
-            for (int e = 0; e < DPL; ++e) sO[(wave * 16 + rr) * D + DPL * lane + e] = o[rr][e];
+            for (int e = 0; e < DPL; ++e) sO[wave * OSTRIDE + rr * D + DPL * lane + e] = o[rr][e];
     }
     __syncthreads();
     float* obase = P.out + ((size_t)seq * P.rows * P.nq + h) * D;
@@ -295,8 +420,8 @@ __global__ void __launch_bounds__(GA_THREADS) ga_attn_kernel(const GaParams P) {
 #pragma unroll
         for (int w = 0; w < GA_WAVES; ++w) {
             const float mw = sML[(w * 16 + rr) * 2];
-            const float f = mw > -INFINITY ? expf(mw - M) : 0.f;
-            num += sO[(w * 16 + rr) * D + dd] * f;
+            const float f = mw > -INFINITY ? (BF ? __builtin_amdgcn_exp2f(mw - M) : expf(mw - M)) : 0.f;
+            num += sO[w * OSTRIDE + rr * D + dd] * f;
             den += sML[(w * 16 + rr) * 2 + 1] * f;
         }
         obase[(size_t)(r0 + rr) * P.nq * D + dd] = num / den;   // (every row sees at least its own real token: den > 0)
