@@ -303,11 +303,11 @@ def summarize(paths):
 # (attention stamps: those of the bf16 kernels; 46 is taken by the float32 kernels only)
 STAMP_NAMES = {1: "start", 32: "attn start", 44: "attn unit top", 45: "attn query rows placed", 46: "attn maxima exchanged",
                47: "attn key groups done", 48: "attn unit done", 34: "attn units done", 36: "attn end", 40: "merge start",
-               41: "merge statistics here", 42: "merge candidates", 62: "end"}
+               41: "merge statistics here", 43: "merge wavefront lists done", 49: "merge barrier passed", 42: "merge candidates", 56: "merge row written", 62: "end"}
 for _ph, _nm in enumerate(["qkv", "oproj", "gateup", "down", "lm"]):
     for _k, _sfx in enumerate(["enter", "panel staged", "streamed", "tile sums added", "epilogue done", "end"]):
         STAMP_NAMES[2 + _ph * 6 + _k] = _nm + " " + _sfx
-STAMP_ORDER = [1] + list(range(2, 8)) + [32, 44, 45, 46, 47, 48, 34, 36] + list(range(8, 32)) + [40, 41, 42, 62]
+STAMP_ORDER = [1] + list(range(2, 8)) + [32, 44, 45, 46, 47, 48, 34, 36] + list(range(8, 32)) + [40, 41, 43, 49, 42, 56, 62]
 
 
 def timeline(torch, wl, steps=30):

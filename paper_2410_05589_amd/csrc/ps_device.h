@@ -2371,7 +2371,9 @@ __device__ __forceinline__ void lm_merge_row(const StepParams& P, int m, int wav
         if (lane == 0) sk[wave * PS_MAX_TOPK + t] = best;
         prev = best;                                       // 0: exhausted, every later entry is "none"
     }
+    stamp(P, blockIdx.x, 43);
     __syncthreads();
+    stamp(P, blockIdx.x, 49);
     float mx = -INFINITY;
 #pragma unroll
     for (int w = 0; w < PS_WAVES; ++w) mx = fmaxf(mx, sf[w]);
@@ -2415,6 +2417,7 @@ __device__ __forceinline__ void lm_merge_row(const StepParams& P, int m, int wav
             }
             prev2 = best;
         }
+        stamp(P, blockIdx.x, 56);
     }
     __syncthreads();   // the scratch is reused by the next row
 }
