@@ -229,6 +229,42 @@ def test_sequences_with_different_accepted_lengths(dtype):
     d.close()
 
 
+def test_rounds_of_a_batch_whose_sequences_accept_different_lengths():
+    """Three rounds of drafting for three sequences that accept different numbers of tokens each round (n_new_seq),
+    committed by advancing every sequence's length by what it accepted: the [MASK] rows of a round are overwritten
+    by the next, positions continue per sequence.  After every round each sequence is compared with the oracle run
+    on that sequence alone from the oracle's own caches of the round before."""
+    shape = small_shape("bf16", hidden=512, n_heads=8, n_kv_heads=4, head_dim=64, ffn=1024, vocab=1500)
+    n_max, k, topk = 4, 3, 4
+    kv0 = (120, 0, 33)
+    wl = Workload("ragged rounds", shape, batch=3, kv_len=kv0, n_new=n_max, k=k, topk=topk, seed=72)
+    w = inputs.make_weights(shape, wl.seed)
+    inp = inputs.make_step_inputs(wl, slack=16)
+    off = inp["kv_offsets"]
+    d = _drafter(shape, w, max_batch=3, max_new=n_max, max_positions=max(kv0) + 16 + n_max + k, k_max=k)
+    kc_g, vc_g = inp["k_cache"], inp["v_cache"]
+    kc_o = [inp["k_cache"][off[b]:off[b + 1]] for b in range(3)]
+    vc_o = [inp["v_cache"][off[b]:off[b + 1]] for b in range(3)]
+    L = np.array(kv0, dtype=np.int32)
+    g = np.random.default_rng(6)
+    for rnd, acc in enumerate([(1, 4, 2), (3, 1, 4), (2, 2, 1)]):
+        x = inputs.f32_to_bf16_bits(g.standard_normal((3, n_max, shape.hidden)).astype(np.float32))
+        cur = dict(inp, x=x, k_cache=kc_g, v_cache=vc_g, kv_len=L.copy())
+        res = run_gpu_step(d, cur, n_max, k, topk, n_new_seq=np.array(acc, dtype=np.int32))
+        for b, nb in enumerate(acc):
+            one = dict(x=x[b:b + 1, n_max - nb:], k_cache=kc_o[b], v_cache=vc_o[b],
+                       kv_offsets=np.array([0, off[b + 1] - off[b]], dtype=np.int64), kv_len=L[b:b + 1].copy())
+            ref = oracle_step(shape, w, one, nb, k, topk)
+            got = {n: res[n][b:b + 1] for n in ("top_ids", "top_p", "lse", "logits", "probs")}
+            got["hidden_out"] = res["hidden_out"][b:b + 1, n_max - nb:]
+            got["k_cache"], got["v_cache"] = res["k_cache"][off[b]:off[b + 1]], res["v_cache"][off[b]:off[b + 1]]
+            print("round", rnd, "sequence", b, "accepted", nb, compare_with_oracle(shape, got, ref, one, nb, k, topk, check_cache=False), flush=True)
+            kc_o[b], vc_o[b] = ref["k_cache"], ref["v_cache"]
+        kc_g, vc_g = res["k_cache"], res["v_cache"]
+        L = L + np.array(acc, dtype=np.int32)
+    d.close()
+
+
 def test_without_final_norm():
     shape = small_shape("bf16", final_norm=False)
     wl = Workload("nonorm", shape, batch=2, kv_len=(33, 64), n_new=1, k=4, topk=4, seed=24)
