@@ -76,3 +76,30 @@ def test_no_flat_loads_and_no_spills_in_the_kernels_the_workloads_use(asm):
     for n, v in spills.items():
         if "fused_kernel" in n and "ELi4EEv" not in n:      # (64 rows = four column tiles is the one variant that spills)
             assert v == 0, (n, v)
+
+
+def test_attention_loop_keeps_the_next_key_groups_in_flight(asm):
+    """bf16 attention: while a wavefront works on two groups of keys, the K and V rows of the next two (16 loads)
+    must stay in flight: every wait inside the loop over key groups leaves at least 8 loads outstanding.  (Requests
+    under a condition would make the compiler wait for all of them.)"""
+    text = asm[asm.index("_Z12attn2_kernel"):]
+    text = text[:text.index("s_endpgm")]
+    loops = {}          # header label -> lines of all the blocks of that (inner) loop
+    cur = None
+    for line in text.splitlines():
+        m = re.match(r"^\.L(BB\d+_\d+):\s*(;.*)?$", line)
+        if m:
+            note = m.group(2) or ""
+            h = re.search(r"in Loop: Header=(BB\d+_\d+) Depth=2", note)
+            cur = h.group(1) if h else (m.group(1) if "Parent Loop" in note and "Depth=1" in note else None)
+            continue
+        if cur:
+            loops.setdefault(cur, []).append(line)
+    found = []
+    for header, body in loops.items():
+        n_mfma = sum("v_mfma" in l for l in body)
+        n_load = sum("global_load_dwordx4" in l for l in body)
+        if n_mfma >= 40 and n_load >= 16:
+            found.append((header, [int(m.group(1)) for l in body for m in [re.search(r"vmcnt\((\d+)\)", l)] if m]))
+    assert len(found) == 1, found
+    assert found[0][1] and min(found[0][1]) >= 8, found
