@@ -1,22 +1,22 @@
 // Attention of group-wise parallel training (see include/ps_train.h; Section 4.1).
 //
 // Three kernels per call: the rotary table (cos, sin of position * base^(-2j/d) in double precision), the
-// rotation of q (to float32) and k (to the storage type, rounded as the inference path caches keys), and the
-// attention itself.
+// rotation of k (to the storage type, rounded as the inference path caches keys), and the attention itself,
+// which rotates its 16 query rows (in float32) while it stages them.
 //
 // The attention kernel never touches a key the mask hides.  A query tile is a whole number of parallel groups
 // (as many as fit into 16 rows); what its rows may see are (a) real tokens of groups up to their own - these
 // are gathered with a stride of k + 1 rows, 16 per key tile - and (b) [MASK] tokens of their own group, which
 // all lie inside the query tile's own 16 rows: one more key tile.  The wavefronts of a workgroup take the key
 // tiles in turn, each with its own running maximum, sum and output (online softmax); their results meet in LDS
-// at the end.  Scores are one MFMA tile per key tile (the keys' rows are the 16-row operand, straight from
-// memory; the 16 query rows, split into bf16 high and low parts, the 16-column operand in LDS).  P.V for bf16
-// values is MFMA work too: the score tile comes out of the matrix core with a lane holding four consecutive keys of
-// one query, which is exactly the 16-row operand layout of v_mfma_f32_16x16x16_bf16 (P, split into high and low
-// parts); the other operand needs four consecutive keys of one value column per lane, so the wavefront passes its
-// 16 value rows through LDS with the rows of a key pair interleaved (one dword = the same column of two keys).
-// A wavefront works on two key tiles at a time (one softmax update per 32 keys, one v_mfma_f32_16x16x32_bf16 per
-// part and 16 output columns) and refills the tiles' registers as soon as they are consumed.
+// at the end.  Scores are one MFMA tile per key tile (the keys' rows are the 16-row operand; the 16 query rows, split
+// into bf16 high and low parts, the 16-column operand in LDS).  P.V for bf16 values is MFMA work too: the score tile
+// comes out of the matrix core with a lane holding four consecutive keys of one query, which is exactly the 16-row
+// operand layout (P, split into high and low parts); the other operand needs consecutive keys of one value column
+// per lane, so the value rows pass through LDS, transposed in units of key pairs.  A wavefront works on two key tiles
+// at a time (one softmax update per 32 keys, one v_mfma_f32_16x16x32_bf16 per part and 16 output columns) and refills
+// the tiles' registers as soon as they are consumed.  The K and V rows are loaded 64 adjacent bytes per four lanes and
+// change to the operand order in LDS (see the bf16 branch of the kernel).
 // float32 values take plain FMAs, a key tile at a time: a lane owns head_dim / 64 output columns for all 16 rows.
 #include "ps_device.h"
 #include "ps_train.h"
@@ -31,7 +31,6 @@ struct GaParams {
     const void *q, *k_, *v;
     float* out;
     float2* table;      // [T + k][d / 2]
-    float* q_rot;       // [seqs][rows][nq][d]
     void* k_rot;        // [seqs][rows][nkv][d] storage type
     double log_base;
 };
@@ -46,21 +45,18 @@ __global__ void __launch_bounds__(256) ga_table_kernel(const GaParams P) {
     }
 }
 
-// one thread per (row, head, pair of 4 + 4 elements j..j+3, j+d/2..): q heads first, then k heads
+// rotary embedding of the keys: one thread per (row, kv head, pair of 4 + 4 elements j..j+3, j+d/2..)
 template <typename WT, int D>
 __global__ void __launch_bounds__(256) ga_rope_kernel(const GaParams P) {
     constexpr int ESZ = Traits<WT>::ESZ, Q4 = D / 8;     // groups of 4 pairs per head
-    const long long n = (long long)P.seqs * P.rows * (P.nq + P.nkv) * Q4;
+    const long long n = (long long)P.seqs * P.rows * P.nkv * Q4;
     for (long long x = (long long)blockIdx.x * 256 + threadIdx.x; x < n; x += (long long)gridDim.x * 256) {
         const int g4 = (int)(x % Q4);
-        long long y = x / Q4;
-        const int h = (int)(y % (P.nq + P.nkv));
-        const long long sr = y / (P.nq + P.nkv);           // seq * rows + row
-        const int row = (int)(sr % P.rows);
+        const long long y = x / Q4;                        // (seq * rows + row) * nkv + head
+        const int row = (int)((y / P.nkv) % P.rows);
         const int pos = row / (P.k + 1) + row % (P.k + 1);  // group + slot
-        const bool isq = h < P.nq;
-        const size_t base = isq ? ((size_t)sr * P.nq + h) * D : ((size_t)sr * P.nkv + (h - P.nq)) * D;
-        const char* src = (const char*)(isq ? P.q : P.k_);
+        const size_t base = (size_t)y * D;
+        const char* src = (const char*)P.k_;
         const f32x4 a = load4<WT>(src + (base + 4 * g4) * ESZ), b = load4<WT>(src + (base + D / 2 + 4 * g4) * ESZ);
         f32x4 ra, rb;
 #pragma unroll
@@ -69,13 +65,8 @@ __global__ void __launch_bounds__(256) ga_rope_kernel(const GaParams P) {
             ra[e] = a[e] * t.x - b[e] * t.y;
             rb[e] = b[e] * t.x + a[e] * t.y;
         }
-        if (isq) {
-            *reinterpret_cast<f32x4*>(P.q_rot + base + 4 * g4) = ra;
-            *reinterpret_cast<f32x4*>(P.q_rot + base + D / 2 + 4 * g4) = rb;
-        } else {
-            store4<WT>((char*)P.k_rot + (base + 4 * g4) * ESZ, ra);
-            store4<WT>((char*)P.k_rot + (base + D / 2 + 4 * g4) * ESZ, rb);
-        }
+        store4<WT>((char*)P.k_rot + (base + 4 * g4) * ESZ, ra);
+        store4<WT>((char*)P.k_rot + (base + D / 2 + 4 * g4) * ESZ, rb);
     }
 }
 
@@ -87,11 +78,15 @@ __global__ void __launch_bounds__(GA_THREADS, Traits<WT>::BF ? 3 : 2) ga_attn_ke
     constexpr int OFF_P = OFF_Q + 16 * D * 4;               // float32 values: [waves][16 rows][16 keys] probabilities
     constexpr int OFF_A = OFF_P + (BF ? 0 : GA_WAVES * 16 * 16 * 4);   // [waves][16] rescale factors of the running output
     constexpr int OFF_ML = OFF_A + GA_WAVES * 16 * 4;       // [waves][16][2] final (max, sum)
-    constexpr int VSTR = D + 8;                             // dwords between key pairs of the staged values (no bank conflicts)
-    // bf16 values: [waves][2 key tiles][8 key pairs][VSTR] dwords (value of key 2m, value of key 2m+1); a wavefront's
-    // final output [16][D] takes the place of its staged values (which it alone uses).  float32: [waves][16][D] outputs
-    constexpr int OSTRIDE = BF ? 2 * 8 * VSTR : 16 * D;     // floats between the wavefronts' output areas
-    static_assert(!BF || 2 * 8 * VSTR >= 16 * D, "a wavefront's outputs fit its staging area");
+    // bf16 values, per wavefront, [4 blocks of 4 keys][RSTR] dwords: a column of a block holds four dwords, the values of
+    // keys (4 kb, 4 kb + 1) and (4 kb + 2, 4 kb + 3) of the first key tile, then those of the second; every 8 columns
+    // 4 dwords are left out and every block 4 more, which keeps writers and readers off each other's LDS banks.  The
+    // same area first takes the K rows of the two tiles on their way from the order they are loaded in to the order
+    // the matrix core wants (16 keys x 2 D bytes per tile), and in the end the wavefront's output [16][D].
+    // float32: [waves][16][D] outputs
+    constexpr int RSTR = (D / 8) * 36 + 4;
+    constexpr int OSTRIDE = BF ? 4 * RSTR : 16 * D;         // floats between the wavefronts' areas
+    static_assert(!BF || (OSTRIDE >= 16 * D && OSTRIDE * 4 >= 2 * 16 * D * 2), "a wavefront's outputs and its staged K rows fit its area");
     constexpr int OFF_O = OFF_ML + GA_WAVES * 16 * 2 * 4;
     constexpr int OFF_V = OFF_O;
     __shared__ __attribute__((aligned(16))) char smem[OFF_O + GA_WAVES * OSTRIDE * 4];
@@ -108,26 +103,34 @@ __global__ void __launch_bounds__(GA_THREADS, Traits<WT>::BF ? 3 : 2) ga_attn_ke
     float* sA = reinterpret_cast<float*>(smem + OFF_A) + wave * 16;
     float* sML = reinterpret_cast<float*>(smem + OFF_ML);
     float* sO = reinterpret_cast<float*>(smem + OFF_O);
-    unsigned* sV = reinterpret_cast<unsigned*>(smem + OFF_V) + wave * 2 * 8 * VSTR;
+    unsigned* sV = reinterpret_cast<unsigned*>(smem + OFF_V) + wave * OSTRIDE;
     typedef short s16x4 __attribute__((ext_vector_type(4)));
 
-    // ---- the query rows (rotated, float32) into LDS as the 16-column MFMA operand; rows beyond the tile repeat the last
-    const float* qbase = P.q_rot + ((size_t)seq * P.rows * P.nq + h) * D;
-    for (int t2 = tid; t2 < 16 * (D / 4); t2 += GA_THREADS) {
-        const int r = min(t2 / (D / 4), nrows - 1), g4 = t2 % (D / 4);
-        const u32x4 x = *reinterpret_cast<const u32x4*>(qbase + (size_t)(r0 + r) * P.nq * D + 4 * g4);
-        attn_store_q<WT, D>(sQ, t2, x);
+    // ---- the query rows, rotated in float32 (bf16 values: and scaled by log2(e) / sqrt(d), so the scores come out in
+    // units of ln 2), into LDS as the 16-column MFMA operand; rows beyond the tile repeat the last
+    const char* qsrc = (const char*)P.q + ((size_t)seq * P.rows * P.nq + h) * D * ESZ;
+    const float qscale = BF ? P.inv_sqrt_d * 1.4426950408889634f : 1.f;
+    for (int t2 = tid; t2 < 16 * (D / 8); t2 += GA_THREADS) {
+        const int r = min(t2 / (D / 8), nrows - 1), g4 = t2 % (D / 8);
+        const int row = r0 + r, pos = row / K1 + row % K1;                      // group + slot
+        const char* qrow = qsrc + (size_t)row * P.nq * D * ESZ;
+        const f32x4 a = load4<WT>(qrow + 4 * g4 * ESZ), b = load4<WT>(qrow + (D / 2 + 4 * g4) * ESZ);
+        u32x4 ra, rb;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const float2 t = P.table[(size_t)pos * (D / 2) + 4 * g4 + e];
+            ra[e] = __float_as_uint((a[e] * t.x - b[e] * t.y) * qscale);
+            rb[e] = __float_as_uint((b[e] * t.x + a[e] * t.y) * qscale);
+        }
+        const int ts = (t2 / (D / 8)) * (D / 4) + g4;                           // (row, group of 4 elements) as attn_store_q counts
+        attn_store_q<WT, D>(sQ, ts, ra);
+        attn_store_q<WT, D>(sQ, ts + D / 8, rb);
     }
     __syncthreads();
-    BRegs<WT, 1> bq[STEPS];
+    BRegs<WT, 1> bq[STEPS];                                 // float32: the query rows stay in registers (bf16: read per step)
+    if constexpr (!BF) {
 #pragma unroll
-    for (int t = 0; t < STEPS; ++t) {
-        if constexpr (BF) {
-            bq[t].h[0] = ld16(sQ + (2 * t * 64 + lane) * 16);
-            bq[t].l[0] = ld16(sQ + ((2 * t + 1) * 64 + lane) * 16);
-        } else {
-            bq[t].h[0] = ld16(sQ + (t * 64 + lane) * 16);
-        }
+        for (int t = 0; t < STEPS; ++t) bq[t].h[0] = ld16(sQ + (t * 64 + lane) * 16);
     }
     // this lane's query (column c of the score tile): group and slot
     const int qr = min(c, nrows - 1), qg = g0 + qr / K1, qs = qr % K1;
@@ -152,61 +155,94 @@ __global__ void __launch_bounds__(GA_THREADS, Traits<WT>::BF ? 3 : 2) ga_attn_ke
     auto key_row = [&](int t, int j) __attribute__((always_inline)) {
         return t >= n_real ? r0 + min(j, nrows - 1) : min(16 * t + j, g_last) * K1;
     };
-    constexpr int CBN = D / 16;                             // column blocks of 16
-    const int vm = lane / CBN, vcb = lane % CBN;            // bf16 values: this lane's key pair and column block (lanes < 8 CBN)
-    // The loads of a key tile: K rows as the MFMA operand (lane (c, kb): bytes [64 t + 16 kb, +16) of key c), and
-    // the value rows.  They are requested one tile ahead, while the previous tile is worked on.
-    auto load_tile = [&](int t, uint4 (&kreg)[STEPS], uint4 (&va)[2], uint4 (&vb)[2], raw_t (&vraw)[BF ? 1 : 16]) __attribute__((always_inline)) {
-        const char* krow = kbase + (size_t)key_row(t, c) * rstride + kb * 16;
-#pragma unroll
-        for (int st = 0; st < STEPS; ++st) kreg[st] = ld16(krow + st * 64);
-        if constexpr (BF) {
-            const int mm = min(vm, 7);
-            const char* pa_ = vbase + (size_t)key_row(t, 2 * mm) * rstride + vcb * 32;
-            const char* pb_ = vbase + (size_t)key_row(t, 2 * mm + 1) * rstride + vcb * 32;
-            va[0] = ld16(pa_); va[1] = ld16(pa_ + 16);
-            vb[0] = ld16(pb_); vb[1] = ld16(pb_ + 16);
-        } else {
-#pragma unroll
-            for (int j = 0; j < 16; ++j)
-                vraw[j] = *reinterpret_cast<const raw_t*>(vbase + (size_t)key_row(t, j) * rstride + (size_t)DPL * lane * ESZ);
-        }
-    };
     const int n_tiles = n_real + (P.k > 0 ? 1 : 0);         // real-token tiles, then the own-[MASK] tile
     if constexpr (BF) {
-        // bf16 values: a wavefront works on two key tiles at a time (tiles kt and kt + 4 of the query tile's list),
-        // with the K and V rows of the next two requested meanwhile (two sets of registers take turns, every request
-        // unconditional: beyond the last tile it repeats it and nobody uses it).  Scores in units of ln 2 (the
-        // exponentials are single v_exp_f32); the maxima and sums of the four lanes that share a query row are
-        // exchanged with row swaps; the 32 keys of the two tiles feed one v_mfma_f32_16x16x32_bf16 per part (P high,
-        // P low) and 16 output columns; the running output is rescaled only when a maximum moved.
-        constexpr float LOG2E = 1.4426950408889634f;
-        const float scale2 = P.inv_sqrt_d * LOG2E;
-        struct KvT { uint4 k[STEPS]; uint4 va[2], vb[2]; };
-        const int vmm = min(vm, 7);
+        // bf16 values: a wavefront works on two key tiles at a time (tiles kt and kt + 4 of the query tile's list) and
+        // refills the tiles' registers as soon as they are consumed (every request unconditional: beyond the last tile
+        // it repeats it and nobody uses it).
+        //
+        // Loads: four adjacent lanes read 64 adjacent bytes (the texture unit handles a load in units of four lanes; a
+        // lane that fetched its own MFMA operand directly would make every lane of such a unit touch another row).
+        // K: lane (key = lane / 4, j = lane % 4) reads bytes [64 t + 16 j, +16) of its key in request t; the rows pass
+        // through LDS, where lane (c, kb) picks up bytes [64 t + 16 kb, +16) of key c, its operand of MFMA step t (the
+        // 16-byte pieces of a row are placed at (t ^ key % 4, j ^ key / 4 % 4), which keeps writers and readers off
+        // each other's banks).  V: lane (kbw = lane / (D/8), cc = lane % (D/8)) reads 16 bytes (columns 8 cc .. 8 cc + 7)
+        // of keys 4 kbw .. 4 kbw + 3 of both tiles and stores, per column, the dwords (key 4 kbw, 4 kbw + 1) and
+        // (4 kbw + 2, 4 kbw + 3) of the first tile and of the second side by side: lane (c, kb) then reads, per 16 output
+        // columns, one 16-byte piece = its 8 keys of the 32-key contraction (index 8 kb + e = key 4 kb + e of the first
+        // tile, 4 kb + e - 4 of the second).
+        //
+        // Scores in units of ln 2 (the exponentials are single v_exp_f32); the maxima and sums of the four lanes that
+        // share a query row are exchanged with row swaps; the running output is rescaled only when a maximum moved.
+        constexpr int NCH = D / 8;                          // 16-byte pieces of a K or V row
+        constexpr int KT = 16 * D * 2;                      // bytes of a staged K tile
+        struct KvT { uint4 k[STEPS]; uint4 v[4]; };
+        const unsigned rs32 = (unsigned)rstride;
+        // K: the lane's key and piece as a loader, and its offsets into the staged tile as a writer (request 0) and as a
+        // reader (step 0); request / step t flips bits 6.. of the offset
+        const int kkey = lane >> 2, kj = lane & 3;
+        constexpr int TM = STEPS - 1, TL = STEPS == 4 ? 2 : 1;   // the row's 64-byte segments: mask and log2
+        auto k_lds = [&](int key, int j) __attribute__((always_inline)) {
+            return key * (2 * D) + (((key & TM)) << 6) + ((j ^ ((key >> TL) & 3)) << 4);
+        };
+        char* const sK = reinterpret_cast<char*>(sV);
+        const int kw_rel = k_lds(kkey, kj), kr_rel = k_lds(c, kb);
+        // Addresses: a wavefront-uniform base (the tile's first row) plus a 32-bit offset per lane.  For a tile of real
+        // tokens that lies inside the sequence the offset is the same every time; the last such tile (rows clamped to the
+        // last group) and the tile of the own [MASK] rows compute theirs.
+        const unsigned K1rs = (unsigned)K1 * rs32;                      // bytes between real tokens
+        const size_t tileb = (size_t)16 * K1rs;                         // ... between key tiles of real tokens
+        const char* const kown = kbase + (size_t)r0 * rs32;
+        const char* const vown = vbase + (size_t)r0 * rs32;
+        const unsigned koff_real = (unsigned)kkey * K1rs + kj * 16, koff_own = (unsigned)min(kkey, nrows - 1) * rs32 + kj * 16;
+        // V: the lane's block of four keys and its piece of their rows (lanes beyond 4 NCH repeat the last block and store nothing)
+        const int kbw = min(lane / NCH, 3), cc = lane % NCH;
+        const bool vlane = lane < 4 * NCH;
+        const unsigned voff_real = (unsigned)(4 * kbw) * K1rs + cc * 16;
+        unsigned* const sVw = sV + kbw * RSTR + cc * 36;
+        const unsigned* const sVr = sV + kb * RSTR + (c >> 3) * 36 + (c & 7) * 4;
         // (requests beyond the last tile repeat it: nobody uses them)
         auto load_k = [&](int t, KvT& r) __attribute__((always_inline)) {
-            const char* krow = kbase + (size_t)key_row(min(t, n_tiles - 1), c) * rstride + kb * 16;
+            const int tc = min(t, n_tiles - 1);
+            const char* sb = kown;
+            unsigned off = koff_own;
+            if (tc < n_real) {
+                sb = kbase + (size_t)tc * tileb;
+                off = 16 * tc + 15 <= g_last ? koff_real : (unsigned)min(kkey, g_last - 16 * tc) * K1rs + kj * 16;
+            }
 #pragma unroll
-            for (int st = 0; st < STEPS; ++st) r.k[st] = ld16(krow + st * 64);
+            for (int st = 0; st < STEPS; ++st) r.k[st] = ld16(sb + off + st * 64);
         };
         auto load_v = [&](int t, KvT& r) __attribute__((always_inline)) {
             const int tc = min(t, n_tiles - 1);
-            const char* pa_ = vbase + (size_t)key_row(tc, 2 * vmm) * rstride + vcb * 32;
-            const char* pb_ = vbase + (size_t)key_row(tc, 2 * vmm + 1) * rstride + vcb * 32;
-            r.va[0] = ld16(pa_); r.va[1] = ld16(pa_ + 16);
-            r.vb[0] = ld16(pb_); r.vb[1] = ld16(pb_ + 16);
+            if (tc < n_real && 16 * tc + 15 <= g_last) {
+                const char* sb = vbase + (size_t)tc * tileb;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) r.v[i] = ld16(sb + (size_t)i * K1rs + voff_real);
+            } else {
+                const bool real = tc < n_real;
+                const char* sb = real ? vbase + (size_t)tc * tileb : vown;
+                const unsigned step = real ? K1rs : rs32;
+                const int last = real ? g_last - 16 * tc : nrows - 1;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) r.v[i] = ld16(sb + (unsigned)min(4 * kbw + i, last) * step + cc * 16);
+            }
         };
-        // is key j of tile t visible to this lane's query?
-        auto visible = [&](int t, int j) __attribute__((always_inline)) {
-            if (t < n_real) return 16 * t + j <= qg;                          // the real token of a group up to the query's own
-            if (t >= n_tiles) return false;
-            const int kg = g0 + j / K1, ks = j % K1;                          // a [MASK] token of the query's own group, not after it
-            return j < nrows && ks > 0 && kg == qg && ks <= qs;
-        };
+        // which keys 4 kb + e of a tile this lane's query sees: e in [lo, hi].  Real tokens: those of groups up to the
+        // query's own; the tile's own [MASK] rows: those of the query's group, up to its slot
+        const int real_hi0 = qlive ? qg - 4 * kb : -(1 << 20);
+        const int own_lo = qr - qs + 1 - 4 * kb, own_hi = qlive ? qr - 4 * kb : -(1 << 20);
         // the pair of tiles (t0, t0 + 4); its registers are refilled with the pair (t0 + 8, t0 + 12) as soon as they are
-        // consumed: the K rows after the score MFMAs, the V rows once they are staged in LDS
+        // consumed: the K rows once they are in LDS, the V rows once they are staged
         auto process2 = [&](KvT (&r)[2], int t0) __attribute__((always_inline)) {
+#pragma unroll
+            for (int g = 0; g < 2; ++g)
+#pragma unroll
+                for (int t = 0; t < STEPS; ++t)
+                    *reinterpret_cast<uint4*>(sK + g * KT + (kw_rel ^ (t << 6))) = r[g].k[t];
+            load_k(t0 + 2 * GA_WAVES, r[0]); load_k(t0 + 3 * GA_WAVES, r[1]);
+            lds_sync_wave();
+            __builtin_amdgcn_wave_barrier();
             f32x4 acc[2][1];
 #pragma unroll
             for (int g = 0; g < 2; ++g) acc[g][0] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -216,17 +252,32 @@ __global__ void __launch_bounds__(GA_THREADS, Traits<WT>::BF ? 3 : 2) ga_attn_ke
                 bqt.h[0] = ld16(sQ + (2 * t * 64 + lane) * 16);
                 bqt.l[0] = ld16(sQ + ((2 * t + 1) * 64 + lane) * 16);
 #pragma unroll
-                for (int g = 0; g < 2; ++g) mma_step<WT, 1>(r[g].k[t], bqt, acc[g]);
+                for (int g = 0; g < 2; ++g)
+                    mma_step<WT, 1>(ld16(sK + g * KT + (kr_rel ^ (t << 6))), bqt, acc[g]);
             }
-            load_k(t0 + 2 * GA_WAVES, r[0]); load_k(t0 + 3 * GA_WAVES, r[1]);
             float sc[2][4], mt = -INFINITY;
+            const int t1 = t0 + GA_WAVES;
+            if (t1 < n_real && 16 * t1 + 15 <= g0) {        // every key of both tiles is visible to every query of the tile
 #pragma unroll
-            for (int g = 0; g < 2; ++g)
+                for (int g = 0; g < 2; ++g)
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    sc[g][e] = (qlive && visible(t0 + GA_WAVES * g, 4 * kb + e)) ? acc[g][0][e] * scale2 : -INFINITY;
-                    mt = fmaxf(mt, sc[g][e]);
+                    for (int e = 0; e < 4; ++e) {
+                        sc[g][e] = acc[g][0][e];
+                        mt = fmaxf(mt, sc[g][e]);
+                    }
+            } else {
+#pragma unroll
+                for (int g = 0; g < 2; ++g) {
+                    const int t = t0 + GA_WAVES * g;
+                    const int lo = t < n_real ? 0 : own_lo;
+                    const int hi = t < n_real ? real_hi0 - 16 * t : (t < n_tiles ? own_hi : -(1 << 20));
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        sc[g][e] = (e >= lo && e <= hi) ? acc[g][0][e] : -INFINITY;
+                        mt = fmaxf(mt, sc[g][e]);
+                    }
                 }
+            }
             mt = quad_rows_max(mt);
             const float m_new = fmaxf(m_run, mt);
             const float alpha = m_new > -INFINITY ? __builtin_amdgcn_exp2f(m_run - m_new) : 1.f;
@@ -244,19 +295,18 @@ __global__ void __launch_bounds__(GA_THREADS, Traits<WT>::BF ? 3 : 2) ga_attn_ke
             l_run = l_run * alpha + ls;
             m_run = m_new;
             if (kb == 0) sA[c] = alpha;
-            if (vm < 8) {                                   // the value rows into LDS, the two keys of a pair interleaved
+            if (vlane) {                                    // the value rows into LDS (after the last read of the K rows there)
 #pragma unroll
-                for (int g = 0; g < 2; ++g) {
-                    unsigned ov[16];
+                for (int w = 0; w < 4; ++w) {               // dword w of the lane's 16 bytes: columns 2 w and 2 w + 1
+                    unsigned lo[4], hi[4];
 #pragma unroll
-                    for (int w = 0; w < 8; ++w) {
-                        const unsigned a2 = w < 4 ? (&r[g].va[0].x)[w] : (&r[g].va[1].x)[w - 4], b2 = w < 4 ? (&r[g].vb[0].x)[w] : (&r[g].vb[1].x)[w - 4];
-                        ov[2 * w] = __builtin_amdgcn_perm(b2, a2, 0x05040100u);
-                        ov[2 * w + 1] = __builtin_amdgcn_perm(b2, a2, 0x07060302u);
+                    for (int g = 0; g < 2; ++g) {
+                        const unsigned k0 = (&r[g].v[0].x)[w], k1 = (&r[g].v[1].x)[w], k2 = (&r[g].v[2].x)[w], k3 = (&r[g].v[3].x)[w];
+                        lo[2 * g] = __builtin_amdgcn_perm(k1, k0, 0x05040100u); lo[2 * g + 1] = __builtin_amdgcn_perm(k3, k2, 0x05040100u);
+                        hi[2 * g] = __builtin_amdgcn_perm(k1, k0, 0x07060302u); hi[2 * g + 1] = __builtin_amdgcn_perm(k3, k2, 0x07060302u);
                     }
-                    uint4* dst = reinterpret_cast<uint4*>(sV + (g * 8 + vm) * VSTR + 16 * vcb);
-#pragma unroll
-                    for (int w = 0; w < 4; ++w) dst[w] = make_uint4(ov[4 * w], ov[4 * w + 1], ov[4 * w + 2], ov[4 * w + 3]);
+                    *reinterpret_cast<uint4*>(sVw + 8 * w) = make_uint4(lo[0], lo[1], lo[2], lo[3]);
+                    *reinterpret_cast<uint4*>(sVw + 8 * w + 4) = make_uint4(hi[0], hi[1], hi[2], hi[3]);
                 }
             }
             load_v(t0 + 2 * GA_WAVES, r[0]); load_v(t0 + 3 * GA_WAVES, r[1]);
@@ -276,12 +326,17 @@ __global__ void __launch_bounds__(GA_THREADS, Traits<WT>::BF ? 3 : 2) ga_attn_ke
             }
             const bf16x8 pa = __builtin_bit_cast(bf16x8, make_uint4(ph2[0][0], ph2[0][1], ph2[1][0], ph2[1][1]));
             const bf16x8 pb = __builtin_bit_cast(bf16x8, make_uint4(pl2[0][0], pl2[0][1], pl2[1][0], pl2[1][1]));
+            // four blocks of 16 output columns at a time: the MFMAs with P's high parts, then those with its low parts
+            // (an MFMA that follows the one it depends on directly would wait for it)
 #pragma unroll
-            for (int j = 0; j < D / 16; ++j) {
-                const bf16x8 vv = __builtin_bit_cast(bf16x8, make_uint4(sV[(2 * kb) * VSTR + 16 * j + c], sV[(2 * kb + 1) * VSTR + 16 * j + c],
-                                                                        sV[(8 + 2 * kb) * VSTR + 16 * j + c], sV[(8 + 2 * kb + 1) * VSTR + 16 * j + c]));
-                const f32x4 t = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa, vv, oacc[j], 0, 0, 0);
-                oacc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pb, vv, t, 0, 0, 0);
+            for (int j0 = 0; j0 < D / 16; j0 += 4) {
+                bf16x8 vv[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) vv[u] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(sVr + 72 * (j0 + u)));
+#pragma unroll
+                for (int u = 0; u < 4; ++u) oacc[j0 + u] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa, vv[u], oacc[j0 + u], 0, 0, 0);
+#pragma unroll
+                for (int u = 0; u < 4; ++u) oacc[j0 + u] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pb, vv[u], oacc[j0 + u], 0, 0, 0);
             }
             lds_sync_wave();
             __builtin_amdgcn_wave_barrier();
@@ -291,110 +346,86 @@ __global__ void __launch_bounds__(GA_THREADS, Traits<WT>::BF ? 3 : 2) ga_attn_ke
         load_v(wave, ra[0]); load_v(wave + GA_WAVES, ra[1]);
         for (int kt = wave; kt < n_tiles; kt += 2 * GA_WAVES) process2(ra, kt);
     } else {
-    uint4 kreg[STEPS], va[2], vb[2], kreg_n[STEPS], va_n[2], vb_n[2];
-    raw_t vraw[BF ? 1 : 16], vraw_n[BF ? 1 : 16];
-    load_tile(min(wave, n_tiles - 1), kreg, va, vb, vraw);
-    for (int kt = wave; kt < n_tiles; kt += GA_WAVES) {
-        const bool own = kt == n_real;                      // the [MASK] tokens of the tile's own groups
-        load_tile(min(kt + GA_WAVES, n_tiles - 1), kreg_n, va_n, vb_n, vraw_n);   // (beyond the last: a repeat nobody uses)
-        f32x4 acc[1] = {f32x4{0.f, 0.f, 0.f, 0.f}};
+        // float32 values: a key tile at a time; the K rows (lane (c, kb): bytes [64 t + 16 kb, +16) of key c, its MFMA
+        // operand) and the value rows (a lane owns D / 64 columns of all 16 keys) are requested one tile ahead
+        auto load_tile = [&](int t, uint4 (&kreg)[STEPS], raw_t (&vraw)[16]) __attribute__((always_inline)) {
+            const char* krow = kbase + (size_t)key_row(t, c) * rstride + kb * 16;
 #pragma unroll
-        for (int t = 0; t < STEPS; ++t) mma_step<WT, 1>(kreg[t], bq[t], acc);
-        // scores of keys 4 kb .. 4 kb + 3 for query c, masked
-        float sc[4], mt = -INFINITY;
+            for (int st = 0; st < STEPS; ++st) kreg[st] = ld16(krow + st * 64);
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            const int j = 4 * kb + r;
-            bool vis;
-            if (own) {
-                const int kg = g0 + j / K1, ks = j % K1;
-                vis = j < nrows && ks > 0 && kg == qg && ks <= qs;       // a [MASK] token of the query's own group, not after it
-            } else {
-                vis = 16 * kt + j <= qg;                                  // the real token of a group up to the query's own
-            }
-            sc[r] = (vis && qlive) ? acc[0][r] * P.inv_sqrt_d : -INFINITY;
-            mt = fmaxf(mt, sc[r]);
-        }
-        mt = fmaxf(mt, __shfl_xor(mt, 16, 64));
-        mt = fmaxf(mt, __shfl_xor(mt, 32, 64));
-        const float m_new = fmaxf(m_run, mt);
-        const float alpha = m_new > -INFINITY ? expf(m_run - m_new) : 1.f;   // exp(-inf) = 0 when nothing was seen before
-        f32x4 pr;
-        float ls = 0.f;
+            for (int j = 0; j < 16; ++j)
+                vraw[j] = *reinterpret_cast<const raw_t*>(vbase + (size_t)key_row(t, j) * rstride + (size_t)DPL * lane * ESZ);
+        };
+        uint4 kreg[STEPS], kreg_n[STEPS];
+        raw_t vraw[16], vraw_n[16];
+        load_tile(min(wave, n_tiles - 1), kreg, vraw);
+        for (int kt = wave; kt < n_tiles; kt += GA_WAVES) {
+            const bool own = kt == n_real;                      // the [MASK] tokens of the tile's own groups
+            load_tile(min(kt + GA_WAVES, n_tiles - 1), kreg_n, vraw_n);   // (beyond the last: a repeat nobody uses)
+            f32x4 acc[1] = {f32x4{0.f, 0.f, 0.f, 0.f}};
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            pr[r] = sc[r] > -INFINITY ? expf(sc[r] - m_new) : 0.f;
-            ls += pr[r];
-        }
-        ls += __shfl_xor(ls, 16, 64);
-        ls += __shfl_xor(ls, 32, 64);
-        l_run = l_run * alpha + ls;
-        m_run = m_new;
-        *reinterpret_cast<f32x4*>(sP + c * 16 + 4 * kb) = pr;
-        if (kb == 0) sA[c] = alpha;
-        lds_sync_wave();                                    // written and read by this wavefront only
-        __builtin_amdgcn_wave_barrier();
-        if constexpr (BF) {
-            // the value rows into LDS, the two keys of a pair interleaved column by column
-            if (vm < 8) {
-                unsigned ov[16];
+            for (int t = 0; t < STEPS; ++t) mma_step<WT, 1>(kreg[t], bq[t], acc);
+            // scores of keys 4 kb .. 4 kb + 3 for query c, masked
+            float sc[4], mt = -INFINITY;
 #pragma unroll
-                for (int w = 0; w < 8; ++w) {
-                    const unsigned a2 = w < 4 ? (&va[0].x)[w] : (&va[1].x)[w - 4], b2 = w < 4 ? (&vb[0].x)[w] : (&vb[1].x)[w - 4];
-                    ov[2 * w] = (a2 & 0xFFFFu) | (b2 << 16);
-                    ov[2 * w + 1] = (a2 >> 16) | (b2 & 0xFFFF0000u);
+            for (int r = 0; r < 4; ++r) {
+                const int j = 4 * kb + r;
+                bool vis;
+                if (own) {
+                    const int kg = g0 + j / K1, ks = j % K1;
+                    vis = j < nrows && ks > 0 && kg == qg && ks <= qs;       // a [MASK] token of the query's own group, not after it
+                } else {
+                    vis = 16 * kt + j <= qg;                                  // the real token of a group up to the query's own
                 }
-                uint4* dst = reinterpret_cast<uint4*>(sV + vm * VSTR + 16 * vcb);
-#pragma unroll
-                for (int w = 0; w < 4; ++w) dst[w] = make_uint4(ov[4 * w], ov[4 * w + 1], ov[4 * w + 2], ov[4 * w + 3]);
+                sc[r] = (vis && qlive) ? acc[0][r] * P.inv_sqrt_d : -INFINITY;
+                mt = fmaxf(mt, sc[r]);
             }
-            lds_sync_wave();
+            mt = fmaxf(mt, __shfl_xor(mt, 16, 64));
+            mt = fmaxf(mt, __shfl_xor(mt, 32, 64));
+            const float m_new = fmaxf(m_run, mt);
+            const float alpha = m_new > -INFINITY ? expf(m_run - m_new) : 1.f;   // exp(-inf) = 0 when nothing was seen before
+            f32x4 pr;
+            float ls = 0.f;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                pr[r] = sc[r] > -INFINITY ? expf(sc[r] - m_new) : 0.f;
+                ls += pr[r];
+            }
+            ls += __shfl_xor(ls, 16, 64);
+            ls += __shfl_xor(ls, 32, 64);
+            l_run = l_run * alpha + ls;
+            m_run = m_new;
+            *reinterpret_cast<f32x4*>(sP + c * 16 + 4 * kb) = pr;
+            if (kb == 0) sA[c] = alpha;
+            lds_sync_wave();                                    // written and read by this wavefront only
             __builtin_amdgcn_wave_barrier();
-            // P (query c, keys 4 kb .. 4 kb + 3) as the 16-row operand, split into bf16 high and low parts
-            const unsigned h01 = pack_bf16x2(pr[0], pr[1]), h23 = pack_bf16x2(pr[2], pr[3]);
-            const unsigned l01 = pack_bf16x2(pr[0] - __uint_as_float(h01 << 16), pr[1] - __uint_as_float(h01 & 0xFFFF0000u));
-            const unsigned l23 = pack_bf16x2(pr[2] - __uint_as_float(h23 << 16), pr[3] - __uint_as_float(h23 & 0xFFFF0000u));
-            const s16x4 ph_ = __builtin_bit_cast(s16x4, make_uint2(h01, h23)), pl_ = __builtin_bit_cast(s16x4, make_uint2(l01, l23));
-            const f32x4 al = *reinterpret_cast<const f32x4*>(sA + 4 * kb);   // rescale factors of rows 4 kb .. 4 kb + 3
-#pragma unroll
-            for (int j = 0; j < D / 16; ++j) {
-                // values of keys 4 kb .. 4 kb + 3, column 16 j + c: the key pairs 2 kb and 2 kb + 1
-                const unsigned w0 = sV[(2 * kb) * VSTR + 16 * j + c], w1 = sV[(2 * kb + 1) * VSTR + 16 * j + c];
-                const s16x4 vv = __builtin_bit_cast(s16x4, make_uint2(w0, w1));
-                f32x4 t = oacc[j] * al;
-                t = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(ph_, vv, t, 0, 0, 0);
-                oacc[j] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pl_, vv, t, 0, 0, 0);
-            }
-        } else {
             float v[16][DPL];
-    #pragma unroll
+#pragma unroll
             for (int j = 0; j < 16; ++j) widen_v(vraw[j], v[j]);
-    #pragma unroll
+#pragma unroll
             for (int rr = 0; rr < 16; ++rr) {
                 if (rr < nrows) {                               // wavefront-uniform
                     const float a = sA[rr];
                     const f32x4* prow = reinterpret_cast<const f32x4*>(sP + rr * 16);
-    #pragma unroll
+#pragma unroll
                     for (int e = 0; e < DPL; ++e) o[rr][e] *= a;
-    #pragma unroll
+#pragma unroll
                     for (int k4 = 0; k4 < 4; ++k4) {
                         const f32x4 p4 = prow[k4];
-    #pragma unroll
+#pragma unroll
                         for (int r = 0; r < 4; ++r)
-    #pragma unroll
+#pragma unroll
                             for (int e = 0; e < DPL; ++e) o[rr][e] += p4[r] * v[4 * k4 + r][e];
                     }
                 }
             }
+            lds_sync_wave();
+            __builtin_amdgcn_wave_barrier();                    // the next tile overwrites the probabilities
+#pragma unroll
+            for (int st = 0; st < STEPS; ++st) kreg[st] = kreg_n[st];
+#pragma unroll
+            for (int j = 0; j < 16; ++j) vraw[j] = vraw_n[j];
         }
-        lds_sync_wave();
-        __builtin_amdgcn_wave_barrier();                    // the next tile overwrites the probabilities
-#pragma unroll
-        for (int st = 0; st < STEPS; ++st) kreg[st] = kreg_n[st];
-        va[0] = va_n[0]; va[1] = va_n[1]; vb[0] = vb_n[0]; vb[1] = vb_n[1];
-#pragma unroll
-        for (int j = 0; j < (BF ? 1 : 16); ++j) vraw[j] = vraw_n[j];
-    }
     }
     // ---- the wavefronts' results meet in LDS
     if (kb == 0) { sML[(wave * 16 + c) * 2] = m_run; sML[(wave * 16 + c) * 2 + 1] = l_run; }
@@ -438,23 +469,23 @@ int check(const ps_group_attn_args* a) {
     if (a->head_dim != 64 && a->head_dim != 128) return PS_ERR_UNSUPPORTED;
     if (a->k > 15 || (long long)a->tokens + a->k > (1 << 20)) return PS_ERR_UNSUPPORTED;
     if (a->n_heads > 65535 || a->seqs > 65535) return PS_ERR_UNSUPPORTED;
+    if ((long long)(a->k + 1) * a->n_kv_heads * a->head_dim * 4 > (1LL << 27)) return PS_ERR_UNSUPPORTED;   // 32-bit offsets inside a key tile
     return PS_OK;
 }
 
-struct GaLayout { size_t table, q_rot, k_rot, total; };
+struct GaLayout { size_t table, k_rot, total; };
 GaLayout layout(const ps_group_attn_args* a) {
     GaLayout L;
     const size_t rows = (size_t)a->tokens * (a->k + 1), esz = a->dtype == PS_BF16 ? 2 : 4;
     L.table = 0;
-    L.q_rot = a256((size_t)(a->tokens + a->k) * (a->head_dim / 2) * sizeof(float2));
-    L.k_rot = L.q_rot + a256((size_t)a->seqs * rows * a->n_heads * a->head_dim * 4);
+    L.k_rot = a256((size_t)(a->tokens + a->k) * (a->head_dim / 2) * sizeof(float2));
     L.total = L.k_rot + a256((size_t)a->seqs * rows * a->n_kv_heads * a->head_dim * esz);
     return L;
 }
 
 template <typename WT, int D>
 int launch(const GaParams& P, hipStream_t s) {
-    const long long nrope = (long long)P.seqs * P.rows * (P.nq + P.nkv) * (D / 8);
+    const long long nrope = (long long)P.seqs * P.rows * P.nkv * (D / 8);
     hipLaunchKernelGGL((ga_table_kernel<D>), dim3(min(1024, ((P.T + P.k) * (D / 2) + 255) / 256)), dim3(256), 0, s, P);
     hipLaunchKernelGGL((ga_rope_kernel<WT, D>), dim3((unsigned)min(65535LL, (nrope + 255) / 256)), dim3(256), 0, s, P);
     hipLaunchKernelGGL((ga_attn_kernel<WT, D>), dim3(P.ntiles, P.nq, P.seqs), dim3(GA_THREADS), 0, s, P);
@@ -481,7 +512,7 @@ extern "C" int ps_group_attention(const ps_group_attn_args* a, void* stream) {
     P.inv_sqrt_d = (float)(1.0 / sqrt((double)a->head_dim));
     P.q = a->q; P.k_ = a->k_; P.v = a->v; P.out = a->out;
     char* ws = (char*)a->workspace;
-    P.table = (float2*)(ws + L.table); P.q_rot = (float*)(ws + L.q_rot); P.k_rot = ws + L.k_rot;
+    P.table = (float2*)(ws + L.table); P.k_rot = ws + L.k_rot;
     P.log_base = log((double)a->rope_base);
     hipStream_t s = (hipStream_t)stream;
     if (a->dtype == PS_BF16) return a->head_dim == 128 ? launch<bf16_t, 128>(P, s) : launch<bf16_t, 64>(P, s);

@@ -57,6 +57,15 @@ def test_longer_sequence_and_other_rope_base_bf16():
     _case(1, 300, 4, 8, 2, 128, "bf16", 7, base=500000.0)
 
 
+def test_longer_sequences_with_other_group_sizes():
+    """Several pairs of key tiles per wavefront (tiles every query sees entirely, the clamped last tile, the tile of
+    the own [MASK] rows) with 2, 1 and 8 groups per query tile."""
+    _case(1, 200, 7, 4, 4, 128, "bf16", 8)
+    _case(1, 130, 15, 2, 1, 128, "bf16", 9)
+    _case(2, 150, 1, 4, 2, 64, "bf16", 10)
+    _case(1, 120, 3, 4, 4, 128, "f32", 11)
+
+
 def test_sampled_rows_at_the_benchmark_size():
     """T 2048, k 4, 32 heads x 128 (the 7B drafter's layer), bf16: rows the oracle works out one by one."""
     T, k, nq, d = 2048, 4, 32, 128
