@@ -28,11 +28,11 @@ extern "C" {
  *   out        DEVICE [seqs, rows, n_heads, head_dim] float32, written: softmax(q k^T / sqrt(head_dim)) v per head
  *              under the mask above; query head h uses kv head h / (n_heads / n_kv_heads)
  *   workspace  DEVICE, at least ps_group_attention_workspace_bytes(args) bytes, 256-byte aligned, owned by the
- *              caller: the rotary table and the rotated q (float32) and k (dtype: keys are rounded to the
- *              storage type after the rotary embedding, as the inference path caches them)
+ *              caller: the rotary table and the rotated k (dtype: keys are rounded to the storage type after
+ *              the rotary embedding, as the inference path caches them; queries are rotated in float32 on chip)
  * The rotary embedding (pairs (j, j + head_dim / 2), angle position * rope_base^(-2j / head_dim), computed in
  * double precision) is applied inside.  Supported: head_dim 64 or 128; k + 1 <= 16; n_heads a multiple of
- * n_kv_heads; dtype PS_F32 or PS_BF16; tokens + k <= 2^20.  Errors: PS_ERR_NULL, PS_ERR_SHAPE (a size < 1,
+ * n_kv_heads; dtype PS_F32 or PS_BF16; tokens + k <= 2^20; (k + 1) * n_kv_heads * head_dim <= 2^25.  Errors: PS_ERR_NULL, PS_ERR_SHAPE (a size < 1,
  * k < 0), PS_ERR_UNSUPPORTED, PS_ERR_WORKSPACE, PS_ERR_DEVICE.
  */
 typedef struct ps_group_attn_args {

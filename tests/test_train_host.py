@@ -48,7 +48,7 @@ def test_validation_on_the_host(lib):
     for kw in (dict(seqs=0), dict(tokens=0), dict(k=-1), dict(n_kv_heads=3), dict(dtype=5), dict(rope_base=0.0)):
         assert TR.ps_group_attention(args(**kw), None) == B.PS_ERR_SHAPE, kw
         assert TR.ps_group_attention_workspace_bytes(args(**kw)) == 0
-    for kw in (dict(head_dim=96), dict(k=16), dict(tokens=1 << 20)):
+    for kw in (dict(head_dim=96), dict(k=16), dict(tokens=1 << 20), dict(k=15, n_heads=32768, n_kv_heads=32768, head_dim=128)):
         assert TR.ps_group_attention(args(**kw), None) == B.PS_ERR_UNSUPPORTED, kw
     for n in ("q", "k_", "v", "out", "workspace"):
         assert TR.ps_group_attention(args(**{n: None}), None) == B.PS_ERR_NULL, n
