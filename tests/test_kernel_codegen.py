@@ -103,3 +103,26 @@ def test_attention_loop_keeps_the_next_key_groups_in_flight(asm):
             found.append((header, [int(m.group(1)) for l in body for m in [re.search(r"vmcnt\((\d+)\)", l)] if m]))
     assert len(found) == 1, found
     assert found[0][1] and min(found[0][1]) >= 8, found
+
+
+def test_training_attention_kernel_fits_four_workgroups_per_compute_unit(tmp_path):
+    """The bf16 training attention runs four workgroups (16 wavefronts) per compute unit: at most 128 vector
+    registers per lane and 40 KiB of LDS per workgroup, no flat loads (LDS addresses stay LDS addresses), and
+    only a handful of spilled registers (loop-invariant values)."""
+    out = str(tmp_path / "ps_train.s")
+    cmd = [build.hipcc_path(), "--offload-arch=gfx950", "-O3", "-std=c++17", "-fno-gpu-rdc", "-fvisibility=hidden",
+           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+           "-mllvm", "-instcombine-max-copied-from-constant-users=10000",
+           "-I", os.path.join(ROOT, "include"), "-I", build.CSRC,
+           "--cuda-device-only", "-S", "-o", out, os.path.join(build.CSRC, "ps_train.hip")]
+    res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    assert res.returncode == 0, res.stdout[-2000:]
+    text = open(out).read()
+    assert "flat_load" not in text
+    seen = 0
+    for m in re.finditer(r"\.group_segment_fixed_size:\s+(\d+)\n(?:.*\n)*?\s+\.name:\s+(\S+)\n(?:.*\n)*?\s+\.vgpr_count:\s+(\d+)\n\s+\.vgpr_spill_count:\s+(\d+)", text):
+        lds, name, vgpr, spill = int(m.group(1)), m.group(2), int(m.group(3)), int(m.group(4))
+        if "ga_attn_bf16_kernel" in name:
+            seen += 1
+            assert vgpr <= 128 and lds <= 40 * 1024 and spill <= 4, (name, vgpr, lds, spill)
+    assert seen == 2        # head_dim 64 and 128
